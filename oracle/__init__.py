@@ -1,0 +1,146 @@
+"""Python binding of the CPU oracle -- TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import
+this package; the GPU library never does.  All arrays are host numpy arrays.
+"""
+import ctypes
+import os
+import subprocess
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libvq_oracle.so")
+_SRC = os.path.join(_HERE, "vq_oracle.cpp")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with g++ (a second of CPU work)."""
+    if force or not os.path.exists(_LIB_PATH) or os.path.getmtime(_LIB_PATH) < os.path.getmtime(_SRC):
+        subprocess.check_call(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
+                               "-Wall", "-Wextra", _SRC, "-o", _LIB_PATH, "-lpthread"])
+    return _LIB_PATH
+
+
+class _Layer(ctypes.Structure):
+    _fields_ = [
+        ("out_features", ctypes.c_int32), ("in_features", ctypes.c_int32),
+        ("v", ctypes.c_int32), ("k", ctypes.c_int32), ("k_res", ctypes.c_int32),
+        ("n_outlier_cols", ctypes.c_int32), ("v_out", ctypes.c_int32), ("k_out", ctypes.c_int32),
+        ("codebook", ctypes.c_void_p), ("codebook_res", ctypes.c_void_p), ("codebook_out", ctypes.c_void_p),
+        ("idx", ctypes.c_void_p), ("idx_row_stride", ctypes.c_int64),
+        ("idx_res", ctypes.c_void_p), ("idx_res_row_stride", ctypes.c_int64),
+        ("idx_out", ctypes.c_void_p), ("idx_out_row_stride", ctypes.c_int64),
+        ("scale", ctypes.c_void_p), ("bias", ctypes.c_void_p),
+    ]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB_PATH)
+        L.vq_oracle_half_to_float.restype = ctypes.c_float
+        L.vq_oracle_half_to_float.argtypes = [ctypes.c_uint16]
+        L.vq_oracle_float_to_half.restype = ctypes.c_uint16
+        L.vq_oracle_float_to_half.argtypes = [ctypes.c_float]
+        L.vq_oracle_index_bits.argtypes = [ctypes.c_int32]
+        L.vq_oracle_unpack_row.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_void_p]
+        L.vq_oracle_dequant.argtypes = [ctypes.POINTER(_Layer), ctypes.c_void_p, ctypes.c_int64, ctypes.c_int]
+        L.vq_oracle_matmul.argtypes = [ctypes.POINTER(_Layer), ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32,
+                                       ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int]
+        _lib = L
+    return _lib
+
+
+def default_threads() -> int:
+    return max(1, len(os.sched_getaffinity(0)))
+
+
+def _ptr(a):
+    return a.ctypes.data if a is not None else None
+
+
+def _c(a, dtype):
+    if a is None:
+        return None
+    a = np.ascontiguousarray(a)
+    assert a.dtype == dtype, (a.dtype, dtype)
+    return a
+
+
+def _describe(layer):
+    """ctypes layer record + the arrays it points into (kept alive by the caller)."""
+    keep = dict(
+        codebook=_c(layer.codebook, np.float16), codebook_res=_c(layer.codebook_res, np.float16),
+        codebook_out=_c(layer.codebook_out, np.float16), idx=_c(layer.idx, np.uint8),
+        idx_res=_c(layer.idx_res, np.uint8), idx_out=_c(layer.idx_out, np.uint8),
+        scale=_c(layer.scale, np.float16), bias=_c(layer.bias, np.float16))
+
+    def stride(a):
+        return a.shape[1] if a is not None else 0
+    d = _Layer(layer.out_features, layer.in_features, layer.v, layer.k, layer.k_res,
+               layer.n_outlier_cols, layer.v_out, layer.k_out,
+               _ptr(keep["codebook"]), _ptr(keep["codebook_res"]), _ptr(keep["codebook_out"]),
+               _ptr(keep["idx"]), stride(keep["idx"]), _ptr(keep["idx_res"]), stride(keep["idx_res"]),
+               _ptr(keep["idx_out"]), stride(keep["idx_out"]), _ptr(keep["scale"]), _ptr(keep["bias"]))
+    return d, keep
+
+
+class OracleError(RuntimeError):
+    pass
+
+
+def half_to_float(bits: int) -> float:
+    return lib().vq_oracle_half_to_float(int(bits))
+
+
+def float_to_half(value) -> int:
+    return lib().vq_oracle_float_to_half(ctypes.c_float(value))
+
+
+def index_bits(k: int) -> int:
+    return lib().vq_oracle_index_bits(int(k))
+
+
+def unpack_row(row: np.ndarray, bits: int, count: int) -> np.ndarray:
+    row = _c(row, np.uint8)
+    out = np.empty(count, dtype=np.int32)
+    rc = lib().vq_oracle_unpack_row(_ptr(row), bits, count, _ptr(out))
+    if rc:
+        raise OracleError("unpack_row failed: %d" % rc)
+    return out
+
+
+def dequant(layer, ldw: int | None = None, n_threads: int | None = None) -> np.ndarray:
+    """Restored weights, fp16 [out][ldw]; columns >= in_features are left zero."""
+    d, keep = _describe(layer)
+    ldw = layer.in_features if ldw is None else ldw
+    W = np.zeros((layer.out_features, ldw), dtype=np.float16)
+    rc = lib().vq_oracle_dequant(ctypes.byref(d), _ptr(W), ldw, n_threads or default_threads())
+    if rc:
+        raise OracleError("dequant failed: %d" % rc)
+    return W
+
+
+def matmul(layer, x: np.ndarray, rows=None, n_threads: int | None = None) -> np.ndarray:
+    """fp64 [tokens][out] (or [tokens][len(rows)]): restored weights times fp16 activations x [tokens][in]."""
+    d, keep = _describe(layer)
+    x = _c(x, np.float16)
+    assert x.ndim == 2 and x.shape[1] >= layer.in_features
+    tokens = x.shape[0]
+    rows_a = None if rows is None else np.ascontiguousarray(rows, dtype=np.int32)
+    n_rows = layer.out_features if rows_a is None else len(rows_a)
+    y = np.zeros((tokens, n_rows), dtype=np.float64)
+    rc = lib().vq_oracle_matmul(ctypes.byref(d), _ptr(x), x.shape[1], tokens, _ptr(rows_a), n_rows,
+                                _ptr(y), n_rows, n_threads or default_threads())
+    if rc:
+        raise OracleError("matmul failed: %d" % rc)
+    return y
+
+
+# decode GEMV and prefill GEMM are the same definition at different token counts
+gemv = matmul
+gemm = matmul

@@ -1,0 +1,66 @@
+/* CPU oracle for the vector-quantized linear layer -- TEST INFRASTRUCTURE ONLY.
+ *
+ * A slow, plain restatement of what the layer computes, used to check the GPU
+ * library and as the timed CPU baseline.  It shares no code, header or table
+ * with the GPU library, and nothing in the product path may call it.
+ *
+ * What is computed follows the paper's description of inference: a weight
+ * vector is restored by looking its index up in the codebook (Sec. 2.2,
+ * "Vector Quantization"), the residual codebook's centroid is added to it
+ * (Sec. 3.2.2, "Residual Vector Quantization"), a small set of outlier
+ * columns uses a codebook of its own (Sec. 3.2.3, "Outlier Elimination";
+ * parameters v0,k0,v1,k1,k2 of App. "Parameter Description"), and the restored
+ * FP16 matrix multiplies the activations (App. "Our Dequantization
+ * Implementation").  Per-output-channel scale and bias are applied to the
+ * restored weight before it is rounded to FP16.
+ *
+ * All pointers are HOST pointers.  Parity status: every function here is
+ * pinned by tests that do not depend on the oracle itself (hand-written byte
+ * streams, one-hot lookups, W*e_j = column j, an independent triple-loop
+ * matmul on unpacked indices, the compiler's own FP16 conversions).
+ */
+#ifndef VQ_ORACLE_H
+#define VQ_ORACLE_H
+#include <stdint.h>
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct vq_oracle_layer {
+  int32_t out_features, in_features;      /* M rows (outputs), N columns (inputs)             */
+  int32_t v, k;                           /* main codebook: vector length, entries            */
+  int32_t k_res;                          /* residual codebook entries (same v); 0 = none     */
+  int32_t n_outlier_cols, v_out, k_out;   /* first n columns use the outlier codebook; 0=none */
+  const uint16_t *codebook;               /* fp16 bits [k][v]                                 */
+  const uint16_t *codebook_res;           /* fp16 bits [k_res][v]                             */
+  const uint16_t *codebook_out;           /* fp16 bits [k_out][v_out]                         */
+  const uint8_t *idx;      int64_t idx_row_stride;      /* per-row bitstreams, stride in bytes */
+  const uint8_t *idx_res;  int64_t idx_res_row_stride;
+  const uint8_t *idx_out;  int64_t idx_out_row_stride;
+  const uint16_t *scale, *bias;           /* fp16 bits [out_features]; NULL = 1.0 / 0.0       */
+} vq_oracle_layer;
+
+enum { VQO_OK = 0, VQO_ERR_ARG = -1, VQO_ERR_INDEX_RANGE = -2 };
+
+/* IEEE binary16 <-> binary32, round-to-nearest-even, subnormals kept, overflow to infinity. */
+float    vq_oracle_half_to_float(uint16_t h);
+uint16_t vq_oracle_float_to_half(float f);
+
+/* ceil(log2 k), at least 1: bits of one stored index. */
+int vq_oracle_index_bits(int32_t k);
+
+/* Read `count` indices of `bits` bits from one row's little-endian bitstream. */
+int vq_oracle_unpack_row(const uint8_t *row, int bits, int64_t count, int32_t *out);
+
+/* Restored weight matrix as fp16 bits, W[o*ldw + c] for c < in_features. */
+int vq_oracle_dequant(const vq_oracle_layer *L, uint16_t *W, int64_t ldw, int n_threads);
+
+/* y[t*ldy + j] = sum_c W[rows[j]][c] * x[t*ldx + c] in fp64, c ascending.
+ * rows == NULL means all rows (n_rows = out_features, j = o).                                */
+int vq_oracle_matmul(const vq_oracle_layer *L, const uint16_t *x, int64_t ldx, int32_t n_tokens,
+                     const int32_t *rows, int32_t n_rows, double *y, int64_t ldy, int n_threads);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
