@@ -1,0 +1,109 @@
+/* vq.h -- C ABI of the MI355X (gfx950) vector-quantized linear layer.
+ *
+ * The layer stores, per length-v weight vector, an index into a codebook of k
+ * FP16 centroids (paper Sec. 2.2 "Vector Quantization": weights are restored
+ * "from the lookup table by index and centroid"; index bits = log2(k) per
+ * vector).  Optional extras, all from the paper's parameter list
+ * (App. "Parameter Description": v0,k0 / v1,k1 / k2):
+ *   - a residual codebook of k_res entries with the same v, whose centroid is
+ *     ADDED to the main one (Sec. 3.2.2 "Residual Vector Quantization");
+ *   - outlier columns: the first n_outlier_cols input columns are coded with a
+ *     codebook of their own (v_out, k_out) and have no residual
+ *     (Sec. 3.2.3 "Outlier Elimination").
+ * Per-output-channel FP16 scale and bias are applied to the restored weight:
+ *     W[o][c] = fp16( fma( scale[o], d[o][c], bias[o] ) ),  d in binary32.
+ * Inference is two-phase (App. "Our Dequantization Implementation"): prompts
+ * restore W and run a matrix product (vq_dequant, vq_gemm); decoding fuses
+ * restore and matrix-vector product (vq_gemv).
+ *
+ * Orientation: W is [out_features][in_features] (rows = outputs).  Vector p of
+ * row o covers input columns n_outlier_cols + p*v ... + v-1; P = ceil((in -
+ * n_outlier_cols)/v) vectors per row; elements past in_features in the last
+ * vector are decoded and dropped.
+ *
+ * Index streams: one per codebook.  Row o of a stream starts at byte
+ * o*row_stride and is a little-endian bitstream: index p occupies bits
+ * [p*b, (p+1)*b), b = ceil(log2 k) (at least 1); bit t is bit (t mod 8) of byte
+ * (t div 8).  b = 8 / 16 are plain uint8 / little-endian uint16 arrays.
+ * row_stride is a multiple of 16 and at least ceil(P*b/8); pad bits are
+ * ignored.  An index >= k (possible only when k is not a power of two) decodes
+ * to an unspecified centroid of the same table; it never causes an
+ * out-of-bounds access.
+ *
+ * Every pointer is a DEVICE pointer owned by the caller (the descriptor itself
+ * is host memory, read during the call only).  Calls enqueue work on
+ * `hip_stream` (NULL = the default stream) and return without synchronising;
+ * nothing is allocated, freed or retained.  Output elements outside the
+ * logical extents (columns >= in_features of W, columns >= out_features of y)
+ * are not written.  Return value: VQ_OK or a negative vq_status; no exception
+ * crosses the boundary.  Thread-safe.
+ */
+#ifndef VQ_H
+#define VQ_H
+#include <stddef.h>
+#include <stdint.h>
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum vq_status {
+  VQ_OK = 0,
+  VQ_ERR_NULL = -1,        /* a required pointer is NULL                                   */
+  VQ_ERR_SHAPE = -2,       /* a size, stride or leading dimension is out of range           */
+  VQ_ERR_ALIGNMENT = -3,   /* a pointer or stride misses its required alignment             */
+  VQ_ERR_UNSUPPORTED = -4, /* valid layer, but no kernel handles it                         */
+  VQ_ERR_HIP = -5,         /* the HIP runtime reported a launch error                       */
+  VQ_ERR_WORKSPACE = -6    /* workspace missing or smaller than vq_gemm_workspace_bytes     */
+} vq_status;
+
+typedef struct vq_layer_desc {
+  uint32_t struct_size;                    /* = sizeof(vq_layer_desc)                              */
+  int32_t out_features, in_features;       /* M, N (logical, unpadded); 1 .. 2^24                  */
+  int32_t v, k;                            /* main codebook: v in [1,16], k in [2,65536]           */
+  int32_t k_res;                           /* residual entries, 0 = none; same v                   */
+  int32_t n_outlier_cols, v_out, k_out;    /* 0 = none; n % v_out == 0; n <= in_features           */
+  const void *codebook;                    /* fp16 [k][v] row-major, 16-byte aligned               */
+  const void *codebook_res;                /* fp16 [k_res][v]                                      */
+  const void *codebook_out;                /* fp16 [k_out][v_out]                                  */
+  const void *idx;      int64_t idx_row_stride;       /* bytes; 16-byte aligned base and stride    */
+  const void *idx_res;  int64_t idx_res_row_stride;
+  const void *idx_out;  int64_t idx_out_row_stride;
+  const void *scale;                       /* fp16 [out_features], 2-byte aligned; NULL = 1.0      */
+  const void *bias;                        /* fp16 [out_features]; NULL = 0.0                      */
+} vq_layer_desc;
+
+/* Host-only check of a descriptor (no GPU work): the status any entry point would return for it. */
+int vq_validate(const vq_layer_desc *desc);
+
+/* Restore the weight matrix (Sec. 2.2; App. "Our Dequantization Implementation", first phase).
+ * W: fp16 [out_features][ldw], ldw >= in_features (elements), 2-byte aligned.  Bit-exact definition:
+ * binary32 add of main and residual centroid, one binary32 fma with scale/bias, round-to-nearest-even
+ * to binary16 (subnormals kept, overflow to infinity).                                              */
+int vq_dequant(const vq_layer_desc *desc, void *W, int64_t ldw, void *hip_stream);
+
+/* Decode-phase fused restore + matrix-vector product ("QGemv", App. "Our Dequantization
+ * Implementation", second phase): y[b][o] = sum_c W[o][c] * x[b][c], binary32 accumulation on the
+ * vector ALUs, fp16 result.  x: fp16 [batch][ldx], ldx >= in_features; y: fp16 [batch][ldy],
+ * ldy >= out_features; batch in [1,16]; x and y 2-byte aligned (a 16-byte aligned x with ldx % 8 == 0
+ * lets the fastest kernels run).  y must not alias x.                                               */
+int vq_gemv(const vq_layer_desc *desc, const void *x, int64_t ldx, int32_t batch,
+            void *y, int64_t ldy, void *hip_stream);
+
+/* Prompt-phase product for many tokens: Y[t][o] = sum_c W[o][c] * X[t][c] with the restored weights
+ * fed to FP16 matrix cores through on-chip tiles (W is never written to memory), binary32
+ * accumulation, fp16 result.  X: fp16 [tokens][ldx], 16-byte aligned, ldx % 8 == 0; Y: fp16
+ * [tokens][ldy], ldy >= out_features; tokens >= 1.  `workspace` must hold
+ * vq_gemm_workspace_bytes(desc, tokens) bytes (16-byte aligned; may be NULL when that is 0).       */
+int vq_gemm(const vq_layer_desc *desc, const void *X, int64_t ldx, int32_t tokens,
+            void *Y, int64_t ldy, void *workspace, size_t workspace_bytes, void *hip_stream);
+size_t vq_gemm_workspace_bytes(const vq_layer_desc *desc, int32_t tokens);
+
+/* Text for a status code (static storage).  */
+const char *vq_status_string(int status);
+/* Library version, major*10000 + minor*100 + patch. */
+int vq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VQ_H */

@@ -1,0 +1,168 @@
+"""Thin Python binding of libvq.so, the gfx950 vector-quantized linear layer (argument marshalling only).
+
+Every step of the path (index unpack, codebook lookup, residual sum, outlier columns, scale/bias,
+GEMV / GEMM) runs in the HIP kernels behind the C ABI of include/vq.h.  PyTorch is used for device
+memory and streams only.  There is no CPU fallback: a missing library raises.
+"""
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libvq.so")
+
+VQ_OK, VQ_ERR_NULL, VQ_ERR_SHAPE, VQ_ERR_ALIGNMENT, VQ_ERR_UNSUPPORTED, VQ_ERR_HIP, VQ_ERR_WORKSPACE = 0, -1, -2, -3, -4, -5, -6
+
+
+class vq_layer_desc(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32),
+        ("out_features", ctypes.c_int32), ("in_features", ctypes.c_int32),
+        ("v", ctypes.c_int32), ("k", ctypes.c_int32), ("k_res", ctypes.c_int32),
+        ("n_outlier_cols", ctypes.c_int32), ("v_out", ctypes.c_int32), ("k_out", ctypes.c_int32),
+        ("codebook", ctypes.c_void_p), ("codebook_res", ctypes.c_void_p), ("codebook_out", ctypes.c_void_p),
+        ("idx", ctypes.c_void_p), ("idx_row_stride", ctypes.c_int64),
+        ("idx_res", ctypes.c_void_p), ("idx_res_row_stride", ctypes.c_int64),
+        ("idx_out", ctypes.c_void_p), ("idx_out_row_stride", ctypes.c_int64),
+        ("scale", ctypes.c_void_p), ("bias", ctypes.c_void_p),
+    ]
+
+
+class VQError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (where, vq_status_string(status), status))
+
+
+_lib = None
+
+
+def load():
+    """Load libvq.so (build it first with build.py or __graft_entry__.build()).  Raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libvq.so is not built: run `python -m paper_2409_17066_amd.build` (needs hipcc)")
+    try:
+        import torch  # noqa: F401  -- loads the HIP runtime this process will share with the library
+    except ImportError:
+        pass
+    L = ctypes.CDLL(LIB_PATH)
+    P = ctypes.POINTER(vq_layer_desc)
+    L.vq_validate.argtypes = [P]
+    L.vq_dequant.argtypes = [P, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+    L.vq_gemv.argtypes = [P, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+    L.vq_gemm.argtypes = [P, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
+                          ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    L.vq_gemm_workspace_bytes.argtypes = [P, ctypes.c_int32]
+    L.vq_gemm_workspace_bytes.restype = ctypes.c_size_t
+    L.vq_status_string.argtypes = [ctypes.c_int]
+    L.vq_status_string.restype = ctypes.c_char_p
+    L.vq_version.restype = ctypes.c_int
+    for f in (L.vq_validate, L.vq_dequant, L.vq_gemv, L.vq_gemm):
+        f.restype = ctypes.c_int
+    _lib = L
+    return L
+
+
+EXPORTED = ["vq_validate", "vq_dequant", "vq_gemv", "vq_gemm", "vq_gemm_workspace_bytes", "vq_status_string", "vq_version"]
+
+
+# ---- the C entry points, same names, raw pointers (ints) and sizes ---------------------------------------
+def vq_validate(desc):
+    return load().vq_validate(ctypes.byref(desc) if desc is not None else None)
+
+
+def vq_dequant(desc, W_ptr, ldw, stream=None):
+    return load().vq_dequant(ctypes.byref(desc) if desc is not None else None, W_ptr, ldw, stream)
+
+
+def vq_gemv(desc, x_ptr, ldx, batch, y_ptr, ldy, stream=None):
+    return load().vq_gemv(ctypes.byref(desc) if desc is not None else None, x_ptr, ldx, batch, y_ptr, ldy, stream)
+
+
+def vq_gemm(desc, X_ptr, ldx, tokens, Y_ptr, ldy, workspace_ptr=None, workspace_bytes=0, stream=None):
+    return load().vq_gemm(ctypes.byref(desc) if desc is not None else None, X_ptr, ldx, tokens, Y_ptr, ldy,
+                          workspace_ptr, workspace_bytes, stream)
+
+
+def vq_gemm_workspace_bytes(desc, tokens):
+    return load().vq_gemm_workspace_bytes(ctypes.byref(desc), tokens)
+
+
+def vq_status_string(status):
+    return load().vq_status_string(status).decode()
+
+
+def vq_version():
+    return load().vq_version()
+
+
+# ---- conveniences over torch tensors (allocation and pointer extraction only) ----------------------------
+class DeviceLayer:
+    """Device copies of one layer's arrays plus the descriptor that points at them."""
+
+    def __init__(self, layer, device="cuda"):
+        import torch
+        self.layer = layer
+        self.tensors = {}
+
+        def up(name, arr):
+            if arr is None:
+                return None
+            t = torch.from_numpy(arr).to(device).contiguous()
+            self.tensors[name] = t
+            return t.data_ptr()
+
+        def stride(a):
+            return a.shape[1] if a is not None else 0
+        self.desc = vq_layer_desc(
+            ctypes.sizeof(vq_layer_desc), layer.out_features, layer.in_features, layer.v, layer.k, layer.k_res,
+            layer.n_outlier_cols, layer.v_out, layer.k_out,
+            up("codebook", layer.codebook), up("codebook_res", layer.codebook_res), up("codebook_out", layer.codebook_out),
+            up("idx", layer.idx), stride(layer.idx), up("idx_res", layer.idx_res), stride(layer.idx_res),
+            up("idx_out", layer.idx_out), stride(layer.idx_out), up("scale", layer.scale), up("bias", layer.bias))
+
+
+def _stream():
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def dequant(dl: DeviceLayer, ldw=None):
+    """fp16 [out][ldw] restored weights on the device (columns >= in_features are zero-initialised, never written)."""
+    import torch
+    L = dl.layer
+    ldw = L.in_features if ldw is None else ldw
+    W = torch.zeros((L.out_features, ldw), dtype=torch.float16, device="cuda")
+    rc = vq_dequant(dl.desc, W.data_ptr(), ldw, _stream())
+    if rc != VQ_OK:
+        raise VQError(rc, "vq_dequant")
+    return W
+
+
+def gemv(dl: DeviceLayer, x, out=None):
+    """x: fp16 [batch][>=in] device tensor -> fp16 [batch][out]."""
+    import torch
+    assert x.is_cuda and x.dtype == torch.float16 and x.dim() == 2 and x.stride(1) == 1
+    y = out if out is not None else torch.empty((x.shape[0], dl.layer.out_features), dtype=torch.float16, device="cuda")
+    rc = vq_gemv(dl.desc, x.data_ptr(), x.stride(0), x.shape[0], y.data_ptr(), y.stride(0), _stream())
+    if rc != VQ_OK:
+        raise VQError(rc, "vq_gemv")
+    return y
+
+
+def gemm(dl: DeviceLayer, X, out=None, workspace=None):
+    """X: fp16 [tokens][>=in] device tensor -> fp16 [tokens][out]."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.stride(1) == 1
+    Y = out if out is not None else torch.empty((X.shape[0], dl.layer.out_features), dtype=torch.float16, device="cuda")
+    need = vq_gemm_workspace_bytes(dl.desc, X.shape[0])
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device="cuda")
+    rc = vq_gemm(dl.desc, X.data_ptr(), X.stride(0), X.shape[0], Y.data_ptr(), Y.stride(0),
+                 workspace.data_ptr() if workspace is not None else None,
+                 workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream())
+    if rc != VQ_OK:
+        raise VQError(rc, "vq_gemm")
+    return Y

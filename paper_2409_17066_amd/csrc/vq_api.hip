@@ -1,0 +1,126 @@
+// C-ABI entry points: descriptor validation and dispatch.  All device work is in the kernel files.
+#include "vq_common.hpp"
+
+namespace vq {
+
+static bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+static int check_stream(const void *idx, long long stride, int per_row, int bits) {
+  if (!idx) return VQ_ERR_NULL;
+  if (stride < ((long long)per_row * bits + 7) / 8) return VQ_ERR_SHAPE;
+  if (stride % 16 != 0 || !aligned(idx, 16)) return VQ_ERR_ALIGNMENT;
+  return VQ_OK;
+}
+
+int make_params(const vq_layer_desc *d, Params *p) {
+  if (!d) return VQ_ERR_NULL;
+  if (d->struct_size != sizeof(vq_layer_desc)) return VQ_ERR_SHAPE;
+  const int lim = 1 << 24;
+  if (d->out_features < 1 || d->out_features > lim || d->in_features < 1 || d->in_features > lim) return VQ_ERR_SHAPE;
+  if (d->v < 1 || d->v > 16 || d->k < 2 || d->k > 65536) return VQ_ERR_SHAPE;
+  if (d->k_res != 0 && (d->k_res < 2 || d->k_res > 65536)) return VQ_ERR_SHAPE;
+  if (d->n_outlier_cols < 0) return VQ_ERR_SHAPE;
+  if (d->n_outlier_cols > 0) {
+    if (d->v_out < 1 || d->v_out > 16 || d->k_out < 2 || d->k_out > 65536) return VQ_ERR_SHAPE;
+    if (d->n_outlier_cols % d->v_out != 0 || d->n_outlier_cols >= d->in_features) return VQ_ERR_SHAPE;
+  }
+  Params q{};
+  q.out_features = d->out_features; q.in_features = d->in_features;
+  q.v = d->v; q.k = d->k; q.bits = index_bits(d->k);
+  q.k_res = d->k_res; q.bits_res = d->k_res ? index_bits(d->k_res) : 0;
+  q.n_out = d->n_outlier_cols;
+  q.v_out = q.n_out ? d->v_out : 1; q.k_out = q.n_out ? d->k_out : 0; q.bits_out = q.n_out ? index_bits(d->k_out) : 0;
+  q.P = (d->in_features - q.n_out + d->v - 1) / d->v;
+  q.Q = q.n_out ? q.n_out / d->v_out : 0;
+  if (!d->codebook) return VQ_ERR_NULL;
+  if (!aligned(d->codebook, 16)) return VQ_ERR_ALIGNMENT;
+  int rc = check_stream(d->idx, d->idx_row_stride, q.P, q.bits);
+  if (rc != VQ_OK) return rc;
+  if (q.k_res) {
+    if (!d->codebook_res) return VQ_ERR_NULL;
+    if (!aligned(d->codebook_res, 16)) return VQ_ERR_ALIGNMENT;
+    rc = check_stream(d->idx_res, d->idx_res_row_stride, q.P, q.bits_res);
+    if (rc != VQ_OK) return rc;
+  }
+  if (q.n_out) {
+    if (!d->codebook_out) return VQ_ERR_NULL;
+    if (!aligned(d->codebook_out, 16)) return VQ_ERR_ALIGNMENT;
+    rc = check_stream(d->idx_out, d->idx_out_row_stride, q.Q, q.bits_out);
+    if (rc != VQ_OK) return rc;
+  }
+  if ((d->scale && !aligned(d->scale, 2)) || (d->bias && !aligned(d->bias, 2))) return VQ_ERR_ALIGNMENT;
+  q.cb = static_cast<const __half *>(d->codebook);
+  q.cb_res = q.k_res ? static_cast<const __half *>(d->codebook_res) : nullptr;
+  q.cb_out = q.n_out ? static_cast<const __half *>(d->codebook_out) : nullptr;
+  q.idx = static_cast<const uint8_t *>(d->idx); q.stride = d->idx_row_stride;
+  q.idx_res = q.k_res ? static_cast<const uint8_t *>(d->idx_res) : nullptr; q.stride_res = q.k_res ? d->idx_res_row_stride : 0;
+  q.idx_out = q.n_out ? static_cast<const uint8_t *>(d->idx_out) : nullptr; q.stride_out = q.n_out ? d->idx_out_row_stride : 0;
+  q.scale = static_cast<const __half *>(d->scale);
+  q.bias = static_cast<const __half *>(d->bias);
+  if (p) *p = q;
+  return VQ_OK;
+}
+
+}  // namespace vq
+
+using vq::aligned;
+
+extern "C" int vq_validate(const vq_layer_desc *desc) { return vq::make_params(desc, nullptr); }
+
+extern "C" int vq_dequant(const vq_layer_desc *desc, void *W, int64_t ldw, void *hip_stream) {
+  vq::Params p;
+  int rc = vq::make_params(desc, &p);
+  if (rc != VQ_OK) return rc;
+  if (!W) return VQ_ERR_NULL;
+  if (ldw < p.in_features) return VQ_ERR_SHAPE;
+  if (!aligned(W, 2)) return VQ_ERR_ALIGNMENT;
+  return vq::launch_dequant(p, static_cast<__half *>(W), ldw, static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int vq_gemv(const vq_layer_desc *desc, const void *x, int64_t ldx, int32_t batch,
+                       void *y, int64_t ldy, void *hip_stream) {
+  vq::Params p;
+  int rc = vq::make_params(desc, &p);
+  if (rc != VQ_OK) return rc;
+  if (!x || !y) return VQ_ERR_NULL;
+  if (batch < 1 || batch > 16 || ldx < p.in_features || ldy < p.out_features) return VQ_ERR_SHAPE;
+  if (!aligned(x, 2) || !aligned(y, 2)) return VQ_ERR_ALIGNMENT;
+  return vq::launch_gemv(p, static_cast<const __half *>(x), ldx, batch, static_cast<__half *>(y), ldy,
+                         static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" size_t vq_gemm_workspace_bytes(const vq_layer_desc *desc, int32_t tokens) {
+  vq::Params p;
+  if (vq::make_params(desc, &p) != VQ_OK || tokens < 1) return 0;
+  return vq::gemm_workspace_bytes(p, tokens);
+}
+
+extern "C" int vq_gemm(const vq_layer_desc *desc, const void *X, int64_t ldx, int32_t tokens,
+                       void *Y, int64_t ldy, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  vq::Params p;
+  int rc = vq::make_params(desc, &p);
+  if (rc != VQ_OK) return rc;
+  if (!X || !Y) return VQ_ERR_NULL;
+  if (tokens < 1 || tokens > (1 << 24) || ldx < p.in_features || ldy < p.out_features) return VQ_ERR_SHAPE;
+  if (!aligned(X, 16) || (ldx & 7) || !aligned(Y, 2)) return VQ_ERR_ALIGNMENT;
+  const size_t need = vq::gemm_workspace_bytes(p, tokens);
+  if (need && (!workspace || workspace_bytes < need)) return VQ_ERR_WORKSPACE;
+  if (need && !aligned(workspace, 16)) return VQ_ERR_ALIGNMENT;
+  return vq::launch_gemm(p, static_cast<const __half *>(X), ldx, tokens, static_cast<__half *>(Y), ldy,
+                         workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" const char *vq_status_string(int status) {
+  switch (status) {
+    case VQ_OK: return "ok";
+    case VQ_ERR_NULL: return "a required pointer is NULL";
+    case VQ_ERR_SHAPE: return "size, stride or leading dimension out of range";
+    case VQ_ERR_ALIGNMENT: return "pointer or stride misaligned";
+    case VQ_ERR_UNSUPPORTED: return "no kernel handles this layer";
+    case VQ_ERR_HIP: return "HIP launch error";
+    case VQ_ERR_WORKSPACE: return "workspace missing or too small";
+    default: return "unknown status";
+  }
+}
+
+extern "C" int vq_version(void) { return 100; }

@@ -1,0 +1,65 @@
+// Shared host/device declarations of the gfx950 VQ linear-layer library (internal).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+#include "../../include/vq.h"
+
+namespace vq {
+
+// Layer parameters in the form kernels take by value.
+struct Params {
+  int out_features, in_features;
+  int v, k, bits;
+  int k_res, bits_res;
+  int n_out, v_out, k_out, bits_out;
+  int P, Q;                      // main / outlier vectors per row
+  const __half *cb, *cb_res, *cb_out;
+  const uint8_t *idx, *idx_res, *idx_out;
+  long long stride, stride_res, stride_out;   // bytes per row of each stream
+  const __half *scale, *bias;
+};
+
+inline int index_bits(int k) { int b = 1; while ((1 << b) < k) ++b; return b; }
+
+// Host-side validation shared by the entry points; fills `p` on success.
+int make_params(const vq_layer_desc *d, Params *p);
+
+// Kernel launchers (each returns a vq_status).
+int launch_dequant(const Params &p, __half *W, long long ldw, hipStream_t s);
+int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
+int launch_gemm(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy,
+                void *workspace, size_t workspace_bytes, hipStream_t s);
+size_t gemm_workspace_bytes(const Params &p, int tokens);
+
+#ifdef __HIPCC__
+// Index p of a row's little-endian bitstream (bits <= 16).  `row` is 4-byte aligned and the row's
+// stride covers every dword that holds one of its P*bits bits, so both loads stay inside the row.
+__device__ __forceinline__ unsigned load_index(const uint8_t *row, long long p, int bits) {
+  const long long bit = p * bits;
+  const unsigned *w = reinterpret_cast<const unsigned *>(row) + (bit >> 5);
+  const int sh = (int)(bit & 31);
+  unsigned lo = w[0] >> sh;
+  if (sh + bits > 32) lo |= w[1] << (32 - sh);
+  return lo & ((1u << bits) - 1u);
+}
+
+// The bit-exact restore of one weight: binary32 add of centroids happens at the caller, then one
+// binary32 fma and one round-to-nearest-even conversion to binary16 (Sec. 2.2 lookup, Sec. 3.2.2 sum
+// of tables).  The empty asm keeps the compiler from merging fma and conversion into the mixed-
+// precision fma (v_fma_mixlo_f16), which rounds the exact result once, straight to binary16, and so
+// differs from the two-step definition on double-rounding cases.
+__device__ __forceinline__ __half restore(float d, float scale, float bias) {
+  float w32 = __fmaf_rn(scale, d, bias);
+  asm volatile("" : "+v"(w32));
+  return __float2half_rn(w32);
+}
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+  return x;
+}
+#endif
+
+}  // namespace vq

@@ -1,0 +1,52 @@
+// vq_dequant: restore the FP16 weight matrix (paper Sec. 2.2 lookup; Sec. 3.2.2 residual sum;
+// Sec. 3.2.3 outlier columns; App. "Our Dequantization Implementation", first phase).
+#include "vq_common.hpp"
+
+namespace vq {
+
+// Any (v, k, residual, outlier) combination: one thread restores one vector.  Consecutive threads
+// take consecutive vectors of one row, so a wave's stores cover one contiguous span of the row.
+__global__ __launch_bounds__(256) void dequant_generic_kernel(Params p, __half *W, long long ldw, int blocks_per_row) {
+  const int o = blockIdx.x / blocks_per_row;
+  const int slot = (blockIdx.x % blocks_per_row) * 256 + threadIdx.x;
+  if (slot >= p.Q + p.P) return;
+  const float s = p.scale ? __half2float(p.scale[o]) : 1.0f;
+  const float b = p.bias ? __half2float(p.bias[o]) : 0.0f;
+  __half *wrow = W + (long long)o * ldw;
+  if (slot < p.Q) {
+    unsigned i = load_index(p.idx_out + (long long)o * p.stride_out, slot, p.bits_out);
+    i = min(i, (unsigned)p.k_out - 1u);
+    const __half *e = p.cb_out + (long long)i * p.v_out;
+    const int c0 = slot * p.v_out;
+    for (int j = 0; j < p.v_out; ++j) wrow[c0 + j] = restore(__half2float(e[j]), s, b);
+  } else {
+    const int pp = slot - p.Q;
+    unsigned i = load_index(p.idx + (long long)o * p.stride, pp, p.bits);
+    i = min(i, (unsigned)p.k - 1u);
+    const __half *e = p.cb + (long long)i * p.v;
+    const __half *er = nullptr;
+    if (p.k_res) {
+      unsigned r = load_index(p.idx_res + (long long)o * p.stride_res, pp, p.bits_res);
+      r = min(r, (unsigned)p.k_res - 1u);
+      er = p.cb_res + (long long)r * p.v;
+    }
+    const int c0 = p.n_out + pp * p.v;
+    for (int j = 0; j < p.v; ++j) {
+      if (c0 + j >= p.in_features) break;
+      float d = __half2float(e[j]);
+      if (er) d = __fadd_rn(d, __half2float(er[j]));
+      wrow[c0 + j] = restore(d, s, b);
+    }
+  }
+}
+
+int launch_dequant(const Params &p, __half *W, long long ldw, hipStream_t s) {
+  const int slots = p.P + p.Q;
+  const int blocks_per_row = (slots + 255) / 256;
+  const long long blocks = (long long)blocks_per_row * p.out_features;
+  if (blocks > 0x7fffffffLL) return VQ_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(dequant_generic_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, W, ldw, blocks_per_row);
+  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+}  // namespace vq

@@ -1,0 +1,140 @@
+// vq_gemm: prompt-phase product Y = X * W^T with W restored on the fly into LDS tiles that feed the
+// FP16 matrix cores (paper App. "Our Dequantization Implementation", first phase, but without ever
+// writing W to memory).  Accumulation in binary32, FP16 result.
+#include "vq_common.hpp"
+
+namespace vq {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 128;        // tokens per workgroup tile
+constexpr int BN = 128;        // output channels per workgroup tile
+constexpr int BK = 32;         // input columns per step
+constexpr int LDT = BK + 8;    // LDS row pitch in halfs: 80 bytes, so 8 consecutive rows hit 8 different 16-byte bank groups
+
+// Restore columns [c0, c0+n) of row o into dst (LDS), zero past in_features.  Any layer shape.
+__device__ __forceinline__ void restore_run_generic(const Params &p, int o, int c0, int n, float s, float b, __half *dst) {
+  int c = c0;
+  int j = 0, len = 0;                     // position inside / length of the current vector
+  const __half *e = nullptr, *er = nullptr;
+  for (int t = 0; t < n; ++t, ++c) {
+    if (o >= p.out_features || c >= p.in_features) { dst[t] = __float2half_rn(0.0f); continue; }
+    if (j >= len) {                       // fetch the vector that holds column c
+      er = nullptr;
+      if (c < p.n_out) {
+        const int q = c / p.v_out;
+        j = c - q * p.v_out; len = p.v_out;
+        unsigned i = min(load_index(p.idx_out + (long long)o * p.stride_out, q, p.bits_out), (unsigned)p.k_out - 1u);
+        e = p.cb_out + (long long)i * p.v_out;
+      } else {
+        const int cc = c - p.n_out;
+        const int pp = cc / p.v;
+        j = cc - pp * p.v; len = p.v;
+        unsigned i = min(load_index(p.idx + (long long)o * p.stride, pp, p.bits), (unsigned)p.k - 1u);
+        e = p.cb + (long long)i * p.v;
+        if (p.k_res) {
+          unsigned r = min(load_index(p.idx_res + (long long)o * p.stride_res, pp, p.bits_res), (unsigned)p.k_res - 1u);
+          er = p.cb_res + (long long)r * p.v;
+        }
+      }
+    }
+    float d = __half2float(e[j]);
+    if (er) d = __fadd_rn(d, __half2float(er[j]));
+    dst[t] = restore(d, s, b);
+    ++j;
+    if (c + 1 == p.n_out) j = len;        // the outlier region ends: force a fetch from the main stream
+  }
+}
+
+// 256 threads = 4 waves in a 2x2 arrangement; each wave owns a 64x64 block of the 128x128 tile as
+// 2x2 MFMA 32x32x16 blocks.  Operand layout of v_mfma_f32_32x32x16_f16: lane l supplies row/column
+// (l & 31) and the 8 consecutive k values starting at 8*(l >> 5); it receives column (l & 31) and,
+// in result register r, row 8*(r >> 2) + 4*(l >> 5) + (r & 3).
+__global__ __launch_bounds__(256) void gemm_tile_kernel(Params p, const __half *__restrict__ X, long long ldx, int tokens,
+                                                        __half *__restrict__ Y, long long ldy) {
+  __shared__ __attribute__((aligned(16))) __half Xs[BM * LDT];
+  __shared__ __attribute__((aligned(16))) __half Ws[BN * LDT];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n0 = blockIdx.x * BN, m0 = blockIdx.y * BM;
+  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+
+  float16v acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.0f;
+
+  // W restore assignment: thread -> (row tid/2, 16 columns)
+  const int w_row = tid >> 1, w_col = (tid & 1) * 16;
+  const int o_w = n0 + w_row;
+  const float s_w = (p.scale && o_w < p.out_features) ? __half2float(p.scale[o_w]) : 1.0f;
+  const float b_w = (p.bias && o_w < p.out_features) ? __half2float(p.bias[o_w]) : 0.0f;
+
+  for (int k0 = 0; k0 < p.in_features; k0 += BK) {
+    // X tile: 128 rows x 4 chunks of 8 halfs; thread takes chunks tid and tid+256
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int chunk = tid + h * 256;
+      const int row = chunk >> 2, col = (chunk & 3) * 8;
+      const int t = m0 + row, c = k0 + col;
+      uint4 val = make_uint4(0, 0, 0, 0);
+      if (t < tokens) {
+        const __half *src = X + (long long)t * ldx + c;
+        if (c + 8 <= p.in_features) {
+          val = *reinterpret_cast<const uint4 *>(src);
+        } else if (c < p.in_features) {
+          __half tmp[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) tmp[i] = (c + i < p.in_features) ? src[i] : __float2half_rn(0.0f);
+          val = *reinterpret_cast<uint4 *>(tmp);
+        }
+      }
+      *reinterpret_cast<uint4 *>(&Xs[row * LDT + col]) = val;
+    }
+    restore_run_generic(p, o_w, k0 + w_col, 16, s_w, b_w, &Ws[w_row * LDT + w_col]);
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < BK; ks += 16) {
+      half8 af[2], bf[2];
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+        af[a] = *reinterpret_cast<const half8 *>(&Xs[(wm + a * 32 + (lane & 31)) * LDT + ks + (lane >> 5) * 8]);
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+        bf[c] = *reinterpret_cast<const half8 *>(&Ws[(wn + c * 32 + (lane & 31)) * LDT + ks + (lane >> 5) * 8]);
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+          acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[a], bf[c], acc[a][c], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      const int o = n0 + wn + c * 32 + (lane & 31);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int t = m0 + wm + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (t < tokens && o < p.out_features) Y[(long long)t * ldy + o] = __float2half_rn(acc[a][c][r]);
+      }
+    }
+}
+
+size_t gemm_workspace_bytes(const Params &, int) { return 0; }
+
+int launch_gemm(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy,
+                void *, size_t, hipStream_t s) {
+  const unsigned gx = (unsigned)((p.out_features + BN - 1) / BN), gy = (unsigned)((tokens + BM - 1) / BM);
+  if (gy > 65535u) return VQ_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(gemm_tile_kernel, dim3(gx, gy), dim3(256), 0, s, p, X, ldx, tokens, Y, ldy);
+  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+}  // namespace vq

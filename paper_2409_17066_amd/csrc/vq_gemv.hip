@@ -1,0 +1,60 @@
+// vq_gemv: decode-phase fused restore + matrix-vector product for batch 1..16
+// (paper App. "Our Dequantization Implementation", second phase: the FP16 weights are never written).
+#include "vq_common.hpp"
+
+namespace vq {
+
+// Any layer: one wave per output row, lanes stride over the row's vectors, tables read through the
+// cache hierarchy.  Slow but complete; the specialised kernels below take the common shapes.
+__global__ __launch_bounds__(256) void gemv_generic_kernel(Params p, const __half *__restrict__ x, long long ldx, int batch,
+                                                           __half *__restrict__ y, long long ldy) {
+  const int lane = threadIdx.x & 63;
+  const int o = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (o >= p.out_features) return;
+  const float s = p.scale ? __half2float(p.scale[o]) : 1.0f;
+  const float b = p.bias ? __half2float(p.bias[o]) : 0.0f;
+  float acc[16];
+#pragma unroll
+  for (int t = 0; t < 16; ++t) acc[t] = 0.0f;
+  for (int slot = lane; slot < p.Q + p.P; slot += 64) {
+    const __half *e, *er = nullptr;
+    int c0, len;
+    if (slot < p.Q) {
+      unsigned i = min(load_index(p.idx_out + (long long)o * p.stride_out, slot, p.bits_out), (unsigned)p.k_out - 1u);
+      e = p.cb_out + (long long)i * p.v_out;
+      c0 = slot * p.v_out; len = p.v_out;
+    } else {
+      const int pp = slot - p.Q;
+      unsigned i = min(load_index(p.idx + (long long)o * p.stride, pp, p.bits), (unsigned)p.k - 1u);
+      e = p.cb + (long long)i * p.v;
+      if (p.k_res) {
+        unsigned r = min(load_index(p.idx_res + (long long)o * p.stride_res, pp, p.bits_res), (unsigned)p.k_res - 1u);
+        er = p.cb_res + (long long)r * p.v;
+      }
+      c0 = p.n_out + pp * p.v; len = min(p.v, p.in_features - c0);
+    }
+    for (int j = 0; j < len; ++j) {
+      float d = __half2float(e[j]);
+      if (er) d = __fadd_rn(d, __half2float(er[j]));
+      const float w = __half2float(restore(d, s, b));
+#pragma unroll
+      for (int t = 0; t < 16; ++t)
+        if (t < batch) acc[t] = __fmaf_rn(w, __half2float(x[t * ldx + c0 + j]), acc[t]);
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < 16; ++t) {
+    if (t < batch) {
+      const float r = wave_sum(acc[t]);
+      if (lane == 0) y[t * ldy + o] = __float2half_rn(r);
+    }
+  }
+}
+
+int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
+  const unsigned blocks = (unsigned)((p.out_features + 3) / 4);
+  hipLaunchKernelGGL(gemv_generic_kernel, dim3(blocks), dim3(256), 0, s, p, x, ldx, batch, y, ldy);
+  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+}  // namespace vq

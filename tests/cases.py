@@ -1,0 +1,27 @@
+"""Small layers for GPU parity: every shape spans several kernel tiles and ends in a ragged tail."""
+import vq_synth as s
+
+# name -> make_layer keyword arguments (config id 300+ keeps their seeds apart from the benchmark layers)
+SMALL = {
+    "v6_k256": dict(out_features=70, in_features=391, v=6, k=256),
+    "v6_k4096": dict(out_features=261, in_features=1030, v=6, k=4096),
+    "v6_k4096_res4096": dict(out_features=133, in_features=1000, v=6, k=4096, k_res=4096),
+    "v6_res256_outlier": dict(out_features=150, in_features=1207, v=6, k=4096, k_res=256, n_outlier_cols=24, v_out=4, k_out=4096),
+    "v8_k65536": dict(out_features=200, in_features=520, v=8, k=65536),
+    "v8_k65536_unscaled": dict(out_features=129, in_features=264, v=8, k=65536, with_scale=False, with_bias=False),
+    "odd_everything": dict(out_features=37, in_features=203, v=5, k=37, k_res=11, n_outlier_cols=9, v_out=3, k_out=5),
+    "v1_k2": dict(out_features=9, in_features=77, v=1, k=2),
+    "v16_k300": dict(out_features=33, in_features=530, v=16, k=300, with_scale=False),
+    "v2_k16_nobias": dict(out_features=65, in_features=130, v=2, k=16, with_bias=False),
+    "v4_k256_res16": dict(out_features=64, in_features=256, v=4, k=256, k_res=16),
+    "v12_k4096_res4096": dict(out_features=40, in_features=600, v=12, k=4096, k_res=4096),
+    "single_row": dict(out_features=1, in_features=4096, v=6, k=4096),
+    "single_vector": dict(out_features=300, in_features=5, v=6, k=4096),
+    "padded_stride": dict(out_features=50, in_features=300, v=6, k=4096, k_res=256, extra_stride=2),
+}
+
+
+def small_layer(name):
+    kw = dict(SMALL[name])
+    return s.make_layer(300 + list(SMALL).index(name), name, kw.pop("out_features"), kw.pop("in_features"),
+                        kw.pop("v"), kw.pop("k"), **kw)

@@ -1,0 +1,94 @@
+"""The C-ABI boundary on the host: exported symbols and argument validation (no GPU work is enqueued)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2409_17066_amd as vq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "vq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(vq_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = vq.load()
+    names = _declared_functions()
+    assert set(names) == set(vq.EXPORTED)
+    for n in names:
+        assert getattr(lib, n) is not None
+        assert callable(getattr(vq, n))        # the binding carries the same names
+
+
+def test_version_and_status_strings():
+    assert vq.vq_version() >= 100
+    texts = {vq.vq_status_string(s) for s in range(0, -7, -1)}
+    assert len(texts) == 7 and vq.vq_status_string(-99) == "unknown status"
+
+
+def _desc(**kw):
+    d = vq.vq_layer_desc(ctypes.sizeof(vq.vq_layer_desc), 8, 30, 6, 256, 0, 0, 0, 0,
+                         0x1000, None, None, 0x2000, 16, None, 0, None, 0, None, None)
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+def test_valid_descriptor_passes():
+    assert vq.vq_validate(_desc()) == vq.VQ_OK
+    assert vq.vq_validate(_desc(k_res=16, codebook_res=0x3000, idx_res=0x4000, idx_res_row_stride=16)) == vq.VQ_OK
+    assert vq.vq_validate(_desc(n_outlier_cols=8, v_out=4, k_out=16, codebook_out=0x3000, idx_out=0x4000,
+                                idx_out_row_stride=16)) == vq.VQ_OK
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(struct_size=4), vq.VQ_ERR_SHAPE),
+    (dict(out_features=0), vq.VQ_ERR_SHAPE),
+    (dict(in_features=0), vq.VQ_ERR_SHAPE),
+    (dict(v=0), vq.VQ_ERR_SHAPE), (dict(v=17), vq.VQ_ERR_SHAPE),
+    (dict(k=1), vq.VQ_ERR_SHAPE), (dict(k=65537), vq.VQ_ERR_SHAPE),
+    (dict(k_res=1), vq.VQ_ERR_SHAPE),
+    (dict(codebook=None), vq.VQ_ERR_NULL), (dict(idx=None), vq.VQ_ERR_NULL),
+    (dict(codebook=0x1008), vq.VQ_ERR_ALIGNMENT), (dict(idx=0x2004), vq.VQ_ERR_ALIGNMENT),
+    (dict(idx_row_stride=0), vq.VQ_ERR_SHAPE),            # 5 vectors x 8 bits need 5 bytes
+    (dict(idx_row_stride=24), vq.VQ_ERR_ALIGNMENT),
+    (dict(k_res=16), vq.VQ_ERR_NULL),
+    (dict(k_res=16, codebook_res=0x3000, idx_res=0x4000, idx_res_row_stride=0), vq.VQ_ERR_SHAPE),
+    (dict(n_outlier_cols=7, v_out=4, k_out=16, codebook_out=0x3000, idx_out=0x4000, idx_out_row_stride=16), vq.VQ_ERR_SHAPE),
+    (dict(n_outlier_cols=32, v_out=4, k_out=16, codebook_out=0x3000, idx_out=0x4000, idx_out_row_stride=16), vq.VQ_ERR_SHAPE),
+    (dict(n_outlier_cols=8, v_out=4, k_out=16), vq.VQ_ERR_NULL),
+    (dict(scale=0x5001), vq.VQ_ERR_ALIGNMENT),
+])
+def test_invalid_descriptors(kw, status):
+    assert vq.vq_validate(_desc(**kw)) == status
+
+
+def test_entry_points_reject_bad_arguments_before_any_launch():
+    d = _desc()
+    assert vq.vq_validate(None) == vq.VQ_ERR_NULL
+    assert vq.vq_dequant(None, 0x9000, 30) == vq.VQ_ERR_NULL
+    assert vq.vq_dequant(d, None, 30) == vq.VQ_ERR_NULL
+    assert vq.vq_dequant(d, 0x9000, 29) == vq.VQ_ERR_SHAPE
+    assert vq.vq_dequant(d, 0x9001, 30) == vq.VQ_ERR_ALIGNMENT
+    assert vq.vq_gemv(d, None, 30, 1, 0x9000, 8) == vq.VQ_ERR_NULL
+    assert vq.vq_gemv(d, 0x8000, 30, 0, 0x9000, 8) == vq.VQ_ERR_SHAPE
+    assert vq.vq_gemv(d, 0x8000, 30, 17, 0x9000, 8) == vq.VQ_ERR_SHAPE
+    assert vq.vq_gemv(d, 0x8000, 28, 1, 0x9000, 8) == vq.VQ_ERR_SHAPE
+    assert vq.vq_gemv(d, 0x8000, 30, 1, 0x9000, 7) == vq.VQ_ERR_SHAPE
+    assert vq.vq_gemv(d, 0x8001, 30, 1, 0x9000, 8) == vq.VQ_ERR_ALIGNMENT
+    assert vq.vq_gemv(d, 0x8000, 30, 1, 0x9001, 8) == vq.VQ_ERR_ALIGNMENT
+    assert vq.vq_gemm(d, 0x8000, 32, 0, 0x9000, 8) == vq.VQ_ERR_SHAPE        # empty token batch
+    assert vq.vq_gemm(d, 0x8000, 30, 4, 0x9000, 8) == vq.VQ_ERR_ALIGNMENT    # ldx not a multiple of 8
+    assert vq.vq_gemm(d, 0x8008, 32, 4, 0x9000, 8) == vq.VQ_ERR_ALIGNMENT
+    assert vq.vq_gemm(d, None, 32, 4, 0x9000, 8) == vq.VQ_ERR_NULL
+    assert vq.vq_gemm_workspace_bytes(_desc(v=0), 4) == 0
+
+
+def test_binding_has_no_cpu_fallback():
+    src = open(os.path.join(ROOT, "paper_2409_17066_amd", "__init__.py")).read()
+    assert "oracle" not in src.replace("no CPU fallback", "")

@@ -1,0 +1,113 @@
+"""GPU parity: the HIP library through its C ABI against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+import oracle
+import vq_synth as s
+from cases import SMALL, small_layer
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-2        # max |y - y_ref| <= TOL * RMS(y_ref): the stated bar for GEMV and GEMM
+
+
+def _check_matmul(y_gpu, y_ref, what):
+    y = y_gpu.float().cpu().numpy().astype(np.float64)
+    rms = np.sqrt((y_ref ** 2).mean())
+    err = np.abs(y - y_ref).max()
+    assert np.isfinite(y).all(), what
+    assert err <= TOL * rms, "%s: max abs err %.3e > %.0e * rms %.3e" % (what, err, TOL, rms)
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_dequant_bit_exact_small(gpu_lib, name):
+    import torch
+    L = small_layer(name)
+    dl = gpu_lib.DeviceLayer(L)
+    for ldw in (L.in_features, L.in_features + 11):
+        W = gpu_lib.dequant(dl, ldw)
+        torch.cuda.synchronize()
+        want = oracle.dequant(L, ldw)
+        assert np.array_equal(W.cpu().numpy().view(np.uint16), want.view(np.uint16)), name
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+@pytest.mark.parametrize("batch", [1, 2, 3, 4, 8, 16])
+def test_gemv_small(gpu_lib, name, batch):
+    import torch
+    L = small_layer(name)
+    dl = gpu_lib.DeviceLayer(L)
+    x = s.make_activations(300, L, batch)
+    y = gpu_lib.gemv(dl, torch.from_numpy(x).cuda())
+    torch.cuda.synchronize()
+    _check_matmul(y, oracle.gemv(L, x), "%s batch %d" % (name, batch))
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+@pytest.mark.parametrize("tokens", [1, 37, 130, 300])
+def test_gemm_small(gpu_lib, name, tokens):
+    import torch
+    L = small_layer(name)
+    dl = gpu_lib.DeviceLayer(L)
+    x = s.make_activations(300, L, tokens)
+    ldx = (L.in_features + 7) // 8 * 8
+    X = torch.zeros((tokens, ldx), dtype=torch.float16, device="cuda")
+    X[:, : L.in_features] = torch.from_numpy(x).cuda()
+    if ldx > L.in_features:
+        X[:, L.in_features:] = float("nan")           # padding of the caller's buffer must never be read into the sum
+    Y = gpu_lib.gemm(dl, X)
+    torch.cuda.synchronize()
+    _check_matmul(Y, oracle.gemm(L, x), "%s tokens %d" % (name, tokens))
+
+
+def test_gemv_strided_buffers_and_untouched_padding(gpu_lib):
+    import torch
+    L = small_layer("v6_res256_outlier")
+    dl = gpu_lib.DeviceLayer(L)
+    x = s.make_activations(300, L, 4)
+    xb = torch.full((4, L.in_features + 10), float("nan"), dtype=torch.float16, device="cuda")
+    xb[:, : L.in_features] = torch.from_numpy(x).cuda()
+    yb = torch.full((4, L.out_features + 6), 7.0, dtype=torch.float16, device="cuda")
+    gpu_lib.gemv(dl, xb, out=yb)
+    torch.cuda.synchronize()
+    _check_matmul(yb[:, : L.out_features], oracle.gemv(L, x), "strided")
+    assert (yb[:, L.out_features:] == 7.0).all()
+
+
+def test_unit_activation_reads_back_a_column(gpu_lib):
+    import torch
+    L = small_layer("v6_res256_outlier")
+    dl = gpu_lib.DeviceLayer(L)
+    W = oracle.dequant(L).astype(np.float64)
+    cols = [0, 5, 23, 24, 29, 30, 1205, 1206]
+    for c0 in range(0, len(cols), 4):
+        x = np.zeros((4, L.in_features), dtype=np.float16)
+        for t, c in enumerate(cols[c0:c0 + 4]):
+            x[t, c] = 1.0
+        y = gpu_lib.gemv(dl, torch.from_numpy(x).cuda()).float().cpu().numpy()
+        for t, c in enumerate(cols[c0:c0 + 4]):
+            assert np.allclose(y[t], W[:, c], rtol=2e-3, atol=1e-7)
+
+
+def test_runs_are_deterministic(gpu_lib):
+    import torch
+    L = small_layer("v6_k4096_res4096")
+    dl = gpu_lib.DeviceLayer(L)
+    x = torch.from_numpy(s.make_activations(300, L, 4)).cuda()
+    a = gpu_lib.gemv(dl, x).clone()
+    for _ in range(3):
+        assert torch.equal(gpu_lib.gemv(dl, x), a)
+
+
+def test_non_default_stream(gpu_lib):
+    import torch
+    L = small_layer("v6_k4096")
+    dl = gpu_lib.DeviceLayer(L)
+    x = s.make_activations(300, L, 1)
+    xs = torch.from_numpy(x).cuda()
+    torch.cuda.synchronize()
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        y = gpu_lib.gemv(dl, xs)
+    st.synchronize()
+    _check_matmul(y, oracle.gemv(L, x), "side stream")
