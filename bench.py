@@ -1,0 +1,248 @@
+#!/usr/bin/env python3
+"""Benchmark of the VQ linear-layer hot path on one MI355X.
+
+A step is one batch-1 vq_gemv call (index unpack -> codebook lookups -> residual / outlier merge ->
+scale/bias -> matrix-vector product) on the Llama-2-7B-shaped 11008 x 4096 layer (v=6, k=4096,
+12-bit packed indices).  Consecutive steps rotate over distinct device copies of the index stream
+whose total size exceeds the 256 MB Infinity Cache, so every step streams its indices from HBM.
+`value` is algorithmic bytes per step / time per step.  The other layers (residual, outlier columns,
+batch > 1), the prefill vq_gemm and vq_dequant are timed briefly and reported under "detail".
+
+Prints ONE JSON line.  Inputs are seeded synthetic tensors that stand in for real quantized
+checkpoints (same shapes and (v, k) settings; Gaussian tables, uniform indices).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor figure
+MFMA_FP16_PEAK_TFLOPS = 2500.0  # dense FP16 matrix-core peak, vendor figure
+ROTATE_BYTES = 640 << 20        # footprint of the rotated index copies (> 2 x the 256 MB Infinity Cache)
+
+# HBM traffic per launch from `rocprofv3 --pmc` (FETCH_SIZE and WRITE_SIZE, each scaled by what the same
+# counter reads for a copy kernel of known size); see profiles/.  None until measured for the kernel in use.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--config", type=int, default=1, help="benchmark configuration of the headline GEMV (1 or 3)")
+    ap.add_argument("--no-detail", action="store_true", help="skip the secondary measurements")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    return ap.parse_args()
+
+
+class Rotation:
+    """R device copies of a layer's index streams (tables, scale and bias are shared)."""
+
+    def __init__(self, vq, layer, min_bytes=ROTATE_BYTES, max_copies=64):
+        import torch
+        self.base = vq.DeviceLayer(layer)
+        stream_bytes = sum(a.nbytes for a in (layer.idx, layer.idx_res, layer.idx_out) if a is not None)
+        copies = max(2, min(max_copies, -(-min_bytes // stream_bytes)))
+        self.descs = [self.base.desc]
+        self.keep = []
+        import ctypes
+        for _ in range(copies - 1):
+            d = vq.vq_layer_desc()
+            ctypes.memmove(ctypes.byref(d), ctypes.byref(self.base.desc), ctypes.sizeof(d))
+            for name in ("idx", "idx_res", "idx_out"):
+                t = self.base.tensors.get(name)
+                if t is not None:
+                    c = t.clone()
+                    self.keep.append(c)
+                    setattr(d, name, c.data_ptr())
+            self.descs.append(d)
+        torch.cuda.synchronize()
+        self.copies = copies
+
+
+def timed(launch, steps, warmup, use_graph=True):
+    """Run `warmup` untimed and `steps` timed calls of launch(i).  Returns (wall seconds, event seconds)."""
+    import torch
+    stream = torch.cuda.current_stream()
+    for i in range(warmup):
+        launch(i)
+    torch.cuda.synchronize()
+    graph = None
+    if use_graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
+            for i in range(steps):
+                launch(i)
+        graph.replay()                 # untimed: uploads the graph
+        torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record(stream)
+    if graph is not None:
+        graph.replay()
+    else:
+        for i in range(steps):
+            launch(i)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall, e0.elapsed_time(e1) * 1e-3
+
+
+def bench_gemv(vq, layer, x_np, steps, warmup, use_graph):
+    import torch
+    rot = Rotation(vq, layer)
+    x = torch.from_numpy(x_np).cuda()
+    batch = x.shape[0]
+    y = torch.empty((batch, layer.out_features), dtype=torch.float16, device="cuda")
+    xp, yp, ldx, ldy = x.data_ptr(), y.data_ptr(), x.stride(0), y.stride(0)
+
+    def launch(i):
+        rc = vq.vq_gemv(rot.descs[i % rot.copies], xp, ldx, batch, yp, ldy, torch.cuda.current_stream().cuda_stream)
+        if rc != 0:
+            raise vq.VQError(rc, "vq_gemv")
+    wall, ev = timed(launch, steps, warmup, use_graph)
+    return dict(wall_s=wall, event_s=ev, copies=rot.copies, y=y)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the layer shards by output rows; no multi-GPU path is built). "
+              "Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import vq_synth as s
+    import paper_2409_17066_amd as vq
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    vq.load()
+    torch.cuda.set_device(0)
+    use_graph = not args.no_graph
+    cfg = args.config
+    spec = s.CONFIGS[cfg]
+    _, layer = next(s.config_layers(cfg))
+    x_np = s.make_activations(cfg, layer, 1, outlier_gain=spec.get("outlier_gain", 1.0))
+    r = bench_gemv(vq, layer, x_np, args.steps, args.warmup, use_graph)
+    alg = layer.algorithmic_bytes(1)
+    sec = r["event_s"] / args.steps
+    gbps = alg / sec / 1e9
+    wall_gbps = alg * args.steps / r["wall_s"] / 1e9
+    workload = "cfg%d %s %dx%d v%d k%d%s%s batch1 gemv" % (
+        cfg, layer.name, layer.out_features, layer.in_features, layer.v, layer.k,
+        " res%d" % layer.k_res if layer.k_res else "", " outlier%d" % layer.n_outlier_cols if layer.n_outlier_cols else "")
+    result = {
+        "metric": "batch-1 VQ-GEMV effective HBM bandwidth (algorithmic bytes / time)",
+        "value": round(wall_gbps, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(r["wall_s"] / args.steps * 1e3, 6), "us_per_step": round(r["wall_s"] / args.steps * 1e6, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16 in, f32 accumulate",
+        "data": "synthetic (seeded Gaussian tables, uniform indices; stands in for quantized Llama-2 layers)",
+        "config": {"workload": workload, "algorithmic_bytes": alg, "index_copies_rotated": r["copies"],
+                   "launch": "hip graph replay" if use_graph else "eager"},
+        "roofline": {"bound": "hbm", "achieved": round(gbps, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg),
+                     "kernel_us": round(sec * 1e6, 3)},
+    }
+
+    # parity spot check of the timed configuration against the oracle (sampled rows)
+    import oracle
+    rows = np.unique(np.linspace(0, layer.out_features - 1, 256).astype(np.int32))
+    ref = oracle.gemv(layer, x_np, rows=rows)
+    full_rms = float(np.sqrt((ref ** 2).mean()))
+    err = float(np.abs(r["y"].float().cpu().numpy()[:, rows] - ref).max())
+    result["parity"] = {"max_abs_err": err, "tolerance": 1e-2 * full_rms, "ok": bool(err <= 1e-2 * full_rms)}
+
+    if not args.no_cpu_baseline:
+        nthreads = oracle.default_threads()
+        t_end = time.perf_counter() + args.cpu_seconds
+        best, passes = None, 0
+        while passes < 3 or time.perf_counter() < t_end:
+            t0 = time.perf_counter()
+            oracle.gemv(layer, x_np, n_threads=nthreads)
+            dt = time.perf_counter() - t0
+            best = dt if best is None else min(best, dt)
+            passes += 1
+            if passes >= 200:
+                break
+        result["cpu_baseline"] = {"value": round(alg / best / 1e9, 4), "unit": "GB/s", "cores": nthreads, "kind": "oracle",
+                                  "sample": "%d full passes of the same layer and activation (best pass %.1f ms)" % (passes, best * 1e3)}
+
+    if not args.no_detail:
+        result["detail"] = detail(vq, s, np, torch, use_graph, skip=(cfg, 1))
+    print(json.dumps(result))
+
+
+def detail(vq, s, np, torch, use_graph, skip):
+    """Short timings of the other benchmark layers and entry points."""
+    out = []
+    steps, warmup = 400, 50
+
+    def gemv_line(cfg, ordinal, layer, batch):
+        spec = s.CONFIGS[cfg]
+        x_np = s.make_activations(cfg, layer, batch, layer_ordinal=ordinal, outlier_gain=spec.get("outlier_gain", 1.0))
+        r = bench_gemv(vq, layer, x_np, steps, warmup, use_graph)
+        sec = r["event_s"] / steps
+        alg = layer.algorithmic_bytes(batch)
+        flops = 2.0 * batch * layer.out_features * layer.in_features
+        out.append({"op": "vq_gemv", "cfg": cfg, "layer": layer.name, "batch": batch, "us": round(sec * 1e6, 3),
+                    "GB/s": round(alg / sec / 1e9, 1), "frac_hbm_peak": round(alg / sec / 1e9 / HBM_PEAK_GBPS, 4),
+                    "TFLOP/s": round(flops / sec / 1e12, 2)})
+
+    for cfg in (1, 2, 3):
+        spec = s.CONFIGS[cfg]
+        names = [n for n, _, _ in spec["layers"]]
+        if cfg == 2:
+            names = ["q", "gate", "down"]              # k, v, o share q's shape; up shares gate's
+        for ordinal, layer in s.config_layers(cfg):
+            if layer.name not in names:
+                continue
+            for batch in spec["rows"]:
+                if (cfg, batch) == skip:
+                    continue
+                gemv_line(cfg, ordinal, layer, batch)
+            del layer
+    # prefill GEMM and dequant on the 8192 x 8192, v=8, k=65536 layer
+    _, L4 = next(s.config_layers(4))
+    dl = vq.DeviceLayer(L4)
+    for tokens in s.CONFIGS[4]["rows"]:
+        X = torch.from_numpy(s.make_activations(4, L4, tokens)).cuda()
+        Y = torch.empty((tokens, L4.out_features), dtype=torch.float16, device="cuda")
+        need = vq.vq_gemm_workspace_bytes(dl.desc, tokens)
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+
+        def launch(i):
+            rc = vq.vq_gemm(dl.desc, X.data_ptr(), X.stride(0), tokens, Y.data_ptr(), Y.stride(0), ws.data_ptr(), need,
+                            torch.cuda.current_stream().cuda_stream)
+            if rc != 0:
+                raise vq.VQError(rc, "vq_gemm")
+        n = 10
+        wall, ev = timed(launch, n, 2, use_graph=False)
+        sec = ev / n
+        flops = 2.0 * tokens * L4.out_features * L4.in_features
+        out.append({"op": "vq_gemm", "cfg": 4, "tokens": tokens, "us": round(sec * 1e6, 1),
+                    "TFLOP/s": round(flops / sec / 1e12, 1), "frac_mfma_peak": round(flops / sec / 1e12 / MFMA_FP16_PEAK_TFLOPS, 4)})
+    W = torch.empty((L4.out_features, L4.in_features), dtype=torch.float16, device="cuda")
+
+    def launch_dq(i):
+        rc = vq.vq_dequant(dl.desc, W.data_ptr(), W.stride(0), torch.cuda.current_stream().cuda_stream)
+        if rc != 0:
+            raise vq.VQError(rc, "vq_dequant")
+    wall, ev = timed(launch_dq, 20, 3, use_graph=False)
+    sec = ev / 20
+    moved = W.numel() * 2 + L4.idx.nbytes + L4.codebook.nbytes
+    out.append({"op": "vq_dequant", "cfg": 4, "us": round(sec * 1e6, 1), "GB/s": round(moved / sec / 1e9, 1),
+                "frac_hbm_peak": round(moved / sec / 1e9 / HBM_PEAK_GBPS, 4)})
+    return out
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,83 @@
+"""GPU parity at the five benchmark configurations, full size, through the C ABI."""
+import numpy as np
+import pytest
+
+import oracle
+import vq_synth as s
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-2
+
+
+@pytest.fixture(scope="module")
+def layers():
+    cache = {}
+
+    def get(cfg, name=None):
+        key = (cfg, name)
+        if key not in cache:
+            cache.clear()                      # one big layer resident at a time
+            cache[key] = next(s.config_layers(cfg, only=name))
+        return cache[key]
+    return get
+
+
+def _dequant_exact(gpu_lib, L):
+    import torch
+    dl = gpu_lib.DeviceLayer(L)
+    W = gpu_lib.dequant(dl)
+    torch.cuda.synchronize()
+    got = W.cpu().numpy().view(np.uint16)
+    del W
+    want = oracle.dequant(L).view(np.uint16)
+    assert np.array_equal(got, want)
+    return dl
+
+
+def _matmul_ok(y, ref, what):
+    y = y.float().cpu().numpy().astype(np.float64)
+    rms = np.sqrt((ref ** 2).mean())
+    err = np.abs(y - ref).max()
+    assert np.isfinite(y).all() and err <= TOL * rms, "%s: err %.3e rms %.3e" % (what, err, rms)
+
+
+@pytest.mark.parametrize("cfg,name", [(0, "tiny"), (1, "up"), (2, "q"), (2, "gate"), (2, "down"), (3, "down70b"), (4, "prefill")])
+def test_config_dequant_and_gemv(gpu_lib, layers, cfg, name):
+    import torch
+    ordinal, L = layers(cfg, name)
+    dl = _dequant_exact(gpu_lib, L)
+    spec = s.CONFIGS[cfg]
+    batches = spec["rows"] if cfg != 4 else [1, 16]
+    for batch in batches:
+        x = s.make_activations(cfg, L, batch, layer_ordinal=ordinal, outlier_gain=spec.get("outlier_gain", 1.0))
+        y = gpu_lib.gemv(dl, torch.from_numpy(x).cuda())
+        torch.cuda.synchronize()
+        _matmul_ok(y, oracle.gemv(L, x), "cfg%d %s batch %d" % (cfg, name, batch))
+
+
+@pytest.mark.parametrize("tokens", [512, 1024, 2048])
+def test_config4_prefill_gemm(gpu_lib, layers, tokens):
+    import torch
+    _, L = layers(4, "prefill")
+    dl = gpu_lib.DeviceLayer(L)
+    x = s.make_activations(4, L, tokens)
+    Y = gpu_lib.gemm(dl, torch.from_numpy(x).cuda())
+    torch.cuda.synchronize()
+    if tokens == 512:
+        _matmul_ok(Y, oracle.gemm(L, x), "cfg4 T=512 full")
+    else:
+        # larger token counts: every 16th output row plus the edges, all tokens
+        rows = np.unique(np.concatenate([np.arange(0, L.out_features, 16), [L.out_features - 1, 127, 128, 8191 - 128]])).astype(np.int32)
+        ref = oracle.gemm(L, x, rows=rows)
+        _matmul_ok(Y[:, torch.from_numpy(rows.astype(np.int64)).cuda()], ref, "cfg4 T=%d sampled rows" % tokens)
+
+
+def test_config3_small_gemm_with_outliers(gpu_lib, layers):
+    import torch
+    _, L = layers(3, "down70b")
+    sub = s.make_layer(3, "slice", 256, L.in_features, 6, 4096, 256, 288, 4, 4096)
+    dl = gpu_lib.DeviceLayer(sub)
+    x = s.make_activations(3, sub, 64, outlier_gain=10.0)
+    Y = gpu_lib.gemm(dl, torch.from_numpy(x).cuda())
+    torch.cuda.synchronize()
+    _matmul_ok(Y, oracle.gemm(sub, x), "cfg3 slice gemm")
