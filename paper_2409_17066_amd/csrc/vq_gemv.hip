@@ -1,6 +1,7 @@
 // vq_gemv: decode-phase fused restore + matrix-vector product for batch 1..16
 // (paper App. "Our Dequantization Implementation", second phase: the FP16 weights are never written).
 #include "vq_common.hpp"
+#include <cstdlib>
 
 namespace vq {
 
@@ -51,7 +52,27 @@ __global__ __launch_bounds__(256) void gemv_generic_kernel(Params p, const __hal
   }
 }
 
+bool gemv_fast_applicable(const Params &p, const __half *x, long long ldx);
+int launch_gemv_fast(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
+
+static bool force_generic() {
+  static const bool v = [] { const char *e = getenv("VQ_GEMV_KERNEL"); return e && e[0] == 'g'; }();
+  return v;
+}
+
 int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
+  if (!force_generic() && gemv_fast_applicable(p, x, ldx)) {
+    // batch rows go in groups of 4, 2 or 1; every group streams the indices once
+    int done = 0, rc = VQ_OK;
+    while (done < batch) {
+      const int g = batch - done >= 4 ? 4 : batch - done >= 2 ? 2 : 1;
+      rc = launch_gemv_fast(p, x + done * ldx, ldx, g, y + done * ldy, ldy, s);
+      if (rc != VQ_OK) break;
+      done += g;
+    }
+    if (rc == VQ_OK) return VQ_OK;
+    if (rc != VQ_ERR_UNSUPPORTED || done != 0) return rc;
+  }
   const unsigned blocks = (unsigned)((p.out_features + 3) / 4);
   hipLaunchKernelGGL(gemv_generic_kernel, dim3(blocks), dim3(256), 0, s, p, x, ldx, batch, y, ldy);
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;

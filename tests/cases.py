@@ -17,6 +17,9 @@ SMALL = {
     "v12_k4096_res4096": dict(out_features=40, in_features=600, v=12, k=4096, k_res=4096),
     "single_row": dict(out_features=1, in_features=4096, v=6, k=4096),
     "single_vector": dict(out_features=300, in_features=5, v=6, k=4096),
+    "v6_exact_fit": dict(out_features=3, in_features=6144, v=6, k=4096, k_res=4096),      # stream fills its row stride exactly
+    "v6_many_rows": dict(out_features=9000, in_features=390, v=6, k=4096, k_res=256),    # several row chunks per workgroup
+    "v6_wide_outlier": dict(out_features=70, in_features=2600, v=6, k=4096, n_outlier_cols=1200, v_out=4, k_out=4096),
     "padded_stride": dict(out_features=50, in_features=300, v=6, k=4096, k_res=256, extra_stride=2),
 }
 
