@@ -64,9 +64,12 @@ int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __ha
   if (!force_generic() && gemv_fast_applicable(p, x, ldx)) {
     // batch rows go in groups of 4, 2 or 1; every group streams the indices once
     int done = 0, rc = VQ_OK;
+    int g_max = 4;                      // largest group the layer's plan admits (found on the first group)
     while (done < batch) {
-      const int g = batch - done >= 4 ? 4 : batch - done >= 2 ? 2 : 1;
+      int g = batch - done >= 4 ? 4 : batch - done >= 2 ? 2 : 1;
+      if (g > g_max) g = g_max;
       rc = launch_gemv_fast(p, x + done * ldx, ldx, g, y + done * ldy, ldy, s);
+      if (rc == VQ_ERR_UNSUPPORTED && g > 1) { g_max = g / 2; continue; }
       if (rc != VQ_OK) break;
       done += g;
     }

@@ -10,15 +10,22 @@
 // accumulates with v_dot2_f32_f16.  Row sums are reduced across the wave with DPP and across slices
 // through a small LDS array; scale and bias are applied once per row as y = s * sum(d x) + b * sum(x).
 #include "vq_common.hpp"
+#include <cstdlib>
 
 namespace vq {
+
+#ifdef VQ_PROFILE
+__device__ unsigned long long g_prof[1024 * 16 * 8];
+#define VQ_STAMP(i) do { if (lane == 0) g_prof[(blockIdx.x * 16 + wv) * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define VQ_STAMP(i) do { } while (0)
+#endif
 
 namespace {
 
 constexpr int NW = 16;           // waves per workgroup
-constexpr int RC = 32;           // rows per reduction chunk
+constexpr int RC = 64;           // rows per reduction chunk
 constexpr int MAX_SLICES = 16;
-constexpr int NDW = 8;           // dwords in an index window
 
 struct GemvPlan {
   int W, U;                      // main slices per row, vectors per lane
@@ -26,13 +33,21 @@ struct GemvPlan {
   int RS;                        // row streams (rows in flight) for the main waves
   int rows_per_wg;
   unsigned lds_res, lds_out, lds_part, lds_xsum;   // byte offsets into dynamic LDS (main table at 0)
+  unsigned x_bytes;                                // bytes of one activation row staged through LDS (multiple of 16)
 };
 
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef unsigned uint4v __attribute__((ext_vector_type(4)));
+typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+typedef unsigned uint3v __attribute__((ext_vector_type(3)));
 
 __device__ __forceinline__ float dot2(unsigned a, unsigned b, float c) {
   return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, a), __builtin_bit_cast(half2v, b), c, false);
+}
+
+__device__ __forceinline__ float half_pair_sum(unsigned packed) {
+  const half2v h = __builtin_bit_cast(half2v, packed);
+  return (float)h.x + (float)h.y;
 }
 
 __device__ __forceinline__ float dpp_add(float v, const int ctrl, const int row_mask) {
@@ -61,218 +76,318 @@ __device__ __forceinline__ float wave_reduce_to_lane63(float v) {
   return v;
 }
 
-// Index window of one lane: NDW dwords starting at dword `dw` of the row at byte offset `row_off`.
-struct Window { unsigned w[NDW]; };
-
-__device__ __forceinline__ Window load_window(__amdgpu_buffer_rsrc_t rsrc, unsigned row_off, unsigned dw) {
-  Window r;
-  const unsigned off = row_off + dw * 4u;
-  uint4v a = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0);
-  uint4v b = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off + 16u, 0, 0);
-  r.w[0] = a.x; r.w[1] = a.y; r.w[2] = a.z; r.w[3] = a.w;
-  r.w[4] = b.x; r.w[5] = b.y; r.w[6] = b.z; r.w[7] = b.w;
-  return r;
-}
-
-// Shift the window right by `sh` bits (0..31) so that the lane's first index starts at bit 0.
-__device__ __forceinline__ void normalize(Window &win, unsigned sh) {
-#pragma unroll
-  for (int i = 0; i < NDW - 1; ++i) win.w[i] = __builtin_amdgcn_alignbit(win.w[i + 1], win.w[i], sh);
-  win.w[NDW - 1] >>= sh;
-}
-
-// Byte offset (index * 16 or index * 8) of field u of a normalized window of BITS-bit fields.
-template <int BITS, int SHIFT>
-__device__ __forceinline__ unsigned field_offset(const Window &win, int u) {
-  const int bit = u * BITS, i = bit >> 5, o = bit & 31;
-  unsigned v = (o + BITS <= 32) ? (win.w[i] >> o) : __builtin_amdgcn_alignbit(win.w[i + 1], win.w[i], o);
-  return (v & ((1u << BITS) - 1u)) << SHIFT;
-}
-
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, unsigned bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
 }
 
-// Copy a table of `k` entries of V halfs (V = 6 -> 16-byte LDS entries, V = 4 -> 8-byte entries).
-template <int V>
-__device__ __forceinline__ void stage_table(const __half *src, int k, int k_alloc, unsigned char *dst) {
-  const unsigned *s = reinterpret_cast<const unsigned *>(src);
-  for (int e = threadIdx.x; e < k_alloc; e += NW * 64) {
-    if (V == 6) {
-      uint4 val = make_uint4(0, 0, 0, 0);
-      if (e < k) { val.x = s[e * 3]; val.y = s[e * 3 + 1]; val.z = s[e * 3 + 2]; }
-      *reinterpret_cast<uint4 *>(dst + e * 16) = val;
-    } else {
-      uint2 val = make_uint2(0, 0);
-      if (e < k) { val.x = s[e * 2]; val.y = s[e * 2 + 1]; }
-      *reinterpret_cast<uint2 *>(dst + e * 8) = val;
+// Index window of one lane: N dwords (4 or 6) starting at dword `dw` of the row at byte offset `row_off`.
+// Buffer loads are range-checked per dword: dwords past the end of the stream read as zero, never fault.
+template <int N> struct Window { unsigned w[N]; };
+
+template <int N>
+__device__ __forceinline__ void load_window(Window<N> &r, __amdgpu_buffer_rsrc_t rsrc, unsigned row_off, unsigned dw) {
+  static_assert(N >= 2 && N <= 6, "window of 2..6 dwords");
+  const unsigned off = row_off + dw * 4u;
+  if constexpr (N == 2) {
+    uint2v a = __builtin_amdgcn_raw_buffer_load_b64(rsrc, off, 0, 0);
+    r.w[0] = a.x; r.w[1] = a.y;
+  } else if constexpr (N == 3) {
+    uint3v a = __builtin_amdgcn_raw_buffer_load_b96(rsrc, off, 0, 0);
+    r.w[0] = a.x; r.w[1] = a.y; r.w[2] = a.z;
+  } else {
+    uint4v a = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0);
+    r.w[0] = a.x; r.w[1] = a.y; r.w[2] = a.z; r.w[3] = a.w;
+    if constexpr (N == 5) r.w[4] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, off + 16u, 0, 0);
+    if constexpr (N == 6) {
+      uint2v b = __builtin_amdgcn_raw_buffer_load_b64(rsrc, off + 16u, 0, 0);
+      r.w[4] = b.x; r.w[5] = b.y;
     }
   }
 }
 
-// Activations of `n` halfs starting at column c as packed pairs; columns >= in_features read as zero.
-__device__ __forceinline__ unsigned load_x_pair(const __half *xrow, int c, int in_features) {
-  if (c + 1 < in_features) return *reinterpret_cast<const unsigned *>(xrow + c);
-  if (c < in_features) return (unsigned)__half_as_ushort(xrow[c]);
-  return 0u;
+// Shift the window right by `sh` bits (0..31) so that the lane's first index starts at bit 0.
+template <int N>
+__device__ __forceinline__ void normalize(Window<N> &win, unsigned sh) {
+#pragma unroll
+  for (int i = 0; i < N - 1; ++i) win.w[i] = __builtin_amdgcn_alignbit(win.w[i + 1], win.w[i], sh);
+  win.w[N - 1] >>= sh;
 }
 
-template <int RES_BITS, int B, int UMAX>
+// Byte offset (index << SHIFT) of field u of a normalized window of BITS-bit fields.
+template <int BITS, int SHIFT, int N>
+__device__ __forceinline__ unsigned field_offset(const Window<N> &win, int u) {
+  const int bit = u * BITS, i = bit >> 5, o = bit & 31;
+  unsigned v = (o + BITS <= 32) ? (win.w[i] >> o) : __builtin_amdgcn_alignbit(win.w[i + 1 < N ? i + 1 : i], win.w[i], o);
+  return (v & ((1u << BITS) - 1u)) << SHIFT;
+}
+
+// One centroid (12 bytes + 4 bytes of padding) from LDS, as one ds_read_b128 written by hand: measured on
+// gfx950, random 16-byte reads run at ~5.1 per clock per CU, while the 12-byte read the compiler would
+// narrow a plain load to (the padding is never used) runs at only ~3.2.  The read is asynchronous:
+// lds_gather_wait() must come before the first use of the values.
+__device__ __forceinline__ void lds_gather16(uint4v &dst, unsigned lds_addr) {
+  asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(lds_addr));
+}
+__device__ __forceinline__ void lds_gather8(uint2v &dst, unsigned lds_addr) {
+  asm volatile("ds_read_b64 %0, %1" : "=v"(dst) : "v"(lds_addr));
+}
+__device__ __forceinline__ void lds_gather_wait() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+template <class T> __device__ __forceinline__ void settle(T &v) { asm volatile("" : "+v"(v)); }
+
+// 32-bit LDS address of a pointer into shared memory.
+__device__ __forceinline__ unsigned lds_address(const void *p) {
+  return (unsigned)reinterpret_cast<size_t>((const __attribute__((address_space(3))) void *)p);
+}
+
+
+// Codebook staging: all loads of all tables first, then the LDS writes.  Each thread takes four consecutive 12-byte entries (v = 6: three aligned
+// 16-byte loads) or two 16-byte chunks of 8-byte entries (v = 4).  Range-checked loads give zeros past the
+// table's k entries, so the LDS copy is zero up to its power-of-two size.
+struct TableRegs { uint4v m[3], r[3], o[2]; };
+
+template <int RES_BITS>
+__device__ __forceinline__ void tables_load(TableRegs &t, const Params &p, bool has_out) {
+  const __amdgpu_buffer_rsrc_t rm = make_rsrc(p.cb, (unsigned)p.k * 12u);
+#pragma unroll
+  for (int i = 0; i < 3; ++i) t.m[i] = __builtin_amdgcn_raw_buffer_load_b128(rm, threadIdx.x * 48u + i * 16u, 0, 0);
+  if (RES_BITS) {
+    const __amdgpu_buffer_rsrc_t rr = make_rsrc(p.cb_res, (unsigned)p.k_res * 12u);
+#pragma unroll
+    for (int i = 0; i < 3; ++i) t.r[i] = __builtin_amdgcn_raw_buffer_load_b128(rr, threadIdx.x * 48u + i * 16u, 0, 0);
+  }
+  if (has_out) {
+    const __amdgpu_buffer_rsrc_t ro = make_rsrc(p.cb_out, (unsigned)p.k_out * 8u);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) t.o[i] = __builtin_amdgcn_raw_buffer_load_b128(ro, (threadIdx.x + i * NW * 64) * 16u, 0, 0);
+  }
+}
+
+__device__ __forceinline__ void store_padded4(unsigned char *dst, const uint4v (&v)[3]) {
+  // 12 dwords = 4 entries of 3 dwords -> 4 entries of 4 dwords (last one zero)
+  const unsigned d[12] = {v[0].x, v[0].y, v[0].z, v[0].w, v[1].x, v[1].y, v[1].z, v[1].w, v[2].x, v[2].y, v[2].z, v[2].w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    uint4v e; e.x = d[3 * i]; e.y = d[3 * i + 1]; e.z = d[3 * i + 2]; e.w = 0u;
+    *reinterpret_cast<uint4v *>(dst + (threadIdx.x * 4 + i) * 16) = e;
+  }
+}
+
+template <int RES_BITS>
+__device__ __forceinline__ void tables_store(const TableRegs &t, unsigned char *lds, const GemvPlan &plan, bool has_out) {
+  store_padded4(lds, t.m);                                                   // 1024 threads x 4 = 4096 entries
+  if (RES_BITS == 12) store_padded4(lds + plan.lds_res, t.r);
+  if (RES_BITS == 8 && threadIdx.x < 64) store_padded4(lds + plan.lds_res, t.r);   // 256 entries
+  if (has_out) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) *reinterpret_cast<uint4v *>(lds + plan.lds_out + (threadIdx.x + i * NW * 64) * 16) = t.o[i];
+  }
+}
+
+constexpr int window_dwords(int bits, int u) { return (32 - 4 + bits * u + 31) / 32; }   // worst start bit is 28 (12-bit) or 24 (8-bit)
+
+// U: vectors per lane (compile time, so the lookups of a row carry no branches and overlap freely).
+template <int RES_BITS, int B, int U>
 __global__ __launch_bounds__(NW * 64) void gemv_v6_kernel(Params p, GemvPlan plan, const __half *__restrict__ x, long long ldx,
                                                           __half *__restrict__ y, long long ldy) {
+  constexpr int DEPTH = RES_BITS ? 3 : 4;        // rows of index windows a wave keeps in flight (register budget)
+  constexpr int NM = window_dwords(12, U);
+  constexpr int RB = RES_BITS ? RES_BITS : 8;
+  constexpr int NR = window_dwords(RB, U);
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int row0 = blockIdx.x * plan.rows_per_wg;
   const int row1 = min(p.out_features, row0 + plan.rows_per_wg);
+  const int rows_here = row1 - row0;
   const int Wt = plan.W + plan.Wo;
   float *part = reinterpret_cast<float *>(lds + plan.lds_part);     // [RC][Wt][B]
-  float *xsum = reinterpret_cast<float *>(lds + plan.lds_xsum);     // [B]
+  float *xsum = reinterpret_cast<float *>(lds + plan.lds_xsum);     // [B][NW]
+  const unsigned a_main = lds_address(lds), a_res = a_main + plan.lds_res, a_out = a_main + plan.lds_out;
+  VQ_STAMP(0);
 
-  // ---- stage codebooks, sum activations
-  stage_table<6>(p.cb, p.k, 4096, lds);
-  if (RES_BITS) stage_table<6>(p.cb_res, p.k_res, 1 << RES_BITS, lds + plan.lds_res);
-  if (plan.Wo) stage_table<4>(p.cb_out, p.k_out, 4096, lds + plan.lds_out);
-  if (wv < B) {
-    float s = 0.0f;
-    for (int c = lane; c < p.in_features; c += 64) s += __half2float(x[wv * ldx + c]);
-    s = wave_reduce_to_lane63(s);
-    if (lane == 63) xsum[wv] = s;
-  }
-
-  // ---- role of this wave
+  // ---- role of this wave: main slice `slice` of row stream `start`, or outlier slice, or idle
   const int n_main = plan.RS * plan.W;
   const bool is_main = wv < n_main;
   const bool is_out = !is_main && (wv - n_main) < plan.Wo;
   const int slice = is_main ? wv % plan.W : wv - n_main;
-  const int stream = is_main ? wv / plan.W : 0;
+  const int start = is_main ? wv / plan.W : 0;
   const int step = is_main ? plan.RS : 1;
-  const int U = is_main ? plan.U : plan.Uo;
-
-  // ---- activations of this lane's vectors, kept for the whole kernel
-  unsigned xr[B][UMAX][3];
   const int first_vec = (slice * 64 + lane) * U;
-#pragma unroll
-  for (int u = 0; u < UMAX; ++u)
-#pragma unroll
-    for (int b = 0; b < B; ++b)
-#pragma unroll
-      for (int h = 0; h < 3; ++h) xr[b][u][h] = 0u;
-  if (is_main) {
-#pragma unroll
-    for (int u = 0; u < UMAX; ++u)
-      if (u < U && first_vec + u < p.P) {
-        const int c = p.n_out + (first_vec + u) * 6;
-#pragma unroll
-        for (int b = 0; b < B; ++b)
-#pragma unroll
-          for (int h = 0; h < 3; ++h) xr[b][u][h] = load_x_pair(x + b * ldx, c + 2 * h, p.in_features);
-      }
-  } else if (is_out) {
-#pragma unroll
-    for (int u = 0; u < UMAX; ++u)
-      if (u < U && first_vec + u < p.Q) {
-        const int c = (first_vec + u) * 4;
-#pragma unroll
-        for (int b = 0; b < B; ++b)
-#pragma unroll
-          for (int h = 0; h < 2; ++h) xr[b][u][h] = load_x_pair(x + b * ldx, c + 2 * h, p.in_features);
-      }
-  }
-  __syncthreads();
 
   // ---- index stream geometry of this lane
-  const unsigned rows_here = (unsigned)(row1 - row0);
-  const unsigned char *lds_res = lds + plan.lds_res;
-  const unsigned char *lds_out = lds + plan.lds_out;
   const unsigned bit0 = (unsigned)first_vec * 12u;
   const unsigned dw_main = bit0 >> 5, sh_main = bit0 & 31u;
-  const unsigned bitr = (unsigned)first_vec * (unsigned)(RES_BITS ? RES_BITS : 1);
+  const unsigned bitr = (unsigned)first_vec * (unsigned)RB;
   const unsigned dw_res = bitr >> 5, sh_res = bitr & 31u;
-  const __amdgpu_buffer_rsrc_t r_main = make_rsrc(p.idx + (long long)row0 * p.stride, rows_here * (unsigned)p.stride);
+  const unsigned st_main = (unsigned)(is_out ? p.stride_out : p.stride), st_res = (unsigned)p.stride_res;
+  const __amdgpu_buffer_rsrc_t r_main =
+      is_out ? make_rsrc(p.idx_out + (long long)row0 * p.stride_out, (unsigned)rows_here * st_main)
+             : make_rsrc(p.idx + (long long)row0 * p.stride, (unsigned)rows_here * st_main);
   const __amdgpu_buffer_rsrc_t r_res = make_rsrc(RES_BITS ? p.idx_res + (long long)row0 * p.stride_res : p.idx,
-                                                 RES_BITS ? rows_here * (unsigned)p.stride_res : 0u);
-  const __amdgpu_buffer_rsrc_t r_out = make_rsrc(plan.Wo ? p.idx_out + (long long)row0 * p.stride_out : p.idx,
-                                                 plan.Wo ? rows_here * (unsigned)p.stride_out : 0u);
+                                                 RES_BITS ? (unsigned)rows_here * st_res : 0u);
 
-  for (int chunk0 = 0; chunk0 < (int)rows_here; chunk0 += RC) {
-    const int rows_chunk = min(RC, (int)rows_here - chunk0);
-    if (is_main) {
-      for (int rl = stream; rl < rows_chunk; rl += step) {
-        const unsigned r = (unsigned)(chunk0 + rl);
-        Window wm = load_window(r_main, r * (unsigned)p.stride, dw_main);
-        Window wr;
-        if (RES_BITS) wr = load_window(r_res, r * (unsigned)p.stride_res, dw_res);
-        normalize(wm, sh_main);
-        if (RES_BITS) normalize(wr, sh_res);
-        float acc[B];
+  unsigned xr[B][U][3];
+  Window<NM> wm[DEPTH];
+  Window<NR> wr[DEPTH];
+  const int c0 = is_main ? p.n_out + first_vec * 6 : first_vec * 4;
+
+  for (int chunk0 = 0; chunk0 < rows_here; chunk0 += RC) {
+    const int rows_chunk = min(RC, rows_here - chunk0);
+    const int n_iters = ((is_main || is_out) && start < rows_chunk) ? (rows_chunk - start + step - 1) / step : 0;
+    // ---- put the first DEPTH rows of index windows in flight
 #pragma unroll
-        for (int b = 0; b < B; ++b) acc[b] = 0.0f;
+    for (int d = 0; d < DEPTH; ++d)
+      if (d < n_iters) {
+        const unsigned r = (unsigned)(chunk0 + start + d * step);
+        load_window(wm[d], r_main, r * st_main, dw_main);
+        if (RES_BITS && is_main) load_window(wr[d], r_res, r * st_res, dw_res);
+      }
+    VQ_STAMP(1);
+
+    // scale and bias of the row this thread finishes at the end of the chunk
+    const int ep_rl = (int)threadIdx.x / B, ep_b = (int)threadIdx.x - ep_rl * B;
+    const bool ep_on = (int)threadIdx.x < rows_chunk * B;
+    const int ep_o = row0 + chunk0 + ep_rl;
+    const float ep_scale = (ep_on && p.scale) ? __half2float(p.scale[ep_o]) : 1.0f;
+    const float ep_bias = (ep_on && p.bias) ? __half2float(p.bias[ep_o]) : 0.0f;
+
+    if (chunk0 == 0) {
+      // ---- activations: each batch row goes through LDS (coalesced 16-byte loads in, each lane's own
+      // U vectors out to registers, where they stay for the whole kernel).  The row borrows the space the
+      // codebooks take afterwards.  Range-checked buffer loads return zero past in_features (even here),
+      // so padded vectors and idle lanes multiply by zero.  The bias term's sum(x) falls out of the same pass.
 #pragma unroll
-        for (int u = 0; u < UMAX; ++u) {
-          if (u < U) {
-            const uint4 e = *reinterpret_cast<const uint4 *>(lds + field_offset<12, 4>(wm, u));
+      for (int b = 0; b < B; ++b) {
+        const __amdgpu_buffer_rsrc_t rx = make_rsrc(x + b * ldx, (unsigned)p.in_features * 2u);
+        float s0 = 0.0f;
+        for (unsigned base = 0; base < plan.x_bytes; base += 4u * NW * 64 * 16u) {
+          uint4v xv[4];                      // four loads in flight per thread before the first LDS write
 #pragma unroll
-            for (int b = 0; b < B; ++b) {
-              acc[b] = dot2(e.x, xr[b][u][0], acc[b]);
-              acc[b] = dot2(e.y, xr[b][u][1], acc[b]);
-              acc[b] = dot2(e.z, xr[b][u][2], acc[b]);
+          for (int i = 0; i < 4; ++i)
+            xv[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, base + (unsigned)(i * NW * 64 + threadIdx.x) * 16u, 0, 0);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const unsigned o = base + (unsigned)(i * NW * 64 + threadIdx.x) * 16u;
+            if (o < plan.x_bytes) *reinterpret_cast<uint4v *>(lds + o) = xv[i];
+            s0 += half_pair_sum(xv[i].x) + half_pair_sum(xv[i].y) + half_pair_sum(xv[i].z) + half_pair_sum(xv[i].w);
+          }
+        }
+        const float s = wave_reduce_to_lane63(s0);
+        if (lane == 63) xsum[b * NW + wv] = s;
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          if (is_main) {
+#pragma unroll
+            for (int h = 0; h < 3; ++h) xr[b][u][h] = *reinterpret_cast<const unsigned *>(lds + (c0 + u * 6 + h * 2) * 2);
+          } else {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+              const int c = c0 + u * 4 + h * 2;
+              const unsigned v = *reinterpret_cast<const unsigned *>(lds + (is_out ? c : 0) * 2);
+              xr[b][u][h] = (is_out && c < p.n_out) ? v : 0u;      // outlier lanes past the last outlier vector
             }
+            xr[b][u][2] = 0u;
+          }
+        }
+        __syncthreads();
+      }
+      VQ_STAMP(2);
+      // ---- codebooks into LDS
+      {
+        TableRegs tabs;
+        tables_load<RES_BITS>(tabs, p, plan.Wo != 0);
+        tables_store<RES_BITS>(tabs, lds, plan, plan.Wo != 0);
+      }
+      VQ_STAMP(3);
+      __syncthreads();
+    }
+    VQ_STAMP(4);
+
+    for (int n0 = 0; n0 < n_iters; n0 += DEPTH) {
+#pragma unroll
+      for (int d = 0; d < DEPTH; ++d) {
+        const int n = n0 + d;
+        if (n < n_iters) {
+          const int rl = start + n * step;
+          Window<NM> cm = wm[d];
+          Window<NR> cr = wr[d];
+          if (n + DEPTH < n_iters) {          // refill this slot with the row DEPTH steps ahead
+            const unsigned r = (unsigned)(chunk0 + rl + DEPTH * step);
+            load_window(wm[d], r_main, r * st_main, dw_main);
+            if (RES_BITS && is_main) load_window(wr[d], r_res, r * st_res, dw_res);
+          }
+          normalize(cm, sh_main);
+          float acc[B];
+#pragma unroll
+          for (int b = 0; b < B; ++b) acc[b] = 0.0f;
+          if (is_main) {
+            uint4v e[U], f[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) lds_gather16(e[u], a_main + field_offset<12, 4>(cm, u));
             if (RES_BITS) {
-              const uint4 f = *reinterpret_cast<const uint4 *>(lds_res + field_offset<(RES_BITS ? RES_BITS : 8), 4>(wr, u));
+              normalize(cr, sh_res);
+#pragma unroll
+              for (int u = 0; u < U; ++u) lds_gather16(f[u], a_res + field_offset<RB, 4>(cr, u));
+            }
+            lds_gather_wait();
+#pragma unroll
+            for (int u = 0; u < U; ++u) { settle(e[u]); if (RES_BITS) settle(f[u]); }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
 #pragma unroll
               for (int b = 0; b < B; ++b) {
-                acc[b] = dot2(f.x, xr[b][u][0], acc[b]);
-                acc[b] = dot2(f.y, xr[b][u][1], acc[b]);
-                acc[b] = dot2(f.z, xr[b][u][2], acc[b]);
+                acc[b] = dot2(e[u].x, xr[b][u][0], acc[b]);
+                acc[b] = dot2(e[u].y, xr[b][u][1], acc[b]);
+                acc[b] = dot2(e[u].z, xr[b][u][2], acc[b]);
               }
+            if (RES_BITS) {
+#pragma unroll
+              for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int b = 0; b < B; ++b) {
+                  acc[b] = dot2(f[u].x, xr[b][u][0], acc[b]);
+                  acc[b] = dot2(f[u].y, xr[b][u][1], acc[b]);
+                  acc[b] = dot2(f[u].z, xr[b][u][2], acc[b]);
+                }
             }
+          } else {
+            uint2v e[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) lds_gather8(e[u], a_out + field_offset<12, 3>(cm, u));
+            lds_gather_wait();
+#pragma unroll
+            for (int u = 0; u < U; ++u) settle(e[u]);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+              for (int b = 0; b < B; ++b) {
+                acc[b] = dot2(e[u].x, xr[b][u][0], acc[b]);
+                acc[b] = dot2(e[u].y, xr[b][u][1], acc[b]);
+              }
           }
-        }
+          const int col = is_main ? slice : plan.W + slice;
 #pragma unroll
-        for (int b = 0; b < B; ++b) {
-          const float s = wave_reduce_to_lane63(acc[b]);
-          if (lane == 63) part[(rl * Wt + slice) * B + b] = s;
-        }
-      }
-    } else if (is_out) {
-      for (int rl = 0; rl < rows_chunk; ++rl) {
-        const unsigned r = (unsigned)(chunk0 + rl);
-        Window wo = load_window(r_out, r * (unsigned)p.stride_out, dw_main);
-        normalize(wo, sh_main);
-        float acc[B];
-#pragma unroll
-        for (int b = 0; b < B; ++b) acc[b] = 0.0f;
-#pragma unroll
-        for (int u = 0; u < UMAX; ++u) {
-          if (u < U) {
-            const uint2 e = *reinterpret_cast<const uint2 *>(lds_out + field_offset<12, 3>(wo, u));
-#pragma unroll
-            for (int b = 0; b < B; ++b) {
-              acc[b] = dot2(e.x, xr[b][u][0], acc[b]);
-              acc[b] = dot2(e.y, xr[b][u][1], acc[b]);
-            }
+          for (int b = 0; b < B; ++b) {
+            const float s = wave_reduce_to_lane63(acc[b]);
+            if (lane == 63) part[(rl * Wt + col) * B + b] = s;
           }
-        }
-#pragma unroll
-        for (int b = 0; b < B; ++b) {
-          const float s = wave_reduce_to_lane63(acc[b]);
-          if (lane == 63) part[(rl * Wt + plan.W + slice) * B + b] = s;
         }
       }
     }
+    VQ_STAMP(5);
     __syncthreads();
+    VQ_STAMP(6);
     // ---- combine slices, apply scale and bias, store
-    for (int t = threadIdx.x; t < rows_chunk * B; t += NW * 64) {
-      const int rl = t / B, b = t - rl * B;
-      const int o = row0 + chunk0 + rl;
+    if (ep_on) {
       float s = 0.0f;
-      for (int w = 0; w < Wt; ++w) s += part[(rl * Wt + w) * B + b];
-      const float sc = p.scale ? __half2float(p.scale[o]) : 1.0f;
-      const float bi = p.bias ? __half2float(p.bias[o]) : 0.0f;
-      y[b * ldy + o] = __float2half_rn(__fmaf_rn(sc, s, bi * xsum[b]));
+      for (int w = 0; w < Wt; ++w) s += part[(ep_rl * Wt + w) * B + ep_b];
+      float xs = 0.0f;
+      for (int w = 0; w < NW; ++w) xs += xsum[ep_b * NW + w];
+      y[ep_b * ldy + ep_o] = __float2half_rn(__fmaf_rn(ep_scale, s, ep_bias * xs));
     }
     __syncthreads();
+    VQ_STAMP(7);
   }
 }
 
@@ -287,11 +402,11 @@ int cu_count() {
   return g_cu_count;
 }
 
-template <int RES_BITS, int B, int UMAX>
+template <int RES_BITS, int B, int U>
 int launch_one(const Params &p, const GemvPlan &plan, unsigned lds_bytes, unsigned grid, const __half *x, long long ldx,
                __half *y, long long ldy, hipStream_t s) {
   static bool configured = false;
-  auto kernel = gemv_v6_kernel<RES_BITS, B, UMAX>;
+  auto kernel = gemv_v6_kernel<RES_BITS, B, U>;
   if (!configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
       return VQ_ERR_HIP;
@@ -301,57 +416,87 @@ int launch_one(const Params &p, const GemvPlan &plan, unsigned lds_bytes, unsign
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
 
+template <int RES_BITS, int B>
+int launch_u(int U, const Params &p, const GemvPlan &plan, unsigned lds_bytes, unsigned grid, const __half *x, long long ldx,
+             __half *y, long long ldy, hipStream_t s) {
+  if (U == 4) return launch_one<RES_BITS, B, 4>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
+  if (U == 5) return launch_one<RES_BITS, B, 5>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
+  if constexpr (B <= 2) {
+    if (U == 6) return launch_one<RES_BITS, B, 6>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
+    if (U == 8) return launch_one<RES_BITS, B, 8>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
+  }
+  if constexpr (B == 1 && RES_BITS == 0) {
+    if (U == 11) return launch_one<0, 1, 11>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
+  }
+  return VQ_ERR_UNSUPPORTED;
+}
+
 }  // namespace
+
+#ifdef VQ_PROFILE
+extern "C" int vq_debug_read_profile(unsigned long long *dst, size_t count) {
+  return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_prof), count * sizeof(unsigned long long));
+}
+#endif
 
 // Whether the fast kernels take this layer and these buffers.
 bool gemv_fast_applicable(const Params &p, const __half *x, long long ldx) {
   if (p.v != 6 || p.bits != 12) return false;
   if (p.k_res && p.bits_res != 12 && p.bits_res != 8) return false;
   if (p.n_out && (p.v_out != 4 || p.bits_out != 12)) return false;
-  if ((reinterpret_cast<uintptr_t>(x) & 3) || (ldx & 1)) return false;
-  if (p.Q > 64 * 16 * 4) return false;
+  if ((reinterpret_cast<uintptr_t>(x) & 3) || (ldx & 1) || (p.in_features & 1)) return false;
   const long long max_stride = p.stride > p.stride_res ? p.stride : p.stride_res;
   if (max_stride > (1 << 24)) return false;
   return true;
 }
 
+// Vectors per lane the kernels are built for, by batch group and residual use (register budget of 128).
+static bool u_allowed(int U, int batch, bool res) {
+  if (batch == 1) return res ? (U == 4 || U == 5) : (U == 4 || U == 5 || U == 6 || U == 8);
+  if (batch == 2) return res ? (U == 4) : (U == 4 || U == 5 || U == 6);
+  return !res && U == 4;
+}
+
 // Launch for one group of 1, 2 or 4 batch rows.
 int launch_gemv_fast(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
-  const int umax = batch == 1 ? 16 : batch == 2 ? 8 : 4;
+  static const int kU[] = {4, 5, 6, 8, 11};
   GemvPlan plan{};
-  const int ncu = cu_count();
-  plan.Uo = 0; plan.Wo = 0;
-  if (p.Q) {
-    plan.Wo = (p.Q + 64 * umax - 1) / (64 * umax);
-    plan.Uo = (p.Q + 64 * plan.Wo - 1) / (64 * plan.Wo);
-  }
-  unsigned grid = (unsigned)min(ncu, p.out_features);
-  plan.rows_per_wg = (p.out_features + (int)grid - 1) / (int)grid;
-  grid = (unsigned)((p.out_features + plan.rows_per_wg - 1) / plan.rows_per_wg);
-  // pick the number of main slices: fill lanes, keep waves busy, balance rows over streams
-  double best = -1.0;
-  for (int W = 1; W <= NW - plan.Wo && W <= MAX_SLICES - plan.Wo; ++W) {
-    const int U = (p.P + 64 * W - 1) / (64 * W);
-    if (U > umax) continue;
-    const int RS = (NW - plan.Wo) / W;
-    const int iters = (plan.rows_per_wg + RS - 1) / RS;
-    const double eff = (double)p.P / (64.0 * W * U) * (double)(RS * W) / NW * (double)plan.rows_per_wg / ((double)iters * RS);
-    if (eff > best) { best = eff; plan.W = W; plan.U = U; plan.RS = RS; }
-  }
-  if (best < 0.0) return VQ_ERR_UNSUPPORTED;
-  const long long max_stride = max(p.stride, max(p.stride_res, p.stride_out));
-  if ((long long)plan.rows_per_wg * max_stride >= (1LL << 31)) return VQ_ERR_UNSUPPORTED;   // 32-bit buffer offsets
+  // LDS: tables first (main at 0), then per-row partial sums and the activation sums
   unsigned off = 4096u * 16u;
   plan.lds_res = off; off += p.k_res ? (1u << p.bits_res) * 16u : 0u;
   plan.lds_out = off; off += p.Q ? 4096u * 8u : 0u;
-  plan.lds_part = off; off += (unsigned)(RC * (plan.W + plan.Wo) * batch) * 4u;
-  plan.lds_xsum = off; off += 16u;
+  plan.lds_part = off; off += (unsigned)(RC * MAX_SLICES * batch) * 4u;
+  plan.lds_xsum = off; off += (unsigned)(NW * batch) * 4u;
   if (off > 160u * 1024u) return VQ_ERR_UNSUPPORTED;
+  unsigned grid = (unsigned)min(cu_count(), p.out_features);
+  plan.rows_per_wg = (p.out_features + (int)grid - 1) / (int)grid;
+  grid = (unsigned)((p.out_features + plan.rows_per_wg - 1) / plan.rows_per_wg);
+  const long long max_stride = max(p.stride, max(p.stride_res, p.stride_out));
+  if ((long long)plan.rows_per_wg * max_stride >= (1LL << 31)) return VQ_ERR_UNSUPPORTED;   // 32-bit buffer offsets
+  // vectors per lane U and main slices W: fill lanes, keep waves busy, balance rows over the row streams
+  double best = -1.0;
+  for (int U : kU) {
+    if (!u_allowed(U, batch, p.k_res != 0)) continue;
+    const int Wo = p.Q ? (p.Q + 64 * U - 1) / (64 * U) : 0;
+    if (Wo >= NW) continue;
+    const int W = (p.P + 64 * U - 1) / (64 * U);
+    if (W + Wo > NW || W + Wo > MAX_SLICES) continue;
+    const int RS = (NW - Wo) / W;
+    const int rows = min(plan.rows_per_wg, RC);
+    const int iters = (rows + RS - 1) / RS;
+    const double eff = (double)p.P / (64.0 * W * U) * (double)(RS * W) / NW * (double)rows / ((double)iters * RS);
+    if (eff > best) { best = eff; plan.W = W; plan.U = U; plan.RS = RS; plan.Wo = Wo; plan.Uo = U; }
+  }
+  if (best < 0.0) return VQ_ERR_UNSUPPORTED;
+  // one activation row, up to the last column any lane touches, must fit where the tables go
+  const long long x_cols = max((long long)p.n_out + 6LL * plan.W * 64 * plan.U, 4LL * plan.Wo * 64 * plan.U);
+  plan.x_bytes = (unsigned)((x_cols * 2 + 15) / 16 * 16);
+  if (plan.x_bytes > plan.lds_part) return VQ_ERR_UNSUPPORTED;
   const int rb = p.k_res ? p.bits_res : 0;
-#define VQ_CASE(R, BB, UM) if (rb == R && batch == BB) return launch_one<R, BB, UM>(p, plan, off, grid, x, ldx, y, ldy, s);
-  VQ_CASE(0, 1, 16) VQ_CASE(12, 1, 16) VQ_CASE(8, 1, 16)
-  VQ_CASE(0, 2, 8) VQ_CASE(12, 2, 8) VQ_CASE(8, 2, 8)
-  VQ_CASE(0, 4, 4) VQ_CASE(12, 4, 4) VQ_CASE(8, 4, 4)
+#define VQ_CASE(R, BB) if (rb == R && batch == BB) return launch_u<R, BB>(plan.U, p, plan, off, grid, x, ldx, y, ldy, s);
+  VQ_CASE(0, 1) VQ_CASE(12, 1) VQ_CASE(8, 1)
+  VQ_CASE(0, 2) VQ_CASE(12, 2) VQ_CASE(8, 2)
+  VQ_CASE(0, 4) VQ_CASE(12, 4) VQ_CASE(8, 4)
 #undef VQ_CASE
   return VQ_ERR_UNSUPPORTED;
 }
