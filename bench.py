@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--copy-kernel", action="store_true",
+                    help="also run a plain 1 GiB device copy (counter calibration for rocprofv3 --pmc runs)")
     return ap.parse_args()
 
 
@@ -176,6 +178,14 @@ def main():
         result["cpu_baseline"] = {"value": round(alg / best / 1e9, 4), "unit": "GB/s", "cores": nthreads, "kind": "oracle",
                                   "sample": "%d full passes of the same layer and activation (best pass %.1f ms)" % (passes, best * 1e3)}
 
+    if args.copy_kernel:
+        # a plain copy of known size: reads 1 GiB, writes 1 GiB (what FETCH_SIZE / WRITE_SIZE are scaled by)
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        result["copy_kernel_bytes_each_way"] = a.numel() * 4
     if not args.no_detail:
         result["detail"] = detail(vq, s, np, torch, use_graph, skip=(cfg, 1))
     print(json.dumps(result))

@@ -40,7 +40,11 @@ __global__ __launch_bounds__(256) void dequant_generic_kernel(Params p, __half *
   }
 }
 
+int launch_dequant_fast(const Params &p, __half *W, long long ldw, hipStream_t s);
+
 int launch_dequant(const Params &p, __half *W, long long ldw, hipStream_t s) {
+  const int rc = launch_dequant_fast(p, W, ldw, s);
+  if (rc != VQ_ERR_UNSUPPORTED) return rc;
   const int slots = p.P + p.Q;
   const int blocks_per_row = (slots + 255) / 256;
   const long long blocks = (long long)blocks_per_row * p.out_features;

@@ -1,0 +1,222 @@
+// vq_dequant fast paths (paper Sec. 2.2: restore by index and centroid; App. "Our Dequantization
+// Implementation", first phase).  Output-write bound: 2 bytes out per weight against 0.25-0.5 bytes in.
+//
+//  * v = 6, 12-bit indices, optional residual (12- or 8-bit indices), optional outlier columns (v = 4,
+//    12-bit indices): codebooks in LDS, one wave restores 64 consecutive vectors (768 bytes of a row)
+//    at a time, passes them through a private LDS strip and writes them out as aligned 16-byte stores.
+//  * v = 8, 16-bit indices (k up to 65536, codebook in L2): one lane per vector, one 16-byte gather and
+//    one 16-byte store.
+// The arithmetic is the bit-exact definition: binary32 add of main and residual centroid, one binary32
+// fma with scale and bias, one round-to-nearest-even conversion.
+#include "vq_common.hpp"
+#include <cstdlib>
+
+namespace vq {
+
+namespace {
+
+typedef unsigned uint4v __attribute__((ext_vector_type(4)));
+typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+
+constexpr int NW = 16;   // waves per workgroup (v = 6 kernel)
+
+__device__ __forceinline__ unsigned restore_pair(unsigned main, unsigned res, bool has_res, float s, float b) {
+  float lo = __half2float(__ushort_as_half((unsigned short)(main & 0xFFFFu)));
+  float hi = __half2float(__ushort_as_half((unsigned short)(main >> 16)));
+  if (has_res) {
+    lo = __fadd_rn(lo, __half2float(__ushort_as_half((unsigned short)(res & 0xFFFFu))));
+    hi = __fadd_rn(hi, __half2float(__ushort_as_half((unsigned short)(res >> 16))));
+  }
+  return (unsigned)__half_as_ushort(restore(lo, s, b)) | ((unsigned)__half_as_ushort(restore(hi, s, b)) << 16);
+}
+
+struct DqPlan {
+  unsigned lds_res, lds_out, lds_strip;   // byte offsets in dynamic LDS (main table at 0)
+  int main_chunks, out_chunks;            // 64-vector chunks per row
+  long long total_chunks;
+  int wide;                               // 1: every row start is 16-byte aligned and ldw % 8 == 0
+};
+
+template <int RES_BITS>
+__global__ __launch_bounds__(NW * 64) void dequant_v6_kernel(Params p, DqPlan plan, __half *__restrict__ W, long long ldw) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const int lane = threadIdx.x & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  // ---- codebooks into LDS: entries padded to 16 bytes (v = 6) or kept at 8 bytes (v = 4)
+  {
+    const unsigned *s = reinterpret_cast<const unsigned *>(p.cb);
+    for (int e = threadIdx.x; e < 4096; e += NW * 64) {
+      uint4v val = {0u, 0u, 0u, 0u};
+      if (e < p.k) { val.x = s[e * 3]; val.y = s[e * 3 + 1]; val.z = s[e * 3 + 2]; }
+      *reinterpret_cast<uint4v *>(lds + e * 16) = val;
+    }
+    if (RES_BITS) {
+      const unsigned *r = reinterpret_cast<const unsigned *>(p.cb_res);
+      for (int e = threadIdx.x; e < (1 << RES_BITS); e += NW * 64) {
+        uint4v val = {0u, 0u, 0u, 0u};
+        if (e < p.k_res) { val.x = r[e * 3]; val.y = r[e * 3 + 1]; val.z = r[e * 3 + 2]; }
+        *reinterpret_cast<uint4v *>(lds + plan.lds_res + e * 16) = val;
+      }
+    }
+    if (plan.out_chunks) {
+      const unsigned *q = reinterpret_cast<const unsigned *>(p.cb_out);
+      for (int e = threadIdx.x; e < 4096; e += NW * 64) {
+        uint2v val = {0u, 0u};
+        if (e < p.k_out) { val.x = q[e * 2]; val.y = q[e * 2 + 1]; }
+        *reinterpret_cast<uint2v *>(lds + plan.lds_out + e * 8) = val;
+      }
+    }
+  }
+  __syncthreads();
+
+  unsigned char *strip = lds + plan.lds_strip + wv * 768;     // this wave's 64 x 12 bytes
+  const int chunks_per_row = plan.main_chunks + plan.out_chunks;
+  for (long long id = (long long)blockIdx.x * NW + wv; id < plan.total_chunks; id += (long long)gridDim.x * NW) {
+    const int o = (int)(id / chunks_per_row);
+    const int ch = (int)(id - (long long)o * chunks_per_row);
+    const float s = p.scale ? __half2float(p.scale[o]) : 1.0f;
+    const float b = p.bias ? __half2float(p.bias[o]) : 0.0f;
+    __half *wrow = W + (long long)o * ldw;
+    int c_first, n_cols, piece;            // first column of the chunk, its valid columns, bytes per vector
+    if (ch < plan.out_chunks) {
+      const int q = ch * 64 + lane;
+      c_first = ch * 256; n_cols = min(256, p.n_out - c_first); piece = 8;
+      uint2v w = {0u, 0u};
+      if (q < p.Q) {
+        const unsigned i = load_index(p.idx_out + (long long)o * p.stride_out, q, 12);
+        const uint2v e = *reinterpret_cast<const uint2v *>(lds + plan.lds_out + i * 8);
+        w.x = restore_pair(e.x, 0u, false, s, b);
+        w.y = restore_pair(e.y, 0u, false, s, b);
+      }
+      *reinterpret_cast<uint2v *>(strip + lane * 8) = w;
+    } else {
+      const int pp = (ch - plan.out_chunks) * 64 + lane;
+      c_first = p.n_out + (ch - plan.out_chunks) * 384; n_cols = min(384, p.in_features - c_first); piece = 12;
+      unsigned w0 = 0u, w1 = 0u, w2 = 0u;
+      if (pp < p.P) {
+        const unsigned i = load_index(p.idx + (long long)o * p.stride, pp, 12);
+        const uint4v e = *reinterpret_cast<const uint4v *>(lds + i * 16);
+        uint4v f = {0u, 0u, 0u, 0u};
+        if (RES_BITS) {
+          const unsigned r = load_index(p.idx_res + (long long)o * p.stride_res, pp, RES_BITS ? RES_BITS : 8);
+          f = *reinterpret_cast<const uint4v *>(lds + plan.lds_res + r * 16);
+        }
+        w0 = restore_pair(e.x, f.x, RES_BITS != 0, s, b);
+        w1 = restore_pair(e.y, f.y, RES_BITS != 0, s, b);
+        w2 = restore_pair(e.z, f.z, RES_BITS != 0, s, b);
+      }
+      unsigned *dst = reinterpret_cast<unsigned *>(strip + lane * 12);
+      dst[0] = w0; dst[1] = w1; dst[2] = w2;
+    }
+    (void)piece;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // ---- strip -> memory: n_cols halfs starting at column c_first
+    if (plan.wide && (c_first & 7) == 0) {
+      const int c = lane * 8;                                   // 48 lanes x 8 halfs cover 384 columns
+      if (c + 8 <= n_cols) {
+        *reinterpret_cast<uint4v *>(wrow + c_first + c) = *reinterpret_cast<const uint4v *>(strip + c * 2);
+      } else {
+        for (int j = c; j < n_cols; ++j) wrow[c_first + j] = *reinterpret_cast<const __half *>(strip + j * 2);
+      }
+    } else {
+      for (int j = lane; j < n_cols; j += 64) wrow[c_first + j] = *reinterpret_cast<const __half *>(strip + j * 2);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+__device__ __forceinline__ unsigned restore_pair_nores(unsigned main, float s, float b, bool lo_on, bool hi_on) {
+  const float lo = __half2float(__ushort_as_half((unsigned short)(main & 0xFFFFu)));
+  const float hi = __half2float(__ushort_as_half((unsigned short)(main >> 16)));
+  const unsigned rl = lo_on ? (unsigned)__half_as_ushort(restore(lo, s, b)) : 0u;
+  const unsigned rh = hi_on ? (unsigned)__half_as_ushort(restore(hi, s, b)) : 0u;
+  return rl | (rh << 16);
+}
+
+// v = 8, 16-bit indices, no residual, no outlier columns.  One lane per vector.
+__global__ __launch_bounds__(256) void dequant_v8_kernel(Params p, __half *__restrict__ W, long long ldw, int wide, int blocks_per_row) {
+  const int o = blockIdx.x / blocks_per_row;
+  const int pp = (blockIdx.x % blocks_per_row) * 256 + threadIdx.x;
+  if (pp >= p.P) return;
+  const unsigned short raw = reinterpret_cast<const unsigned short *>(p.idx + (long long)o * p.stride)[pp];
+  const unsigned i = min((unsigned)raw, (unsigned)p.k - 1u);
+  const uint4v e = reinterpret_cast<const uint4v *>(p.cb)[i];
+  const float s = p.scale ? __half2float(p.scale[o]) : 1.0f;
+  const float b = p.bias ? __half2float(p.bias[o]) : 0.0f;
+  const int c0 = pp * 8, valid = min(8, p.in_features - c0);
+  uint4v w;
+  w.x = restore_pair_nores(e.x, s, b, 0 < valid, 1 < valid);
+  w.y = restore_pair_nores(e.y, s, b, 2 < valid, 3 < valid);
+  w.z = restore_pair_nores(e.z, s, b, 4 < valid, 5 < valid);
+  w.w = restore_pair_nores(e.w, s, b, 6 < valid, 7 < valid);
+  __half *dst = W + (long long)o * ldw + c0;
+  if (wide && valid == 8) {
+    *reinterpret_cast<uint4v *>(dst) = w;
+  } else {
+    const unsigned d[4] = {w.x, w.y, w.z, w.w};
+    for (int j = 0; j < valid; ++j) dst[j] = __ushort_as_half((unsigned short)(d[j >> 1] >> ((j & 1) * 16)));
+  }
+}
+
+int g_cus = 0;
+int cu_count() {
+  if (!g_cus) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+    g_cus = n;
+  }
+  return g_cus;
+}
+
+template <int RES_BITS>
+int launch_v6(const Params &p, const DqPlan &plan, unsigned lds_bytes, __half *W, long long ldw, hipStream_t s) {
+  static bool configured = false;
+  auto kernel = dequant_v6_kernel<RES_BITS>;
+  if (!configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+      return VQ_ERR_HIP;
+    configured = true;
+  }
+  const long long want = (plan.total_chunks + NW - 1) / NW;
+  const unsigned grid = (unsigned)(want < cu_count() ? want : cu_count());
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(NW * 64), lds_bytes, s, p, plan, W, ldw);
+  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+}  // namespace
+
+// Returns VQ_ERR_UNSUPPORTED when no fast kernel takes the layer (the caller then uses the generic kernel).
+int launch_dequant_fast(const Params &p, __half *W, long long ldw, hipStream_t s) {
+  static const bool off = [] { const char *e = getenv("VQ_DEQUANT_KERNEL"); return e && e[0] == 'g'; }();
+  if (off) return VQ_ERR_UNSUPPORTED;
+  const bool aligned16 = (reinterpret_cast<uintptr_t>(W) & 15) == 0 && (ldw & 7) == 0;
+  if (p.v == 8 && p.bits == 16 && p.k_res == 0 && p.n_out == 0) {
+    const int bpr = (p.P + 255) / 256;
+    const long long blocks = (long long)bpr * p.out_features;
+    if (blocks > 0x7fffffffLL) return VQ_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(dequant_v8_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, W, ldw, aligned16 ? 1 : 0, bpr);
+    return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+  }
+  if (p.v != 6 || p.bits != 12) return VQ_ERR_UNSUPPORTED;
+  if (p.k_res && p.bits_res != 12 && p.bits_res != 8) return VQ_ERR_UNSUPPORTED;
+  if (p.n_out && (p.v_out != 4 || p.bits_out != 12)) return VQ_ERR_UNSUPPORTED;
+  DqPlan plan{};
+  unsigned offb = 4096u * 16u;
+  plan.lds_res = offb; offb += p.k_res ? (1u << p.bits_res) * 16u : 0u;
+  plan.lds_out = offb; offb += p.n_out ? 4096u * 8u : 0u;
+  plan.lds_strip = offb; offb += NW * 768u;
+  if (offb > 160u * 1024u) return VQ_ERR_UNSUPPORTED;
+  plan.main_chunks = (p.P + 63) / 64;
+  plan.out_chunks = p.n_out ? (p.Q + 63) / 64 : 0;
+  plan.total_chunks = (long long)(plan.main_chunks + plan.out_chunks) * p.out_features;
+  plan.wide = (aligned16 && (p.n_out & 7) == 0) ? 1 : 0;
+  const int rb = p.k_res ? p.bits_res : 0;
+  if (rb == 0) return launch_v6<0>(p, plan, offb, W, ldw, s);
+  if (rb == 12) return launch_v6<12>(p, plan, offb, W, ldw, s);
+  return launch_v6<8>(p, plan, offb, W, ldw, s);
+}
+
+}  // namespace vq

@@ -2,6 +2,7 @@
 // FP16 matrix cores (paper App. "Our Dequantization Implementation", first phase, but without ever
 // writing W to memory).  Accumulation in binary32, FP16 result.
 #include "vq_common.hpp"
+#include <cstdlib>
 
 namespace vq {
 
@@ -129,8 +130,13 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(Params p, const __half *
 
 size_t gemm_workspace_bytes(const Params &, int) { return 0; }
 
+bool gemm_fused_applicable(const Params &p);
+int launch_gemm_fused(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy, hipStream_t s);
+
 int launch_gemm(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy,
                 void *, size_t, hipStream_t s) {
+  static const bool force_generic = [] { const char *e = getenv("VQ_GEMM_KERNEL"); return e && e[0] == 'g'; }();
+  if (!force_generic && gemm_fused_applicable(p)) return launch_gemm_fused(p, X, ldx, tokens, Y, ldy, s);
   const unsigned gx = (unsigned)((p.out_features + BN - 1) / BN), gy = (unsigned)((tokens + BM - 1) / BM);
   if (gy > 65535u) return VQ_ERR_UNSUPPORTED;
   hipLaunchKernelGGL(gemm_tile_kernel, dim3(gx, gy), dim3(256), 0, s, p, X, ldx, tokens, Y, ldy);
