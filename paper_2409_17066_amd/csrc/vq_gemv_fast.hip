@@ -24,7 +24,7 @@ __device__ unsigned long long g_prof[1024 * 16 * 8];
 namespace {
 
 constexpr int NW = 16;           // waves per workgroup
-constexpr int RC = 64;           // rows per reduction chunk
+constexpr int RC_MAX = 64;       // most rows per reduction chunk
 constexpr int MAX_SLICES = 16;
 
 struct GemvPlan {
@@ -32,8 +32,10 @@ struct GemvPlan {
   int Wo, Uo;                    // outlier slices per row, outlier vectors per lane
   int RS;                        // row streams (rows in flight) for the main waves
   int rows_per_wg;
-  unsigned lds_res, lds_out, lds_part, lds_xsum;   // byte offsets into dynamic LDS (main table at 0)
-  unsigned x_bytes;                                // bytes of one activation row staged through LDS (multiple of 16)
+  unsigned lds_out, lds_part, lds_xsum;            // byte offsets into dynamic LDS (the v=6 tables start at 0)
+  unsigned lds_x;                                  // activation rows in LDS: B regions of x_bytes each
+  unsigned x_bytes;                                // bytes of one staged activation row (multiple of 1024)
+  int rc;                                          // rows per reduction chunk
 };
 
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
@@ -107,26 +109,40 @@ __device__ __forceinline__ void load_window(Window<N> &r, __amdgpu_buffer_rsrc_t
 
 // Shift the window right by `sh` bits (0..31) so that the lane's first index starts at bit 0.
 template <int N>
-__device__ __forceinline__ void normalize(Window<N> &win, unsigned sh) {
+__device__ __forceinline__ void normalize_from(Window<N> &out, const Window<N> &in, unsigned sh) {
 #pragma unroll
-  for (int i = 0; i < N - 1; ++i) win.w[i] = __builtin_amdgcn_alignbit(win.w[i + 1], win.w[i], sh);
-  win.w[N - 1] >>= sh;
+  for (int i = 0; i < N - 1; ++i) out.w[i] = __builtin_amdgcn_alignbit(in.w[i + 1], in.w[i], sh);
+  out.w[N - 1] = in.w[N - 1] >> sh;
 }
 
-// Byte offset (index << SHIFT) of field u of a normalized window of BITS-bit fields.
-template <int BITS, int SHIFT, int N>
-__device__ __forceinline__ unsigned field_offset(const Window<N> &win, int u) {
+// Field u (BITS wide) of a normalized window.
+template <int BITS, int N>
+__device__ __forceinline__ unsigned field(const Window<N> &win, int u) {
   const int bit = u * BITS, i = bit >> 5, o = bit & 31;
-  unsigned v = (o + BITS <= 32) ? (win.w[i] >> o) : __builtin_amdgcn_alignbit(win.w[i + 1 < N ? i + 1 : i], win.w[i], o);
-  return (v & ((1u << BITS) - 1u)) << SHIFT;
+  if (o + BITS <= 32) return __builtin_amdgcn_ubfe(win.w[i], o, BITS);
+  return __builtin_amdgcn_alignbit(win.w[i + 1 < N ? i + 1 : i], win.w[i], o) & ((1u << BITS) - 1u);
+}
+
+// Byte offset (index << SHIFT) of field u of a normalized window, in two VALU ops: one shift that lands the
+// field SHIFT bits up, one mask.  (Fields that straddle two dwords cost one funnel shift more.)
+template <int BITS, int SHIFT, int N>
+__device__ __forceinline__ unsigned field_addr(const Window<N> &win, int u) {
+  const int bit = u * BITS, i = bit >> 5, o = bit & 31;
+  constexpr unsigned mask = ((1u << BITS) - 1u) << SHIFT;
+  if (o + BITS <= 32) {
+    const unsigned w = win.w[i];
+    return (o >= SHIFT ? (w >> (o - SHIFT)) : (w << (SHIFT - o))) & mask;
+  }
+  return (__builtin_amdgcn_alignbit(win.w[i + 1 < N ? i + 1 : i], win.w[i], o) << SHIFT) & mask;
 }
 
 // One centroid (12 bytes + 4 bytes of padding) from LDS, as one ds_read_b128 written by hand: measured on
 // gfx950, random 16-byte reads run at ~5.1 per clock per CU, while the 12-byte read the compiler would
 // narrow a plain load to (the padding is never used) runs at only ~3.2.  The read is asynchronous:
 // lds_gather_wait() must come before the first use of the values.
+template <int OFF>
 __device__ __forceinline__ void lds_gather16(uint4v &dst, unsigned lds_addr) {
-  asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(lds_addr));
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(lds_addr), "n"(OFF));
 }
 __device__ __forceinline__ void lds_gather8(uint2v &dst, unsigned lds_addr) {
   asm volatile("ds_read_b64 %0, %1" : "=v"(dst) : "v"(lds_addr));
@@ -162,21 +178,35 @@ __device__ __forceinline__ void tables_load(TableRegs &t, const Params &p, bool 
   }
 }
 
-__device__ __forceinline__ void store_padded4(unsigned char *dst, const uint4v (&v)[3]) {
-  // 12 dwords = 4 entries of 3 dwords -> 4 entries of 4 dwords (last one zero)
+// Table layouts in LDS, all with 16-byte entries (a 32-byte interleave of main and residual entries was
+// tried and lost: each table then only touches half of the banks).  The 8-bit residual table goes first so
+// that both gathers are "index << 4" plus an immediate offset:
+//   no residual:      main at 0
+//   8-bit residual:   residual at 0 (4 KB), main at 4096
+//   12-bit residual:  main at 0, residual at 65536 (one add per lookup: the offset field holds 16 bits)
+template <int RES_BITS> struct Layout {
+  static constexpr unsigned MAIN_OFF = RES_BITS == 8 ? 4096u : 0u, MAIN_SH = 4u;
+  static constexpr unsigned RES_OFF = 0u, RES_SH = 4u, RES_ADD = RES_BITS == 12 ? 65536u : 0u;
+  static constexpr unsigned BYTES = RES_BITS == 0 ? 65536u : RES_BITS == 8 ? 4096u + 65536u : 131072u;
+};
+
+template <unsigned OFF, unsigned SH>
+__device__ __forceinline__ void store_padded4(unsigned char *lds, const uint4v (&v)[3]) {
+  // 12 dwords = 4 entries of 3 dwords -> 4 slots of 4 dwords (last one zero)
   const unsigned d[12] = {v[0].x, v[0].y, v[0].z, v[0].w, v[1].x, v[1].y, v[1].z, v[1].w, v[2].x, v[2].y, v[2].z, v[2].w};
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     uint4v e; e.x = d[3 * i]; e.y = d[3 * i + 1]; e.z = d[3 * i + 2]; e.w = 0u;
-    *reinterpret_cast<uint4v *>(dst + (threadIdx.x * 4 + i) * 16) = e;
+    *reinterpret_cast<uint4v *>(lds + OFF + ((threadIdx.x * 4 + i) << SH)) = e;
   }
 }
 
 template <int RES_BITS>
 __device__ __forceinline__ void tables_store(const TableRegs &t, unsigned char *lds, const GemvPlan &plan, bool has_out) {
-  store_padded4(lds, t.m);                                                   // 1024 threads x 4 = 4096 entries
-  if (RES_BITS == 12) store_padded4(lds + plan.lds_res, t.r);
-  if (RES_BITS == 8 && threadIdx.x < 64) store_padded4(lds + plan.lds_res, t.r);   // 256 entries
+  typedef Layout<RES_BITS> L;
+  store_padded4<L::MAIN_OFF, L::MAIN_SH>(lds, t.m);                          // 1024 threads x 4 = 4096 entries
+  if (RES_BITS == 12) store_padded4<L::RES_OFF, L::RES_SH>(lds + L::RES_ADD, t.r);
+  if (RES_BITS == 8 && threadIdx.x < 64) store_padded4<L::RES_OFF, L::RES_SH>(lds, t.r);   // 256 entries
   if (has_out) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) *reinterpret_cast<uint4v *>(lds + plan.lds_out + (threadIdx.x + i * NW * 64) * 16) = t.o[i];
@@ -186,7 +216,9 @@ __device__ __forceinline__ void tables_store(const TableRegs &t, unsigned char *
 constexpr int window_dwords(int bits, int u) { return (32 - 4 + bits * u + 31) / 32; }   // worst start bit is 28 (12-bit) or 24 (8-bit)
 
 // U: vectors per lane (compile time, so the lookups of a row carry no branches and overlap freely).
-template <int RES_BITS, int B, int U>
+// L1R: of a lane's U residual lookups, how many go to the residual table in memory (through the vector L1,
+// which gathers in parallel with LDS) instead of its LDS copy; only used for small residual tables.
+template <int RES_BITS, int B, int U, int L1R>
 __global__ __launch_bounds__(NW * 64) void gemv_v6_kernel(Params p, GemvPlan plan, const __half *__restrict__ x, long long ldx,
                                                           __half *__restrict__ y, long long ldy) {
   constexpr int DEPTH = RES_BITS ? 3 : 4;        // rows of index windows a wave keeps in flight (register budget)
@@ -200,9 +232,10 @@ __global__ __launch_bounds__(NW * 64) void gemv_v6_kernel(Params p, GemvPlan pla
   const int row1 = min(p.out_features, row0 + plan.rows_per_wg);
   const int rows_here = row1 - row0;
   const int Wt = plan.W + plan.Wo;
-  float *part = reinterpret_cast<float *>(lds + plan.lds_part);     // [RC][Wt][B]
+  float *part = reinterpret_cast<float *>(lds + plan.lds_part);     // [rc][Wt][B]
   float *xsum = reinterpret_cast<float *>(lds + plan.lds_xsum);     // [B][NW]
-  const unsigned a_main = lds_address(lds), a_res = a_main + plan.lds_res, a_out = a_main + plan.lds_out;
+  typedef Layout<RES_BITS> LY;
+  const unsigned a_out = lds_address(lds) + plan.lds_out;
   VQ_STAMP(0);
 
   // ---- role of this wave: main slice `slice` of row stream `start`, or outlier slice, or idle
@@ -225,14 +258,15 @@ __global__ __launch_bounds__(NW * 64) void gemv_v6_kernel(Params p, GemvPlan pla
              : make_rsrc(p.idx + (long long)row0 * p.stride, (unsigned)rows_here * st_main);
   const __amdgpu_buffer_rsrc_t r_res = make_rsrc(RES_BITS ? p.idx_res + (long long)row0 * p.stride_res : p.idx,
                                                  RES_BITS ? (unsigned)rows_here * st_res : 0u);
+  const __amdgpu_buffer_rsrc_t r_cbres = make_rsrc(RES_BITS ? (const void *)p.cb_res : (const void *)p.cb, RES_BITS ? (unsigned)p.k_res * 12u : 0u);
 
   unsigned xr[B][U][3];
   Window<NM> wm[DEPTH];
   Window<NR> wr[DEPTH];
   const int c0 = is_main ? p.n_out + first_vec * 6 : first_vec * 4;
 
-  for (int chunk0 = 0; chunk0 < rows_here; chunk0 += RC) {
-    const int rows_chunk = min(RC, rows_here - chunk0);
+  for (int chunk0 = 0; chunk0 < rows_here; chunk0 += plan.rc) {
+    const int rows_chunk = min(plan.rc, rows_here - chunk0);
     const int n_iters = ((is_main || is_out) && start < rows_chunk) ? (rows_chunk - start + step - 1) / step : 0;
     // ---- put the first DEPTH rows of index windows in flight
 #pragma unroll
@@ -252,45 +286,15 @@ __global__ __launch_bounds__(NW * 64) void gemv_v6_kernel(Params p, GemvPlan pla
     const float ep_bias = (ep_on && p.bias) ? __half2float(p.bias[ep_o]) : 0.0f;
 
     if (chunk0 == 0) {
-      // ---- activations: each batch row goes through LDS (coalesced 16-byte loads in, each lane's own
-      // U vectors out to registers, where they stay for the whole kernel).  The row borrows the space the
-      // codebooks take afterwards.  Range-checked buffer loads return zero past in_features (even here),
-      // so padded vectors and idle lanes multiply by zero.  The bias term's sum(x) falls out of the same pass.
+      // ---- activations: every batch row is copied into LDS by asynchronous, range-checked 16-byte loads
+      // that write LDS directly (zeros past in_features, which is even here, so padded vectors and idle
+      // lanes multiply by zero); wave w copies 1 KB pieces w, w+16, ...  No registers are held meanwhile.
 #pragma unroll
       for (int b = 0; b < B; ++b) {
         const __amdgpu_buffer_rsrc_t rx = make_rsrc(x + b * ldx, (unsigned)p.in_features * 2u);
-        float s0 = 0.0f;
-        for (unsigned base = 0; base < plan.x_bytes; base += 4u * NW * 64 * 16u) {
-          uint4v xv[4];                      // four loads in flight per thread before the first LDS write
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            xv[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, base + (unsigned)(i * NW * 64 + threadIdx.x) * 16u, 0, 0);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const unsigned o = base + (unsigned)(i * NW * 64 + threadIdx.x) * 16u;
-            if (o < plan.x_bytes) *reinterpret_cast<uint4v *>(lds + o) = xv[i];
-            s0 += half_pair_sum(xv[i].x) + half_pair_sum(xv[i].y) + half_pair_sum(xv[i].z) + half_pair_sum(xv[i].w);
-          }
-        }
-        const float s = wave_reduce_to_lane63(s0);
-        if (lane == 63) xsum[b * NW + wv] = s;
-        __syncthreads();
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          if (is_main) {
-#pragma unroll
-            for (int h = 0; h < 3; ++h) xr[b][u][h] = *reinterpret_cast<const unsigned *>(lds + (c0 + u * 6 + h * 2) * 2);
-          } else {
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-              const int c = c0 + u * 4 + h * 2;
-              const unsigned v = *reinterpret_cast<const unsigned *>(lds + (is_out ? c : 0) * 2);
-              xr[b][u][h] = (is_out && c < p.n_out) ? v : 0u;      // outlier lanes past the last outlier vector
-            }
-            xr[b][u][2] = 0u;
-          }
-        }
-        __syncthreads();
+        for (unsigned piece = (unsigned)wv * 1024u; piece < plan.x_bytes; piece += NW * 1024u)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void *)(lds + plan.lds_x + b * plan.x_bytes + piece),
+                                                   16, piece + lane * 16u, 0, 0, 0);
       }
       VQ_STAMP(2);
       // ---- codebooks into LDS
@@ -299,8 +303,36 @@ __global__ __launch_bounds__(NW * 64) void gemv_v6_kernel(Params p, GemvPlan pla
         tables_load<RES_BITS>(tabs, p, plan.Wo != 0);
         tables_store<RES_BITS>(tabs, lds, plan, plan.Wo != 0);
       }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the direct-to-LDS copies have landed
       VQ_STAMP(3);
       __syncthreads();
+      // ---- this lane's activations into registers (kept for the whole kernel), and sum(x) for the bias term
+#pragma unroll
+      for (int b = 0; b < B; ++b) {
+        const unsigned char *xl = lds + plan.lds_x + b * plan.x_bytes;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          if (is_main) {
+#pragma unroll
+            for (int h = 0; h < 3; ++h) xr[b][u][h] = *reinterpret_cast<const unsigned *>(xl + (c0 + u * 6 + h * 2) * 2);
+          } else {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+              const int c = c0 + u * 4 + h * 2;
+              const unsigned v = *reinterpret_cast<const unsigned *>(xl + (is_out ? c : 0) * 2);
+              xr[b][u][h] = (is_out && c < p.n_out) ? v : 0u;      // outlier lanes past the last outlier vector
+            }
+            xr[b][u][2] = 0u;
+          }
+        }
+        float s0 = 0.0f;
+        for (unsigned o = threadIdx.x * 16u; o < plan.x_bytes; o += NW * 64 * 16u) {
+          const uint4v v = *reinterpret_cast<const uint4v *>(xl + o);
+          s0 += half_pair_sum(v.x) + half_pair_sum(v.y) + half_pair_sum(v.z) + half_pair_sum(v.w);
+        }
+        const float s = wave_reduce_to_lane63(s0);
+        if (lane == 63) xsum[b * NW + wv] = s;
+      }
     }
     VQ_STAMP(4);
 
@@ -310,29 +342,35 @@ __global__ __launch_bounds__(NW * 64) void gemv_v6_kernel(Params p, GemvPlan pla
         const int n = n0 + d;
         if (n < n_iters) {
           const int rl = start + n * step;
-          Window<NM> cm = wm[d];
-          Window<NR> cr = wr[d];
+          Window<NM> cm;
+          Window<NR> cr;
+          normalize_from(cm, wm[d], sh_main);
+          if (RES_BITS && is_main) normalize_from(cr, wr[d], sh_res);
+          uint3v g[L1R > 0 ? L1R : 1];
+          if (L1R > 0 && is_main) {             // memory-side residual gathers go out before the refill loads
+#pragma unroll
+            for (int u = 0; u < L1R; ++u)
+              g[u] = __builtin_amdgcn_raw_buffer_load_b96(r_cbres, field<RB>(cr, u) * 12u, 0, 0);
+          }
           if (n + DEPTH < n_iters) {          // refill this slot with the row DEPTH steps ahead
             const unsigned r = (unsigned)(chunk0 + rl + DEPTH * step);
             load_window(wm[d], r_main, r * st_main, dw_main);
             if (RES_BITS && is_main) load_window(wr[d], r_res, r * st_res, dw_res);
           }
-          normalize(cm, sh_main);
           float acc[B];
 #pragma unroll
           for (int b = 0; b < B; ++b) acc[b] = 0.0f;
           if (is_main) {
             uint4v e[U], f[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) lds_gather16(e[u], a_main + field_offset<12, 4>(cm, u));
+            for (int u = 0; u < U; ++u) lds_gather16<LY::MAIN_OFF>(e[u], field_addr<12, LY::MAIN_SH>(cm, u));
             if (RES_BITS) {
-              normalize(cr, sh_res);
 #pragma unroll
-              for (int u = 0; u < U; ++u) lds_gather16(f[u], a_res + field_offset<RB, 4>(cr, u));
+              for (int u = L1R; u < U; ++u) lds_gather16<LY::RES_OFF>(f[u], field_addr<RB, LY::RES_SH>(cr, u) + LY::RES_ADD);
             }
             lds_gather_wait();
 #pragma unroll
-            for (int u = 0; u < U; ++u) { settle(e[u]); if (RES_BITS) settle(f[u]); }
+            for (int u = 0; u < U; ++u) { settle(e[u]); if (RES_BITS && u >= L1R) settle(f[u]); }
 #pragma unroll
             for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -343,18 +381,26 @@ __global__ __launch_bounds__(NW * 64) void gemv_v6_kernel(Params p, GemvPlan pla
               }
             if (RES_BITS) {
 #pragma unroll
-              for (int u = 0; u < U; ++u)
+              for (int u = L1R; u < U; ++u)
 #pragma unroll
                 for (int b = 0; b < B; ++b) {
                   acc[b] = dot2(f[u].x, xr[b][u][0], acc[b]);
                   acc[b] = dot2(f[u].y, xr[b][u][1], acc[b]);
                   acc[b] = dot2(f[u].z, xr[b][u][2], acc[b]);
                 }
+#pragma unroll
+              for (int u = 0; u < L1R; ++u)
+#pragma unroll
+                for (int b = 0; b < B; ++b) {
+                  acc[b] = dot2(g[u].x, xr[b][u][0], acc[b]);
+                  acc[b] = dot2(g[u].y, xr[b][u][1], acc[b]);
+                  acc[b] = dot2(g[u].z, xr[b][u][2], acc[b]);
+                }
             }
           } else {
             uint2v e[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) lds_gather8(e[u], a_out + field_offset<12, 3>(cm, u));
+            for (int u = 0; u < U; ++u) lds_gather8(e[u], field_addr<12, 3>(cm, u) + a_out);
             lds_gather_wait();
 #pragma unroll
             for (int u = 0; u < U; ++u) settle(e[u]);
@@ -402,11 +448,11 @@ int cu_count() {
   return g_cu_count;
 }
 
-template <int RES_BITS, int B, int U>
+template <int RES_BITS, int B, int U, int L1R = 0>
 int launch_one(const Params &p, const GemvPlan &plan, unsigned lds_bytes, unsigned grid, const __half *x, long long ldx,
                __half *y, long long ldy, hipStream_t s) {
   static bool configured = false;
-  auto kernel = gemv_v6_kernel<RES_BITS, B, U>;
+  auto kernel = gemv_v6_kernel<RES_BITS, B, U, L1R>;
   if (!configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
       return VQ_ERR_HIP;
@@ -420,6 +466,12 @@ template <int RES_BITS, int B>
 int launch_u(int U, const Params &p, const GemvPlan &plan, unsigned lds_bytes, unsigned grid, const __half *x, long long ldx,
              __half *y, long long ldy, hipStream_t s) {
   if (U == 4) return launch_one<RES_BITS, B, 4>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
+  if constexpr (RES_BITS == 8 && B == 1) {
+    static const int l1r = [] { const char *e = getenv("VQ_GEMV_L1R"); return e ? atoi(e) : 0; }();
+    if (U == 5 && l1r == 1) return launch_one<8, 1, 5, 1>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
+    if (U == 5 && l1r == 2) return launch_one<8, 1, 5, 2>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
+    if (U == 5 && l1r == 3) return launch_one<8, 1, 5, 3>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
+  }
   if (U == 5) return launch_one<RES_BITS, B, 5>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
   if constexpr (B <= 2) {
     if (U == 6) return launch_one<RES_BITS, B, 6>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
@@ -461,12 +513,11 @@ static bool u_allowed(int U, int batch, bool res) {
 int launch_gemv_fast(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
   static const int kU[] = {4, 5, 6, 8, 11};
   GemvPlan plan{};
-  // LDS: tables first (main at 0), then per-row partial sums and the activation sums
-  unsigned off = 4096u * 16u;
-  plan.lds_res = off; off += p.k_res ? (1u << p.bits_res) * 16u : 0u;
+  // LDS: tables first (main at 0); the activation rows, partial sums and activation sums follow once the
+  // slicing is known
+  const int rb = p.k_res ? p.bits_res : 0;
+  unsigned off = rb == 0 ? Layout<0>::BYTES : rb == 8 ? Layout<8>::BYTES : Layout<12>::BYTES;
   plan.lds_out = off; off += p.Q ? 4096u * 8u : 0u;
-  plan.lds_part = off; off += (unsigned)(RC * MAX_SLICES * batch) * 4u;
-  plan.lds_xsum = off; off += (unsigned)(NW * batch) * 4u;
   if (off > 160u * 1024u) return VQ_ERR_UNSUPPORTED;
   unsigned grid = (unsigned)min(cu_count(), p.out_features);
   plan.rows_per_wg = (p.out_features + (int)grid - 1) / (int)grid;
@@ -482,17 +533,23 @@ int launch_gemv_fast(const Params &p, const __half *x, long long ldx, int batch,
     const int W = (p.P + 64 * U - 1) / (64 * U);
     if (W + Wo > NW || W + Wo > MAX_SLICES) continue;
     const int RS = (NW - Wo) / W;
-    const int rows = min(plan.rows_per_wg, RC);
+    const int rows = min(plan.rows_per_wg, RC_MAX);
     const int iters = (rows + RS - 1) / RS;
     const double eff = (double)p.P / (64.0 * W * U) * (double)(RS * W) / NW * (double)rows / ((double)iters * RS);
     if (eff > best) { best = eff; plan.W = W; plan.U = U; plan.RS = RS; plan.Wo = Wo; plan.Uo = U; }
   }
   if (best < 0.0) return VQ_ERR_UNSUPPORTED;
-  // one activation row, up to the last column any lane touches, must fit where the tables go
+  // one activation row, up to the last column any lane touches, in 1 KB pieces
   const long long x_cols = max((long long)p.n_out + 6LL * plan.W * 64 * plan.U, 4LL * plan.Wo * 64 * plan.U);
-  plan.x_bytes = (unsigned)((x_cols * 2 + 15) / 16 * 16);
-  if (plan.x_bytes > plan.lds_part) return VQ_ERR_UNSUPPORTED;
-  const int rb = p.k_res ? p.bits_res : 0;
+  plan.x_bytes = (unsigned)((x_cols * 2 + 1023) / 1024 * 1024);
+  plan.lds_x = off; off += plan.x_bytes * (unsigned)batch;
+  plan.lds_xsum = off; off += (unsigned)(NW * batch) * 4u;
+  plan.lds_part = off;
+  if (off >= 160u * 1024u) return VQ_ERR_UNSUPPORTED;
+  const int per_row = (plan.W + plan.Wo) * batch * 4;
+  plan.rc = min(RC_MAX, (int)((160u * 1024u - off) / (unsigned)per_row));
+  if (plan.rc < plan.RS || plan.rc < 1) return VQ_ERR_UNSUPPORTED;
+  off += (unsigned)(plan.rc * per_row);
 #define VQ_CASE(R, BB) if (rb == R && batch == BB) return launch_u<R, BB>(plan.U, p, plan, off, grid, x, ldx, y, ldy, s);
   VQ_CASE(0, 1) VQ_CASE(12, 1) VQ_CASE(8, 1)
   VQ_CASE(0, 2) VQ_CASE(12, 2) VQ_CASE(8, 2)
