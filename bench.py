@@ -24,9 +24,10 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor figure
 MFMA_FP16_PEAK_TFLOPS = 2500.0  # dense FP16 matrix-core peak, vendor figure
 ROTATE_BYTES = 640 << 20        # footprint of the rotated index copies (> 2 x the 256 MB Infinity Cache)
 
-# HBM traffic per launch from `rocprofv3 --pmc` (FETCH_SIZE and WRITE_SIZE, each scaled by what the same
-# counter reads for a copy kernel of known size); see profiles/.  None until measured for the kernel in use.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM traffic per launch from `rocprofv3 --pmc` (FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by
+# what the same counter reads for a 1 GiB device copy in the same run: FETCH_SIZE x 2.0, WRITE_SIZE x 1.0);
+# figures and commands in profiles/gemv_v6_cfg1_batch1.txt.  Keyed by benchmark configuration.
+MEASURED_TRAFFIC_BYTES = {1: int((5937.4 * 2.0 + 29.0 * 1.0) * 1024)}
 
 
 def parse():
@@ -250,6 +251,20 @@ def detail(vq, s, np, torch, use_graph, skip):
     sec = ev / 20
     moved = W.numel() * 2 + L4.idx.nbytes + L4.codebook.nbytes
     out.append({"op": "vq_dequant", "cfg": 4, "us": round(sec * 1e6, 1), "GB/s": round(moved / sec / 1e9, 1),
+                "frac_hbm_peak": round(moved / sec / 1e9 / HBM_PEAK_GBPS, 4)})
+    # dequant of the 7B-shaped layer (v=6, k=4096)
+    _, L1 = next(s.config_layers(1))
+    dl1 = vq.DeviceLayer(L1)
+    W1 = torch.empty((L1.out_features, L1.in_features), dtype=torch.float16, device="cuda")
+
+    def launch_dq1(i):
+        rc = vq.vq_dequant(dl1.desc, W1.data_ptr(), W1.stride(0), torch.cuda.current_stream().cuda_stream)
+        if rc != 0:
+            raise vq.VQError(rc, "vq_dequant")
+    wall, ev = timed(launch_dq1, 20, 3, use_graph=False)
+    sec = ev / 20
+    moved = W1.numel() * 2 + L1.algorithmic_bytes(1)
+    out.append({"op": "vq_dequant", "cfg": 1, "us": round(sec * 1e6, 1), "GB/s": round(moved / sec / 1e9, 1),
                 "frac_hbm_peak": round(moved / sec / 1e9 / HBM_PEAK_GBPS, 4)})
     return out
 
