@@ -136,7 +136,10 @@ int launch_gemm_fused(const Params &p, const __half *X, long long ldx, int token
 int launch_gemm(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy,
                 void *, size_t, hipStream_t s) {
   static const bool force_generic = [] { const char *e = getenv("VQ_GEMM_KERNEL"); return e && e[0] == 'g'; }();
-  if (!force_generic && gemm_fused_applicable(p)) return launch_gemm_fused(p, X, ldx, tokens, Y, ldy, s);
+  if (!force_generic && gemm_fused_applicable(p)) {
+    const int rc = launch_gemm_fused(p, X, ldx, tokens, Y, ldy, s);
+    if (rc != VQ_ERR_UNSUPPORTED) return rc;
+  }
   const unsigned gx = (unsigned)((p.out_features + BN - 1) / BN), gy = (unsigned)((tokens + BM - 1) / BM);
   if (gy > 65535u) return VQ_ERR_UNSUPPORTED;
   hipLaunchKernelGGL(gemm_tile_kernel, dim3(gx, gy), dim3(256), 0, s, p, X, ldx, tokens, Y, ldy);

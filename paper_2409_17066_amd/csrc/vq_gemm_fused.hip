@@ -2,13 +2,15 @@
 // L2 / Infinity Cache, not in LDS), no residual, no outlier columns -- the paper's v=8 / k=65536 setting
 // (App. "Impact of Vector Length").  Y = X * W^T with W restored on the fly; W never touches memory.
 //
-// A workgroup of 4 waves owns BM tokens x 128 output channels; wave w owns token rows [w*BM/4, ...) and
-// all 128 channels, as (BM/128) x 4 MFMA 32x32x16 blocks.  Per 32-column step the workgroup gathers
-// 128 x 4 centroids (16 bytes each, one per thread-vector) from the codebook, applies scale and bias,
-// and writes the FP16 tile to LDS; the activation tile goes through LDS too.  Both tiles are double
-// buffered, and the centroid gathers run GD steps ahead of their use, fed by an index tile that is
-// staged in LDS every 16 steps.  The taller the token tile, the fewer times a centroid is gathered:
-// each gather pulls a whole 128-byte line out of L2 for 16 useful bytes, which is what bounds this kernel.
+// A workgroup owns BM tokens x 128 output channels and splits its 8 waves in two roles that share each SIMD:
+//  * waves 0-3 ("consumers") only issue MFMA: wave w owns token rows [w*BM/4, ...) and all 128 channels as
+//    (BM/128) x 4 blocks of v_mfma_f32_32x32x16_f16, reading both operands from LDS;
+//  * waves 4-7 ("producers") keep the tiles coming: per 32-column step they gather 128 x 4 centroids
+//    (16 bytes each, two per thread, issued GD steps ahead), apply scale and bias, write the FP16 W tile
+//    to LDS (double buffered), and start the asynchronous global->LDS copies of the activation tile
+//    XD steps ahead (XOR-swizzled 64-byte rows).
+// One barrier per step.  The taller the token tile, the fewer times a centroid is gathered: each gather
+// pulls a whole 128-byte line out of L2 for 16 useful bytes, which is what finally bounds this kernel.
 #include "vq_common.hpp"
 #include <cstdlib>
 
@@ -22,117 +24,180 @@ typedef unsigned uint4v __attribute__((ext_vector_type(4)));
 
 constexpr int BN = 128;       // output channels per workgroup
 constexpr int BK = 32;        // columns per step (4 vectors of 8)
-constexpr int LDT = BK + 8;   // LDS row pitch in halfs (80 bytes: 8 consecutive rows fall in 8 different 16-byte bank groups)
-constexpr int SS = 16;        // steps per index tile (16 * 4 = 64 indices = 128 bytes per row)
-constexpr int GD = 3;         // gather distance in steps
+constexpr int LDT = BK + 8;   // W tile row pitch in halfs (80 bytes: 8 consecutive rows fall in 8 different 16-byte bank groups)
+constexpr int GD = 4;         // centroid gathers run this many steps ahead (one register slot per step)
+constexpr int XD = 3;         // activation copies run this many steps ahead
+constexpr int NSX = XD + 1;   // activation stages in LDS
 
-__device__ __forceinline__ unsigned restore2(unsigned packed, float s, float b, bool lo_on, bool hi_on) {
+__device__ __forceinline__ unsigned restore2(unsigned packed, float s, float b) {
   const unsigned short l = (unsigned short)(packed & 0xFFFFu), h = (unsigned short)(packed >> 16);
-  const __half rl = lo_on ? restore(__half2float(__ushort_as_half(l)), s, b) : __ushort_as_half(0);
-  const __half rh = hi_on ? restore(__half2float(__ushort_as_half(h)), s, b) : __ushort_as_half(0);
+  const __half rl = restore(__half2float(__ushort_as_half(l)), s, b);
+  const __half rh = restore(__half2float(__ushort_as_half(h)), s, b);
   return (unsigned)__half_as_ushort(rl) | ((unsigned)__half_as_ushort(rh) << 16);
 }
 
-// eight halfs -> scale * d + bias in binary32 -> eight halfs; elements >= valid become zero
-__device__ __forceinline__ uint4v restore8(uint4v d, float s, float b, int valid) {
-  uint4v out;
-  out.x = restore2(d.x, s, b, 0 < valid, 1 < valid);
-  out.y = restore2(d.y, s, b, 2 < valid, 3 < valid);
-  out.z = restore2(d.z, s, b, 4 < valid, 5 < valid);
-  out.w = restore2(d.w, s, b, 6 < valid, 7 < valid);
+// eight halfs -> scale * d + bias in binary32 -> eight halfs (all zero when `on` is false)
+__device__ __forceinline__ uint4v restore8(uint4v d, float s, float b, bool on) {
+  uint4v out = {0u, 0u, 0u, 0u};
+  if (on) {
+    out.x = restore2(d.x, s, b);
+    out.y = restore2(d.y, s, b);
+    out.z = restore2(d.z, s, b);
+    out.w = restore2(d.w, s, b);
+  }
   return out;
 }
 
+// Workgroup barrier for the step loop.  __syncthreads() carries a release fence, for which the compiler waits
+// until EVERY outstanding memory operation of the wave has completed (s_waitcnt vmcnt(0)): that drains the
+// centroid gathers and activation copies that were issued steps ahead on purpose, and made each step cost a
+// full memory round trip.  Here only LDS traffic is waited for; the caller waits for the global->LDS copies
+// it needs by count.
+__device__ __forceinline__ void step_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+// Loads whose completion the kernel tracks itself.  The compiler's own wait insertion cannot count memory
+// operations across the unrolled, looping producer schedule and falls back to "wait for everything" at the
+// first use of a loaded register, which again drains the prefetch queues every step.  These loads are
+// therefore issued from inline assembly and consumed only after an explicit s_waitcnt with a counted bound.
+__device__ __forceinline__ void async_load16(uint4v &dst, const void *base, unsigned byte_offset) {
+  asm volatile("global_load_dwordx4 %0, %1, %2" : "=&v"(dst) : "v"(byte_offset), "s"(base) : "memory");
+}
+__device__ __forceinline__ void async_load16(uint4v &dst, const void *address) {
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(dst) : "v"(address) : "memory");
+}
+template <int N> __device__ __forceinline__ void wait_vmem_at_most() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+template <class T> __device__ __forceinline__ void settle(T &v) { asm volatile("" : "+v"(v)); }
+
+// Activation tile in LDS: [stage][BM rows][32 halfs], rows unpadded (64 bytes) because the asynchronous copy
+// writes 64 lanes x 16 bytes contiguously.  The four 16-byte chunks of a row are XOR-swizzled with bits 1..2
+// of the row so that the MFMA operand reads (32 rows, same chunk) spread over all banks.
+__device__ __forceinline__ unsigned x_slot(unsigned row, unsigned chunk) {     // byte offset inside a stage
+  return row * 64u + ((chunk ^ ((row >> 1) & 3u)) << 4);
+}
+
+// in_features % 32 == 0 here.  Wave w owns token rows [w*BM/4, (w+1)*BM/4) and all 128 channels.
 template <int BM>
-__global__ __launch_bounds__(256) void gemm_v8_kernel(Params p, const __half *__restrict__ X, long long ldx, int tokens,
+__global__ __launch_bounds__(512) void gemm_v8_kernel(Params p, const __half *__restrict__ X, long long ldx, int tokens,
                                                       __half *__restrict__ Y, long long ldy) {
-  constexpr int MB = BM / 128;                 // 32-row MFMA blocks per wave along the tokens
-  constexpr int XCH = BM * BK * 2 / 16 / 256;  // 16-byte activation chunks per thread per step
+  constexpr int MB = BM / 128;                  // 32-row MFMA blocks per wave along the tokens
+  constexpr int XW = BM / 64;                   // 1 KB activation pieces per wave per step (BM*64 bytes / 4 waves / 1 KB)
+  constexpr unsigned XSTAGE = BM * 64u;         // bytes per activation stage
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  __half *Xs = reinterpret_cast<__half *>(smem);                                   // [2][BM][LDT]
-  __half *Ws = Xs + 2 * BM * LDT;                                                  // [2][BN][LDT]
-  unsigned short *Is = reinterpret_cast<unsigned short *>(Ws + 2 * BN * LDT);      // [2][BN][SS*4]
+  unsigned char *Xs = smem;                                                        // [NSX][BM][64 bytes]
+  __half *Ws = reinterpret_cast<__half *>(smem + NSX * XSTAGE);                    // [2][BN][LDT]
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave8 = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const bool producer = wave8 >= 4;
+  const int wave = wave8 & 3;                   // index within the role
+  const int tid = threadIdx.x & 255;            // thread index within the role
   const int n0 = blockIdx.x * BN, m0 = blockIdx.y * BM;
-  const int ksteps = (p.in_features + BK - 1) / BK;
+  const int ksteps = p.in_features / BK;
 
-  // ---- this thread's share of the W tile: row w_row, vectors w_vec and w_vec + 1 of every step
-  const int w_row = tid >> 1, w_vec = (tid & 1) * 2;
+  // ---- this thread's share of the W tile: row w_row, vectors 2*w_half and 2*w_half + 1 of every step
+  const int w_row = tid >> 1, w_half = tid & 1;
+  const bool w_on = n0 + w_row < p.out_features;
   const int o_w = min(n0 + w_row, p.out_features - 1);
   const float s_w = p.scale ? __half2float(p.scale[o_w]) : 1.0f;
   const float b_w = p.bias ? __half2float(p.bias[o_w]) : 0.0f;
-  const uint4v *cb = reinterpret_cast<const uint4v *>(p.cb);
+  // activations: range-checked against the end of the last token row, so rows >= tokens read zeros
+  const __amdgpu_buffer_rsrc_t r_x = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<__half *>(X), 0, (unsigned)(((long long)(tokens - 1) * ldx + p.in_features) * 2), 0x00020000);
 
-  // index tile loader: 128 rows x 128 bytes per 16 steps = 1024 chunks of 16 bytes, 4 per thread
-  uint4v ireg[4];
-  auto load_index_tile = [&](int ss) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int c = tid + i * 256, row = c >> 3, part = c & 7;
-      const int o = min(n0 + row, p.out_features - 1);
-      const long long off = (long long)ss * (SS * 8) + part * 16;
-      ireg[i] = (off + 16 <= p.stride) ? *reinterpret_cast<const uint4v *>(p.idx + (long long)o * p.stride + off)
-                                       : uint4v{0u, 0u, 0u, 0u};
-    }
+  uint4v greg[GD][2];       // centroids of the steps in flight; step kt uses slot kt % GD
+  const unsigned char *irow = p.idx + (long long)o_w * p.stride;     // ksteps % 4 == 0: every 32-byte read stays in the row
+  // index pairs of four consecutive steps starting at step k4 (a multiple of 4): 32 bytes of this row, raw
+  auto load_indices = [&](int k4, uint4v &lo, uint4v &hi) {
+    async_load16(lo, irow + (long long)k4 * 8);
+    async_load16(hi, irow + (long long)k4 * 8 + 16);
   };
-  auto store_index_tile = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int c = tid + i * 256, row = c >> 3, part = c & 7;
-      *reinterpret_cast<uint4v *>(Is + (buf * BN + row) * (SS * 4) + part * 8) = ireg[i];
-    }
+  auto pick = [&](const uint4v &lo, const uint4v &hi, int j) -> unsigned {     // this thread's pair of step k4 + j
+    return j == 0 ? (w_half ? lo.y : lo.x) : j == 1 ? (w_half ? lo.w : lo.z) : j == 2 ? (w_half ? hi.y : hi.x) : (w_half ? hi.w : hi.z);
   };
-
-  // gather ring: centroids of steps kt+1 .. kt+GD in flight
-  uint4v greg[GD][2];
-  auto issue_gather = [&](int slot, int kt) {      // kt: step whose centroids to fetch; its index tile is in LDS
-    const int buf = (kt / SS) & 1, col = (kt % SS) * 4 + w_vec;
-    const unsigned pair = *reinterpret_cast<const unsigned *>(Is + (buf * BN + w_row) * (SS * 4) + col);
+  auto issue_gather = [&](uint4v (&g)[2], unsigned pair) {
     const unsigned i0 = min(pair & 0xFFFFu, (unsigned)p.k - 1u), i1 = min(pair >> 16, (unsigned)p.k - 1u);
-    greg[slot][0] = cb[i0];
-    greg[slot][1] = cb[i1];
+    async_load16(g[0], p.cb, i0 * 16u);
+    async_load16(g[1], p.cb, i1 * 16u);
   };
-
-  // activation tile loader
-  uint4v xreg[XCH];
-  auto load_x = [&](int kt) {
-#pragma unroll
-    for (int i = 0; i < XCH; ++i) {
-      const int c = tid + i * 256, row = c >> 2, col = (c & 3) * 8;
-      const int t = m0 + row, cc = kt * BK + col;
-      uint4v v = {0u, 0u, 0u, 0u};
-      if (t < tokens && cc < p.in_features) {
-        const __half *src = X + (long long)t * ldx + cc;
-        if (cc + 8 <= p.in_features) {
-          v = *reinterpret_cast<const uint4v *>(src);
-        } else {
-          __half tmp[8];
-#pragma unroll
-          for (int j = 0; j < 8; ++j) tmp[j] = (cc + j < p.in_features) ? src[j] : __ushort_as_half(0);
-          v = *reinterpret_cast<uint4v *>(tmp);
-        }
-      }
-      xreg[i] = v;
-    }
-  };
-  auto store_x = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < XCH; ++i) {
-      const int c = tid + i * 256, row = c >> 2, col = (c & 3) * 8;
-      *reinterpret_cast<uint4v *>(Xs + (buf * BM + row) * LDT + col) = xreg[i];
-    }
-  };
-  auto store_w = [&](int buf, int slot, int kt) {
+  auto store_w = [&](int buf, uint4v (&g)[2]) {
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      const int c0 = (kt * 4 + w_vec + j) * 8;                       // first column of this vector
-      const int valid = (n0 + w_row < p.out_features) ? max(0, min(8, p.in_features - c0)) : 0;
-      const uint4v w = restore8(greg[slot][j], s_w, b_w, valid);
-      *reinterpret_cast<uint4v *>(Ws + (buf * BN + w_row) * LDT + (w_vec + j) * 8) = w;
+      settle(g[j]);
+      *reinterpret_cast<uint4v *>(Ws + (buf * BN + w_row) * LDT + (w_half * 2 + j) * 8) = restore8(g[j], s_w, b_w, w_on);
+    }
+  };
+  // asynchronous copy of the activation tile of step kt into its stage: wave w copies pieces w*XW .. w*XW+XW-1
+  auto copy_x = [&](int kt) {
+    const unsigned stage = (unsigned)(kt % NSX) * XSTAGE;
+#pragma unroll
+    for (int i = 0; i < XW; ++i) {
+      const unsigned piece = (unsigned)(wave * XW + i);                 // 16 rows per piece
+      const unsigned r = piece * 16u + ((unsigned)lane >> 2), cs = (unsigned)lane & 3u;   // LDS slot (r, cs) holds chunk cs ^ swz(r)
+      const unsigned c = cs ^ ((r >> 1) & 3u);
+      const unsigned goff = (unsigned)(((long long)(m0 + (int)r) * ldx + (long long)kt * BK + c * 8) * 2);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r_x, (__attribute__((address_space(3))) void *)(Xs + stage + piece * 1024u), 16, goff, 0, 0, 0);
     }
   };
 
+  // The two roles run separate loops with the same number of barriers (one after the prologue, one per step),
+  // so that the accumulators of the consumers and the gather registers of the producers never live together.
+  if (producer) {
+    // Memory operations of a producer wave, in issue order, per step kt: [two index loads when kt % 4 == 0],
+    // XW activation copies (for step kt+XD), ... two centroid gathers (for step kt+1+GD).  They complete in order.
+    uint4v nlo, nhi, flo, fhi;            // raw indices of the next group and of the group after it
+    // ---- prologue: activations of steps 0 .. XD-1 in flight, centroids of steps 0 .. GD-1 in flight, W tile 0 in LDS
+#pragma unroll
+    for (int j = 0; j < XD; ++j)
+      if (j < ksteps) copy_x(j);
+    load_indices(0, flo, fhi);
+    if (GD < ksteps) load_indices(GD, nlo, nhi);
+    wait_vmem_at_most<0>();
+    settle(flo); settle(fhi); settle(nlo); settle(nhi);
+#pragma unroll
+    for (int j = 0; j < GD; ++j)
+      if (j < ksteps) issue_gather(greg[j], pick(flo, fhi, j));
+    wait_vmem_at_most<0>();
+    store_w(0, greg[0]);
+    if (GD < ksteps) issue_gather(greg[0], pick(nlo, nhi, 0));     // slot 0 now carries step GD
+    wait_vmem_at_most<0>();
+    __syncthreads();
+    for (int k4 = 0; k4 < ksteps; k4 += GD) {
+      const bool far_on = k4 + 2 * GD < ksteps;
+      if (far_on) load_indices(k4 + 2 * GD, flo, fhi);           // used from step k4 + 3 on
+#pragma unroll
+      for (int j = 0; j < GD; ++j) {
+        const int kt = k4 + j;                                    // ksteps % 4 == 0: kt < ksteps
+        const bool steady = kt + 5 < ksteps;                      // every step from kt-3 to kt issued its full set
+        if (kt + XD < ksteps) copy_x(kt + XD);
+        if (kt + 1 < ksteps) {
+          // The centroids of step kt+1 (slot (j+1) % GD) went out at the end of step kt-GD; since then this wave
+          // issued XW + 2 operations in each of steps kt-3 .. kt-1 and XW in this one (index loads not counted:
+          // with them the bound only gets safer).
+          if (steady) wait_vmem_at_most<GD * XW + 2 * (GD - 1)>(); else wait_vmem_at_most<0>();
+          const int sl = (j + 1) % GD;
+          store_w((kt & 1) ^ 1, greg[sl]);
+          if (kt + 1 + GD < ksteps) {
+            // the wait above also covers the index loads this gather needs (they are older than those centroids)
+            if (j + 1 < GD) { settle(nlo); settle(nhi); issue_gather(greg[sl], pick(nlo, nhi, j + 1)); }
+            else { settle(flo); settle(fhi); issue_gather(greg[sl], pick(flo, fhi, 0)); }
+          }
+        }
+        // The activation tile of step kt+1 must have landed before the barrier: its copies went out at step
+        // kt+1-XD, followed by two gathers in that step and XW + 2 operations in each later step up to kt.
+        if (steady) wait_vmem_at_most<(XD - 1) * (XW + 2) + 2>(); else wait_vmem_at_most<0>();
+        step_barrier();
+      }
+      // the group after next becomes the next group (its loads are older than everything waited for above)
+      nlo = flo; nhi = fhi;
+    }
+    return;
+  }
+
+  // ---- consumers
   float16v acc[MB][4];
 #pragma unroll
   for (int a = 0; a < MB; ++a)
@@ -140,37 +205,17 @@ __global__ __launch_bounds__(256) void gemm_v8_kernel(Params p, const __half *__
     for (int c = 0; c < 4; ++c)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.0f;
-
-  // ---- prologue: index tile 0 (and 1), activations of step 0, centroids of steps 0 .. GD-1
-  load_index_tile(0);
-  load_x(0);
-  store_index_tile(0);
-  __syncthreads();
-  if (SS < ksteps) load_index_tile(1);
-  {
-    // step 0's centroids are needed at once: fetch them through slot 0, then refill the ring for steps 1 .. GD
-    issue_gather(0, 0);
-    store_x(0);
-    store_w(0, 0, 0);
-  }
-#pragma unroll
-  for (int g = 0; g < GD; ++g)
-    if (1 + g < ksteps) issue_gather(g, 1 + g);      // slot g holds step 1 + g  (step kt lives in slot (kt - 1) % GD)
-  __syncthreads();
-
   const int wm = wave * (BM / 4);
+  __syncthreads();                                              // W tile and activation tile of step 0 are in LDS
   for (int kt = 0; kt < ksteps; ++kt) {
-    const int cur = kt & 1, nxt = cur ^ 1;
-    const bool more = kt + 1 < ksteps;
-    if (more) load_x(kt + 1);
-    // a new index tile becomes current every SS steps: tile (kt+1+GD)/SS must be in LDS before its gathers go out
-    // ---- MFMA on the current buffers
+    const int cur = kt & 1;
+    const unsigned char *xs = Xs + (unsigned)(kt % NSX) * XSTAGE;
 #pragma unroll
     for (int ks = 0; ks < BK; ks += 16) {
       half8 af[MB], bf[4];
 #pragma unroll
       for (int a = 0; a < MB; ++a)
-        af[a] = *reinterpret_cast<const half8 *>(Xs + (cur * BM + wm + a * 32 + (lane & 31)) * LDT + ks + (lane >> 5) * 8);
+        af[a] = *reinterpret_cast<const half8 *>(xs + x_slot((unsigned)(wm + a * 32 + (lane & 31)), (unsigned)(ks / 8 + (lane >> 5))));
 #pragma unroll
       for (int c = 0; c < 4; ++c)
         bf[c] = *reinterpret_cast<const half8 *>(Ws + (cur * BN + c * 32 + (lane & 31)) * LDT + ks + (lane >> 5) * 8);
@@ -179,16 +224,7 @@ __global__ __launch_bounds__(256) void gemm_v8_kernel(Params p, const __half *__
 #pragma unroll
         for (int c = 0; c < 4; ++c) acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[a], bf[c], acc[a][c], 0, 0, 0);
     }
-    if (more) {
-      store_x(nxt);
-      store_w(nxt, kt % GD, kt + 1);                 // step kt+1 lives in slot kt % GD
-    }
-    // index tile hand-over: when step kt+1+GD starts a new tile, that tile must already sit in LDS
-    const int g_next = kt + 1 + GD;                  // step whose gather is issued after this barrier
-    if (g_next % SS == 0 && g_next < ksteps) store_index_tile((g_next / SS) & 1);
-    __syncthreads();
-    if (g_next % SS == 0 && g_next + SS < ksteps) load_index_tile(g_next / SS + 1);
-    if (g_next < ksteps) issue_gather(kt % GD, g_next);
+    step_barrier();
   }
 
   // ---- store: lane holds channel (lane & 31) of block c and 16 token rows of block a
@@ -209,7 +245,7 @@ template <int BM>
 int launch_fused(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy, hipStream_t s) {
   static bool configured = false;
   auto kernel = gemm_v8_kernel<BM>;
-  const unsigned lds = (2 * BM * LDT + 2 * BN * LDT) * 2 + 2 * BN * SS * 4 * 2;
+  const unsigned lds = NSX * BM * 64u + 2u * BN * LDT * 2u;
   if (!configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
       return VQ_ERR_HIP;
@@ -217,20 +253,20 @@ int launch_fused(const Params &p, const __half *X, long long ldx, int tokens, __
   }
   const unsigned gx = (unsigned)((p.out_features + BN - 1) / BN), gy = (unsigned)((tokens + BM - 1) / BM);
   if (gy > 65535u) return VQ_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL(kernel, dim3(gx, gy), dim3(256), lds, s, p, X, ldx, tokens, Y, ldy);
+  hipLaunchKernelGGL(kernel, dim3(gx, gy), dim3(512), lds, s, p, X, ldx, tokens, Y, ldy);
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
 
 }  // namespace
 
 bool gemm_fused_applicable(const Params &p) {
-  return p.v == 8 && p.bits == 16 && p.k_res == 0 && p.n_out == 0;
+  return p.v == 8 && p.bits == 16 && p.k_res == 0 && p.n_out == 0 && p.in_features % (4 * BK) == 0;
 }
 
 int launch_gemm_fused(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy, hipStream_t s) {
   static const int force_bm = [] { const char *e = getenv("VQ_GEMM_BM"); return e ? atoi(e) : 0; }();
-  const int bm = force_bm ? force_bm : (tokens > 512 ? 512 : 256);
-  if (bm == 512) return launch_fused<512>(p, X, ldx, tokens, Y, ldy, s);
+  const int bm = force_bm ? force_bm : 256;
+  if (((long long)(tokens - 1) * ldx + p.in_features) * 2 >= (1LL << 32)) return VQ_ERR_UNSUPPORTED;   // 32-bit buffer offsets
   if (bm == 128) return launch_fused<128>(p, X, ldx, tokens, Y, ldy, s);
   return launch_fused<256>(p, X, ldx, tokens, Y, ldy, s);
 }
