@@ -2,10 +2,10 @@
 // L2 / Infinity Cache, not in LDS), no residual, no outlier columns -- the paper's v=8 / k=65536 setting
 // (App. "Impact of Vector Length").  Y = X * W^T with W restored on the fly; W never touches memory.
 //
-// A workgroup owns BM tokens x 128 output channels and splits its 8 waves in two roles that share each SIMD:
-//  * waves 0-3 ("consumers") only issue MFMA: wave w owns token rows [w*BM/4, ...) and all 128 channels as
-//    (BM/128) x 4 blocks of v_mfma_f32_32x32x16_f16, reading both operands from LDS;
-//  * waves 4-7 ("producers") keep the tiles coming: per 32-column step they gather 128 x 4 centroids
+// A workgroup owns BM tokens x 128 output channels and splits its waves in two roles that share the SIMDs:
+//  * BM/64 "consumer" waves only issue MFMA: wave w owns token rows [64 w, 64 w + 64) and all 128 channels as
+//    2 x 4 blocks of v_mfma_f32_32x32x16_f16, reading both operands from LDS;
+//  * four "producer" waves keep the tiles coming: per 32-column step they gather 128 x 4 centroids
 //    (16 bytes each, two per thread, issued GD steps ahead), apply scale and bias, write the FP16 W tile
 //    to LDS (double buffered), and start the asynchronous global->LDS copies of the activation tile
 //    XD steps ahead (XOR-swizzled 64-byte rows).
@@ -25,7 +25,7 @@ typedef unsigned uint4v __attribute__((ext_vector_type(4)));
 constexpr int BN = 128;       // output channels per workgroup
 constexpr int BK = 32;        // columns per step (4 vectors of 8)
 constexpr int LDT = BK + 8;   // W tile row pitch in halfs (80 bytes: 8 consecutive rows fall in 8 different 16-byte bank groups)
-constexpr int GD = 4;         // centroid gathers run this many steps ahead (one register slot per step)
+constexpr int GD = 8;         // centroid gathers run this many steps ahead (one register slot per step); also the index group size
 constexpr int XD = 3;         // activation copies run this many steps ahead
 constexpr int NSX = XD + 1;   // activation stages in LDS
 
@@ -81,10 +81,10 @@ __device__ __forceinline__ unsigned x_slot(unsigned row, unsigned chunk) {     /
 
 // in_features % 32 == 0 here.  Wave w owns token rows [w*BM/4, (w+1)*BM/4) and all 128 channels.
 template <int BM>
-__global__ __launch_bounds__(512) void gemm_v8_kernel(Params p, const __half *__restrict__ X, long long ldx, int tokens,
+__global__ __launch_bounds__((BM / 64 + 4) * 64) void gemm_v8_kernel(Params p, const __half *__restrict__ X, long long ldx, int tokens,
                                                       __half *__restrict__ Y, long long ldy) {
-  constexpr int MB = BM / 128;                  // 32-row MFMA blocks per wave along the tokens
-  constexpr int XW = BM / 64;                   // 1 KB activation pieces per wave per step (BM*64 bytes / 4 waves / 1 KB)
+  constexpr int NC = BM / 64;                   // consumer waves: each owns 64 token rows x 128 channels
+  constexpr int MB = 2;                         // 32-row MFMA blocks per consumer wave along the tokens
   constexpr unsigned XSTAGE = BM * 64u;         // bytes per activation stage
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char *Xs = smem;                                                        // [NSX][BM][64 bytes]
@@ -92,9 +92,9 @@ __global__ __launch_bounds__(512) void gemm_v8_kernel(Params p, const __half *__
 
   const int lane = threadIdx.x & 63;
   const int wave8 = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const bool producer = wave8 >= 4;
-  const int wave = wave8 & 3;                   // index within the role
-  const int tid = threadIdx.x & 255;            // thread index within the role
+  const bool producer = wave8 >= NC;
+  const int wave = producer ? wave8 - NC : wave8;             // index within the role
+  const int tid = producer ? (int)threadIdx.x - NC * 64 : (int)threadIdx.x;   // thread index within the role
   const int n0 = blockIdx.x * BN, m0 = blockIdx.y * BM;
   const int ksteps = p.in_features / BK;
 
@@ -108,96 +108,86 @@ __global__ __launch_bounds__(512) void gemm_v8_kernel(Params p, const __half *__
   const __amdgpu_buffer_rsrc_t r_x = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<__half *>(X), 0, (unsigned)(((long long)(tokens - 1) * ldx + p.in_features) * 2), 0x00020000);
 
-  uint4v greg[GD][2];       // centroids of the steps in flight; step kt uses slot kt % GD
-  const unsigned char *irow = p.idx + (long long)o_w * p.stride;     // ksteps % 4 == 0: every 32-byte read stays in the row
-  // index pairs of four consecutive steps starting at step k4 (a multiple of 4): 32 bytes of this row, raw
-  auto load_indices = [&](int k4, uint4v &lo, uint4v &hi) {
-    async_load16(lo, irow + (long long)k4 * 8);
-    async_load16(hi, irow + (long long)k4 * 8 + 16);
-  };
-  auto pick = [&](const uint4v &lo, const uint4v &hi, int j) -> unsigned {     // this thread's pair of step k4 + j
-    return j == 0 ? (w_half ? lo.y : lo.x) : j == 1 ? (w_half ? lo.w : lo.z) : j == 2 ? (w_half ? hi.y : hi.x) : (w_half ? hi.w : hi.z);
-  };
-  auto issue_gather = [&](uint4v (&g)[2], unsigned pair) {
-    const unsigned i0 = min(pair & 0xFFFFu, (unsigned)p.k - 1u), i1 = min(pair >> 16, (unsigned)p.k - 1u);
-    async_load16(g[0], p.cb, i0 * 16u);
-    async_load16(g[1], p.cb, i1 * 16u);
-  };
-  auto store_w = [&](int buf, uint4v (&g)[2]) {
+  // The two roles run separate loops with the same number of barriers (one after the prologue, one per step),
+  // so that the accumulators of the consumers and the gather registers of the producers never live together.
+  if (producer) {
+    uint4v greg[GD][2];       // centroids of the steps in flight; step kt uses slot kt % GD
+    struct IdxGroup { uint4v q[GD / 2]; };   // raw indices of GD consecutive steps of this row: 8 bytes per step
+    const unsigned char *irow = p.idx + (long long)o_w * p.stride;     // ksteps % GD == 0: every read stays in the row
+    auto load_indices = [&](int k0, IdxGroup &g) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      settle(g[j]);
-      *reinterpret_cast<uint4v *>(Ws + (buf * BN + w_row) * LDT + (w_half * 2 + j) * 8) = restore8(g[j], s_w, b_w, w_on);
+      for (int i = 0; i < GD / 2; ++i) async_load16(g.q[i], irow + (long long)k0 * 8 + i * 16);
+    };
+    auto settle_group = [&](IdxGroup &g) {
+#pragma unroll
+      for (int i = 0; i < GD / 2; ++i) settle(g.q[i]);
+    };
+    auto pick = [&](const IdxGroup &g, int j) -> unsigned {     // this thread's index pair of step k0 + j
+      const uint4v &v = g.q[j >> 1];
+      return (j & 1) ? (w_half ? v.w : v.z) : (w_half ? v.y : v.x);
+    };
+    auto issue_gather = [&](uint4v (&g)[2], unsigned pair) {
+      const unsigned i0 = min(pair & 0xFFFFu, (unsigned)p.k - 1u), i1 = min(pair >> 16, (unsigned)p.k - 1u);
+      async_load16(g[0], p.cb, i0 * 16u);
+      async_load16(g[1], p.cb, i1 * 16u);
+    };
+    auto store_w = [&](int buf, uint4v (&g)[2]) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        settle(g[j]);
+        *reinterpret_cast<uint4v *>(Ws + (buf * BN + w_row) * LDT + (w_half * 2 + j) * 8) = restore8(g[j], s_w, b_w, w_on);
+      }
+    };
+    // Memory operations of a producer wave, in issue order: per step two centroid gathers (for step kt+1+GD), plus
+    // GD/2 index loads at the start of every group of GD steps.  They complete in order.
+    IdxGroup nxt, far;        // raw indices of the next group and of the group after it
+    load_indices(0, far);
+    if (GD < ksteps) load_indices(GD, nxt);
+    wait_vmem_at_most<0>();
+    settle_group(far); settle_group(nxt);
+#pragma unroll
+    for (int j = 0; j < GD; ++j) issue_gather(greg[j], pick(far, j));        // steps 0 .. GD-1
+    wait_vmem_at_most<0>();
+    store_w(0, greg[0]);
+    if (GD < ksteps) issue_gather(greg[0], pick(nxt, 0));                    // slot 0 now carries step GD
+    step_barrier();
+    for (int k0 = 0; k0 < ksteps; k0 += GD) {
+      if (k0 + 2 * GD < ksteps) load_indices(k0 + 2 * GD, far);             // first used at the last step of this group
+#pragma unroll
+      for (int j = 0; j < GD; ++j) {
+        const int kt = k0 + j;                                    // ksteps % GD == 0: kt < ksteps
+        if (kt + 1 < ksteps) {
+          // The centroids of step kt+1 (slot (j+1) % GD) went out at the end of step kt-GD, followed by two
+          // gathers in each of the GD-1 steps since (index loads not counted: with them the bound only gets safer).
+          if (kt + GD < ksteps) wait_vmem_at_most<2 * (GD - 1)>(); else wait_vmem_at_most<0>();
+          const int sl = (j + 1) % GD;
+          store_w((kt & 1) ^ 1, greg[sl]);
+          if (kt + 1 + GD < ksteps) {
+            // the wait above also covers the index loads this gather needs (they are older than those centroids)
+            if (j + 1 < GD) { settle_group(nxt); issue_gather(greg[sl], pick(nxt, j + 1)); }
+            else { settle_group(far); issue_gather(greg[sl], pick(far, 0)); }
+          }
+        }
+        step_barrier();
+      }
+      nxt = far;      // the group after next becomes the next group (its loads completed before the last wait above)
     }
-  };
-  // asynchronous copy of the activation tile of step kt into its stage: wave w copies pieces w*XW .. w*XW+XW-1
+    return;
+  }
+
+  // ---- consumers: each wave streams its own 64 token rows through its slice of the activation stages (no other
+  // wave touches them, so only the wave's own counted wait stands between a copy and its use) and multiplies
   auto copy_x = [&](int kt) {
     const unsigned stage = (unsigned)(kt % NSX) * XSTAGE;
 #pragma unroll
-    for (int i = 0; i < XW; ++i) {
-      const unsigned piece = (unsigned)(wave * XW + i);                 // 16 rows per piece
+    for (int i = 0; i < 4; ++i) {
+      const unsigned piece = (unsigned)(wave * 4 + i);                  // 16 rows per 1 KB piece
       const unsigned r = piece * 16u + ((unsigned)lane >> 2), cs = (unsigned)lane & 3u;   // LDS slot (r, cs) holds chunk cs ^ swz(r)
       const unsigned c = cs ^ ((r >> 1) & 3u);
       const unsigned goff = (unsigned)(((long long)(m0 + (int)r) * ldx + (long long)kt * BK + c * 8) * 2);
       __builtin_amdgcn_raw_ptr_buffer_load_lds(r_x, (__attribute__((address_space(3))) void *)(Xs + stage + piece * 1024u), 16, goff, 0, 0, 0);
     }
   };
-
-  // The two roles run separate loops with the same number of barriers (one after the prologue, one per step),
-  // so that the accumulators of the consumers and the gather registers of the producers never live together.
-  if (producer) {
-    // Memory operations of a producer wave, in issue order, per step kt: [two index loads when kt % 4 == 0],
-    // XW activation copies (for step kt+XD), ... two centroid gathers (for step kt+1+GD).  They complete in order.
-    uint4v nlo, nhi, flo, fhi;            // raw indices of the next group and of the group after it
-    // ---- prologue: activations of steps 0 .. XD-1 in flight, centroids of steps 0 .. GD-1 in flight, W tile 0 in LDS
-#pragma unroll
-    for (int j = 0; j < XD; ++j)
-      if (j < ksteps) copy_x(j);
-    load_indices(0, flo, fhi);
-    if (GD < ksteps) load_indices(GD, nlo, nhi);
-    wait_vmem_at_most<0>();
-    settle(flo); settle(fhi); settle(nlo); settle(nhi);
-#pragma unroll
-    for (int j = 0; j < GD; ++j)
-      if (j < ksteps) issue_gather(greg[j], pick(flo, fhi, j));
-    wait_vmem_at_most<0>();
-    store_w(0, greg[0]);
-    if (GD < ksteps) issue_gather(greg[0], pick(nlo, nhi, 0));     // slot 0 now carries step GD
-    wait_vmem_at_most<0>();
-    __syncthreads();
-    for (int k4 = 0; k4 < ksteps; k4 += GD) {
-      const bool far_on = k4 + 2 * GD < ksteps;
-      if (far_on) load_indices(k4 + 2 * GD, flo, fhi);           // used from step k4 + 3 on
-#pragma unroll
-      for (int j = 0; j < GD; ++j) {
-        const int kt = k4 + j;                                    // ksteps % 4 == 0: kt < ksteps
-        const bool steady = kt + 5 < ksteps;                      // every step from kt-3 to kt issued its full set
-        if (kt + XD < ksteps) copy_x(kt + XD);
-        if (kt + 1 < ksteps) {
-          // The centroids of step kt+1 (slot (j+1) % GD) went out at the end of step kt-GD; since then this wave
-          // issued XW + 2 operations in each of steps kt-3 .. kt-1 and XW in this one (index loads not counted:
-          // with them the bound only gets safer).
-          if (steady) wait_vmem_at_most<GD * XW + 2 * (GD - 1)>(); else wait_vmem_at_most<0>();
-          const int sl = (j + 1) % GD;
-          store_w((kt & 1) ^ 1, greg[sl]);
-          if (kt + 1 + GD < ksteps) {
-            // the wait above also covers the index loads this gather needs (they are older than those centroids)
-            if (j + 1 < GD) { settle(nlo); settle(nhi); issue_gather(greg[sl], pick(nlo, nhi, j + 1)); }
-            else { settle(flo); settle(fhi); issue_gather(greg[sl], pick(flo, fhi, 0)); }
-          }
-        }
-        // The activation tile of step kt+1 must have landed before the barrier: its copies went out at step
-        // kt+1-XD, followed by two gathers in that step and XW + 2 operations in each later step up to kt.
-        if (steady) wait_vmem_at_most<(XD - 1) * (XW + 2) + 2>(); else wait_vmem_at_most<0>();
-        step_barrier();
-      }
-      // the group after next becomes the next group (its loads are older than everything waited for above)
-      nlo = flo; nhi = fhi;
-    }
-    return;
-  }
-
-  // ---- consumers
   float16v acc[MB][4];
 #pragma unroll
   for (int a = 0; a < MB; ++a)
@@ -205,10 +195,15 @@ __global__ __launch_bounds__(512) void gemm_v8_kernel(Params p, const __half *__
     for (int c = 0; c < 4; ++c)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.0f;
-  const int wm = wave * (BM / 4);
-  __syncthreads();                                              // W tile and activation tile of step 0 are in LDS
+  const int wm = wave * 64;
+#pragma unroll
+  for (int j = 0; j < XD; ++j)
+    if (j < ksteps) copy_x(j);
+  wait_vmem_at_most<0>();
+  step_barrier();                                               // the W tile of step 0 is in LDS
   for (int kt = 0; kt < ksteps; ++kt) {
     const int cur = kt & 1;
+    if (kt + XD < ksteps) copy_x(kt + XD);
     const unsigned char *xs = Xs + (unsigned)(kt % NSX) * XSTAGE;
 #pragma unroll
     for (int ks = 0; ks < BK; ks += 16) {
@@ -224,6 +219,8 @@ __global__ __launch_bounds__(512) void gemm_v8_kernel(Params p, const __half *__
 #pragma unroll
         for (int c = 0; c < 4; ++c) acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[a], bf[c], acc[a][c], 0, 0, 0);
     }
+    // this wave's rows of step kt+1 went out at step kt+1-XD; four copies per step since
+    if (kt + XD < ksteps) wait_vmem_at_most<4 * (XD - 1)>(); else wait_vmem_at_most<0>();
     step_barrier();
   }
 
@@ -253,20 +250,21 @@ int launch_fused(const Params &p, const __half *X, long long ldx, int tokens, __
   }
   const unsigned gx = (unsigned)((p.out_features + BN - 1) / BN), gy = (unsigned)((tokens + BM - 1) / BM);
   if (gy > 65535u) return VQ_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL(kernel, dim3(gx, gy), dim3(512), lds, s, p, X, ldx, tokens, Y, ldy);
+  hipLaunchKernelGGL(kernel, dim3(gx, gy), dim3((BM / 64 + 4) * 64), lds, s, p, X, ldx, tokens, Y, ldy);
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
 
 }  // namespace
 
 bool gemm_fused_applicable(const Params &p) {
-  return p.v == 8 && p.bits == 16 && p.k_res == 0 && p.n_out == 0 && p.in_features % (4 * BK) == 0;
+  return p.v == 8 && p.bits == 16 && p.k_res == 0 && p.n_out == 0 && p.in_features % (GD * BK) == 0;
 }
 
 int launch_gemm_fused(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy, hipStream_t s) {
   static const int force_bm = [] { const char *e = getenv("VQ_GEMM_BM"); return e ? atoi(e) : 0; }();
-  const int bm = force_bm ? force_bm : 256;
+  const int bm = force_bm ? force_bm : (tokens > 512 ? 512 : 256);
   if (((long long)(tokens - 1) * ldx + p.in_features) * 2 >= (1LL << 32)) return VQ_ERR_UNSUPPORTED;   // 32-bit buffer offsets
+  if (bm == 512) return launch_fused<512>(p, X, ldx, tokens, Y, ldy, s);
   if (bm == 128) return launch_fused<128>(p, X, ldx, tokens, Y, ldy, s);
   return launch_fused<256>(p, X, ldx, tokens, Y, ldy, s);
 }

@@ -8,6 +8,7 @@ SMALL = {
     "v6_k4096_res4096": dict(out_features=133, in_features=1000, v=6, k=4096, k_res=4096),
     "v6_res256_outlier": dict(out_features=150, in_features=1207, v=6, k=4096, k_res=256, n_outlier_cols=24, v_out=4, k_out=4096),
     "v8_k65536": dict(out_features=200, in_features=520, v=8, k=65536),
+    "v8_fused_path": dict(out_features=200, in_features=768, v=8, k=65536),                # in % 256 == 0: the fused MFMA kernel
     "v8_k65536_unscaled": dict(out_features=129, in_features=264, v=8, k=65536, with_scale=False, with_bias=False),
     "odd_everything": dict(out_features=37, in_features=203, v=5, k=37, k_res=11, n_outlier_cols=9, v_out=3, k_out=5),
     "v1_k2": dict(out_features=9, in_features=77, v=1, k=2),
