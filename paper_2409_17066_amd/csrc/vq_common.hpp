@@ -55,6 +55,20 @@ __device__ __forceinline__ __half restore(float d, float scale, float bias) {
   return __float2half_rn(w32);
 }
 
+// Touch the first `LINES` 64-byte lines of the kernel-argument segment with independent scalar loads.  The
+// compiler loads arguments lazily, a few at a time, each group waiting for its own miss in the scalar cache
+// (the segment is written by the host just before the launch); issuing one load per line up front overlaps
+// those misses, and the later argument loads hit.
+__device__ __forceinline__ void warm_kernel_arguments() {      // first four lines = 256 bytes
+#if defined(__HIP_DEVICE_COMPILE__)
+  const auto ka = __builtin_amdgcn_kernarg_segment_ptr();
+  unsigned a, b, c, d;
+  asm volatile("s_load_dword %0, %4, 0x0\n\ts_load_dword %1, %4, 0x40\n\ts_load_dword %2, %4, 0x80\n\t"
+               "s_load_dword %3, %4, 0xc0\n\ts_waitcnt lgkmcnt(0)"
+               : "=&s"(a), "=&s"(b), "=&s"(c), "=&s"(d) : "s"(ka) : "memory");
+#endif
+}
+
 __device__ __forceinline__ float wave_sum(float x) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);

@@ -36,6 +36,7 @@ struct GemvPlan {
   unsigned lds_x;                                  // activation rows in LDS: B regions of x_bytes each
   unsigned x_bytes;                                // bytes of one staged activation row (multiple of 1024)
   int rc;                                          // rows per reduction chunk
+  unsigned role[16];                               // per wave: slice | first row << 8 | main << 16 | outlier << 17
 };
 
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
@@ -226,6 +227,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_v6_kernel(Params p, GemvPlan pla
   constexpr int RB = RES_BITS ? RES_BITS : 8;
   constexpr int NR = window_dwords(RB, U);
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  warm_kernel_arguments();                      // Params + GemvPlan + four scalars: about 250 bytes
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int row0 = blockIdx.x * plan.rows_per_wg;
@@ -239,11 +241,10 @@ __global__ __launch_bounds__(NW * 64) void gemv_v6_kernel(Params p, GemvPlan pla
   VQ_STAMP(0);
 
   // ---- role of this wave: main slice `slice` of row stream `start`, or outlier slice, or idle
-  const int n_main = plan.RS * plan.W;
-  const bool is_main = wv < n_main;
-  const bool is_out = !is_main && (wv - n_main) < plan.Wo;
-  const int slice = is_main ? wv % plan.W : wv - n_main;
-  const int start = is_main ? wv / plan.W : 0;
+  const unsigned role = plan.role[wv];          // worked out on the host: no divisions here
+  const bool is_main = (role >> 16) & 1u, is_out = (role >> 17) & 1u;
+  const int slice = (int)(role & 0xFFu);
+  const int start = (int)((role >> 8) & 0xFFu);
   const int step = is_main ? plan.RS : 1;
   const int first_vec = (slice * 64 + lane) * U;
 
@@ -267,11 +268,11 @@ __global__ __launch_bounds__(NW * 64) void gemv_v6_kernel(Params p, GemvPlan pla
 
   for (int chunk0 = 0; chunk0 < rows_here; chunk0 += plan.rc) {
     const int rows_chunk = min(plan.rc, rows_here - chunk0);
-    const int n_iters = ((is_main || is_out) && start < rows_chunk) ? (rows_chunk - start + step - 1) / step : 0;
+    const int row_end = (is_main || is_out) ? rows_chunk : 0;     // rows start, start+step, ... below row_end are this wave's
     // ---- put the first DEPTH rows of index windows in flight
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)
-      if (d < n_iters) {
+      if (start + d * step < row_end) {
         const unsigned r = (unsigned)(chunk0 + start + d * step);
         load_window(wm[d], r_main, r * st_main, dw_main);
         if (RES_BITS && is_main) load_window(wr[d], r_res, r * st_res, dw_res);
@@ -336,12 +337,11 @@ __global__ __launch_bounds__(NW * 64) void gemv_v6_kernel(Params p, GemvPlan pla
     }
     VQ_STAMP(4);
 
-    for (int n0 = 0; n0 < n_iters; n0 += DEPTH) {
+    for (int rl0 = start; rl0 < row_end; rl0 += DEPTH * step) {
 #pragma unroll
       for (int d = 0; d < DEPTH; ++d) {
-        const int n = n0 + d;
-        if (n < n_iters) {
-          const int rl = start + n * step;
+        const int rl = rl0 + d * step;
+        if (rl < row_end) {
           Window<NM> cm;
           Window<NR> cr;
           normalize_from(cm, wm[d], sh_main);
@@ -352,7 +352,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_v6_kernel(Params p, GemvPlan pla
             for (int u = 0; u < L1R; ++u)
               g[u] = __builtin_amdgcn_raw_buffer_load_b96(r_cbres, field<RB>(cr, u) * 12u, 0, 0);
           }
-          if (n + DEPTH < n_iters) {          // refill this slot with the row DEPTH steps ahead
+          if (rl + DEPTH * step < row_end) {  // refill this slot with the row DEPTH steps ahead
             const unsigned r = (unsigned)(chunk0 + rl + DEPTH * step);
             load_window(wm[d], r_main, r * st_main, dw_main);
             if (RES_BITS && is_main) load_window(wr[d], r_res, r * st_res, dw_res);
@@ -539,6 +539,12 @@ int launch_gemv_fast(const Params &p, const __half *x, long long ldx, int batch,
     if (eff > best) { best = eff; plan.W = W; plan.U = U; plan.RS = RS; plan.Wo = Wo; plan.Uo = U; }
   }
   if (best < 0.0) return VQ_ERR_UNSUPPORTED;
+  for (int w = 0; w < NW; ++w) {
+    const int n_main = plan.RS * plan.W;
+    if (w < n_main) plan.role[w] = (unsigned)(w % plan.W) | ((unsigned)(w / plan.W) << 8) | (1u << 16);
+    else if (w - n_main < plan.Wo) plan.role[w] = (unsigned)(w - n_main) | (1u << 17);
+    else plan.role[w] = 0u;
+  }
   // one activation row, up to the last column any lane touches, in 1 KB pieces
   const long long x_cols = max((long long)p.n_out + 6LL * plan.W * 64 * plan.U, 4LL * plan.Wo * 64 * plan.U);
   plan.x_bytes = (unsigned)((x_cols * 2 + 1023) / 1024 * 1024);
