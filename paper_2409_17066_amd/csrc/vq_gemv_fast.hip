@@ -33,7 +33,8 @@ struct GemvPlan {
   int RS;                        // row streams (rows in flight) for the main waves
   int rows_per_wg;
   unsigned lds_out, lds_part, lds_xsum;            // byte offsets into dynamic LDS (the v=6 tables start at 0)
-  unsigned lds_x;                                  // activation rows in LDS: B regions of x_bytes each
+  unsigned lds_x;                                  // activation rows in LDS: x_regions regions of x_bytes each
+  int x_regions;                                   // batch rows staged at a time (1 .. B)
   unsigned x_bytes;                                // bytes of one staged activation row (multiple of 1024)
   int rc;                                          // rows per reduction chunk
   unsigned role[16];                               // per wave: slice | first row << 8 | main << 16 | outlier << 17
@@ -287,30 +288,37 @@ __global__ __launch_bounds__(NW * 64) void gemv_v6_kernel(Params p, GemvPlan pla
     const float ep_bias = (ep_on && p.bias) ? __half2float(p.bias[ep_o]) : 0.0f;
 
     if (chunk0 == 0) {
-      // ---- activations: every batch row is copied into LDS by asynchronous, range-checked 16-byte loads
-      // that write LDS directly (zeros past in_features, which is even here, so padded vectors and idle
-      // lanes multiply by zero); wave w copies 1 KB pieces w, w+16, ...  No registers are held meanwhile.
-#pragma unroll
-      for (int b = 0; b < B; ++b) {
-        const __amdgpu_buffer_rsrc_t rx = make_rsrc(x + b * ldx, (unsigned)p.in_features * 2u);
-        for (unsigned piece = (unsigned)wv * 1024u; piece < plan.x_bytes; piece += NW * 1024u)
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void *)(lds + plan.lds_x + b * plan.x_bytes + piece),
-                                                   16, piece + lane * 16u, 0, 0, 0);
-      }
-      VQ_STAMP(2);
       // ---- codebooks into LDS
       {
         TableRegs tabs;
         tables_load<RES_BITS>(tabs, p, plan.Wo != 0);
         tables_store<RES_BITS>(tabs, lds, plan, plan.Wo != 0);
       }
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the direct-to-LDS copies have landed
-      VQ_STAMP(3);
-      __syncthreads();
-      // ---- this lane's activations into registers (kept for the whole kernel), and sum(x) for the bias term
+      VQ_STAMP(2);
+      // ---- activations: batch rows are copied into LDS by asynchronous, range-checked 16-byte loads that write
+      // LDS directly (zeros past in_features, which is even here, so padded vectors and idle lanes multiply by
+      // zero); wave w copies 1 KB pieces w, w+16, ...  plan.x_regions rows fit at a time (all of them when LDS
+      // allows); each lane then moves its own vectors to registers, where they stay for the whole kernel.
 #pragma unroll
-      for (int b = 0; b < B; ++b) {
-        const unsigned char *xl = lds + plan.lds_x + b * plan.x_bytes;
+      for (int b0 = 0; b0 < B; ++b0) {
+        const int region = b0 % plan.x_regions;
+        if (region == 0) {
+          if (b0 != 0) __syncthreads();                       // everyone has read the previous group of rows
+#pragma unroll
+          for (int bb = 0; bb < B; ++bb) {
+            if (bb >= b0 && bb < b0 + plan.x_regions) {
+              const __amdgpu_buffer_rsrc_t rx = make_rsrc(x + bb * ldx, (unsigned)p.in_features * 2u);
+              for (unsigned piece = (unsigned)wv * 1024u; piece < plan.x_bytes; piece += NW * 1024u)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void *)(lds + plan.lds_x + (bb - b0) * plan.x_bytes + piece),
+                                                         16, piece + lane * 16u, 0, 0, 0);
+            }
+          }
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the direct-to-LDS copies have landed
+          VQ_STAMP(3);
+          __syncthreads();
+        }
+        const int b = b0;
+        const unsigned char *xl = lds + plan.lds_x + region * plan.x_bytes;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
           if (is_main) {
@@ -361,25 +369,30 @@ __global__ __launch_bounds__(NW * 64) void gemv_v6_kernel(Params p, GemvPlan pla
 #pragma unroll
           for (int b = 0; b < B; ++b) acc[b] = 0.0f;
           if (is_main) {
-            uint4v e[U], f[U];
+            // main lookups, then (second phase, reusing the registers) the LDS-side residual lookups
+            {
+              uint4v e[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) lds_gather16<LY::MAIN_OFF>(e[u], field_addr<12, LY::MAIN_SH>(cm, u));
+              for (int u = 0; u < U; ++u) lds_gather16<LY::MAIN_OFF>(e[u], field_addr<12, LY::MAIN_SH>(cm, u));
+              lds_gather_wait();
+#pragma unroll
+              for (int u = 0; u < U; ++u) settle(e[u]);
+#pragma unroll
+              for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int b = 0; b < B; ++b) {
+                  acc[b] = dot2(e[u].x, xr[b][u][0], acc[b]);
+                  acc[b] = dot2(e[u].y, xr[b][u][1], acc[b]);
+                  acc[b] = dot2(e[u].z, xr[b][u][2], acc[b]);
+                }
+            }
             if (RES_BITS) {
+              uint4v f[U];
 #pragma unroll
               for (int u = L1R; u < U; ++u) lds_gather16<LY::RES_OFF>(f[u], field_addr<RB, LY::RES_SH>(cr, u) + LY::RES_ADD);
-            }
-            lds_gather_wait();
+              lds_gather_wait();
 #pragma unroll
-            for (int u = 0; u < U; ++u) { settle(e[u]); if (RES_BITS && u >= L1R) settle(f[u]); }
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-              for (int b = 0; b < B; ++b) {
-                acc[b] = dot2(e[u].x, xr[b][u][0], acc[b]);
-                acc[b] = dot2(e[u].y, xr[b][u][1], acc[b]);
-                acc[b] = dot2(e[u].z, xr[b][u][2], acc[b]);
-              }
-            if (RES_BITS) {
+              for (int u = L1R; u < U; ++u) settle(f[u]);
 #pragma unroll
               for (int u = L1R; u < U; ++u)
 #pragma unroll
@@ -504,9 +517,9 @@ bool gemv_fast_applicable(const Params &p, const __half *x, long long ldx) {
 
 // Vectors per lane the kernels are built for, by batch group and residual use (register budget of 128).
 static bool u_allowed(int U, int batch, bool res) {
-  if (batch == 1) return res ? (U == 4 || U == 5) : (U == 4 || U == 5 || U == 6 || U == 8);
-  if (batch == 2) return res ? (U == 4) : (U == 4 || U == 5 || U == 6);
-  return !res && U == 4;
+  if (batch == 1) return res ? (U == 4 || U == 5 || U == 6) : (U == 4 || U == 5 || U == 6 || U == 8);
+  if (batch == 2) return res ? (U == 4 || U == 5) : (U == 4 || U == 5);
+  return U == 4;
 }
 
 // Launch for one group of 1, 2 or 4 batch rows.
@@ -548,11 +561,15 @@ int launch_gemv_fast(const Params &p, const __half *x, long long ldx, int batch,
   // one activation row, up to the last column any lane touches, in 1 KB pieces
   const long long x_cols = max((long long)p.n_out + 6LL * plan.W * 64 * plan.U, 4LL * plan.Wo * 64 * plan.U);
   plan.x_bytes = (unsigned)((x_cols * 2 + 1023) / 1024 * 1024);
-  plan.lds_x = off; off += plan.x_bytes * (unsigned)batch;
+  const int per_row = (plan.W + plan.Wo) * batch * 4;
+  const unsigned fixed = off + (unsigned)(NW * batch) * 4u + (unsigned)(plan.RS * per_row);   // tables, sums, fewest partial rows
+  if (fixed + plan.x_bytes > 160u * 1024u) return VQ_ERR_UNSUPPORTED;
+  plan.x_regions = (int)min((unsigned)batch, (160u * 1024u - fixed) / plan.x_bytes);
+  if (plan.x_regions == 3) plan.x_regions = 2;                 // groups of equal size
+  plan.lds_x = off; off += plan.x_bytes * (unsigned)plan.x_regions;
   plan.lds_xsum = off; off += (unsigned)(NW * batch) * 4u;
   plan.lds_part = off;
   if (off >= 160u * 1024u) return VQ_ERR_UNSUPPORTED;
-  const int per_row = (plan.W + plan.Wo) * batch * 4;
   plan.rc = min(RC_MAX, (int)((160u * 1024u - off) / (unsigned)per_row));
   if (plan.rc < plan.RS || plan.rc < 1) return VQ_ERR_UNSUPPORTED;
   off += (unsigned)(plan.rc * per_row);
