@@ -55,13 +55,27 @@ __global__ __launch_bounds__(256) void gemv_generic_kernel(Params p, const __hal
 bool gemv_fast_applicable(const Params &p, const __half *x, long long ldx);
 int launch_gemv_fast(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
 
-static bool force_generic() {
-  static const bool v = [] { const char *e = getenv("VQ_GEMV_KERNEL"); return e && e[0] == 'g'; }();
-  return v;
+int launch_gemv_mfma(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
+
+// VQ_GEMV_KERNEL=g forces the generic kernel, =m the matrix-core kernel, =d the dot-product kernels
+// (testing and measurement; unset: chosen by batch).  Read at every call so that one process can test them all.
+static char forced_kernel() {
+  const char *e = getenv("VQ_GEMV_KERNEL");
+  return e ? e[0] : '\0';
 }
+static bool force_generic() { return forced_kernel() == 'g'; }
 
 int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
-  if (!force_generic() && gemv_fast_applicable(p, x, ldx)) {
+  // Matrix-core kernel: one launch for any batch, at about the cost of a batch-1 launch of the dot-product
+  // kernels; those are still a little faster for one row (and for two rows of a layer with few output rows
+  // per compute unit), so they keep these cases.
+  const bool fast = !force_generic() && gemv_fast_applicable(p, x, ldx);
+  const bool many_rows = p.out_features > 16 * 256;
+  if (fast && forced_kernel() != 'd' && (batch >= 3 || (batch == 2 && many_rows) || forced_kernel() == 'm')) {
+    const int rc = launch_gemv_mfma(p, x, ldx, batch, y, ldy, s);
+    if (rc != VQ_ERR_UNSUPPORTED) return rc;
+  }
+  if (fast) {
     // batch rows go in groups of 4, 2 or 1; every group streams the indices once
     int done = 0, rc = VQ_OK;
     int g_max = 4;                      // largest group the layer's plan admits (found on the first group)
@@ -75,6 +89,10 @@ int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __ha
     }
     if (rc == VQ_OK) return VQ_OK;
     if (rc != VQ_ERR_UNSUPPORTED || done != 0) return rc;
+    if (forced_kernel() != 'd') {       // a shape the dot-product kernels do not take
+      rc = launch_gemv_mfma(p, x, ldx, batch, y, ldy, s);
+      if (rc != VQ_ERR_UNSUPPORTED) return rc;
+    }
   }
   const unsigned blocks = (unsigned)((p.out_features + 3) / 4);
   hipLaunchKernelGGL(gemv_generic_kernel, dim3(blocks), dim3(256), 0, s, p, x, ldx, batch, y, ldy);

@@ -10,6 +10,7 @@
 // accumulates with v_dot2_f32_f16.  Row sums are reduced across the wave with DPP and across slices
 // through a small LDS array; scale and bias are applied once per row as y = s * sum(d x) + b * sum(x).
 #include "vq_common.hpp"
+#include "vq_v6.hpp"
 #include <cstdlib>
 
 namespace vq {
@@ -22,6 +23,8 @@ __device__ unsigned long long g_prof[1024 * 16 * 8];
 #endif
 
 namespace {
+
+using namespace v6;
 
 constexpr int NW = 16;           // waves per workgroup
 constexpr int RC_MAX = 64;       // most rows per reduction chunk
@@ -39,124 +42,6 @@ struct GemvPlan {
   int rc;                                          // rows per reduction chunk
   unsigned role[16];                               // per wave: slice | first row << 8 | main << 16 | outlier << 17
 };
-
-typedef _Float16 half2v __attribute__((ext_vector_type(2)));
-typedef unsigned uint4v __attribute__((ext_vector_type(4)));
-typedef unsigned uint2v __attribute__((ext_vector_type(2)));
-typedef unsigned uint3v __attribute__((ext_vector_type(3)));
-
-__device__ __forceinline__ float dot2(unsigned a, unsigned b, float c) {
-  return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, a), __builtin_bit_cast(half2v, b), c, false);
-}
-
-__device__ __forceinline__ float half_pair_sum(unsigned packed) {
-  const half2v h = __builtin_bit_cast(half2v, packed);
-  return (float)h.x + (float)h.y;
-}
-
-__device__ __forceinline__ float dpp_add(float v, const int ctrl, const int row_mask) {
-  // v + (lane-permuted v); lanes whose row is masked out add 0
-  int moved;
-  switch (ctrl) {   // the builtin wants literal control words
-    case 0xB1: moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, false); break;
-    case 0x4E: moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, false); break;
-    case 0x141: moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, false); break;
-    case 0x140: moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, false); break;
-    case 0x142: moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x142, 0xA, 0xF, false); break;
-    default: moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x143, 0xC, 0xF, false); break;
-  }
-  (void)row_mask;
-  return v + __builtin_bit_cast(float, moved);
-}
-
-// Sum over the 64 lanes of a wave; the total lands in lane 63.
-__device__ __forceinline__ float wave_reduce_to_lane63(float v) {
-  v = dpp_add(v, 0xB1, 0xF);    // quad_perm [1,0,3,2]
-  v = dpp_add(v, 0x4E, 0xF);    // quad_perm [2,3,0,1]
-  v = dpp_add(v, 0x141, 0xF);   // row_half_mirror
-  v = dpp_add(v, 0x140, 0xF);   // row_mirror: every lane of a 16-lane row now holds the row's sum
-  v = dpp_add(v, 0x142, 0xA);   // row_bcast15 into rows 1 and 3
-  v = dpp_add(v, 0x143, 0xC);   // row_bcast31 into rows 2 and 3
-  return v;
-}
-
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, unsigned bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
-}
-
-// Index window of one lane: N dwords (4 or 6) starting at dword `dw` of the row at byte offset `row_off`.
-// Buffer loads are range-checked per dword: dwords past the end of the stream read as zero, never fault.
-template <int N> struct Window { unsigned w[N]; };
-
-template <int N>
-__device__ __forceinline__ void load_window(Window<N> &r, __amdgpu_buffer_rsrc_t rsrc, unsigned row_off, unsigned dw) {
-  static_assert(N >= 2 && N <= 6, "window of 2..6 dwords");
-  const unsigned off = row_off + dw * 4u;
-  if constexpr (N == 2) {
-    uint2v a = __builtin_amdgcn_raw_buffer_load_b64(rsrc, off, 0, 0);
-    r.w[0] = a.x; r.w[1] = a.y;
-  } else if constexpr (N == 3) {
-    uint3v a = __builtin_amdgcn_raw_buffer_load_b96(rsrc, off, 0, 0);
-    r.w[0] = a.x; r.w[1] = a.y; r.w[2] = a.z;
-  } else {
-    uint4v a = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0);
-    r.w[0] = a.x; r.w[1] = a.y; r.w[2] = a.z; r.w[3] = a.w;
-    if constexpr (N == 5) r.w[4] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, off + 16u, 0, 0);
-    if constexpr (N == 6) {
-      uint2v b = __builtin_amdgcn_raw_buffer_load_b64(rsrc, off + 16u, 0, 0);
-      r.w[4] = b.x; r.w[5] = b.y;
-    }
-  }
-}
-
-// Shift the window right by `sh` bits (0..31) so that the lane's first index starts at bit 0.
-template <int N>
-__device__ __forceinline__ void normalize_from(Window<N> &out, const Window<N> &in, unsigned sh) {
-#pragma unroll
-  for (int i = 0; i < N - 1; ++i) out.w[i] = __builtin_amdgcn_alignbit(in.w[i + 1], in.w[i], sh);
-  out.w[N - 1] = in.w[N - 1] >> sh;
-}
-
-// Field u (BITS wide) of a normalized window.
-template <int BITS, int N>
-__device__ __forceinline__ unsigned field(const Window<N> &win, int u) {
-  const int bit = u * BITS, i = bit >> 5, o = bit & 31;
-  if (o + BITS <= 32) return __builtin_amdgcn_ubfe(win.w[i], o, BITS);
-  return __builtin_amdgcn_alignbit(win.w[i + 1 < N ? i + 1 : i], win.w[i], o) & ((1u << BITS) - 1u);
-}
-
-// Byte offset (index << SHIFT) of field u of a normalized window, in two VALU ops: one shift that lands the
-// field SHIFT bits up, one mask.  (Fields that straddle two dwords cost one funnel shift more.)
-template <int BITS, int SHIFT, int N>
-__device__ __forceinline__ unsigned field_addr(const Window<N> &win, int u) {
-  const int bit = u * BITS, i = bit >> 5, o = bit & 31;
-  constexpr unsigned mask = ((1u << BITS) - 1u) << SHIFT;
-  if (o + BITS <= 32) {
-    const unsigned w = win.w[i];
-    return (o >= SHIFT ? (w >> (o - SHIFT)) : (w << (SHIFT - o))) & mask;
-  }
-  return (__builtin_amdgcn_alignbit(win.w[i + 1 < N ? i + 1 : i], win.w[i], o) << SHIFT) & mask;
-}
-
-// One centroid (12 bytes + 4 bytes of padding) from LDS, as one ds_read_b128 written by hand: measured on
-// gfx950, random 16-byte reads run at ~5.1 per clock per CU, while the 12-byte read the compiler would
-// narrow a plain load to (the padding is never used) runs at only ~3.2.  The read is asynchronous:
-// lds_gather_wait() must come before the first use of the values.
-template <int OFF>
-__device__ __forceinline__ void lds_gather16(uint4v &dst, unsigned lds_addr) {
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(lds_addr), "n"(OFF));
-}
-__device__ __forceinline__ void lds_gather8(uint2v &dst, unsigned lds_addr) {
-  asm volatile("ds_read_b64 %0, %1" : "=v"(dst) : "v"(lds_addr));
-}
-__device__ __forceinline__ void lds_gather_wait() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
-template <class T> __device__ __forceinline__ void settle(T &v) { asm volatile("" : "+v"(v)); }
-
-// 32-bit LDS address of a pointer into shared memory.
-__device__ __forceinline__ unsigned lds_address(const void *p) {
-  return (unsigned)reinterpret_cast<size_t>((const __attribute__((address_space(3))) void *)p);
-}
-
 
 // Codebook staging: all loads of all tables first, then the LDS writes.  Each thread takes four consecutive 12-byte entries (v = 6: three aligned
 // 16-byte loads) or two 16-byte chunks of 8-byte entries (v = 4).  Range-checked loads give zeros past the
@@ -179,18 +64,6 @@ __device__ __forceinline__ void tables_load(TableRegs &t, const Params &p, bool 
     for (int i = 0; i < 2; ++i) t.o[i] = __builtin_amdgcn_raw_buffer_load_b128(ro, (threadIdx.x + i * NW * 64) * 16u, 0, 0);
   }
 }
-
-// Table layouts in LDS, all with 16-byte entries (a 32-byte interleave of main and residual entries was
-// tried and lost: each table then only touches half of the banks).  The 8-bit residual table goes first so
-// that both gathers are "index << 4" plus an immediate offset:
-//   no residual:      main at 0
-//   8-bit residual:   residual at 0 (4 KB), main at 4096
-//   12-bit residual:  main at 0, residual at 65536 (one add per lookup: the offset field holds 16 bits)
-template <int RES_BITS> struct Layout {
-  static constexpr unsigned MAIN_OFF = RES_BITS == 8 ? 4096u : 0u, MAIN_SH = 4u;
-  static constexpr unsigned RES_OFF = 0u, RES_SH = 4u, RES_ADD = RES_BITS == 12 ? 65536u : 0u;
-  static constexpr unsigned BYTES = RES_BITS == 0 ? 65536u : RES_BITS == 8 ? 4096u + 65536u : 131072u;
-};
 
 template <unsigned OFF, unsigned SH>
 __device__ __forceinline__ void store_padded4(unsigned char *lds, const uint4v (&v)[3]) {

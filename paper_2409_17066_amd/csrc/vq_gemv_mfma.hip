@@ -1,0 +1,524 @@
+// vq_gemv on the matrix cores, for the same layers as the dot-product kernel (v = 6, 12-bit indices,
+// optional 12- or 8-bit residual codebook, optional v = 4 outlier columns; App. "Parameter Description")
+// and any batch 1..16: the decode-side product of Sec. 2.2's lookup with a handful of activation rows.
+//
+// One v_mfma_f32_16x16x32_f16 multiplies 16 output rows by 16 tokens over 32 "k" slots.  The k order is
+// free as long as both operands agree, so a slot group of 8 halves is one codebook vector: 6 (or 4)
+// values plus zero padding.  Lane l of a wave supplies, as operand A, the 16-byte LDS entry of row
+// (l & 15) for vector group (l >> 4) -- exactly what one ds_read_b128 gather returns -- and, as operand
+// B, the matching 6 activations of token (l & 15).  A gathered centroid therefore feeds one instruction
+// instead of 3 * batch dot-product operations, and the sum over a wave's lanes happens inside the MFMA:
+// the kernel runs at the LDS gather rate for every batch up to 16.
+//
+// Work split: a workgroup owns a block of rows (a multiple of 16) and walks them in chunks of up to four
+// 16-row blocks; within a chunk it makes passes over the columns: in pass p wave w covers vectors
+// [(p * MW + w) * 32, +32), eight per lane, whose 96 index bits are exactly three aligned dwords.  The
+// activations of a pass sit in registers (B operands) and are reused by every block of the chunk; index
+// words and the next pass's activations are loaded one pass ahead.  Each wave ends a chunk with a
+// 16 x 16 partial per block; partials meet in LDS, one wave per block adds them up and applies
+// y = scale * sum(d x) + bias * sum(x).  sum(x) comes from one more MFMA per pass against all-ones rows.
+#include "vq_common.hpp"
+#include "vq_v6.hpp"
+#include <cstdlib>
+
+namespace vq {
+#ifdef VQ_PROFILE
+__device__ unsigned long long g_prof_m[1024 * 16 * 8];
+#define VQ_STAMP(i) do { if (lane == 0) g_prof_m[(blockIdx.x * 16 + wv) * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define VQ_STAMP(i) do { } while (0)
+#endif
+namespace {
+
+using namespace v6;
+
+constexpr int NBMAX = 4;         // 16-row blocks per chunk
+constexpr int VPL = 8;           // vectors per lane per pass: 8 x 12 bits = 3 dwords, 8 x 8 bits = 2 dwords
+
+struct MfmaPlan {
+  int rows_per_wg;               // multiple of 16
+  int nb;                        // blocks per chunk, 1 .. NBMAX
+  int part_bufs;                 // 1: barrier after the reduction as well; 2: chunks alternate buffers
+  unsigned lds_out, lds_part, lds_xs;
+  unsigned x_bytes;              // bytes from x[0][0] to the end of the last batch row
+  int y_wide;                    // y rows allow 8-byte stores
+};
+
+typedef _Float16 half8v __attribute__((ext_vector_type(8)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float4v mfma16(uint4v a, uint4v b, float4v c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, a), __builtin_bit_cast(half8v, b), c, 0, 0, 0);
+}
+
+// Barrier for LDS traffic only: __syncthreads() would also wait for the index and activation loads that are
+// in flight for the next pass.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+// The index words and activations that run ahead of the computation are loaded from inline assembly and
+// waited for with counted s_waitcnt: the compiler's own wait insertion, across this kernel's control flow,
+// falls back to "wait for everything" at the first use of a loaded register, which would serialise the
+// prefetch ring.  Vector memory loads return in issue order, so "at most N outstanding" is exact when N is
+// the number of loads known to have been issued after the one needed (more loads after it only make the
+// wait stricter).  Descriptors are built by hand so that they can be passed as scalar operands: raw
+// buffers with per-dword range checking, out-of-range dwords read as zero.
+__device__ __forceinline__ uint4v scalar_rsrc(const void *base, unsigned bytes) {
+  const unsigned long long a = reinterpret_cast<unsigned long long>(base);
+  uint4v r;
+  r.x = (unsigned)a; r.y = (unsigned)(a >> 32) & 0xFFFFu; r.z = bytes; r.w = 0x00020000u;
+  return r;
+}
+__device__ __forceinline__ void async_load_b64(uint2v &dst, uint4v rsrc, unsigned off) {
+  asm volatile("buffer_load_dwordx2 %0, %1, %2, 0 offen" : "=&v"(dst) : "v"(off), "s"(rsrc) : "memory");
+}
+__device__ __forceinline__ void async_load_b96(uint3v &dst, uint4v rsrc, unsigned off) {
+  asm volatile("buffer_load_dwordx3 %0, %1, %2, 0 offen" : "=&v"(dst) : "v"(off), "s"(rsrc) : "memory");
+}
+template <int N> __device__ __forceinline__ void wait_vmem_at_most() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+template <int OFF>
+__device__ __forceinline__ void async_load_b128_at(uint4v &dst, uint4v rsrc, unsigned off) {
+  asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen offset:%3" : "=&v"(dst) : "v"(off), "s"(rsrc), "n"(OFF) : "memory");
+}
+
+// Codebooks into LDS with entries padded to 16 bytes (v = 6) or as they are (v = 4, 8 bytes), by T threads, in
+// two steps so that the index loads of the first passes can be issued in between: the table loads (hits in
+// L2 for all but the first workgroups) then return first and need not wait behind loads from HBM.
+// Range-checked loads return zeros past the k entries a table really has.
+template <int RES_BITS, int T> struct TableStage {
+  static constexpr int GROUPS = 1024 / T;       // groups of 4 entries (48 bytes) per thread and table of 4096
+  uint4v m[GROUPS][3], r[RES_BITS == 12 ? GROUPS : 1][3], o[2048 / T];
+
+  __device__ __forceinline__ void issue(const Params &p) {
+    const uint4v rm = scalar_rsrc(p.cb, (unsigned)p.k * 12u);
+#pragma unroll
+    for (int gi = 0; gi < GROUPS; ++gi) {
+      const unsigned off = (threadIdx.x + gi * T) * 48u;
+      async_load_b128_at<0>(m[gi][0], rm, off); async_load_b128_at<16>(m[gi][1], rm, off); async_load_b128_at<32>(m[gi][2], rm, off);
+    }
+    if (RES_BITS == 12) {
+      const uint4v rr = scalar_rsrc(p.cb_res, (unsigned)p.k_res * 12u);
+#pragma unroll
+      for (int gi = 0; gi < GROUPS; ++gi) {
+        const unsigned off = (threadIdx.x + gi * T) * 48u;
+        async_load_b128_at<0>(r[gi][0], rr, off); async_load_b128_at<16>(r[gi][1], rr, off); async_load_b128_at<32>(r[gi][2], rr, off);
+      }
+    }
+    if (RES_BITS == 8) {                         // 256 entries: every wave loads them, the first one stores them
+      const uint4v rr = scalar_rsrc(p.cb_res, (unsigned)p.k_res * 12u);
+      const unsigned off = (threadIdx.x & 63u) * 48u;
+      async_load_b128_at<0>(r[0][0], rr, off); async_load_b128_at<16>(r[0][1], rr, off); async_load_b128_at<32>(r[0][2], rr, off);
+    }
+    if (p.Q) {                                   // 4096 entries of 8 bytes
+      const uint4v ro = scalar_rsrc(p.cb_out, (unsigned)p.k_out * 8u);
+#pragma unroll
+      for (int i = 0; i < 2048 / T; ++i) async_load_b128_at<0>(o[i], ro, (threadIdx.x + i * T) * 16u);
+    }
+  }
+
+  static __device__ __forceinline__ void put4(unsigned char *base, unsigned first_entry, uint4v (&v)[3]) {
+    settle(v[0]); settle(v[1]); settle(v[2]);
+    const unsigned d[12] = {v[0].x, v[0].y, v[0].z, v[0].w, v[1].x, v[1].y, v[1].z, v[1].w, v[2].x, v[2].y, v[2].z, v[2].w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint4v e; e.x = d[3 * i]; e.y = d[3 * i + 1]; e.z = d[3 * i + 2]; e.w = 0u;
+      *reinterpret_cast<uint4v *>(base + (first_entry + i) * 16u) = e;
+    }
+  }
+
+  // after a wait that covers the loads of issue()
+  __device__ __forceinline__ void store(const Params &p, unsigned char *lds, unsigned lds_out) {
+    typedef Layout<RES_BITS> L;
+#pragma unroll
+    for (int gi = 0; gi < GROUPS; ++gi) put4(lds + L::MAIN_OFF, (threadIdx.x + gi * T) * 4u, m[gi]);
+    if (RES_BITS == 12) {
+#pragma unroll
+      for (int gi = 0; gi < GROUPS; ++gi) put4(lds + L::RES_ADD, (threadIdx.x + gi * T) * 4u, r[gi]);
+    }
+    if (RES_BITS == 8 && threadIdx.x < 64) put4(lds, threadIdx.x * 4u, r[0]);
+    if (p.Q) {
+#pragma unroll
+      for (int i = 0; i < 2048 / T; ++i) {
+        settle(o[i]);
+        *reinterpret_cast<uint4v *>(lds + lds_out + (threadIdx.x + i * T) * 16u) = o[i];
+      }
+    }
+  }
+};
+
+// Vector-ALU work is what this kernel has least of: a wave-wide VALU instruction occupies its SIMD for four
+// cycles, a wave-wide 16-byte LDS gather occupies the LDS for about twelve, so more than ~12 VALU
+// instructions per gather (summed over the four SIMDs) and the LDS starves.  Hence: two instructions per
+// LDS address, activations loaded straight into MFMA operand registers, load addresses advanced by
+// additions, end-of-row masking only in the one column group that needs it.
+template <int RES_BITS, int MW, int NB>
+__global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPlan plan, const __half *__restrict__ x, long long ldx,
+                                                                int batch, __half *__restrict__ y, long long ldy) {
+  typedef Layout<RES_BITS> LY;
+  constexpr int RB = RES_BITS ? RES_BITS : 8;
+  constexpr int PA = NB == 2 ? 4 : 2;                   // passes whose index words are in flight or in registers
+  constexpr int XD = 1, XS = XD + 1;                    // activations run XD passes ahead, in XS register sets
+  static_assert(PA % XS == 0, "the unrolled pass loop must map passes to activation sets statically");
+  constexpr int R = PA * NB;                            // ring of index-word slots: slot (j, b) = j * NB + b
+  constexpr int S = RES_BITS ? 2 : 1;                   // loads per slot
+  // loads issued after a slot's own by the time the slot is used, while the ring is being refilled: the other
+  // R - 1 slots and PA groups of eight activation loads; after a pass's activation loads: XD passes of refills
+  // and the activation loads of the passes in between
+  constexpr int AFTER_SLOT = (R - 1) * S + 8 * PA, AFTER_X = XD * NB * S + (XD - 1) * 8;
+  static_assert(AFTER_SLOT < 64, "vmcnt holds 6 bits");
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  warm_kernel_arguments();
+  const int lane = threadIdx.x & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int n = lane & 15, g = lane >> 4;       // A: row n of the block, vector group g.  B: token n.  D: token n, rows 4g..4g+3
+  VQ_STAMP(0);
+  const int row0 = blockIdx.x * plan.rows_per_wg;
+  const int rows_here = min(p.out_features - row0, plan.rows_per_wg);
+  const int n_blocks = (rows_here + 15) >> 4;
+  const int n_chunks = (n_blocks + NB - 1) / NB;
+  const unsigned a_out = lds_address(lds) + plan.lds_out;
+
+  const unsigned st_main = (unsigned)p.stride, st_res = (unsigned)p.stride_res, st_out = (unsigned)p.stride_out;
+  const uint4v r_main = scalar_rsrc(p.idx + (long long)row0 * p.stride, (unsigned)rows_here * st_main);
+  const uint4v r_res = scalar_rsrc(RES_BITS ? p.idx_res + (long long)row0 * p.stride_res : p.idx,
+                                   RES_BITS ? (unsigned)rows_here * st_res : 0u);
+  const uint4v r_xa = scalar_rsrc(x, plan.x_bytes);
+  const __amdgpu_buffer_rsrc_t r_out = make_rsrc(p.Q ? p.idx_out + (long long)row0 * p.stride_out : p.idx,
+                                                 p.Q ? (unsigned)rows_here * st_out : 0u);
+  const __amdgpu_buffer_rsrc_t r_x = make_rsrc(x, plan.x_bytes);
+  const __amdgpu_buffer_rsrc_t r_scale = make_rsrc(p.scale ? p.scale : p.cb, p.scale ? (unsigned)p.out_features * 2u : 0u);
+  const __amdgpu_buffer_rsrc_t r_bias = make_rsrc(p.bias ? p.bias : p.cb, p.bias ? (unsigned)p.out_features * 2u : 0u);
+  // tokens past the batch read out of range, i.e. zeros
+  const unsigned xrow = n < batch ? (unsigned)((long long)n * ldx * 2) : 0x80000000u;
+
+  // passes in which this wave has vectors: a prefix 0 .. my_passes-1 (pass p: group p * MW + wv of 32 vectors)
+  const int wave_groups = (p.P + 31) >> 5;
+  const int my_passes = wave_groups > wv ? (wave_groups - wv + MW - 1) / MW : 0;
+  const int eff_passes = max(my_passes, 1);                                   // a wave without vectors still walks the chunks
+  const int out_groups = (p.Q + 31) >> 5;
+  const int my_out_passes = out_groups > wv ? (out_groups - wv + MW - 1) / MW : 0;
+  // a group whose 192 columns (plus the two halves the last 16-byte load overshoots) end inside the row needs no masking
+  const int clean_groups = (p.in_features - p.n_out - 2) / 192;              // groups 0 .. clean_groups-1 are clean
+  const int last_clean_pass = clean_groups - 1 - wv >= 0 ? (clean_groups - 1 - wv) / MW : -1;
+
+  uint3v win[R], wres[RES_BITS == 12 ? R : 1];   // index words, PA passes deep
+  uint2v wres8[RES_BITS == 8 ? R : 1];
+  uint4v bxs[XS][VPL];                           // B operands (activations) of the current and of the next XD passes
+
+  // The wave's passes form one sequence over all chunks; the loader runs PA passes ahead of the consumer.
+  // Loader addresses: byte offset of the loader's pass inside a row, and of each block's row `n` in the streams.
+  int lp = 0;
+  unsigned l_main = (unsigned)(wv * 4 + g) * 12u, l_res = (unsigned)(wv * 4 + g) * (RES_BITS == 8 ? 8u : 12u);
+  unsigned lrow_main[NB], lrow_res[NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) { lrow_main[b] = (unsigned)(b * 16 + n) * st_main; lrow_res[b] = (unsigned)(b * 16 + n) * st_res; }
+  auto advance_loader = [&]() {
+    if (++lp == eff_passes) {
+      lp = 0;
+      l_main = (unsigned)(wv * 4 + g) * 12u; l_res = (unsigned)(wv * 4 + g) * (RES_BITS == 8 ? 8u : 12u);
+#pragma unroll
+      for (int b = 0; b < NB; ++b) { lrow_main[b] += (unsigned)(NB * 16) * st_main; lrow_res[b] += (unsigned)(NB * 16) * st_res; }
+    } else {
+      l_main += (MW * 4) * 12u; l_res += (MW * 4) * (RES_BITS == 8 ? 8u : 12u);
+    }
+  };
+  auto load_slot = [&](int slot, int b) {       // rows past the end read zeros
+    async_load_b96(win[slot], r_main, lrow_main[b] + l_main);
+    if (RES_BITS == 12) async_load_b96(wres[slot], r_res, lrow_res[b] + l_res);
+    if (RES_BITS == 8) async_load_b64(wres8[slot], r_res, lrow_res[b] + l_res);
+  };
+  // activations of one pass: eight overlapping 16-byte loads, one per vector; the fourth dword belongs to the
+  // next vector and meets the zero padding of the codebook entries
+  auto issue_x = [&](uint4v (&bx)[VPL], int pass) {
+    const unsigned off = xrow + ((unsigned)p.n_out + (unsigned)((pass * MW + wv) * 4 + g) * (VPL * 6u)) * 2u;
+    async_load_b128_at<0>(bx[0], r_xa, off);  async_load_b128_at<12>(bx[1], r_xa, off);
+    async_load_b128_at<24>(bx[2], r_xa, off); async_load_b128_at<36>(bx[3], r_xa, off);
+    async_load_b128_at<48>(bx[4], r_xa, off); async_load_b128_at<60>(bx[5], r_xa, off);
+    async_load_b128_at<72>(bx[6], r_xa, off); async_load_b128_at<84>(bx[7], r_xa, off);
+  };
+
+  {
+    TableStage<RES_BITS, MW * 64> tables;
+    tables.issue(p);
+    if (my_passes > 0) {
+#pragma unroll
+      for (int j = 0; j < PA; ++j) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) load_slot(j * NB + b, b);
+        advance_loader();
+      }
+#pragma unroll
+      for (int d = 0; d < XD; ++d) issue_x(bxs[d], d % my_passes);
+      VQ_STAMP(1);
+      wait_vmem_at_most<R * S + 8 * XD>();       // the tables are in; the index words may still be on their way
+    } else {
+      wait_vmem_at_most<0>();
+    }
+    tables.store(p, lds, plan.lds_out);
+  }
+  VQ_STAMP(2);
+  lds_barrier();
+  VQ_STAMP(3);
+
+  const uint4v ones = {0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0u};
+  float4v acc[NB];
+  float4v xs = {0.0f, 0.0f, 0.0f, 0.0f};
+  unsigned short ep_scale[4], ep_bias[4];          // raw halves; converted where they are used
+  int buf = 0, c = 0, pass = 0;
+  while (c < n_chunks) {
+#pragma unroll
+    for (int j = 0; j < PA; ++j) {
+      if (c < n_chunks) {
+        const int nb_c = min(NB, n_blocks - c * NB);
+        const int ep_o = row0 + (c * NB + wv) * 16 + 4 * g;      // wave b finishes block b of the chunk
+        if (pass == 0) {
+          // ---- chunk start
+#pragma unroll
+          for (int b = 0; b < NB; ++b) acc[b] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
+          if (wv < nb_c) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              ep_scale[r] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r_scale, (unsigned)(ep_o + r) * 2u, 0, 0);
+              ep_bias[r] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r_bias, (unsigned)(ep_o + r) * 2u, 0, 0);
+            }
+          }
+          // outlier columns (v = 4): same scheme with 8-byte table entries; their loads are not run ahead
+          for (int q = 0; q < my_out_passes; ++q) {
+            const unsigned lane_group = (unsigned)((q * MW + wv) * 4 + g);
+            uint3v wo[NB];
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+              wo[b] = __builtin_amdgcn_raw_buffer_load_b96(r_out, (unsigned)((c * NB + b) * 16 + n) * st_out + lane_group * 12u, 0, 0);
+            const unsigned col = lane_group * (VPL * 4u);
+            uint4v xo[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) xo[i] = __builtin_amdgcn_raw_buffer_load_b128(r_x, xrow + (col + i * 8u) * 2u, 0, 0);
+            const unsigned xd[16] = {xo[0].x, xo[0].y, xo[0].z, xo[0].w, xo[1].x, xo[1].y, xo[1].z, xo[1].w,
+                                     xo[2].x, xo[2].y, xo[2].z, xo[2].w, xo[3].x, xo[3].y, xo[3].z, xo[3].w};
+            uint4v bx[VPL];
+#pragma unroll
+            for (int u = 0; u < VPL; ++u) {
+              bx[u].x = (int)(col + 4 * u) < p.n_out ? xd[2 * u] : 0u;         // n_out is a multiple of 4
+              bx[u].y = (int)(col + 4 * u) < p.n_out ? xd[2 * u + 1] : 0u;
+              bx[u].z = 0u; bx[u].w = 0u;
+            }
+            if (c == 0) {
+#pragma unroll
+              for (int u = 0; u < VPL; ++u) xs = mfma16(ones, bx[u], xs);
+            }
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+              if (b < nb_c) {
+                Window<3> cw; cw.w[0] = wo[b].x; cw.w[1] = wo[b].y; cw.w[2] = wo[b].z;
+                uint2v e[VPL];
+#pragma unroll
+                for (int u = 0; u < VPL; ++u) lds_gather8(e[u], field_addr<12, 3>(cw, u) + a_out);
+                lds_gather_wait();
+#pragma unroll
+                for (int u = 0; u < VPL; ++u) settle(e[u]);
+#pragma unroll
+                for (int u = 0; u < VPL; ++u) {
+                  uint4v a; a.x = e[u].x; a.y = e[u].y; a.z = 0u; a.w = 0u;
+                  acc[b] = mfma16(a, bx[u], acc[b]);
+                }
+              }
+          }
+        }
+
+        if (my_passes > 0) {
+          // ---- one pass over this wave's 32 vectors of every block of the chunk
+          // Every pass issues the same number of loads, also past the end of the sequence (the loader's offsets are
+          // then out of range: such loads fetch nothing and return zeros), so the counted waits hold throughout.
+          uint4v (&bx)[VPL] = bxs[j % XS];
+          wait_vmem_at_most<AFTER_X>();
+#pragma unroll
+          for (int u = 0; u < VPL; ++u) settle(bx[u]);
+          if (pass > last_clean_pass) {          // the group that holds the end of the row: zero what lies past it
+            const int col = p.n_out + ((pass * MW + wv) * 4 + g) * (VPL * 6);
+#pragma unroll
+            for (int u = 0; u < VPL; ++u) {
+              bx[u].x = col + 6 * u < p.in_features ? bx[u].x : 0u;           // in_features is even
+              bx[u].y = col + 6 * u + 2 < p.in_features ? bx[u].y : 0u;
+              bx[u].z = col + 6 * u + 4 < p.in_features ? bx[u].z : 0u;
+              bx[u].w = 0u;
+            }
+          }
+          if (c == 0) {
+#pragma unroll
+            for (int u = 0; u < VPL; ++u) xs = mfma16(ones, bx[u], xs);
+          }
+          issue_x(bxs[(j + XD) % XS], (pass + XD) % my_passes);
+#pragma unroll
+          for (int b = 0; b < NB; ++b) {
+            const int slot = j * NB + b;
+            wait_vmem_at_most<AFTER_SLOT>();
+            settle(win[slot]);
+            if (RES_BITS == 12) settle(wres[slot]);
+            if (RES_BITS == 8) settle(wres8[slot]);
+            Window<3> cm, cr;
+            cm.w[0] = win[slot].x; cm.w[1] = win[slot].y; cm.w[2] = win[slot].z;
+            if (RES_BITS == 12) { cr.w[0] = wres[slot].x; cr.w[1] = wres[slot].y; cr.w[2] = wres[slot].z; }
+            if (RES_BITS == 8) { cr.w[0] = wres8[slot].x; cr.w[1] = wres8[slot].y; cr.w[2] = 0u; }
+            unsigned am[VPL], ar[VPL];                           // LDS addresses, before the slot is overwritten
+#pragma unroll
+            for (int u = 0; u < VPL; ++u) {
+              am[u] = field_addr<12, LY::MAIN_SH>(cm, u);
+              ar[u] = RES_BITS ? field_addr<RB, LY::RES_SH>(cr, u) + LY::RES_ADD : 0u;
+              settle(am[u]);
+              if (RES_BITS) settle(ar[u]);
+            }
+            load_slot(slot, b);                                  // refill with the pass PA ahead
+            if (b < nb_c) {
+              {
+                uint4v e[VPL];
+#pragma unroll
+                for (int u = 0; u < VPL; ++u) lds_gather16<LY::MAIN_OFF>(e[u], am[u]);
+                lds_gather_wait();
+#pragma unroll
+                for (int u = 0; u < VPL; ++u) settle(e[u]);
+#pragma unroll
+                for (int u = 0; u < VPL; ++u) acc[b] = mfma16(e[u], bx[u], acc[b]);
+              }
+              if (RES_BITS) {
+                uint4v f[VPL];
+#pragma unroll
+                for (int u = 0; u < VPL; ++u) lds_gather16<LY::RES_OFF>(f[u], ar[u]);
+                lds_gather_wait();
+#pragma unroll
+                for (int u = 0; u < VPL; ++u) settle(f[u]);
+#pragma unroll
+                for (int u = 0; u < VPL; ++u) acc[b] = mfma16(f[u], bx[u], acc[b]);
+              }
+            }
+          }
+        }
+        advance_loader();
+
+        if (pass == eff_passes - 1) {
+          // ---- chunk end: partial sums to LDS; wave b adds up block b, applies scale and bias, stores
+          VQ_STAMP(4);
+          unsigned char *pbase = lds + plan.lds_part + (unsigned)(buf * NB) * (MW * 1024u);
+#pragma unroll
+          for (int b = 0; b < NB; ++b)
+            if (b < nb_c) *reinterpret_cast<float4v *>(pbase + (unsigned)(b * MW + wv) * 1024u + lane * 16u) = acc[b];
+          float *xs_part = reinterpret_cast<float *>(lds + plan.lds_xs);       // [MW][16]
+          if (c == 0 && g == 0) xs_part[wv * 16 + n] = xs.x;
+          lds_barrier();
+          VQ_STAMP(5);
+          if (wv < nb_c) {
+            float4v s = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int w = 0; w < MW; ++w) s += *reinterpret_cast<const float4v *>(pbase + (unsigned)(wv * MW + w) * 1024u + lane * 16u);
+            float xsum = 0.0f;
+#pragma unroll
+            for (int w = 0; w < MW; ++w) xsum += xs_part[w * 16 + n];
+            const float sv[4] = {s.x, s.y, s.z, s.w};
+            __half out[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const float sc = p.scale ? (float)__builtin_bit_cast(_Float16, ep_scale[r]) : 1.0f;
+              const float bi = p.bias ? (float)__builtin_bit_cast(_Float16, ep_bias[r]) : 0.0f;
+              out[r] = __float2half_rn(__fmaf_rn(sc, sv[r], bi * xsum));
+            }
+            if (n < batch) {
+              __half *dst = y + (long long)n * ldy + ep_o;
+              if (plan.y_wide && ep_o + 3 < p.out_features) {
+                uint2v pk;
+                pk.x = (unsigned)__half_as_ushort(out[0]) | ((unsigned)__half_as_ushort(out[1]) << 16);
+                pk.y = (unsigned)__half_as_ushort(out[2]) | ((unsigned)__half_as_ushort(out[3]) << 16);
+                *reinterpret_cast<uint2v *>(dst) = pk;
+              } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                  if (ep_o + r < p.out_features) dst[r] = out[r];
+              }
+            }
+          }
+          VQ_STAMP(6);
+          if (plan.part_bufs == 1) lds_barrier(); else buf ^= 1;
+          pass = 0; ++c;
+        } else {
+          ++pass;
+        }
+      }
+    }
+  }
+}
+
+int g_cu_count = 0;
+
+int cu_count() {
+  if (g_cu_count == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+    g_cu_count = n;
+  }
+  return g_cu_count;
+}
+
+template <int RES_BITS, int MW, int NB>
+int launch_one(const Params &p, const MfmaPlan &plan, unsigned lds_bytes, unsigned grid, const __half *x, long long ldx, int batch,
+               __half *y, long long ldy, hipStream_t s) {
+  static bool configured = false;
+  auto kernel = gemv_v6_mfma_kernel<RES_BITS, MW, NB>;
+  if (!configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+      return VQ_ERR_HIP;
+    configured = true;
+  }
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(MW * 64), lds_bytes, s, p, plan, x, ldx, batch, y, ldy);
+  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+#ifndef VQ_MFMA_WAVES
+#define VQ_MFMA_WAVES 8
+#endif
+constexpr int MW = VQ_MFMA_WAVES;
+
+}  // namespace
+
+#ifdef VQ_PROFILE
+extern "C" int vq_debug_read_profile_m(unsigned long long *dst, size_t count) {
+  return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_prof_m), count * sizeof(unsigned long long));
+}
+#endif
+
+// Launch for batch 1..16.  The caller has checked gemv_fast_applicable().
+int launch_gemv_mfma(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
+  MfmaPlan plan{};
+  const int rb = p.k_res ? p.bits_res : 0;
+  unsigned off = rb == 0 ? Layout<0>::BYTES : rb == 8 ? Layout<8>::BYTES : Layout<12>::BYTES;
+  plan.lds_out = off; off += p.Q ? 4096u * 8u : 0u;
+  plan.lds_xs = off; off += MW * 16u * 4u;
+  plan.lds_part = off;
+  const unsigned lds_cap = 160u * 1024u;
+  if (off + MW * 1024u > lds_cap) return VQ_ERR_UNSUPPORTED;
+  const int blocks_total = (p.out_features + 15) / 16;
+  const int cus = cu_count();
+  const int blocks_per_wg = (blocks_total + cus - 1) / cus;
+  plan.rows_per_wg = blocks_per_wg * 16;
+  const unsigned grid = (unsigned)((blocks_total + blocks_per_wg - 1) / blocks_per_wg);
+  const int fit = (int)((lds_cap - off) / (MW * 1024u));                 // 16-row partial blocks that fit
+  plan.nb = min(min(NBMAX, blocks_per_wg), fit);
+  plan.part_bufs = (fit >= 2 * plan.nb && blocks_per_wg > plan.nb) ? 2 : 1;
+  off += (unsigned)(plan.part_bufs * plan.nb) * (MW * 1024u);
+  const long long max_stride = max(p.stride, max(p.stride_res, p.stride_out));
+  if ((long long)(plan.rows_per_wg + 16 * NBMAX * 8) * max_stride >= (1LL << 31)) return VQ_ERR_UNSUPPORTED;   // 32-bit buffer offsets
+  const long long x_bytes = ((long long)(batch - 1) * ldx + p.in_features) * 2;
+  if (ldx < 0 || x_bytes >= (1LL << 31) - (1 << 20)) return VQ_ERR_UNSUPPORTED;
+  plan.x_bytes = (unsigned)x_bytes;
+  plan.y_wide = ((reinterpret_cast<uintptr_t>(y) & 7) == 0 && (ldy & 3) == 0) ? 1 : 0;
+#define VQ_CASE(RBITS, NBLK) \
+  if (rb == RBITS && plan.nb == NBLK) return launch_one<RBITS, MW, NBLK>(p, plan, off, grid, x, ldx, batch, y, ldy, s);
+  VQ_CASE(0, 1) VQ_CASE(0, 2) VQ_CASE(0, 3) VQ_CASE(0, 4)
+  VQ_CASE(8, 1) VQ_CASE(8, 2) VQ_CASE(8, 3) VQ_CASE(8, 4)
+  VQ_CASE(12, 1) VQ_CASE(12, 2) VQ_CASE(12, 3) VQ_CASE(12, 4)
+#undef VQ_CASE
+  return VQ_ERR_UNSUPPORTED;
+}
+
+}  // namespace vq

@@ -42,7 +42,7 @@ def _matmul_ok(y, ref, what):
 
 
 @pytest.mark.parametrize("cfg,name", [(0, "tiny"), (1, "up"), (2, "q"), (2, "gate"), (2, "down"), (3, "down70b"), (4, "prefill")])
-def test_config_dequant_and_gemv(gpu_lib, layers, cfg, name):
+def test_config_dequant_and_gemv(gpu_lib, layers, monkeypatch, cfg, name):
     import torch
     ordinal, L = layers(cfg, name)
     dl = _dequant_exact(gpu_lib, L)
@@ -50,9 +50,15 @@ def test_config_dequant_and_gemv(gpu_lib, layers, cfg, name):
     batches = spec["rows"] if cfg != 4 else [1, 16]
     for batch in batches:
         x = s.make_activations(cfg, L, batch, layer_ordinal=ordinal, outlier_gain=spec.get("outlier_gain", 1.0))
-        y = gpu_lib.gemv(dl, torch.from_numpy(x).cuda())
-        torch.cuda.synchronize()
-        _matmul_ok(y, oracle.gemv(L, x), "cfg%d %s batch %d" % (cfg, name, batch))
+        ref = oracle.gemv(L, x)
+        xd = torch.from_numpy(x).cuda()
+        for kernel in ("auto", "m", "d"):              # default dispatch, matrix-core kernel, dot-product kernels
+            if kernel != "auto":
+                monkeypatch.setenv("VQ_GEMV_KERNEL", kernel)
+            y = gpu_lib.gemv(dl, xd)
+            torch.cuda.synchronize()
+            monkeypatch.delenv("VQ_GEMV_KERNEL", raising=False)
+            _matmul_ok(y, ref, "cfg%d %s batch %d kernel %s" % (cfg, name, batch, kernel))
 
 
 @pytest.mark.parametrize("tokens", [512, 1024, 2048])

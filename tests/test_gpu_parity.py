@@ -33,8 +33,13 @@ def test_dequant_bit_exact_small(gpu_lib, name):
 
 @pytest.mark.parametrize("name", list(SMALL))
 @pytest.mark.parametrize("batch", [1, 2, 3, 4, 8, 16])
-def test_gemv_small(gpu_lib, name, batch):
+@pytest.mark.parametrize("kernel", ["auto", "m", "d"])
+def test_gemv_small(gpu_lib, monkeypatch, name, batch, kernel):
+    """Every batch through the default dispatch, then with the matrix-core kernel and the dot-product kernels forced
+    (layers they do not take fall through to the generic kernel)."""
     import torch
+    if kernel != "auto":
+        monkeypatch.setenv("VQ_GEMV_KERNEL", kernel)
     L = small_layer(name)
     dl = gpu_lib.DeviceLayer(L)
     x = s.make_activations(300, L, batch)
