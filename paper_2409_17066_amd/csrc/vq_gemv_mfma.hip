@@ -42,6 +42,7 @@ struct MfmaPlan {
   unsigned lds_out, lds_part, lds_xs;
   unsigned x_bytes;              // bytes from x[0][0] to the end of the last batch row
   int y_wide;                    // y rows allow 8-byte stores
+  unsigned lds_sb;               // scale | bias << 16 of the workgroup's rows
 };
 
 typedef _Float16 half8v __attribute__((ext_vector_type(8)));
@@ -66,6 +67,14 @@ __device__ __forceinline__ void lds_barrier() {
 // the number of loads known to have been issued after the one needed (more loads after it only make the
 // wait stricter).  Descriptors are built by hand so that they can be passed as scalar operands: raw
 // buffers with per-dword range checking, out-of-range dwords read as zero.
+//
+// Two rules keep this sound.  (1) Every asynchronous destination is a read-write ("+v") operand, refilled in
+// straight-line code: the new value is tied to the register of the old one, so a slot keeps its register
+// through every branch and loop edge.  With write-only operands, or a refill inside a branch, the compiler
+// merges old and new values with register copies at the joins -- copies of a register whose load has not
+// landed yet.  The build also refuses any spill in these kernels, for the same reason.  (2) Every load
+// instruction keeps at least one lane in range.  A load whose lanes are all out of range fetches nothing and
+// has been seen to complete ahead of older loads, which breaks the counting.
 __device__ __forceinline__ uint4v scalar_rsrc(const void *base, unsigned bytes) {
   const unsigned long long a = reinterpret_cast<unsigned long long>(base);
   uint4v r;
@@ -73,16 +82,16 @@ __device__ __forceinline__ uint4v scalar_rsrc(const void *base, unsigned bytes) 
   return r;
 }
 __device__ __forceinline__ void async_load_b64(uint2v &dst, uint4v rsrc, unsigned off) {
-  asm volatile("buffer_load_dwordx2 %0, %1, %2, 0 offen" : "=&v"(dst) : "v"(off), "s"(rsrc) : "memory");
+  asm volatile("buffer_load_dwordx2 %0, %1, %2, 0 offen" : "+v"(dst) : "v"(off), "s"(rsrc) : "memory");
 }
 __device__ __forceinline__ void async_load_b96(uint3v &dst, uint4v rsrc, unsigned off) {
-  asm volatile("buffer_load_dwordx3 %0, %1, %2, 0 offen" : "=&v"(dst) : "v"(off), "s"(rsrc) : "memory");
+  asm volatile("buffer_load_dwordx3 %0, %1, %2, 0 offen" : "+v"(dst) : "v"(off), "s"(rsrc) : "memory");
 }
 template <int N> __device__ __forceinline__ void wait_vmem_at_most() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
 template <int OFF>
 __device__ __forceinline__ void async_load_b128_at(uint4v &dst, uint4v rsrc, unsigned off) {
-  asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen offset:%3" : "=&v"(dst) : "v"(off), "s"(rsrc), "n"(OFF) : "memory");
+  asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen offset:%3" : "+v"(dst) : "v"(off), "s"(rsrc), "n"(OFF) : "memory");
 }
 
 // Codebooks into LDS with entries padded to 16 bytes (v = 6) or as they are (v = 4, 8 bytes), by T threads, in
@@ -192,8 +201,11 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
   const __amdgpu_buffer_rsrc_t r_x = make_rsrc(x, plan.x_bytes);
   const __amdgpu_buffer_rsrc_t r_scale = make_rsrc(p.scale ? p.scale : p.cb, p.scale ? (unsigned)p.out_features * 2u : 0u);
   const __amdgpu_buffer_rsrc_t r_bias = make_rsrc(p.bias ? p.bias : p.cb, p.bias ? (unsigned)p.out_features * 2u : 0u);
-  // tokens past the batch read out of range, i.e. zeros
-  const unsigned xrow = n < batch ? (unsigned)((long long)n * ldx * 2) : 0x80000000u;
+  // Lanes of tokens past the batch read out of range, i.e. nothing -- except token 15, which loads the start of the
+  // first row so that every activation load keeps a lane in range (rule 2 above; with 16 tokens the rows before the
+  // last one do that).  What it feeds into the MFMA only reaches an output column that is never stored.
+  const bool token_on = n < batch;
+  const unsigned xrow = token_on ? (unsigned)((long long)n * ldx * 2) : n == 15 ? 0u : 0x80000000u;
 
   // passes in which this wave has vectors: a prefix 0 .. my_passes-1 (pass p: group p * MW + wv of 32 vectors)
   const int wave_groups = (p.P + 31) >> 5;
@@ -208,10 +220,20 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
   uint3v win[R], wres[RES_BITS == 12 ? R : 1];   // index words, PA passes deep
   uint2v wres8[RES_BITS == 8 ? R : 1];
   uint4v bxs[XS][VPL];                           // B operands (activations) of the current and of the next XD passes
+#pragma unroll
+  for (int i = 0; i < R; ++i) {
+    win[i] = uint3v{0u, 0u, 0u};
+    if (RES_BITS == 12) wres[i] = uint3v{0u, 0u, 0u};
+    if (RES_BITS == 8) wres8[i] = uint2v{0u, 0u};
+  }
+#pragma unroll
+  for (int i = 0; i < XS; ++i)
+#pragma unroll
+    for (int u = 0; u < VPL; ++u) bxs[i][u] = uint4v{0u, 0u, 0u, 0u};
 
   // The wave's passes form one sequence over all chunks; the loader runs PA passes ahead of the consumer.
   // Loader addresses: byte offset of the loader's pass inside a row, and of each block's row `n` in the streams.
-  int lp = 0;
+  int lp = 0, lc = 0;
   unsigned l_main = (unsigned)(wv * 4 + g) * 12u, l_res = (unsigned)(wv * 4 + g) * (RES_BITS == 8 ? 8u : 12u);
   unsigned lrow_main[NB], lrow_res[NB];
 #pragma unroll
@@ -220,21 +242,31 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
     if (++lp == eff_passes) {
       lp = 0;
       l_main = (unsigned)(wv * 4 + g) * 12u; l_res = (unsigned)(wv * 4 + g) * (RES_BITS == 8 ? 8u : 12u);
+      // past the last chunk the loader starts over: what it loads then is never used, but stays an ordinary load
+      const bool wrap = ++lc == n_chunks;
+      if (wrap) lc = 0;
 #pragma unroll
-      for (int b = 0; b < NB; ++b) { lrow_main[b] += (unsigned)(NB * 16) * st_main; lrow_res[b] += (unsigned)(NB * 16) * st_res; }
+      for (int b = 0; b < NB; ++b) {
+        lrow_main[b] = wrap ? (unsigned)(b * 16 + n) * st_main : lrow_main[b] + (unsigned)(NB * 16) * st_main;
+        lrow_res[b] = wrap ? (unsigned)(b * 16 + n) * st_res : lrow_res[b] + (unsigned)(NB * 16) * st_res;
+      }
     } else {
       l_main += (MW * 4) * 12u; l_res += (MW * 4) * (RES_BITS == 8 ? 8u : 12u);
     }
   };
-  auto load_slot = [&](int slot, int b) {       // rows past the end read zeros
-    async_load_b96(win[slot], r_main, lrow_main[b] + l_main);
-    if (RES_BITS == 12) async_load_b96(wres[slot], r_res, lrow_res[b] + l_res);
-    if (RES_BITS == 8) async_load_b64(wres8[slot], r_res, lrow_res[b] + l_res);
+  auto load_slot = [&](int slot, int b) {       // rows past the end of a ragged block read zeros
+    // a block past the last one (the last chunk may be short) is replaced by the workgroup's first block
+    const bool real = lc * NB + b < n_blocks;
+    const unsigned o_main = (real ? lrow_main[b] : (unsigned)n * st_main) + l_main;
+    const unsigned o_res = (real ? lrow_res[b] : (unsigned)n * st_res) + l_res;
+    async_load_b96(win[slot], r_main, o_main);
+    if (RES_BITS == 12) async_load_b96(wres[slot], r_res, o_res);
+    if (RES_BITS == 8) async_load_b64(wres8[slot], r_res, o_res);
   };
   // activations of one pass: eight overlapping 16-byte loads, one per vector; the fourth dword belongs to the
   // next vector and meets the zero padding of the codebook entries
   auto issue_x = [&](uint4v (&bx)[VPL], int pass) {
-    const unsigned off = xrow + ((unsigned)p.n_out + (unsigned)((pass * MW + wv) * 4 + g) * (VPL * 6u)) * 2u;
+    const unsigned off = token_on ? xrow + ((unsigned)p.n_out + (unsigned)((pass * MW + wv) * 4 + g) * (VPL * 6u)) * 2u : xrow;
     async_load_b128_at<0>(bx[0], r_xa, off);  async_load_b128_at<12>(bx[1], r_xa, off);
     async_load_b128_at<24>(bx[2], r_xa, off); async_load_b128_at<36>(bx[3], r_xa, off);
     async_load_b128_at<48>(bx[4], r_xa, off); async_load_b128_at<60>(bx[5], r_xa, off);
@@ -242,7 +274,7 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
   };
 
   {
-    TableStage<RES_BITS, MW * 64> tables;
+    TableStage<RES_BITS, MW * 64> tables{};
     tables.issue(p);
     if (my_passes > 0) {
 #pragma unroll
@@ -260,14 +292,22 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
     }
     tables.store(p, lds, plan.lds_out);
   }
+  // scale and bias of the workgroup's rows, one dword per row, for the reductions at the chunk ends
+  for (int r = (int)threadIdx.x; r < plan.rows_per_wg; r += MW * 64) {
+    const unsigned short sc = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r_scale, (unsigned)(row0 + r) * 2u, 0, 0);
+    const unsigned short bi = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r_bias, (unsigned)(row0 + r) * 2u, 0, 0);
+    *reinterpret_cast<unsigned *>(lds + plan.lds_sb + (unsigned)r * 4u) = (unsigned)sc | ((unsigned)bi << 16);
+  }
   VQ_STAMP(2);
   lds_barrier();
   VQ_STAMP(3);
+  // The counted waits assume the steady pattern of loads that only the loop below issues: everything issued so
+  // far has to be in first.
+  wait_vmem_at_most<0>();
 
   const uint4v ones = {0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0u};
   float4v acc[NB];
   float4v xs = {0.0f, 0.0f, 0.0f, 0.0f};
-  unsigned short ep_scale[4], ep_bias[4];          // raw halves; converted where they are used
   int buf = 0, c = 0, pass = 0;
   while (c < n_chunks) {
 #pragma unroll
@@ -279,13 +319,6 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
           // ---- chunk start
 #pragma unroll
           for (int b = 0; b < NB; ++b) acc[b] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
-          if (wv < nb_c) {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              ep_scale[r] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r_scale, (unsigned)(ep_o + r) * 2u, 0, 0);
-              ep_bias[r] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r_bias, (unsigned)(ep_o + r) * 2u, 0, 0);
-            }
-          }
           // outlier columns (v = 4): same scheme with 8-byte table entries; their loads are not run ahead
           for (int q = 0; q < my_out_passes; ++q) {
             const unsigned lane_group = (unsigned)((q * MW + wv) * 4 + g);
@@ -331,8 +364,8 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
 
         if (my_passes > 0) {
           // ---- one pass over this wave's 32 vectors of every block of the chunk
-          // Every pass issues the same number of loads, also past the end of the sequence (the loader's offsets are
-          // then out of range: such loads fetch nothing and return zeros), so the counted waits hold throughout.
+          // Every pass issues the same number of loads, also past the end of the sequence (the loader then starts
+          // over), so the counted waits hold throughout.
           uint4v (&bx)[VPL] = bxs[j % XS];
           wait_vmem_at_most<AFTER_X>();
 #pragma unroll
@@ -363,20 +396,17 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
             cm.w[0] = win[slot].x; cm.w[1] = win[slot].y; cm.w[2] = win[slot].z;
             if (RES_BITS == 12) { cr.w[0] = wres[slot].x; cr.w[1] = wres[slot].y; cr.w[2] = wres[slot].z; }
             if (RES_BITS == 8) { cr.w[0] = wres8[slot].x; cr.w[1] = wres8[slot].y; cr.w[2] = 0u; }
-            unsigned am[VPL], ar[VPL];                           // LDS addresses, before the slot is overwritten
+            // LDS addresses and the main gathers come before the slot is overwritten by its refill
+            unsigned ar[VPL];
+            uint4v e[VPL];
 #pragma unroll
             for (int u = 0; u < VPL; ++u) {
-              am[u] = field_addr<12, LY::MAIN_SH>(cm, u);
-              ar[u] = RES_BITS ? field_addr<RB, LY::RES_SH>(cr, u) + LY::RES_ADD : 0u;
-              settle(am[u]);
-              if (RES_BITS) settle(ar[u]);
+              if (RES_BITS) { ar[u] = field_addr<RB, LY::RES_SH>(cr, u) + LY::RES_ADD; settle(ar[u]); }
+              lds_gather16<LY::MAIN_OFF>(e[u], field_addr<12, LY::MAIN_SH>(cm, u));
             }
             load_slot(slot, b);                                  // refill with the pass PA ahead
             if (b < nb_c) {
               {
-                uint4v e[VPL];
-#pragma unroll
-                for (int u = 0; u < VPL; ++u) lds_gather16<LY::MAIN_OFF>(e[u], am[u]);
                 lds_gather_wait();
 #pragma unroll
                 for (int u = 0; u < VPL; ++u) settle(e[u]);
@@ -417,11 +447,13 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
 #pragma unroll
             for (int w = 0; w < MW; ++w) xsum += xs_part[w * 16 + n];
             const float sv[4] = {s.x, s.y, s.z, s.w};
+            const uint4v sb = *reinterpret_cast<const uint4v *>(lds + plan.lds_sb + (unsigned)((c * NB + wv) * 16 + 4 * g) * 4u);
+            const unsigned sbw[4] = {sb.x, sb.y, sb.z, sb.w};             // per row: scale | bias << 16, as staged at the start
             __half out[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-              const float sc = p.scale ? (float)__builtin_bit_cast(_Float16, ep_scale[r]) : 1.0f;
-              const float bi = p.bias ? (float)__builtin_bit_cast(_Float16, ep_bias[r]) : 0.0f;
+              const float sc = p.scale ? (float)__builtin_bit_cast(_Float16, (unsigned short)sbw[r]) : 1.0f;
+              const float bi = p.bias ? (float)__builtin_bit_cast(_Float16, (unsigned short)(sbw[r] >> 16)) : 0.0f;
               out[r] = __float2half_rn(__fmaf_rn(sc, sv[r], bi * xsum));
             }
             if (n < batch) {
@@ -490,20 +522,26 @@ extern "C" int vq_debug_read_profile_m(unsigned long long *dst, size_t count) {
 // Launch for batch 1..16.  The caller has checked gemv_fast_applicable().
 int launch_gemv_mfma(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
   MfmaPlan plan{};
+  if (p.in_features < 64) return VQ_ERR_UNSUPPORTED;      // idle lanes load the first 100 bytes of the first activation row
   const int rb = p.k_res ? p.bits_res : 0;
   unsigned off = rb == 0 ? Layout<0>::BYTES : rb == 8 ? Layout<8>::BYTES : Layout<12>::BYTES;
   plan.lds_out = off; off += p.Q ? 4096u * 8u : 0u;
   plan.lds_xs = off; off += MW * 16u * 4u;
-  plan.lds_part = off;
   const unsigned lds_cap = 160u * 1024u;
-  if (off + MW * 1024u > lds_cap) return VQ_ERR_UNSUPPORTED;
   const int blocks_total = (p.out_features + 15) / 16;
   const int cus = cu_count();
   const int blocks_per_wg = (blocks_total + cus - 1) / cus;
   plan.rows_per_wg = blocks_per_wg * 16;
   const unsigned grid = (unsigned)((blocks_total + blocks_per_wg - 1) / blocks_per_wg);
+  plan.lds_sb = off; off += (unsigned)plan.rows_per_wg * 4u;
+  plan.lds_part = off;
+  if (off + MW * 1024u > lds_cap) return VQ_ERR_UNSUPPORTED;
   const int fit = (int)((lds_cap - off) / (MW * 1024u));                 // 16-row partial blocks that fit
-  plan.nb = min(min(NBMAX, blocks_per_wg), fit);
+  // Blocks per chunk: as many as the kernel's 256 registers allow -- four, three with an 8-bit residual stream in the
+  // prefetch ring, two with a 12-bit one.  More would spill, which these kernels must not (see the build script).
+  static const int nb_cap = [] { const char *e = getenv("VQ_MFMA_NB"); return e ? atoi(e) : NBMAX; }();
+  plan.nb = min(min(min(rb == 12 ? 2 : rb == 8 ? 3 : NBMAX, nb_cap), blocks_per_wg), fit);
+  if (plan.nb < 1) return VQ_ERR_UNSUPPORTED;
   plan.part_bufs = (fit >= 2 * plan.nb && blocks_per_wg > plan.nb) ? 2 : 1;
   off += (unsigned)(plan.part_bufs * plan.nb) * (MW * 1024u);
   const long long max_stride = max(p.stride, max(p.stride_res, p.stride_out));
@@ -515,8 +553,8 @@ int launch_gemv_mfma(const Params &p, const __half *x, long long ldx, int batch,
 #define VQ_CASE(RBITS, NBLK) \
   if (rb == RBITS && plan.nb == NBLK) return launch_one<RBITS, MW, NBLK>(p, plan, off, grid, x, ldx, batch, y, ldy, s);
   VQ_CASE(0, 1) VQ_CASE(0, 2) VQ_CASE(0, 3) VQ_CASE(0, 4)
-  VQ_CASE(8, 1) VQ_CASE(8, 2) VQ_CASE(8, 3) VQ_CASE(8, 4)
-  VQ_CASE(12, 1) VQ_CASE(12, 2) VQ_CASE(12, 3) VQ_CASE(12, 4)
+  VQ_CASE(8, 1) VQ_CASE(8, 2) VQ_CASE(8, 3)
+  VQ_CASE(12, 1) VQ_CASE(12, 2)
 #undef VQ_CASE
   return VQ_ERR_UNSUPPORTED;
 }
