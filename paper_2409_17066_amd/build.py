@@ -2,6 +2,12 @@
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
+
+try:
+    from . import check_async
+except ImportError:                      # run as a script
+    import check_async
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
@@ -18,6 +24,9 @@ NO_SPILL = {"vq_gemv_mfma.hip", "vq_gemm_fused.hip"}
 # five address registers at kernel entry, before its first asynchronous load, and reloads them in the epilogue.
 SPILLS_ALLOWED = {"gemm_v8_kernelILi512E": 5}
 REMARKS = ["-Rpass-analysis=kernel-resource-usage"]
+# The same files, and the dot-product GEMV with its hand-issued LDS reads, get their device assembly audited for
+# instructions that touch a register while an inline-assembly load into it is pending (check_async.py).
+AUDITED = ["vq_gemv_mfma.hip", "vq_gemm_fused.hip", "vq_gemv_fast.hip"]
 
 
 def check_no_spills(src: str, remarks: str) -> None:
@@ -54,6 +63,14 @@ def build(verbose: bool = False) -> str:
             out = "\n".join(l for l in out.splitlines() if "remark:" not in l)
         if verbose and out.strip():
             print(out)
+    def audit(src):
+        return src, check_async.audit(check_async.device_asm(hipcc, FLAGS, os.path.join(CSRC, src)))
+    with ThreadPoolExecutor(max_workers=len(AUDITED)) as pool:
+        for src, findings in pool.map(audit, AUDITED):
+            if findings:
+                name, label, text, regs = findings[0]
+                raise RuntimeError("%s: %d instruction(s) touch a register with an asynchronous load pending, e.g. in %s %s: %s"
+                                   % (src, len(findings), name, label, text))
     # no rpath: inside a PyTorch process the already-loaded HIP runtime (same soname) is the one used
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     subprocess.check_call(cmd)
