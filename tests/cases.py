@@ -22,6 +22,13 @@ SMALL = {
     "v6_many_rows": dict(out_features=9000, in_features=390, v=6, k=4096, k_res=256),    # several row chunks per workgroup
     "v6_wide_outlier": dict(out_features=70, in_features=2600, v=6, k=4096, n_outlier_cols=1200, v_out=4, k_out=4096),
     "padded_stride": dict(out_features=50, in_features=300, v=6, k=4096, k_res=256, extra_stride=2),
+    # the matrix-core GEMV: more 16-row blocks per workgroup than one chunk holds (4, 3 or 2 by residual kind), a ragged
+    # last block, and more column passes per wave than its prefetch ring holds
+    "v6_chunks": dict(out_features=20501, in_features=198, v=6, k=4096),
+    "v6_chunks_res8_outlier": dict(out_features=16421, in_features=210, v=6, k=4096, k_res=256, n_outlier_cols=12, v_out=4, k_out=4096),
+    "v6_chunks_res12": dict(out_features=12303, in_features=198, v=6, k=4096, k_res=4096),
+    "v6_passes": dict(out_features=40, in_features=7000, v=6, k=4096, k_res=4096),
+    "v6_passes_res8": dict(out_features=37, in_features=9100, v=6, k=4096, k_res=256),
 }
 
 

@@ -65,17 +65,24 @@ def test_gemm_small(gpu_lib, name, tokens):
     _check_matmul(Y, oracle.gemm(L, x), "%s tokens %d" % (name, tokens))
 
 
-def test_gemv_strided_buffers_and_untouched_padding(gpu_lib):
+@pytest.mark.parametrize("kernel", ["auto", "m", "d"])
+@pytest.mark.parametrize("batch", [1, 4, 5, 16])
+@pytest.mark.parametrize("name,pad_x,pad_y", [("v6_res256_outlier", 10, 6), ("v6_k4096_res4096", 2, 1), ("v6_passes", 6, 3)])
+def test_gemv_strided_buffers_and_untouched_padding(gpu_lib, monkeypatch, name, pad_x, pad_y, batch, kernel):
+    """Row strides larger than the rows, NaN in the caller's padding (it must never reach a sum), sentinel values
+    in the output padding (they must survive); odd output strides take the kernels' narrow store paths."""
     import torch
-    L = small_layer("v6_res256_outlier")
+    if kernel != "auto":
+        monkeypatch.setenv("VQ_GEMV_KERNEL", kernel)
+    L = small_layer(name)
     dl = gpu_lib.DeviceLayer(L)
-    x = s.make_activations(300, L, 4)
-    xb = torch.full((4, L.in_features + 10), float("nan"), dtype=torch.float16, device="cuda")
+    x = s.make_activations(300, L, batch)
+    xb = torch.full((batch, L.in_features + pad_x), float("nan"), dtype=torch.float16, device="cuda")
     xb[:, : L.in_features] = torch.from_numpy(x).cuda()
-    yb = torch.full((4, L.out_features + 6), 7.0, dtype=torch.float16, device="cuda")
+    yb = torch.full((batch, L.out_features + pad_y), 7.0, dtype=torch.float16, device="cuda")
     gpu_lib.gemv(dl, xb, out=yb)
     torch.cuda.synchronize()
-    _check_matmul(yb[:, : L.out_features], oracle.gemv(L, x), "strided")
+    _check_matmul(yb[:, : L.out_features], oracle.gemv(L, x), "strided %s batch %d" % (name, batch))
     assert (yb[:, L.out_features:] == 7.0).all()
 
 
@@ -94,11 +101,12 @@ def test_unit_activation_reads_back_a_column(gpu_lib):
             assert np.allclose(y[t], W[:, c], rtol=2e-3, atol=1e-7)
 
 
-def test_runs_are_deterministic(gpu_lib):
+@pytest.mark.parametrize("batch", [1, 4, 16])
+def test_runs_are_deterministic(gpu_lib, batch):
     import torch
     L = small_layer("v6_k4096_res4096")
     dl = gpu_lib.DeviceLayer(L)
-    x = torch.from_numpy(s.make_activations(300, L, 4)).cuda()
+    x = torch.from_numpy(s.make_activations(300, L, batch)).cuda()
     a = gpu_lib.gemv(dl, x).clone()
     for _ in range(3):
         assert torch.equal(gpu_lib.gemv(dl, x), a)
