@@ -34,6 +34,8 @@ struct DqPlan {
   unsigned lds_res, lds_out, lds_strip;   // byte offsets in dynamic LDS (main table at 0)
   int main_chunks, out_chunks;            // 64-vector chunks per row
   long long total_chunks;
+  long long step;                         // chunks between consecutive chunks of one wave = workgroups x waves
+  int step_rows, step_chunks;             // step = step_rows * chunks per row + step_chunks
   int wide;                               // 1: every row start is 16-byte aligned and ldw % 8 == 0
 };
 
@@ -71,19 +73,54 @@ __global__ __launch_bounds__(NW * 64) void dequant_v6_kernel(Params p, DqPlan pl
 
   unsigned char *strip = lds + plan.lds_strip + wv * 768;     // this wave's 64 x 12 bytes
   const int chunks_per_row = plan.main_chunks + plan.out_chunks;
-  for (long long id = (long long)blockIdx.x * NW + wv; id < plan.total_chunks; id += (long long)gridDim.x * NW) {
-    const int o = (int)(id / chunks_per_row);
-    const int ch = (int)(id - (long long)o * chunks_per_row);
-    const float s = p.scale ? __half2float(p.scale[o]) : 1.0f;
-    const float b = p.bias ? __half2float(p.bias[o]) : 0.0f;
-    __half *wrow = W + (long long)o * ldw;
-    int c_first, n_cols, piece;            // first column of the chunk, its valid columns, bytes per vector
+
+  // One chunk = 64 vectors of one row.  What a chunk needs from memory (its index words, the row's scale and bias)
+  // is loaded one chunk ahead: with one round trip per chunk exposed, the kernel ran at the memory latency.
+  struct Fetch { unsigned m0, m1, r0, r1, sc, bi; };
+  auto fetch = [&](int o, int ch, Fetch &f) {
+    f.sc = p.scale ? (unsigned)__half_as_ushort(p.scale[o]) : 0x3C00u;
+    f.bi = p.bias ? (unsigned)__half_as_ushort(p.bias[o]) : 0u;
+    f.m0 = f.m1 = f.r0 = f.r1 = 0u;
     if (ch < plan.out_chunks) {
       const int q = ch * 64 + lane;
-      c_first = ch * 256; n_cols = min(256, p.n_out - c_first); piece = 8;
+      if (q < p.Q) {
+        const unsigned *w = reinterpret_cast<const unsigned *>(p.idx_out + (long long)o * p.stride_out) + ((q * 12) >> 5);
+        f.m0 = w[0]; f.m1 = ((q * 12) & 31) > 20 ? w[1] : 0u;
+      }
+    } else {
+      const int pp = (ch - plan.out_chunks) * 64 + lane;
+      if (pp < p.P) {
+        const unsigned *w = reinterpret_cast<const unsigned *>(p.idx + (long long)o * p.stride) + ((pp * 12) >> 5);
+        f.m0 = w[0]; f.m1 = ((pp * 12) & 31) > 20 ? w[1] : 0u;
+        if (RES_BITS) {
+          constexpr int RB = RES_BITS ? RES_BITS : 8;
+          const unsigned *r = reinterpret_cast<const unsigned *>(p.idx_res + (long long)o * p.stride_res) + ((pp * RB) >> 5);
+          f.r0 = r[0]; f.r1 = ((pp * RB) & 31) > 32 - RB ? r[1] : 0u;
+        }
+      }
+    }
+  };
+  auto field12 = [](unsigned w0, unsigned w1, int bit) { return __builtin_amdgcn_alignbit(w1, w0, (unsigned)bit & 31u) & 0xFFFu; };
+
+  // chunk ids of this wave: first, first + step, ...; (row, chunk in row) advance without a division
+  const long long first = (long long)blockIdx.x * NW + wv;
+  int o = (int)(first / chunks_per_row), ch = (int)(first - (long long)o * chunks_per_row);
+  Fetch cur, nxt;
+  if (first < plan.total_chunks) fetch(o, ch, cur);
+  for (long long id = first; id < plan.total_chunks; id += plan.step) {
+    int o2 = o + plan.step_rows, ch2 = ch + plan.step_chunks;
+    if (ch2 >= chunks_per_row) { ch2 -= chunks_per_row; ++o2; }
+    if (id + plan.step < plan.total_chunks) fetch(o2, ch2, nxt);
+    const float s = __half2float(__ushort_as_half((unsigned short)cur.sc));
+    const float b = __half2float(__ushort_as_half((unsigned short)cur.bi));
+    __half *wrow = W + (long long)o * ldw;
+    int c_first, n_cols;                   // first column of the chunk, its valid columns
+    if (ch < plan.out_chunks) {
+      const int q = ch * 64 + lane;
+      c_first = ch * 256; n_cols = min(256, p.n_out - c_first);
       uint2v w = {0u, 0u};
       if (q < p.Q) {
-        const unsigned i = load_index(p.idx_out + (long long)o * p.stride_out, q, 12);
+        const unsigned i = field12(cur.m0, cur.m1, q * 12);
         const uint2v e = *reinterpret_cast<const uint2v *>(lds + plan.lds_out + i * 8);
         w.x = restore_pair(e.x, 0u, false, s, b);
         w.y = restore_pair(e.y, 0u, false, s, b);
@@ -91,14 +128,15 @@ __global__ __launch_bounds__(NW * 64) void dequant_v6_kernel(Params p, DqPlan pl
       *reinterpret_cast<uint2v *>(strip + lane * 8) = w;
     } else {
       const int pp = (ch - plan.out_chunks) * 64 + lane;
-      c_first = p.n_out + (ch - plan.out_chunks) * 384; n_cols = min(384, p.in_features - c_first); piece = 12;
+      c_first = p.n_out + (ch - plan.out_chunks) * 384; n_cols = min(384, p.in_features - c_first);
       unsigned w0 = 0u, w1 = 0u, w2 = 0u;
       if (pp < p.P) {
-        const unsigned i = load_index(p.idx + (long long)o * p.stride, pp, 12);
+        const unsigned i = field12(cur.m0, cur.m1, pp * 12);
         const uint4v e = *reinterpret_cast<const uint4v *>(lds + i * 16);
         uint4v f = {0u, 0u, 0u, 0u};
         if (RES_BITS) {
-          const unsigned r = load_index(p.idx_res + (long long)o * p.stride_res, pp, RES_BITS ? RES_BITS : 8);
+          constexpr int RB = RES_BITS ? RES_BITS : 8;
+          const unsigned r = __builtin_amdgcn_alignbit(cur.r1, cur.r0, (unsigned)(pp * RB) & 31u) & ((1u << RB) - 1u);
           f = *reinterpret_cast<const uint4v *>(lds + plan.lds_res + r * 16);
         }
         w0 = restore_pair(e.x, f.x, RES_BITS != 0, s, b);
@@ -108,7 +146,6 @@ __global__ __launch_bounds__(NW * 64) void dequant_v6_kernel(Params p, DqPlan pl
       unsigned *dst = reinterpret_cast<unsigned *>(strip + lane * 12);
       dst[0] = w0; dst[1] = w1; dst[2] = w2;
     }
-    (void)piece;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -125,6 +162,7 @@ __global__ __launch_bounds__(NW * 64) void dequant_v6_kernel(Params p, DqPlan pl
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
+    o = o2; ch = ch2; cur = nxt;
   }
 }
 
@@ -172,7 +210,7 @@ int cu_count() {
 }
 
 template <int RES_BITS>
-int launch_v6(const Params &p, const DqPlan &plan, unsigned lds_bytes, __half *W, long long ldw, hipStream_t s) {
+int launch_v6(const Params &p, DqPlan plan, unsigned lds_bytes, __half *W, long long ldw, hipStream_t s) {
   static bool configured = false;
   auto kernel = dequant_v6_kernel<RES_BITS>;
   if (!configured) {
@@ -180,8 +218,14 @@ int launch_v6(const Params &p, const DqPlan &plan, unsigned lds_bytes, __half *W
       return VQ_ERR_HIP;
     configured = true;
   }
+  // the kernel needs few registers, so as many workgroups per compute unit as their LDS allows (at most two: 32 waves)
   const long long want = (plan.total_chunks + NW - 1) / NW;
-  const unsigned grid = (unsigned)(want < cu_count() ? want : cu_count());
+  const long long slots = (long long)cu_count() * (2u * lds_bytes <= 160u * 1024u ? 2 : 1);
+  const unsigned grid = (unsigned)(want < slots ? want : slots);
+  const int cpr = plan.main_chunks + plan.out_chunks;
+  plan.step = (long long)grid * NW;
+  plan.step_rows = (int)(plan.step / cpr);
+  plan.step_chunks = (int)(plan.step % cpr);
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(NW * 64), lds_bytes, s, p, plan, W, ldw);
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
