@@ -137,5 +137,113 @@ template <int RES_BITS> struct Layout {
 };
 
 
+// Barrier for LDS traffic only: __syncthreads() would also wait for the index and activation loads that are
+// in flight for the next pass.
+static __device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+// The index words and activations that run ahead of the computation are loaded from inline assembly and
+// waited for with counted s_waitcnt: the compiler's own wait insertion, across this kernel's control flow,
+// falls back to "wait for everything" at the first use of a loaded register, which would serialise the
+// prefetch ring.  Vector memory loads return in issue order, so "at most N outstanding" is exact when N is
+// the number of loads known to have been issued after the one needed (more loads after it only make the
+// wait stricter).  Descriptors are built by hand so that they can be passed as scalar operands: raw
+// buffers with per-dword range checking, out-of-range dwords read as zero.
+//
+// Two rules keep this sound.  (1) Every asynchronous destination is a read-write ("+v") operand, refilled in
+// straight-line code: the new value is tied to the register of the old one, so a slot keeps its register
+// through every branch and loop edge.  With write-only operands, or a refill inside a branch, the compiler
+// merges old and new values with register copies at the joins -- copies of a register whose load has not
+// landed yet.  The build also refuses any spill in these kernels, for the same reason.  (2) Every load
+// instruction keeps at least one lane in range.  A load whose lanes are all out of range fetches nothing and
+// has been seen to complete ahead of older loads, which breaks the counting.
+static __device__ __forceinline__ uint4v scalar_rsrc(const void *base, unsigned bytes) {
+  const unsigned long long a = reinterpret_cast<unsigned long long>(base);
+  uint4v r;
+  r.x = (unsigned)a; r.y = (unsigned)(a >> 32) & 0xFFFFu; r.z = bytes; r.w = 0x00020000u;
+  return r;
+}
+static __device__ __forceinline__ void async_load_b64(uint2v &dst, uint4v rsrc, unsigned off) {
+  asm volatile("buffer_load_dwordx2 %0, %1, %2, 0 offen" : "+v"(dst) : "v"(off), "s"(rsrc) : "memory");
+}
+static __device__ __forceinline__ void async_load_b96(uint3v &dst, uint4v rsrc, unsigned off) {
+  asm volatile("buffer_load_dwordx3 %0, %1, %2, 0 offen" : "+v"(dst) : "v"(off), "s"(rsrc) : "memory");
+}
+template <int N> static __device__ __forceinline__ void wait_vmem_at_most() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+template <int OFF>
+static __device__ __forceinline__ void async_load_b128_at(uint4v &dst, uint4v rsrc, unsigned off) {
+  asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen offset:%3" : "+v"(dst) : "v"(off), "s"(rsrc), "n"(OFF) : "memory");
+}
+
+// Codebooks into LDS with entries padded to 16 bytes (v = 6) or as they are (v = 4, 8 bytes), by T threads, in
+// two steps so that the index loads of the first passes can be issued in between: the table loads (hits in
+// L2 for all but the first workgroups) then return first and need not wait behind loads from HBM.
+// Range-checked loads return zeros past the k entries a table really has.
+template <int RES_BITS, int T> struct TableStage {
+  static constexpr int GROUPS = 1024 / T;       // groups of 4 entries (48 bytes) per thread and table of 4096
+  uint4v m[GROUPS][3], r[RES_BITS == 12 ? GROUPS : 1][3], o[2048 / T];
+
+  __device__ __forceinline__ void issue(const Params &p) {
+    const uint4v rm = scalar_rsrc(p.cb, (unsigned)p.k * 12u);
+#pragma unroll
+    for (int gi = 0; gi < GROUPS; ++gi) {
+      const unsigned off = (threadIdx.x + gi * T) * 48u;
+      async_load_b128_at<0>(m[gi][0], rm, off); async_load_b128_at<16>(m[gi][1], rm, off); async_load_b128_at<32>(m[gi][2], rm, off);
+    }
+    if (RES_BITS == 12) {
+      const uint4v rr = scalar_rsrc(p.cb_res, (unsigned)p.k_res * 12u);
+#pragma unroll
+      for (int gi = 0; gi < GROUPS; ++gi) {
+        const unsigned off = (threadIdx.x + gi * T) * 48u;
+        async_load_b128_at<0>(r[gi][0], rr, off); async_load_b128_at<16>(r[gi][1], rr, off); async_load_b128_at<32>(r[gi][2], rr, off);
+      }
+    }
+    if (RES_BITS == 8) {                         // 256 entries: every wave loads them, the first one stores them
+      const uint4v rr = scalar_rsrc(p.cb_res, (unsigned)p.k_res * 12u);
+      const unsigned off = (threadIdx.x & 63u) * 48u;
+      async_load_b128_at<0>(r[0][0], rr, off); async_load_b128_at<16>(r[0][1], rr, off); async_load_b128_at<32>(r[0][2], rr, off);
+    }
+    if (p.Q) {                                   // 4096 entries of 8 bytes
+      const uint4v ro = scalar_rsrc(p.cb_out, (unsigned)p.k_out * 8u);
+#pragma unroll
+      for (int i = 0; i < 2048 / T; ++i) async_load_b128_at<0>(o[i], ro, (threadIdx.x + i * T) * 16u);
+    }
+  }
+
+  static __device__ __forceinline__ void put4(unsigned char *base, unsigned first_entry, uint4v (&v)[3]) {
+    settle(v[0]); settle(v[1]); settle(v[2]);
+    const unsigned d[12] = {v[0].x, v[0].y, v[0].z, v[0].w, v[1].x, v[1].y, v[1].z, v[1].w, v[2].x, v[2].y, v[2].z, v[2].w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint4v e; e.x = d[3 * i]; e.y = d[3 * i + 1]; e.z = d[3 * i + 2]; e.w = 0u;
+      *reinterpret_cast<uint4v *>(base + (first_entry + i) * 16u) = e;
+    }
+  }
+
+  // after a wait that covers the loads of issue()
+  __device__ __forceinline__ void store(const Params &p, unsigned char *lds, unsigned lds_out) {
+    typedef Layout<RES_BITS> L;
+#pragma unroll
+    for (int gi = 0; gi < GROUPS; ++gi) put4(lds + L::MAIN_OFF, (threadIdx.x + gi * T) * 4u, m[gi]);
+    if (RES_BITS == 12) {
+#pragma unroll
+      for (int gi = 0; gi < GROUPS; ++gi) put4(lds + L::RES_ADD, (threadIdx.x + gi * T) * 4u, r[gi]);
+    }
+    if (RES_BITS == 8 && threadIdx.x < 64) put4(lds, threadIdx.x * 4u, r[0]);
+    if (p.Q) {
+#pragma unroll
+      for (int i = 0; i < 2048 / T; ++i) {
+        settle(o[i]);
+        *reinterpret_cast<uint4v *>(lds + lds_out + (threadIdx.x + i * T) * 16u) = o[i];
+      }
+    }
+  }
+};
+
+
 }  // namespace v6
 }  // namespace vq
