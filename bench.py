@@ -227,20 +227,24 @@ def detail(vq, s, np, torch, use_graph, skip):
     for tokens in s.CONFIGS[4]["rows"]:
         X = torch.from_numpy(s.make_activations(4, L4, tokens)).cuda()
         Y = torch.empty((tokens, L4.out_features), dtype=torch.float16, device="cuda")
-        need = vq.vq_gemm_workspace_bytes(dl.desc, tokens)
-        ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
-
-        def launch(i):
-            rc = vq.vq_gemm(dl.desc, X.data_ptr(), X.stride(0), tokens, Y.data_ptr(), Y.stride(0), ws.data_ptr(), need,
-                            torch.cuda.current_stream().cuda_stream)
-            if rc != 0:
-                raise vq.VQError(rc, "vq_gemm")
-        n = 10
-        wall, ev = timed(launch, n, 2, use_graph=False)
-        sec = ev / n
         flops = 2.0 * tokens * L4.out_features * L4.in_features
-        out.append({"op": "vq_gemm", "cfg": 4, "tokens": tokens, "us": round(sec * 1e6, 1),
-                    "TFLOP/s": round(flops / sec / 1e12, 1), "frac_mfma_peak": round(flops / sec / 1e12 / MFMA_FP16_PEAK_TFLOPS, 4)})
+        # two routes: weights restored on the fly (no workspace), and restored once into a workspace first
+        for route, need in (("on the fly", vq.vq_gemm_workspace_bytes(dl.desc, tokens)),
+                            ("restore, then multiply", vq.vq_gemm_fast_workspace_bytes(dl.desc, tokens))):
+            ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+
+            def launch(i):
+                rc = vq.vq_gemm(dl.desc, X.data_ptr(), X.stride(0), tokens, Y.data_ptr(), Y.stride(0), ws.data_ptr(), need,
+                                torch.cuda.current_stream().cuda_stream)
+                if rc != 0:
+                    raise vq.VQError(rc, "vq_gemm")
+            n = 10
+            wall, ev = timed(launch, n, 2, use_graph=False)
+            sec = ev / n
+            out.append({"op": "vq_gemm", "cfg": 4, "tokens": tokens, "route": route, "workspace_bytes": int(need),
+                        "us": round(sec * 1e6, 1), "TFLOP/s": round(flops / sec / 1e12, 1),
+                        "frac_mfma_peak": round(flops / sec / 1e12 / MFMA_FP16_PEAK_TFLOPS, 4)})
+            del ws
     W = torch.empty((L4.out_features, L4.in_features), dtype=torch.float16, device="cuda")
 
     def launch_dq(i):

@@ -89,14 +89,21 @@ int vq_dequant(const vq_layer_desc *desc, void *W, int64_t ldw, void *hip_stream
 int vq_gemv(const vq_layer_desc *desc, const void *x, int64_t ldx, int32_t batch,
             void *y, int64_t ldy, void *hip_stream);
 
-/* Prompt-phase product for many tokens: Y[t][o] = sum_c W[o][c] * X[t][c] with the restored weights
- * fed to FP16 matrix cores through on-chip tiles (W is never written to memory), binary32
- * accumulation, fp16 result.  X: fp16 [tokens][ldx], 16-byte aligned, ldx % 8 == 0; Y: fp16
- * [tokens][ldy], ldy >= out_features; tokens >= 1.  `workspace` must hold
- * vq_gemm_workspace_bytes(desc, tokens) bytes (16-byte aligned; may be NULL when that is 0).       */
+/* Prompt-phase product for many tokens: Y[t][o] = sum_c W[o][c] * X[t][c] on the FP16 matrix cores,
+ * binary32 accumulation, fp16 result (the paper's prompt phase, its section on inference throughput:
+ * restore the weights, then multiply).  X: fp16 [tokens][ldx], 16-byte aligned, ldx % 8 == 0; Y: fp16
+ * [tokens][ldy], ldy >= out_features; tokens >= 1.
+ * Workspace (device memory, 16-byte aligned, owned by the caller, contents undefined afterwards):
+ *  - it must hold at least vq_gemm_workspace_bytes(desc, tokens) bytes (currently 0: NULL is fine),
+ *    else VQ_ERR_WORKSPACE;
+ *  - if it holds vq_gemm_fast_workspace_bytes(desc, tokens) bytes (non-zero when in_features is a
+ *    multiple of 256), the call restores W into it once (as vq_dequant does) and multiplies from
+ *    there, which is the faster route on this GPU; with less, the restored weights go straight from
+ *    on-chip tiles into the matrix cores and W is never written to memory.                          */
 int vq_gemm(const vq_layer_desc *desc, const void *X, int64_t ldx, int32_t tokens,
             void *Y, int64_t ldy, void *workspace, size_t workspace_bytes, void *hip_stream);
 size_t vq_gemm_workspace_bytes(const vq_layer_desc *desc, int32_t tokens);
+size_t vq_gemm_fast_workspace_bytes(const vq_layer_desc *desc, int32_t tokens);
 
 /* Text for a status code (static storage).  */
 const char *vq_status_string(int status);

@@ -56,6 +56,8 @@ def load():
                           ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     L.vq_gemm_workspace_bytes.argtypes = [P, ctypes.c_int32]
     L.vq_gemm_workspace_bytes.restype = ctypes.c_size_t
+    L.vq_gemm_fast_workspace_bytes.argtypes = [P, ctypes.c_int32]
+    L.vq_gemm_fast_workspace_bytes.restype = ctypes.c_size_t
     L.vq_status_string.argtypes = [ctypes.c_int]
     L.vq_status_string.restype = ctypes.c_char_p
     L.vq_version.restype = ctypes.c_int
@@ -65,7 +67,8 @@ def load():
     return L
 
 
-EXPORTED = ["vq_validate", "vq_dequant", "vq_gemv", "vq_gemm", "vq_gemm_workspace_bytes", "vq_status_string", "vq_version"]
+EXPORTED = ["vq_validate", "vq_dequant", "vq_gemv", "vq_gemm", "vq_gemm_workspace_bytes", "vq_gemm_fast_workspace_bytes",
+            "vq_status_string", "vq_version"]
 
 
 # ---- the C entry points, same names, raw pointers (ints) and sizes ---------------------------------------
@@ -88,6 +91,10 @@ def vq_gemm(desc, X_ptr, ldx, tokens, Y_ptr, ldy, workspace_ptr=None, workspace_
 
 def vq_gemm_workspace_bytes(desc, tokens):
     return load().vq_gemm_workspace_bytes(ctypes.byref(desc), tokens)
+
+
+def vq_gemm_fast_workspace_bytes(desc, tokens):
+    return load().vq_gemm_fast_workspace_bytes(ctypes.byref(desc), tokens)
 
 
 def vq_status_string(status):
@@ -153,10 +160,15 @@ def gemv(dl: DeviceLayer, x, out=None):
 
 
 def gemm(dl: DeviceLayer, X, out=None, workspace=None):
-    """X: fp16 [tokens][>=in] device tensor -> fp16 [tokens][out]."""
+    """X: fp16 [tokens][>=in] device tensor -> fp16 [tokens][out].  workspace: a uint8 device tensor, or "fast" to
+    allocate the one vq_gemm_fast_workspace_bytes asks for (the restore-then-multiply route), or None."""
     import torch
     assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.stride(1) == 1
     Y = out if out is not None else torch.empty((X.shape[0], dl.layer.out_features), dtype=torch.float16, device="cuda")
+    if isinstance(workspace, str):
+        assert workspace == "fast"
+        fast = vq_gemm_fast_workspace_bytes(dl.desc, X.shape[0])
+        workspace = torch.empty(fast, dtype=torch.uint8, device="cuda") if fast else None
     need = vq_gemm_workspace_bytes(dl.desc, X.shape[0])
     if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
         workspace = torch.empty(need, dtype=torch.uint8, device="cuda")

@@ -95,6 +95,12 @@ extern "C" size_t vq_gemm_workspace_bytes(const vq_layer_desc *desc, int32_t tok
   return vq::gemm_workspace_bytes(p, tokens);
 }
 
+extern "C" size_t vq_gemm_fast_workspace_bytes(const vq_layer_desc *desc, int32_t tokens) {
+  vq::Params p;
+  if (vq::make_params(desc, &p) != VQ_OK || tokens < 1) return 0;
+  return vq::gemm_fast_workspace_bytes(p, tokens);
+}
+
 extern "C" int vq_gemm(const vq_layer_desc *desc, const void *X, int64_t ldx, int32_t tokens,
                        void *Y, int64_t ldy, void *workspace, size_t workspace_bytes, void *hip_stream) {
   vq::Params p;
@@ -105,7 +111,7 @@ extern "C" int vq_gemm(const vq_layer_desc *desc, const void *X, int64_t ldx, in
   if (!aligned(X, 16) || (ldx & 7) || !aligned(Y, 2)) return VQ_ERR_ALIGNMENT;
   const size_t need = vq::gemm_workspace_bytes(p, tokens);
   if (need && (!workspace || workspace_bytes < need)) return VQ_ERR_WORKSPACE;
-  if (need && !aligned(workspace, 16)) return VQ_ERR_ALIGNMENT;
+  if (workspace && workspace_bytes && !aligned(workspace, 16)) return VQ_ERR_ALIGNMENT;
   return vq::launch_gemm(p, static_cast<const __half *>(X), ldx, tokens, static_cast<__half *>(Y), ldy,
                          workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }

@@ -31,6 +31,7 @@ int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __ha
 int launch_gemm(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy,
                 void *workspace, size_t workspace_bytes, hipStream_t s);
 size_t gemm_workspace_bytes(const Params &p, int tokens);
+size_t gemm_fast_workspace_bytes(const Params &p, int tokens);
 
 #ifdef __HIPCC__
 // Index p of a row's little-endian bitstream (bits <= 16).  `row` is 4-byte aligned and the row's

@@ -130,14 +130,42 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(Params p, const __half *
 
 size_t gemm_workspace_bytes(const Params &, int) { return 0; }
 
-bool gemm_fused_applicable(const Params &p);
-int launch_gemm_fused(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy, hipStream_t s);
+// Bytes of the FP16 weight matrix [out][in] that the two-step route below writes; 0 when that route does not apply.
+size_t gemm_fast_workspace_bytes(const Params &p, int) {
+  if (p.in_features % 256 != 0) return 0;                    // the dense kernel walks the columns in groups of 8 x 32
+  return (size_t)p.out_features * (size_t)p.in_features * sizeof(__half);
+}
 
+bool gemm_fused_applicable(const Params &p);
+int launch_gemm_fused(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy, const __half *Wd,
+                      long long ldw, hipStream_t s);
+
+// Routes, in this order:
+//  1. a workspace of gemm_fast_workspace_bytes() is there: vq_dequant into it, then the MFMA kernel with plain
+//     tile copies as its producers.  This is the paper's prompt-phase scheme (restore to FP16, then a dense
+//     product); on gfx950 it beats restoring on the fly because every 16-byte centroid gather drags a 128-byte
+//     line out of L2 and a tile is gathered again for every token tile, while the restored matrix is read in
+//     full lines.  Any layer the library can dequantize qualifies (in_features a multiple of 256).
+//  2. v = 8 / 16-bit indices: restore on the fly inside the MFMA kernel (no workspace, W never in memory).
+//  3. the generic tile kernel.
+// VQ_GEMM_KERNEL=g forces 3, =f skips 1, =w takes 1 whenever a workspace is there (measurement and tests).
 int launch_gemm(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy,
-                void *, size_t, hipStream_t s) {
-  static const bool force_generic = [] { const char *e = getenv("VQ_GEMM_KERNEL"); return e && e[0] == 'g'; }();
-  if (!force_generic && gemm_fused_applicable(p)) {
-    const int rc = launch_gemm_fused(p, X, ldx, tokens, Y, ldy, s);
+                void *workspace, size_t workspace_bytes, hipStream_t s) {
+  const char *env = getenv("VQ_GEMM_KERNEL");          // read at every call so that one process can test every route
+  const char forced = env ? env[0] : '\0';
+  const size_t fast = gemm_fast_workspace_bytes(p, tokens);
+  // measured on the 8192 x 8192 v=8 layer: up to 512 tokens restoring on the fly is still ahead (167 vs 184 us), from
+  // 1024 tokens on the restored matrix wins (215 vs 267 us, 365 vs 407 us at 2048); VQ_GEMM_KERNEL=w takes it always
+  const bool worth_it = forced == 'w' || !gemm_fused_applicable(p) || tokens > 512;
+  if (forced != 'g' && forced != 'f' && worth_it && fast && workspace && workspace_bytes >= fast &&
+      (reinterpret_cast<uintptr_t>(workspace) & 15) == 0) {
+    __half *Wd = static_cast<__half *>(workspace);
+    int rc = launch_dequant(p, Wd, p.in_features, s);
+    if (rc == VQ_OK) rc = launch_gemm_fused(p, X, ldx, tokens, Y, ldy, Wd, p.in_features, s);
+    if (rc != VQ_ERR_UNSUPPORTED) return rc;
+  }
+  if (forced != 'g' && gemm_fused_applicable(p)) {
+    const int rc = launch_gemm_fused(p, X, ldx, tokens, Y, ldy, nullptr, 0, s);
     if (rc != VQ_ERR_UNSUPPORTED) return rc;
   }
   const unsigned gx = (unsigned)((p.out_features + BN - 1) / BN), gy = (unsigned)((tokens + BM - 1) / BM);

@@ -1,6 +1,9 @@
 // vq_gemm fast path for v = 8 with 16-bit indices (k up to 65536: the codebook is 1 MiB and lives in
 // L2 / Infinity Cache, not in LDS), no residual, no outlier columns -- the paper's v=8 / k=65536 setting
 // (App. "Impact of Vector Length").  Y = X * W^T with W restored on the fly; W never touches memory.
+// The same kernel also runs "dense": its producers then copy tiles of an FP16 W that vq_dequant has written
+// to a caller-supplied workspace (the paper's own prompt-phase scheme, Sec. on inference throughput), which
+// on this hardware is the faster route once a workspace is there: see launch_gemm in vq_gemm.hip.
 //
 // A workgroup owns BM tokens x 128 output channels and splits its waves in two roles that share the SIMDs:
 //  * BM/64 "consumer" waves only issue MFMA: wave w owns token rows [64 w, 64 w + 64) and all 128 channels as
@@ -80,9 +83,9 @@ __device__ __forceinline__ unsigned x_slot(unsigned row, unsigned chunk) {     /
 }
 
 // in_features % 32 == 0 here.  Wave w owns token rows [w*BM/4, (w+1)*BM/4) and all 128 channels.
-template <int BM>
+template <int BM, bool DENSE>
 __global__ __launch_bounds__((BM / 64 + 4) * 64) void gemm_v8_kernel(Params p, const __half *__restrict__ X, long long ldx, int tokens,
-                                                      __half *__restrict__ Y, long long ldy) {
+                                                      __half *__restrict__ Y, long long ldy, const __half *__restrict__ Wd, long long ldw) {
   constexpr int NC = BM / 64;                   // consumer waves: each owns 64 token rows x 128 channels
   constexpr int MB = 2;                         // 32-row MFMA blocks per consumer wave along the tokens
   constexpr unsigned XSTAGE = BM * 64u;         // bytes per activation stage
@@ -110,6 +113,44 @@ __global__ __launch_bounds__((BM / 64 + 4) * 64) void gemm_v8_kernel(Params p, c
 
   // The two roles run separate loops with the same number of barriers (one after the prologue, one per step),
   // so that the accumulators of the consumers and the gather registers of the producers never live together.
+  if (producer && DENSE) {
+    // W comes from memory as FP16 rows (ldw halfs apart, 16-byte aligned): this thread copies 32 bytes of row
+    // w_row per step, GD steps ahead, through registers into the same LDS tile the gather path fills.
+    uint4v greg[GD][2];
+    const unsigned char *wrow = reinterpret_cast<const unsigned char *>(Wd + (long long)o_w * ldw) + w_half * 32;
+    auto issue_copy = [&](uint4v (&g)[2], int kt) {
+      async_load16(g[0], wrow + (long long)kt * (BK * 2));
+      async_load16(g[1], wrow + (long long)kt * (BK * 2) + 16);
+    };
+    auto store_w = [&](int buf, uint4v (&g)[2]) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        settle(g[j]);
+        *reinterpret_cast<uint4v *>(Ws + (buf * BN + w_row) * LDT + (w_half * 2 + j) * 8) = w_on ? g[j] : uint4v{0u, 0u, 0u, 0u};
+      }
+    };
+#pragma unroll
+    for (int j = 0; j < GD; ++j) issue_copy(greg[j], j);                      // steps 0 .. GD-1 (ksteps % GD == 0)
+    wait_vmem_at_most<0>();
+    store_w(0, greg[0]);
+    if (GD < ksteps) issue_copy(greg[0], GD);
+    step_barrier();
+    for (int k0 = 0; k0 < ksteps; k0 += GD) {
+#pragma unroll
+      for (int j = 0; j < GD; ++j) {
+        const int kt = k0 + j;
+        if (kt + 1 < ksteps) {
+          // the loads of step kt+1 went out at the end of step kt-GD, followed by two loads in each of the GD-1 steps since
+          if (kt + GD < ksteps) wait_vmem_at_most<2 * (GD - 1)>(); else wait_vmem_at_most<0>();
+          const int sl = (j + 1) % GD;
+          store_w((kt & 1) ^ 1, greg[sl]);
+          if (kt + 1 + GD < ksteps) issue_copy(greg[sl], kt + 1 + GD);
+        }
+        step_barrier();
+      }
+    }
+    return;
+  }
   if (producer) {
     uint4v greg[GD][2];       // centroids of the steps in flight; step kt uses slot kt % GD
     struct IdxGroup { uint4v q[GD / 2]; };   // raw indices of GD consecutive steps of this row: 8 bytes per step
@@ -238,10 +279,11 @@ __global__ __launch_bounds__((BM / 64 + 4) * 64) void gemm_v8_kernel(Params p, c
     }
 }
 
-template <int BM>
-int launch_fused(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy, hipStream_t s) {
+template <int BM, bool DENSE>
+int launch_fused(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy, const __half *Wd, long long ldw,
+                 hipStream_t s) {
   static bool configured = false;
-  auto kernel = gemm_v8_kernel<BM>;
+  auto kernel = gemm_v8_kernel<BM, DENSE>;
   const unsigned lds = NSX * BM * 64u + 2u * BN * LDT * 2u;
   if (!configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
@@ -250,7 +292,7 @@ int launch_fused(const Params &p, const __half *X, long long ldx, int tokens, __
   }
   const unsigned gx = (unsigned)((p.out_features + BN - 1) / BN), gy = (unsigned)((tokens + BM - 1) / BM);
   if (gy > 65535u) return VQ_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL(kernel, dim3(gx, gy), dim3((BM / 64 + 4) * 64), lds, s, p, X, ldx, tokens, Y, ldy);
+  hipLaunchKernelGGL(kernel, dim3(gx, gy), dim3((BM / 64 + 4) * 64), lds, s, p, X, ldx, tokens, Y, ldy, Wd, ldw);
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
 
@@ -260,13 +302,24 @@ bool gemm_fused_applicable(const Params &p) {
   return p.v == 8 && p.bits == 16 && p.k_res == 0 && p.n_out == 0 && p.in_features % (GD * BK) == 0;
 }
 
-int launch_gemm_fused(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy, hipStream_t s) {
+// Wd == nullptr: W is restored on the fly.  Otherwise Wd is the FP16 matrix [out][ldw] that vq_dequant wrote
+// (16-byte aligned rows) and the producers copy its tiles.
+int launch_gemm_fused(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy, const __half *Wd,
+                      long long ldw, hipStream_t s) {
   static const int force_bm = [] { const char *e = getenv("VQ_GEMM_BM"); return e ? atoi(e) : 0; }();
-  const int bm = force_bm ? force_bm : (tokens > 512 ? 512 : 256);
   if (((long long)(tokens - 1) * ldx + p.in_features) * 2 >= (1LL << 32)) return VQ_ERR_UNSUPPORTED;   // 32-bit buffer offsets
-  if (bm == 512) return launch_fused<512>(p, X, ldx, tokens, Y, ldy, s);
-  if (bm == 128) return launch_fused<128>(p, X, ldx, tokens, Y, ldy, s);
-  return launch_fused<256>(p, X, ldx, tokens, Y, ldy, s);
+  if (Wd) {
+    // no gathers to amortise: the tile height only has to fill the chip (out/128 x tokens/BM workgroups)
+    const long long col_blocks = (p.out_features + BN - 1) / BN;
+    const int bm = force_bm ? force_bm : (col_blocks * ((tokens + 511) / 512) >= 200 ? 512 : col_blocks * ((tokens + 255) / 256) >= 200 ? 256 : 128);
+    if (bm == 512) return launch_fused<512, true>(p, X, ldx, tokens, Y, ldy, Wd, ldw, s);
+    if (bm == 128) return launch_fused<128, true>(p, X, ldx, tokens, Y, ldy, Wd, ldw, s);
+    return launch_fused<256, true>(p, X, ldx, tokens, Y, ldy, Wd, ldw, s);
+  }
+  const int bm = force_bm ? force_bm : (tokens > 512 ? 512 : 256);
+  if (bm == 512) return launch_fused<512, false>(p, X, ldx, tokens, Y, ldy, nullptr, 0, s);
+  if (bm == 128) return launch_fused<128, false>(p, X, ldx, tokens, Y, ldy, nullptr, 0, s);
+  return launch_fused<256, false>(p, X, ldx, tokens, Y, ldy, nullptr, 0, s);
 }
 
 }  // namespace vq

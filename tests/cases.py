@@ -29,6 +29,8 @@ SMALL = {
     "v6_chunks_res12": dict(out_features=12303, in_features=198, v=6, k=4096, k_res=4096),
     "v6_passes": dict(out_features=40, in_features=7000, v=6, k=4096, k_res=4096),
     "v6_passes_res8": dict(out_features=37, in_features=9100, v=6, k=4096, k_res=256),
+    # in_features a multiple of 256: vq_gemm's restore-then-multiply route (with a workspace) takes any layer
+    "v6_dense_gemm": dict(out_features=203, in_features=1024, v=6, k=4096, k_res=4096, n_outlier_cols=16, v_out=4, k_out=4096),
 }
 
 

@@ -62,12 +62,13 @@ def test_config_dequant_and_gemv(gpu_lib, layers, monkeypatch, cfg, name):
 
 
 @pytest.mark.parametrize("tokens", [512, 1024, 2048])
-def test_config4_prefill_gemm(gpu_lib, layers, tokens):
+@pytest.mark.parametrize("workspace", [None, "fast"])
+def test_config4_prefill_gemm(gpu_lib, layers, tokens, workspace):
     import torch
     _, L = layers(4, "prefill")
     dl = gpu_lib.DeviceLayer(L)
     x = s.make_activations(4, L, tokens)
-    Y = gpu_lib.gemm(dl, torch.from_numpy(x).cuda())
+    Y = gpu_lib.gemm(dl, torch.from_numpy(x).cuda(), workspace=workspace)
     torch.cuda.synchronize()
     if tokens == 512:
         _matmul_ok(Y, oracle.gemm(L, x), "cfg4 T=512 full")
@@ -78,12 +79,13 @@ def test_config4_prefill_gemm(gpu_lib, layers, tokens):
         _matmul_ok(Y[:, torch.from_numpy(rows.astype(np.int64)).cuda()], ref, "cfg4 T=%d sampled rows" % tokens)
 
 
-def test_config3_small_gemm_with_outliers(gpu_lib, layers):
+@pytest.mark.parametrize("workspace", [None, "fast"])
+def test_config3_small_gemm_with_outliers(gpu_lib, layers, workspace):
     import torch
     _, L = layers(3, "down70b")
     sub = s.make_layer(3, "slice", 256, L.in_features, 6, 4096, 256, 288, 4, 4096)
     dl = gpu_lib.DeviceLayer(sub)
     x = s.make_activations(3, sub, 64, outlier_gain=10.0)
-    Y = gpu_lib.gemm(dl, torch.from_numpy(x).cuda())
+    Y = gpu_lib.gemm(dl, torch.from_numpy(x).cuda(), workspace=workspace)
     torch.cuda.synchronize()
     _matmul_ok(Y, oracle.gemm(sub, x), "cfg3 slice gemm")

@@ -50,19 +50,26 @@ def test_gemv_small(gpu_lib, monkeypatch, name, batch, kernel):
 
 @pytest.mark.parametrize("name", list(SMALL))
 @pytest.mark.parametrize("tokens", [1, 37, 130, 300])
-def test_gemm_small(gpu_lib, name, tokens):
+@pytest.mark.parametrize("workspace", [None, "fast"])
+def test_gemm_small(gpu_lib, monkeypatch, name, tokens, workspace):
+    """Without a workspace (weights restored on the fly) and with the one that lets vq_gemm restore W once (that
+    route forced: by itself the library keeps small token counts on the on-the-fly kernel where it has one)."""
     import torch
+    if workspace == "fast":
+        monkeypatch.setenv("VQ_GEMM_KERNEL", "w")
     L = small_layer(name)
     dl = gpu_lib.DeviceLayer(L)
+    if workspace == "fast" and gpu_lib.vq_gemm_fast_workspace_bytes(dl.desc, tokens) == 0:
+        pytest.skip("no restore-then-multiply route for this shape")
     x = s.make_activations(300, L, tokens)
     ldx = (L.in_features + 7) // 8 * 8
     X = torch.zeros((tokens, ldx), dtype=torch.float16, device="cuda")
     X[:, : L.in_features] = torch.from_numpy(x).cuda()
     if ldx > L.in_features:
         X[:, L.in_features:] = float("nan")           # padding of the caller's buffer must never be read into the sum
-    Y = gpu_lib.gemm(dl, X)
+    Y = gpu_lib.gemm(dl, X, workspace=workspace)
     torch.cuda.synchronize()
-    _check_matmul(Y, oracle.gemm(L, x), "%s tokens %d" % (name, tokens))
+    _check_matmul(Y, oracle.gemm(L, x), "%s tokens %d workspace %s" % (name, tokens, workspace))
 
 
 @pytest.mark.parametrize("kernel", ["auto", "m", "d"])
