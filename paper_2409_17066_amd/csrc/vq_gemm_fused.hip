@@ -27,7 +27,7 @@ typedef unsigned uint4v __attribute__((ext_vector_type(4)));
 
 constexpr int BN = 128;       // output channels per workgroup
 constexpr int BK = 32;        // columns per step (4 vectors of 8)
-constexpr int LDT = BK + 8;   // W tile row pitch in halfs (80 bytes: 8 consecutive rows fall in 8 different 16-byte bank groups)
+constexpr int LDT = BK;       // W tile row pitch in halfs: 64-byte rows, chunks swizzled like the activation tile
 constexpr int GD = 8;         // centroid gathers run this many steps ahead (one register slot per step); also the index group size
 constexpr int XD = 3;         // activation copies run this many steps ahead
 constexpr int NSX = XD + 1;   // activation stages in LDS
@@ -75,11 +75,14 @@ __device__ __forceinline__ void async_load16(uint4v &dst, const void *address) {
 template <int N> __device__ __forceinline__ void wait_vmem_at_most() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 template <class T> __device__ __forceinline__ void settle(T &v) { asm volatile("" : "+v"(v)); }
 
-// Activation tile in LDS: [stage][BM rows][32 halfs], rows unpadded (64 bytes) because the asynchronous copy
-// writes 64 lanes x 16 bytes contiguously.  The four 16-byte chunks of a row are XOR-swizzled with bits 1..2
-// of the row so that the MFMA operand reads (32 rows, same chunk) spread over all banks.
-__device__ __forceinline__ unsigned x_slot(unsigned row, unsigned chunk) {     // byte offset inside a stage
-  return row * 64u + ((chunk ^ ((row >> 1) & 3u)) << 4);
+// Both tiles in LDS are [rows][32 halfs] with unpadded 64-byte rows (the asynchronous activation copy writes
+// 64 lanes x 16 bytes contiguously).  An MFMA operand read is 16-lane groups of 16 consecutive rows, same
+// 16-byte chunk; LDS serves 64 banks x 4 bytes per cycle, i.e. sixteen 16-byte groups, and row r's chunks
+// start at group 4r mod 16: rows r, r+4, r+8, r+12 collide unless their chunks differ.  XOR-ing the chunk
+// index with bits 2..3 of the row makes every such read, and the producers' writes, conflict-free.
+__device__ __forceinline__ unsigned swz(unsigned row) { return (row >> 2) & 3u; }
+__device__ __forceinline__ unsigned x_slot(unsigned row, unsigned chunk) {     // byte offset inside a stage / W buffer
+  return row * 64u + ((chunk ^ swz(row)) << 4);
 }
 
 // in_features % 32 == 0 here.  Wave w owns token rows [w*BM/4, (w+1)*BM/4) and all 128 channels.
@@ -126,7 +129,7 @@ __global__ __launch_bounds__((BM / 64 + 4) * 64) void gemm_v8_kernel(Params p, c
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         settle(g[j]);
-        *reinterpret_cast<uint4v *>(Ws + (buf * BN + w_row) * LDT + (w_half * 2 + j) * 8) = w_on ? g[j] : uint4v{0u, 0u, 0u, 0u};
+        *reinterpret_cast<uint4v *>(reinterpret_cast<unsigned char *>(Ws + buf * BN * LDT) + x_slot((unsigned)w_row, (unsigned)(w_half * 2 + j))) = w_on ? g[j] : uint4v{0u, 0u, 0u, 0u};
       }
     };
 #pragma unroll
@@ -176,7 +179,7 @@ __global__ __launch_bounds__((BM / 64 + 4) * 64) void gemm_v8_kernel(Params p, c
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         settle(g[j]);
-        *reinterpret_cast<uint4v *>(Ws + (buf * BN + w_row) * LDT + (w_half * 2 + j) * 8) = restore8(g[j], s_w, b_w, w_on);
+        *reinterpret_cast<uint4v *>(reinterpret_cast<unsigned char *>(Ws + buf * BN * LDT) + x_slot((unsigned)w_row, (unsigned)(w_half * 2 + j))) = restore8(g[j], s_w, b_w, w_on);
       }
     };
     // Memory operations of a producer wave, in issue order: per step two centroid gathers (for step kt+1+GD), plus
@@ -224,7 +227,7 @@ __global__ __launch_bounds__((BM / 64 + 4) * 64) void gemm_v8_kernel(Params p, c
     for (int i = 0; i < 4; ++i) {
       const unsigned piece = (unsigned)(wave * 4 + i);                  // 16 rows per 1 KB piece
       const unsigned r = piece * 16u + ((unsigned)lane >> 2), cs = (unsigned)lane & 3u;   // LDS slot (r, cs) holds chunk cs ^ swz(r)
-      const unsigned c = cs ^ ((r >> 1) & 3u);
+      const unsigned c = cs ^ swz(r);
       const unsigned goff = (unsigned)(((long long)(m0 + (int)r) * ldx + (long long)kt * BK + c * 8) * 2);
       __builtin_amdgcn_raw_ptr_buffer_load_lds(r_x, (__attribute__((address_space(3))) void *)(Xs + stage + piece * 1024u), 16, goff, 0, 0, 0);
     }
@@ -254,7 +257,7 @@ __global__ __launch_bounds__((BM / 64 + 4) * 64) void gemm_v8_kernel(Params p, c
         af[a] = *reinterpret_cast<const half8 *>(xs + x_slot((unsigned)(wm + a * 32 + (lane & 31)), (unsigned)(ks / 8 + (lane >> 5))));
 #pragma unroll
       for (int c = 0; c < 4; ++c)
-        bf[c] = *reinterpret_cast<const half8 *>(Ws + (cur * BN + c * 32 + (lane & 31)) * LDT + ks + (lane >> 5) * 8);
+        bf[c] = *reinterpret_cast<const half8 *>(reinterpret_cast<const unsigned char *>(Ws + cur * BN * LDT) + x_slot((unsigned)(c * 32 + (lane & 31)), (unsigned)(ks / 8 + (lane >> 5))));
 #pragma unroll
       for (int a = 0; a < MB; ++a)
 #pragma unroll
