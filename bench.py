@@ -48,11 +48,11 @@ def parse():
 class Rotation:
     """R device copies of a layer's index streams (tables, scale and bias are shared)."""
 
-    def __init__(self, vq, layer, min_bytes=ROTATE_BYTES, max_copies=64):
+    def __init__(self, vq, layer, min_bytes=ROTATE_BYTES, max_copies=64, min_copies=2):
         import torch
         self.base = vq.DeviceLayer(layer)
         stream_bytes = sum(a.nbytes for a in (layer.idx, layer.idx_res, layer.idx_out) if a is not None)
-        copies = max(2, min(max_copies, -(-min_bytes // stream_bytes)))
+        copies = max(min_copies, min(max_copies, -(-min_bytes // stream_bytes)))
         self.descs = [self.base.desc]
         self.keep = []
         import ctypes
@@ -100,9 +100,9 @@ def timed(launch, steps, warmup, use_graph=True):
     return wall, e0.elapsed_time(e1) * 1e-3
 
 
-def bench_gemv(vq, layer, x_np, steps, warmup, use_graph):
+def bench_gemv(vq, layer, x_np, steps, warmup, use_graph, rotate=True):
     import torch
-    rot = Rotation(vq, layer)
+    rot = Rotation(vq, layer) if rotate else Rotation(vq, layer, min_bytes=0, min_copies=1)
     x = torch.from_numpy(x_np).cuda()
     batch = x.shape[0]
     y = torch.empty((batch, layer.out_features), dtype=torch.float16, device="cuda")
@@ -187,6 +187,24 @@ def main():
             b.copy_(a)
         torch.cuda.synchronize()
         result["copy_kernel_bytes_each_way"] = a.numel() * 4
+    # context, never the headline: the same launches on ONE copy of the indices (they then come from the 256 MB
+    # Infinity Cache, not from HBM), and what a plain device-to-device copy of 1 GiB moves per second on this machine
+    warm = bench_gemv(vq, layer, x_np, args.steps, args.warmup, use_graph, rotate=False)
+    a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    b = torch.empty_like(a)
+    b.copy_(a)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        b.copy_(a)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 2 * a.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del a, b
+    result["context"] = {"cache_warm_us_per_step": round(warm["event_s"] / args.steps * 1e6, 3),
+                         "cache_warm_GB/s": round(alg / (warm["event_s"] / args.steps) / 1e9, 1),
+                         "device_copy_GB/s_read_plus_write": round(copy_gbps, 1),
+                         "achieved_over_device_copy": round(gbps / copy_gbps, 4)}
     if not args.no_detail:
         result["detail"] = detail(vq, s, np, torch, use_graph, skip=(cfg, 1))
     print(json.dumps(result))
@@ -196,6 +214,7 @@ def detail(vq, s, np, torch, use_graph, skip):
     """Short timings of the other benchmark layers and entry points."""
     out = []
     steps, warmup = 400, 50
+    cfg2_bytes = {}
 
     def gemv_line(cfg, ordinal, layer, batch):
         spec = s.CONFIGS[cfg]
@@ -203,6 +222,7 @@ def detail(vq, s, np, torch, use_graph, skip):
         r = bench_gemv(vq, layer, x_np, steps, warmup, use_graph)
         sec = r["event_s"] / steps
         alg = layer.algorithmic_bytes(batch)
+        cfg2_bytes[layer.name, batch] = alg
         flops = 2.0 * batch * layer.out_features * layer.in_features
         out.append({"op": "vq_gemv", "cfg": cfg, "layer": layer.name, "batch": batch, "us": round(sec * 1e6, 3),
                     "GB/s": round(alg / sec / 1e9, 1), "frac_hbm_peak": round(alg / sec / 1e9 / HBM_PEAK_GBPS, 4),
@@ -221,6 +241,16 @@ def detail(vq, s, np, torch, use_graph, skip):
                     continue
                 gemv_line(cfg, ordinal, layer, batch)
             del layer
+        if cfg == 2:
+            # one decoder layer = q, k, v, o (q's shape) + gate, up (gate's shape) + down: seven GEMV calls
+            for batch in spec["rows"]:
+                us = {d["layer"]: d["us"] for d in out if d["op"] == "vq_gemv" and d["cfg"] == 2 and d["batch"] == batch}
+                total_us = 4 * us["q"] + 2 * us["gate"] + us["down"]
+                alg = sum(m * layer_bytes for m, layer_bytes in
+                          ((4, cfg2_bytes["q", batch]), (2, cfg2_bytes["gate", batch]), (1, cfg2_bytes["down", batch])))
+                out.append({"op": "vq_gemv x7 (whole cfg2 layer: 4 q-shaped, 2 gate-shaped, down; sum of the per-call times)",
+                            "cfg": 2, "batch": batch, "us": round(total_us, 2), "GB/s": round(alg / total_us / 1e3, 1),
+                            "frac_hbm_peak": round(alg / total_us / 1e3 / HBM_PEAK_GBPS, 4)})
     # prefill GEMM and dequant on the 8192 x 8192, v=8, k=65536 layer
     _, L4 = next(s.config_layers(4))
     dl = vq.DeviceLayer(L4)
