@@ -200,7 +200,10 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
 
   const uint4v ones = {0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0u};
   float4v acc[NB];
-  float4v xs = {0.0f, 0.0f, 0.0f, 0.0f};
+  // sum of each token's activations over this wave's columns, kept in LDS (slot [wave][token], touched by this wave only
+  // until the first chunk's barrier): a register accumulator would stay allocated through the whole kernel
+  float *xs_part = reinterpret_cast<float *>(lds + plan.lds_xs);       // [MW][16]
+  if (g == 0) xs_part[wv * 16 + n] = 0.0f;
   int buf = 0, c = 0, pass = 0;
   while (c < n_chunks) {
 #pragma unroll
@@ -233,8 +236,10 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
               bx[u].z = 0u; bx[u].w = 0u;
             }
             if (c == 0) {
+              float4v xs = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
               for (int u = 0; u < VPL; ++u) xs = mfma16(ones, bx[u], xs);
+              if (g == 0) xs_part[wv * 16 + n] += xs.x;
             }
 #pragma unroll
             for (int b = 0; b < NB; ++b)
@@ -274,8 +279,10 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
             }
           }
           if (c == 0) {
+            float4v xs = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
             for (int u = 0; u < VPL; ++u) xs = mfma16(ones, bx[u], xs);
+            if (g == 0) xs_part[wv * 16 + n] += xs.x;
           }
           issue_x(bxs[(j + XD) % XS], (pass + XD) % my_passes);
 #pragma unroll
@@ -328,8 +335,6 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
 #pragma unroll
           for (int b = 0; b < NB; ++b)
             if (b < nb_c) *reinterpret_cast<float4v *>(pbase + (unsigned)(b * MW + wv) * 1024u + lane * 16u) = acc[b];
-          float *xs_part = reinterpret_cast<float *>(lds + plan.lds_xs);       // [MW][16]
-          if (c == 0 && g == 0) xs_part[wv * 16 + n] = xs.x;
           lds_barrier();
           VQ_STAMP(5);
           if (wv < nb_c) {
@@ -430,10 +435,10 @@ int launch_gemv_mfma(const Params &p, const __half *x, long long ldx, int batch,
   plan.lds_part = off;
   if (off + MW * 1024u > lds_cap) return VQ_ERR_UNSUPPORTED;
   const int fit = (int)((lds_cap - off) / (MW * 1024u));                 // 16-row partial blocks that fit
-  // Blocks per chunk: as many as the kernel's 256 registers allow -- four, three with an 8-bit residual stream in the
-  // prefetch ring, two with a 12-bit one.  More would spill, which these kernels must not (see the build script).
+  // Blocks per chunk: as many as the kernel's 256 registers allow -- four, or three with a residual index stream in the
+  // prefetch ring.  More would spill, which these kernels must not (see the build script).
   static const int nb_cap = [] { const char *e = getenv("VQ_MFMA_NB"); return e ? atoi(e) : NBMAX; }();
-  plan.nb = min(min(min(rb == 12 ? 2 : rb == 8 ? 3 : NBMAX, nb_cap), blocks_per_wg), fit);
+  plan.nb = min(min(min(rb ? 3 : NBMAX, nb_cap), blocks_per_wg), fit);
   if (plan.nb < 1) return VQ_ERR_UNSUPPORTED;
   plan.part_bufs = (fit >= 2 * plan.nb && blocks_per_wg > plan.nb) ? 2 : 1;
   off += (unsigned)(plan.part_bufs * plan.nb) * (MW * 1024u);
@@ -447,7 +452,7 @@ int launch_gemv_mfma(const Params &p, const __half *x, long long ldx, int batch,
   if (rb == RBITS && plan.nb == NBLK) return launch_one<RBITS, MW, NBLK>(p, plan, off, grid, x, ldx, batch, y, ldy, s);
   VQ_CASE(0, 1) VQ_CASE(0, 2) VQ_CASE(0, 3) VQ_CASE(0, 4)
   VQ_CASE(8, 1) VQ_CASE(8, 2) VQ_CASE(8, 3)
-  VQ_CASE(12, 1) VQ_CASE(12, 2)
+  VQ_CASE(12, 1) VQ_CASE(12, 2) VQ_CASE(12, 3)
 #undef VQ_CASE
   return VQ_ERR_UNSUPPORTED;
 }
