@@ -358,13 +358,15 @@ int launch_u(int U, const Params &p, const GemvPlan &plan, unsigned lds_bytes, u
     if (U == 5 && l1r == 2) return launch_one<8, 1, 5, 2>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
     if (U == 5 && l1r == 3) return launch_one<8, 1, 5, 3>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
   }
-  if (U == 5) return launch_one<RES_BITS, B, 5>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
+  // (the combinations u_allowed() admits, no others: each costs build time and library size)
   if constexpr (B <= 2) {
+    if (U == 5) return launch_one<RES_BITS, B, 5>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
+  }
+  if constexpr (B == 1) {
     if (U == 6) return launch_one<RES_BITS, B, 6>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
-    if (U == 8) return launch_one<RES_BITS, B, 8>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
   }
   if constexpr (B == 1 && RES_BITS == 0) {
-    if (U == 11) return launch_one<0, 1, 11>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
+    if (U == 8) return launch_one<0, 1, 8>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
   }
   return VQ_ERR_UNSUPPORTED;
 }
@@ -397,7 +399,7 @@ static bool u_allowed(int U, int batch, bool res) {
 
 // Launch for one group of 1, 2 or 4 batch rows.
 int launch_gemv_fast(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
-  static const int kU[] = {4, 5, 6, 8, 11};
+  static const int kU[] = {4, 5, 6, 8};
   GemvPlan plan{};
   // LDS: tables first (main at 0); the activation rows, partial sums and activation sums follow once the
   // slicing is known
