@@ -15,7 +15,8 @@ _SRC = os.path.join(_HERE, "vq_oracle.cpp")
 
 def build(force: bool = False) -> str:
     """Compile the oracle with g++ (a second of CPU work)."""
-    if force or not os.path.exists(_LIB_PATH) or os.path.getmtime(_LIB_PATH) < os.path.getmtime(_SRC):
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(os.path.join(_HERE, "vq_oracle.h")))
+    if force or not os.path.exists(_LIB_PATH) or os.path.getmtime(_LIB_PATH) < newest:
         subprocess.check_call(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
                                "-Wall", "-Wextra", _SRC, "-o", _LIB_PATH, "-lpthread"])
     return _LIB_PATH
@@ -31,6 +32,7 @@ class _Layer(ctypes.Structure):
         ("idx_res", ctypes.c_void_p), ("idx_res_row_stride", ctypes.c_int64),
         ("idx_out", ctypes.c_void_p), ("idx_out_row_stride", ctypes.c_int64),
         ("scale", ctypes.c_void_p), ("bias", ctypes.c_void_p),
+        ("group_vectors", ctypes.c_int32),
     ]
 
 
@@ -85,7 +87,8 @@ def _describe(layer):
                layer.n_outlier_cols, layer.v_out, layer.k_out,
                _ptr(keep["codebook"]), _ptr(keep["codebook_res"]), _ptr(keep["codebook_out"]),
                _ptr(keep["idx"]), stride(keep["idx"]), _ptr(keep["idx_res"]), stride(keep["idx_res"]),
-               _ptr(keep["idx_out"]), stride(keep["idx_out"]), _ptr(keep["scale"]), _ptr(keep["bias"]))
+               _ptr(keep["idx_out"]), stride(keep["idx_out"]), _ptr(keep["scale"]), _ptr(keep["bias"]),
+               int(getattr(layer, "group_vectors", 0)))
     return d, keep
 
 

@@ -71,7 +71,7 @@ namespace {
 struct RowDecoder {
   const vq_oracle_layer *L;
   int b, b_res, b_out;
-  int64_t P, Q;
+  int64_t P, Q, Pg;            // Pg: vectors per codebook group
   std::vector<int32_t> i_main, i_res, i_out;
   explicit RowDecoder(const vq_oracle_layer *layer) : L(layer) {
     b = vq_oracle_index_bits(L->k);
@@ -80,6 +80,7 @@ struct RowDecoder {
     const int64_t main_cols = (int64_t)L->in_features - L->n_outlier_cols;
     P = (main_cols + L->v - 1) / L->v;
     Q = L->n_outlier_cols ? L->n_outlier_cols / L->v_out : 0;
+    Pg = L->group_vectors > 0 ? L->group_vectors : (P > 0 ? P : 1);
     i_main.resize(P); i_res.resize(L->k_res ? P : 0); i_out.resize(Q);
   }
   // Restored row o as fp16 bits, w16[c] for c < in_features.
@@ -100,11 +101,12 @@ struct RowDecoder {
         const int64_t cc = c - L->n_outlier_cols, p = cc / L->v, j = cc % L->v;
         const int32_t i = i_main[p];
         if (i >= L->k) return VQO_ERR_INDEX_RANGE;
-        d = vq_oracle_half_to_float(L->codebook[(int64_t)i * L->v + j]);
+        const int64_t group = p / Pg;                        // this vector's tables
+        d = vq_oracle_half_to_float(L->codebook[(group * L->k + i) * L->v + j]);
         if (L->k_res) {
           const int32_t r = i_res[p];
           if (r >= L->k_res) return VQO_ERR_INDEX_RANGE;
-          volatile float sum = d + vq_oracle_half_to_float(L->codebook_res[(int64_t)r * L->v + j]);  // binary32 add
+          volatile float sum = d + vq_oracle_half_to_float(L->codebook_res[(group * L->k_res + r) * L->v + j]);  // binary32 add
           d = sum;
         }
       }
@@ -117,6 +119,7 @@ struct RowDecoder {
 
 int check_layer(const vq_oracle_layer *L) {
   if (!L || !L->codebook || !L->idx) return VQO_ERR_ARG;
+  if (L->group_vectors < 0) return VQO_ERR_ARG;
   if (L->out_features < 0 || L->in_features < 0 || L->v < 1 || L->k < 1) return VQO_ERR_ARG;
   if (L->k_res && (!L->codebook_res || !L->idx_res)) return VQO_ERR_ARG;
   if (L->n_outlier_cols) {

@@ -9,8 +9,10 @@
  * "Vector Quantization"), the residual codebook's centroid is added to it
  * (Sec. 3.2.2, "Residual Vector Quantization"), a small set of outlier
  * columns uses a codebook of its own (Sec. 3.2.3, "Outlier Elimination";
- * parameters v0,k0,v1,k1,k2 of App. "Parameter Description"), and the restored
- * FP16 matrix multiplies the activations (App. "Our Dequantization
+ * parameters v0,k0,v1,k1,k2 of App. "Parameter Description"), the weight
+ * matrix may be split into groups that each have a codebook of their own
+ * (Sec. 3.1, the paragraph on groups; "group num" in the parameter tables), and
+ * the restored FP16 matrix multiplies the activations (App. "Our Dequantization
  * Implementation").  Per-output-channel scale and bias are applied to the
  * restored weight before it is rounded to FP16.
  *
@@ -38,6 +40,12 @@ typedef struct vq_oracle_layer {
   const uint8_t *idx_res;  int64_t idx_res_row_stride;
   const uint8_t *idx_out;  int64_t idx_out_row_stride;
   const uint16_t *scale, *bias;           /* fp16 bits [out_features]; NULL = 1.0 / 0.0       */
+  /* Groups: with group_vectors > 0 the main vectors of a row are split into consecutive ranges of group_vectors
+   * vectors (the last range may be shorter), ceil(P / group_vectors) groups in all, and each group has its own
+   * main table and, if there is a residual codebook, its own residual table: vector p reads the tables of group
+   * p / group_vectors.  codebook is then [groups][k][v] and codebook_res [groups][k_res][v].  0 means one
+   * group.  Outlier columns keep their single table.                                            */
+  int32_t group_vectors;
 } vq_oracle_layer;
 
 enum { VQO_OK = 0, VQO_ERR_ARG = -1, VQO_ERR_INDEX_RANGE = -2 };

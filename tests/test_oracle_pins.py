@@ -120,6 +120,55 @@ def test_outlier_columns_use_only_their_own_stream():
     assert np.array_equal(W[:, :8].view(np.uint16), L.codebook_out[L.raw_idx_out].reshape(4, 8).view(np.uint16))
 
 
+def test_groups_are_the_concatenation_of_single_table_layers():
+    """Sec. 3.1 (groups): every range of columns is a layer of its own with its own tables."""
+    kw = dict(out_features=4, in_features=8 + 6 * 19 - 2, k=64, k_res=16, n_outlier_cols=8, v_out=4, k_out=32)
+    Pg = 8
+    L = _tiny(group_vectors=Pg, **kw)
+    assert L.n_groups == 3 and L.codebook.shape == (3 * 64, 6) and L.codebook_res.shape == (3 * 16, 6)
+    W = oracle.dequant(L).view(np.uint16)
+    for g in range(L.n_groups):
+        lo, hi = g * Pg, min((g + 1) * Pg, L.vectors_per_row)
+        c0, c1 = 8 + lo * 6, min(8 + hi * 6, L.in_features)
+        sub = s.VQLayer("sub", 4, c1 - c0, 6, 64, 16)
+        sub.codebook, sub.codebook_res = L.codebook[g * 64:(g + 1) * 64], L.codebook_res[g * 16:(g + 1) * 16]
+        sub.raw_idx, sub.raw_idx_res = L.raw_idx[:, lo:hi], L.raw_idx_res[:, lo:hi]
+        sub.scale, sub.bias = L.scale, L.bias
+        _repack(sub)
+        assert np.array_equal(oracle.dequant(sub).view(np.uint16), W[:, c0:c1]), g
+    # the outlier columns do not depend on the grouping
+    assert np.array_equal(W[:, :8], oracle.dequant(_tiny(**kw)).view(np.uint16)[:, :8])
+
+
+def test_group_tables_reach_only_their_own_columns():
+    kw = dict(out_features=3, in_features=6 * 21, k=32, k_res=8)
+    ref = oracle.dequant(_tiny(group_vectors=8, **kw)).view(np.uint16)
+    for which in ("codebook", "codebook_res"):
+        rows = 32 if which == "codebook" else 8
+        for g in range(3):
+            L = _tiny(group_vectors=8, **kw)
+            getattr(L, which)[g * rows:(g + 1) * rows] += np.float16(0.25)
+            W = oracle.dequant(L).view(np.uint16)
+            differs = (W != ref).any(axis=0).reshape(21, 6).any(axis=1)
+            assert np.array_equal(differs, np.arange(21) // 8 == g), (which, g)
+
+
+def test_one_group_and_equal_tables_reduce_to_the_plain_layer():
+    kw = dict(out_features=3, in_features=100, k=64, k_res=16)
+    plain = _tiny(**kw)
+    want = oracle.dequant(plain).view(np.uint16)
+    for Pg in (plain.vectors_per_row, plain.vectors_per_row + 5):          # one group that holds every vector
+        L = _tiny(group_vectors=Pg, **kw)
+        assert L.n_groups == 1
+        assert np.array_equal(oracle.dequant(L).view(np.uint16), want)
+    L = _tiny(group_vectors=5, **kw)
+    L.codebook = np.tile(plain.codebook, (L.n_groups, 1))
+    L.codebook_res = np.tile(plain.codebook_res, (L.n_groups, 1))
+    assert np.array_equal(oracle.dequant(L).view(np.uint16), want)
+    x = s.make_activations(200, L, 2)
+    assert np.array_equal(oracle.matmul(L, x), oracle.matmul(plain, x))
+
+
 def test_scale_and_bias_semantics():
     L = _tiny(k_res=16)
     L.codebook[:] = 0
@@ -182,9 +231,12 @@ def _naive_dequant(L):
                 d = Fraction(float(L.codebook_out[L.raw_idx_out[o, c // L.v_out], c % L.v_out]))
             else:
                 cc = c - L.n_outlier_cols
-                d = Fraction(float(L.codebook[L.raw_idx[o, cc // L.v], cc % L.v]))
+                p = cc // L.v
+                g = p // L.group_vectors if L.group_vectors else 0
+                d = Fraction(float(L.codebook.reshape(-1, L.k, L.v)[g, L.raw_idx[o, p], cc % L.v]))
                 if L.k_res:
-                    d = _round_fraction(d + Fraction(float(L.codebook_res[L.raw_idx_res[o, cc // L.v], cc % L.v])), 24, -126)
+                    r = L.codebook_res.reshape(-1, L.k_res, L.v)[g, L.raw_idx_res[o, p], cc % L.v]
+                    d = _round_fraction(d + Fraction(float(r)), 24, -126)
             w32 = _round_fraction(sc * d + bi, 24, -126)
             W[o, c] = float(_round_fraction(w32, 11, -14))
     return W
@@ -199,6 +251,9 @@ CASES = [
     dict(out_features=2, in_features=9, v=1, k=2),
     dict(out_features=2, in_features=33, v=16, k=300, with_scale=False),
     dict(out_features=2, in_features=12, v=2, k=16, with_bias=False),
+    dict(out_features=3, in_features=61, v=6, k=256, group_vectors=4),                        # 11 vectors: groups of 4, 4, 3
+    dict(out_features=3, in_features=75, v=6, k=64, k_res=16, n_outlier_cols=8, v_out=4, k_out=32, group_vectors=8),
+    dict(out_features=2, in_features=23, v=5, k=37, k_res=11, group_vectors=1),                # a table per vector
 ]
 
 

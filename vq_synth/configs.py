@@ -27,8 +27,9 @@ class VQLayer:
     n_outlier_cols: int = 0
     v_out: int = 0
     k_out: int = 0
-    codebook: np.ndarray = None          # fp16 [k][v]
-    codebook_res: np.ndarray = None      # fp16 [k_res][v] or None
+    group_vectors: int = 0               # > 0: every range of this many vectors of a row has tables of its own
+    codebook: np.ndarray = None          # fp16 [n_groups * k][v]: the groups' tables one after the other
+    codebook_res: np.ndarray = None      # fp16 [n_groups * k_res][v] or None
     codebook_out: np.ndarray = None      # fp16 [k_out][v_out] or None
     idx: np.ndarray = None               # uint8 [out][stride]
     idx_res: np.ndarray = None
@@ -48,6 +49,10 @@ class VQLayer:
         return self.n_outlier_cols // self.v_out if self.n_outlier_cols else 0
 
     @property
+    def n_groups(self) -> int:
+        return -(-self.vectors_per_row // self.group_vectors) if self.group_vectors > 0 else 1
+
+    @property
     def bits(self) -> int:
         return index_bits(self.k)
 
@@ -63,7 +68,7 @@ class VQLayer:
         """Bytes one call must move: unpadded index bits, tables, scale/bias, activations in, outputs out."""
         P, Q, M = self.vectors_per_row, self.outlier_vectors_per_row, self.out_features
         idx_bits = M * (P * (self.bits + self.bits_res) + Q * self.bits_out)
-        tables = 2 * (self.k * self.v + self.k_res * self.v + self.k_out * self.v_out)
+        tables = 2 * (self.n_groups * (self.k * self.v + self.k_res * self.v) + self.k_out * self.v_out)
         sb = 2 * M * ((self.scale is not None) + (self.bias is not None))
         return idx_bits // 8 + tables + sb + 2 * batch * self.in_features + 2 * batch * M
 
@@ -71,18 +76,21 @@ class VQLayer:
 def make_layer(config: int, name: str, out_features: int, in_features: int, v: int, k: int,
                k_res: int = 0, n_outlier_cols: int = 0, v_out: int = 0, k_out: int = 0,
                layer_ordinal: int = 0, with_scale: bool = True, with_bias: bool = True,
-               extra_stride: int = 0) -> VQLayer:
-    """Build one layer from the seeded streams.  `extra_stride` adds 16-byte units of row padding."""
+               extra_stride: int = 0, group_vectors: int = 0) -> VQLayer:
+    """Build one layer from the seeded streams.  `extra_stride` adds 16-byte units of row padding; with
+    `group_vectors` every range of that many vectors gets main (and residual) tables of its own, all drawn from
+    one stream, group after group."""
     def seed(t):
         return g.tensor_seed(config, t, layer_ordinal)
 
-    L = VQLayer(name, out_features, in_features, v, k, k_res, n_outlier_cols, v_out, k_out)
+    L = VQLayer(name, out_features, in_features, v, k, k_res, n_outlier_cols, v_out, k_out, group_vectors)
     P, Q = L.vectors_per_row, L.outlier_vectors_per_row
-    L.codebook = g.to_fp16(g.normal(seed(g.T_CODEBOOK), k * v, SIGMA_MAIN)).reshape(k, v)
+    n_groups = L.n_groups
+    L.codebook = g.to_fp16(g.normal(seed(g.T_CODEBOOK), n_groups * k * v, SIGMA_MAIN)).reshape(n_groups * k, v)
     L.raw_idx = g.random_indices(seed(g.T_IDX), out_features, P, k)
     L.idx = pack_indices(L.raw_idx, L.bits, row_stride_bytes(P, L.bits) + 16 * extra_stride)
     if k_res:
-        L.codebook_res = g.to_fp16(g.normal(seed(g.T_CODEBOOK_RES), k_res * v, SIGMA_RES)).reshape(k_res, v)
+        L.codebook_res = g.to_fp16(g.normal(seed(g.T_CODEBOOK_RES), n_groups * k_res * v, SIGMA_RES)).reshape(n_groups * k_res, v)
         L.raw_idx_res = g.random_indices(seed(g.T_IDX_RES), out_features, P, k_res)
         L.idx_res = pack_indices(L.raw_idx_res, L.bits_res, row_stride_bytes(P, L.bits_res) + 16 * extra_stride)
     if n_outlier_cols:
