@@ -57,7 +57,7 @@ typedef enum vq_status {
 } vq_status;
 
 typedef struct vq_layer_desc {
-  uint32_t struct_size;                    /* = sizeof(vq_layer_desc)                              */
+  uint32_t struct_size;                    /* = sizeof(vq_layer_desc), or VQ_LAYER_DESC_SIZE_V1     */
   int32_t out_features, in_features;       /* M, N (logical, unpadded); 1 .. 2^24                  */
   int32_t v, k;                            /* main codebook: v in [1,16], k in [2,65536]           */
   int32_t k_res;                           /* residual entries, 0 = none; same v                   */
@@ -70,7 +70,17 @@ typedef struct vq_layer_desc {
   const void *idx_out;  int64_t idx_out_row_stride;
   const void *scale;                       /* fp16 [out_features], 2-byte aligned; NULL = 1.0      */
   const void *bias;                        /* fp16 [out_features]; NULL = 0.0                      */
+  /* Codebook groups (Sec. 3.1, the paragraph on groups; "group num" in App. "Parameter Description"): with
+   * group_vectors > 0 every range of group_vectors consecutive main vectors of a row (the last range may be
+   * shorter) has its own main table and, with a residual codebook, its own residual table; vector p reads the
+   * tables of group p / group_vectors.  codebook is then fp16 [groups][k][v] and codebook_res fp16
+   * [groups][k_res][v], groups = ceil(P / group_vectors), P = ceil((in_features - n_outlier_cols) / v).
+   * 0 = one group.  Outlier columns keep their single table.  The fast kernels take group_vectors % 8 == 0.
+   * A caller that sets struct_size to VQ_LAYER_DESC_SIZE_V1 (the layout up to `bias`) gets one group.    */
+  int32_t group_vectors;
 } vq_layer_desc;
+
+#define VQ_LAYER_DESC_SIZE_V1 ((uint32_t)offsetof(vq_layer_desc, group_vectors))
 
 /* Host-only check of a descriptor (no GPU work): the status any entry point would return for it. */
 int vq_validate(const vq_layer_desc *desc);

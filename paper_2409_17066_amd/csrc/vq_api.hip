@@ -14,7 +14,9 @@ static int check_stream(const void *idx, long long stride, int per_row, int bits
 
 int make_params(const vq_layer_desc *d, Params *p) {
   if (!d) return VQ_ERR_NULL;
-  if (d->struct_size != sizeof(vq_layer_desc)) return VQ_ERR_SHAPE;
+  if (d->struct_size != sizeof(vq_layer_desc) && d->struct_size != VQ_LAYER_DESC_SIZE_V1) return VQ_ERR_SHAPE;
+  const int group_vectors = d->struct_size == sizeof(vq_layer_desc) ? d->group_vectors : 0;
+  if (group_vectors < 0) return VQ_ERR_SHAPE;
   const int lim = 1 << 24;
   if (d->out_features < 1 || d->out_features > lim || d->in_features < 1 || d->in_features > lim) return VQ_ERR_SHAPE;
   if (d->v < 1 || d->v > 16 || d->k < 2 || d->k > 65536) return VQ_ERR_SHAPE;
@@ -32,6 +34,8 @@ int make_params(const vq_layer_desc *d, Params *p) {
   q.v_out = q.n_out ? d->v_out : 1; q.k_out = q.n_out ? d->k_out : 0; q.bits_out = q.n_out ? index_bits(d->k_out) : 0;
   q.P = (d->in_features - q.n_out + d->v - 1) / d->v;
   q.Q = q.n_out ? q.n_out / d->v_out : 0;
+  q.Pg = group_vectors > 0 && group_vectors < q.P ? group_vectors : q.P;
+  q.n_groups = (q.P + q.Pg - 1) / q.Pg;
   if (!d->codebook) return VQ_ERR_NULL;
   if (!aligned(d->codebook, 16)) return VQ_ERR_ALIGNMENT;
   int rc = check_stream(d->idx, d->idx_row_stride, q.P, q.bits);

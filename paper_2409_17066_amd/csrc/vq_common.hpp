@@ -14,6 +14,7 @@ struct Params {
   int k_res, bits_res;
   int n_out, v_out, k_out, bits_out;
   int P, Q;                      // main / outlier vectors per row
+  int Pg, n_groups;              // vectors per codebook group (P if there is one group), groups; tables are [group][k][v]
   const __half *cb, *cb_res, *cb_out;
   const uint8_t *idx, *idx_res, *idx_out;
   long long stride, stride_res, stride_out;   // bytes per row of each stream

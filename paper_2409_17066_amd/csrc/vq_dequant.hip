@@ -23,12 +23,13 @@ __global__ __launch_bounds__(256) void dequant_generic_kernel(Params p, __half *
     const int pp = slot - p.Q;
     unsigned i = load_index(p.idx + (long long)o * p.stride, pp, p.bits);
     i = min(i, (unsigned)p.k - 1u);
-    const __half *e = p.cb + (long long)i * p.v;
+    const long long group = pp / p.Pg;                          // this vector's tables
+    const __half *e = p.cb + (group * p.k + i) * p.v;
     const __half *er = nullptr;
     if (p.k_res) {
       unsigned r = load_index(p.idx_res + (long long)o * p.stride_res, pp, p.bits_res);
       r = min(r, (unsigned)p.k_res - 1u);
-      er = p.cb_res + (long long)r * p.v;
+      er = p.cb_res + (group * p.k_res + r) * p.v;
     }
     const int c0 = p.n_out + pp * p.v;
     for (int j = 0; j < p.v; ++j) {

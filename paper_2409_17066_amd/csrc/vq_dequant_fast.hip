@@ -181,7 +181,7 @@ __global__ __launch_bounds__(256) void dequant_v8_kernel(Params p, __half *__res
   if (pp >= p.P) return;
   const unsigned short raw = reinterpret_cast<const unsigned short *>(p.idx + (long long)o * p.stride)[pp];
   const unsigned i = min((unsigned)raw, (unsigned)p.k - 1u);
-  const uint4v e = reinterpret_cast<const uint4v *>(p.cb)[i];
+  const uint4v e = reinterpret_cast<const uint4v *>(p.cb)[(size_t)(pp / p.Pg) * (size_t)p.k + i];   // its group's table
   const float s = p.scale ? __half2float(p.scale[o]) : 1.0f;
   const float b = p.bias ? __half2float(p.bias[o]) : 0.0f;
   const int c0 = pp * 8, valid = min(8, p.in_features - c0);
@@ -247,6 +247,27 @@ int launch_dequant_fast(const Params &p, __half *W, long long ldw, hipStream_t s
   if (p.v != 6 || p.bits != 12) return VQ_ERR_UNSUPPORTED;
   if (p.k_res && p.bits_res != 12 && p.bits_res != 8) return VQ_ERR_UNSUPPORTED;
   if (p.n_out && (p.v_out != 4 || p.bits_out != 12)) return VQ_ERR_UNSUPPORTED;
+  if (p.n_groups > 1) {
+    // Codebook groups (Sec. 3.1): a group is a layer of its own over a range of columns -- one launch each, on the
+    // group's tables, its part of the index streams (a group of 8 n vectors starts on a dword of a 12- or 8-bit
+    // stream) and its columns of W.  The outlier columns go with the first group.
+    if (p.Pg & 7) return VQ_ERR_UNSUPPORTED;
+    for (int g = 0; g < p.n_groups; ++g) {
+      Params q = p;
+      const int v_lo = g * p.Pg;
+      q.P = min(p.Pg, p.P - v_lo); q.Pg = q.P; q.n_groups = 1;
+      q.cb = p.cb + (long long)g * p.k * 6;
+      q.cb_res = p.k_res ? p.cb_res + (long long)g * p.k_res * 6 : nullptr;
+      q.idx = p.idx + (long long)(v_lo >> 3) * 12;
+      q.idx_res = p.k_res ? p.idx_res + (long long)(v_lo >> 3) * p.bits_res : nullptr;
+      const int col_lo = g ? p.n_out + v_lo * 6 : 0;
+      if (g) { q.n_out = 0; q.Q = 0; q.k_out = 0; q.bits_out = 0; q.cb_out = nullptr; q.idx_out = nullptr; q.stride_out = 0; }
+      q.in_features = min(p.in_features, p.n_out + (v_lo + q.P) * 6) - col_lo;
+      const int rc = launch_dequant_fast(q, W + col_lo, ldw, s);
+      if (rc != VQ_OK) return g == 0 ? rc : (rc == VQ_ERR_UNSUPPORTED ? VQ_ERR_HIP : rc);
+    }
+    return VQ_OK;
+  }
   DqPlan plan{};
   unsigned offb = 4096u * 16u;
   plan.lds_res = offb; offb += p.k_res ? (1u << p.bits_res) * 16u : 0u;

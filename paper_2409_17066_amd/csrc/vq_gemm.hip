@@ -33,10 +33,11 @@ __device__ __forceinline__ void restore_run_generic(const Params &p, int o, int 
         const int pp = cc / p.v;
         j = cc - pp * p.v; len = p.v;
         unsigned i = min(load_index(p.idx + (long long)o * p.stride, pp, p.bits), (unsigned)p.k - 1u);
-        e = p.cb + (long long)i * p.v;
+        const long long group = pp / p.Pg;
+        e = p.cb + (group * p.k + i) * p.v;
         if (p.k_res) {
           unsigned r = min(load_index(p.idx_res + (long long)o * p.stride_res, pp, p.bits_res), (unsigned)p.k_res - 1u);
-          er = p.cb_res + (long long)r * p.v;
+          er = p.cb_res + (group * p.k_res + r) * p.v;
         }
       }
     }

@@ -27,10 +27,11 @@ __global__ __launch_bounds__(256) void gemv_generic_kernel(Params p, const __hal
     } else {
       const int pp = slot - p.Q;
       unsigned i = min(load_index(p.idx + (long long)o * p.stride, pp, p.bits), (unsigned)p.k - 1u);
-      e = p.cb + (long long)i * p.v;
+      const long long group = pp / p.Pg;
+      e = p.cb + (group * p.k + i) * p.v;
       if (p.k_res) {
         unsigned r = min(load_index(p.idx_res + (long long)o * p.stride_res, pp, p.bits_res), (unsigned)p.k_res - 1u);
-        er = p.cb_res + (long long)r * p.v;
+        er = p.cb_res + (group * p.k_res + r) * p.v;
       }
       c0 = p.n_out + pp * p.v; len = min(p.v, p.in_features - c0);
     }
@@ -68,14 +69,15 @@ static bool force_generic() { return forced_kernel() == 'g'; }
 int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
   // Matrix-core kernel: one launch for any batch, at about the cost of a batch-1 launch of the dot-product
   // kernels; those are still a little faster for one row (and for two rows of a layer with few output rows
-  // per compute unit), so they keep these cases.
+  // per compute unit), so they keep these cases.  Layers with codebook groups always go to the matrix-core kernel:
+  // it is the one that swaps the tables in LDS group by group.
   const bool fast = !force_generic() && gemv_fast_applicable(p, x, ldx);
   const bool many_rows = p.out_features > 16 * 256;
-  if (fast && forced_kernel() != 'd' && (batch >= 3 || (batch == 2 && many_rows) || forced_kernel() == 'm')) {
+  if (fast && forced_kernel() != 'd' && (batch >= 3 || (batch == 2 && many_rows) || forced_kernel() == 'm' || p.n_groups > 1)) {
     const int rc = launch_gemv_mfma(p, x, ldx, batch, y, ldy, s);
     if (rc != VQ_ERR_UNSUPPORTED) return rc;
   }
-  if (fast) {
+  if (fast && p.n_groups == 1) {
     // batch rows go in groups of 4, 2 or 1; every group streams the indices once
     int done = 0, rc = VQ_OK;
     int g_max = 4;                      // largest group the layer's plan admits (found on the first group)

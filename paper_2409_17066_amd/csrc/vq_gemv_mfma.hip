@@ -17,6 +17,10 @@
 // words and the next pass's activations are loaded one pass ahead.  Each wave ends a chunk with a
 // 16 x 16 partial per block; partials meet in LDS, one wave per block adds them up and applies
 // y = scale * sum(d x) + bias * sum(x).  sum(x) comes from one more MFMA per pass against all-ones rows.
+//
+// Codebook groups (Sec. 3.1: every range of columns has tables of its own): the workgroup walks its rows once per
+// group, with that group's tables in LDS and only that group's columns; the per-block sums stay in LDS, in
+// binary32, from one group to the next, and the last group applies scale and bias and stores.
 #include "vq_common.hpp"
 #include "vq_v6.hpp"
 #include <cstdlib>
@@ -43,6 +47,7 @@ struct MfmaPlan {
   unsigned x_bytes;              // bytes from x[0][0] to the end of the last batch row
   int y_wide;                    // y rows allow 8-byte stores
   unsigned lds_sb;               // scale | bias << 16 of the workgroup's rows
+  unsigned lds_yacc;             // grouped layers: binary32 sums of the groups so far, 1 KB per 16-row block
 };
 
 typedef _Float16 half8v __attribute__((ext_vector_type(8)));
@@ -57,7 +62,7 @@ __device__ __forceinline__ float4v mfma16(uint4v a, uint4v b, float4v c) {
 // instructions per gather (summed over the four SIMDs) and the LDS starves.  Hence: two instructions per
 // LDS address, activations loaded straight into MFMA operand registers, load addresses advanced by
 // additions, end-of-row masking only in the one column group that needs it.
-template <int RES_BITS, int MW, int NB>
+template <int RES_BITS, int MW, int NB, bool GROUPED>
 __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPlan plan, const __half *__restrict__ x, long long ldx,
                                                                 int batch, __half *__restrict__ y, long long ldy) {
   typedef Layout<RES_BITS> LY;
@@ -100,16 +105,6 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
   const bool token_on = n < batch;
   const unsigned xrow = token_on ? (unsigned)((long long)n * ldx * 2) : n == 15 ? 0u : 0x80000000u;
 
-  // passes in which this wave has vectors: a prefix 0 .. my_passes-1 (pass p: group p * MW + wv of 32 vectors)
-  const int wave_groups = (p.P + 31) >> 5;
-  const int my_passes = wave_groups > wv ? (wave_groups - wv + MW - 1) / MW : 0;
-  const int eff_passes = max(my_passes, 1);                                   // a wave without vectors still walks the chunks
-  const int out_groups = (p.Q + 31) >> 5;
-  const int my_out_passes = out_groups > wv ? (out_groups - wv + MW - 1) / MW : 0;
-  // a group whose 192 columns (plus the two halves the last 16-byte load overshoots) end inside the row needs no masking
-  const int clean_groups = (p.in_features - p.n_out - 2) / 192;              // groups 0 .. clean_groups-1 are clean
-  const int last_clean_pass = clean_groups - 1 - wv >= 0 ? (clean_groups - 1 - wv) / MW : -1;
-
   uint3v win[R], wres[RES_BITS == 12 ? R : 1];   // index words, PA passes deep
   uint2v wres8[RES_BITS == 8 ? R : 1];
   uint4v bxs[XS][VPL];                           // B operands (activations) of the current and of the next XD passes
@@ -124,17 +119,47 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
 #pragma unroll
     for (int u = 0; u < VPL; ++u) bxs[i][u] = uint4v{0u, 0u, 0u, 0u};
 
+  const uint4v ones = {0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0u};
+  float4v acc[NB];
+  // sum of each token's activations over this wave's columns, kept in LDS (slot [wave][token], touched by this wave only
+  // until the first chunk's barrier): a register accumulator would stay allocated through the whole kernel
+  float *xs_part = reinterpret_cast<float *>(lds + plan.lds_xs);       // [MW][16]
+  if (g == 0) xs_part[wv * 16 + n] = 0.0f;
+  int buf = 0;
+
+  const int n_groups = GROUPED ? p.n_groups : 1;
+  for (int grp = 0; grp < n_groups; ++grp) {
+  // ---- this codebook group's vectors [v_lo, v_lo + v_n) and columns [col_lo, col_hi) of every row
+  const int v_lo = GROUPED ? grp * p.Pg : 0;                                  // a multiple of 8: a dword boundary in the streams
+  const int v_n = GROUPED ? min(p.Pg, p.P - v_lo) : p.P;
+  const int col_lo = p.n_out + v_lo * 6;
+  const int col_hi = GROUPED ? min(p.in_features, col_lo + v_n * 6) : p.in_features;
+  const unsigned gb_main = (unsigned)(v_lo >> 3) * 12u, gb_res = (unsigned)(v_lo >> 3) * (RES_BITS == 8 ? 8u : 12u);
+  // passes in which this wave has vectors: a prefix 0 .. my_passes-1 (pass p: group p * MW + wv of 32 vectors)
+  const int wave_groups = (v_n + 31) >> 5;
+  const int my_passes = wave_groups > wv ? (wave_groups - wv + MW - 1) / MW : 0;
+  const int eff_passes = max(my_passes, 1);                                   // a wave without vectors still walks the chunks
+  // ... and still fills its prefetch ring at the start, so that the start is one straight line of loads for every wave
+  // (a refill inside a branch costs a second set of registers); it loads what wave 0 loads, which is in range, and
+  // never looks at it
+  const int wl = my_passes > 0 ? wv : 0;
+  const int out_groups = grp == 0 ? (p.Q + 31) >> 5 : 0;                      // outlier columns go with the first group
+  const int my_out_passes = out_groups > wv ? (out_groups - wv + MW - 1) / MW : 0;
+  // a group whose 192 columns (plus the two halves the last 16-byte load overshoots) end before col_hi needs no masking
+  const int clean_groups = (col_hi - col_lo - 2) / 192;                       // groups 0 .. clean_groups-1 are clean
+  const int last_clean_pass = clean_groups - 1 - wv >= 0 ? (clean_groups - 1 - wv) / MW : -1;
+
   // The wave's passes form one sequence over all chunks; the loader runs PA passes ahead of the consumer.
   // Loader addresses: byte offset of the loader's pass inside a row, and of each block's row `n` in the streams.
   int lp = 0, lc = 0;
-  unsigned l_main = (unsigned)(wv * 4 + g) * 12u, l_res = (unsigned)(wv * 4 + g) * (RES_BITS == 8 ? 8u : 12u);
+  unsigned l_main = gb_main + (unsigned)(wl * 4 + g) * 12u, l_res = gb_res + (unsigned)(wl * 4 + g) * (RES_BITS == 8 ? 8u : 12u);
   unsigned lrow_main[NB], lrow_res[NB];
 #pragma unroll
   for (int b = 0; b < NB; ++b) { lrow_main[b] = (unsigned)(b * 16 + n) * st_main; lrow_res[b] = (unsigned)(b * 16 + n) * st_res; }
   auto advance_loader = [&]() {
     if (++lp == eff_passes) {
       lp = 0;
-      l_main = (unsigned)(wv * 4 + g) * 12u; l_res = (unsigned)(wv * 4 + g) * (RES_BITS == 8 ? 8u : 12u);
+      l_main = gb_main + (unsigned)(wl * 4 + g) * 12u; l_res = gb_res + (unsigned)(wl * 4 + g) * (RES_BITS == 8 ? 8u : 12u);
       // past the last chunk the loader starts over: what it loads then is never used, but stays an ordinary load
       const bool wrap = ++lc == n_chunks;
       if (wrap) lc = 0;
@@ -159,7 +184,7 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
   // activations of one pass: eight overlapping 16-byte loads, one per vector; the fourth dword belongs to the
   // next vector and meets the zero padding of the codebook entries
   auto issue_x = [&](uint4v (&bx)[VPL], int pass) {
-    const unsigned off = token_on ? xrow + ((unsigned)p.n_out + (unsigned)((pass * MW + wv) * 4 + g) * (VPL * 6u)) * 2u : xrow;
+    const unsigned off = token_on ? xrow + ((unsigned)col_lo + (unsigned)((pass * MW + wl) * 4 + g) * (VPL * 6u)) * 2u : xrow;
     async_load_b128_at<0>(bx[0], r_xa, off);  async_load_b128_at<12>(bx[1], r_xa, off);
     async_load_b128_at<24>(bx[2], r_xa, off); async_load_b128_at<36>(bx[3], r_xa, off);
     async_load_b128_at<48>(bx[4], r_xa, off); async_load_b128_at<60>(bx[5], r_xa, off);
@@ -168,25 +193,25 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
 
   {
     TableStage<RES_BITS, MW * 64> tables{};
-    tables.issue(p);
-    if (my_passes > 0) {
+    // (with groups: the thread id is made opaque in every round, or the table addresses derived from it would be kept
+    // in registers through the main loop for the next group)
+    unsigned tid = threadIdx.x;
+    if (GROUPED) asm volatile("" : "+v"(tid));
+    tables.issue(p, grp, grp == 0, tid);
 #pragma unroll
-      for (int j = 0; j < PA; ++j) {
+    for (int j = 0; j < PA; ++j) {
 #pragma unroll
-        for (int b = 0; b < NB; ++b) load_slot(j * NB + b, b);
-        advance_loader();
-      }
-#pragma unroll
-      for (int d = 0; d < XD; ++d) issue_x(bxs[d], d % my_passes);
-      VQ_STAMP(1);
-      wait_vmem_at_most<R * S + 8 * XD>();       // the tables are in; the index words may still be on their way
-    } else {
-      wait_vmem_at_most<0>();
+      for (int b = 0; b < NB; ++b) load_slot(j * NB + b, b);
+      advance_loader();
     }
-    tables.store(p, lds, plan.lds_out);
+#pragma unroll
+    for (int d = 0; d < XD; ++d) issue_x(bxs[d], d % eff_passes);
+    VQ_STAMP(1);
+    wait_vmem_at_most<R * S + 8 * XD>();         // the tables are in; the index words may still be on their way
+    tables.store(p, lds, plan.lds_out, grp == 0, tid);
   }
   // scale and bias of the workgroup's rows, one dword per row, for the reductions at the chunk ends
-  for (int r = (int)threadIdx.x; r < plan.rows_per_wg; r += MW * 64) {
+  for (int r = (int)threadIdx.x; r < (grp == 0 ? plan.rows_per_wg : 0); r += MW * 64) {
     const unsigned short sc = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r_scale, (unsigned)(row0 + r) * 2u, 0, 0);
     const unsigned short bi = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r_bias, (unsigned)(row0 + r) * 2u, 0, 0);
     *reinterpret_cast<unsigned *>(lds + plan.lds_sb + (unsigned)r * 4u) = (unsigned)sc | ((unsigned)bi << 16);
@@ -198,13 +223,7 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
   // far has to be in first.
   wait_vmem_at_most<0>();
 
-  const uint4v ones = {0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0u};
-  float4v acc[NB];
-  // sum of each token's activations over this wave's columns, kept in LDS (slot [wave][token], touched by this wave only
-  // until the first chunk's barrier): a register accumulator would stay allocated through the whole kernel
-  float *xs_part = reinterpret_cast<float *>(lds + plan.lds_xs);       // [MW][16]
-  if (g == 0) xs_part[wv * 16 + n] = 0.0f;
-  int buf = 0, c = 0, pass = 0;
+  int c = 0, pass = 0;
   while (c < n_chunks) {
 #pragma unroll
     for (int j = 0; j < PA; ++j) {
@@ -269,12 +288,12 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
 #pragma unroll
           for (int u = 0; u < VPL; ++u) settle(bx[u]);
           if (pass > last_clean_pass) {          // the group that holds the end of the row: zero what lies past it
-            const int col = p.n_out + ((pass * MW + wv) * 4 + g) * (VPL * 6);
+            const int col = col_lo + ((pass * MW + wv) * 4 + g) * (VPL * 6);
 #pragma unroll
             for (int u = 0; u < VPL; ++u) {
-              bx[u].x = col + 6 * u < p.in_features ? bx[u].x : 0u;           // in_features is even
-              bx[u].y = col + 6 * u + 2 < p.in_features ? bx[u].y : 0u;
-              bx[u].z = col + 6 * u + 4 < p.in_features ? bx[u].z : 0u;
+              bx[u].x = col + 6 * u < col_hi ? bx[u].x : 0u;                  // col_lo and col_hi are even
+              bx[u].y = col + 6 * u + 2 < col_hi ? bx[u].y : 0u;
+              bx[u].z = col + 6 * u + 4 < col_hi ? bx[u].z : 0u;
               bx[u].w = 0u;
             }
           }
@@ -341,6 +360,12 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
             float4v s = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
             for (int w = 0; w < MW; ++w) s += *reinterpret_cast<const float4v *>(pbase + (unsigned)(wv * MW + w) * 1024u + lane * 16u);
+            // sums of the groups so far: this lane of this wave is the only one that ever touches its slot
+            float4v *ya = reinterpret_cast<float4v *>(lds + plan.lds_yacc + (unsigned)((c * NB + wv) * 64 + lane) * 16u);
+            if (GROUPED && grp > 0) s += *ya;
+            if (GROUPED && grp + 1 < n_groups) {
+              *ya = s;
+            } else {
             float xsum = 0.0f;
 #pragma unroll
             for (int w = 0; w < MW; ++w) xsum += xs_part[w * 16 + n];
@@ -367,6 +392,7 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
                   if (ep_o + r < p.out_features) dst[r] = out[r];
               }
             }
+            }
           }
           VQ_STAMP(6);
           if (plan.part_bufs == 1) lds_barrier(); else buf ^= 1;
@@ -376,6 +402,10 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
         }
       }
     }
+  }
+  // Loads of the loader's run past the last chunk are still on their way; they must be in before the next group
+  // refills the same registers from its own start.
+  if (GROUPED) wait_vmem_at_most<0>();
   }
 }
 
@@ -390,11 +420,11 @@ int cu_count() {
   return g_cu_count;
 }
 
-template <int RES_BITS, int MW, int NB>
+template <int RES_BITS, int MW, int NB, bool GROUPED>
 int launch_one(const Params &p, const MfmaPlan &plan, unsigned lds_bytes, unsigned grid, const __half *x, long long ldx, int batch,
                __half *y, long long ldy, hipStream_t s) {
   static bool configured = false;
-  auto kernel = gemv_v6_mfma_kernel<RES_BITS, MW, NB>;
+  auto kernel = gemv_v6_mfma_kernel<RES_BITS, MW, NB, GROUPED>;
   if (!configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
       return VQ_ERR_HIP;
@@ -432,13 +462,18 @@ int launch_gemv_mfma(const Params &p, const __half *x, long long ldx, int batch,
   plan.rows_per_wg = blocks_per_wg * 16;
   const unsigned grid = (unsigned)((blocks_total + blocks_per_wg - 1) / blocks_per_wg);
   plan.lds_sb = off; off += (unsigned)plan.rows_per_wg * 4u;
+  const bool grouped = p.n_groups > 1;
+  if (grouped && (p.Pg & 7)) return VQ_ERR_UNSUPPORTED;   // a group must start on a dword of the 12- and 8-bit streams
+  plan.lds_yacc = off; off += grouped ? (unsigned)blocks_per_wg * 1024u : 0u;
   plan.lds_part = off;
   if (off + MW * 1024u > lds_cap) return VQ_ERR_UNSUPPORTED;
   const int fit = (int)((lds_cap - off) / (MW * 1024u));                 // 16-row partial blocks that fit
   // Blocks per chunk: as many as the kernel's 256 registers allow -- four, or three with a residual index stream in the
   // prefetch ring.  More would spill, which these kernels must not (see the build script).
   static const int nb_cap = [] { const char *e = getenv("VQ_MFMA_NB"); return e ? atoi(e) : NBMAX; }();
-  plan.nb = min(min(min(rb ? 3 : NBMAX, nb_cap), blocks_per_wg), fit);
+  // (with codebook groups one fewer: the group loop costs registers of its own)
+  const int nb_regs = grouped ? (rb == 12 ? 2 : 3) : (rb ? 3 : NBMAX);
+  plan.nb = min(min(min(nb_regs, nb_cap), blocks_per_wg), fit);
   if (plan.nb < 1) return VQ_ERR_UNSUPPORTED;
   plan.part_bufs = (fit >= 2 * plan.nb && blocks_per_wg > plan.nb) ? 2 : 1;
   off += (unsigned)(plan.part_bufs * plan.nb) * (MW * 1024u);
@@ -449,7 +484,9 @@ int launch_gemv_mfma(const Params &p, const __half *x, long long ldx, int batch,
   plan.x_bytes = (unsigned)x_bytes;
   plan.y_wide = ((reinterpret_cast<uintptr_t>(y) & 7) == 0 && (ldy & 3) == 0) ? 1 : 0;
 #define VQ_CASE(RBITS, NBLK) \
-  if (rb == RBITS && plan.nb == NBLK) return launch_one<RBITS, MW, NBLK>(p, plan, off, grid, x, ldx, batch, y, ldy, s);
+  if (rb == RBITS && plan.nb == NBLK && !grouped) return launch_one<RBITS, MW, NBLK, false>(p, plan, off, grid, x, ldx, batch, y, ldy, s); \
+  if (rb == RBITS && plan.nb == NBLK && grouped && NBLK <= (RBITS == 12 ? 2 : 3)) \
+    return launch_one<RBITS, MW, (NBLK <= (RBITS == 12 ? 2 : 3) ? NBLK : 1), true>(p, plan, off, grid, x, ldx, batch, y, ldy, s);
   VQ_CASE(0, 1) VQ_CASE(0, 2) VQ_CASE(0, 3) VQ_CASE(0, 4)
   VQ_CASE(8, 1) VQ_CASE(8, 2) VQ_CASE(8, 3)
   VQ_CASE(12, 1) VQ_CASE(12, 2) VQ_CASE(12, 3)

@@ -187,30 +187,31 @@ template <int RES_BITS, int T> struct TableStage {
   static constexpr int GROUPS = 1024 / T;       // groups of 4 entries (48 bytes) per thread and table of 4096
   uint4v m[GROUPS][3], r[RES_BITS == 12 ? GROUPS : 1][3], o[2048 / T];
 
-  __device__ __forceinline__ void issue(const Params &p) {
-    const uint4v rm = scalar_rsrc(p.cb, (unsigned)p.k * 12u);
+  // `group` selects the main and residual tables of one codebook group; `outliers` = 0 leaves the outlier table out
+  __device__ __forceinline__ void issue(const Params &p, int group = 0, bool outliers = true, unsigned tid = threadIdx.x) {
+    const uint4v rm = scalar_rsrc(p.cb + (long long)group * p.k * 6, (unsigned)p.k * 12u);
 #pragma unroll
     for (int gi = 0; gi < GROUPS; ++gi) {
-      const unsigned off = (threadIdx.x + gi * T) * 48u;
+      const unsigned off = (tid + gi * T) * 48u;
       async_load_b128_at<0>(m[gi][0], rm, off); async_load_b128_at<16>(m[gi][1], rm, off); async_load_b128_at<32>(m[gi][2], rm, off);
     }
     if (RES_BITS == 12) {
-      const uint4v rr = scalar_rsrc(p.cb_res, (unsigned)p.k_res * 12u);
+      const uint4v rr = scalar_rsrc(p.cb_res + (long long)group * p.k_res * 6, (unsigned)p.k_res * 12u);
 #pragma unroll
       for (int gi = 0; gi < GROUPS; ++gi) {
-        const unsigned off = (threadIdx.x + gi * T) * 48u;
+        const unsigned off = (tid + gi * T) * 48u;
         async_load_b128_at<0>(r[gi][0], rr, off); async_load_b128_at<16>(r[gi][1], rr, off); async_load_b128_at<32>(r[gi][2], rr, off);
       }
     }
     if (RES_BITS == 8) {                         // 256 entries: every wave loads them, the first one stores them
-      const uint4v rr = scalar_rsrc(p.cb_res, (unsigned)p.k_res * 12u);
-      const unsigned off = (threadIdx.x & 63u) * 48u;
+      const uint4v rr = scalar_rsrc(p.cb_res + (long long)group * p.k_res * 6, (unsigned)p.k_res * 12u);
+      const unsigned off = (tid & 63u) * 48u;
       async_load_b128_at<0>(r[0][0], rr, off); async_load_b128_at<16>(r[0][1], rr, off); async_load_b128_at<32>(r[0][2], rr, off);
     }
-    if (p.Q) {                                   // 4096 entries of 8 bytes
+    if (p.Q && outliers) {                       // 4096 entries of 8 bytes
       const uint4v ro = scalar_rsrc(p.cb_out, (unsigned)p.k_out * 8u);
 #pragma unroll
-      for (int i = 0; i < 2048 / T; ++i) async_load_b128_at<0>(o[i], ro, (threadIdx.x + i * T) * 16u);
+      for (int i = 0; i < 2048 / T; ++i) async_load_b128_at<0>(o[i], ro, (tid + i * T) * 16u);
     }
   }
 
@@ -225,20 +226,20 @@ template <int RES_BITS, int T> struct TableStage {
   }
 
   // after a wait that covers the loads of issue()
-  __device__ __forceinline__ void store(const Params &p, unsigned char *lds, unsigned lds_out) {
+  __device__ __forceinline__ void store(const Params &p, unsigned char *lds, unsigned lds_out, bool outliers = true, unsigned tid = threadIdx.x) {
     typedef Layout<RES_BITS> L;
 #pragma unroll
-    for (int gi = 0; gi < GROUPS; ++gi) put4(lds + L::MAIN_OFF, (threadIdx.x + gi * T) * 4u, m[gi]);
+    for (int gi = 0; gi < GROUPS; ++gi) put4(lds + L::MAIN_OFF, (tid + gi * T) * 4u, m[gi]);
     if (RES_BITS == 12) {
 #pragma unroll
-      for (int gi = 0; gi < GROUPS; ++gi) put4(lds + L::RES_ADD, (threadIdx.x + gi * T) * 4u, r[gi]);
+      for (int gi = 0; gi < GROUPS; ++gi) put4(lds + L::RES_ADD, (tid + gi * T) * 4u, r[gi]);
     }
-    if (RES_BITS == 8 && threadIdx.x < 64) put4(lds, threadIdx.x * 4u, r[0]);
-    if (p.Q) {
+    if (RES_BITS == 8 && tid < 64) put4(lds, tid * 4u, r[0]);
+    if (p.Q && outliers) {
 #pragma unroll
       for (int i = 0; i < 2048 / T; ++i) {
         settle(o[i]);
-        *reinterpret_cast<uint4v *>(lds + lds_out + (threadIdx.x + i * T) * 16u) = o[i];
+        *reinterpret_cast<uint4v *>(lds + lds_out + (tid + i * T) * 16u) = o[i];
       }
     }
   }

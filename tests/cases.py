@@ -31,6 +31,21 @@ SMALL = {
     "v6_passes_res8": dict(out_features=37, in_features=9100, v=6, k=4096, k_res=256),
     # in_features a multiple of 256: vq_gemm's restore-then-multiply route (with a workspace) takes any layer
     "v6_dense_gemm": dict(out_features=203, in_features=1024, v=6, k=4096, k_res=4096, n_outlier_cols=16, v_out=4, k_out=4096),
+    # codebook groups: a table (and residual table) per range of vectors.  Group sizes that are multiples of 8 vectors run
+    # on the fast kernels (ragged last group, groups narrower than one pass of the eight waves, several chunks of rows
+    # whose sums wait in LDS for the next group, groups longer than the prefetch ring); the others on the generic ones
+    "grp_v6": dict(out_features=261, in_features=1030, v=6, k=4096, group_vectors=64),
+    "grp_v6_res12": dict(out_features=133, in_features=1000, v=6, k=4096, k_res=4096, group_vectors=40),
+    "grp_v6_res8_outlier": dict(out_features=150, in_features=1207, v=6, k=4096, k_res=256, n_outlier_cols=24, v_out=4, k_out=4096, group_vectors=64),
+    "grp_v6_chunks": dict(out_features=20501, in_features=198, v=6, k=4096, group_vectors=16),
+    "grp_v6_chunks_res12": dict(out_features=12303, in_features=390, v=6, k=4096, k_res=4096, group_vectors=24),
+    "grp_v6_passes": dict(out_features=40, in_features=7000, v=6, k=4096, k_res=4096, group_vectors=600),
+    "grp_v6_sixteen": dict(out_features=300, in_features=4096, v=6, k=4096, group_vectors=48),
+    "grp_v6_small_tables": dict(out_features=70, in_features=391, v=6, k=3000, k_res=200, group_vectors=8),
+    "grp_v6_unaligned": dict(out_features=70, in_features=800, v=6, k=4096, k_res=256, group_vectors=20),
+    "grp_v6_dense_gemm": dict(out_features=203, in_features=1024, v=6, k=4096, k_res=4096, n_outlier_cols=16, v_out=4, k_out=4096, group_vectors=56),
+    "grp_v8": dict(out_features=200, in_features=768, v=8, k=65536, group_vectors=40),
+    "grp_odd": dict(out_features=37, in_features=203, v=5, k=37, k_res=11, n_outlier_cols=9, v_out=3, k_out=5, group_vectors=7),
 }
 
 

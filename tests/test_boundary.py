@@ -46,8 +46,17 @@ def test_valid_descriptor_passes():
                                 idx_out_row_stride=16)) == vq.VQ_OK
 
 
+def test_codebook_groups_in_the_descriptor():
+    assert vq.vq_validate(_desc(group_vectors=2)) == vq.VQ_OK               # 5 vectors: groups of 2, 2, 1
+    assert vq.vq_validate(_desc(group_vectors=1000)) == vq.VQ_OK            # one group
+    # the layout that ends with `bias` is still taken, as a layer with one group (whatever follows it in memory)
+    old = vq.vq_layer_desc.group_vectors.offset
+    assert vq.vq_validate(_desc(struct_size=old, group_vectors=-5)) == vq.VQ_OK
+
+
 @pytest.mark.parametrize("kw,status", [
     (dict(struct_size=4), vq.VQ_ERR_SHAPE),
+    (dict(group_vectors=-1), vq.VQ_ERR_SHAPE),
     (dict(out_features=0), vq.VQ_ERR_SHAPE),
     (dict(in_features=0), vq.VQ_ERR_SHAPE),
     (dict(v=0), vq.VQ_ERR_SHAPE), (dict(v=17), vq.VQ_ERR_SHAPE),
