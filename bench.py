@@ -300,6 +300,18 @@ def detail(vq, s, np, torch, use_graph, skip):
     moved = W1.numel() * 2 + L1.algorithmic_bytes(1)
     out.append({"op": "vq_dequant", "cfg": 1, "us": round(sec * 1e6, 1), "GB/s": round(moved / sec / 1e9, 1),
                 "frac_hbm_peak": round(moved / sec / 1e9 / HBM_PEAK_GBPS, 4)})
+    del dl1, W1
+    # codebook groups on the headline shape: "group num" 4 and 16 of the paper's parameter table, as group sizes
+    # rounded up to 8 vectors
+    for group_vectors in (176, 48):
+        Lg = s.make_layer(1, "up", L1.out_features, L1.in_features, 6, 4096, group_vectors=group_vectors)
+        for batch in (1, 16):
+            r = bench_gemv(vq, Lg, s.make_activations(1, Lg, batch), steps, warmup, use_graph)
+            sec = r["event_s"] / steps
+            alg = Lg.algorithmic_bytes(batch)
+            out.append({"op": "vq_gemv", "cfg": "1 with codebook groups", "groups": Lg.n_groups, "group_vectors": group_vectors,
+                        "batch": batch, "us": round(sec * 1e6, 3), "GB/s": round(alg / sec / 1e9, 1),
+                        "frac_hbm_peak": round(alg / sec / 1e9 / HBM_PEAK_GBPS, 4)})
     return out
 
 
