@@ -251,6 +251,32 @@ def detail(vq, s, np, torch, use_graph, skip):
                 out.append({"op": "vq_gemv x7 (whole cfg2 layer: 4 q-shaped, 2 gate-shaped, down; sum of the per-call times)",
                             "cfg": 2, "batch": batch, "us": round(total_us, 2), "GB/s": round(alg / total_us / 1e3, 1),
                             "frac_hbm_peak": round(alg / total_us / 1e3 / HBM_PEAK_GBPS, 4)})
+    # the same decoder layer as a chain on one stream: q, k, v in one vq_gemv_multi launch, o, gate and up in one launch,
+    # down -- four launches instead of seven, every layer's index streams rotated like the single calls above
+    layers2 = {L.name: L for _, L in s.config_layers(2)}
+    rots = {n: Rotation(vq, L, min_bytes=ROTATE_BYTES // 4) for n, L in layers2.items()}
+    for batch in s.CONFIGS[2]["rows"]:
+        xs = {n: torch.from_numpy(s.make_activations(2, layers2[n], batch)).cuda() for n in ("q", "o", "gate", "down")}
+        ys = {n: torch.empty((batch, L.out_features), dtype=torch.float16, device="cuda") for n, L in layers2.items()}
+        alg = sum(L.algorithmic_bytes(batch) for L in layers2.values())
+        for fused in (True, False):
+            def chain(i):
+                st = torch.cuda.current_stream().cuda_stream
+                for group in ((("q", "k", "v"), ("o",), ("gate", "up"), ("down",)) if fused else tuple((n,) for n in layers2)):
+                    x = xs[{"k": "q", "v": "q", "up": "gate"}.get(group[0], group[0])]
+                    descs = [rots[n].descs[i % rots[n].copies] for n in group]
+                    rc = vq.vq_gemv_multi(descs, x.data_ptr(), x.stride(0), batch, [ys[n].data_ptr() for n in group],
+                                          [ys[n].stride(0) for n in group], st)
+                    if rc != 0:
+                        raise vq.VQError(rc, "vq_gemv_multi")
+            n_steps = 100
+            wall, ev = timed(chain, n_steps, 10, use_graph)
+            us = ev / n_steps * 1e6
+            out.append({"op": "cfg2 decoder layer as a chain of %d launches (%s)" % (4 if fused else 7,
+                                                                                  "qkv and gate+up fused by vq_gemv_multi" if fused else "one vq_gemv per projection"),
+                        "cfg": 2, "batch": batch, "us": round(us, 2), "GB/s": round(alg / us / 1e3, 1),
+                        "frac_hbm_peak": round(alg / us / 1e3 / HBM_PEAK_GBPS, 4)})
+    del rots, xs, ys
     # prefill GEMM and dequant on the 8192 x 8192, v=8, k=65536 layer
     _, L4 = next(s.config_layers(4))
     dl = vq.DeviceLayer(L4)

@@ -99,6 +99,19 @@ int vq_dequant(const vq_layer_desc *desc, void *W, int64_t ldw, void *hip_stream
 int vq_gemv(const vq_layer_desc *desc, const void *x, int64_t ldx, int32_t batch,
             void *y, int64_t ldy, void *hip_stream);
 
+/* vq_gemv for several layers that read the same activations -- the query, key and value projections of a
+ * decoder layer, or its gate and up projections -- as one launch: y[i][b][o] = sum_c W_i[o][c] * x[b][c] for
+ * i < n_layers, each result what vq_gemv's matrix-core kernel gives for that layer alone, bit for bit.
+ * A decode-sized product is bound by launch and start-up time, not by its streaming time (the paper's section
+ * on inference throughput reports the same for its own kernels), so fusing the launches is where the time goes.
+ * descs: host array of n_layers descriptor pointers, all with the same in_features; y, ldy: host arrays of
+ * n_layers device pointers / leading dimensions (ldy[i] >= out_features of layer i); the outputs must not overlap
+ * each other or x.  n_layers in [1, 8].  Layers that the fused kernel does not take together (different residual
+ * kinds, codebook groups, shapes outside the fast kernels) are launched one after the other on the same stream:
+ * the results are the same.  Errors as for vq_gemv; nothing is launched when any argument is rejected.       */
+int vq_gemv_multi(const vq_layer_desc *const *descs, int32_t n_layers, const void *x, int64_t ldx, int32_t batch,
+                  void *const *y, const int64_t *ldy, void *hip_stream);
+
 /* Prompt-phase product for many tokens: Y[t][o] = sum_c W[o][c] * X[t][c] on the FP16 matrix cores,
  * binary32 accumulation, fp16 result (the paper's prompt phase, its section on inference throughput:
  * restore the weights, then multiply).  X: fp16 [tokens][ldx], 16-byte aligned, ldx % 8 == 0; Y: fp16

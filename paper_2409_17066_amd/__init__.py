@@ -53,6 +53,8 @@ def load():
     L.vq_validate.argtypes = [P]
     L.vq_dequant.argtypes = [P, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
     L.vq_gemv.argtypes = [P, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+    L.vq_gemv_multi.argtypes = [ctypes.POINTER(P), ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32,
+                                ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_int64), ctypes.c_void_p]
     L.vq_gemm.argtypes = [P, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
                           ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     L.vq_gemm_workspace_bytes.argtypes = [P, ctypes.c_int32]
@@ -62,13 +64,13 @@ def load():
     L.vq_status_string.argtypes = [ctypes.c_int]
     L.vq_status_string.restype = ctypes.c_char_p
     L.vq_version.restype = ctypes.c_int
-    for f in (L.vq_validate, L.vq_dequant, L.vq_gemv, L.vq_gemm):
+    for f in (L.vq_validate, L.vq_dequant, L.vq_gemv, L.vq_gemv_multi, L.vq_gemm):
         f.restype = ctypes.c_int
     _lib = L
     return L
 
 
-EXPORTED = ["vq_validate", "vq_dequant", "vq_gemv", "vq_gemm", "vq_gemm_workspace_bytes", "vq_gemm_fast_workspace_bytes",
+EXPORTED = ["vq_validate", "vq_dequant", "vq_gemv", "vq_gemv_multi", "vq_gemm", "vq_gemm_workspace_bytes", "vq_gemm_fast_workspace_bytes",
             "vq_status_string", "vq_version"]
 
 
@@ -83,6 +85,16 @@ def vq_dequant(desc, W_ptr, ldw, stream=None):
 
 def vq_gemv(desc, x_ptr, ldx, batch, y_ptr, ldy, stream=None):
     return load().vq_gemv(ctypes.byref(desc) if desc is not None else None, x_ptr, ldx, batch, y_ptr, ldy, stream)
+
+
+def vq_gemv_multi(descs, x_ptr, ldx, batch, y_ptrs, ldys, stream=None):
+    """descs: sequence of vq_layer_desc; y_ptrs, ldys: sequences of device pointers (ints) and leading dimensions."""
+    n = len(descs)
+    P = ctypes.POINTER(vq_layer_desc)
+    d = (P * n)(*[ctypes.pointer(x) for x in descs]) if descs is not None else None
+    ys = (ctypes.c_void_p * n)(*y_ptrs) if y_ptrs is not None else None
+    ld = (ctypes.c_int64 * n)(*ldys) if ldys is not None else None
+    return load().vq_gemv_multi(d, n, x_ptr, ldx, batch, ys, ld, stream)
 
 
 def vq_gemm(desc, X_ptr, ldx, tokens, Y_ptr, ldy, workspace_ptr=None, workspace_bytes=0, stream=None):
@@ -159,6 +171,19 @@ def gemv(dl: DeviceLayer, x, out=None):
     if rc != VQ_OK:
         raise VQError(rc, "vq_gemv")
     return y
+
+
+def gemv_multi(dls, x, outs=None):
+    """Several layers on the same x (fp16 [batch][>=in] device tensor) in one call -> list of fp16 [batch][out_i]."""
+    import torch
+    assert x.is_cuda and x.dtype == torch.float16 and x.dim() == 2 and x.stride(1) == 1
+    ys = outs if outs is not None else [torch.empty((x.shape[0], dl.layer.out_features), dtype=torch.float16, device="cuda")
+                                        for dl in dls]
+    rc = vq_gemv_multi([dl.desc for dl in dls], x.data_ptr(), x.stride(0), x.shape[0], [y.data_ptr() for y in ys],
+                       [y.stride(0) for y in ys], _stream())
+    if rc != VQ_OK:
+        raise VQError(rc, "vq_gemv_multi")
+    return ys
 
 
 def gemm(dl: DeviceLayer, X, out=None, workspace=None):

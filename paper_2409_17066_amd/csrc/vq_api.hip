@@ -93,6 +93,25 @@ extern "C" int vq_gemv(const vq_layer_desc *desc, const void *x, int64_t ldx, in
                          static_cast<hipStream_t>(hip_stream));
 }
 
+extern "C" int vq_gemv_multi(const vq_layer_desc *const *descs, int32_t n_layers, const void *x, int64_t ldx, int32_t batch,
+                             void *const *y, const int64_t *ldy, void *hip_stream) {
+  constexpr int MAX_LAYERS = 8;
+  if (!descs || !y || !ldy || !x) return VQ_ERR_NULL;
+  if (n_layers < 1 || n_layers > MAX_LAYERS || batch < 1 || batch > 16) return VQ_ERR_SHAPE;
+  vq::Params p[MAX_LAYERS];
+  __half *ys[MAX_LAYERS];
+  long long ldys[MAX_LAYERS];
+  for (int i = 0; i < n_layers; ++i) {
+    const int rc = vq::make_params(descs[i], &p[i]);
+    if (rc != VQ_OK) return rc;
+    if (!y[i]) return VQ_ERR_NULL;
+    if (p[i].in_features != p[0].in_features || ldx < p[i].in_features || ldy[i] < p[i].out_features) return VQ_ERR_SHAPE;
+    if (!aligned(x, 2) || !aligned(y[i], 2)) return VQ_ERR_ALIGNMENT;
+    ys[i] = static_cast<__half *>(y[i]); ldys[i] = ldy[i];
+  }
+  return vq::launch_gemv_multi(p, n_layers, static_cast<const __half *>(x), ldx, batch, ys, ldys, static_cast<hipStream_t>(hip_stream));
+}
+
 extern "C" size_t vq_gemm_workspace_bytes(const vq_layer_desc *desc, int32_t tokens) {
   vq::Params p;
   if (vq::make_params(desc, &p) != VQ_OK || tokens < 1) return 0;

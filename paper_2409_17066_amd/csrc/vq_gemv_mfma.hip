@@ -62,9 +62,10 @@ __device__ __forceinline__ float4v mfma16(uint4v a, uint4v b, float4v c) {
 // instructions per gather (summed over the four SIMDs) and the LDS starves.  Hence: two instructions per
 // LDS address, activations loaded straight into MFMA operand registers, load addresses advanced by
 // additions, end-of-row masking only in the one column group that needs it.
+// `wg` is the workgroup's number within its layer (a launch may hold the workgroups of several layers).
 template <int RES_BITS, int MW, int NB, bool GROUPED>
-__global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPlan plan, const __half *__restrict__ x, long long ldx,
-                                                                int batch, __half *__restrict__ y, long long ldy) {
+__device__ __forceinline__ void gemv_v6_mfma_body(const Params &p, const MfmaPlan &plan, const __half *__restrict__ x, long long ldx,
+                                                  int batch, __half *__restrict__ y, long long ldy, int wg) {
   typedef Layout<RES_BITS> LY;
   constexpr int RB = RES_BITS ? RES_BITS : 8;
   constexpr int PA = NB == 2 ? 4 : 2;                   // passes whose index words are in flight or in registers
@@ -78,12 +79,11 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
   constexpr int AFTER_SLOT = (R - 1) * S + 8 * PA, AFTER_X = XD * NB * S + (XD - 1) * 8;
   static_assert(AFTER_SLOT < 64, "vmcnt holds 6 bits");
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-  warm_kernel_arguments();
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = lane & 15, g = lane >> 4;       // A: row n of the block, vector group g.  B: token n.  D: token n, rows 4g..4g+3
   VQ_STAMP(0);
-  const int row0 = blockIdx.x * plan.rows_per_wg;
+  const int row0 = wg * plan.rows_per_wg;
   const int rows_here = min(p.out_features - row0, plan.rows_per_wg);
   const int n_blocks = (rows_here + 15) >> 4;
   const int n_chunks = (n_blocks + NB - 1) / NB;
@@ -409,6 +409,39 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
   }
 }
 
+template <int RES_BITS, int MW, int NB, bool GROUPED>
+__global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPlan plan, const __half *__restrict__ x, long long ldx,
+                                                                int batch, __half *__restrict__ y, long long ldy) {
+  warm_kernel_arguments();
+  gemv_v6_mfma_body<RES_BITS, MW, NB, GROUPED>(p, plan, x, ldx, batch, y, ldy, (int)blockIdx.x);
+}
+
+// Several layers that read the same activations (the query, key and value projections of a decoder layer; its gate
+// and up projections) in one launch: the launch and start-up cost of a decode-sized product (App. "Our Dequantization
+// Implementation", second phase) is several times its streaming time, so one launch for three layers costs about
+// what one layer costs.  Every workgroup belongs to one layer and runs the single-layer kernel on it.
+constexpr int MULTI_MAX = 8;
+struct MultiLayer {
+  Params p;
+  MfmaPlan plan;
+  __half *y;
+  long long ldy;
+};
+struct MultiArgs {
+  int n;
+  int first_wg[MULTI_MAX + 1];             // layer i owns workgroups [first_wg[i], first_wg[i + 1])
+  MultiLayer layer[MULTI_MAX];
+};
+
+template <int RES_BITS, int MW, int NB>
+__global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_multi_kernel(MultiArgs a, const __half *__restrict__ x, long long ldx, int batch) {
+  warm_kernel_arguments();
+  int i = 0;
+  while (i + 1 < a.n && (int)blockIdx.x >= a.first_wg[i + 1]) ++i;
+  const MultiLayer &l = a.layer[i];
+  gemv_v6_mfma_body<RES_BITS, MW, NB, false>(l.p, l.plan, x, ldx, batch, l.y, l.ldy, (int)blockIdx.x - a.first_wg[i]);
+}
+
 int g_cu_count = 0;
 
 int cu_count() {
@@ -447,8 +480,18 @@ extern "C" int vq_debug_read_profile_m(unsigned long long *dst, size_t count) {
 }
 #endif
 
-// Launch for batch 1..16.  The caller has checked gemv_fast_applicable().
-int launch_gemv_mfma(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
+namespace {
+
+struct Planned {
+  MfmaPlan plan;
+  unsigned lds_bytes, grid;
+  int rb;
+  bool grouped;
+};
+
+// Work split and LDS layout of one layer when every workgroup takes `blocks_per_wg` 16-row blocks.  nb_force > 0
+// fixes the blocks per chunk (several layers in one launch share one kernel instantiation).
+int make_plan(const Params &p, int batch, long long ldx, const __half *y, long long ldy, int blocks_per_wg, int nb_force, Planned *out) {
   MfmaPlan plan{};
   if (p.in_features < 64) return VQ_ERR_UNSUPPORTED;      // idle lanes load the first 100 bytes of the first activation row
   const int rb = p.k_res ? p.bits_res : 0;
@@ -457,10 +500,8 @@ int launch_gemv_mfma(const Params &p, const __half *x, long long ldx, int batch,
   plan.lds_xs = off; off += MW * 16u * 4u;
   const unsigned lds_cap = 160u * 1024u;
   const int blocks_total = (p.out_features + 15) / 16;
-  const int cus = cu_count();
-  const int blocks_per_wg = (blocks_total + cus - 1) / cus;
   plan.rows_per_wg = blocks_per_wg * 16;
-  const unsigned grid = (unsigned)((blocks_total + blocks_per_wg - 1) / blocks_per_wg);
+  out->grid = (unsigned)((blocks_total + blocks_per_wg - 1) / blocks_per_wg);
   plan.lds_sb = off; off += (unsigned)plan.rows_per_wg * 4u;
   const bool grouped = p.n_groups > 1;
   if (grouped && (p.Pg & 7)) return VQ_ERR_UNSUPPORTED;   // a group must start on a dword of the 12- and 8-bit streams
@@ -474,6 +515,7 @@ int launch_gemv_mfma(const Params &p, const __half *x, long long ldx, int batch,
   // (with codebook groups one fewer: the group loop costs registers of its own)
   const int nb_regs = grouped ? (rb == 12 ? 2 : 3) : (rb ? 3 : NBMAX);
   plan.nb = min(min(min(nb_regs, nb_cap), blocks_per_wg), fit);
+  if (nb_force > 0) { if (nb_force > plan.nb) return VQ_ERR_UNSUPPORTED; plan.nb = nb_force; }
   if (plan.nb < 1) return VQ_ERR_UNSUPPORTED;
   plan.part_bufs = (fit >= 2 * plan.nb && blocks_per_wg > plan.nb) ? 2 : 1;
   off += (unsigned)(plan.part_bufs * plan.nb) * (MW * 1024u);
@@ -483,10 +525,88 @@ int launch_gemv_mfma(const Params &p, const __half *x, long long ldx, int batch,
   if (ldx < 0 || x_bytes >= (1LL << 31) - (1 << 20)) return VQ_ERR_UNSUPPORTED;
   plan.x_bytes = (unsigned)x_bytes;
   plan.y_wide = ((reinterpret_cast<uintptr_t>(y) & 7) == 0 && (ldy & 3) == 0) ? 1 : 0;
+  out->plan = plan; out->lds_bytes = off; out->rb = rb; out->grouped = grouped;
+  return VQ_OK;
+}
+
+template <int RES_BITS, int NB>
+int launch_multi(const MultiArgs &a, unsigned lds_bytes, unsigned grid, const __half *x, long long ldx, int batch, hipStream_t s) {
+  static bool configured = false;
+  auto kernel = gemv_v6_mfma_multi_kernel<RES_BITS, MW, NB>;
+  if (!configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+      return VQ_ERR_HIP;
+    configured = true;
+  }
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(MW * 64), lds_bytes, s, a, x, ldx, batch);
+  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+}  // namespace
+
+// Launch for batch 1..16.  The caller has checked gemv_fast_applicable().
+int launch_gemv_mfma(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
+  const int blocks_total = (p.out_features + 15) / 16;
+  const int cus = cu_count();
+  Planned pl;
+  const int rc = make_plan(p, batch, ldx, y, ldy, (blocks_total + cus - 1) / cus, 0, &pl);
+  if (rc != VQ_OK) return rc;
+  const MfmaPlan &plan = pl.plan;
+  const int rb = pl.rb;
+  const bool grouped = pl.grouped;
+  const unsigned off = pl.lds_bytes, grid = pl.grid;
 #define VQ_CASE(RBITS, NBLK) \
   if (rb == RBITS && plan.nb == NBLK && !grouped) return launch_one<RBITS, MW, NBLK, false>(p, plan, off, grid, x, ldx, batch, y, ldy, s); \
   if (rb == RBITS && plan.nb == NBLK && grouped && NBLK <= (RBITS == 12 ? 2 : 3)) \
     return launch_one<RBITS, MW, (NBLK <= (RBITS == 12 ? 2 : 3) ? NBLK : 1), true>(p, plan, off, grid, x, ldx, batch, y, ldy, s);
+  VQ_CASE(0, 1) VQ_CASE(0, 2) VQ_CASE(0, 3) VQ_CASE(0, 4)
+  VQ_CASE(8, 1) VQ_CASE(8, 2) VQ_CASE(8, 3)
+  VQ_CASE(12, 1) VQ_CASE(12, 2) VQ_CASE(12, 3)
+#undef VQ_CASE
+  return VQ_ERR_UNSUPPORTED;
+}
+
+// n layers (2 .. MULTI_MAX) on the same activations in one launch.  VQ_ERR_UNSUPPORTED when the layers do not fit
+// one kernel instantiation (different residual kinds, codebook groups, different in_features) or one launch; the
+// caller then launches them one by one.  The caller has checked gemv_fast_applicable() for each.
+int launch_gemv_mfma_multi(const Params *ps, int n, const __half *x, long long ldx, int batch, __half *const *ys,
+                           const long long *ldys, hipStream_t s) {
+  if (n < 2 || n > MULTI_MAX) return VQ_ERR_UNSUPPORTED;
+  const int cus = cu_count();
+  long long blocks_all = 0;
+  for (int i = 0; i < n; ++i) {
+    if (ps[i].in_features != ps[0].in_features || ps[i].n_groups > 1) return VQ_ERR_UNSUPPORTED;
+    if ((ps[i].k_res ? ps[i].bits_res : 0) != (ps[0].k_res ? ps[0].bits_res : 0)) return VQ_ERR_UNSUPPORTED;
+    blocks_all += (ps[i].out_features + 15) / 16;
+  }
+  // every workgroup takes the same number of 16-row blocks of one layer: the smallest number with which all the
+  // workgroups run at once, one per compute unit
+  int b = (int)((blocks_all + cus - 1) / cus);
+  for (;; ++b) {
+    long long wgs = 0;
+    for (int i = 0; i < n; ++i) wgs += ((ps[i].out_features + 15) / 16 + b - 1) / b;
+    if (wgs <= cus) break;
+  }
+  MultiArgs a{};
+  Planned pl[MULTI_MAX];
+  int nb = NBMAX;
+  for (int pass = 0; pass < 2; ++pass) {                  // first the blocks per chunk every layer admits, then the plans with it
+    for (int i = 0; i < n; ++i) {
+      const int rc = make_plan(ps[i], batch, ldx, ys[i], ldys[i], b, pass ? nb : 0, &pl[i]);
+      if (rc != VQ_OK) return rc;
+      if (!pass) nb = min(nb, pl[i].plan.nb);
+    }
+  }
+  unsigned lds_bytes = 0;
+  a.n = n;
+  for (int i = 0; i < n; ++i) {
+    a.first_wg[i + 1] = a.first_wg[i] + (int)pl[i].grid;
+    a.layer[i].p = ps[i]; a.layer[i].plan = pl[i].plan; a.layer[i].y = ys[i]; a.layer[i].ldy = ldys[i];
+    lds_bytes = max(lds_bytes, pl[i].lds_bytes);
+  }
+  const unsigned grid = (unsigned)a.first_wg[n];
+  const int rb = pl[0].rb;
+#define VQ_CASE(RBITS, NBLK) if (rb == RBITS && nb == NBLK) return launch_multi<RBITS, NBLK>(a, lds_bytes, grid, x, ldx, batch, s);
   VQ_CASE(0, 1) VQ_CASE(0, 2) VQ_CASE(0, 3) VQ_CASE(0, 4)
   VQ_CASE(8, 1) VQ_CASE(8, 2) VQ_CASE(8, 3)
   VQ_CASE(12, 1) VQ_CASE(12, 2) VQ_CASE(12, 3)

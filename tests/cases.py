@@ -53,3 +53,32 @@ def small_layer(name):
     kw = dict(SMALL[name])
     return s.make_layer(300 + list(SMALL).index(name), name, kw.pop("out_features"), kw.pop("in_features"),
                         kw.pop("v"), kw.pop("k"), **kw)
+
+
+# Sets of layers that read the same activations, for vq_gemv_multi: name -> list of make_layer keyword arguments.
+MULTI = {
+    "qkv_v6": [dict(out_features=261, in_features=1030, v=6, k=4096), dict(out_features=70, in_features=1030, v=6, k=4096),
+               dict(out_features=133, in_features=1030, v=6, k=3000)],
+    "gate_up_res12": [dict(out_features=133, in_features=1000, v=6, k=4096, k_res=4096),
+                      dict(out_features=150, in_features=1000, v=6, k=4096, k_res=4096, with_bias=False)],
+    "res8_outlier_pair": [dict(out_features=150, in_features=1207, v=6, k=4096, k_res=256, n_outlier_cols=24, v_out=4, k_out=4096),
+                          dict(out_features=47, in_features=1207, v=6, k=4096, k_res=256)],
+    # many 16-row blocks per workgroup, different for each layer, ragged last blocks
+    "many_rows": [dict(out_features=20501, in_features=198, v=6, k=4096), dict(out_features=12303, in_features=198, v=6, k=4096),
+                  dict(out_features=5, in_features=198, v=6, k=4096)],
+    "eight_layers": [dict(out_features=40 + 16 * i, in_features=600, v=6, k=4096, k_res=256) for i in range(8)],
+    # sets that the fused kernel does not take together: they run one after the other
+    "mixed_residual_kinds": [dict(out_features=70, in_features=1000, v=6, k=4096), dict(out_features=70, in_features=1000, v=6, k=4096, k_res=4096)],
+    "with_groups": [dict(out_features=70, in_features=1000, v=6, k=4096, group_vectors=64), dict(out_features=33, in_features=1000, v=6, k=4096)],
+    "generic_shapes": [dict(out_features=200, in_features=520, v=8, k=65536), dict(out_features=37, in_features=520, v=5, k=37, k_res=11)],
+    "single": [dict(out_features=261, in_features=1030, v=6, k=4096)],
+}
+
+
+def multi_layers(name):
+    out = []
+    for i, kw in enumerate(MULTI[name]):
+        kw = dict(kw)
+        out.append(s.make_layer(400 + list(MULTI).index(name), "%s_%d" % (name, i), kw.pop("out_features"), kw.pop("in_features"),
+                                kw.pop("v"), kw.pop("k"), layer_ordinal=i, **kw))
+    return out

@@ -98,6 +98,22 @@ def test_entry_points_reject_bad_arguments_before_any_launch():
     assert vq.vq_gemm_workspace_bytes(_desc(v=0), 4) == 0
 
 
+def test_gemv_multi_rejects_bad_arguments_before_any_launch():
+    d, e = _desc(), _desc(out_features=5)
+    ok = dict(x_ptr=0x8000, ldx=30, batch=1, y_ptrs=[0x9000, 0xA000], ldys=[8, 5])
+    assert vq.vq_gemv_multi([d, e], **dict(ok, x_ptr=None)) == vq.VQ_ERR_NULL
+    assert vq.vq_gemv_multi([d, e], **dict(ok, y_ptrs=[0x9000, None])) == vq.VQ_ERR_NULL
+    assert vq.vq_gemv_multi([d, e], **dict(ok, batch=0)) == vq.VQ_ERR_SHAPE
+    assert vq.vq_gemv_multi([d, e], **dict(ok, batch=17)) == vq.VQ_ERR_SHAPE
+    assert vq.vq_gemv_multi([d, e], **dict(ok, ldys=[8, 4])) == vq.VQ_ERR_SHAPE
+    assert vq.vq_gemv_multi([d, e], **dict(ok, ldx=29)) == vq.VQ_ERR_SHAPE
+    assert vq.vq_gemv_multi([d, e], **dict(ok, y_ptrs=[0x9000, 0xA001])) == vq.VQ_ERR_ALIGNMENT
+    assert vq.vq_gemv_multi([d, _desc(in_features=36, idx_row_stride=16)], **ok) == vq.VQ_ERR_SHAPE     # not the same activations
+    assert vq.vq_gemv_multi([d, _desc(v=0)], **ok) == vq.VQ_ERR_SHAPE
+    assert vq.vq_gemv_multi([d] * 9, 0x8000, 30, 1, [0x9000] * 9, [8] * 9) == vq.VQ_ERR_SHAPE
+    assert vq.vq_gemv_multi([], 0x8000, 30, 1, [], []) == vq.VQ_ERR_SHAPE
+
+
 def test_binding_has_no_cpu_fallback():
     src = open(os.path.join(ROOT, "paper_2409_17066_amd", "__init__.py")).read()
     assert "oracle" not in src.replace("no CPU fallback", "")

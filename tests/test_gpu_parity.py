@@ -4,7 +4,7 @@ import pytest
 
 import oracle
 import vq_synth as s
-from cases import SMALL, small_layer
+from cases import SMALL, MULTI, small_layer, multi_layers
 
 pytestmark = pytest.mark.gpu
 
@@ -131,3 +131,44 @@ def test_non_default_stream(gpu_lib):
         y = gpu_lib.gemv(dl, xs)
     st.synchronize()
     _check_matmul(y, oracle.gemv(L, x), "side stream")
+
+
+FUSED_SETS = ("qkv_v6", "gate_up_res12", "res8_outlier_pair", "many_rows", "eight_layers")
+
+
+@pytest.mark.parametrize("name", list(MULTI))
+@pytest.mark.parametrize("batch", [1, 3, 16])
+def test_gemv_multi(gpu_lib, monkeypatch, name, batch):
+    """Several layers on the same activations in one call: each output against the oracle's product for that layer,
+    bit-identical to the matrix-core kernel on the layer alone, and padding between output rows left alone."""
+    import torch
+    layers = multi_layers(name)
+    dls = [gpu_lib.DeviceLayer(L) for L in layers]
+    x_np = s.make_activations(400, layers[0], batch)
+    x = torch.from_numpy(x_np).cuda()
+    pad = 3
+    outs = [torch.full((batch, L.out_features + pad), -7.0, dtype=torch.float16, device="cuda") for L in layers]
+    ys = gpu_lib.gemv_multi(dls, x, outs=[o[:, :L.out_features] for o, L in zip(outs, layers)])
+    torch.cuda.synchronize()
+    monkeypatch.setenv("VQ_GEMV_KERNEL", "m")
+    for L, dl, y, o in zip(layers, dls, ys, outs):
+        _check_matmul(y, oracle.gemv(L, x_np), "%s / %s batch %d" % (name, L.name, batch))
+        assert (o[:, L.out_features:] == -7.0).all()
+        alone = gpu_lib.gemv(dl, x)
+        torch.cuda.synchronize()
+        if name in FUSED_SETS:       # the others go one by one through vq_gemv's own dispatch
+            assert torch.equal(alone, y), L.name
+
+
+def test_gemv_multi_one_by_one_matches_fused(gpu_lib, monkeypatch):
+    import torch
+    layers = multi_layers("qkv_v6")
+    dls = [gpu_lib.DeviceLayer(L) for L in layers]
+    x = torch.from_numpy(s.make_activations(400, layers[0], 4)).cuda()
+    fused = [y.clone() for y in gpu_lib.gemv_multi(dls, x)]
+    monkeypatch.setenv("VQ_GEMV_MULTI", "0")
+    monkeypatch.setenv("VQ_GEMV_KERNEL", "m")
+    apart = gpu_lib.gemv_multi(dls, x)
+    torch.cuda.synchronize()
+    for a, b in zip(fused, apart):
+        assert torch.equal(a, b)
