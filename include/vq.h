@@ -102,8 +102,10 @@ int vq_gemv(const vq_layer_desc *desc, const void *x, int64_t ldx, int32_t batch
 /* vq_gemv for several layers that read the same activations -- the query, key and value projections of a
  * decoder layer, or its gate and up projections -- as one launch: y[i][b][o] = sum_c W_i[o][c] * x[b][c] for
  * i < n_layers, each result what vq_gemv's matrix-core kernel gives for that layer alone, bit for bit.
- * A decode-sized product is bound by launch and start-up time, not by its streaming time (the paper's section
- * on inference throughput reports the same for its own kernels), so fusing the launches is where the time goes.
+ * The operation is the decode-phase product of App. "Our Dequantization Implementation", once per layer.  On this
+ * GPU a decode-sized product spends more time on launch and start-up than on streaming its indices, so launching
+ * less often is what speeds up decoding (the paper's own tok/s figures were taken without such measures: footnote
+ * to its table of 2-bit LLaMA-2 results).
  * descs: host array of n_layers descriptor pointers, all with the same in_features; y, ldy: host arrays of
  * n_layers device pointers / leading dimensions (ldy[i] >= out_features of layer i); the outputs must not overlap
  * each other or x.  n_layers in [1, 8].  Layers that the fused kernel does not take together (different residual

@@ -417,9 +417,9 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
 }
 
 // Several layers that read the same activations (the query, key and value projections of a decoder layer; its gate
-// and up projections) in one launch: the launch and start-up cost of a decode-sized product (App. "Our Dequantization
-// Implementation", second phase) is several times its streaming time, so one launch for three layers costs about
-// what one layer costs.  Every workgroup belongs to one layer and runs the single-layer kernel on it.
+// and up projections) in one launch.  The launch and start-up cost of a decode-sized product (App. "Our
+// Dequantization Implementation", second phase) is as large as its streaming time or larger, and one launch pays
+// it once.  Every workgroup belongs to one layer and runs the single-layer kernel body on it.
 constexpr int MULTI_MAX = 8;
 struct MultiLayer {
   Params p;
