@@ -6,6 +6,7 @@
 #include <thread>
 #include <vector>
 #include <atomic>
+#include <algorithm>
 
 extern "C" float vq_oracle_half_to_float(uint16_t h) {
   // binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits.
@@ -189,6 +190,41 @@ extern "C" int vq_oracle_matmul(const vq_oracle_layer *L, const uint16_t *x, int
         y[(int64_t)t * ldy + j] = acc;
       }
     }
+    return (int)VQO_OK;
+  });
+}
+
+// Eq. 2 (Sec. 2.2) and the residual stage's equation (Sec. 3.2.2): index of the nearest centroid, every vector
+// against every centroid.  The header states the arithmetic; volatile keeps each binary32 step a step of its own.
+extern "C" int vq_oracle_assign(const uint16_t *W, const uint16_t *B, int64_t ld, int32_t rows, int32_t cols,
+                                const uint16_t *codebook, int32_t v, int32_t k, int32_t *out, int n_threads) {
+  if (!W || !codebook || !out || rows < 0 || cols < 1 || ld < cols || v < 1 || k < 1) return VQO_ERR_ARG;
+  const int64_t P = ((int64_t)cols + v - 1) / v;
+  std::vector<float> C((size_t)k * v);
+  for (int64_t e = 0; e < (int64_t)k * v; ++e) C[e] = vq_oracle_half_to_float(codebook[e]);
+  return parallel_rows(rows, n_threads, [&](int64_t lo, int64_t hi) {
+    std::vector<float> t(v);
+    for (int64_t o = lo; o < hi; ++o)
+      for (int64_t p = 0; p < P; ++p) {
+        const int64_t c0 = p * v;
+        const int len = (int)std::min<int64_t>(v, cols - c0);
+        for (int j = 0; j < len; ++j) {
+          volatile float tj = vq_oracle_half_to_float(W[o * ld + c0 + j]);
+          if (B) tj = tj - vq_oracle_half_to_float(B[o * ld + c0 + j]);
+          t[j] = tj;
+        }
+        int32_t best = 0;
+        float best_d = 0.0f;
+        for (int32_t i = 0; i < k; ++i) {
+          volatile float d = 0.0f;
+          for (int j = 0; j < len; ++j) {
+            volatile float diff = t[j] - C[(size_t)i * v + j];
+            d = std::fmaf(diff, diff, d);
+          }
+          if (i == 0 || d < best_d) { best = i; best_d = d; }        // strict: the first of equal distances stays
+        }
+        out[o * P + p] = best;
+      }
     return (int)VQO_OK;
   });
 }

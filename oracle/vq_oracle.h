@@ -68,6 +68,18 @@ int vq_oracle_dequant(const vq_oracle_layer *L, uint16_t *W, int64_t ldw, int n_
 int vq_oracle_matmul(const vq_oracle_layer *L, const uint16_t *x, int64_t ldx, int32_t n_tokens,
                      const int32_t *rows, int32_t n_rows, double *y, int64_t ldy, int n_threads);
 
+/* Nearest-centroid assignment, the encode side of the lookup (Eq. 2 of Sec. 2.2; with B, the residual stage's
+ * equation in Sec. 3.2.2, B being the first stage's restored values).  W, B: fp16 bits [rows][ld]; vectors run along a
+ * row, vector p = columns [p v, p v + v), the last one cut at `cols`; codebook: fp16 bits [k][v].
+ * t_j = W[o][p v + j] (- B[o][p v + j]),  d_i = sum_j (t_j - C[i][j])^2,  out[o * P + p] = the smallest i among those
+ * with the smallest d_i, P = ceil(cols / v).
+ * The paper fixes no precision for the distance, and a distance decides an integer, so the arithmetic is spelled out
+ * and the HIP kernel follows the same: everything in binary32, round to nearest even; t_j is one subtraction of the
+ * two widened binary16 values; every term is one subtraction and one fused multiply-add into the running sum, which
+ * starts at +0 and takes j in ascending order.                                                                      */
+int vq_oracle_assign(const uint16_t *W, const uint16_t *B, int64_t ld, int32_t rows, int32_t cols,
+                     const uint16_t *codebook, int32_t v, int32_t k, int32_t *out, int n_threads);
+
 #ifdef __cplusplus
 }
 #endif
