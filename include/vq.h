@@ -114,6 +114,20 @@ int vq_gemv(const vq_layer_desc *desc, const void *x, int64_t ldx, int32_t batch
 int vq_gemv_multi(const vq_layer_desc *const *descs, int32_t n_layers, const void *x, int64_t ldx, int32_t batch,
                   void *const *y, const int64_t *ldy, void *hip_stream);
 
+/* Encode side of the lookup: the index of the nearest centroid of every length-v vector along the rows of a weight
+ * matrix (Eq. 2 of Sec. 2.2), written as the packed index stream that the entry points above read.  With B, the
+ * vectors of W - B are assigned: the residual stage of Sec. 3.2.2, B being what the first stage restores.
+ * W, B: fp16 [rows][ld], ld >= cols, 2-byte aligned, B may be NULL; vector p of a row = columns [p v, p v + v), the
+ * last one cut at cols and compared over its own elements only.  codebook: fp16 [k][v], v in [1,16], k in [2,65536].
+ * idx: [rows][idx_row_stride] bytes, 16-byte aligned base and stride, stride >= ceil(P * b / 8) rounded up to 4,
+ * P = ceil(cols / v), b = ceil(log2 k); every dword that holds one of the P * b bits of a row is written (bits past
+ * them zero), the rest of the stride is left alone.
+ * The distance decides an integer, so its arithmetic is part of the definition: binary32, round to nearest even;
+ * t_j = W - B is one subtraction; d_i = sum_j (t_j - C[i][j])^2 with one subtraction and one fused multiply-add per
+ * element into a sum that starts at +0, j ascending; the result is the smallest i among the smallest d_i.      */
+int vq_assign(const void *W, const void *B, int64_t ld, int32_t rows, int32_t cols, const void *codebook, int32_t v, int32_t k,
+              void *idx, int64_t idx_row_stride, void *hip_stream);
+
 /* Prompt-phase product for many tokens: Y[t][o] = sum_c W[o][c] * X[t][c] on the FP16 matrix cores,
  * binary32 accumulation, fp16 result (the paper's prompt phase, its section on inference throughput:
  * restore the weights, then multiply).  X: fp16 [tokens][ldx], 16-byte aligned, ldx % 8 == 0; Y: fp16

@@ -114,6 +114,20 @@ def test_gemv_multi_rejects_bad_arguments_before_any_launch():
     assert vq.vq_gemv_multi([], 0x8000, 30, 1, [], []) == vq.VQ_ERR_SHAPE
 
 
+def test_assign_rejects_bad_arguments_before_any_launch():
+    ok = dict(W_ptr=0x8000, B_ptr=None, ld=30, rows=8, cols=30, codebook_ptr=0x1000, v=6, k=256, idx_ptr=0x2000, idx_row_stride=16)
+    assert vq.vq_assign(**dict(ok, W_ptr=None)) == vq.VQ_ERR_NULL
+    assert vq.vq_assign(**dict(ok, codebook_ptr=None)) == vq.VQ_ERR_NULL
+    assert vq.vq_assign(**dict(ok, idx_ptr=None)) == vq.VQ_ERR_NULL
+    for bad in (dict(rows=0), dict(cols=0), dict(ld=29), dict(v=0), dict(v=17), dict(k=1), dict(k=65537)):
+        assert vq.vq_assign(**dict(ok, **bad)) == vq.VQ_ERR_SHAPE, bad
+    assert vq.vq_assign(**dict(ok, cols=30, k=4096, idx_row_stride=0)) == vq.VQ_ERR_SHAPE       # 5 x 12 bits need 8 bytes
+    assert vq.vq_assign(**dict(ok, W_ptr=0x8001)) == vq.VQ_ERR_ALIGNMENT
+    assert vq.vq_assign(**dict(ok, B_ptr=0x8001)) == vq.VQ_ERR_ALIGNMENT
+    assert vq.vq_assign(**dict(ok, idx_ptr=0x2008)) == vq.VQ_ERR_ALIGNMENT
+    assert vq.vq_assign(**dict(ok, idx_row_stride=24)) == vq.VQ_ERR_ALIGNMENT
+
+
 def test_binding_has_no_cpu_fallback():
     src = open(os.path.join(ROOT, "paper_2409_17066_amd", "__init__.py")).read()
     assert "oracle" not in src.replace("no CPU fallback", "")
