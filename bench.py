@@ -22,6 +22,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor figure
 MFMA_FP16_PEAK_TFLOPS = 2500.0  # dense FP16 matrix-core peak, vendor figure
+FP32_VECTOR_PEAK_TFLOPS = 157.3   # published fp32 vector peak (packed FMA on 256 compute units at 2.4 GHz)
 ROTATE_BYTES = 640 << 20        # footprint of the rotated index copies (> 2 x the 256 MB Infinity Cache)
 
 # HBM traffic per launch from `rocprofv3 --pmc` (FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by
@@ -327,6 +328,24 @@ def detail(vq, s, np, torch, use_graph, skip):
     out.append({"op": "vq_dequant", "cfg": 1, "us": round(sec * 1e6, 1), "GB/s": round(moved / sec / 1e9, 1),
                 "frac_hbm_peak": round(moved / sec / 1e9 / HBM_PEAK_GBPS, 4)})
     del dl1, W1
+    # encode side: nearest-centroid assignment of the headline layer's 11008 x 683 vectors against its 4096 x 6 table
+    Wenc = torch.from_numpy(s.to_fp16(s.normal(77, L1.out_features * L1.in_features, 0.02)).reshape(L1.out_features, L1.in_features)).cuda()
+    Cenc = torch.from_numpy(L1.codebook).cuda()
+    idx_enc = vq.assign(Wenc, Cenc)
+
+    def launch_assign(i):
+        rc = vq.vq_assign(Wenc.data_ptr(), None, Wenc.stride(0), Wenc.shape[0], Wenc.shape[1], Cenc.data_ptr(), 6, 4096,
+                          idx_enc.data_ptr(), idx_enc.stride(0), torch.cuda.current_stream().cuda_stream)
+        if rc != 0:
+            raise vq.VQError(rc, "vq_assign")
+    wall, ev = timed(launch_assign, 3, 1, use_graph=False)
+    sec = ev / 3
+    pairs = float(L1.out_features) * (L1.in_features // 6) * 4096
+    flops = pairs * (3 * 6 + 1)            # per (vector, centroid): v subtractions, v multiply-adds, one compare
+    out.append({"op": "vq_assign", "cfg": 1, "ms": round(sec * 1e3, 3), "T pairs/s": round(pairs / sec / 1e12, 3),
+                "TFLOP/s": round(flops / sec / 1e12, 1), "bound": "alu",
+                "frac_fp32_vector_peak": round(flops / sec / 1e12 / FP32_VECTOR_PEAK_TFLOPS, 4)})
+    del Wenc, Cenc, idx_enc
     # codebook groups on the headline shape: "group num" 4 and 16 of the paper's parameter table, as group sizes
     # rounded up to 8 vectors
     for group_vectors in (176, 48):
