@@ -89,3 +89,30 @@ def test_config3_small_gemm_with_outliers(gpu_lib, layers, workspace):
     Y = gpu_lib.gemm(dl, torch.from_numpy(x).cuda(), workspace=workspace)
     torch.cuda.synchronize()
     _matmul_ok(Y, oracle.gemm(sub, x), "cfg3 slice gemm")
+
+
+@pytest.mark.parametrize("names", [("q", "k", "v"), ("gate", "up")])
+def test_config2_projections_in_one_launch(gpu_lib, names):
+    """vq_gemv_multi as the benchmark runs it: the 7B decoder layer's q, k, v (and gate, up) on one x, every output row."""
+    import torch
+    pairs = [next(s.config_layers(2, only=n)) for n in names]
+    dls = [gpu_lib.DeviceLayer(L) for _, L in pairs]
+    for batch in s.CONFIGS[2]["rows"]:
+        x = s.make_activations(2, pairs[0][1], batch, layer_ordinal=pairs[0][0])
+        ys = gpu_lib.gemv_multi(dls, torch.from_numpy(x).cuda())
+        torch.cuda.synchronize()
+        for (_, L), y in zip(pairs, ys):
+            _matmul_ok(y, oracle.gemv(L, x), "cfg2 %s of %s batch %d" % (L.name, "+".join(names), batch))
+
+
+@pytest.mark.parametrize("group_vectors", [176, 48])
+def test_headline_shape_with_codebook_groups(gpu_lib, group_vectors):
+    """The 11008 x 4096 layer split into 4 and 15 codebook groups, as bench.py's detail lines time it."""
+    import torch
+    L = s.make_layer(1, "up", 11008, 4096, 6, 4096, group_vectors=group_vectors)
+    dl = _dequant_exact(gpu_lib, L)
+    for batch in (1, 16):
+        x = s.make_activations(1, L, batch)
+        y = gpu_lib.gemv(dl, torch.from_numpy(x).cuda())
+        torch.cuda.synchronize()
+        _matmul_ok(y, oracle.gemv(L, x), "grouped headline shape, %d vectors a group, batch %d" % (group_vectors, batch))
