@@ -101,7 +101,7 @@ int vq_gemv(const vq_layer_desc *desc, const void *x, int64_t ldx, int32_t batch
 
 /* vq_gemv for several layers that read the same activations -- the query, key and value projections of a
  * decoder layer, or its gate and up projections -- as one launch: y[i][b][o] = sum_c W_i[o][c] * x[b][c] for
- * i < n_layers, each result what vq_gemv's matrix-core kernel gives for that layer alone, bit for bit.
+ * i < n_layers, each result to vq_gemv's bar for that layer (the same kernel bodies run; deterministic run to run).
  * The operation is the decode-phase product of App. "Our Dequantization Implementation", once per layer.  On this
  * GPU a decode-sized product spends more time on launch and start-up than on streaming its indices, so launching
  * less often is what speeds up decoding (the paper's own tok/s figures were taken without such measures: footnote

@@ -103,14 +103,19 @@ int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __ha
 
 int launch_gemv_mfma_multi(const Params *ps, int n, const __half *x, long long ldx, int batch, __half *const *ys,
                            const long long *ldys, hipStream_t s);
+int launch_gemv_fast_multi(const Params *ps, int n, const __half *x, __half *const *ys, hipStream_t s);
 
-// Several layers on the same activations: one launch of the matrix-core kernel when all of them take it together,
-// else (and with VQ_GEMV_MULTI=0, for measurement and tests) one vq_gemv after the other.
+// Several layers on the same activations: one launch of the dot-product kernel (one row) or of the matrix-core kernel
+// (more rows; VQ_GEMV_KERNEL=m: always) when all of them take it together, else (and with VQ_GEMV_MULTI=0, for measurement and tests) one vq_gemv after the other.
 int launch_gemv_multi(const Params *ps, int n, const __half *x, long long ldx, int batch, __half *const *ys, const long long *ldys,
                       hipStream_t s) {
   const char *env = getenv("VQ_GEMV_MULTI");
   bool fused = n >= 2 && !(env && env[0] == '0') && forced_kernel() != 'g' && forced_kernel() != 'd';
   for (int i = 0; fused && i < n; ++i) fused = gemv_fast_applicable(ps[i], x, ldx);
+  if (fused && batch == 1 && forced_kernel() != 'm') {     // a single row: the dot-product kernel is the faster body
+    const int rc = launch_gemv_fast_multi(ps, n, x, ys, s);
+    if (rc != VQ_ERR_UNSUPPORTED) return rc;
+  }
   if (fused) {
     const int rc = launch_gemv_mfma_multi(ps, n, x, ldx, batch, ys, ldys, s);
     if (rc != VQ_ERR_UNSUPPORTED) return rc;

@@ -93,18 +93,18 @@ constexpr int window_dwords(int bits, int u) { return (32 - 4 + bits * u + 31) /
 // U: vectors per lane (compile time, so the lookups of a row carry no branches and overlap freely).
 // L1R: of a lane's U residual lookups, how many go to the residual table in memory (through the vector L1,
 // which gathers in parallel with LDS) instead of its LDS copy; only used for small residual tables.
+// `wg`: the workgroup's number within its layer (a launch may hold the workgroups of several layers).
 template <int RES_BITS, int B, int U, int L1R>
-__global__ __launch_bounds__(NW * 64) void gemv_v6_kernel(Params p, GemvPlan plan, const __half *__restrict__ x, long long ldx,
-                                                          __half *__restrict__ y, long long ldy) {
+__device__ __forceinline__ void gemv_v6_body(const Params &p, const GemvPlan &plan, const __half *__restrict__ x, long long ldx,
+                                             __half *__restrict__ y, long long ldy, int wg) {
   constexpr int DEPTH = RES_BITS ? 3 : 4;        // rows of index windows a wave keeps in flight (register budget)
   constexpr int NM = window_dwords(12, U);
   constexpr int RB = RES_BITS ? RES_BITS : 8;
   constexpr int NR = window_dwords(RB, U);
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-  warm_kernel_arguments();                      // Params + GemvPlan + four scalars: about 250 bytes
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int row0 = blockIdx.x * plan.rows_per_wg;
+  const int row0 = wg * plan.rows_per_wg;
   const int row1 = min(p.out_features, row0 + plan.rows_per_wg);
   const int rows_here = row1 - row0;
   const int Wt = plan.W + plan.Wo;
@@ -323,6 +323,37 @@ __global__ __launch_bounds__(NW * 64) void gemv_v6_kernel(Params p, GemvPlan pla
   }
 }
 
+template <int RES_BITS, int B, int U, int L1R>
+__global__ __launch_bounds__(NW * 64) void gemv_v6_kernel(Params p, GemvPlan plan, const __half *__restrict__ x, long long ldx,
+                                                          __half *__restrict__ y, long long ldy) {
+  warm_kernel_arguments();                      // Params + GemvPlan + four scalars: about 250 bytes
+  gemv_v6_body<RES_BITS, B, U, L1R>(p, plan, x, ldx, y, ldy, (int)blockIdx.x);
+}
+
+// Several layers on one activation row in one launch (the query, key and value projections; gate and up): every
+// workgroup belongs to one layer and runs the body above on it.  Batch 1 only: this is the kernel that a single
+// decode step runs, where the launch and start-up cost weighs most.
+constexpr int MULTI_MAX = 8;
+struct MultiLayer {
+  Params p;
+  GemvPlan plan;
+  __half *y;
+};
+struct MultiArgs {
+  int n;
+  int first_wg[MULTI_MAX + 1];             // layer i owns workgroups [first_wg[i], first_wg[i + 1])
+  MultiLayer layer[MULTI_MAX];
+};
+
+template <int RES_BITS, int U>
+__global__ __launch_bounds__(NW * 64) void gemv_v6_multi_kernel(MultiArgs a, const __half *__restrict__ x) {
+  warm_kernel_arguments();
+  int i = 0;
+  while (i + 1 < a.n && (int)blockIdx.x >= a.first_wg[i + 1]) ++i;
+  const MultiLayer &l = a.layer[i];
+  gemv_v6_body<RES_BITS, 1, U, 0>(l.p, l.plan, x, 0, l.y, 0, (int)blockIdx.x - a.first_wg[i]);
+}
+
 int g_cu_count = 0;
 
 int cu_count() {
@@ -398,8 +429,11 @@ static bool u_allowed(int U, int batch, bool res) {
   return U == 4;
 }
 
-// Launch for one group of 1, 2 or 4 batch rows.
-int launch_gemv_fast(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
+namespace {
+
+// Work split and LDS layout of one layer.  rows_per_wg == 0: one workgroup per compute unit; u_force > 0: that many
+// vectors per lane or nothing (several layers in one launch share one kernel instantiation).
+int make_plan(const Params &p, int batch, int rows_per_wg, int u_force, GemvPlan *out, unsigned *lds_bytes, unsigned *grid_out) {
   static const int kU[] = {4, 5, 6, 8};
   GemvPlan plan{};
   // LDS: tables first (main at 0); the activation rows, partial sums and activation sums follow once the
@@ -408,15 +442,19 @@ int launch_gemv_fast(const Params &p, const __half *x, long long ldx, int batch,
   unsigned off = rb == 0 ? Layout<0>::BYTES : rb == 8 ? Layout<8>::BYTES : Layout<12>::BYTES;
   plan.lds_out = off; off += p.Q ? 4096u * 8u : 0u;
   if (off > 160u * 1024u) return VQ_ERR_UNSUPPORTED;
-  unsigned grid = (unsigned)min(cu_count(), p.out_features);
-  plan.rows_per_wg = (p.out_features + (int)grid - 1) / (int)grid;
-  grid = (unsigned)((p.out_features + plan.rows_per_wg - 1) / plan.rows_per_wg);
+  if (rows_per_wg > 0) {
+    plan.rows_per_wg = rows_per_wg;
+  } else {
+    const unsigned g = (unsigned)min(cu_count(), p.out_features);
+    plan.rows_per_wg = (p.out_features + (int)g - 1) / (int)g;
+  }
+  *grid_out = (unsigned)((p.out_features + plan.rows_per_wg - 1) / plan.rows_per_wg);
   const long long max_stride = max(p.stride, max(p.stride_res, p.stride_out));
   if ((long long)plan.rows_per_wg * max_stride >= (1LL << 31)) return VQ_ERR_UNSUPPORTED;   // 32-bit buffer offsets
   // vectors per lane U and main slices W: fill lanes, keep waves busy, balance rows over the row streams
   double best = -1.0;
   for (int U : kU) {
-    if (!u_allowed(U, batch, p.k_res != 0)) continue;
+    if (!u_allowed(U, batch, p.k_res != 0) || (u_force > 0 && U != u_force)) continue;
     const int Wo = p.Q ? (p.Q + 64 * U - 1) / (64 * U) : 0;
     if (Wo >= NW) continue;
     const int W = (p.P + 64 * U - 1) / (64 * U);
@@ -449,10 +487,80 @@ int launch_gemv_fast(const Params &p, const __half *x, long long ldx, int batch,
   plan.rc = min(RC_MAX, (int)((160u * 1024u - off) / (unsigned)per_row));
   if (plan.rc < plan.RS || plan.rc < 1) return VQ_ERR_UNSUPPORTED;
   off += (unsigned)(plan.rc * per_row);
+  *out = plan; *lds_bytes = off;
+  return VQ_OK;
+}
+
+template <int RES_BITS, int U>
+int launch_multi(const MultiArgs &a, unsigned lds_bytes, unsigned grid, const __half *x, hipStream_t s) {
+  static bool configured = false;
+  auto kernel = gemv_v6_multi_kernel<RES_BITS, U>;
+  if (!configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+      return VQ_ERR_HIP;
+    configured = true;
+  }
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(NW * 64), lds_bytes, s, a, x);
+  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+}  // namespace
+
+// Launch for one group of 1, 2 or 4 batch rows.
+int launch_gemv_fast(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
+  if (p.n_groups > 1) return VQ_ERR_UNSUPPORTED;          // one table set per workgroup: layers with codebook groups go elsewhere
+  GemvPlan plan;
+  unsigned off = 0, grid = 0;
+  const int rc = make_plan(p, batch, 0, 0, &plan, &off, &grid);
+  if (rc != VQ_OK) return rc;
+  const int rb = p.k_res ? p.bits_res : 0;
 #define VQ_CASE(R, BB) if (rb == R && batch == BB) return launch_u<R, BB>(plan.U, p, plan, off, grid, x, ldx, y, ldy, s);
   VQ_CASE(0, 1) VQ_CASE(12, 1) VQ_CASE(8, 1)
   VQ_CASE(0, 2) VQ_CASE(12, 2) VQ_CASE(8, 2)
   VQ_CASE(0, 4) VQ_CASE(12, 4) VQ_CASE(8, 4)
+#undef VQ_CASE
+  return VQ_ERR_UNSUPPORTED;
+}
+
+// n layers (2 .. MULTI_MAX) on the same single activation row in one launch.  VQ_ERR_UNSUPPORTED when the layers do not
+// fit one kernel instantiation (different residual kinds or vectors per lane, codebook groups, different in_features).
+// The caller has checked gemv_fast_applicable() for each.
+int launch_gemv_fast_multi(const Params *ps, int n, const __half *x, __half *const *ys, hipStream_t s) {
+  if (n < 2 || n > MULTI_MAX) return VQ_ERR_UNSUPPORTED;
+  const int cus = cu_count();
+  long long rows_all = 0;
+  for (int i = 0; i < n; ++i) {
+    if (ps[i].in_features != ps[0].in_features || ps[i].n_groups > 1) return VQ_ERR_UNSUPPORTED;
+    if ((ps[i].k_res ? ps[i].bits_res : 0) != (ps[0].k_res ? ps[0].bits_res : 0)) return VQ_ERR_UNSUPPORTED;
+    rows_all += ps[i].out_features;
+  }
+  // every workgroup takes the same number of rows of one layer: the smallest number with which all the workgroups run
+  // at once, one per compute unit
+  int r = (int)((rows_all + cus - 1) / cus);
+  for (;; ++r) {
+    long long wgs = 0;
+    for (int i = 0; i < n; ++i) wgs += (ps[i].out_features + r - 1) / r;
+    if (wgs <= cus) break;
+  }
+  MultiArgs a{};
+  unsigned lds_bytes = 0;
+  int U = 0;
+  a.n = n;
+  for (int i = 0; i < n; ++i) {
+    unsigned off = 0, grid = 0;
+    const int rc = make_plan(ps[i], 1, r, U, &a.layer[i].plan, &off, &grid);
+    if (rc != VQ_OK) return rc;
+    U = a.layer[i].plan.U;                               // the first layer's choice binds the others
+    a.layer[i].p = ps[i]; a.layer[i].y = ys[i];
+    a.first_wg[i + 1] = a.first_wg[i] + (int)grid;
+    lds_bytes = max(lds_bytes, off);
+  }
+  const unsigned grid = (unsigned)a.first_wg[n];
+  const int rb = ps[0].k_res ? ps[0].bits_res : 0;
+#define VQ_CASE(R, UU) if (rb == R && U == UU) return launch_multi<R, UU>(a, lds_bytes, grid, x, s);
+  VQ_CASE(0, 4) VQ_CASE(0, 5) VQ_CASE(0, 6) VQ_CASE(0, 8)
+  VQ_CASE(12, 4) VQ_CASE(12, 5) VQ_CASE(12, 6)
+  VQ_CASE(8, 4) VQ_CASE(8, 5) VQ_CASE(8, 6)
 #undef VQ_CASE
   return VQ_ERR_UNSUPPORTED;
 }

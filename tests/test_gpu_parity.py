@@ -140,7 +140,8 @@ FUSED_SETS = ("qkv_v6", "gate_up_res12", "res8_outlier_pair", "many_rows", "eigh
 @pytest.mark.parametrize("batch", [1, 3, 16])
 def test_gemv_multi(gpu_lib, monkeypatch, name, batch):
     """Several layers on the same activations in one call: each output against the oracle's product for that layer,
-    bit-identical to the matrix-core kernel on the layer alone, and padding between output rows left alone."""
+    for more than one row bit-identical to the matrix-core kernel on the layer alone, and padding between output rows
+    left alone."""
     import torch
     layers = multi_layers(name)
     dls = [gpu_lib.DeviceLayer(L) for L in layers]
@@ -156,8 +157,21 @@ def test_gemv_multi(gpu_lib, monkeypatch, name, batch):
         assert (o[:, L.out_features:] == -7.0).all()
         alone = gpu_lib.gemv(dl, x)
         torch.cuda.synchronize()
-        if name in FUSED_SETS:       # the others go one by one through vq_gemv's own dispatch
-            assert torch.equal(alone, y), L.name
+        if name in FUSED_SETS and batch > 1:       # one row runs the dot-product body, whose split (and so its summation
+            assert torch.equal(alone, y), L.name   # order) depends on the rows per workgroup; the others go one by one
+
+
+@pytest.mark.parametrize("name", FUSED_SETS)
+def test_gemv_multi_single_row_with_the_matrix_core_body(gpu_lib, monkeypatch, name):
+    import torch
+    monkeypatch.setenv("VQ_GEMV_KERNEL", "m")
+    layers = multi_layers(name)
+    dls = [gpu_lib.DeviceLayer(L) for L in layers]
+    x_np = s.make_activations(400, layers[0], 1)
+    ys = gpu_lib.gemv_multi(dls, torch.from_numpy(x_np).cuda())
+    torch.cuda.synchronize()
+    for L, y in zip(layers, ys):
+        _check_matmul(y, oracle.gemv(L, x_np), "%s / %s" % (name, L.name))
 
 
 def test_gemv_multi_one_by_one_matches_fused(gpu_lib, monkeypatch):
