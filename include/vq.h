@@ -99,6 +99,18 @@ int vq_dequant(const vq_layer_desc *desc, void *W, int64_t ldw, void *hip_stream
 int vq_gemv(const vq_layer_desc *desc, const void *x, int64_t ldx, int32_t batch,
             void *y, int64_t ldy, void *hip_stream);
 
+/* vq_gemv with a workspace on loan (device memory, 256-byte aligned, owned by the caller, contents undefined
+ * afterwards).  Only layers with codebook groups (Sec. 3.1) use it: with vq_gemv_workspace_bytes(desc, batch) bytes
+ * every workgroup takes one group, whose tables it loads once, and a share of the rows, writes binary32 sums to the
+ * workspace, and a second kernel adds the groups up in ascending order and applies scale and bias -- instead of every
+ * workgroup walking all groups and swapping its tables for each.  vq_gemv_workspace_bytes returns 0 when no kernel
+ * would use a workspace for this layer.  With workspace NULL or smaller than that, and for every other layer, the
+ * call is vq_gemv.  Same arguments, bar and errors as vq_gemv; a workspace that is not 256-byte aligned is
+ * VQ_ERR_ALIGNMENT.  Calls that share a workspace must not overlap.                                          */
+size_t vq_gemv_workspace_bytes(const vq_layer_desc *desc, int32_t batch);
+int vq_gemv_with_workspace(const vq_layer_desc *desc, const void *x, int64_t ldx, int32_t batch, void *y, int64_t ldy,
+                           void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* vq_gemv for several layers that read the same activations -- the query, key and value projections of a
  * decoder layer, or its gate and up projections -- as one launch: y[i][b][o] = sum_c W_i[o][c] * x[b][c] for
  * i < n_layers, each result to vq_gemv's bar for that layer (the same kernel bodies run; deterministic run to run).

@@ -53,6 +53,10 @@ def load():
     L.vq_validate.argtypes = [P]
     L.vq_dequant.argtypes = [P, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
     L.vq_gemv.argtypes = [P, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+    L.vq_gemv_workspace_bytes.argtypes = [P, ctypes.c_int32]
+    L.vq_gemv_workspace_bytes.restype = ctypes.c_size_t
+    L.vq_gemv_with_workspace.argtypes = [P, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
+                                         ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     L.vq_gemv_multi.argtypes = [ctypes.POINTER(P), ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32,
                                 ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_int64), ctypes.c_void_p]
     L.vq_assign.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
@@ -66,13 +70,13 @@ def load():
     L.vq_status_string.argtypes = [ctypes.c_int]
     L.vq_status_string.restype = ctypes.c_char_p
     L.vq_version.restype = ctypes.c_int
-    for f in (L.vq_validate, L.vq_dequant, L.vq_gemv, L.vq_gemv_multi, L.vq_gemm, L.vq_assign):
+    for f in (L.vq_validate, L.vq_dequant, L.vq_gemv, L.vq_gemv_with_workspace, L.vq_gemv_multi, L.vq_gemm, L.vq_assign):
         f.restype = ctypes.c_int
     _lib = L
     return L
 
 
-EXPORTED = ["vq_validate", "vq_dequant", "vq_gemv", "vq_gemv_multi", "vq_gemm", "vq_gemm_workspace_bytes", "vq_gemm_fast_workspace_bytes",
+EXPORTED = ["vq_validate", "vq_dequant", "vq_gemv", "vq_gemv_workspace_bytes", "vq_gemv_with_workspace", "vq_gemv_multi", "vq_gemm", "vq_gemm_workspace_bytes", "vq_gemm_fast_workspace_bytes",
             "vq_assign", "vq_status_string", "vq_version"]
 
 
@@ -87,6 +91,15 @@ def vq_dequant(desc, W_ptr, ldw, stream=None):
 
 def vq_gemv(desc, x_ptr, ldx, batch, y_ptr, ldy, stream=None):
     return load().vq_gemv(ctypes.byref(desc) if desc is not None else None, x_ptr, ldx, batch, y_ptr, ldy, stream)
+
+
+def vq_gemv_workspace_bytes(desc, batch):
+    return load().vq_gemv_workspace_bytes(ctypes.byref(desc), batch)
+
+
+def vq_gemv_with_workspace(desc, x_ptr, ldx, batch, y_ptr, ldy, workspace_ptr=None, workspace_bytes=0, stream=None):
+    return load().vq_gemv_with_workspace(ctypes.byref(desc) if desc is not None else None, x_ptr, ldx, batch, y_ptr, ldy,
+                                         workspace_ptr, workspace_bytes, stream)
 
 
 def vq_gemv_multi(descs, x_ptr, ldx, batch, y_ptrs, ldys, stream=None):
@@ -168,12 +181,20 @@ def dequant(dl: DeviceLayer, ldw=None):
     return W
 
 
-def gemv(dl: DeviceLayer, x, out=None):
-    """x: fp16 [batch][>=in] device tensor -> fp16 [batch][out]."""
+def gemv(dl: DeviceLayer, x, out=None, workspace=None):
+    """x: fp16 [batch][>=in] device tensor -> fp16 [batch][out].  workspace: a uint8 device tensor, or "fast" to allocate
+    the one vq_gemv_workspace_bytes asks for (layers with codebook groups), or None."""
     import torch
     assert x.is_cuda and x.dtype == torch.float16 and x.dim() == 2 and x.stride(1) == 1
     y = out if out is not None else torch.empty((x.shape[0], dl.layer.out_features), dtype=torch.float16, device="cuda")
-    rc = vq_gemv(dl.desc, x.data_ptr(), x.stride(0), x.shape[0], y.data_ptr(), y.stride(0), _stream())
+    if workspace is None:
+        rc = vq_gemv(dl.desc, x.data_ptr(), x.stride(0), x.shape[0], y.data_ptr(), y.stride(0), _stream())
+    else:
+        if isinstance(workspace, str):
+            assert workspace == "fast"
+            workspace = torch.empty(max(vq_gemv_workspace_bytes(dl.desc, x.shape[0]), 256), dtype=torch.uint8, device="cuda")
+        rc = vq_gemv_with_workspace(dl.desc, x.data_ptr(), x.stride(0), x.shape[0], y.data_ptr(), y.stride(0),
+                                    workspace.data_ptr(), workspace.numel(), _stream())
     if rc != VQ_OK:
         raise VQError(rc, "vq_gemv")
     return y

@@ -93,6 +93,26 @@ extern "C" int vq_gemv(const vq_layer_desc *desc, const void *x, int64_t ldx, in
                          static_cast<hipStream_t>(hip_stream));
 }
 
+extern "C" size_t vq_gemv_workspace_bytes(const vq_layer_desc *desc, int32_t batch) {
+  vq::Params p;
+  if (vq::make_params(desc, &p) != VQ_OK || batch < 1 || batch > 16) return 0;
+  // the size does not depend on x; the fast kernels' conditions on x are checked again at the call
+  return vq::gemv_workspace_bytes(p, nullptr, p.in_features + (p.in_features & 1), batch);
+}
+
+extern "C" int vq_gemv_with_workspace(const vq_layer_desc *desc, const void *x, int64_t ldx, int32_t batch, void *y, int64_t ldy,
+                                      void *workspace, size_t workspace_bytes, void *hip_stream) {
+  vq::Params p;
+  int rc = vq::make_params(desc, &p);
+  if (rc != VQ_OK) return rc;
+  if (!x || !y) return VQ_ERR_NULL;
+  if (batch < 1 || batch > 16 || ldx < p.in_features || ldy < p.out_features) return VQ_ERR_SHAPE;
+  if (!aligned(x, 2) || !aligned(y, 2)) return VQ_ERR_ALIGNMENT;
+  if (workspace && workspace_bytes && !aligned(workspace, 256)) return VQ_ERR_ALIGNMENT;
+  return vq::launch_gemv_ws(p, static_cast<const __half *>(x), ldx, batch, static_cast<__half *>(y), ldy, workspace, workspace_bytes,
+                            static_cast<hipStream_t>(hip_stream));
+}
+
 extern "C" int vq_gemv_multi(const vq_layer_desc *const *descs, int32_t n_layers, const void *x, int64_t ldx, int32_t batch,
                              void *const *y, const int64_t *ldy, void *hip_stream) {
   constexpr int MAX_LAYERS = 8;

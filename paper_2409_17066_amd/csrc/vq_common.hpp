@@ -29,6 +29,9 @@ int make_params(const vq_layer_desc *d, Params *p);
 // Kernel launchers (each returns a vq_status).
 int launch_dequant(const Params &p, __half *W, long long ldw, hipStream_t s);
 int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
+size_t gemv_workspace_bytes(const Params &p, const __half *x, long long ldx, int batch);
+int launch_gemv_ws(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, void *workspace,
+                   size_t workspace_bytes, hipStream_t s);
 int launch_gemv_multi(const Params *ps, int n, const __half *x, long long ldx, int batch, __half *const *ys, const long long *ldys,
                       hipStream_t s);
 int launch_gemm(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy,

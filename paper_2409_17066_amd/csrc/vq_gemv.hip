@@ -101,6 +101,28 @@ int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __ha
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
 
+size_t gemv_mfma_groups_workspace_bytes(const Params &p, int batch);
+int launch_gemv_mfma_groups(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, void *workspace,
+                            hipStream_t s);
+
+// A workspace serves layers with codebook groups on the matrix-core kernel: one group per workgroup, then a sum over
+// the groups.  VQ_GEMV_GROUPS=loop keeps every workgroup walking all groups (measurement and tests).
+size_t gemv_workspace_bytes(const Params &p, const __half *x, long long ldx, int batch) {
+  if (force_generic() || forced_kernel() == 'd' || !gemv_fast_applicable(p, x, ldx)) return 0;
+  return gemv_mfma_groups_workspace_bytes(p, batch);
+}
+
+int launch_gemv_ws(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, void *workspace,
+                   size_t workspace_bytes, hipStream_t s) {
+  const char *env = getenv("VQ_GEMV_GROUPS");
+  const size_t need = gemv_workspace_bytes(p, x, ldx, batch);
+  if (need && workspace && workspace_bytes >= need && !(env && env[0] == 'l')) {
+    const int rc = launch_gemv_mfma_groups(p, x, ldx, batch, y, ldy, workspace, s);
+    if (rc != VQ_ERR_UNSUPPORTED) return rc;
+  }
+  return launch_gemv(p, x, ldx, batch, y, ldy, s);
+}
+
 int launch_gemv_mfma_multi(const Params *ps, int n, const __half *x, long long ldx, int batch, __half *const *ys,
                            const long long *ldys, hipStream_t s);
 int launch_gemv_fast_multi(const Params *ps, int n, const __half *x, __half *const *ys, hipStream_t s);

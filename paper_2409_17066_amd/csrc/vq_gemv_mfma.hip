@@ -50,6 +50,14 @@ struct MfmaPlan {
   unsigned lds_yacc;             // grouped layers: binary32 sums of the groups so far, 1 KB per 16-row block
 };
 
+// Which codebook groups a workgroup walks, and where their sums go: the finished fp16 outputs (part == nullptr), or --
+// when every workgroup takes one group and the groups meet in a second kernel -- binary32 sums without scale and bias,
+// part[token][row] for this range, plus the activation sums of the range's columns, part_xs[group * 16 + token].
+struct GroupRange {
+  int begin, end;
+  float *part, *part_xs;
+};
+
 typedef _Float16 half8v __attribute__((ext_vector_type(8)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 
@@ -65,7 +73,8 @@ __device__ __forceinline__ float4v mfma16(uint4v a, uint4v b, float4v c) {
 // `wg` is the workgroup's number within its layer (a launch may hold the workgroups of several layers).
 template <int RES_BITS, int MW, int NB, bool GROUPED>
 __device__ __forceinline__ void gemv_v6_mfma_body(const Params &p, const MfmaPlan &plan, const __half *__restrict__ x, long long ldx,
-                                                  int batch, __half *__restrict__ y, long long ldy, int wg) {
+                                                  int batch, __half *__restrict__ y, long long ldy, int wg,
+                                                  const GroupRange gr = GroupRange{0, 1, nullptr, nullptr}) {
   typedef Layout<RES_BITS> LY;
   constexpr int RB = RES_BITS ? RES_BITS : 8;
   constexpr int PA = NB == 2 ? 4 : 2;                   // passes whose index words are in flight or in registers
@@ -127,8 +136,9 @@ __device__ __forceinline__ void gemv_v6_mfma_body(const Params &p, const MfmaPla
   if (g == 0) xs_part[wv * 16 + n] = 0.0f;
   int buf = 0;
 
-  const int n_groups = GROUPED ? p.n_groups : 1;
-  for (int grp = 0; grp < n_groups; ++grp) {
+  const int grp_end = GROUPED ? gr.end : 1;
+  const bool partial = GROUPED && gr.part != nullptr;
+  for (int grp = GROUPED ? gr.begin : 0; grp < grp_end; ++grp) {
   // ---- this codebook group's vectors [v_lo, v_lo + v_n) and columns [col_lo, col_hi) of every row
   const int v_lo = GROUPED ? grp * p.Pg : 0;                                  // a multiple of 8: a dword boundary in the streams
   const int v_n = GROUPED ? min(p.Pg, p.P - v_lo) : p.P;
@@ -211,7 +221,7 @@ __device__ __forceinline__ void gemv_v6_mfma_body(const Params &p, const MfmaPla
     tables.store(p, lds, plan.lds_out, grp == 0, tid);
   }
   // scale and bias of the workgroup's rows, one dword per row, for the reductions at the chunk ends
-  for (int r = (int)threadIdx.x; r < (grp == 0 ? plan.rows_per_wg : 0); r += MW * 64) {
+  for (int r = (int)threadIdx.x; r < (grp == (GROUPED ? gr.begin : 0) && !partial ? plan.rows_per_wg : 0); r += MW * 64) {
     const unsigned short sc = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r_scale, (unsigned)(row0 + r) * 2u, 0, 0);
     const unsigned short bi = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r_bias, (unsigned)(row0 + r) * 2u, 0, 0);
     *reinterpret_cast<unsigned *>(lds + plan.lds_sb + (unsigned)r * 4u) = (unsigned)sc | ((unsigned)bi << 16);
@@ -362,14 +372,26 @@ __device__ __forceinline__ void gemv_v6_mfma_body(const Params &p, const MfmaPla
             for (int w = 0; w < MW; ++w) s += *reinterpret_cast<const float4v *>(pbase + (unsigned)(wv * MW + w) * 1024u + lane * 16u);
             // sums of the groups so far: this lane of this wave is the only one that ever touches its slot
             float4v *ya = reinterpret_cast<float4v *>(lds + plan.lds_yacc + (unsigned)((c * NB + wv) * 64 + lane) * 16u);
-            if (GROUPED && grp > 0) s += *ya;
-            if (GROUPED && grp + 1 < n_groups) {
-              *ya = s;
-            } else {
+            if (GROUPED && grp > gr.begin) s += *ya;
             float xsum = 0.0f;
 #pragma unroll
             for (int w = 0; w < MW; ++w) xsum += xs_part[w * 16 + n];
             const float sv[4] = {s.x, s.y, s.z, s.w};
+            if (GROUPED && grp + 1 < grp_end) {
+              *ya = s;
+            } else if (partial) {
+              if (n < batch) {
+                float *dst = gr.part + (long long)n * p.out_features + ep_o;
+                if (ep_o + 3 < p.out_features && (p.out_features & 3) == 0) {
+                  *reinterpret_cast<float4v *>(dst) = s;
+                } else {
+#pragma unroll
+                  for (int r = 0; r < 4; ++r)
+                    if (ep_o + r < p.out_features) dst[r] = sv[r];
+                }
+                if (wg == 0 && c == 0 && wv == 0 && g == 0) gr.part_xs[grp * 16 + n] = xsum;
+              }
+            } else {
             const uint4v sb = *reinterpret_cast<const uint4v *>(lds + plan.lds_sb + (unsigned)((c * NB + wv) * 16 + 4 * g) * 4u);
             const unsigned sbw[4] = {sb.x, sb.y, sb.z, sb.w};             // per row: scale | bias << 16, as staged at the start
             __half out[4];
@@ -413,7 +435,35 @@ template <int RES_BITS, int MW, int NB, bool GROUPED>
 __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPlan plan, const __half *__restrict__ x, long long ldx,
                                                                 int batch, __half *__restrict__ y, long long ldy) {
   warm_kernel_arguments();
-  gemv_v6_mfma_body<RES_BITS, MW, NB, GROUPED>(p, plan, x, ldx, batch, y, ldy, (int)blockIdx.x);
+  gemv_v6_mfma_body<RES_BITS, MW, NB, GROUPED>(p, plan, x, ldx, batch, y, ldy, (int)blockIdx.x, GroupRange{0, p.n_groups, nullptr, nullptr});
+}
+
+// A layer with codebook groups when the caller lends a workspace: every workgroup takes one group (its tables go into
+// LDS once) and a share of the rows, the binary32 sums go to the workspace [group][token][row], and the kernel below
+// adds the groups up.  Without a workspace the workgroups cannot meet, and each walks all groups (the kernel above).
+template <int RES_BITS, int MW, int NB>
+__global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_groups_kernel(Params p, MfmaPlan plan, const __half *__restrict__ x, long long ldx,
+                                                                       int batch, float *__restrict__ part, float *__restrict__ part_xs,
+                                                                       int wgs_per_group) {
+  warm_kernel_arguments();
+  const int grp = (int)blockIdx.x / wgs_per_group, wg = (int)blockIdx.x - grp * wgs_per_group;
+  gemv_v6_mfma_body<RES_BITS, MW, NB, true>(p, plan, x, ldx, batch, nullptr, 0, wg,
+                                            GroupRange{grp, grp + 1, part + (long long)grp * batch * p.out_features, part_xs});
+}
+
+// y[t][o] = fp16(scale[o] * sum_g part[g][t][o] + bias[o] * sum_g part_xs[g][t]), groups in ascending order.
+__global__ __launch_bounds__(256) void gemv_groups_finish_kernel(const float *__restrict__ part, const float *__restrict__ part_xs, int n_groups,
+                                                                 int batch, int out_features, const __half *__restrict__ scale,
+                                                                 const __half *__restrict__ bias, __half *__restrict__ y, long long ldy) {
+  const int o = blockIdx.x * 256 + threadIdx.x, t = blockIdx.y;          // one token per grid row
+  if (o >= out_features) return;
+  const float sc = scale ? __half2float(scale[o]) : 1.0f, bi = bias ? __half2float(bias[o]) : 0.0f;
+  float sum = 0.0f, xs = 0.0f;
+  for (int gi = 0; gi < n_groups; ++gi) {
+    sum += part[((long long)gi * batch + t) * out_features + o];
+    xs += part_xs[gi * 16 + t];
+  }
+  y[(long long)t * ldy + o] = __float2half_rn(__fmaf_rn(sc, sum, bi * xs));
 }
 
 // Several layers that read the same activations (the query, key and value projections of a decoder layer; its gate
@@ -491,7 +541,8 @@ struct Planned {
 
 // Work split and LDS layout of one layer when every workgroup takes `blocks_per_wg` 16-row blocks.  nb_force > 0
 // fixes the blocks per chunk (several layers in one launch share one kernel instantiation).
-int make_plan(const Params &p, int batch, long long ldx, const __half *y, long long ldy, int blocks_per_wg, int nb_force, Planned *out) {
+int make_plan(const Params &p, int batch, long long ldx, const __half *y, long long ldy, int blocks_per_wg, int nb_force, Planned *out,
+              bool partial = false) {
   MfmaPlan plan{};
   if (p.in_features < 64) return VQ_ERR_UNSUPPORTED;      // idle lanes load the first 100 bytes of the first activation row
   const int rb = p.k_res ? p.bits_res : 0;
@@ -502,10 +553,10 @@ int make_plan(const Params &p, int batch, long long ldx, const __half *y, long l
   const int blocks_total = (p.out_features + 15) / 16;
   plan.rows_per_wg = blocks_per_wg * 16;
   out->grid = (unsigned)((blocks_total + blocks_per_wg - 1) / blocks_per_wg);
-  plan.lds_sb = off; off += (unsigned)plan.rows_per_wg * 4u;
+  plan.lds_sb = off; off += partial ? 0u : (unsigned)plan.rows_per_wg * 4u;
   const bool grouped = p.n_groups > 1;
   if (grouped && (p.Pg & 7)) return VQ_ERR_UNSUPPORTED;   // a group must start on a dword of the 12- and 8-bit streams
-  plan.lds_yacc = off; off += grouped ? (unsigned)blocks_per_wg * 1024u : 0u;
+  plan.lds_yacc = off; off += grouped && !partial ? (unsigned)blocks_per_wg * 1024u : 0u;
   plan.lds_part = off;
   if (off + MW * 1024u > lds_cap) return VQ_ERR_UNSUPPORTED;
   const int fit = (int)((lds_cap - off) / (MW * 1024u));                 // 16-row partial blocks that fit
@@ -564,6 +615,43 @@ int launch_gemv_mfma(const Params &p, const __half *x, long long ldx, int batch,
   VQ_CASE(12, 1) VQ_CASE(12, 2) VQ_CASE(12, 3)
 #undef VQ_CASE
   return VQ_ERR_UNSUPPORTED;
+}
+
+// Bytes of the workspace with which a layer with codebook groups runs as "one group per workgroup, then add up"; 0 when
+// that route does not apply (one group, group size not a multiple of 8 vectors, more groups than compute units).
+size_t gemv_mfma_groups_workspace_bytes(const Params &p, int batch) {
+  if (p.n_groups < 2 || (p.Pg & 7) || p.n_groups > cu_count()) return 0;
+  return ((size_t)p.n_groups * ((size_t)batch * (size_t)p.out_features + 16) * sizeof(float) + 255) / 256 * 256;
+}
+
+// The caller has checked gemv_fast_applicable() and that the workspace holds gemv_mfma_groups_workspace_bytes().
+int launch_gemv_mfma_groups(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, void *workspace,
+                            hipStream_t s) {
+  const int wgs_per_group = cu_count() / p.n_groups;
+  if (wgs_per_group < 1) return VQ_ERR_UNSUPPORTED;
+  const int blocks_total = (p.out_features + 15) / 16;
+  Planned pl;
+  const int rc = make_plan(p, batch, ldx, y, ldy, (blocks_total + wgs_per_group - 1) / wgs_per_group, 0, &pl, true);
+  if (rc != VQ_OK) return rc;
+  float *part = static_cast<float *>(workspace);
+  float *part_xs = part + (size_t)p.n_groups * (size_t)batch * (size_t)p.out_features;
+  const unsigned grid = pl.grid * (unsigned)p.n_groups;            // pl.grid workgroups per group
+  const void *kernel = nullptr;
+#define VQ_CASE(RBITS, NBLK) \
+  if (pl.rb == RBITS && pl.plan.nb == NBLK && NBLK <= (RBITS == 12 ? 2 : 3)) \
+    kernel = reinterpret_cast<const void *>(gemv_v6_mfma_groups_kernel<RBITS, MW, (NBLK <= (RBITS == 12 ? 2 : 3) ? NBLK : 1)>);
+  VQ_CASE(0, 1) VQ_CASE(0, 2) VQ_CASE(0, 3) VQ_CASE(8, 1) VQ_CASE(8, 2) VQ_CASE(8, 3) VQ_CASE(12, 1) VQ_CASE(12, 2)
+#undef VQ_CASE
+  if (!kernel) return VQ_ERR_UNSUPPORTED;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return VQ_ERR_HIP;
+  Params pc = p;
+  MfmaPlan plan = pl.plan;
+  int wpg = (int)pl.grid;
+  void *args[] = {&pc, &plan, &x, &ldx, &batch, &part, &part_xs, &wpg};
+  if (hipLaunchKernel(kernel, dim3(grid), dim3(MW * 64), args, pl.lds_bytes, s) != hipSuccess) return VQ_ERR_HIP;
+  hipLaunchKernelGGL(gemv_groups_finish_kernel, dim3((unsigned)((p.out_features + 255) / 256), (unsigned)batch), dim3(256), 0, s, part, part_xs, p.n_groups,
+                     batch, p.out_features, p.scale, p.bias, y, ldy);
+  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
 
 // n layers (2 .. MULTI_MAX) on the same activations in one launch.  VQ_ERR_UNSUPPORTED when the layers do not fit

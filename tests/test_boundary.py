@@ -114,6 +114,19 @@ def test_gemv_multi_rejects_bad_arguments_before_any_launch():
     assert vq.vq_gemv_multi([], 0x8000, 30, 1, [], []) == vq.VQ_ERR_SHAPE
 
 
+def test_gemv_with_workspace_rejects_bad_arguments_before_any_launch():
+    d = _desc()
+    assert vq.vq_gemv_workspace_bytes(d, 4) == 0                       # one group: no kernel would use a workspace
+    assert vq.vq_gemv_workspace_bytes(_desc(v=0), 4) == 0
+    assert vq.vq_gemv_with_workspace(d, None, 30, 1, 0x9000, 8) == vq.VQ_ERR_NULL
+    assert vq.vq_gemv_with_workspace(d, 0x8000, 30, 17, 0x9000, 8) == vq.VQ_ERR_SHAPE
+    assert vq.vq_gemv_with_workspace(d, 0x8000, 30, 1, 0x9001, 8) == vq.VQ_ERR_ALIGNMENT
+    assert vq.vq_gemv_with_workspace(d, 0x8000, 30, 1, 0x9000, 8, 0xA010, 4096) == vq.VQ_ERR_ALIGNMENT
+    big = _desc(in_features=6 * 64, idx_row_stride=96, v=6, k=4096, group_vectors=16)
+    assert vq.vq_gemv_workspace_bytes(big, 2) >= 4 * (2 * 8 + 16) * 4   # 4 groups x (2 tokens x 8 rows + 16 activation sums)
+    assert vq.vq_gemv_workspace_bytes(_desc(in_features=6 * 64, idx_row_stride=96, v=6, k=4096, group_vectors=12), 2) == 0
+
+
 def test_assign_rejects_bad_arguments_before_any_launch():
     ok = dict(W_ptr=0x8000, B_ptr=None, ld=30, rows=8, cols=30, codebook_ptr=0x1000, v=6, k=256, idx_ptr=0x2000, idx_row_stride=16)
     assert vq.vq_assign(**dict(ok, W_ptr=None)) == vq.VQ_ERR_NULL

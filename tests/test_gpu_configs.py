@@ -113,6 +113,8 @@ def test_headline_shape_with_codebook_groups(gpu_lib, group_vectors):
     dl = _dequant_exact(gpu_lib, L)
     for batch in (1, 16):
         x = s.make_activations(1, L, batch)
-        y = gpu_lib.gemv(dl, torch.from_numpy(x).cuda())
-        torch.cuda.synchronize()
-        _matmul_ok(y, oracle.gemv(L, x), "grouped headline shape, %d vectors a group, batch %d" % (group_vectors, batch))
+        ref = oracle.gemv(L, x)
+        for workspace in (None, "fast"):
+            y = gpu_lib.gemv(dl, torch.from_numpy(x).cuda(), workspace=workspace)
+            torch.cuda.synchronize()
+            _matmul_ok(y, ref, "grouped headline shape, %d vectors a group, batch %d, workspace %s" % (group_vectors, batch, workspace))

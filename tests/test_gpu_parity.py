@@ -186,3 +186,39 @@ def test_gemv_multi_one_by_one_matches_fused(gpu_lib, monkeypatch):
     torch.cuda.synchronize()
     for a, b in zip(fused, apart):
         assert torch.equal(a, b)
+
+
+GROUPED_FAST = [n for n, kw in SMALL.items() if kw.get("group_vectors", 0) % 8 == 0 and kw.get("group_vectors", 0) > 0 and kw["v"] == 6]
+
+
+@pytest.mark.parametrize("name", GROUPED_FAST)
+@pytest.mark.parametrize("batch", [1, 4, 16])
+def test_gemv_groups_with_workspace(gpu_lib, monkeypatch, name, batch):
+    """Layers with codebook groups when the caller lends a workspace: one group per workgroup, then the sum over groups.
+    Against the oracle, and against the route without a workspace (same per-group sums, added in the same order)."""
+    import torch
+    L = small_layer(name)
+    dl = gpu_lib.DeviceLayer(L)
+    need = gpu_lib.vq_gemv_workspace_bytes(dl.desc, batch)
+    if L.in_features % 2:
+        assert need == 0                # not a layer of the fast kernels: no workspace route
+        return
+    assert need >= L.n_groups * batch * L.out_features * 4
+    x_np = s.make_activations(300, L, batch)
+    x = torch.from_numpy(x_np).cuda()
+    ws = torch.full((need + 256,), 0xFF, dtype=torch.uint8, device="cuda")       # NaN patterns: nothing may be read before it is written
+    y = gpu_lib.gemv(dl, x, workspace=ws[:need])
+    torch.cuda.synchronize()
+    _check_matmul(y, oracle.gemv(L, x_np), "%s batch %d with workspace" % (name, batch))
+    assert (ws[need:] == 0xFF).all()
+    small = gpu_lib.gemv(dl, x, workspace=ws[:need - 256])                         # too small: the plain route
+    plain = gpu_lib.gemv(dl, x)
+    torch.cuda.synchronize()
+    assert torch.equal(small, plain)
+    _check_matmul(plain, oracle.gemv(L, x_np), "%s batch %d" % (name, batch))
+
+
+def test_gemv_workspace_is_not_asked_for_without_groups(gpu_lib):
+    for name in ("v6_k4096", "v8_k65536", "grp_v6_unaligned", "grp_odd"):
+        dl = gpu_lib.DeviceLayer(small_layer(name))
+        assert gpu_lib.vq_gemv_workspace_bytes(dl.desc, 4) == 0, name
