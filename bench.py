@@ -101,16 +101,22 @@ def timed(launch, steps, warmup, use_graph=True):
     return wall, e0.elapsed_time(e1) * 1e-3
 
 
-def bench_gemv(vq, layer, x_np, steps, warmup, use_graph, rotate=True):
+def bench_gemv(vq, layer, x_np, steps, warmup, use_graph, rotate=True, workspace=False):
     import torch
     rot = Rotation(vq, layer) if rotate else Rotation(vq, layer, min_bytes=0, min_copies=1)
     x = torch.from_numpy(x_np).cuda()
     batch = x.shape[0]
     y = torch.empty((batch, layer.out_features), dtype=torch.float16, device="cuda")
     xp, yp, ldx, ldy = x.data_ptr(), y.data_ptr(), x.stride(0), y.stride(0)
+    need = vq.vq_gemv_workspace_bytes(rot.descs[0], batch) if workspace else 0
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
 
     def launch(i):
-        rc = vq.vq_gemv(rot.descs[i % rot.copies], xp, ldx, batch, yp, ldy, torch.cuda.current_stream().cuda_stream)
+        st = torch.cuda.current_stream().cuda_stream
+        if workspace:
+            rc = vq.vq_gemv_with_workspace(rot.descs[i % rot.copies], xp, ldx, batch, yp, ldy, ws.data_ptr(), need, st)
+        else:
+            rc = vq.vq_gemv(rot.descs[i % rot.copies], xp, ldx, batch, yp, ldy, st)
         if rc != 0:
             raise vq.VQError(rc, "vq_gemv")
     wall, ev = timed(launch, steps, warmup, use_graph)
@@ -351,12 +357,13 @@ def detail(vq, s, np, torch, use_graph, skip):
     for group_vectors in (176, 48):
         Lg = s.make_layer(1, "up", L1.out_features, L1.in_features, 6, 4096, group_vectors=group_vectors)
         for batch in (1, 16):
-            r = bench_gemv(vq, Lg, s.make_activations(1, Lg, batch), steps, warmup, use_graph)
-            sec = r["event_s"] / steps
-            alg = Lg.algorithmic_bytes(batch)
-            out.append({"op": "vq_gemv", "cfg": "1 with codebook groups", "groups": Lg.n_groups, "group_vectors": group_vectors,
-                        "batch": batch, "us": round(sec * 1e6, 3), "GB/s": round(alg / sec / 1e9, 1),
-                        "frac_hbm_peak": round(alg / sec / 1e9 / HBM_PEAK_GBPS, 4)})
+            for with_ws in (False, True):
+                r = bench_gemv(vq, Lg, s.make_activations(1, Lg, batch), steps, warmup, use_graph, workspace=with_ws)
+                sec = r["event_s"] / steps
+                alg = Lg.algorithmic_bytes(batch)
+                out.append({"op": "vq_gemv_with_workspace" if with_ws else "vq_gemv", "cfg": "1 with codebook groups", "groups": Lg.n_groups,
+                            "group_vectors": group_vectors, "batch": batch, "us": round(sec * 1e6, 3), "GB/s": round(alg / sec / 1e9, 1),
+                            "frac_hbm_peak": round(alg / sec / 1e9 / HBM_PEAK_GBPS, 4)})
     return out
 
 
