@@ -12,7 +12,7 @@
 // binary32 and is read with wave-uniform addresses (one broadcast read feeds VB x 64 distances).  Tables larger than
 // the LDS chunk (k = 65536) are walked chunk by chunk with the running minimum kept in registers.  A row's last
 // vector, when the row length is not a multiple of v, is compared over its own elements only; those few vectors
-// go through a second, plain kernel that inserts their bits into the stream afterwards.
+// go through a second, plain kernel (a wave per row) that inserts their bits into the stream afterwards.
 #include "vq_common.hpp"
 
 namespace vq {
@@ -95,11 +95,13 @@ __global__ __launch_bounds__(AT) void assign_kernel(const __half *__restrict__ W
 }
 
 // The cut-off last vector of every row (row length not a multiple of v): distance over its `len` elements only.
-// One lane per row; runs after assign_kernel on the same stream and sets the vector's bits, which that kernel left zero.
+// One wave per row: lane l takes centroids l, l + 64, ... in ascending order (strict "less" keeps the lowest index of
+// equal distances among its own), then the lanes meet with the same rule -- smaller distance, else smaller index.
+// Runs after assign_kernel on the same stream and sets the vector's bits, which that kernel left zero.
 __global__ __launch_bounds__(256) void assign_tail_kernel(const __half *__restrict__ W, const __half *__restrict__ B, long long ld, int rows,
                                                           int p_full, int v, int len, const __half *__restrict__ codebook, int k, int bits,
                                                           unsigned char *__restrict__ idx, long long idx_stride) {
-  const int o = blockIdx.x * 256 + threadIdx.x;
+  const int o = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (o >= rows) return;
   float t[16];
   for (int j = 0; j < len; ++j) {
@@ -109,15 +111,21 @@ __global__ __launch_bounds__(256) void assign_tail_kernel(const __half *__restri
     t[j] = x;
   }
   float best = __builtin_inff();
-  unsigned arg = 0;
-  for (int i = 0; i < k; ++i) {
+  unsigned arg = 0xFFFFFFFFu;                                // a lane without centroids (k < 64) never wins
+  for (int i = lane; i < k; i += 64) {
     float d = 0.0f;
     for (int j = 0; j < len; ++j) {
       const float diff = __fsub_rn(t[j], __half2float(codebook[(long long)i * v + j]));
       d = __fmaf_rn(diff, diff, d);
     }
-    if (d < best) { best = d; arg = (unsigned)i; }
+    if (d < best || arg == 0xFFFFFFFFu) { best = d; arg = (unsigned)i; }
   }
+  for (int s = 32; s > 0; s >>= 1) {
+    const float od = __shfl_xor(best, s, 64);
+    const unsigned oa = __shfl_xor(arg, s, 64);
+    if (oa != 0xFFFFFFFFu && (arg == 0xFFFFFFFFu || od < best || (od == best && oa < arg))) { best = od; arg = oa; }
+  }
+  if (lane != 0) return;
   unsigned *row = reinterpret_cast<unsigned *>(idx + (long long)o * idx_stride);
   const long long bit = (long long)p_full * bits;
   const int sh = (int)(bit & 31);
@@ -161,7 +169,7 @@ int launch_assign(const __half *W, const __half *B, long long ld, int rows, int 
     default: break;
   }
   if (rc != VQ_OK || p_all == p_full) return rc;
-  hipLaunchKernelGGL(assign_tail_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, s, W, B, ld, rows, p_full, v, cols - p_full * v,
+  hipLaunchKernelGGL(assign_tail_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, W, B, ld, rows, p_full, v, cols - p_full * v,
                      codebook, k, bits, idx, idx_stride);
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
