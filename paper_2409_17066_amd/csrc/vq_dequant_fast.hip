@@ -39,11 +39,36 @@ struct DqPlan {
   int wide;                               // 1: every row start is 16-byte aligned and ldw % 8 == 0
 };
 
+// wgs_per_group > 0: a layer with codebook groups (Sec. 3.1).  A group is a layer of its own over a range of columns --
+// its tables, its part of the index streams (a group of 8 n vectors starts on a dword of a 12- or 8-bit stream), its
+// columns of W -- so workgroups [g * wgs_per_group, (g + 1) * wgs_per_group) take group g and see only that layer; the
+// outlier columns go with group 0.
 template <int RES_BITS>
-__global__ __launch_bounds__(NW * 64) void dequant_v6_kernel(Params p, DqPlan plan, __half *__restrict__ W, long long ldw) {
+__global__ __launch_bounds__(NW * 64) void dequant_v6_kernel(Params p, DqPlan plan, __half *__restrict__ W, long long ldw, int wgs_per_group) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  int wg = (int)blockIdx.x;
+  if (wgs_per_group > 0) {
+    const int grp = wg / wgs_per_group;
+    wg -= grp * wgs_per_group;
+    const int v_lo = grp * p.Pg;
+    p.P = min(p.Pg, p.P - v_lo);
+    p.cb += (long long)grp * p.k * 6;
+    if (RES_BITS) p.cb_res += (long long)grp * p.k_res * 6;
+    p.idx += (long long)(v_lo >> 3) * 12;
+    if (RES_BITS) p.idx_res += (long long)(v_lo >> 3) * RES_BITS;
+    const int col_lo = grp ? p.n_out + v_lo * 6 : 0;
+    p.in_features = min(p.in_features, p.n_out + (v_lo + p.P) * 6) - col_lo;
+    W += col_lo;
+    if (grp) { p.n_out = 0; p.Q = 0; plan.out_chunks = 0; }
+    plan.main_chunks = (p.P + 63) / 64;
+    const int cpr = plan.main_chunks + plan.out_chunks;
+    plan.total_chunks = (long long)cpr * p.out_features;
+    plan.step = (long long)wgs_per_group * NW;
+    plan.step_rows = (int)(plan.step / cpr);
+    plan.step_chunks = (int)(plan.step % cpr);
+  }
   // ---- codebooks into LDS: entries padded to 16 bytes (v = 6) or kept at 8 bytes (v = 4)
   {
     const unsigned *s = reinterpret_cast<const unsigned *>(p.cb);
@@ -103,7 +128,7 @@ __global__ __launch_bounds__(NW * 64) void dequant_v6_kernel(Params p, DqPlan pl
   auto field12 = [](unsigned w0, unsigned w1, int bit) { return __builtin_amdgcn_alignbit(w1, w0, (unsigned)bit & 31u) & 0xFFFu; };
 
   // chunk ids of this wave: first, first + step, ...; (row, chunk in row) advance without a division
-  const long long first = (long long)blockIdx.x * NW + wv;
+  const long long first = (long long)wg * NW + wv;
   int o = (int)(first / chunks_per_row), ch = (int)(first - (long long)o * chunks_per_row);
   Fetch cur, nxt;
   if (first < plan.total_chunks) fetch(o, ch, cur);
@@ -211,6 +236,8 @@ int cu_count() {
 
 template <int RES_BITS>
 int launch_v6(const Params &p, DqPlan plan, unsigned lds_bytes, __half *W, long long ldw, hipStream_t s) {
+  const int cus = cu_count();
+  if (p.n_groups > cus) return VQ_ERR_UNSUPPORTED;
   static bool configured = false;
   auto kernel = dequant_v6_kernel<RES_BITS>;
   if (!configured) {
@@ -219,14 +246,20 @@ int launch_v6(const Params &p, DqPlan plan, unsigned lds_bytes, __half *W, long 
     configured = true;
   }
   // the kernel needs few registers, so as many workgroups per compute unit as their LDS allows (at most two: 32 waves)
+  const long long slots = (long long)cus * (2u * lds_bytes <= 160u * 1024u ? 2 : 1);
+  if (p.n_groups > 1) {
+    // the workgroups are shared out evenly over the groups; each group's chunk walk is worked out in the kernel
+    const int wgs_per_group = (int)max(1LL, slots / p.n_groups);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(wgs_per_group * p.n_groups)), dim3(NW * 64), lds_bytes, s, p, plan, W, ldw, wgs_per_group);
+    return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+  }
   const long long want = (plan.total_chunks + NW - 1) / NW;
-  const long long slots = (long long)cu_count() * (2u * lds_bytes <= 160u * 1024u ? 2 : 1);
   const unsigned grid = (unsigned)(want < slots ? want : slots);
   const int cpr = plan.main_chunks + plan.out_chunks;
   plan.step = (long long)grid * NW;
   plan.step_rows = (int)(plan.step / cpr);
   plan.step_chunks = (int)(plan.step % cpr);
-  hipLaunchKernelGGL(kernel, dim3(grid), dim3(NW * 64), lds_bytes, s, p, plan, W, ldw);
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(NW * 64), lds_bytes, s, p, plan, W, ldw, 0);
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
 
@@ -247,27 +280,7 @@ int launch_dequant_fast(const Params &p, __half *W, long long ldw, hipStream_t s
   if (p.v != 6 || p.bits != 12) return VQ_ERR_UNSUPPORTED;
   if (p.k_res && p.bits_res != 12 && p.bits_res != 8) return VQ_ERR_UNSUPPORTED;
   if (p.n_out && (p.v_out != 4 || p.bits_out != 12)) return VQ_ERR_UNSUPPORTED;
-  if (p.n_groups > 1) {
-    // Codebook groups (Sec. 3.1): a group is a layer of its own over a range of columns -- one launch each, on the
-    // group's tables, its part of the index streams (a group of 8 n vectors starts on a dword of a 12- or 8-bit
-    // stream) and its columns of W.  The outlier columns go with the first group.
-    if (p.Pg & 7) return VQ_ERR_UNSUPPORTED;
-    for (int g = 0; g < p.n_groups; ++g) {
-      Params q = p;
-      const int v_lo = g * p.Pg;
-      q.P = min(p.Pg, p.P - v_lo); q.Pg = q.P; q.n_groups = 1;
-      q.cb = p.cb + (long long)g * p.k * 6;
-      q.cb_res = p.k_res ? p.cb_res + (long long)g * p.k_res * 6 : nullptr;
-      q.idx = p.idx + (long long)(v_lo >> 3) * 12;
-      q.idx_res = p.k_res ? p.idx_res + (long long)(v_lo >> 3) * p.bits_res : nullptr;
-      const int col_lo = g ? p.n_out + v_lo * 6 : 0;
-      if (g) { q.n_out = 0; q.Q = 0; q.k_out = 0; q.bits_out = 0; q.cb_out = nullptr; q.idx_out = nullptr; q.stride_out = 0; }
-      q.in_features = min(p.in_features, p.n_out + (v_lo + q.P) * 6) - col_lo;
-      const int rc = launch_dequant_fast(q, W + col_lo, ldw, s);
-      if (rc != VQ_OK) return g == 0 ? rc : (rc == VQ_ERR_UNSUPPORTED ? VQ_ERR_HIP : rc);
-    }
-    return VQ_OK;
-  }
+  if (p.n_groups > 1 && (p.Pg & 7)) return VQ_ERR_UNSUPPORTED;    // a group must start on a dword of the index streams
   DqPlan plan{};
   unsigned offb = 4096u * 16u;
   plan.lds_res = offb; offb += p.k_res ? (1u << p.bits_res) * 16u : 0u;
