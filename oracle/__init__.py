@@ -32,7 +32,7 @@ class _Layer(ctypes.Structure):
         ("idx_res", ctypes.c_void_p), ("idx_res_row_stride", ctypes.c_int64),
         ("idx_out", ctypes.c_void_p), ("idx_out_row_stride", ctypes.c_int64),
         ("scale", ctypes.c_void_p), ("bias", ctypes.c_void_p),
-        ("group_vectors", ctypes.c_int32),
+        ("group_vectors", ctypes.c_int32), ("orientation", ctypes.c_int32),
     ]
 
 
@@ -90,7 +90,7 @@ def _describe(layer):
                _ptr(keep["codebook"]), _ptr(keep["codebook_res"]), _ptr(keep["codebook_out"]),
                _ptr(keep["idx"]), stride(keep["idx"]), _ptr(keep["idx_res"]), stride(keep["idx_res"]),
                _ptr(keep["idx_out"]), stride(keep["idx_out"]), _ptr(keep["scale"]), _ptr(keep["bias"]),
-               int(getattr(layer, "group_vectors", 0)))
+               int(getattr(layer, "group_vectors", 0)), int(getattr(layer, "orientation", 0)))
     return d, keep
 
 

@@ -72,34 +72,40 @@ namespace {
 struct RowDecoder {
   const vq_oracle_layer *L;
   int b, b_res, b_out;
-  int64_t P, Q, Pg;            // Pg: vectors per codebook group
+  int64_t P, Q, Pg;            // indices per main / outlier stream; Pg: stream positions per codebook group
+  bool down;                   // orientation 1: vectors run down the output dimension
   std::vector<int32_t> i_main, i_res, i_out;
   explicit RowDecoder(const vq_oracle_layer *layer) : L(layer) {
     b = vq_oracle_index_bits(L->k);
     b_res = L->k_res ? vq_oracle_index_bits(L->k_res) : 0;
     b_out = L->n_outlier_cols ? vq_oracle_index_bits(L->k_out) : 0;
+    down = L->orientation == 1;
     const int64_t main_cols = (int64_t)L->in_features - L->n_outlier_cols;
-    P = (main_cols + L->v - 1) / L->v;
-    Q = L->n_outlier_cols ? L->n_outlier_cols / L->v_out : 0;
+    P = down ? main_cols : (main_cols + L->v - 1) / L->v;
+    Q = !L->n_outlier_cols ? 0 : down ? L->n_outlier_cols : L->n_outlier_cols / L->v_out;
     Pg = L->group_vectors > 0 ? L->group_vectors : (P > 0 ? P : 1);
     i_main.resize(P); i_res.resize(L->k_res ? P : 0); i_out.resize(Q);
   }
   // Restored row o as fp16 bits, w16[c] for c < in_features.
   int decode(int64_t o, uint16_t *w16) {
-    vq_oracle_unpack_row(L->idx + o * L->idx_row_stride, b, P, i_main.data());
-    if (L->k_res) vq_oracle_unpack_row(L->idx_res + o * L->idx_res_row_stride, b_res, P, i_res.data());
-    if (Q) vq_oracle_unpack_row(L->idx_out + o * L->idx_out_row_stride, b_out, Q, i_out.data());
+    // the streams that hold row o: its own (orientation 0), or the one of its block of v (v_out) rows
+    const int64_t s_main = down ? o / L->v : o, s_out = down && Q ? o / L->v_out : o;
+    vq_oracle_unpack_row(L->idx + s_main * L->idx_row_stride, b, P, i_main.data());
+    if (L->k_res) vq_oracle_unpack_row(L->idx_res + s_main * L->idx_res_row_stride, b_res, P, i_res.data());
+    if (Q) vq_oracle_unpack_row(L->idx_out + s_out * L->idx_out_row_stride, b_out, Q, i_out.data());
     const float s = L->scale ? vq_oracle_half_to_float(L->scale[o]) : 1.0f;
     const float bias = L->bias ? vq_oracle_half_to_float(L->bias[o]) : 0.0f;
     for (int64_t c = 0; c < L->in_features; ++c) {
       float d;
       if (c < L->n_outlier_cols) {
-        const int64_t q = c / L->v_out, j = c % L->v_out;
+        // which index of the outlier stream, which element of its centroid
+        const int64_t q = down ? c : c / L->v_out, j = down ? o % L->v_out : c % L->v_out;
         const int32_t i = i_out[q];
         if (i >= L->k_out) return VQO_ERR_INDEX_RANGE;
         d = vq_oracle_half_to_float(L->codebook_out[(int64_t)i * L->v_out + j]);
       } else {
-        const int64_t cc = c - L->n_outlier_cols, p = cc / L->v, j = cc % L->v;
+        const int64_t cc = c - L->n_outlier_cols;
+        const int64_t p = down ? cc : cc / L->v, j = down ? o % L->v : cc % L->v;
         const int32_t i = i_main[p];
         if (i >= L->k) return VQO_ERR_INDEX_RANGE;
         const int64_t group = p / Pg;                        // this vector's tables
@@ -120,12 +126,12 @@ struct RowDecoder {
 
 int check_layer(const vq_oracle_layer *L) {
   if (!L || !L->codebook || !L->idx) return VQO_ERR_ARG;
-  if (L->group_vectors < 0) return VQO_ERR_ARG;
+  if (L->group_vectors < 0 || (L->orientation != 0 && L->orientation != 1)) return VQO_ERR_ARG;
   if (L->out_features < 0 || L->in_features < 0 || L->v < 1 || L->k < 1) return VQO_ERR_ARG;
   if (L->k_res && (!L->codebook_res || !L->idx_res)) return VQO_ERR_ARG;
   if (L->n_outlier_cols) {
     if (!L->codebook_out || !L->idx_out || L->v_out < 1 || L->k_out < 1) return VQO_ERR_ARG;
-    if (L->n_outlier_cols % L->v_out || L->n_outlier_cols > L->in_features) return VQO_ERR_ARG;
+    if ((L->orientation == 0 && L->n_outlier_cols % L->v_out) || L->n_outlier_cols > L->in_features) return VQO_ERR_ARG;
   }
   return VQO_OK;
 }

@@ -46,6 +46,15 @@ typedef struct vq_oracle_layer {
    * p / group_vectors.  codebook is then [groups][k][v] and codebook_res [groups][k_res][v].  0 means one
    * group.  Outlier columns keep their single table.                                            */
   int32_t group_vectors;
+  /* Orientation of the vectors.  0: along the input dimension of an output row, as described above.
+   * 1: the paper's own (Sec. 3.1: a quantized column is a stack of centroids; Algorithm 1 quantizes W[m:m+v, n]): a
+   * vector covers v consecutive output rows of one input column.  Stream p of idx (and idx_res) then belongs to output
+   * rows [p v, p v + v), the last one cut at out_features, and holds one index per main column: position t is column
+   * n_outlier_cols + t, and W[p v + j][n_outlier_cols + t] comes from element j of its centroid.  There are
+   * ceil(out_features / v) such streams.  Stream q of idx_out belongs to rows [q v_out, q v_out + v_out) and holds one
+   * index per outlier column (n_outlier_cols need not be a multiple of v_out here).  Codebook groups are ranges of
+   * group_vectors stream positions, i.e. of main columns.  Scale and bias stay per output row.                  */
+  int32_t orientation;
 } vq_oracle_layer;
 
 enum { VQO_OK = 0, VQO_ERR_ARG = -1, VQO_ERR_INDEX_RANGE = -2 };

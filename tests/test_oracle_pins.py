@@ -169,6 +169,44 @@ def test_one_group_and_equal_tables_reduce_to_the_plain_layer():
     assert np.array_equal(oracle.matmul(L, x), oracle.matmul(plain, x))
 
 
+def test_vectors_down_the_output_dimension_are_the_transposed_layer():
+    """Sec. 3.1 / Algorithm 1: a column of the quantized matrix is a stack of centroids.  With the same tables and the
+    transposed index matrix this is the transpose of a layer whose vectors run along the rows."""
+    M, N = 24, 11
+    down = _tiny(out_features=M, in_features=N, v=6, k=64, k_res=16, orientation=1, with_scale=False, with_bias=False)
+    assert down.raw_idx.shape == (M // 6, N)
+    along = s.VQLayer("t", N, M, 6, 64, 16)
+    along.codebook, along.codebook_res = down.codebook, down.codebook_res
+    along.raw_idx, along.raw_idx_res = down.raw_idx.T.copy(), down.raw_idx_res.T.copy()
+    _repack(along)
+    assert np.array_equal(oracle.dequant(down).view(np.uint16), oracle.dequant(along).view(np.uint16).T)
+    x = s.make_activations(200, down, 2)
+    # y = W x for the layer; for its transpose the same numbers come out of the matrix restored above
+    assert np.allclose(oracle.matmul(down, x), x.astype(np.float64) @ oracle.dequant(along).astype(np.float64), rtol=1e-12)
+
+
+def test_vectors_down_the_output_dimension_streams_and_rows():
+    kw = dict(out_features=14, in_features=21, v=4, k=32, k_res=8, n_outlier_cols=5, v_out=3, k_out=16, orientation=1)
+    ref = oracle.dequant(_tiny(**kw)).view(np.uint16)
+    # one index of main stream 2 (rows 8..11), position 7 (column 5 + 7): exactly those four weights change
+    L = _tiny(**kw)
+    L.raw_idx[2, 7] = (L.raw_idx[2, 7] + 1) % L.k
+    _repack(L)
+    diff = oracle.dequant(L).view(np.uint16) != ref
+    assert diff[8:12, 12].any() and diff.sum() == diff[8:12, 12].sum()
+    # one index of outlier stream 4 (rows 12, 13: the last block is cut at 14 rows), column 2
+    L = _tiny(**kw)
+    L.raw_idx_out[4, 2] = (L.raw_idx_out[4, 2] + 1) % L.k_out
+    _repack(L)
+    diff = oracle.dequant(L).view(np.uint16) != ref
+    assert diff[12:14, 2].any() and diff.sum() == diff[12:14, 2].sum()
+    # scale and bias stay per output row
+    L = _tiny(**kw)
+    L.scale[5] = np.float16(2.0) * L.scale[5]
+    diff = oracle.dequant(L).view(np.uint16) != ref
+    assert diff[5].any() and not np.delete(diff, 5, axis=0).any()
+
+
 def test_scale_and_bias_semantics():
     L = _tiny(k_res=16)
     L.codebook[:] = 0
@@ -227,15 +265,18 @@ def _naive_dequant(L):
         sc = Fraction(float(L.scale[o])) if L.scale is not None else Fraction(1)
         bi = Fraction(float(L.bias[o])) if L.bias is not None else Fraction(0)
         for c in range(L.in_features):
+            down = L.orientation == 1          # vectors down the output dimension: stream o // v, element o % v, one index a column
             if c < L.n_outlier_cols:
-                d = Fraction(float(L.codebook_out[L.raw_idx_out[o, c // L.v_out], c % L.v_out]))
+                i = L.raw_idx_out[o // L.v_out, c] if down else L.raw_idx_out[o, c // L.v_out]
+                d = Fraction(float(L.codebook_out[i, o % L.v_out if down else c % L.v_out]))
             else:
                 cc = c - L.n_outlier_cols
-                p = cc // L.v
+                p = cc if down else cc // L.v
+                stream, j = (o // L.v, o % L.v) if down else (o, cc % L.v)
                 g = p // L.group_vectors if L.group_vectors else 0
-                d = Fraction(float(L.codebook.reshape(-1, L.k, L.v)[g, L.raw_idx[o, p], cc % L.v]))
+                d = Fraction(float(L.codebook.reshape(-1, L.k, L.v)[g, L.raw_idx[stream, p], j]))
                 if L.k_res:
-                    r = L.codebook_res.reshape(-1, L.k_res, L.v)[g, L.raw_idx_res[o, p], cc % L.v]
+                    r = L.codebook_res.reshape(-1, L.k_res, L.v)[g, L.raw_idx_res[stream, p], j]
                     d = _round_fraction(d + Fraction(float(r)), 24, -126)
             w32 = _round_fraction(sc * d + bi, 24, -126)
             W[o, c] = float(_round_fraction(w32, 11, -14))
@@ -254,6 +295,10 @@ CASES = [
     dict(out_features=3, in_features=61, v=6, k=256, group_vectors=4),                        # 11 vectors: groups of 4, 4, 3
     dict(out_features=3, in_features=75, v=6, k=64, k_res=16, n_outlier_cols=8, v_out=4, k_out=32, group_vectors=8),
     dict(out_features=2, in_features=23, v=5, k=37, k_res=11, group_vectors=1),                # a table per vector
+    # vectors down the output dimension: rows not a multiple of v, outlier columns not a multiple of v_out, groups of columns
+    dict(out_features=20, in_features=37, v=6, k=64, k_res=16, n_outlier_cols=5, v_out=4, k_out=32, orientation=1),
+    dict(out_features=13, in_features=9, v=8, k=300, orientation=1, with_scale=False),
+    dict(out_features=7, in_features=30, v=3, k=16, k_res=4, orientation=1, group_vectors=8, with_bias=False),
 ]
 
 

@@ -28,6 +28,7 @@ class VQLayer:
     v_out: int = 0
     k_out: int = 0
     group_vectors: int = 0               # > 0: every range of this many vectors of a row has tables of its own
+    orientation: int = 0                 # 0: vectors along the input dimension of a row; 1: down the output dimension
     codebook: np.ndarray = None          # fp16 [n_groups * k][v]: the groups' tables one after the other
     codebook_res: np.ndarray = None      # fp16 [n_groups * k_res][v] or None
     codebook_out: np.ndarray = None      # fp16 [k_out][v_out] or None
@@ -40,13 +41,29 @@ class VQLayer:
     raw_idx_res: np.ndarray = None
     raw_idx_out: np.ndarray = None
 
+    # An index stream holds `vectors_per_row` indices.  Orientation 0: one stream per output row, a vector covers v
+    # consecutive input columns.  Orientation 1 (the paper's: Sec. 3.1, a column is a stack of centroids): one stream per v
+    # consecutive output rows, one index per input column.
     @property
     def vectors_per_row(self) -> int:
-        return -(-(self.in_features - self.n_outlier_cols) // self.v)
+        main = self.in_features - self.n_outlier_cols
+        return main if self.orientation else -(-main // self.v)
 
     @property
     def outlier_vectors_per_row(self) -> int:
-        return self.n_outlier_cols // self.v_out if self.n_outlier_cols else 0
+        if not self.n_outlier_cols:
+            return 0
+        return self.n_outlier_cols if self.orientation else self.n_outlier_cols // self.v_out
+
+    @property
+    def streams(self) -> int:
+        return -(-self.out_features // self.v) if self.orientation else self.out_features
+
+    @property
+    def outlier_streams(self) -> int:
+        if not self.n_outlier_cols:
+            return 0
+        return -(-self.out_features // self.v_out) if self.orientation else self.out_features
 
     @property
     def n_groups(self) -> int:
@@ -67,7 +84,7 @@ class VQLayer:
     def algorithmic_bytes(self, batch: int) -> int:
         """Bytes one call must move: unpadded index bits, tables, scale/bias, activations in, outputs out."""
         P, Q, M = self.vectors_per_row, self.outlier_vectors_per_row, self.out_features
-        idx_bits = M * (P * (self.bits + self.bits_res) + Q * self.bits_out)
+        idx_bits = self.streams * P * (self.bits + self.bits_res) + self.outlier_streams * Q * self.bits_out
         tables = 2 * (self.n_groups * (self.k * self.v + self.k_res * self.v) + self.k_out * self.v_out)
         sb = 2 * M * ((self.scale is not None) + (self.bias is not None))
         return idx_bits // 8 + tables + sb + 2 * batch * self.in_features + 2 * batch * M
@@ -76,27 +93,27 @@ class VQLayer:
 def make_layer(config: int, name: str, out_features: int, in_features: int, v: int, k: int,
                k_res: int = 0, n_outlier_cols: int = 0, v_out: int = 0, k_out: int = 0,
                layer_ordinal: int = 0, with_scale: bool = True, with_bias: bool = True,
-               extra_stride: int = 0, group_vectors: int = 0) -> VQLayer:
+               extra_stride: int = 0, group_vectors: int = 0, orientation: int = 0) -> VQLayer:
     """Build one layer from the seeded streams.  `extra_stride` adds 16-byte units of row padding; with
     `group_vectors` every range of that many vectors gets main (and residual) tables of its own, all drawn from
     one stream, group after group."""
     def seed(t):
         return g.tensor_seed(config, t, layer_ordinal)
 
-    L = VQLayer(name, out_features, in_features, v, k, k_res, n_outlier_cols, v_out, k_out, group_vectors)
+    L = VQLayer(name, out_features, in_features, v, k, k_res, n_outlier_cols, v_out, k_out, group_vectors, orientation)
     P, Q = L.vectors_per_row, L.outlier_vectors_per_row
     n_groups = L.n_groups
     L.codebook = g.to_fp16(g.normal(seed(g.T_CODEBOOK), n_groups * k * v, SIGMA_MAIN)).reshape(n_groups * k, v)
-    L.raw_idx = g.random_indices(seed(g.T_IDX), out_features, P, k)
+    L.raw_idx = g.random_indices(seed(g.T_IDX), L.streams, P, k)
     L.idx = pack_indices(L.raw_idx, L.bits, row_stride_bytes(P, L.bits) + 16 * extra_stride)
     if k_res:
         L.codebook_res = g.to_fp16(g.normal(seed(g.T_CODEBOOK_RES), n_groups * k_res * v, SIGMA_RES)).reshape(n_groups * k_res, v)
-        L.raw_idx_res = g.random_indices(seed(g.T_IDX_RES), out_features, P, k_res)
+        L.raw_idx_res = g.random_indices(seed(g.T_IDX_RES), L.streams, P, k_res)
         L.idx_res = pack_indices(L.raw_idx_res, L.bits_res, row_stride_bytes(P, L.bits_res) + 16 * extra_stride)
     if n_outlier_cols:
-        assert n_outlier_cols % v_out == 0
+        assert orientation or n_outlier_cols % v_out == 0
         L.codebook_out = g.to_fp16(g.normal(seed(g.T_CODEBOOK_OUT), k_out * v_out, SIGMA_OUT)).reshape(k_out, v_out)
-        L.raw_idx_out = g.random_indices(seed(g.T_IDX_OUT), out_features, Q, k_out)
+        L.raw_idx_out = g.random_indices(seed(g.T_IDX_OUT), L.outlier_streams, Q, k_out)
         L.idx_out = pack_indices(L.raw_idx_out, L.bits_out, row_stride_bytes(Q, L.bits_out) + 16 * extra_stride)
     if with_scale:
         L.scale = g.to_fp16(0.5 + g.uniform01(seed(g.T_SCALE), out_features))
