@@ -78,6 +78,17 @@ typedef struct vq_layer_desc {
    * 0 = one group.  Outlier columns keep their single table.  The fast kernels take group_vectors % 8 == 0.
    * A caller that sets struct_size to VQ_LAYER_DESC_SIZE_V1 (the layout up to `bias`) gets one group.    */
   int32_t group_vectors;
+  /* Orientation of the vectors.  0: along the input dimension of an output row (everything above).  1: the paper's own
+   * (Sec. 3.1: a quantized column is a stack of centroids; Algorithm 1 quantizes W[m:m+v, n]): a vector covers v
+   * consecutive output rows of one input column.  Stream p of idx (and idx_res), p < ceil(out_features / v), belongs
+   * to output rows [p v, p v + v), cut at out_features, and holds one index per main column: position t is column
+   * n_outlier_cols + t, and W[p v + j][n_outlier_cols + t] is element j of its centroid.  Stream q of idx_out,
+   * q < ceil(out_features / v_out), belongs to rows [q v_out, q v_out + v_out) and holds one index per outlier column
+   * (n_outlier_cols need not be a multiple of v_out).  Codebook groups are ranges of group_vectors stream positions,
+   * i.e. of main columns.  Scale and bias stay per output row.  This field occupies what used to be padding after
+   * group_vectors: descriptors that were zeroed as a whole keep orientation 0.  Layers of orientation 1 run on the
+   * generic kernels (and through vq_gemm's restore-then-multiply route).                                          */
+  int32_t orientation;
 } vq_layer_desc;
 
 #define VQ_LAYER_DESC_SIZE_V1 ((uint32_t)offsetof(vq_layer_desc, group_vectors))

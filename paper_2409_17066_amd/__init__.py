@@ -24,7 +24,7 @@ class vq_layer_desc(ctypes.Structure):
         ("idx_res", ctypes.c_void_p), ("idx_res_row_stride", ctypes.c_int64),
         ("idx_out", ctypes.c_void_p), ("idx_out_row_stride", ctypes.c_int64),
         ("scale", ctypes.c_void_p), ("bias", ctypes.c_void_p),
-        ("group_vectors", ctypes.c_int32),
+        ("group_vectors", ctypes.c_int32), ("orientation", ctypes.c_int32),
     ]
 
 
@@ -161,7 +161,7 @@ class DeviceLayer:
             up("codebook", layer.codebook), up("codebook_res", layer.codebook_res), up("codebook_out", layer.codebook_out),
             up("idx", layer.idx), stride(layer.idx), up("idx_res", layer.idx_res), stride(layer.idx_res),
             up("idx_out", layer.idx_out), stride(layer.idx_out), up("scale", layer.scale), up("bias", layer.bias),
-            int(getattr(layer, "group_vectors", 0)))
+            int(getattr(layer, "group_vectors", 0)), int(getattr(layer, "orientation", 0)))
 
 
 def _stream():

@@ -16,7 +16,8 @@ int make_params(const vq_layer_desc *d, Params *p) {
   if (!d) return VQ_ERR_NULL;
   if (d->struct_size != sizeof(vq_layer_desc) && d->struct_size != VQ_LAYER_DESC_SIZE_V1) return VQ_ERR_SHAPE;
   const int group_vectors = d->struct_size == sizeof(vq_layer_desc) ? d->group_vectors : 0;
-  if (group_vectors < 0) return VQ_ERR_SHAPE;
+  const int orientation = d->struct_size == sizeof(vq_layer_desc) ? d->orientation : 0;
+  if (group_vectors < 0 || (orientation != 0 && orientation != 1)) return VQ_ERR_SHAPE;
   const int lim = 1 << 24;
   if (d->out_features < 1 || d->out_features > lim || d->in_features < 1 || d->in_features > lim) return VQ_ERR_SHAPE;
   if (d->v < 1 || d->v > 16 || d->k < 2 || d->k > 65536) return VQ_ERR_SHAPE;
@@ -24,7 +25,7 @@ int make_params(const vq_layer_desc *d, Params *p) {
   if (d->n_outlier_cols < 0) return VQ_ERR_SHAPE;
   if (d->n_outlier_cols > 0) {
     if (d->v_out < 1 || d->v_out > 16 || d->k_out < 2 || d->k_out > 65536) return VQ_ERR_SHAPE;
-    if (d->n_outlier_cols % d->v_out != 0 || d->n_outlier_cols >= d->in_features) return VQ_ERR_SHAPE;
+    if ((orientation == 0 && d->n_outlier_cols % d->v_out != 0) || d->n_outlier_cols >= d->in_features) return VQ_ERR_SHAPE;
   }
   Params q{};
   q.out_features = d->out_features; q.in_features = d->in_features;
@@ -32,8 +33,16 @@ int make_params(const vq_layer_desc *d, Params *p) {
   q.k_res = d->k_res; q.bits_res = d->k_res ? index_bits(d->k_res) : 0;
   q.n_out = d->n_outlier_cols;
   q.v_out = q.n_out ? d->v_out : 1; q.k_out = q.n_out ? d->k_out : 0; q.bits_out = q.n_out ? index_bits(d->k_out) : 0;
-  q.P = (d->in_features - q.n_out + d->v - 1) / d->v;
-  q.Q = q.n_out ? q.n_out / d->v_out : 0;
+  q.orientation = orientation;
+  if (orientation == 0) {
+    q.P = (d->in_features - q.n_out + d->v - 1) / d->v;
+    q.Q = q.n_out ? q.n_out / d->v_out : 0;
+    q.S = d->out_features; q.S_out = q.n_out ? d->out_features : 0;
+  } else {
+    q.P = d->in_features - q.n_out;
+    q.Q = q.n_out;
+    q.S = (d->out_features + d->v - 1) / d->v; q.S_out = q.n_out ? (d->out_features + d->v_out - 1) / d->v_out : 0;
+  }
   q.Pg = group_vectors > 0 && group_vectors < q.P ? group_vectors : q.P;
   q.n_groups = (q.P + q.Pg - 1) / q.Pg;
   if (!d->codebook) return VQ_ERR_NULL;

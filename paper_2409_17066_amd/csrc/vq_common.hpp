@@ -15,6 +15,9 @@ struct Params {
   int n_out, v_out, k_out, bits_out;
   int P, Q;                      // main / outlier vectors per row
   int Pg, n_groups;              // vectors per codebook group (P if there is one group), groups; tables are [group][k][v]
+  int orientation;               // 0: a vector covers v input columns of one row; 1: v output rows of one column
+  int S, S_out;                  // index streams (main / outlier): out_features, or ceil(out_features / v) with orientation 1;
+                                 // P and Q are then the indices per stream (main columns / outlier columns)
   const __half *cb, *cb_res, *cb_out;
   const uint8_t *idx, *idx_res, *idx_out;
   long long stride, stride_res, stride_out;   // bytes per row of each stream

@@ -41,9 +41,50 @@ __global__ __launch_bounds__(256) void dequant_generic_kernel(Params p, __half *
   }
 }
 
+// Orientation 1 (vectors down the output dimension; Sec. 3.1, Algorithm 1): one thread restores one vector, i.e. v
+// consecutive rows of one column.  Consecutive threads take consecutive columns of one stream, so each of the v stores
+// of a wave covers one contiguous span of a row.  Blocks [0, main_blocks) take the main streams, the rest the outlier ones.
+__global__ __launch_bounds__(256) void dequant_down_kernel(Params p, __half *W, long long ldw, int bps_main, long long main_blocks, int bps_out) {
+  const bool main = (long long)blockIdx.x < main_blocks;
+  const long long blk = main ? (long long)blockIdx.x : (long long)blockIdx.x - main_blocks;
+  const int bps = main ? bps_main : bps_out;
+  const int stream = (int)(blk / bps);
+  const int t = (int)(blk % bps) * 256 + threadIdx.x;
+  if (t >= (main ? p.P : p.Q)) return;
+  const int v = main ? p.v : p.v_out;
+  const __half *e, *er = nullptr;
+  if (main) {
+    unsigned i = min(load_index(p.idx + (long long)stream * p.stride, t, p.bits), (unsigned)p.k - 1u);
+    const long long group = t / p.Pg;
+    e = p.cb + (group * p.k + i) * p.v;
+    if (p.k_res) {
+      unsigned r = min(load_index(p.idx_res + (long long)stream * p.stride_res, t, p.bits_res), (unsigned)p.k_res - 1u);
+      er = p.cb_res + (group * p.k_res + r) * p.v;
+    }
+  } else {
+    unsigned i = min(load_index(p.idx_out + (long long)stream * p.stride_out, t, p.bits_out), (unsigned)p.k_out - 1u);
+    e = p.cb_out + (long long)i * p.v_out;
+  }
+  const int c = main ? p.n_out + t : t;
+  for (int j = 0; j < v; ++j) {
+    const int o = stream * v + j;
+    if (o >= p.out_features) break;
+    float d = __half2float(e[j]);
+    if (er) d = __fadd_rn(d, __half2float(er[j]));
+    W[(long long)o * ldw + c] = restore(d, p.scale ? __half2float(p.scale[o]) : 1.0f, p.bias ? __half2float(p.bias[o]) : 0.0f);
+  }
+}
+
 int launch_dequant_fast(const Params &p, __half *W, long long ldw, hipStream_t s);
 
 int launch_dequant(const Params &p, __half *W, long long ldw, hipStream_t s) {
+  if (p.orientation == 1) {
+    const int bps_main = (p.P + 255) / 256, bps_out = p.Q ? (p.Q + 255) / 256 : 1;
+    const long long main_blocks = (long long)bps_main * p.S, blocks = main_blocks + (long long)bps_out * p.S_out;
+    if (blocks > 0x7fffffffLL) return VQ_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(dequant_down_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, W, ldw, bps_main, main_blocks, bps_out);
+    return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+  }
   const int rc = launch_dequant_fast(p, W, ldw, s);
   if (rc != VQ_ERR_UNSUPPORTED) return rc;
   const int slots = p.P + p.Q;

@@ -268,7 +268,7 @@ int launch_v6(const Params &p, DqPlan plan, unsigned lds_bytes, __half *W, long 
 // Returns VQ_ERR_UNSUPPORTED when no fast kernel takes the layer (the caller then uses the generic kernel).
 int launch_dequant_fast(const Params &p, __half *W, long long ldw, hipStream_t s) {
   static const bool off = [] { const char *e = getenv("VQ_DEQUANT_KERNEL"); return e && e[0] == 'g'; }();
-  if (off) return VQ_ERR_UNSUPPORTED;
+  if (off || p.orientation != 0) return VQ_ERR_UNSUPPORTED;
   const bool aligned16 = (reinterpret_cast<uintptr_t>(W) & 15) == 0 && (ldw & 7) == 0;
   if (p.v == 8 && p.bits == 16 && p.k_res == 0 && p.n_out == 0) {
     const int bpr = (p.P + 255) / 256;

@@ -16,6 +16,29 @@ constexpr int LDT = BK + 8;    // LDS row pitch in halfs: 80 bytes, so 8 consecu
 
 // Restore columns [c0, c0+n) of row o into dst (LDS), zero past in_features.  Any layer shape.
 __device__ __forceinline__ void restore_run_generic(const Params &p, int o, int c0, int n, float s, float b, __half *dst) {
+  if (p.orientation == 1) {               // vectors down the output dimension: every column of the run is a vector of its own
+    for (int t = 0; t < n; ++t) {
+      const int c = c0 + t;
+      if (o >= p.out_features || c >= p.in_features) { dst[t] = __float2half_rn(0.0f); continue; }
+      float d;
+      if (c < p.n_out) {
+        const int sq = o / p.v_out;
+        unsigned i = min(load_index(p.idx_out + (long long)sq * p.stride_out, c, p.bits_out), (unsigned)p.k_out - 1u);
+        d = __half2float(p.cb_out[(long long)i * p.v_out + (o - sq * p.v_out)]);
+      } else {
+        const int pos = c - p.n_out, sp = o / p.v, j = o - sp * p.v;
+        const long long group = pos / p.Pg;
+        unsigned i = min(load_index(p.idx + (long long)sp * p.stride, pos, p.bits), (unsigned)p.k - 1u);
+        d = __half2float(p.cb[(group * p.k + i) * p.v + j]);
+        if (p.k_res) {
+          unsigned r = min(load_index(p.idx_res + (long long)sp * p.stride_res, pos, p.bits_res), (unsigned)p.k_res - 1u);
+          d = __fadd_rn(d, __half2float(p.cb_res[(group * p.k_res + r) * p.v + j]));
+        }
+      }
+      dst[t] = restore(d, s, b);
+    }
+    return;
+  }
   int c = c0;
   int j = 0, len = 0;                     // position inside / length of the current vector
   const __half *e = nullptr, *er = nullptr;

@@ -302,7 +302,7 @@ int launch_fused(const Params &p, const __half *X, long long ldx, int tokens, __
 }  // namespace
 
 bool gemm_fused_applicable(const Params &p) {
-  return p.v == 8 && p.bits == 16 && p.k_res == 0 && p.n_out == 0 && p.n_groups == 1 && p.in_features % (GD * BK) == 0;
+  return p.orientation == 0 && p.v == 8 && p.bits == 16 && p.k_res == 0 && p.n_out == 0 && p.n_groups == 1 && p.in_features % (GD * BK) == 0;
 }
 
 // Wd == nullptr: W is restored on the fly.  Otherwise Wd is the FP16 matrix [out][ldw] that vq_dequant wrote

@@ -53,6 +53,59 @@ __global__ __launch_bounds__(256) void gemv_generic_kernel(Params p, const __hal
   }
 }
 
+// Orientation 1 (vectors down the output dimension; Sec. 3.1, Algorithm 1): one wave per main stream, i.e. per block of v
+// output rows; lanes stride over the columns and keep one sum per row of the block; the outlier columns of each of these
+// rows come from the outlier stream that holds the row.  One token at a time.  Slow but complete.
+__global__ __launch_bounds__(256) void gemv_down_kernel(Params p, const __half *__restrict__ x, long long ldx, int batch,
+                                                        __half *__restrict__ y, long long ldy) {
+  const int lane = threadIdx.x & 63;
+  const int stream = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (stream >= p.S) return;
+  const int o0 = stream * p.v;
+  float sc[16], bi[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    const bool on = j < p.v && o0 + j < p.out_features;
+    sc[j] = on && p.scale ? __half2float(p.scale[o0 + j]) : 1.0f;
+    bi[j] = on && p.bias ? __half2float(p.bias[o0 + j]) : 0.0f;
+  }
+  for (int t = 0; t < batch; ++t) {
+    const __half *xt = x + (long long)t * ldx;
+    float acc[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[j] = 0.0f;
+    for (int pos = lane; pos < p.P; pos += 64) {
+      unsigned i = min(load_index(p.idx + (long long)stream * p.stride, pos, p.bits), (unsigned)p.k - 1u);
+      const long long group = pos / p.Pg;
+      const __half *e = p.cb + (group * p.k + i) * p.v, *er = nullptr;
+      if (p.k_res) {
+        unsigned r = min(load_index(p.idx_res + (long long)stream * p.stride_res, pos, p.bits_res), (unsigned)p.k_res - 1u);
+        er = p.cb_res + (group * p.k_res + r) * p.v;
+      }
+      const float xv = __half2float(xt[p.n_out + pos]);
+#pragma unroll
+      for (int j = 0; j < 16; ++j)
+        if (j < p.v && o0 + j < p.out_features) {
+          float d = __half2float(e[j]);
+          if (er) d = __fadd_rn(d, __half2float(er[j]));
+          acc[j] = __fmaf_rn(__half2float(restore(d, sc[j], bi[j])), xv, acc[j]);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+      if (j < p.v && o0 + j < p.out_features) {
+        const int o = o0 + j, sq = p.Q ? o / p.v_out : 0, jo = p.Q ? o - sq * p.v_out : 0;
+        for (int pos = lane; pos < p.Q; pos += 64) {
+          unsigned i = min(load_index(p.idx_out + (long long)sq * p.stride_out, pos, p.bits_out), (unsigned)p.k_out - 1u);
+          const float w = __half2float(restore(__half2float(p.cb_out[(long long)i * p.v_out + jo]), sc[j], bi[j]));
+          acc[j] = __fmaf_rn(w, __half2float(xt[pos]), acc[j]);
+        }
+        const float r = wave_sum(acc[j]);
+        if (lane == 0) y[(long long)t * ldy + o] = __float2half_rn(r);
+      }
+  }
+}
+
 bool gemv_fast_applicable(const Params &p, const __half *x, long long ldx);
 int launch_gemv_fast(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
 
@@ -71,6 +124,10 @@ int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __ha
   // kernels; those are still a little faster for one row (and for two rows of a layer with few output rows
   // per compute unit), so they keep these cases.  Layers with codebook groups always go to the matrix-core kernel:
   // it is the one that swaps the tables in LDS group by group.
+  if (p.orientation == 1) {
+    hipLaunchKernelGGL(gemv_down_kernel, dim3((unsigned)((p.S + 3) / 4)), dim3(256), 0, s, p, x, ldx, batch, y, ldy);
+    return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+  }
   const bool fast = !force_generic() && gemv_fast_applicable(p, x, ldx);
   const bool many_rows = p.out_features > 16 * 256;
   if (fast && forced_kernel() != 'd' && (batch >= 3 || (batch == 2 && many_rows) || forced_kernel() == 'm' || p.n_groups > 1)) {

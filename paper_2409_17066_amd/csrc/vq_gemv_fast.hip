@@ -412,7 +412,7 @@ extern "C" int vq_debug_read_profile(unsigned long long *dst, size_t count) {
 
 // Whether the fast kernels take this layer and these buffers.
 bool gemv_fast_applicable(const Params &p, const __half *x, long long ldx) {
-  if (p.v != 6 || p.bits != 12) return false;
+  if (p.orientation != 0 || p.v != 6 || p.bits != 12) return false;
   if (p.n_groups > 1 && (p.Pg & 7)) return false;           // a group starts on a dword of the index streams
   if (p.k_res && p.bits_res != 12 && p.bits_res != 8) return false;
   if (p.n_out && (p.v_out != 4 || p.bits_out != 12)) return false;

@@ -46,6 +46,13 @@ def test_valid_descriptor_passes():
                                 idx_out_row_stride=16)) == vq.VQ_OK
 
 
+def test_vectors_down_the_output_dimension_in_the_descriptor():
+    assert vq.vq_validate(_desc(orientation=1, idx_row_stride=32)) == vq.VQ_OK
+    # outlier columns need not be a multiple of v_out there
+    assert vq.vq_validate(_desc(orientation=1, idx_row_stride=32, n_outlier_cols=7, v_out=4, k_out=16, codebook_out=0x3000,
+                                idx_out=0x4000, idx_out_row_stride=16)) == vq.VQ_OK
+
+
 def test_codebook_groups_in_the_descriptor():
     assert vq.vq_validate(_desc(group_vectors=2)) == vq.VQ_OK               # 5 vectors: groups of 2, 2, 1
     assert vq.vq_validate(_desc(group_vectors=1000)) == vq.VQ_OK            # one group
@@ -57,6 +64,8 @@ def test_codebook_groups_in_the_descriptor():
 @pytest.mark.parametrize("kw,status", [
     (dict(struct_size=4), vq.VQ_ERR_SHAPE),
     (dict(group_vectors=-1), vq.VQ_ERR_SHAPE),
+    (dict(orientation=2), vq.VQ_ERR_SHAPE), (dict(orientation=-1), vq.VQ_ERR_SHAPE),
+    (dict(orientation=1, idx_row_stride=16), vq.VQ_ERR_SHAPE),          # 30 indices of 8 bits a stream need 30 bytes
     (dict(out_features=0), vq.VQ_ERR_SHAPE),
     (dict(in_features=0), vq.VQ_ERR_SHAPE),
     (dict(v=0), vq.VQ_ERR_SHAPE), (dict(v=17), vq.VQ_ERR_SHAPE),
