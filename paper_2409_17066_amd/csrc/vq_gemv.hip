@@ -110,6 +110,8 @@ bool gemv_fast_applicable(const Params &p, const __half *x, long long ldx);
 int launch_gemv_fast(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
 
 int launch_gemv_mfma(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
+bool gemv_down_applicable(const Params &p, const __half *x, long long ldx);
+int launch_gemv_down(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
 
 // VQ_GEMV_KERNEL=g forces the generic kernel, =m the matrix-core kernel, =d the dot-product kernels
 // (testing and measurement; unset: chosen by batch).  Read at every call so that one process can test them all.
@@ -125,6 +127,20 @@ int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __ha
   // per compute unit), so they keep these cases.  Layers with codebook groups always go to the matrix-core kernel:
   // it is the one that swaps the tables in LDS group by group.
   if (p.orientation == 1) {
+    if (!force_generic() && gemv_down_applicable(p, x, ldx)) {
+      // batch rows go in groups of 4, 2 or 1 (fewer when the rows do not fit LDS beside the tables)
+      int done = 0, g_max = 4, rc = VQ_OK;
+      while (done < batch) {
+        int g = batch - done >= 4 ? 4 : batch - done >= 2 ? 2 : 1;
+        if (g > g_max) g = g_max;
+        rc = launch_gemv_down(p, x + done * ldx, ldx, g, y + done * ldy, ldy, s);
+        if (rc == VQ_ERR_UNSUPPORTED && g > 1) { g_max = g / 2; continue; }
+        if (rc != VQ_OK) break;
+        done += g;
+      }
+      if (rc == VQ_OK) return VQ_OK;
+      if (rc != VQ_ERR_UNSUPPORTED || done != 0) return rc;
+    }
     hipLaunchKernelGGL(gemv_down_kernel, dim3((unsigned)((p.S + 3) / 4)), dim3(256), 0, s, p, x, ldx, batch, y, ldy);
     return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
   }

@@ -1,0 +1,284 @@
+// vq_gemv for layers whose vectors run down the output dimension (orientation 1: the paper's own layout, Sec. 3.1 --
+// a quantized column is a stack of centroids -- and Algorithm 1), v = 6, 12-bit indices, optional 12- or 8-bit
+// residual codebook, batch 1, 2 or 4 per launch (App. "Our Dequantization Implementation", second phase).
+//
+// Index stream p holds one index per input column and serves output rows 6p .. 6p+5: a gathered centroid meets ONE
+// activation and feeds six sums, y[6p + j] += C[idx][j] * x[n].  That is six mixed-precision multiply-adds per gather
+// and token (v_fma_mix_f32: fp16 operands, binary32 sum) against three dot products in the row-wise layout, and still
+// about nine vector instructions per gather at batch 1 -- under the dozen that keep the LDS gathers (the bound of all
+// these kernels) busy.  There is nothing to sum across lanes until a stream ends: a lane keeps its six (times batch)
+// sums over all the columns it visits.
+//
+// Work split: a pass of a wave covers 512 columns of one stream, eight per lane (their 96 index bits are three
+// aligned dwords, their activations one 16-byte LDS read per token).  A stream's passes go to WS = 1, 2, 4 or 8 waves of
+// a workgroup (chosen on the host so that the workgroups fill the chip); a workgroup holds the tables and the
+// activation rows in LDS and takes several groups of 8 / WS streams in turn.  Index words run DEPTH passes ahead in a
+// register ring.  A stream ends with a wave-wide sum of the 6 x batch values, a meeting of the WS waves in LDS when
+// WS > 1, and y = scale * sum + bias * sum(x) per output row.
+#include "vq_common.hpp"
+#include "vq_v6.hpp"
+
+namespace vq {
+namespace {
+
+using namespace v6;
+
+constexpr int DW = 8;            // waves per workgroup
+constexpr int DEPTH = 4;         // passes whose index words are in flight or in registers
+constexpr int VPL = 8;           // vectors (columns) per lane and pass
+
+struct DownPlan {
+  int ws_log2;                   // waves per stream
+  int passes;                    // 512-column passes per stream
+  int ppw;                       // passes per wave and stream
+  int iters;                     // groups of DW >> ws_log2 streams per workgroup
+  unsigned lds_x, lds_xsum, lds_part;
+  unsigned x_row_bytes;          // one staged activation row: passes * 1024 bytes, zero past the last column
+};
+
+// The halves of a dword as binary32 (the compiler folds these conversions into v_fma_mix_f32's operand selects).  The
+// dwords are taken as scalars on purpose: a bit cast of a component of a four-wide vector has been miscompiled by this
+// hipcc inside unrolled loops (every use read component 0).
+__device__ __forceinline__ float half_lo(unsigned w) { return (float)__builtin_bit_cast(_Float16, (unsigned short)(w & 0xFFFFu)); }
+__device__ __forceinline__ float half_hi(unsigned w) { return (float)__builtin_bit_cast(_Float16, (unsigned short)(w >> 16)); }
+
+// acc[j] += e_j * x for the six values of one table entry (three dwords) and one activation
+__device__ __forceinline__ void mac6(float (&acc)[6], unsigned e0, unsigned e1, unsigned e2, float xf) {
+  acc[0] = __builtin_fmaf(half_lo(e0), xf, acc[0]);
+  acc[1] = __builtin_fmaf(half_hi(e0), xf, acc[1]);
+  acc[2] = __builtin_fmaf(half_lo(e1), xf, acc[2]);
+  acc[3] = __builtin_fmaf(half_hi(e1), xf, acc[3]);
+  acc[4] = __builtin_fmaf(half_lo(e2), xf, acc[4]);
+  acc[5] = __builtin_fmaf(half_hi(e2), xf, acc[5]);
+}
+
+template <int RES_BITS, int B>
+__global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPlan plan, const __half *__restrict__ x, long long ldx,
+                                                               __half *__restrict__ y, long long ldy) {
+  typedef Layout<RES_BITS> LY;
+  constexpr int RB = RES_BITS ? RES_BITS : 8;
+  constexpr int NR = RES_BITS == 12 ? 3 : 2;             // dwords of a lane's residual indices
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const int lane = threadIdx.x & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int WS = 1 << plan.ws_log2, SPW = DW >> plan.ws_log2;      // waves per stream, streams per group
+  const int ws_i = wv & (WS - 1), slot = wv >> plan.ws_log2;
+
+  // ---- tables into LDS (16-byte entries, zero past k), activation rows (zero past the last column), their sums
+  {
+    const unsigned *src = reinterpret_cast<const unsigned *>(p.cb);
+    for (int e = threadIdx.x; e < 4096; e += DW * 64) {
+      uint4v val = {0u, 0u, 0u, 0u};
+      if (e < p.k) { val.x = src[e * 3]; val.y = src[e * 3 + 1]; val.z = src[e * 3 + 2]; }
+      *reinterpret_cast<uint4v *>(lds + LY::MAIN_OFF + e * 16) = val;
+    }
+    if (RES_BITS) {
+      const unsigned *rsrc = reinterpret_cast<const unsigned *>(p.cb_res);
+      for (int e = threadIdx.x; e < (1 << RB); e += DW * 64) {
+        uint4v val = {0u, 0u, 0u, 0u};
+        if (e < p.k_res) { val.x = rsrc[e * 3]; val.y = rsrc[e * 3 + 1]; val.z = rsrc[e * 3 + 2]; }
+        *reinterpret_cast<uint4v *>(lds + LY::RES_OFF + LY::RES_ADD + e * 16) = val;
+      }
+    }
+    float *xsum = reinterpret_cast<float *>(lds + plan.lds_xsum);             // [B][DW]
+#pragma unroll
+    for (int t = 0; t < B; ++t) {
+      const __half *xt = x + (long long)t * ldx;                             // the layer has no outlier columns: column n is x[n]
+      float sum = 0.0f;
+      for (int c = (int)threadIdx.x * 8; c < plan.passes * 512; c += DW * 64 * 8) {
+        uint4v val = {0u, 0u, 0u, 0u};
+        if (c + 8 <= p.P) {
+          val = *reinterpret_cast<const uint4v *>(xt + c);                   // 16-byte aligned: checked on the host
+        } else if (c < p.P) {
+          unsigned short h[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) h[i] = c + i < p.P ? __half_as_ushort(xt[c + i]) : (unsigned short)0;
+          val.x = h[0] | ((unsigned)h[1] << 16); val.y = h[2] | ((unsigned)h[3] << 16);
+          val.z = h[4] | ((unsigned)h[5] << 16); val.w = h[6] | ((unsigned)h[7] << 16);
+        }
+        *reinterpret_cast<uint4v *>(lds + plan.lds_x + (unsigned)t * plan.x_row_bytes + (unsigned)c * 2u) = val;
+        sum += half_pair_sum(val.x) + half_pair_sum(val.y) + half_pair_sum(val.z) + half_pair_sum(val.w);
+      }
+      sum = wave_sum(sum);
+      if (lane == 0) xsum[t * DW + wv] = sum;
+    }
+  }
+  __syncthreads();
+
+  const unsigned st_main = (unsigned)p.stride, st_res = (unsigned)p.stride_res;
+  const __amdgpu_buffer_rsrc_t r_main = make_rsrc(p.idx, (unsigned)p.S * st_main);
+  const __amdgpu_buffer_rsrc_t r_res = make_rsrc(RES_BITS ? p.idx_res : p.idx, RES_BITS ? (unsigned)p.S * st_res : 0u);
+  const unsigned a_x = lds_address(lds) + plan.lds_x + (unsigned)lane * 16u;
+
+  // The wave's work is one sequence of units, unit k = (group k / ppw of streams, pass k % ppw of this wave in the stream).
+  // A unit past the end of the streams or of a stream's passes is walked like any other -- the barriers below need every
+  // wave -- on the first stream's first pass, and its products are dropped.
+  const int K = plan.iters * plan.ppw;
+  auto unit_stream = [&](int it) { return (it * (int)gridDim.x + (int)blockIdx.x) * SPW + slot; };
+  int l_it = 0, l_i = 0;                               // the loader's position in the same sequence, DEPTH units ahead
+  auto load_unit = [&](Window<3> &wm, Window<NR> &wr) {
+    const int stream = unit_stream(l_it), q = ws_i + l_i * WS;
+    const bool on = l_it < plan.iters && stream < p.S && q < plan.passes;
+    if (++l_i == plan.ppw) { l_i = 0; ++l_it; }
+    const unsigned s_off = on ? (unsigned)stream : 0u, q_off = on ? (unsigned)q : 0u;
+    load_window(wm, r_main, s_off * st_main + q_off * 768u + (unsigned)lane * 12u, 0u);
+    if (RES_BITS == 12) load_window(wr, r_res, s_off * st_res + q_off * 768u + (unsigned)lane * 12u, 0u);
+    if (RES_BITS == 8) load_window(wr, r_res, s_off * st_res + q_off * 512u + (unsigned)lane * 8u, 0u);
+  };
+
+  Window<3> win[DEPTH];
+  Window<NR> wres[DEPTH];
+#pragma unroll
+  for (int d = 0; d < DEPTH; ++d) load_unit(win[d], wres[d]);
+
+  float acc[B][6];
+#pragma unroll
+  for (int t = 0; t < B; ++t)
+#pragma unroll
+    for (int j = 0; j < 6; ++j) acc[t][j] = 0.0f;
+  float *part = reinterpret_cast<float *>(lds + plan.lds_part);               // [DW][B * 6]
+  const float *xsum = reinterpret_cast<const float *>(lds + plan.lds_xsum);
+
+  int it = 0, i = 0;                                   // group and pass-of-this-wave of the current unit
+  for (int k0 = 0; k0 < K; k0 += DEPTH) {
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+      const int k = k0 + d;
+      if (k < K) {
+        const int stream = unit_stream(it), q = ws_i + i * WS;
+        const bool on = stream < p.S && q < plan.passes;
+        const Window<3> cm = win[d];
+        const Window<NR> cr = wres[d];
+        load_unit(win[d], wres[d]);                    // refill the slot; the copies above are what this unit uses
+        if (on) {
+          uint4v e[VPL], f[VPL];
+#pragma unroll
+          for (int u = 0; u < VPL; ++u) lds_gather16<LY::MAIN_OFF>(e[u], field_addr<12, LY::MAIN_SH>(cm, u));
+          if (RES_BITS) {
+#pragma unroll
+            for (int u = 0; u < VPL; ++u) lds_gather16<LY::RES_OFF>(f[u], field_addr<RB, LY::RES_SH>(cr, u) + LY::RES_ADD);
+          }
+          uint4v xv[B];
+#pragma unroll
+          for (int t = 0; t < B; ++t)
+            asm volatile("ds_read_b128 %0, %1" : "=v"(xv[t]) : "v"(a_x + (unsigned)t * plan.x_row_bytes + (unsigned)q * 1024u));
+          lds_gather_wait();
+#pragma unroll
+          for (int u = 0; u < VPL; ++u) { settle(e[u]); if (RES_BITS) settle(f[u]); }
+#pragma unroll
+          for (int t = 0; t < B; ++t) {
+            settle(xv[t]);
+            const unsigned xd[4] = {xv[t].x, xv[t].y, xv[t].z, xv[t].w};
+#pragma unroll
+            for (int u = 0; u < VPL; ++u) {
+              const float xf = (u & 1) ? half_hi(xd[u >> 1]) : half_lo(xd[u >> 1]);
+              mac6(acc[t], e[u].x, e[u].y, e[u].z, xf);
+              if (RES_BITS) mac6(acc[t], f[u].x, f[u].y, f[u].z, xf);
+            }
+          }
+        }
+        if (i == plan.ppw - 1) {
+          // ---- the stream ends for this wave: sum over the lanes, meet the other waves of the stream, store
+          float mine = 0.0f;                           // lane l < 6 B keeps value (token l / 6, row l % 6)
+#pragma unroll
+          for (int t = 0; t < B; ++t)
+#pragma unroll
+            for (int j = 0; j < 6; ++j) {
+              const float s = wave_sum(acc[t][j]);
+              if (lane == t * 6 + j) mine = s;
+              acc[t][j] = 0.0f;
+            }
+          if (WS > 1) {
+            if (lane < 6 * B) part[wv * (6 * B) + lane] = mine;
+            lds_barrier();
+            if (ws_i == 0 && lane < 6 * B) {
+              mine = 0.0f;
+              for (int w = 0; w < WS; ++w) mine += part[(wv + w) * (6 * B) + lane];
+            }
+          }
+          if (ws_i == 0 && lane < 6 * B && stream < p.S) {
+            const int t = lane / 6, o = stream * 6 + (lane - t * 6);
+            if (o < p.out_features) {
+              float xs = 0.0f;
+#pragma unroll
+              for (int w = 0; w < DW; ++w) xs += xsum[t * DW + w];
+              const float sc = p.scale ? __half2float(p.scale[o]) : 1.0f, bi = p.bias ? __half2float(p.bias[o]) : 0.0f;
+              y[(long long)t * ldy + o] = __float2half_rn(__fmaf_rn(sc, mine, bi * xs));
+            }
+          }
+          if (WS > 1) lds_barrier();                   // the partial sums are free again
+          i = 0; ++it;
+        } else {
+          ++i;
+        }
+      }
+    }
+  }
+}
+
+int g_cus_down = 0;
+int cu_count() {
+  if (!g_cus_down) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+    g_cus_down = n;
+  }
+  return g_cus_down;
+}
+
+template <int RES_BITS, int B>
+int launch_one(const Params &p, const DownPlan &plan, unsigned lds_bytes, unsigned grid, const __half *x, long long ldx, __half *y,
+               long long ldy, hipStream_t s) {
+  static bool configured = false;
+  auto kernel = gemv_down_v6_kernel<RES_BITS, B>;
+  if (!configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+      return VQ_ERR_HIP;
+    configured = true;
+  }
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(DW * 64), lds_bytes, s, p, plan, x, ldx, y, ldy);
+  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+}  // namespace
+
+// Whether the kernel above takes this layer and these buffers.
+bool gemv_down_applicable(const Params &p, const __half *x, long long ldx) {
+  if (p.orientation != 1 || p.v != 6 || p.bits != 12 || p.n_out != 0 || p.n_groups != 1) return false;
+  if (p.k_res && p.bits_res != 12 && p.bits_res != 8) return false;
+  if ((reinterpret_cast<uintptr_t>(x) & 15) || (ldx & 7)) return false;
+  const long long max_stride = p.stride > p.stride_res ? p.stride : p.stride_res;
+  return (long long)p.S * max_stride < (1LL << 31);                          // 32-bit buffer offsets
+}
+
+// Launch for one group of 1, 2 or 4 batch rows.  VQ_ERR_UNSUPPORTED when the rows do not fit LDS beside the tables.
+int launch_gemv_down(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
+  DownPlan plan{};
+  const int rb = p.k_res ? p.bits_res : 0;
+  unsigned off = rb == 0 ? Layout<0>::BYTES : rb == 8 ? Layout<8>::BYTES : Layout<12>::BYTES;
+  plan.passes = (p.P + 511) / 512;
+  plan.x_row_bytes = (unsigned)plan.passes * 1024u;
+  plan.lds_x = off; off += plan.x_row_bytes * (unsigned)batch;
+  plan.lds_xsum = off; off += (unsigned)(batch * DW) * 4u;
+  plan.lds_part = off; off += (unsigned)(DW * 6 * batch) * 4u;
+  if (off > 160u * 1024u) return VQ_ERR_UNSUPPORTED;
+  // waves per stream: the choice with the fewest passes on the busiest wave, a stream's end counted as a third of a pass
+  // (half when waves have to meet)
+  const int cus = cu_count();
+  double best = 1e30;
+  unsigned grid = 1;
+  for (int l = 0; l <= 3; ++l) {
+    const int WS = 1 << l, groups = (p.S + (DW >> l) - 1) / (DW >> l);
+    const int iters = (groups + cus - 1) / cus, ppw = (plan.passes + WS - 1) / WS;
+    const double cost = iters * (ppw + (l ? 0.5 : 0.33));
+    if (cost < best) { best = cost; plan.ws_log2 = l; plan.ppw = ppw; plan.iters = iters; grid = (unsigned)((groups + iters - 1) / iters); }
+  }
+#define VQ_CASE(R, BB) if (rb == R && batch == BB) return launch_one<R, BB>(p, plan, off, grid, x, ldx, y, ldy, s);
+  VQ_CASE(0, 1) VQ_CASE(12, 1) VQ_CASE(8, 1)
+  VQ_CASE(0, 2) VQ_CASE(12, 2) VQ_CASE(8, 2)
+  VQ_CASE(0, 4) VQ_CASE(12, 4) VQ_CASE(8, 4)
+#undef VQ_CASE
+  return VQ_ERR_UNSUPPORTED;
+}
+
+}  // namespace vq

@@ -54,6 +54,14 @@ SMALL = {
     "down_groups": dict(out_features=133, in_features=1000, v=6, k=4096, k_res=4096, group_vectors=100, orientation=1),
     "down_odd": dict(out_features=37, in_features=203, v=5, k=37, k_res=11, n_outlier_cols=9, v_out=3, k_out=5, orientation=1),
     "down_v16": dict(out_features=33, in_features=530, v=16, k=300, with_scale=False, orientation=1),
+    # ... and the shapes of the fast kernel for that orientation (v = 6, 12-bit indices, no outlier columns, rows of x on
+    # 16-byte boundaries): ragged last stream and last pass, more stream groups than workgroups, streams split over waves
+    "down_fast_v6": dict(out_features=70, in_features=392, v=6, k=4096, orientation=1),
+    "down_fast_res12": dict(out_features=133, in_features=1000, v=6, k=4096, k_res=4096, orientation=1),
+    "down_fast_res8": dict(out_features=150, in_features=1208, v=6, k=4096, k_res=256, orientation=1),
+    "down_fast_many_streams": dict(out_features=20501, in_features=200, v=6, k=4096, orientation=1),
+    "down_fast_long": dict(out_features=40, in_features=7000, v=6, k=4096, k_res=4096, orientation=1),
+    "down_fast_small_tables": dict(out_features=300, in_features=4096, v=6, k=3000, k_res=200, with_bias=False, orientation=1),
     "down_dense_gemm": dict(out_features=203, in_features=1024, v=6, k=4096, k_res=4096, n_outlier_cols=16, v_out=4, k_out=4096, orientation=1),
 }
 
