@@ -15,6 +15,10 @@
 // activation rows in LDS and takes several groups of 8 / WS streams in turn.  Index words run DEPTH passes ahead in a
 // register ring.  A stream ends with a wave-wide sum of the 6 x batch values, a meeting of the WS waves in LDS when
 // WS > 1, and y = scale * sum + bias * sum(x) per output row.
+//
+// Outlier columns (Sec. 3.2.3; their streams belong to blocks of v_out rows, any v_out and k_out) are few: before the
+// main loop each wave works out, for a share of the workgroup's output rows, the row's sum over the outlier columns --
+// lanes over the columns, index and centroid element straight from memory -- and leaves it in LDS for the row's end.
 #include "vq_common.hpp"
 #include "vq_v6.hpp"
 
@@ -33,6 +37,7 @@ struct DownPlan {
   int ppw;                       // passes per wave and stream
   int iters;                     // groups of DW >> ws_log2 streams per workgroup
   unsigned lds_x, lds_xsum, lds_part;
+  unsigned lds_osum;             // sums over the outlier columns: [workgroup's rows][batch], then [batch] activation sums
   unsigned x_row_bytes;          // one staged activation row: passes * 1024 bytes, zero past the last column
 };
 
@@ -83,12 +88,13 @@ __global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPla
     float *xsum = reinterpret_cast<float *>(lds + plan.lds_xsum);             // [B][DW]
 #pragma unroll
     for (int t = 0; t < B; ++t) {
-      const __half *xt = x + (long long)t * ldx;                             // the layer has no outlier columns: column n is x[n]
+      const __half *xt = x + (long long)t * ldx + p.n_out;                   // main column n is x[n_out + n]
+      const bool wide = (p.n_out & 7) == 0;                                  // then the 16-byte pieces are aligned (x is, on the host's word)
       float sum = 0.0f;
       for (int c = (int)threadIdx.x * 8; c < plan.passes * 512; c += DW * 64 * 8) {
         uint4v val = {0u, 0u, 0u, 0u};
-        if (c + 8 <= p.P) {
-          val = *reinterpret_cast<const uint4v *>(xt + c);                   // 16-byte aligned: checked on the host
+        if (wide && c + 8 <= p.P) {
+          val = *reinterpret_cast<const uint4v *>(xt + c);
         } else if (c < p.P) {
           unsigned short h[8];
 #pragma unroll
@@ -101,6 +107,54 @@ __global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPla
       }
       sum = wave_sum(sum);
       if (lane == 0) xsum[t * DW + wv] = sum;
+    }
+  }
+  if (p.Q) {
+    // rows of this workgroup, in the order the main loop ends them: item r = ((group it) * SPW + slot) * 6 + j
+    float *osum = reinterpret_cast<float *>(lds + plan.lds_osum);
+    const int items = plan.iters * SPW * 6;
+    constexpr int UNR = 6;                               // rows a wave works on at once: their loads overlap
+    for (int r0 = wv; r0 < items; r0 += DW * UNR) {
+      float part_o[UNR][B];
+#pragma unroll
+      for (int uu = 0; uu < UNR; ++uu)
+#pragma unroll
+        for (int t = 0; t < B; ++t) part_o[uu][t] = 0.0f;
+      for (int c = lane; c < p.Q; c += 64) {
+        float xo[B];
+#pragma unroll
+        for (int t = 0; t < B; ++t) xo[t] = __half2float(x[(long long)t * ldx + c]);
+#pragma unroll
+        for (int uu = 0; uu < UNR; ++uu) {
+          const int r = r0 + uu * DW;
+          const int grp_slot = r / 6, j = r - grp_slot * 6;
+          const int it_r = grp_slot / SPW, slot_r = grp_slot - it_r * SPW;
+          const int o = ((it_r * (int)gridDim.x + (int)blockIdx.x) * SPW + slot_r) * 6 + j;
+          if (r < items && o < p.out_features) {
+            const int sq = o / p.v_out, jo = o - sq * p.v_out;
+            const unsigned i = min(load_index(p.idx_out + (long long)sq * p.stride_out, c, p.bits_out), (unsigned)p.k_out - 1u);
+            const float w = __half2float(p.cb_out[(long long)i * p.v_out + jo]);
+#pragma unroll
+            for (int t = 0; t < B; ++t) part_o[uu][t] = __fmaf_rn(w, xo[t], part_o[uu][t]);
+          }
+        }
+      }
+#pragma unroll
+      for (int uu = 0; uu < UNR; ++uu)
+#pragma unroll
+        for (int t = 0; t < B; ++t) {
+          const float tot = wave_sum(part_o[uu][t]);
+          if (lane == 0 && r0 + uu * DW < items) osum[(r0 + uu * DW) * B + t] = tot;
+        }
+    }
+    if (wv == 0) {                                       // activation sums over the outlier columns
+#pragma unroll
+      for (int t = 0; t < B; ++t) {
+        float sx = 0.0f;
+        for (int c = lane; c < p.Q; c += 64) sx += __half2float(x[(long long)t * ldx + c]);
+        sx = wave_sum(sx);
+        if (lane == 0) osum[items * B + t] = sx;
+      }
     }
   }
   __syncthreads();
@@ -137,6 +191,7 @@ __global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPla
 #pragma unroll
     for (int j = 0; j < 6; ++j) acc[t][j] = 0.0f;
   float *part = reinterpret_cast<float *>(lds + plan.lds_part);               // [DW][B * 6]
+  const float *osum = reinterpret_cast<const float *>(lds + plan.lds_osum);
   const float *xsum = reinterpret_cast<const float *>(lds + plan.lds_xsum);
 
   int it = 0, i = 0;                                   // group and pass-of-this-wave of the current unit
@@ -202,6 +257,10 @@ __global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPla
               float xs = 0.0f;
 #pragma unroll
               for (int w = 0; w < DW; ++w) xs += xsum[t * DW + w];
+              if (p.Q) {
+                mine += osum[((it * SPW + slot) * 6 + (lane - t * 6)) * B + t];
+                xs += osum[plan.iters * SPW * 6 * B + t];
+              }
               const float sc = p.scale ? __half2float(p.scale[o]) : 1.0f, bi = p.bias ? __half2float(p.bias[o]) : 0.0f;
               y[(long long)t * ldy + o] = __float2half_rn(__fmaf_rn(sc, mine, bi * xs));
             }
@@ -244,7 +303,7 @@ int launch_one(const Params &p, const DownPlan &plan, unsigned lds_bytes, unsign
 
 // Whether the kernel above takes this layer and these buffers.
 bool gemv_down_applicable(const Params &p, const __half *x, long long ldx) {
-  if (p.orientation != 1 || p.v != 6 || p.bits != 12 || p.n_out != 0 || p.n_groups != 1) return false;
+  if (p.orientation != 1 || p.v != 6 || p.bits != 12 || p.n_groups != 1) return false;
   if (p.k_res && p.bits_res != 12 && p.bits_res != 8) return false;
   if ((reinterpret_cast<uintptr_t>(x) & 15) || (ldx & 7)) return false;
   const long long max_stride = p.stride > p.stride_res ? p.stride : p.stride_res;
@@ -261,7 +320,7 @@ int launch_gemv_down(const Params &p, const __half *x, long long ldx, int batch,
   plan.lds_x = off; off += plan.x_row_bytes * (unsigned)batch;
   plan.lds_xsum = off; off += (unsigned)(batch * DW) * 4u;
   plan.lds_part = off; off += (unsigned)(DW * 6 * batch) * 4u;
-  if (off > 160u * 1024u) return VQ_ERR_UNSUPPORTED;
+  plan.lds_osum = off;                                   // sized below, once the groups per workgroup are known
   // waves per stream: the choice with the fewest passes on the busiest wave, a stream's end counted as a third of a pass
   // (half when waves have to meet)
   const int cus = cu_count();
@@ -273,6 +332,8 @@ int launch_gemv_down(const Params &p, const __half *x, long long ldx, int batch,
     const double cost = iters * (ppw + (l ? 0.5 : 0.33));
     if (cost < best) { best = cost; plan.ws_log2 = l; plan.ppw = ppw; plan.iters = iters; grid = (unsigned)((groups + iters - 1) / iters); }
   }
+  off += p.Q ? (unsigned)((plan.iters * (DW >> plan.ws_log2) * 6 + 1) * batch) * 4u : 0u;
+  if (off > 160u * 1024u) return VQ_ERR_UNSUPPORTED;
 #define VQ_CASE(R, BB) if (rb == R && batch == BB) return launch_one<R, BB>(p, plan, off, grid, x, ldx, y, ldy, s);
   VQ_CASE(0, 1) VQ_CASE(12, 1) VQ_CASE(8, 1)
   VQ_CASE(0, 2) VQ_CASE(12, 2) VQ_CASE(8, 2)

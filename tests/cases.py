@@ -62,6 +62,9 @@ SMALL = {
     "down_fast_many_streams": dict(out_features=20501, in_features=200, v=6, k=4096, orientation=1),
     "down_fast_long": dict(out_features=40, in_features=7000, v=6, k=4096, k_res=4096, orientation=1),
     "down_fast_small_tables": dict(out_features=300, in_features=4096, v=6, k=3000, k_res=200, with_bias=False, orientation=1),
+    "down_fast_outlier": dict(out_features=150, in_features=1208, v=6, k=4096, k_res=256, n_outlier_cols=24, v_out=4, k_out=4096, orientation=1),
+    "down_fast_outlier_41": dict(out_features=261, in_features=2040, v=6, k=4096, n_outlier_cols=41, v_out=4, k_out=4096, orientation=1),
+    "down_fast_outlier_many_streams": dict(out_features=20501, in_features=208, v=6, k=4096, k_res=4096, n_outlier_cols=70, v_out=5, k_out=300, orientation=1),
     "down_dense_gemm": dict(out_features=203, in_features=1024, v=6, k=4096, k_res=4096, n_outlier_cols=16, v_out=4, k_out=4096, orientation=1),
 }
 
