@@ -44,6 +44,12 @@ struct DownPlan {
 // The halves of a dword as binary32 (the compiler folds these conversions into v_fma_mix_f32's operand selects).  The
 // dwords are taken as scalars on purpose: a bit cast of a component of a four-wide vector has been miscompiled by this
 // hipcc inside unrolled loops (every use read component 0).
+// Sum over the wave, the same value in every lane: six DPP steps into lane 63 and a broadcast through a scalar register
+// (the shuffle-based wave_sum goes through the LDS crossbar six times, one after the other; a stream ends with 6 x batch sums).
+__device__ __forceinline__ float wave_total(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wave_reduce_to_lane63(v)), 63));
+}
+
 __device__ __forceinline__ float half_lo(unsigned w) { return (float)__builtin_bit_cast(_Float16, (unsigned short)(w & 0xFFFFu)); }
 __device__ __forceinline__ float half_hi(unsigned w) { return (float)__builtin_bit_cast(_Float16, (unsigned short)(w >> 16)); }
 
@@ -68,6 +74,52 @@ __global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPla
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int WS = 1 << plan.ws_log2, SPW = DW >> plan.ws_log2;      // waves per stream, streams per group
   const int ws_i = wv & (WS - 1), slot = wv >> plan.ws_log2;
+
+  // ---- outlier columns, first half: rows of this workgroup in the order the main loop ends them, item
+  // r = ((group it) * SPW + slot) * 6 + j.  A wave takes UNR rows at a time, lanes over the columns.  All loads are
+  // unconditional (range-checked; a row past the end reads row 0 and counts as zero) so that they overlap, and the index
+  // words of the first batch are asked for here, before the tables are staged, so that their trip to memory overlaps it.
+  constexpr int UNR = 6;
+  struct OutPre { unsigned w0[UNR], w1[UNR]; float xo[B]; };
+  const int items = plan.iters * SPW * 6;
+  const __amdgpu_buffer_rsrc_t r_oidx = make_rsrc(p.Q ? p.idx_out : p.idx, p.Q ? (unsigned)p.S_out * (unsigned)p.stride_out : 0u);
+  const __amdgpu_buffer_rsrc_t r_ocb = make_rsrc(p.Q ? p.cb_out : p.cb, p.Q ? (unsigned)(p.k_out * p.v_out) * 2u : 0u);
+  const __amdgpu_buffer_rsrc_t r_xo = make_rsrc(x, (unsigned)(((long long)(B - 1) * ldx + p.Q) * 2));
+  auto item_row = [&](int r) {                           // output row of item r, or -1
+    const int grp_slot = r / 6, j = r - grp_slot * 6;
+    const int it_r = grp_slot / SPW, slot_r = grp_slot - it_r * SPW;
+    const int o = ((it_r * (int)gridDim.x + (int)blockIdx.x) * SPW + slot_r) * 6 + j;
+    return r < items && o < p.out_features ? o : -1;
+  };
+  auto out_issue = [&](int r0, int c, OutPre &pre) {
+#pragma unroll
+    for (int t = 0; t < B; ++t)
+      pre.xo[t] = __half2float(__ushort_as_half((unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r_xo, (unsigned)(t * ldx + c) * 2u, 0, 0)));
+#pragma unroll
+    for (int uu = 0; uu < UNR; ++uu) {
+      const int o = max(item_row(r0 + uu * DW), 0);
+      const unsigned bit = (unsigned)c * (unsigned)p.bits_out;
+      const unsigned woff = (unsigned)(o / p.v_out) * (unsigned)p.stride_out + (bit >> 5) * 4u;
+      pre.w0[uu] = __builtin_amdgcn_raw_buffer_load_b32(r_oidx, woff, 0, 0);
+      pre.w1[uu] = __builtin_amdgcn_raw_buffer_load_b32(r_oidx, woff + 4u, 0, 0);
+    }
+  };
+  auto out_finish = [&](int r0, int c, const OutPre &pre, float (&part_o)[UNR][B]) {
+#pragma unroll
+    for (int uu = 0; uu < UNR; ++uu) {
+      const int o = item_row(r0 + uu * DW);
+      const bool ok = o >= 0 && c < p.Q;
+      const int oc = max(o, 0), jo = oc - (oc / p.v_out) * p.v_out;
+      const unsigned bit = (unsigned)c * (unsigned)p.bits_out;
+      const unsigned i = min(__builtin_amdgcn_alignbit(pre.w1[uu], pre.w0[uu], bit & 31u) & ((1u << p.bits_out) - 1u), (unsigned)p.k_out - 1u);
+      const unsigned short wh = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r_ocb, (i * (unsigned)p.v_out + (unsigned)jo) * 2u, 0, 0);
+      const float w = ok ? __half2float(__ushort_as_half(wh)) : 0.0f;
+#pragma unroll
+      for (int t = 0; t < B; ++t) part_o[uu][t] = __fmaf_rn(w, pre.xo[t], part_o[uu][t]);
+    }
+  };
+  OutPre pre0;
+  if (p.Q) out_issue(wv, lane, pre0);
 
   // ---- tables into LDS (16-byte entries, zero past k), activation rows (zero past the last column), their sums
   {
@@ -110,40 +162,27 @@ __global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPla
     }
   }
   if (p.Q) {
-    // rows of this workgroup, in the order the main loop ends them: item r = ((group it) * SPW + slot) * 6 + j
     float *osum = reinterpret_cast<float *>(lds + plan.lds_osum);
-    const int items = plan.iters * SPW * 6;
-    constexpr int UNR = 6;                               // rows a wave works on at once: their loads overlap
     for (int r0 = wv; r0 < items; r0 += DW * UNR) {
       float part_o[UNR][B];
 #pragma unroll
       for (int uu = 0; uu < UNR; ++uu)
 #pragma unroll
         for (int t = 0; t < B; ++t) part_o[uu][t] = 0.0f;
-      for (int c = lane; c < p.Q; c += 64) {
-        float xo[B];
-#pragma unroll
-        for (int t = 0; t < B; ++t) xo[t] = __half2float(x[(long long)t * ldx + c]);
-#pragma unroll
-        for (int uu = 0; uu < UNR; ++uu) {
-          const int r = r0 + uu * DW;
-          const int grp_slot = r / 6, j = r - grp_slot * 6;
-          const int it_r = grp_slot / SPW, slot_r = grp_slot - it_r * SPW;
-          const int o = ((it_r * (int)gridDim.x + (int)blockIdx.x) * SPW + slot_r) * 6 + j;
-          if (r < items && o < p.out_features) {
-            const int sq = o / p.v_out, jo = o - sq * p.v_out;
-            const unsigned i = min(load_index(p.idx_out + (long long)sq * p.stride_out, c, p.bits_out), (unsigned)p.k_out - 1u);
-            const float w = __half2float(p.cb_out[(long long)i * p.v_out + jo]);
-#pragma unroll
-            for (int t = 0; t < B; ++t) part_o[uu][t] = __fmaf_rn(w, xo[t], part_o[uu][t]);
-          }
+      for (int c0 = 0; c0 < p.Q; c0 += 64) {
+        if (r0 == wv && c0 == 0) {
+          out_finish(r0, lane, pre0, part_o);          // the loads issued before the tables were staged
+        } else {
+          OutPre pre;
+          out_issue(r0, c0 + lane, pre);
+          out_finish(r0, c0 + lane, pre, part_o);
         }
       }
 #pragma unroll
       for (int uu = 0; uu < UNR; ++uu)
 #pragma unroll
         for (int t = 0; t < B; ++t) {
-          const float tot = wave_sum(part_o[uu][t]);
+          const float tot = wave_total(part_o[uu][t]);
           if (lane == 0 && r0 + uu * DW < items) osum[(r0 + uu * DW) * B + t] = tot;
         }
     }
@@ -239,7 +278,7 @@ __global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPla
           for (int t = 0; t < B; ++t)
 #pragma unroll
             for (int j = 0; j < 6; ++j) {
-              const float s = wave_sum(acc[t][j]);
+              const float s = wave_total(acc[t][j]);
               if (lane == t * 6 + j) mine = s;
               acc[t][j] = 0.0f;
             }
