@@ -76,11 +76,20 @@ __global__ __launch_bounds__(256) void dequant_down_kernel(Params p, __half *W, 
 }
 
 int launch_dequant_fast(const Params &p, __half *W, long long ldw, hipStream_t s);
+int launch_dequant_down_fast(const Params &p, __half *W, long long ldw, hipStream_t s);
 
 int launch_dequant(const Params &p, __half *W, long long ldw, hipStream_t s) {
   if (p.orientation == 1) {
     const int bps_main = (p.P + 255) / 256, bps_out = p.Q ? (p.Q + 255) / 256 : 1;
-    const long long main_blocks = (long long)bps_main * p.S, blocks = main_blocks + (long long)bps_out * p.S_out;
+    long long main_blocks = (long long)bps_main * p.S;
+    const int rc = launch_dequant_down_fast(p, W, ldw, s);          // the main columns, when a fast kernel takes them
+    if (rc == VQ_OK) {
+      if (!p.Q) return VQ_OK;
+      main_blocks = 0;                                               // the generic kernel below: outlier streams only
+    } else if (rc != VQ_ERR_UNSUPPORTED) {
+      return rc;
+    }
+    const long long blocks = main_blocks + (long long)bps_out * p.S_out;
     if (blocks > 0x7fffffffLL) return VQ_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(dequant_down_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, W, ldw, bps_main, main_blocks, bps_out);
     return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;

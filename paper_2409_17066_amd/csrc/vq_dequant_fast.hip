@@ -17,6 +17,7 @@ namespace {
 
 typedef unsigned uint4v __attribute__((ext_vector_type(4)));
 typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+typedef unsigned uint3v __attribute__((ext_vector_type(3)));
 
 constexpr int NW = 16;   // waves per workgroup (v = 6 kernel)
 
@@ -224,6 +225,100 @@ __global__ __launch_bounds__(256) void dequant_v8_kernel(Params p, __half *__res
   }
 }
 
+// Orientation 1 (vectors down the output dimension; Sec. 3.1, Algorithm 1), v = 6, 12-bit indices, optional residual:
+// a wave takes 512 consecutive columns of one index stream at a time, eight per lane (three aligned index dwords), and
+// restores the six rows the stream serves: a lane's eight centroids give, row by row, eight consecutive halves -- one
+// 16-byte store each, a wave writes 1 KB of a row at a time.  Tables in LDS, units (stream, 512 columns) dealt round-robin to
+// the waves of all workgroups.  The outlier columns are left to the generic kernel.
+template <int RES_BITS>
+__global__ __launch_bounds__(NW * 64) void dequant_down_v6_kernel(Params p, unsigned lds_res, __half *__restrict__ W, long long ldw, int wide) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  constexpr int RB = RES_BITS ? RES_BITS : 8;
+  const int lane = threadIdx.x & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  {
+    const unsigned *src = reinterpret_cast<const unsigned *>(p.cb);
+    for (int e = threadIdx.x; e < 4096; e += NW * 64) {
+      uint4v val = {0u, 0u, 0u, 0u};
+      if (e < p.k) { val.x = src[e * 3]; val.y = src[e * 3 + 1]; val.z = src[e * 3 + 2]; }
+      *reinterpret_cast<uint4v *>(lds + e * 16) = val;
+    }
+    if (RES_BITS) {
+      const unsigned *r = reinterpret_cast<const unsigned *>(p.cb_res);
+      for (int e = threadIdx.x; e < (1 << RB); e += NW * 64) {
+        uint4v val = {0u, 0u, 0u, 0u};
+        if (e < p.k_res) { val.x = r[e * 3]; val.y = r[e * 3 + 1]; val.z = r[e * 3 + 2]; }
+        *reinterpret_cast<uint4v *>(lds + lds_res + e * 16) = val;
+      }
+    }
+  }
+  __syncthreads();
+  const int passes = (p.P + 511) / 512;
+  const __amdgpu_buffer_rsrc_t r_main = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char *>(p.idx), 0, (unsigned)p.S * (unsigned)p.stride, 0x00020000);
+  const __amdgpu_buffer_rsrc_t r_res = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char *>(RES_BITS ? p.idx_res : p.idx), 0,
+                                                                         RES_BITS ? (unsigned)p.S * (unsigned)p.stride_res : 0u, 0x00020000);
+  const long long units = (long long)p.S * passes, step = (long long)gridDim.x * NW;
+  for (long long unit = (long long)blockIdx.x * NW + wv; unit < units; unit += step) {
+    const int stream = (int)(unit / passes), q = (int)(unit - (long long)stream * passes);
+    const int pos = q * 512 + lane * 8;                     // the lane's first stream position = main column
+    if (pos >= p.P) continue;
+    // range-checked loads: the lane's twelve bytes may run past the stream's last index, and past the last stream
+    const uint3v wm = __builtin_amdgcn_raw_buffer_load_b96(r_main, (unsigned)stream * (unsigned)p.stride + (unsigned)q * 768u + (unsigned)lane * 12u, 0, 0);
+    unsigned r0 = 0u, r1 = 0u, r2 = 0u;
+    if (RES_BITS == 12) {
+      const uint3v wr = __builtin_amdgcn_raw_buffer_load_b96(r_res, (unsigned)stream * (unsigned)p.stride_res + (unsigned)q * 768u + (unsigned)lane * 12u, 0, 0);
+      r0 = wr.x; r1 = wr.y; r2 = wr.z;
+    }
+    if (RES_BITS == 8) {
+      const uint2v wr = __builtin_amdgcn_raw_buffer_load_b64(r_res, (unsigned)stream * (unsigned)p.stride_res + (unsigned)q * 512u + (unsigned)lane * 8u, 0, 0);
+      r0 = wr.x; r1 = wr.y;
+    }
+    const unsigned mw[3] = {wm.x, wm.y, wm.z}, rw[3] = {r0, r1, r2};
+    unsigned ex[8], ey[8], ez[8], fx[8], fy[8], fz[8];      // the eight centroids' dwords (main / residual)
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int bit = u * 12, i0 = bit >> 5, o = bit & 31;
+      const unsigned idx = (o + 12 <= 32 ? mw[i0] >> o : __builtin_amdgcn_alignbit(mw[i0 + 1 < 3 ? i0 + 1 : i0], mw[i0], o)) & 0xFFFu;
+      const uint4v e = *reinterpret_cast<const uint4v *>(lds + idx * 16);
+      ex[u] = e.x; ey[u] = e.y; ez[u] = e.z;
+      fx[u] = fy[u] = fz[u] = 0u;
+      if (RES_BITS) {
+        const int rbit = u * RB, j0 = rbit >> 5, ro = rbit & 31;
+        const unsigned ridx = (ro + RB <= 32 ? rw[j0] >> ro : __builtin_amdgcn_alignbit(rw[j0 + 1 < 3 ? j0 + 1 : j0], rw[j0], ro)) & ((1u << RB) - 1u);
+        const uint4v f = *reinterpret_cast<const uint4v *>(lds + lds_res + ridx * 16);
+        fx[u] = f.x; fy[u] = f.y; fz[u] = f.z;
+      }
+    }
+    const int n_valid = min(8, p.P - pos);
+#pragma unroll
+    for (int j = 0; j < 6; ++j) {
+      const int o = stream * 6 + j;
+      if (o >= p.out_features) break;
+      const float sc = p.scale ? __half2float(p.scale[o]) : 1.0f, bi = p.bias ? __half2float(p.bias[o]) : 0.0f;
+      unsigned out[4];
+#pragma unroll
+      for (int h = 0; h < 4; ++h) {                         // columns 2h and 2h + 1: element j of centroids 2h, 2h + 1
+        const unsigned ma = j < 2 ? ex[2 * h] : j < 4 ? ey[2 * h] : ez[2 * h], mb = j < 2 ? ex[2 * h + 1] : j < 4 ? ey[2 * h + 1] : ez[2 * h + 1];
+        const unsigned ra = j < 2 ? fx[2 * h] : j < 4 ? fy[2 * h] : fz[2 * h], rb = j < 2 ? fx[2 * h + 1] : j < 4 ? fy[2 * h + 1] : fz[2 * h + 1];
+        const unsigned sh = (j & 1) * 16;
+        float da = __half2float(__ushort_as_half((unsigned short)(ma >> sh))), db = __half2float(__ushort_as_half((unsigned short)(mb >> sh)));
+        if (RES_BITS) {
+          da = __fadd_rn(da, __half2float(__ushort_as_half((unsigned short)(ra >> sh))));
+          db = __fadd_rn(db, __half2float(__ushort_as_half((unsigned short)(rb >> sh))));
+        }
+        out[h] = (unsigned)__half_as_ushort(restore(da, sc, bi)) | ((unsigned)__half_as_ushort(restore(db, sc, bi)) << 16);
+      }
+      __half *dst = W + (long long)o * ldw + p.n_out + pos;
+      if (wide && n_valid == 8) {
+        uint4v pk; pk.x = out[0]; pk.y = out[1]; pk.z = out[2]; pk.w = out[3];
+        *reinterpret_cast<uint4v *>(dst) = pk;
+      } else {
+        for (int c = 0; c < n_valid; ++c) dst[c] = __ushort_as_half((unsigned short)(out[c >> 1] >> ((c & 1) * 16)));
+      }
+    }
+  }
+}
+
 int g_cus = 0;
 int cu_count() {
   if (!g_cus) {
@@ -264,6 +359,30 @@ int launch_v6(const Params &p, DqPlan plan, unsigned lds_bytes, __half *W, long 
 }
 
 }  // namespace
+
+// Main columns of a layer of orientation 1 (v = 6, 12-bit indices, one codebook group); VQ_ERR_UNSUPPORTED otherwise.
+// The outlier columns, if any, are the caller's (generic kernel).
+int launch_dequant_down_fast(const Params &p, __half *W, long long ldw, hipStream_t s) {
+  static const bool off = [] { const char *e = getenv("VQ_DEQUANT_KERNEL"); return e && e[0] == 'g'; }();
+  if (off || p.orientation != 1 || p.v != 6 || p.bits != 12 || p.n_groups != 1) return VQ_ERR_UNSUPPORTED;
+  if (p.k_res && p.bits_res != 12 && p.bits_res != 8) return VQ_ERR_UNSUPPORTED;
+  if ((long long)p.S * max(p.stride, p.stride_res) >= (1LL << 31)) return VQ_ERR_UNSUPPORTED;      // 32-bit buffer offsets
+  const unsigned lds_res = 4096u * 16u;
+  const unsigned lds_bytes = lds_res + (p.k_res ? (1u << p.bits_res) * 16u : 0u);
+  const int wide = ((reinterpret_cast<uintptr_t>(W) & 15) == 0 && (ldw & 7) == 0 && (p.n_out & 7) == 0) ? 1 : 0;
+  const long long units = (long long)p.S * ((p.P + 511) / 512);
+  const long long want = (units + NW - 1) / NW, slots = (long long)cu_count() * (2u * lds_bytes <= 160u * 1024u ? 2 : 1);
+  const unsigned grid = (unsigned)max(1LL, min(want, slots));
+  const void *kernel = !p.k_res ? reinterpret_cast<const void *>(dequant_down_v6_kernel<0>)
+                       : p.bits_res == 12 ? reinterpret_cast<const void *>(dequant_down_v6_kernel<12>)
+                                          : reinterpret_cast<const void *>(dequant_down_v6_kernel<8>);
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return VQ_ERR_HIP;
+  Params pc = p;
+  unsigned lr = lds_res;
+  int w = wide;
+  void *args[] = {&pc, &lr, &W, &ldw, &w};
+  return hipLaunchKernel(kernel, dim3(grid), dim3(NW * 64), args, lds_bytes, s) == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
 
 // Returns VQ_ERR_UNSUPPORTED when no fast kernel takes the layer (the caller then uses the generic kernel).
 int launch_dequant_fast(const Params &p, __half *W, long long ldw, hipStream_t s) {
