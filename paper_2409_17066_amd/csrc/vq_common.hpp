@@ -31,6 +31,7 @@ int make_params(const vq_layer_desc *d, Params *p);
 
 // Kernel launchers (each returns a vq_status).
 int launch_dequant(const Params &p, __half *W, long long ldw, hipStream_t s);
+int launch_dequant_outliers(const Params &p, __half *W, long long ldw, hipStream_t s);   // generic kernel, outlier columns of a row-wise layer only
 int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
 size_t gemv_workspace_bytes(const Params &p, const __half *x, long long ldx, int batch);
 int launch_gemv_ws(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, void *workspace,

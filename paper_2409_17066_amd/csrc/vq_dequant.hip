@@ -75,6 +75,17 @@ __global__ __launch_bounds__(256) void dequant_down_kernel(Params p, __half *W, 
   }
 }
 
+// The outlier columns of a row-wise layer only (the main columns were restored by a fast kernel).
+int launch_dequant_outliers(const Params &p, __half *W, long long ldw, hipStream_t s) {
+  Params q = p;
+  q.P = 0;                                   // the generic kernel's slots are outlier vectors first, then main vectors
+  const int blocks_per_row = (q.Q + 255) / 256;
+  const long long blocks = (long long)blocks_per_row * q.out_features;
+  if (blocks > 0x7fffffffLL) return VQ_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(dequant_generic_kernel, dim3((unsigned)blocks), dim3(256), 0, s, q, W, ldw, blocks_per_row);
+  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
 int launch_dequant_fast(const Params &p, __half *W, long long ldw, hipStream_t s);
 int launch_dequant_down_fast(const Params &p, __half *W, long long ldw, hipStream_t s);
 

@@ -225,6 +225,104 @@ __global__ __launch_bounds__(256) void dequant_v8_kernel(Params p, __half *__res
   }
 }
 
+// The same layers when W allows aligned 16-byte stores everywhere (W 16-byte aligned, ldw and the outlier column count
+// multiples of 8), main columns only, one codebook group: a wave takes 256 consecutive vectors of a row at a time, four per
+// lane (48 index bits: two dwords and a funnel shift), so that the trip through the LDS strip -- each lane leaves its 48
+// bytes, then reads three 16-byte pieces in store order -- ends in three stores of 1 KB per wave instead of one of 768
+// bytes, and a row has a third as many units.  blockDim.x / 64 waves, a 3 KB strip each.
+template <int RES_BITS>
+__global__ __launch_bounds__(1024) void dequant_v6_wide_kernel(Params p, unsigned lds_res, unsigned lds_strip, __half *__restrict__ W, long long ldw) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  constexpr int RB = RES_BITS ? RES_BITS : 8;
+  const int lane = threadIdx.x & 63, n_waves = (int)blockDim.x >> 6;
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  {
+    const unsigned *src = reinterpret_cast<const unsigned *>(p.cb);
+    for (int e = threadIdx.x; e < 4096; e += (int)blockDim.x) {
+      uint4v val = {0u, 0u, 0u, 0u};
+      if (e < p.k) { val.x = src[e * 3]; val.y = src[e * 3 + 1]; val.z = src[e * 3 + 2]; }
+      *reinterpret_cast<uint4v *>(lds + e * 16) = val;
+    }
+    if (RES_BITS) {
+      const unsigned *r = reinterpret_cast<const unsigned *>(p.cb_res);
+      for (int e = threadIdx.x; e < (1 << RB); e += (int)blockDim.x) {
+        uint4v val = {0u, 0u, 0u, 0u};
+        if (e < p.k_res) { val.x = r[e * 3]; val.y = r[e * 3 + 1]; val.z = r[e * 3 + 2]; }
+        *reinterpret_cast<uint4v *>(lds + lds_res + e * 16) = val;
+      }
+    }
+  }
+  __syncthreads();
+  const __amdgpu_buffer_rsrc_t r_main = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char *>(p.idx), 0, (unsigned)p.out_features * (unsigned)p.stride, 0x00020000);
+  const __amdgpu_buffer_rsrc_t r_res = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char *>(RES_BITS ? p.idx_res : p.idx), 0,
+                                                                         RES_BITS ? (unsigned)p.out_features * (unsigned)p.stride_res : 0u, 0x00020000);
+  unsigned char *strip = lds + lds_strip + wv * 3072;
+  const int cpr = (p.P + 255) / 256;                       // units per row
+  const long long units = (long long)p.out_features * cpr, step = (long long)gridDim.x * n_waves;
+  // what a unit needs from memory is asked for one unit ahead
+  struct Fetch { unsigned m0, m1, r0, r1; };
+  const unsigned lane_off = ((unsigned)lane * 6u) & ~3u, lane_sh = ((unsigned)lane & 1u) * 16u;
+  auto fetch = [&](long long unit, Fetch &f) {
+    const int o = (int)(unit / cpr), q = (int)(unit - (long long)o * cpr);
+    const uint2v m = __builtin_amdgcn_raw_buffer_load_b64(r_main, (unsigned)o * (unsigned)p.stride + (unsigned)q * 384u + lane_off, 0, 0);
+    f.m0 = m.x; f.m1 = m.y; f.r0 = f.r1 = 0u;
+    if (RES_BITS == 12) {
+      const uint2v r = __builtin_amdgcn_raw_buffer_load_b64(r_res, (unsigned)o * (unsigned)p.stride_res + (unsigned)q * 384u + lane_off, 0, 0);
+      f.r0 = r.x; f.r1 = r.y;
+    }
+    if (RES_BITS == 8) f.r0 = __builtin_amdgcn_raw_buffer_load_b32(r_res, (unsigned)o * (unsigned)p.stride_res + (unsigned)q * 256u + (unsigned)lane * 4u, 0, 0);
+  };
+  const long long first = (long long)blockIdx.x * n_waves + wv;
+  Fetch cur, nxt;
+  if (first < units) fetch(first, cur);
+  for (long long unit = first; unit < units; unit += step) {
+    if (unit + step < units) fetch(unit + step, nxt);
+    const int o = (int)(unit / cpr), q = (int)(unit - (long long)o * cpr);
+    const float sc = p.scale ? __half2float(p.scale[o]) : 1.0f, bi = p.bias ? __half2float(p.bias[o]) : 0.0f;
+    // the lane's 48 index bits, first index at bit 0
+    const unsigned w0 = __builtin_amdgcn_alignbit(cur.m1, cur.m0, lane_sh), w1 = cur.m1 >> lane_sh;
+    const unsigned idx[4] = {w0 & 0xFFFu, (w0 >> 12) & 0xFFFu, ((w0 >> 24) | (w1 << 8)) & 0xFFFu, (w1 >> 4) & 0xFFFu};
+    unsigned ridx[4] = {0u, 0u, 0u, 0u};
+    if (RES_BITS == 12) {
+      const unsigned v0 = __builtin_amdgcn_alignbit(cur.r1, cur.r0, lane_sh), v1 = cur.r1 >> lane_sh;
+      ridx[0] = v0 & 0xFFFu; ridx[1] = (v0 >> 12) & 0xFFFu; ridx[2] = ((v0 >> 24) | (v1 << 8)) & 0xFFFu; ridx[3] = (v1 >> 4) & 0xFFFu;
+    }
+    if (RES_BITS == 8) { ridx[0] = cur.r0 & 0xFFu; ridx[1] = (cur.r0 >> 8) & 0xFFu; ridx[2] = (cur.r0 >> 16) & 0xFFu; ridx[3] = cur.r0 >> 24; }
+    unsigned out[12];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint4v e = *reinterpret_cast<const uint4v *>(lds + idx[u] * 16);
+      uint4v f = {0u, 0u, 0u, 0u};
+      if (RES_BITS) f = *reinterpret_cast<const uint4v *>(lds + lds_res + ridx[u] * 16);
+      out[3 * u] = restore_pair(e.x, f.x, RES_BITS != 0, sc, bi);
+      out[3 * u + 1] = restore_pair(e.y, f.y, RES_BITS != 0, sc, bi);
+      out[3 * u + 2] = restore_pair(e.z, f.z, RES_BITS != 0, sc, bi);
+    }
+#pragma unroll
+    for (int h = 0; h < 3; ++h) {
+      uint4v pk; pk.x = out[4 * h]; pk.y = out[4 * h + 1]; pk.z = out[4 * h + 2]; pk.w = out[4 * h + 3];
+      *reinterpret_cast<uint4v *>(strip + lane * 48 + h * 16) = pk;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int c_first = p.n_out + q * 1536, n_cols = min(1536, p.in_features - c_first);
+    __half *wrow = W + (long long)o * ldw + c_first;
+#pragma unroll
+    for (int h = 0; h < 3; ++h) {
+      const int c = (h * 64 + lane) * 8;
+      if (c + 8 <= n_cols) {
+        *reinterpret_cast<uint4v *>(wrow + c) = *reinterpret_cast<const uint4v *>(strip + c * 2);
+      } else {
+        for (int j = c; j < n_cols; ++j) wrow[j] = *reinterpret_cast<const __half *>(strip + j * 2);
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    cur = nxt;
+  }
+}
+
 // Orientation 1 (vectors down the output dimension; Sec. 3.1, Algorithm 1), v = 6, 12-bit indices, optional residual:
 // a wave takes 512 consecutive columns of one index stream at a time, eight per lane (three aligned index dwords), and
 // restores the six rows the stream serves: a lane's eight centroids give, row by row, eight consecutive halves -- one
@@ -410,6 +508,24 @@ int launch_dequant_fast(const Params &p, __half *W, long long ldw, hipStream_t s
   plan.out_chunks = p.n_out ? (p.Q + 63) / 64 : 0;
   plan.total_chunks = (long long)(plan.main_chunks + plan.out_chunks) * p.out_features;
   plan.wide = (aligned16 && (p.n_out & 7) == 0) ? 1 : 0;
+  static const bool strip_only = [] { const char *e = getenv("VQ_DEQUANT_KERNEL"); return e && e[0] == 's'; }();   // 's': never the wide kernel
+  if (plan.wide && p.n_groups == 1 && !strip_only && (long long)p.out_features * max(p.stride, p.stride_res) < (1LL << 31)) {
+    // aligned rows: the main columns by the wide kernel, the few outlier columns by the generic kernel
+    const unsigned lds_res = 4096u * 16u, lds_strip = lds_res + (p.k_res ? (1u << p.bits_res) * 16u : 0u);
+    const int waves = lds_strip + 16u * 3072u <= 160u * 1024u ? 16 : 8;
+    const unsigned lds_bytes = lds_strip + (unsigned)waves * 3072u;
+    const long long units = (long long)p.out_features * ((p.P + 255) / 256);
+    const long long want = (units + waves - 1) / waves, slots = (long long)cu_count() * (2u * lds_bytes <= 160u * 1024u ? 2 : 1);
+    const void *kernel = !p.k_res ? reinterpret_cast<const void *>(dequant_v6_wide_kernel<0>)
+                         : p.bits_res == 12 ? reinterpret_cast<const void *>(dequant_v6_wide_kernel<12>)
+                                            : reinterpret_cast<const void *>(dequant_v6_wide_kernel<8>);
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return VQ_ERR_HIP;
+    Params pc = p;
+    unsigned lr = lds_res, lst = lds_strip;
+    void *args[] = {&pc, &lr, &lst, &W, &ldw};
+    if (hipLaunchKernel(kernel, dim3((unsigned)max(1LL, min(want, slots))), dim3(waves * 64), args, lds_bytes, s) != hipSuccess) return VQ_ERR_HIP;
+    return p.n_out ? launch_dequant_outliers(p, W, ldw, s) : VQ_OK;
+  }
   const int rb = p.k_res ? p.bits_res : 0;
   if (rb == 0) return launch_v6<0>(p, plan, offb, W, ldw, s);
   if (rb == 12) return launch_v6<12>(p, plan, offb, W, ldw, s);
