@@ -53,6 +53,7 @@ def lib():
         L.vq_oracle_dequant.argtypes = [ctypes.POINTER(_Layer), ctypes.c_void_p, ctypes.c_int64, ctypes.c_int]
         L.vq_oracle_assign.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                                        ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int]
+        L.vq_oracle_assign_down.argtypes = L.vq_oracle_assign.argtypes
         L.vq_oracle_matmul.argtypes = [ctypes.POINTER(_Layer), ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32,
                                        ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int]
         _lib = L
@@ -147,18 +148,23 @@ def matmul(layer, x: np.ndarray, rows=None, n_threads: int | None = None) -> np.
 
 
 def assign(W: np.ndarray, codebook: np.ndarray, base: np.ndarray | None = None, cols: int | None = None,
-           n_threads: int | None = None) -> np.ndarray:
-    """int32 [rows][ceil(cols / v)]: index of the nearest centroid (fp16 [k][v]) of every length-v vector along the rows
-    of fp16 W [rows][>= cols]; with `base` (same shape), of W - base."""
+           n_threads: int | None = None, orientation: int = 0) -> np.ndarray:
+    """Index of the nearest centroid (fp16 [k][v]) of every length-v vector of fp16 W [rows][>= cols]; with `base` (same
+    shape), of W - base.  orientation 0: vectors along the rows, int32 [rows][ceil(cols / v)]; orientation 1: vectors
+    down the columns, int32 [ceil(rows / v)][cols]."""
     W = _c(W, np.float16)
     codebook = _c(codebook, np.float16)
     base = _c(base, np.float16)
     assert W.ndim == 2 and codebook.ndim == 2 and (base is None or base.shape == W.shape)
     cols = W.shape[1] if cols is None else cols
     k, v = codebook.shape
-    out = np.empty((W.shape[0], -(-cols // v)), dtype=np.int32)
-    rc = lib().vq_oracle_assign(_ptr(W), _ptr(base), W.shape[1], W.shape[0], cols, _ptr(codebook), v, k, _ptr(out),
-                                n_threads or default_threads())
+    if orientation:
+        out = np.empty((-(-W.shape[0] // v), cols), dtype=np.int32)
+        fn = lib().vq_oracle_assign_down
+    else:
+        out = np.empty((W.shape[0], -(-cols // v)), dtype=np.int32)
+        fn = lib().vq_oracle_assign
+    rc = fn(_ptr(W), _ptr(base), W.shape[1], W.shape[0], cols, _ptr(codebook), v, k, _ptr(out), n_threads or default_threads())
     if rc:
         raise OracleError("assign failed: %d" % rc)
     return out

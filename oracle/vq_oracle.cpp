@@ -234,3 +234,37 @@ extern "C" int vq_oracle_assign(const uint16_t *W, const uint16_t *B, int64_t ld
     return (int)VQO_OK;
   });
 }
+
+// Eq. 2 with the paper's own vectors: v consecutive rows of one column (Sec. 3.1; Algorithm 1).
+extern "C" int vq_oracle_assign_down(const uint16_t *W, const uint16_t *B, int64_t ld, int32_t rows, int32_t cols,
+                                     const uint16_t *codebook, int32_t v, int32_t k, int32_t *out, int n_threads) {
+  if (!W || !codebook || !out || rows < 1 || cols < 1 || ld < cols || v < 1 || k < 1) return VQO_ERR_ARG;
+  const int64_t S = ((int64_t)rows + v - 1) / v;
+  std::vector<float> C((size_t)k * v);
+  for (int64_t e = 0; e < (int64_t)k * v; ++e) C[e] = vq_oracle_half_to_float(codebook[e]);
+  return parallel_rows(S, n_threads, [&](int64_t lo, int64_t hi) {
+    std::vector<float> t(v);
+    for (int64_t p = lo; p < hi; ++p) {
+      const int len = (int)std::min<int64_t>(v, rows - p * v);
+      for (int64_t n = 0; n < cols; ++n) {
+        for (int j = 0; j < len; ++j) {
+          volatile float tj = vq_oracle_half_to_float(W[(p * v + j) * ld + n]);
+          if (B) tj = tj - vq_oracle_half_to_float(B[(p * v + j) * ld + n]);
+          t[j] = tj;
+        }
+        int32_t best = 0;
+        float best_d = 0.0f;
+        for (int32_t i = 0; i < k; ++i) {
+          volatile float d = 0.0f;
+          for (int j = 0; j < len; ++j) {
+            volatile float diff = t[j] - C[(size_t)i * v + j];
+            d = std::fmaf(diff, diff, d);
+          }
+          if (i == 0 || d < best_d) { best = i; best_d = d; }
+        }
+        out[p * cols + n] = best;
+      }
+    }
+    return (int)VQO_OK;
+  });
+}

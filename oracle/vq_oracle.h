@@ -89,6 +89,12 @@ int vq_oracle_matmul(const vq_oracle_layer *L, const uint16_t *x, int64_t ldx, i
 int vq_oracle_assign(const uint16_t *W, const uint16_t *B, int64_t ld, int32_t rows, int32_t cols,
                      const uint16_t *codebook, int32_t v, int32_t k, int32_t *out, int n_threads);
 
+/* The same for vectors that run down the columns of W (orientation 1 of vq_oracle_layer; Sec. 3.1, Algorithm 1's
+ * Q(W[m:m+V, n])): vector (p, n) = W[p v + j][n], j < v, the last block of rows cut at `rows` and compared over its own
+ * elements; out[p * cols + n], p < ceil(rows / v).  Same arithmetic, j ascending.                                  */
+int vq_oracle_assign_down(const uint16_t *W, const uint16_t *B, int64_t ld, int32_t rows, int32_t cols,
+                          const uint16_t *codebook, int32_t v, int32_t k, int32_t *out, int n_threads);
+
 #ifdef __cplusplus
 }
 #endif

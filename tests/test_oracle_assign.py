@@ -115,3 +115,26 @@ def test_encoding_a_decoded_layer_returns_its_indices():
     idx = oracle.assign(W, L.codebook)
     assert np.array_equal(idx, L.raw_idx)
     assert np.array_equal(s.pack_indices(idx, L.bits, L.idx.shape[1]), L.idx)
+
+
+@pytest.mark.parametrize("rows,cols,v", [(24, 11, 6), (23, 9, 6), (5, 4, 8), (7, 13, 1)])
+def test_vectors_down_the_columns_are_the_transposed_problem(rows, cols, v):
+    """Sec. 3.1 / Algorithm 1: the paper's vectors are v consecutive rows of a column -- the row-wise vectors of the
+    transposed matrix, cut-off last block included."""
+    rng = np.random.default_rng(rows * 100 + cols)
+    W = rng.normal(0, 0.02, (rows, cols + 2)).astype(np.float16)
+    B = rng.normal(0, 0.01, (rows, cols + 2)).astype(np.float16)
+    C = rng.normal(0, 0.02, (50, v)).astype(np.float16)
+    down = oracle.assign(W, C, cols=cols, orientation=1)
+    assert down.shape == (-(-rows // v), cols)
+    assert np.array_equal(down, oracle.assign(np.ascontiguousarray(W[:, :cols].T), C).T)
+    down_b = oracle.assign(W, C, base=B, cols=cols, orientation=1)
+    assert np.array_equal(down_b, oracle.assign(np.ascontiguousarray(W[:, :cols].T), C, base=np.ascontiguousarray(B[:, :cols].T)).T)
+    assert not np.array_equal(down, down_b)
+
+
+def test_encoding_a_decoded_layer_of_the_papers_orientation_returns_its_indices():
+    L = s.make_layer(212, "rt_down", 20, 33, 6, 256, with_scale=False, with_bias=False, orientation=1)
+    assert len(np.unique(L.codebook, axis=0)) == 256
+    idx = oracle.assign(oracle.dequant(L), L.codebook, orientation=1)
+    assert np.array_equal(idx, L.raw_idx)
