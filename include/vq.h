@@ -151,6 +151,13 @@ int vq_gemv_multi(const vq_layer_desc *const *descs, int32_t n_layers, const voi
 int vq_assign(const void *W, const void *B, int64_t ld, int32_t rows, int32_t cols, const void *codebook, int32_t v, int32_t k,
               void *idx, int64_t idx_row_stride, void *hip_stream);
 
+/* vq_assign for the paper's own vectors (orientation 1 of the descriptor; Sec. 3.1, Algorithm 1's Q(W[m:m+V, n])):
+ * vector (p, n) = W[p v + j][n], j < v, the last block of rows cut at `rows` and compared over its own elements.  idx:
+ * [ceil(rows / v)][idx_row_stride] bytes, stream p holds one index per column, stride >= ceil(cols * b / 8) rounded up
+ * to 4.  Everything else -- B, the arithmetic of the distance, ties, alignment, errors -- as for vq_assign.        */
+int vq_assign_down(const void *W, const void *B, int64_t ld, int32_t rows, int32_t cols, const void *codebook, int32_t v,
+                   int32_t k, void *idx, int64_t idx_row_stride, void *hip_stream);
+
 /* Prompt-phase product for many tokens: Y[t][o] = sum_c W[o][c] * X[t][c] on the FP16 matrix cores,
  * binary32 accumulation, fp16 result (the paper's prompt phase, its section on inference throughput:
  * restore the weights, then multiply).  X: fp16 [tokens][ldx], 16-byte aligned, ldx % 8 == 0; Y: fp16

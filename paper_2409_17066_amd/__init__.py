@@ -61,6 +61,7 @@ def load():
                                 ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_int64), ctypes.c_void_p]
     L.vq_assign.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
                             ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+    L.vq_assign_down.argtypes = L.vq_assign.argtypes
     L.vq_gemm.argtypes = [P, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
                           ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     L.vq_gemm_workspace_bytes.argtypes = [P, ctypes.c_int32]
@@ -70,14 +71,14 @@ def load():
     L.vq_status_string.argtypes = [ctypes.c_int]
     L.vq_status_string.restype = ctypes.c_char_p
     L.vq_version.restype = ctypes.c_int
-    for f in (L.vq_validate, L.vq_dequant, L.vq_gemv, L.vq_gemv_with_workspace, L.vq_gemv_multi, L.vq_gemm, L.vq_assign):
+    for f in (L.vq_validate, L.vq_dequant, L.vq_gemv, L.vq_gemv_with_workspace, L.vq_gemv_multi, L.vq_gemm, L.vq_assign, L.vq_assign_down):
         f.restype = ctypes.c_int
     _lib = L
     return L
 
 
 EXPORTED = ["vq_validate", "vq_dequant", "vq_gemv", "vq_gemv_workspace_bytes", "vq_gemv_with_workspace", "vq_gemv_multi", "vq_gemm", "vq_gemm_workspace_bytes", "vq_gemm_fast_workspace_bytes",
-            "vq_assign", "vq_status_string", "vq_version"]
+            "vq_assign", "vq_assign_down", "vq_status_string", "vq_version"]
 
 
 # ---- the C entry points, same names, raw pointers (ints) and sizes ---------------------------------------
@@ -119,6 +120,10 @@ def vq_gemm(desc, X_ptr, ldx, tokens, Y_ptr, ldy, workspace_ptr=None, workspace_
 
 def vq_assign(W_ptr, B_ptr, ld, rows, cols, codebook_ptr, v, k, idx_ptr, idx_row_stride, stream=None):
     return load().vq_assign(W_ptr, B_ptr, ld, rows, cols, codebook_ptr, v, k, idx_ptr, idx_row_stride, stream)
+
+
+def vq_assign_down(W_ptr, B_ptr, ld, rows, cols, codebook_ptr, v, k, idx_ptr, idx_row_stride, stream=None):
+    return load().vq_assign_down(W_ptr, B_ptr, ld, rows, cols, codebook_ptr, v, k, idx_ptr, idx_row_stride, stream)
 
 
 def vq_gemm_workspace_bytes(desc, tokens):
@@ -213,9 +218,10 @@ def gemv_multi(dls, x, outs=None):
     return ys
 
 
-def assign(W, codebook, base=None, cols=None):
-    """W (and base): fp16 [rows][>= cols] device tensors, codebook: fp16 [k][v] device tensor -> uint8 [rows][stride]
-    packed indices of the nearest centroids (stride: the row's bits rounded up to 16 bytes, padding zero)."""
+def assign(W, codebook, base=None, cols=None, orientation=0):
+    """W (and base): fp16 [rows][>= cols] device tensors, codebook: fp16 [k][v] device tensor -> uint8 [streams][stride]
+    packed indices of the nearest centroids (stride: a stream's bits rounded up to 16 bytes, padding zero).  orientation 0:
+    vectors along the rows, a stream per row; 1: vectors down the columns, a stream per block of v rows."""
     import torch
     assert W.is_cuda and W.dtype == torch.float16 and W.dim() == 2 and W.stride(1) == 1
     assert base is None or (base.dtype == torch.float16 and base.shape == W.shape and base.stride() == W.stride())
@@ -223,12 +229,15 @@ def assign(W, codebook, base=None, cols=None):
     k, v = codebook.shape
     cols = W.shape[1] if cols is None else cols
     bits = max(1, (k - 1).bit_length())
-    stride = (-(-cols // v) * bits + 127) // 128 * 16
-    idx = torch.zeros((W.shape[0], stride), dtype=torch.uint8, device="cuda")
-    rc = vq_assign(W.data_ptr(), base.data_ptr() if base is not None else None, W.stride(0), W.shape[0], cols, codebook.data_ptr(),
-                   v, k, idx.data_ptr(), stride, _stream())
+    per_stream = cols if orientation else -(-cols // v)
+    streams = -(-W.shape[0] // v) if orientation else W.shape[0]
+    stride = (per_stream * bits + 127) // 128 * 16
+    idx = torch.zeros((streams, stride), dtype=torch.uint8, device="cuda")
+    fn = vq_assign_down if orientation else vq_assign
+    rc = fn(W.data_ptr(), base.data_ptr() if base is not None else None, W.stride(0), W.shape[0], cols, codebook.data_ptr(),
+            v, k, idx.data_ptr(), stride, _stream())
     if rc != VQ_OK:
-        raise VQError(rc, "vq_assign")
+        raise VQError(rc, "vq_assign_down" if orientation else "vq_assign")
     return idx
 
 

@@ -183,6 +183,20 @@ extern "C" int vq_assign(const void *W, const void *B, int64_t ld, int32_t rows,
                            static_cast<hipStream_t>(hip_stream));
 }
 
+extern "C" int vq_assign_down(const void *W, const void *B, int64_t ld, int32_t rows, int32_t cols, const void *codebook, int32_t v,
+                              int32_t k, void *idx, int64_t idx_row_stride, void *hip_stream) {
+  if (!W || !codebook || !idx) return VQ_ERR_NULL;
+  const int lim = 1 << 24;
+  if (rows < 1 || rows > lim || cols < 1 || cols > lim || ld < cols || v < 1 || v > 16 || k < 2 || k > 65536) return VQ_ERR_SHAPE;
+  const long long need = (((long long)cols * vq::index_bits(k) + 31) / 32) * 4;             // whole dwords
+  if (idx_row_stride < need) return VQ_ERR_SHAPE;
+  if (!aligned(W, 2) || (B && !aligned(B, 2)) || !aligned(codebook, 2)) return VQ_ERR_ALIGNMENT;
+  if (!aligned(idx, 16) || idx_row_stride % 16 != 0) return VQ_ERR_ALIGNMENT;
+  return vq::launch_assign_down(static_cast<const __half *>(W), static_cast<const __half *>(B), ld, rows, cols,
+                                static_cast<const __half *>(codebook), v, k, static_cast<unsigned char *>(idx), idx_row_stride,
+                                static_cast<hipStream_t>(hip_stream));
+}
+
 extern "C" const char *vq_status_string(int status) {
   switch (status) {
     case VQ_OK: return "ok";

@@ -26,7 +26,7 @@ constexpr int table_stride(int v) { return v <= 2 ? v : v <= 4 ? 4 : v <= 8 ? 8 
 template <int V, int VB>
 __global__ __launch_bounds__(AT) void assign_kernel(const __half *__restrict__ W, const __half *__restrict__ B, long long ld, int rows,
                                                     int p_full, int p_all, const __half *__restrict__ codebook, int k, int bits,
-                                                    int chunk, int seg_len, unsigned char *__restrict__ idx, long long idx_stride) {
+                                                    int chunk, int seg_len, unsigned char *__restrict__ idx, long long idx_stride, int down_rows) {
   extern __shared__ __attribute__((aligned(16))) float table[];       // [chunk][TS]: rows padded to 16-byte reads
   constexpr int TS = table_stride(V);
   const int segs = (p_all + seg_len - 1) / seg_len;
@@ -34,7 +34,10 @@ __global__ __launch_bounds__(AT) void assign_kernel(const __half *__restrict__ W
   const bool live = item < (long long)rows * segs;
   const int o = live ? (int)(item / segs) : 0;
   const int seg = live ? (int)(item - (long long)o * segs) : 0;
-  const __half *wrow = W + (long long)o * ld, *brow = B ? B + (long long)o * ld : nullptr;
+  // down_rows > 0: the vectors run down the columns of a matrix of down_rows rows (Sec. 3.1, Algorithm 1).  "Row" o is then
+  // the index stream of rows [o V, o V + V), its vector u is column u, element j of it sits in row o V + j; a stream whose
+  // block of rows is cut off at the end of the matrix is left to the second kernel as a whole.
+  const bool whole = down_rows == 0 || (o + 1) * V <= down_rows;
   unsigned *out = reinterpret_cast<unsigned *>(idx + (long long)o * idx_stride) + (long long)seg * (seg_len * bits / 32);
   unsigned long long buf = 0;
   int fill = 0;
@@ -51,12 +54,12 @@ __global__ __launch_bounds__(AT) void assign_kernel(const __half *__restrict__ W
 #pragma unroll
     for (int u = 0; u < VB; ++u) {
       best[u] = __builtin_inff(); arg[u] = 0;
-      const bool on = live && p0 + u < p_full;
+      const bool on = live && whole && p0 + u < p_full;
 #pragma unroll
       for (int j = 0; j < V; ++j) {
-        const long long c = (long long)(p0 + u) * V + j;
-        float x = on ? __half2float(wrow[c]) : 0.0f;
-        if (on && brow) x = __fsub_rn(x, __half2float(brow[c]));
+        const long long c = down_rows ? ((long long)o * V + j) * ld + (p0 + u) : (long long)o * ld + (long long)(p0 + u) * V + j;
+        float x = on ? __half2float(W[c]) : 0.0f;
+        if (on && B) x = __fsub_rn(x, __half2float(B[c]));
         t[u][j] = x;
       }
     }
@@ -84,7 +87,7 @@ __global__ __launch_bounds__(AT) void assign_kernel(const __half *__restrict__ W
 #pragma unroll
     for (int u = 0; u < VB; ++u) {
       if (live && p0 + u < p_all) {
-        const unsigned code = p0 + u < p_full ? (unsigned)arg[u] : 0u;
+        const unsigned code = whole && p0 + u < p_full ? (unsigned)arg[u] : 0u;
         buf |= (unsigned long long)code << fill;
         fill += bits;
         if (fill >= 32) { *out++ = (unsigned)buf; buf >>= 32; fill -= 32; }
@@ -133,9 +136,46 @@ __global__ __launch_bounds__(256) void assign_tail_kernel(const __half *__restri
   if (sh + bits > 32) row[(bit >> 5) + 1] |= arg >> (32 - sh);
 }
 
+// The cut-off last block of rows when the vectors run down the columns: every vector of the last index stream has only
+// `len` elements.  One wave per column, as above; the streams' bits are set with an atomic OR because neighbouring columns
+// share dwords (integer, so the result does not depend on the order).
+__global__ __launch_bounds__(256) void assign_tail_down_kernel(const __half *__restrict__ W, const __half *__restrict__ B, long long ld, int cols,
+                                                               int row0, int v, int len, const __half *__restrict__ codebook, int k, int bits,
+                                                               unsigned *__restrict__ stream) {
+  const int n = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (n >= cols) return;
+  float t[16];
+  for (int j = 0; j < len; ++j) {
+    const long long c = (long long)(row0 + j) * ld + n;
+    float x = __half2float(W[c]);
+    if (B) x = __fsub_rn(x, __half2float(B[c]));
+    t[j] = x;
+  }
+  float best = __builtin_inff();
+  unsigned arg = 0xFFFFFFFFu;
+  for (int i = lane; i < k; i += 64) {
+    float d = 0.0f;
+    for (int j = 0; j < len; ++j) {
+      const float diff = __fsub_rn(t[j], __half2float(codebook[(long long)i * v + j]));
+      d = __fmaf_rn(diff, diff, d);
+    }
+    if (d < best || arg == 0xFFFFFFFFu) { best = d; arg = (unsigned)i; }
+  }
+  for (int s = 32; s > 0; s >>= 1) {
+    const float od = __shfl_xor(best, s, 64);
+    const unsigned oa = __shfl_xor(arg, s, 64);
+    if (oa != 0xFFFFFFFFu && (arg == 0xFFFFFFFFu || od < best || (od == best && oa < arg))) { best = od; arg = oa; }
+  }
+  if (lane != 0) return;
+  const long long bit = (long long)n * bits;
+  const int sh = (int)(bit & 31);
+  atomicOr(stream + (bit >> 5), arg << sh);
+  if (sh + bits > 32) atomicOr(stream + (bit >> 5) + 1, arg >> (32 - sh));
+}
+
 template <int V>
 int launch_v(const __half *W, const __half *B, long long ld, int rows, int p_full, int p_all, const __half *codebook, int k, int bits,
-             unsigned char *idx, long long idx_stride, hipStream_t s) {
+             unsigned char *idx, long long idx_stride, hipStream_t s, int down_rows = 0) {
   constexpr int VB = V <= 8 ? 8 : 4;       // vectors a lane holds at once: each centroid read from LDS serves VB x 64 distances
   static bool configured = false;
   auto kernel = assign_kernel<V, VB>;
@@ -151,7 +191,7 @@ int launch_v(const __half *W, const __half *B, long long ld, int rows, int p_ful
   const long long blocks = (items + AT - 1) / AT;
   if (blocks > 0x7fffffffLL) return VQ_ERR_UNSUPPORTED;
   hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(AT), (size_t)chunk * table_stride(V) * sizeof(float), s, W, B, ld, rows, p_full, p_all,
-                     codebook, k, bits, chunk, seg_len, idx, idx_stride);
+                     codebook, k, bits, chunk, seg_len, idx, idx_stride, down_rows);
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
 
@@ -171,6 +211,24 @@ int launch_assign(const __half *W, const __half *B, long long ld, int rows, int 
   if (rc != VQ_OK || p_all == p_full) return rc;
   hipLaunchKernelGGL(assign_tail_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, W, B, ld, rows, p_full, v, cols - p_full * v,
                      codebook, k, bits, idx, idx_stride);
+  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+// Vectors down the columns of W [rows][ld]: index streams [ceil(rows / v)][idx_stride], one index per column.
+int launch_assign_down(const __half *W, const __half *B, long long ld, int rows, int cols, const __half *codebook, int v, int k,
+                       unsigned char *idx, long long idx_stride, hipStream_t s) {
+  const int bits = index_bits(k);
+  const int streams = (rows + v - 1) / v;
+  int rc = VQ_ERR_UNSUPPORTED;
+  switch (v) {
+#define VQ_V(N) case N: rc = launch_v<N>(W, B, ld, streams, cols, cols, codebook, k, bits, idx, idx_stride, s, rows); break;
+    VQ_V(1) VQ_V(2) VQ_V(3) VQ_V(4) VQ_V(5) VQ_V(6) VQ_V(7) VQ_V(8) VQ_V(9) VQ_V(10) VQ_V(11) VQ_V(12) VQ_V(13) VQ_V(14) VQ_V(15) VQ_V(16)
+#undef VQ_V
+    default: break;
+  }
+  if (rc != VQ_OK || rows % v == 0) return rc;
+  hipLaunchKernelGGL(assign_tail_down_kernel, dim3((unsigned)((cols + 3) / 4)), dim3(256), 0, s, W, B, ld, cols, (streams - 1) * v, v,
+                     rows - (streams - 1) * v, codebook, k, bits, reinterpret_cast<unsigned *>(idx + (long long)(streams - 1) * idx_stride));
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
 

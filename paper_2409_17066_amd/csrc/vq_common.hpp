@@ -42,6 +42,8 @@ int launch_gemm(const Params &p, const __half *X, long long ldx, int tokens, __h
                 void *workspace, size_t workspace_bytes, hipStream_t s);
 int launch_assign(const __half *W, const __half *B, long long ld, int rows, int cols, const __half *codebook, int v, int k,
                   unsigned char *idx, long long idx_stride, hipStream_t s);
+int launch_assign_down(const __half *W, const __half *B, long long ld, int rows, int cols, const __half *codebook, int v, int k,
+                       unsigned char *idx, long long idx_stride, hipStream_t s);
 size_t gemm_workspace_bytes(const Params &p, int tokens);
 size_t gemm_fast_workspace_bytes(const Params &p, int tokens);
 

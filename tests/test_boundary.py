@@ -150,6 +150,15 @@ def test_assign_rejects_bad_arguments_before_any_launch():
     assert vq.vq_assign(**dict(ok, idx_row_stride=24)) == vq.VQ_ERR_ALIGNMENT
 
 
+def test_assign_down_rejects_bad_arguments_before_any_launch():
+    ok = dict(W_ptr=0x8000, B_ptr=None, ld=30, rows=8, cols=30, codebook_ptr=0x1000, v=6, k=256, idx_ptr=0x2000, idx_row_stride=32)
+    assert vq.vq_assign_down(**dict(ok, W_ptr=None)) == vq.VQ_ERR_NULL
+    for bad in (dict(rows=0), dict(cols=0), dict(ld=29), dict(v=17), dict(k=1)):
+        assert vq.vq_assign_down(**dict(ok, **bad)) == vq.VQ_ERR_SHAPE, bad
+    assert vq.vq_assign_down(**dict(ok, idx_row_stride=16)) == vq.VQ_ERR_SHAPE         # 30 indices of 8 bits a stream
+    assert vq.vq_assign_down(**dict(ok, idx_ptr=0x2004)) == vq.VQ_ERR_ALIGNMENT
+
+
 def test_binding_has_no_cpu_fallback():
     src = open(os.path.join(ROOT, "paper_2409_17066_amd", "__init__.py")).read()
     assert "oracle" not in src.replace("no CPU fallback", "")

@@ -104,3 +104,33 @@ def test_assign_at_the_headline_size_on_sampled_rows(gpu_lib):
     rows = [0, 1, 4095, 7777, 11006, 11007]
     want = oracle.assign(W[rows], L.codebook)
     assert np.array_equal(idx.cpu().numpy()[rows], s.pack_indices(want, 12, idx.shape[1]))
+
+
+@pytest.mark.parametrize("name", list(CASES))
+@pytest.mark.parametrize("with_base", [False, True])
+def test_assign_down_bit_exact(gpu_lib, name, with_base):
+    """The paper's own vectors (v consecutive rows of a column): index streams per block of rows, bit for bit."""
+    import torch
+    W, C, B, cols = _inputs(name, with_base)
+    k, v = C.shape
+    idx = gpu_lib.assign(torch.from_numpy(W).cuda(), torch.from_numpy(C).cuda(),
+                         base=torch.from_numpy(B).cuda() if with_base else None, cols=cols, orientation=1)
+    torch.cuda.synchronize()
+    want = oracle.assign(W, C, base=B, cols=cols, orientation=1)
+    assert idx.shape[0] == want.shape[0] == -(-W.shape[0] // v)
+    assert np.array_equal(idx.cpu().numpy(), s.pack_indices(want, oracle.index_bits(k), idx.shape[1])), name
+
+
+def test_encode_then_decode_in_the_papers_orientation(gpu_lib):
+    import torch
+    L = s.make_layer(7300, "enc_down", 70, 600, 6, 4096, with_scale=False, with_bias=False, orientation=1)
+    W = s.to_fp16(s.normal(7301, 70 * 600, 0.02)).reshape(70, 600)
+    idx = gpu_lib.assign(torch.from_numpy(W).cuda(), torch.from_numpy(L.codebook).cuda(), orientation=1)
+    L.idx = idx.cpu().numpy()
+    What = gpu_lib.dequant(gpu_lib.DeviceLayer(L))
+    torch.cuda.synchronize()
+    assert np.array_equal(What.cpu().numpy().view(np.uint16), oracle.dequant(L).view(np.uint16))
+    # every restored vector is the nearest centroid of its block of rows: re-encoding returns the same streams
+    again = gpu_lib.assign(What, torch.from_numpy(L.codebook).cuda(), orientation=1)
+    torch.cuda.synchronize()
+    assert torch.equal(again, idx)
