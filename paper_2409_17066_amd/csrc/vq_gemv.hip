@@ -111,7 +111,10 @@ int launch_gemv_fast(const Params &p, const __half *x, long long ldx, int batch,
 
 int launch_gemv_mfma(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
 bool gemv_down_applicable(const Params &p, const __half *x, long long ldx);
-int launch_gemv_down(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
+int launch_gemv_down(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s,
+                     float *part = nullptr, float *part_xs = nullptr, int part_batch = 0);
+int launch_groups_finish(const float *part, const float *part_xs, int n_groups, int batch, const Params &p, __half *y, long long ldy,
+                         hipStream_t s);
 
 // VQ_GEMV_KERNEL=g forces the generic kernel, =m the matrix-core kernel, =d the dot-product kernels
 // (testing and measurement; unset: chosen by batch).  Read at every call so that one process can test them all.
@@ -127,7 +130,7 @@ int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __ha
   // per compute unit), so they keep these cases.  Layers with codebook groups always go to the matrix-core kernel:
   // it is the one that swaps the tables in LDS group by group.
   if (p.orientation == 1) {
-    if (!force_generic() && gemv_down_applicable(p, x, ldx)) {
+    if (!force_generic() && p.n_groups == 1 && gemv_down_applicable(p, x, ldx)) {
       // batch rows go in groups of 4, 2 or 1 (fewer when the rows do not fit LDS beside the tables)
       int done = 0, g_max = 4, rc = VQ_OK;
       while (done < batch) {
@@ -181,7 +184,11 @@ int launch_gemv_mfma_groups(const Params &p, const __half *x, long long ldx, int
 // A workspace serves layers with codebook groups on the matrix-core kernel: one group per workgroup, then a sum over
 // the groups.  VQ_GEMV_GROUPS=loop keeps every workgroup walking all groups (measurement and tests).
 size_t gemv_workspace_bytes(const Params &p, const __half *x, long long ldx, int batch) {
-  if (force_generic() || forced_kernel() == 'd' || !gemv_fast_applicable(p, x, ldx)) return 0;
+  if (force_generic()) return 0;
+  if (p.orientation == 1)           // vectors down the output dimension: the same workspace layout, filled by that orientation's kernel
+    return p.n_groups > 1 && p.n_groups <= 256 && gemv_down_applicable(p, x, ldx)
+               ? ((size_t)p.n_groups * ((size_t)batch * (size_t)p.out_features + 16) * sizeof(float) + 255) / 256 * 256 : 0;
+  if (forced_kernel() == 'd' || !gemv_fast_applicable(p, x, ldx)) return 0;
   return gemv_mfma_groups_workspace_bytes(p, batch);
 }
 
@@ -189,7 +196,20 @@ int launch_gemv_ws(const Params &p, const __half *x, long long ldx, int batch, _
                    size_t workspace_bytes, hipStream_t s) {
   const char *env = getenv("VQ_GEMV_GROUPS");
   const size_t need = gemv_workspace_bytes(p, x, ldx, batch);
-  if (need && workspace && workspace_bytes >= need && !(env && env[0] == 'l')) {
+  if (need && workspace && workspace_bytes >= need && p.orientation == 1) {
+    float *part = static_cast<float *>(workspace), *part_xs = part + (size_t)p.n_groups * (size_t)batch * (size_t)p.out_features;
+    int done = 0, g_max = 4, rc = VQ_OK;
+    while (done < batch) {                                // batch rows in launches of 4, 2 or 1, as without groups
+      int g = batch - done >= 4 ? 4 : batch - done >= 2 ? 2 : 1;
+      if (g > g_max) g = g_max;
+      rc = launch_gemv_down(p, x + done * ldx, ldx, g, nullptr, 0, s, part + (size_t)done * p.out_features, part_xs + done, batch);
+      if (rc == VQ_ERR_UNSUPPORTED && g > 1) { g_max = g / 2; continue; }
+      if (rc != VQ_OK) break;
+      done += g;
+    }
+    if (rc == VQ_OK) return launch_groups_finish(part, part_xs, p.n_groups, batch, p, y, ldy, s);
+    if (rc != VQ_ERR_UNSUPPORTED || done != 0) return rc;
+  } else if (need && workspace && workspace_bytes >= need && !(env && env[0] == 'l')) {
     const int rc = launch_gemv_mfma_groups(p, x, ldx, batch, y, ldy, workspace, s);
     if (rc != VQ_ERR_UNSUPPORTED) return rc;
   }

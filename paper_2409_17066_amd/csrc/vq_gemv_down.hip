@@ -19,6 +19,11 @@
 // Outlier columns (Sec. 3.2.3; their streams belong to blocks of v_out rows, any v_out and k_out) are few: before the
 // main loop each wave works out, for a share of the workgroup's output rows, the row's sum over the outlier columns --
 // lanes over the columns, index and centroid element straight from memory -- and leaves it in LDS for the row's end.
+//
+// Codebook groups (Sec. 3.1: ranges of columns with tables of their own) run when the caller lends a workspace: workgroups
+// [g w, (g + 1) w) see group g as a layer of its own -- its tables, its part of every index stream (a group of 8 n columns
+// starts on a dword), its columns of x, the outlier columns with group 0 -- and leave binary32 sums without scale and bias
+// in the workspace [group][token][row]; the kernel that adds the groups up is the row-wise layers' (vq_gemv_mfma.hip).
 #include "vq_common.hpp"
 #include "vq_v6.hpp"
 
@@ -39,6 +44,9 @@ struct DownPlan {
   unsigned lds_x, lds_xsum, lds_part;
   unsigned lds_osum;             // sums over the outlier columns: [workgroup's rows][batch], then [batch] activation sums
   unsigned x_row_bytes;          // one staged activation row: passes * 1024 bytes, zero past the last column
+  // codebook groups (0 workgroups per group: none): where the sums go instead of y
+  int wgs_per_group, part_batch; // tokens of the whole call: the workspace is [group][part_batch][out_features]
+  float *part, *part_xs;         // already moved to this launch's first token
 };
 
 // The halves of a dword as binary32 (the compiler folds these conversions into v_fma_mix_f32's operand selects).  The
@@ -72,6 +80,22 @@ __global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPla
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  int wg = (int)blockIdx.x, n_wg = (int)gridDim.x, grp = 0, col0 = p.n_out;    // col0: column of x that meets stream position 0
+  unsigned idx_left = (unsigned)p.S * (unsigned)p.stride, res_left = RES_BITS ? (unsigned)p.S * (unsigned)p.stride_res : 0u;
+  if (plan.wgs_per_group > 0) {
+    grp = wg / plan.wgs_per_group; wg -= grp * plan.wgs_per_group; n_wg = plan.wgs_per_group;
+    const int v_lo = grp * p.Pg;
+    p.P = min(p.Pg, p.P - v_lo);
+    col0 += v_lo;
+    p.cb += (long long)grp * p.k * 6;
+    if (RES_BITS) p.cb_res += (long long)grp * p.k_res * 6;
+    const unsigned skip = (unsigned)(v_lo >> 3) * 12u, skip_res = (unsigned)(v_lo >> 3) * (unsigned)RES_BITS;
+    p.idx += skip; idx_left -= skip;
+    if (RES_BITS) { p.idx_res += skip_res; res_left -= skip_res; }
+    if (grp) p.Q = 0;                                    // the outlier columns go with the first group
+    plan.passes = (p.P + 511) >> 9;
+    plan.ppw = (plan.passes + (1 << plan.ws_log2) - 1) >> plan.ws_log2;
+  }
   const int WS = 1 << plan.ws_log2, SPW = DW >> plan.ws_log2;      // waves per stream, streams per group
   const int ws_i = wv & (WS - 1), slot = wv >> plan.ws_log2;
 
@@ -88,7 +112,7 @@ __global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPla
   auto item_row = [&](int r) {                           // output row of item r, or -1
     const int grp_slot = r / 6, j = r - grp_slot * 6;
     const int it_r = grp_slot / SPW, slot_r = grp_slot - it_r * SPW;
-    const int o = ((it_r * (int)gridDim.x + (int)blockIdx.x) * SPW + slot_r) * 6 + j;
+    const int o = ((it_r * n_wg + wg) * SPW + slot_r) * 6 + j;
     return r < items && o < p.out_features ? o : -1;
   };
   auto out_issue = [&](int r0, int c, OutPre &pre) {
@@ -140,8 +164,8 @@ __global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPla
     float *xsum = reinterpret_cast<float *>(lds + plan.lds_xsum);             // [B][DW]
 #pragma unroll
     for (int t = 0; t < B; ++t) {
-      const __half *xt = x + (long long)t * ldx + p.n_out;                   // main column n is x[n_out + n]
-      const bool wide = (p.n_out & 7) == 0;                                  // then the 16-byte pieces are aligned (x is, on the host's word)
+      const __half *xt = x + (long long)t * ldx + col0;                      // stream position n is column col0 + n
+      const bool wide = (col0 & 7) == 0;                                     // then the 16-byte pieces are aligned (x is, on the host's word)
       float sum = 0.0f;
       for (int c = (int)threadIdx.x * 8; c < plan.passes * 512; c += DW * 64 * 8) {
         uint4v val = {0u, 0u, 0u, 0u};
@@ -199,15 +223,15 @@ __global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPla
   __syncthreads();
 
   const unsigned st_main = (unsigned)p.stride, st_res = (unsigned)p.stride_res;
-  const __amdgpu_buffer_rsrc_t r_main = make_rsrc(p.idx, (unsigned)p.S * st_main);
-  const __amdgpu_buffer_rsrc_t r_res = make_rsrc(RES_BITS ? p.idx_res : p.idx, RES_BITS ? (unsigned)p.S * st_res : 0u);
+  const __amdgpu_buffer_rsrc_t r_main = make_rsrc(p.idx, idx_left);
+  const __amdgpu_buffer_rsrc_t r_res = make_rsrc(RES_BITS ? p.idx_res : p.idx, res_left);
   const unsigned a_x = lds_address(lds) + plan.lds_x + (unsigned)lane * 16u;
 
   // The wave's work is one sequence of units, unit k = (group k / ppw of streams, pass k % ppw of this wave in the stream).
   // A unit past the end of the streams or of a stream's passes is walked like any other -- the barriers below need every
   // wave -- on the first stream's first pass, and its products are dropped.
   const int K = plan.iters * plan.ppw;
-  auto unit_stream = [&](int it) { return (it * (int)gridDim.x + (int)blockIdx.x) * SPW + slot; };
+  auto unit_stream = [&](int it) { return (it * n_wg + wg) * SPW + slot; };
   int l_it = 0, l_i = 0;                               // the loader's position in the same sequence, DEPTH units ahead
   auto load_unit = [&](Window<3> &wm, Window<NR> &wr) {
     const int stream = unit_stream(l_it), q = ws_i + l_i * WS;
@@ -300,8 +324,13 @@ __global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPla
                 mine += osum[((it * SPW + slot) * 6 + (lane - t * 6)) * B + t];
                 xs += osum[plan.iters * SPW * 6 * B + t];
               }
-              const float sc = p.scale ? __half2float(p.scale[o]) : 1.0f, bi = p.bias ? __half2float(p.bias[o]) : 0.0f;
-              y[(long long)t * ldy + o] = __float2half_rn(__fmaf_rn(sc, mine, bi * xs));
+              if (plan.part) {                          // one group of several: the sum as it is, for the kernel that adds the groups up
+                plan.part[((long long)grp * plan.part_batch + t) * p.out_features + o] = mine;
+                if (wg == 0 && slot == 0 && it == 0 && lane - t * 6 == 0) plan.part_xs[grp * 16 + t] = xs;
+              } else {
+                const float sc = p.scale ? __half2float(p.scale[o]) : 1.0f, bi = p.bias ? __half2float(p.bias[o]) : 0.0f;
+                y[(long long)t * ldy + o] = __float2half_rn(__fmaf_rn(sc, mine, bi * xs));
+              }
             }
           }
           if (WS > 1) lds_barrier();                   // the partial sums are free again
@@ -342,7 +371,8 @@ int launch_one(const Params &p, const DownPlan &plan, unsigned lds_bytes, unsign
 
 // Whether the kernel above takes this layer and these buffers.
 bool gemv_down_applicable(const Params &p, const __half *x, long long ldx) {
-  if (p.orientation != 1 || p.v != 6 || p.bits != 12 || p.n_groups != 1) return false;
+  if (p.orientation != 1 || p.v != 6 || p.bits != 12) return false;
+  if (p.n_groups > 1 && (p.Pg & 7)) return false;        // a group starts on a dword of the index streams (and needs a workspace)
   if (p.k_res && p.bits_res != 12 && p.bits_res != 8) return false;
   if ((reinterpret_cast<uintptr_t>(x) & 15) || (ldx & 7)) return false;
   const long long max_stride = p.stride > p.stride_res ? p.stride : p.stride_res;
@@ -350,11 +380,16 @@ bool gemv_down_applicable(const Params &p, const __half *x, long long ldx) {
 }
 
 // Launch for one group of 1, 2 or 4 batch rows.  VQ_ERR_UNSUPPORTED when the rows do not fit LDS beside the tables.
-int launch_gemv_down(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
+// part != nullptr: a layer with codebook groups; the sums go to the workspace part[group][part_batch][out_features] (and
+// part_xs[group * 16 + token]), both already moved to this launch's first token.
+int launch_gemv_down(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s,
+                     float *part, float *part_xs, int part_batch) {
   DownPlan plan{};
+  if ((p.n_groups > 1) != (part != nullptr)) return VQ_ERR_UNSUPPORTED;
+  plan.part = part; plan.part_xs = part_xs; plan.part_batch = part_batch;
   const int rb = p.k_res ? p.bits_res : 0;
   unsigned off = rb == 0 ? Layout<0>::BYTES : rb == 8 ? Layout<8>::BYTES : Layout<12>::BYTES;
-  plan.passes = (p.P + 511) / 512;
+  plan.passes = (min(p.P, p.Pg) + 511) / 512;            // of the widest codebook group
   plan.x_row_bytes = (unsigned)plan.passes * 1024u;
   plan.lds_x = off; off += plan.x_row_bytes * (unsigned)batch;
   plan.lds_xsum = off; off += (unsigned)(batch * DW) * 4u;
@@ -362,7 +397,7 @@ int launch_gemv_down(const Params &p, const __half *x, long long ldx, int batch,
   plan.lds_osum = off;                                   // sized below, once the groups per workgroup are known
   // waves per stream: the choice with the fewest passes on the busiest wave, a stream's end counted as a third of a pass
   // (half when waves have to meet)
-  const int cus = cu_count();
+  const int cus = part ? max(1, cu_count() / p.n_groups) : cu_count();      // workgroups one group of columns gets
   double best = 1e30;
   unsigned grid = 1;
   for (int l = 0; l <= 3; ++l) {
@@ -373,6 +408,7 @@ int launch_gemv_down(const Params &p, const __half *x, long long ldx, int batch,
   }
   off += p.Q ? (unsigned)((plan.iters * (DW >> plan.ws_log2) * 6 + 1) * batch) * 4u : 0u;
   if (off > 160u * 1024u) return VQ_ERR_UNSUPPORTED;
+  if (part) { plan.wgs_per_group = (int)grid; grid *= (unsigned)p.n_groups; }
 #define VQ_CASE(R, BB) if (rb == R && batch == BB) return launch_one<R, BB>(p, plan, off, grid, x, ldx, y, ldy, s);
   VQ_CASE(0, 1) VQ_CASE(12, 1) VQ_CASE(8, 1)
   VQ_CASE(0, 2) VQ_CASE(12, 2) VQ_CASE(8, 2)

@@ -654,6 +654,14 @@ int launch_gemv_mfma_groups(const Params &p, const __half *x, long long ldx, int
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
 
+// y = scale * (sum over the groups) + bias * (sum of their activation sums), for any kernel that left per-group sums in a workspace.
+int launch_groups_finish(const float *part, const float *part_xs, int n_groups, int batch, const Params &p, __half *y, long long ldy,
+                         hipStream_t s) {
+  hipLaunchKernelGGL(gemv_groups_finish_kernel, dim3((unsigned)((p.out_features + 255) / 256), (unsigned)batch), dim3(256), 0, s, part, part_xs,
+                     n_groups, batch, p.out_features, p.scale, p.bias, y, ldy);
+  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
 // n layers (2 .. MULTI_MAX) on the same activations in one launch.  VQ_ERR_UNSUPPORTED when the layers do not fit
 // one kernel instantiation (different residual kinds, codebook groups, different in_features) or one launch; the
 // caller then launches them one by one.  The caller has checked gemv_fast_applicable() for each.
