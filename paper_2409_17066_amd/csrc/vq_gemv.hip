@@ -187,7 +187,7 @@ size_t gemv_workspace_bytes(const Params &p, const __half *x, long long ldx, int
   if (force_generic()) return 0;
   if (p.orientation == 1)           // vectors down the output dimension: the same workspace layout, filled by that orientation's kernel
     return p.n_groups > 1 && p.n_groups <= 256 && gemv_down_applicable(p, x, ldx)
-               ? ((size_t)p.n_groups * ((size_t)batch * (size_t)p.out_features + 16) * sizeof(float) + 255) / 256 * 256 : 0;
+               ? ((size_t)(p.n_groups + (p.Q ? 1 : 0)) * ((size_t)batch * (size_t)p.out_features + 16) * sizeof(float) + 255) / 256 * 256 : 0;
   if (forced_kernel() == 'd' || !gemv_fast_applicable(p, x, ldx)) return 0;
   return gemv_mfma_groups_workspace_bytes(p, batch);
 }
@@ -197,7 +197,8 @@ int launch_gemv_ws(const Params &p, const __half *x, long long ldx, int batch, _
   const char *env = getenv("VQ_GEMV_GROUPS");
   const size_t need = gemv_workspace_bytes(p, x, ldx, batch);
   if (need && workspace && workspace_bytes >= need && p.orientation == 1) {
-    float *part = static_cast<float *>(workspace), *part_xs = part + (size_t)p.n_groups * (size_t)batch * (size_t)p.out_features;
+    const int slots = p.n_groups + (p.Q ? 1 : 0);             // the outlier columns are one more set of sums to add up
+    float *part = static_cast<float *>(workspace), *part_xs = part + (size_t)slots * (size_t)batch * (size_t)p.out_features;
     int done = 0, g_max = 4, rc = VQ_OK;
     while (done < batch) {                                // batch rows in launches of 4, 2 or 1, as without groups
       int g = batch - done >= 4 ? 4 : batch - done >= 2 ? 2 : 1;
@@ -207,7 +208,7 @@ int launch_gemv_ws(const Params &p, const __half *x, long long ldx, int batch, _
       if (rc != VQ_OK) break;
       done += g;
     }
-    if (rc == VQ_OK) return launch_groups_finish(part, part_xs, p.n_groups, batch, p, y, ldy, s);
+    if (rc == VQ_OK) return launch_groups_finish(part, part_xs, slots, batch, p, y, ldy, s);
     if (rc != VQ_ERR_UNSUPPORTED || done != 0) return rc;
   } else if (need && workspace && workspace_bytes >= need && !(env && env[0] == 'l')) {
     const int rc = launch_gemv_mfma_groups(p, x, ldx, batch, y, ldy, workspace, s);

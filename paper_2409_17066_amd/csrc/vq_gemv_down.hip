@@ -24,6 +24,8 @@
 // [g w, (g + 1) w) see group g as a layer of its own -- its tables, its part of every index stream (a group of 8 n columns
 // starts on a dword), its columns of x, the outlier columns with group 0 -- and leave binary32 sums without scale and bias
 // in the workspace [group][token][row]; the kernel that adds the groups up is the row-wise layers' (vq_gemv_mfma.hip).
+// The outlier columns then are one more "group" of the workspace, and every workgroup of the launch works out its share
+// of rows of it (a workgroup that owned all the rows of one group of columns would spend longer on them than on its own).
 #include "vq_common.hpp"
 #include "vq_v6.hpp"
 
@@ -92,7 +94,6 @@ __global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPla
     const unsigned skip = (unsigned)(v_lo >> 3) * 12u, skip_res = (unsigned)(v_lo >> 3) * (unsigned)RES_BITS;
     p.idx += skip; idx_left -= skip;
     if (RES_BITS) { p.idx_res += skip_res; res_left -= skip_res; }
-    if (grp) p.Q = 0;                                    // the outlier columns go with the first group
     plan.passes = (p.P + 511) >> 9;
     plan.ppw = (plan.passes + (1 << plan.ws_log2) - 1) >> plan.ws_log2;
   }
@@ -105,11 +106,15 @@ __global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPla
   // words of the first batch are asked for here, before the tables are staged, so that their trip to memory overlaps it.
   constexpr int UNR = 6;
   struct OutPre { unsigned w0[UNR], w1[UNR]; float xo[B]; };
-  const int items = plan.iters * SPW * 6;
+  const bool out_ws = plan.wgs_per_group > 0 && p.Q > 0;   // grouped layer: outlier sums of rows [blockIdx * rpw, +rpw) into the workspace
+  const bool out_lds = plan.wgs_per_group == 0 && p.Q > 0;
+  const int rpw = ((p.out_features + (int)gridDim.x - 1) / (int)gridDim.x);
+  const int items = out_ws ? rpw : plan.iters * SPW * 6;
   const __amdgpu_buffer_rsrc_t r_oidx = make_rsrc(p.Q ? p.idx_out : p.idx, p.Q ? (unsigned)p.S_out * (unsigned)p.stride_out : 0u);
   const __amdgpu_buffer_rsrc_t r_ocb = make_rsrc(p.Q ? p.cb_out : p.cb, p.Q ? (unsigned)(p.k_out * p.v_out) * 2u : 0u);
   const __amdgpu_buffer_rsrc_t r_xo = make_rsrc(x, (unsigned)(((long long)(B - 1) * ldx + p.Q) * 2));
   auto item_row = [&](int r) {                           // output row of item r, or -1
+    if (out_ws) return r < items && (int)blockIdx.x * rpw + r < p.out_features ? (int)blockIdx.x * rpw + r : -1;
     const int grp_slot = r / 6, j = r - grp_slot * 6;
     const int it_r = grp_slot / SPW, slot_r = grp_slot - it_r * SPW;
     const int o = ((it_r * n_wg + wg) * SPW + slot_r) * 6 + j;
@@ -207,7 +212,12 @@ __global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPla
 #pragma unroll
         for (int t = 0; t < B; ++t) {
           const float tot = wave_total(part_o[uu][t]);
-          if (lane == 0 && r0 + uu * DW < items) osum[(r0 + uu * DW) * B + t] = tot;
+          const int o_ws = item_row(r0 + uu * DW);
+          if (out_ws) {
+            if (lane == 0 && o_ws >= 0) plan.part[((long long)p.n_groups * plan.part_batch + t) * p.out_features + o_ws] = tot;
+          } else if (lane == 0 && r0 + uu * DW < items) {
+            osum[(r0 + uu * DW) * B + t] = tot;
+          }
         }
     }
     if (wv == 0) {                                       // activation sums over the outlier columns
@@ -216,7 +226,10 @@ __global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPla
         float sx = 0.0f;
         for (int c = lane; c < p.Q; c += 64) sx += __half2float(x[(long long)t * ldx + c]);
         sx = wave_sum(sx);
-        if (lane == 0) osum[items * B + t] = sx;
+        if (lane == 0) {
+          if (out_ws) { if (blockIdx.x == 0) plan.part_xs[p.n_groups * 16 + t] = sx; }
+          else osum[items * B + t] = sx;
+        }
       }
     }
   }
@@ -320,7 +333,7 @@ __global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPla
               float xs = 0.0f;
 #pragma unroll
               for (int w = 0; w < DW; ++w) xs += xsum[t * DW + w];
-              if (p.Q) {
+              if (out_lds) {
                 mine += osum[((it * SPW + slot) * 6 + (lane - t * 6)) * B + t];
                 xs += osum[plan.iters * SPW * 6 * B + t];
               }

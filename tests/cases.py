@@ -69,6 +69,8 @@ SMALL = {
     "down_fast_groups": dict(out_features=133, in_features=1000, v=6, k=4096, k_res=4096, group_vectors=104, orientation=1),
     "down_fast_groups_outlier": dict(out_features=150, in_features=1208, v=6, k=4096, k_res=256, n_outlier_cols=24, v_out=4, k_out=4096,
                                      group_vectors=200, orientation=1),
+    "down_fast_groups_outlier_tall": dict(out_features=5003, in_features=1240, v=6, k=4096, k_res=4096, n_outlier_cols=40, v_out=8,
+                                          k_out=300, group_vectors=200, orientation=1),
     "down_fast_groups_many": dict(out_features=5000, in_features=4096, v=6, k=4096, group_vectors=600, orientation=1),
     "down_dense_gemm": dict(out_features=203, in_features=1024, v=6, k=4096, k_res=4096, n_outlier_cols=16, v_out=4, k_out=4096, orientation=1),
 }
