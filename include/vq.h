@@ -114,7 +114,10 @@ int vq_gemv(const vq_layer_desc *desc, const void *x, int64_t ldx, int32_t batch
  * afterwards).  Only layers with codebook groups (Sec. 3.1) use it: with vq_gemv_workspace_bytes(desc, batch) bytes
  * every workgroup takes one group, whose tables it loads once, and a share of the rows, writes binary32 sums to the
  * workspace, and a second kernel adds the groups up in ascending order and applies scale and bias -- instead of every
- * workgroup walking all groups and swapping its tables for each.  vq_gemv_workspace_bytes returns 0 when no kernel
+ * workgroup walking all groups and swapping its tables for each.  Layers of orientation 1 with one group use it from
+ * three rows on: the matrix-core kernel of that orientation works in blocks of 16 index streams (96 output rows), too few
+ * to fill the chip on most layers, so with a workspace it also cuts the columns into parts, one workgroup per (block,
+ * part), and the same second kernel adds the parts up.  vq_gemv_workspace_bytes returns 0 when no kernel
  * would use a workspace for this layer.  With workspace NULL or smaller than that, and for every other layer, the
  * call is vq_gemv.  Same arguments, bar and errors as vq_gemv; a workspace that is not 256-byte aligned is
  * VQ_ERR_ALIGNMENT.  Calls that share a workspace must not overlap.                                          */

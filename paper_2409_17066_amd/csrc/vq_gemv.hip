@@ -115,6 +115,10 @@ int launch_gemv_down(const Params &p, const __half *x, long long ldx, int batch,
                      float *part = nullptr, float *part_xs = nullptr, int part_batch = 0);
 int launch_groups_finish(const float *part, const float *part_xs, int n_groups, int batch, const Params &p, __half *y, long long ldy,
                          hipStream_t s);
+bool gemv_down_mfma_applicable(const Params &p, const __half *x, long long ldx, int batch);
+int gemv_down_mfma_parts(const Params &p);
+int launch_gemv_down_mfma(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s,
+                          float *part, float *part_xs, int parts);
 
 // VQ_GEMV_KERNEL=g forces the generic kernel, =m the matrix-core kernel, =d the dot-product kernels
 // (testing and measurement; unset: chosen by batch).  Read at every call so that one process can test them all.
@@ -124,12 +128,28 @@ static char forced_kernel() {
 }
 static bool force_generic() { return forced_kernel() == 'g'; }
 
+static bool down_mfma_wanted(const Params &p, const __half *x, long long ldx, int batch) {
+  const char fk = forced_kernel();
+  return fk != 'g' && fk != 'd' && (batch >= 3 || fk == 'm') && gemv_down_applicable(p, x, ldx) && gemv_down_mfma_applicable(p, x, ldx, batch);
+}
+// Without a workspace a block of 16 streams is one workgroup over all the columns: with few blocks and three or four rows the
+// other kernel, which spreads single streams over the chip, is still ahead (4096 x 11008, 43 blocks: 26 against 34 us).
+static bool down_mfma_alone_wanted(const Params &p, const __half *x, long long ldx, int batch) {
+  return p.n_groups == 1 && down_mfma_wanted(p, x, ldx, batch) && (batch >= 5 || p.S >= 64 * 16 || forced_kernel() == 'm');
+}
+
 int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
   // Matrix-core kernel: one launch for any batch, at about the cost of a batch-1 launch of the dot-product
   // kernels; those are still a little faster for one row (and for two rows of a layer with few output rows
   // per compute unit), so they keep these cases.  Layers with codebook groups always go to the matrix-core kernel:
   // it is the one that swaps the tables in LDS group by group.
   if (p.orientation == 1) {
+    // from three rows on the matrix-core kernel of this orientation is ahead (six multiply-adds per gather and row bind
+    // the other one); VQ_GEMV_KERNEL=m sends every batch there, =d none
+    if (down_mfma_alone_wanted(p, x, ldx, batch)) {
+      const int rc = launch_gemv_down_mfma(p, x, ldx, batch, y, ldy, s, nullptr, nullptr, 1);
+      if (rc != VQ_ERR_UNSUPPORTED) return rc;
+    }
     if (!force_generic() && p.n_groups == 1 && gemv_down_applicable(p, x, ldx)) {
       // batch rows go in groups of 4, 2 or 1 (fewer when the rows do not fit LDS beside the tables)
       int done = 0, g_max = 4, rc = VQ_OK;
@@ -185,6 +205,10 @@ int launch_gemv_mfma_groups(const Params &p, const __half *x, long long ldx, int
 // the groups.  VQ_GEMV_GROUPS=loop keeps every workgroup walking all groups (measurement and tests).
 size_t gemv_workspace_bytes(const Params &p, const __half *x, long long ldx, int batch) {
   if (force_generic()) return 0;
+  if (p.orientation == 1 && down_mfma_wanted(p, x, ldx, batch)) {   // the matrix cores: the workspace lets parts of the columns run side by side
+    const int parts = gemv_down_mfma_parts(p);
+    return parts > 1 ? ((size_t)parts * ((size_t)batch * (size_t)p.out_features + 16) * sizeof(float) + 255) / 256 * 256 : 0;
+  }
   if (p.orientation == 1)           // vectors down the output dimension: the same workspace layout, filled by that orientation's kernel
     return p.n_groups > 1 && p.n_groups <= 256 && gemv_down_applicable(p, x, ldx)
                ? ((size_t)(p.n_groups + (p.Q ? 1 : 0)) * ((size_t)batch * (size_t)p.out_features + 16) * sizeof(float) + 255) / 256 * 256 : 0;
@@ -196,7 +220,13 @@ int launch_gemv_ws(const Params &p, const __half *x, long long ldx, int batch, _
                    size_t workspace_bytes, hipStream_t s) {
   const char *env = getenv("VQ_GEMV_GROUPS");
   const size_t need = gemv_workspace_bytes(p, x, ldx, batch);
-  if (need && workspace && workspace_bytes >= need && p.orientation == 1) {
+  if (need && workspace && workspace_bytes >= need && p.orientation == 1 && down_mfma_wanted(p, x, ldx, batch)) {
+    const int parts = gemv_down_mfma_parts(p);
+    float *part = static_cast<float *>(workspace), *part_xs = part + (size_t)parts * (size_t)batch * (size_t)p.out_features;
+    int rc = launch_gemv_down_mfma(p, x, ldx, batch, nullptr, 0, s, part, part_xs, parts);
+    if (rc == VQ_OK) return launch_groups_finish(part, part_xs, parts, batch, p, y, ldy, s);
+    if (rc != VQ_ERR_UNSUPPORTED) return rc;
+  } else if (need && workspace && workspace_bytes >= need && p.orientation == 1) {
     const int slots = p.n_groups + (p.Q ? 1 : 0);             // the outlier columns are one more set of sums to add up
     float *part = static_cast<float *>(workspace), *part_xs = part + (size_t)slots * (size_t)batch * (size_t)p.out_features;
     int done = 0, g_max = 4, rc = VQ_OK;

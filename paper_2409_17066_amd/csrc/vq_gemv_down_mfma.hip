@@ -1,0 +1,327 @@
+// vq_gemv on the matrix cores for layers whose vectors run down the output dimension (orientation 1: the paper's own
+// layout, Sec. 3.1 and Algorithm 1), v = 6, 12-bit indices, optional 12- or 8-bit residual codebook, no outlier columns,
+// any batch up to 16 in one launch (App. "Our Dequantization Implementation", second phase); several codebook groups
+// when the caller lends a workspace.
+//
+// In this layout a gathered centroid meets ONE activation and feeds six output rows, y[6p + j] += C[I[p][n]][j] * x[n]:
+// on the vector ALUs that is six multiply-adds per gather and token, and from four tokens on the kernel of
+// vq_gemv_down.hip is bound by them.  One v_mfma_f32_16x16x32_f16 takes their place.  Its 32 "k" slots are four groups
+// of eight; a group is one column n of the layer, and the eight slots are the six elements j' of the centroid of that
+// column plus two zeros -- exactly the 16-byte table entry in LDS, as operand A of the stream (l & 15).  Operand B is
+// built to match: its 16 columns are (token, j) pairs, two tokens by six rows, and the value in slot (n, j') of column
+// (t, j) is x[t][n] where j' = j and zero elsewhere.  The product then is D[stream][(t, j)] = sum over the four columns of
+// C[I[stream][n]][j] * x[t][n]: 16 streams x 4 columns x 2 tokens per instruction, a tenth of its multiply-adds put to
+// use, and still several times the rate of the vector ALUs.  A lane builds one B operand with three byte permutes
+// (v_perm_b32 with per-lane selectors that place one half of an activation dword and zero the rest).
+//
+// Work split: a workgroup of eight waves owns one block of 16 index streams (96 output rows) and one part of the
+// columns; wave w takes the part's windows w, w + 8, ... of 32 columns (eight per lane: 96 index bits, three aligned
+// dwords; its eight activations per token are one 16-byte load, read straight from memory -- they are hits in L2 --
+// with range-checked buffer loads).  Index words and activations run a few windows ahead in a register ring.  At the
+// end the waves' 16 x 16 sums per token pair meet in LDS, in the space of the tables, which are no longer needed.
+// With one part the workgroup applies y = scale * sum + bias * sum(x) itself; a block of 16 streams is a coarse unit,
+// though (a 4096 x 4096 layer has 43 of them for 256 compute units), so when the caller lends a workspace the columns
+// are cut into parts, every (block, part) is a workgroup, the binary32 sums go to the workspace [part][token][row] and
+// the kernel that adds up codebook groups (vq_gemv_mfma.hip) adds up the parts.  Codebook groups (Sec. 3.1: ranges of
+// columns with tables of their own) are parts by nature -- a part stages the tables of its group -- and are cut further
+// the same way.
+#include "vq_common.hpp"
+#include "vq_v6.hpp"
+
+namespace vq {
+namespace {
+
+using namespace v6;
+
+constexpr int MW = 8;            // waves per workgroup
+constexpr int VPL = 8;           // columns per lane and window
+
+typedef _Float16 half8v __attribute__((ext_vector_type(8)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+struct DownMfmaPlan {
+  int ksplit;                    // parts of the columns; grid = blocks of 16 streams x ksplit
+  int sub;                       // parts per codebook group: ksplit = groups x sub
+  int wpp;                       // 32-column windows per part
+  int batch;
+  unsigned x_bytes;              // from x[0][0] to the end of the last token's row
+  float *part, *part_xs;         // workspace [part][batch][out_features], [part * 16 + token]; nullptr: one part, the kernel stores y
+};
+
+__device__ __forceinline__ float4v mfma16(uint4v a, uint4v b, float4v c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, a), __builtin_bit_cast(half8v, b), c, 0, 0, 0);
+}
+
+template <int RES_BITS, int NTP>
+__global__ __launch_bounds__(MW * 64) void gemv_down_mfma_kernel(Params p, DownMfmaPlan plan, const __half *__restrict__ x, long long ldx,
+                                                                 __half *__restrict__ y, long long ldy) {
+  typedef Layout<RES_BITS> LY;
+  constexpr int RB = RES_BITS ? RES_BITS : 8;
+  constexpr int NR = RES_BITS == 12 ? 3 : 2;             // dwords of a lane's residual indices
+  constexpr int DEPTH = NTP >= 4 ? 2 : 4;                // windows whose index words and activations are in flight or in registers
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const int lane = threadIdx.x & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int n = lane & 15, g = lane >> 4;                // A: stream n of the block, column group g.  B and D: column n = (token, j)
+  const int blk = (int)blockIdx.x / plan.ksplit, part_i = (int)blockIdx.x - blk * plan.ksplit;
+  // the part's codebook group, its stream positions [pos_lo, pos_hi) -- pos_lo a multiple of 8, a dword boundary of the
+  // streams -- and its windows, counted from pos_lo; a part past a short last group has none and leaves zeros
+  const int grp = part_i / plan.sub, sub_i = part_i - grp * plan.sub;
+  const int pos_lo = grp * p.Pg, pos_hi = min(p.P, pos_lo + p.Pg);
+  const int windows = (pos_hi - pos_lo + 31) >> 5;
+  const int w_lo = sub_i * plan.wpp, w_hi = min(windows, w_lo + plan.wpp);
+  const int my_n = w_hi - w_lo > wv ? (w_hi - w_lo - wv + MW - 1) / MW : 0;  // this wave's windows: w_lo + wv + i * MW
+  const bool need_xs = plan.part == nullptr || blk == 0;
+
+  // ---- tables into LDS: 16-byte entries, zero past k (an index past k, or read beyond a stream's end, meets zeros or a
+  // finite entry and a zero activation)
+  {
+    const unsigned *src = reinterpret_cast<const unsigned *>(p.cb + (long long)grp * p.k * 6);
+    for (int e = threadIdx.x; e < 4096; e += MW * 64) {
+      uint4v val = {0u, 0u, 0u, 0u};
+      if (e < p.k) { val.x = src[e * 3]; val.y = src[e * 3 + 1]; val.z = src[e * 3 + 2]; }
+      *reinterpret_cast<uint4v *>(lds + LY::MAIN_OFF + e * 16) = val;
+    }
+    if (RES_BITS) {
+      const unsigned *rsrc = reinterpret_cast<const unsigned *>(p.cb_res + (long long)grp * p.k_res * 6);
+      for (int e = threadIdx.x; e < (1 << RB); e += MW * 64) {
+        uint4v val = {0u, 0u, 0u, 0u};
+        if (e < p.k_res) { val.x = rsrc[e * 3]; val.y = rsrc[e * 3 + 1]; val.z = rsrc[e * 3 + 2]; }
+        *reinterpret_cast<uint4v *>(lds + LY::RES_OFF + LY::RES_ADD + e * 16) = val;
+      }
+    }
+  }
+
+  // ---- this lane's side of operand B: token tl of a pair and row j of a block of six; columns 12..15 stay zero
+  const int tl = n >= 6 ? 1 : 0, j = n - 6 * tl;
+  const bool col_on = n < 12;
+  // byte selectors that move the low (even column) or high (odd column) half of an activation dword into half (j & 1) of
+  // dword (j >> 1) of the operand, zeros (selector byte 0x0c) everywhere else
+  unsigned sel[3][2];
+#pragma unroll
+  for (int d = 0; d < 3; ++d) {
+    const bool mine = col_on && d == (j >> 1);
+    sel[d][0] = !mine ? 0x0c0c0c0cu : (j & 1) ? 0x01000c0cu : 0x0c0c0100u;
+    sel[d][1] = !mine ? 0x0c0c0c0cu : (j & 1) ? 0x03020c0cu : 0x0c0c0302u;
+  }
+  // byte offset of this lane's first activation of window 0, per token pair; a token past the batch (and the idle columns)
+  // reads out of range, i.e. zeros
+  const int col0 = p.n_out + pos_lo;                     // column of x that meets the part's window 0
+  unsigned xoff[NTP];
+#pragma unroll
+  for (int tp = 0; tp < NTP; ++tp) {
+    const int t = 2 * tp + tl;
+    xoff[tp] = col_on && t < plan.batch ? (unsigned)(((long long)t * ldx + col0 + 8 * g) * 2) : 0x80000000u;
+  }
+
+  const unsigned st_main = (unsigned)p.stride, st_res = (unsigned)p.stride_res;
+  const __amdgpu_buffer_rsrc_t r_main = make_rsrc(p.idx, (unsigned)p.S * st_main);
+  const __amdgpu_buffer_rsrc_t r_res = make_rsrc(RES_BITS ? p.idx_res : p.idx, RES_BITS ? (unsigned)p.S * st_res : 0u);
+  const __amdgpu_buffer_rsrc_t r_x = make_rsrc(x, plan.x_bytes);
+  // a stream past the last one reads out of range: index 0, whose products land in rows that are never stored
+  const unsigned srow_main = (unsigned)(blk * 16 + n) * st_main + (unsigned)(pos_lo >> 3) * 12u;
+  const unsigned srow_res = (unsigned)(blk * 16 + n) * st_res + (unsigned)(pos_lo >> 3) * (unsigned)RB;
+
+  int lw = w_lo + wv;                                    // the loader's window, DEPTH windows ahead of the consumer
+  auto load_unit = [&](Window<3> &wm, Window<NR> &wr, uint4v (&xx)[NTP]) {
+    const unsigned wq = (unsigned)(lw < w_hi ? lw : w_lo);                   // past the end: any window in range, never used
+    lw += MW;
+    load_window(wm, r_main, srow_main + (wq * 4u + (unsigned)g) * 12u, 0u);
+    if (RES_BITS == 12) load_window(wr, r_res, srow_res + (wq * 4u + (unsigned)g) * 12u, 0u);
+    if (RES_BITS == 8) load_window(wr, r_res, srow_res + (wq * 4u + (unsigned)g) * 8u, 0u);
+#pragma unroll
+    for (int tp = 0; tp < NTP; ++tp) xx[tp] = __builtin_amdgcn_raw_buffer_load_b128(r_x, xoff[tp] + wq * 64u, 0, 0);
+  };
+
+  Window<3> win[DEPTH];
+  Window<NR> wres[DEPTH];
+  uint4v xr[DEPTH][NTP];
+#pragma unroll
+  for (int d = 0; d < DEPTH; ++d) load_unit(win[d], wres[d], xr[d]);
+
+  float4v acc[NTP];
+  float xs[NTP];
+#pragma unroll
+  for (int tp = 0; tp < NTP; ++tp) { acc[tp] = float4v{0.0f, 0.0f, 0.0f, 0.0f}; xs[tp] = 0.0f; }
+
+  __syncthreads();                                       // the tables are in
+
+  for (int k0 = 0; k0 < my_n; k0 += DEPTH) {
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+      const int k = k0 + d;
+      if (k < my_n) {
+        const int w = w_lo + wv + k * MW;
+        const Window<3> cm = win[d];
+        const Window<NR> cr = wres[d];
+        uint4v xv[NTP];
+#pragma unroll
+        for (int tp = 0; tp < NTP; ++tp) xv[tp] = xr[d][tp];
+        load_unit(win[d], wres[d], xr[d]);               // refill the slot; the copies above are what this window uses
+        uint4v e[VPL], f[RES_BITS ? VPL : 1];
+#pragma unroll
+        for (int u = 0; u < VPL; ++u) lds_gather16<LY::MAIN_OFF>(e[u], field_addr<12, LY::MAIN_SH>(cm, u));
+        if (RES_BITS) {
+#pragma unroll
+          for (int u = 0; u < VPL; ++u) lds_gather16<LY::RES_OFF>(f[u], field_addr<RB, LY::RES_SH>(cr, u) + LY::RES_ADD);
+        }
+        if (w == windows - 1) {                          // the window that holds the end of the stream or of the group: zero what lies past it
+          const int left = pos_hi - pos_lo - (w * 32 + g * 8);               // of this lane's eight positions
+#pragma unroll
+          for (int tp = 0; tp < NTP; ++tp) {
+            unsigned xd[4] = {xv[tp].x, xv[tp].y, xv[tp].z, xv[tp].w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) xd[q] = left >= 2 * q + 2 ? xd[q] : left == 2 * q + 1 ? xd[q] & 0xFFFFu : 0u;
+            xv[tp].x = xd[0]; xv[tp].y = xd[1]; xv[tp].z = xd[2]; xv[tp].w = xd[3];
+          }
+        }
+        if (need_xs) {
+#pragma unroll
+          for (int tp = 0; tp < NTP; ++tp)
+            xs[tp] = dot2(xv[tp].x, 0x3C003C00u, dot2(xv[tp].y, 0x3C003C00u, dot2(xv[tp].z, 0x3C003C00u, dot2(xv[tp].w, 0x3C003C00u, xs[tp]))));
+        }
+        lds_gather_wait();
+#pragma unroll
+        for (int u = 0; u < VPL; ++u) { settle(e[u]); if (RES_BITS) settle(f[u]); }
+#pragma unroll
+        for (int u = 0; u < VPL; ++u) {
+#pragma unroll
+          for (int tp = 0; tp < NTP; ++tp) {
+            const unsigned xd = (u >> 1) == 0 ? xv[tp].x : (u >> 1) == 1 ? xv[tp].y : (u >> 1) == 2 ? xv[tp].z : xv[tp].w;
+            uint4v b;
+            b.x = __builtin_amdgcn_perm(xd, xd, sel[0][u & 1]);
+            b.y = __builtin_amdgcn_perm(xd, xd, sel[1][u & 1]);
+            b.z = __builtin_amdgcn_perm(xd, xd, sel[2][u & 1]);
+            b.w = 0u;
+            acc[tp] = mfma16(e[u], b, acc[tp]);
+            if (RES_BITS) acc[tp] = mfma16(f[u], b, acc[tp]);
+          }
+        }
+      }
+    }
+  }
+
+  // ---- the waves meet: sums per token pair, 1 KB per wave and pair, in the space of the tables
+  __syncthreads();
+  float4v *pbuf = reinterpret_cast<float4v *>(lds);                           // [NTP][MW][64]
+  float *xsb = reinterpret_cast<float *>(lds + NTP * MW * 1024);              // [MW][NTP][2][4]
+#pragma unroll
+  for (int tp = 0; tp < NTP; ++tp) {
+    pbuf[(tp * MW + wv) * 64 + lane] = acc[tp];
+    if (col_on && j == 0) xsb[((wv * NTP + tp) * 2 + tl) * 4 + g] = xs[tp];
+  }
+  __syncthreads();
+  if (wv < NTP) {                                        // wave tp finishes token pair tp
+    const int tp = wv, t = 2 * tp + tl;
+    float4v s = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int w = 0; w < MW; ++w) s += pbuf[(tp * MW + w) * 64 + lane];
+    if (col_on && t < plan.batch) {
+      float xsum = 0.0f;
+      if (need_xs) {
+#pragma unroll
+        for (int w = 0; w < MW; ++w)
+#pragma unroll
+          for (int gg = 0; gg < 4; ++gg) xsum += xsb[((w * NTP + tp) * 2 + tl) * 4 + gg];
+      }
+      const float sv[4] = {s.x, s.y, s.z, s.w};
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int stream = blk * 16 + 4 * g + r, o = stream * 6 + j;
+        if (stream < p.S && o < p.out_features) {
+          if (plan.part) {
+            plan.part[((long long)part_i * plan.batch + t) * p.out_features + o] = sv[r];
+          } else {
+            const float sc = p.scale ? __half2float(p.scale[o]) : 1.0f, bi = p.bias ? __half2float(p.bias[o]) : 0.0f;
+            y[(long long)t * ldy + o] = __float2half_rn(__fmaf_rn(sc, sv[r], bi * xsum));
+          }
+        }
+      }
+      if (plan.part && blk == 0 && g == 0 && j == 0) plan.part_xs[part_i * 16 + t] = xsum;
+    }
+  }
+}
+
+int g_cus_dm = 0;
+int cu_count() {
+  if (!g_cus_dm) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+    g_cus_dm = n;
+  }
+  return g_cus_dm;
+}
+
+template <int RES_BITS, int NTP>
+int launch_one(const Params &p, const DownMfmaPlan &plan, unsigned grid, const __half *x, long long ldx, __half *y, long long ldy,
+               hipStream_t s) {
+  static bool configured = false;
+  auto kernel = gemv_down_mfma_kernel<RES_BITS, NTP>;
+  if (!configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+      return VQ_ERR_HIP;
+    configured = true;
+  }
+  unsigned lds_bytes = Layout<RES_BITS>::BYTES;
+  const unsigned meet = (unsigned)(NTP * MW) * 1024u + (unsigned)(MW * NTP * 8) * 4u;
+  if (lds_bytes < meet) lds_bytes = meet;
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(MW * 64), lds_bytes, s, p, plan, x, ldx, y, ldy);
+  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+}  // namespace
+
+// Whether the kernel above takes this layer and these buffers (the caller has checked gemv_down_applicable()).
+bool gemv_down_mfma_applicable(const Params &p, const __half *x, long long ldx, int batch) {
+  if (p.orientation != 1 || p.v != 6 || p.bits != 12 || p.Q != 0) return false;
+  if (p.n_groups > 1 && ((p.Pg & 7) || p.n_groups > 256)) return false;     // a group starts on a dword of the index streams
+  if (p.k_res && p.bits_res != 12 && p.bits_res != 8) return false;
+  if (batch < 1 || batch > 16) return false;
+  if ((reinterpret_cast<uintptr_t>(x) & 3) || (ldx & 1) || (p.n_out & 1)) return false;      // activation loads are dword-aligned
+  if (((long long)(batch - 1) * ldx + p.in_features) * 2 >= (1LL << 31)) return false;       // 32-bit buffer offsets
+  const long long max_stride = p.stride > p.stride_res ? p.stride : p.stride_res;
+  return (long long)p.S * max_stride < (1LL << 31);
+}
+
+// Parts the columns are cut into when a workspace is there: enough for the (block, part) workgroups to fill the chip, each
+// part at least one 32-column window per wave.  1: nothing to gain from a workspace.
+// Codebook groups are parts by themselves (a part has one set of tables); each is cut further on the same terms.
+static int parts_per_group(const Params &p) {
+  const int blocks = (p.S + 15) / 16, windows = (min(p.P, p.Pg) + 31) / 32;
+  int want = cu_count() / ((blocks > 0 ? blocks : 1) * p.n_groups);
+  if (want > windows / MW) want = windows / MW;
+  if (want > 16) want = 16;
+  if (want < 2) return 1;
+  const int wpp = (windows + want - 1) / want;
+  return (windows + wpp - 1) / wpp;
+}
+int gemv_down_mfma_parts(const Params &p) { return p.n_groups * parts_per_group(p); }
+
+// part == nullptr: one launch that stores y.  Else parts = gemv_down_mfma_parts(p) > 1 and the sums go to
+// part[parts][batch][out_features], part_xs[parts * 16]; the caller adds them up.
+int launch_gemv_down_mfma(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s,
+                          float *part, float *part_xs, int parts) {
+  DownMfmaPlan plan{};
+  const int blocks = (p.S + 15) / 16, windows = (min(p.P, p.Pg) + 31) / 32;                // windows of the widest group
+  if (blocks < 1 || windows < 1) return VQ_ERR_UNSUPPORTED;
+  if (!part && p.n_groups > 1) return VQ_ERR_UNSUPPORTED;                   // groups meet in the workspace only
+  plan.ksplit = part ? parts : 1;
+  if (plan.ksplit % p.n_groups) return VQ_ERR_UNSUPPORTED;
+  plan.sub = plan.ksplit / p.n_groups;
+  plan.wpp = (windows + plan.sub - 1) / plan.sub;
+  plan.batch = batch;
+  plan.x_bytes = (unsigned)(((long long)(batch - 1) * ldx + p.in_features) * 2);
+  plan.part = part; plan.part_xs = part_xs;
+  const long long grid = (long long)blocks * plan.ksplit;
+  if (grid > 0x7FFFFFFFLL) return VQ_ERR_UNSUPPORTED;
+  const int rb = p.k_res ? p.bits_res : 0;
+  const int ntp = (batch + 1) / 2;
+#define VQ_CASE(R, N, LO) if (rb == R && ntp > LO && ntp <= N) return launch_one<R, N>(p, plan, (unsigned)grid, x, ldx, y, ldy, s);
+  VQ_CASE(0, 1, 0) VQ_CASE(0, 2, 1) VQ_CASE(0, 4, 2) VQ_CASE(0, 8, 4)
+  VQ_CASE(8, 1, 0) VQ_CASE(8, 2, 1) VQ_CASE(8, 4, 2) VQ_CASE(8, 8, 4)
+  VQ_CASE(12, 1, 0) VQ_CASE(12, 2, 1) VQ_CASE(12, 4, 2) VQ_CASE(12, 8, 4)
+#undef VQ_CASE
+  return VQ_ERR_UNSUPPORTED;
+}
+
+}  // namespace vq

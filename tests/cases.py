@@ -65,6 +65,7 @@ SMALL = {
     "down_fast_outlier": dict(out_features=150, in_features=1208, v=6, k=4096, k_res=256, n_outlier_cols=24, v_out=4, k_out=4096, orientation=1),
     "down_fast_outlier_41": dict(out_features=261, in_features=2040, v=6, k=4096, n_outlier_cols=41, v_out=4, k_out=4096, orientation=1),
     "down_fast_outlier_many_streams": dict(out_features=20501, in_features=208, v=6, k=4096, k_res=4096, n_outlier_cols=70, v_out=5, k_out=300, orientation=1),
+    "down_fast_parts": dict(out_features=1000, in_features=2104, v=6, k=4096, k_res=4096, orientation=1),
     # ... with codebook groups over the columns (fast only with a workspace: tests of vq_gemv_with_workspace)
     "down_fast_groups": dict(out_features=133, in_features=1000, v=6, k=4096, k_res=4096, group_vectors=104, orientation=1),
     "down_fast_groups_outlier": dict(out_features=150, in_features=1208, v=6, k=4096, k_res=256, n_outlier_cols=24, v_out=4, k_out=4096,
