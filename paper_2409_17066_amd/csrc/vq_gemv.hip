@@ -130,12 +130,18 @@ static bool force_generic() { return forced_kernel() == 'g'; }
 
 static bool down_mfma_wanted(const Params &p, const __half *x, long long ldx, int batch) {
   const char fk = forced_kernel();
-  return fk != 'g' && fk != 'd' && (batch >= 3 || fk == 'm') && gemv_down_applicable(p, x, ldx) && gemv_down_mfma_applicable(p, x, ldx, batch);
+  return fk != 'g' && fk != 'd' && gemv_down_applicable(p, x, ldx) && gemv_down_mfma_applicable(p, x, ldx, batch);
+}
+// With a workspace (column parts, one workgroup per block of 16 streams and part): from two rows on, and for any batch
+// when there are codebook groups (measured, 4096 x 4096: one row 12.8 against 10.5 us, two rows 13.0 against 12.7 us and
+// level from there; 16 groups, one row: 15.5 against 17.4 us).
+static bool down_mfma_parts_wanted(const Params &p, const __half *x, long long ldx, int batch) {
+  return down_mfma_wanted(p, x, ldx, batch) && (batch >= 2 || p.n_groups > 1 || forced_kernel() == 'm');
 }
 // Without a workspace a block of 16 streams is one workgroup over all the columns: with few blocks and three or four rows the
 // other kernel, which spreads single streams over the chip, is still ahead (4096 x 11008, 43 blocks: 26 against 34 us).
 static bool down_mfma_alone_wanted(const Params &p, const __half *x, long long ldx, int batch) {
-  return p.n_groups == 1 && down_mfma_wanted(p, x, ldx, batch) && (batch >= 5 || p.S >= 64 * 16 || forced_kernel() == 'm');
+  return p.n_groups == 1 && down_mfma_wanted(p, x, ldx, batch) && (batch >= 5 || (batch >= 3 && p.S >= 64 * 16) || forced_kernel() == 'm');
 }
 
 int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
@@ -144,8 +150,8 @@ int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __ha
   // per compute unit), so they keep these cases.  Layers with codebook groups always go to the matrix-core kernel:
   // it is the one that swaps the tables in LDS group by group.
   if (p.orientation == 1) {
-    // from three rows on the matrix-core kernel of this orientation is ahead (six multiply-adds per gather and row bind
-    // the other one); VQ_GEMV_KERNEL=m sends every batch there, =d none
+    // from three to five rows on the matrix-core kernel of this orientation is ahead (six multiply-adds per gather and row
+    // bind the other one); VQ_GEMV_KERNEL=m sends every batch there, =d none
     if (down_mfma_alone_wanted(p, x, ldx, batch)) {
       const int rc = launch_gemv_down_mfma(p, x, ldx, batch, y, ldy, s, nullptr, nullptr, 1);
       if (rc != VQ_ERR_UNSUPPORTED) return rc;
@@ -205,9 +211,9 @@ int launch_gemv_mfma_groups(const Params &p, const __half *x, long long ldx, int
 // the groups.  VQ_GEMV_GROUPS=loop keeps every workgroup walking all groups (measurement and tests).
 size_t gemv_workspace_bytes(const Params &p, const __half *x, long long ldx, int batch) {
   if (force_generic()) return 0;
-  if (p.orientation == 1 && down_mfma_wanted(p, x, ldx, batch)) {   // the matrix cores: the workspace lets parts of the columns run side by side
-    const int parts = gemv_down_mfma_parts(p);
-    return parts > 1 ? ((size_t)parts * ((size_t)batch * (size_t)p.out_features + 16) * sizeof(float) + 255) / 256 * 256 : 0;
+  if (p.orientation == 1 && down_mfma_parts_wanted(p, x, ldx, batch)) {   // the matrix cores: the workspace lets parts of the columns run side by side
+    const int parts = gemv_down_mfma_parts(p);            // the outlier columns are one more set of sums to add up
+    return parts > 1 ? ((size_t)(parts + (p.Q ? 1 : 0)) * ((size_t)batch * (size_t)p.out_features + 16) * sizeof(float) + 255) / 256 * 256 : 0;
   }
   if (p.orientation == 1)           // vectors down the output dimension: the same workspace layout, filled by that orientation's kernel
     return p.n_groups > 1 && p.n_groups <= 256 && gemv_down_applicable(p, x, ldx)
@@ -220,11 +226,11 @@ int launch_gemv_ws(const Params &p, const __half *x, long long ldx, int batch, _
                    size_t workspace_bytes, hipStream_t s) {
   const char *env = getenv("VQ_GEMV_GROUPS");
   const size_t need = gemv_workspace_bytes(p, x, ldx, batch);
-  if (need && workspace && workspace_bytes >= need && p.orientation == 1 && down_mfma_wanted(p, x, ldx, batch)) {
-    const int parts = gemv_down_mfma_parts(p);
-    float *part = static_cast<float *>(workspace), *part_xs = part + (size_t)parts * (size_t)batch * (size_t)p.out_features;
+  if (need && workspace && workspace_bytes >= need && p.orientation == 1 && down_mfma_parts_wanted(p, x, ldx, batch)) {
+    const int parts = gemv_down_mfma_parts(p), slots = parts + (p.Q ? 1 : 0);
+    float *part = static_cast<float *>(workspace), *part_xs = part + (size_t)slots * (size_t)batch * (size_t)p.out_features;
     int rc = launch_gemv_down_mfma(p, x, ldx, batch, nullptr, 0, s, part, part_xs, parts);
-    if (rc == VQ_OK) return launch_groups_finish(part, part_xs, parts, batch, p, y, ldy, s);
+    if (rc == VQ_OK) return launch_groups_finish(part, part_xs, slots, batch, p, y, ldy, s);
     if (rc != VQ_ERR_UNSUPPORTED) return rc;
   } else if (need && workspace && workspace_bytes >= need && p.orientation == 1) {
     const int slots = p.n_groups + (p.Q ? 1 : 0);             // the outlier columns are one more set of sums to add up

@@ -1,5 +1,5 @@
 // vq_gemv on the matrix cores for layers whose vectors run down the output dimension (orientation 1: the paper's own
-// layout, Sec. 3.1 and Algorithm 1), v = 6, 12-bit indices, optional 12- or 8-bit residual codebook, no outlier columns,
+// layout, Sec. 3.1 and Algorithm 1), v = 6, 12-bit indices, optional 12- or 8-bit residual codebook, outlier columns,
 // any batch up to 16 in one launch (App. "Our Dequantization Implementation", second phase); several codebook groups
 // when the caller lends a workspace.
 //
@@ -46,7 +46,13 @@ struct DownMfmaPlan {
   int batch;
   unsigned x_bytes;              // from x[0][0] to the end of the last token's row
   float *part, *part_xs;         // workspace [part][batch][out_features], [part * 16 + token]; nullptr: one part, the kernel stores y
+  // outlier columns: the workgroup's rows of them as a dense tile in LDS
+  unsigned lds_o;                // [OROWS][o_pitch] dwords of weights, [16][o_pitch] of activations, [16][OROWS] sums, [16] activation sums
+  int o_pitch;                   // dwords per tile row: ceil(Q / 2), made odd (rows then start in different banks)
+  int o_rpw;                     // with a workspace: rows per workgroup (the rows are dealt out to all workgroups of the launch)
 };
+
+constexpr int OROWS = 96;        // rows of outlier sums a workgroup works out: its own block's, or its share of all rows (never more)
 
 __device__ __forceinline__ float4v mfma16(uint4v a, uint4v b, float4v c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, a), __builtin_bit_cast(half8v, b), c, 0, 0, 0);
@@ -89,6 +95,50 @@ __global__ __launch_bounds__(MW * 64) void gemv_down_mfma_kernel(Params p, DownM
         if (e < p.k_res) { val.x = rsrc[e * 3]; val.y = rsrc[e * 3 + 1]; val.z = rsrc[e * 3 + 2]; }
         *reinterpret_cast<uint4v *>(lds + LY::RES_OFF + LY::RES_ADD + e * 16) = val;
       }
+    }
+  }
+
+  // ---- outlier columns (Sec. 3.2.3; any v_out and k_out; their index streams belong to blocks of v_out rows): few columns, so
+  // the workgroup's rows of them are restored into a dense tile in LDS -- every (row, column) is independent: one trip to the
+  // index streams, one to the table, for all of them at once -- and multiplied from there once the barrier below has passed.
+  // Without a workspace the rows are the block's own and their sums wait in LDS for the end; with one, the outlier columns
+  // are one more part of the workspace and every workgroup of the launch takes a share of ALL rows.
+  const int o_row_lo = plan.part ? (int)blockIdx.x * plan.o_rpw : blk * OROWS;
+  const int o_rows = p.Q ? max(0, min(plan.part ? plan.o_rpw : OROWS, p.out_features - o_row_lo)) : 0;
+  const int Q2 = 2 * plan.o_pitch;                       // halves per tile row
+  unsigned short *o_tile = reinterpret_cast<unsigned short *>(lds + plan.lds_o);
+  unsigned short *o_x = o_tile + OROWS * Q2;
+  float *o_sum = reinterpret_cast<float *>(o_x + 16 * Q2), *o_xs = o_sum + 16 * OROWS;
+  if (p.Q) {
+    const __amdgpu_buffer_rsrc_t r_oidx = make_rsrc(p.idx_out, (unsigned)p.S_out * (unsigned)p.stride_out);
+    const __amdgpu_buffer_rsrc_t r_ocb = make_rsrc(p.cb_out, (unsigned)(p.k_out * p.v_out) * 2u);
+    constexpr int OU = 4;                                // entries a thread has in flight
+    const int total = o_rows * Q2;
+    for (int e0 = (int)threadIdx.x; e0 < total; e0 += MW * 64 * OU) {
+      unsigned w0[OU], w1[OU], sh[OU], jo[OU];
+      bool ok[OU];
+#pragma unroll
+      for (int uu = 0; uu < OU; ++uu) {
+        const int e = e0 + uu * MW * 64, r = e / Q2, c = e - r * Q2;
+        ok[uu] = e < total && c < p.Q;
+        const int o = o_row_lo + (ok[uu] ? r : 0), sq = o / p.v_out;
+        const unsigned bit = (unsigned)(ok[uu] ? c : 0) * (unsigned)p.bits_out;
+        const unsigned woff = (unsigned)sq * (unsigned)p.stride_out + (bit >> 5) * 4u;
+        jo[uu] = (unsigned)(o - sq * p.v_out); sh[uu] = bit & 31u;
+        w0[uu] = __builtin_amdgcn_raw_buffer_load_b32(r_oidx, woff, 0, 0);
+        w1[uu] = __builtin_amdgcn_raw_buffer_load_b32(r_oidx, woff + 4u, 0, 0);
+      }
+#pragma unroll
+      for (int uu = 0; uu < OU; ++uu) {
+        const unsigned i = min(__builtin_amdgcn_alignbit(w1[uu], w0[uu], sh[uu]) & ((1u << p.bits_out) - 1u), (unsigned)p.k_out - 1u);
+        const unsigned short wh = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r_ocb, (i * (unsigned)p.v_out + jo[uu]) * 2u, 0, 0);
+        const int e = e0 + uu * MW * 64;
+        if (e < total) o_tile[e] = ok[uu] ? wh : (unsigned short)0;
+      }
+    }
+    for (int e = (int)threadIdx.x; e < 16 * Q2; e += MW * 64) {
+      const int t = e / Q2, c = e - t * Q2;
+      o_x[e] = t < plan.batch && c < p.Q ? __half_as_ushort(x[(long long)t * ldx + c]) : (unsigned short)0;
     }
   }
 
@@ -145,6 +195,34 @@ __global__ __launch_bounds__(MW * 64) void gemv_down_mfma_kernel(Params p, DownM
   for (int tp = 0; tp < NTP; ++tp) { acc[tp] = float4v{0.0f, 0.0f, 0.0f, 0.0f}; xs[tp] = 0.0f; }
 
   __syncthreads();                                       // the tables are in
+
+  if (p.Q) {                                             // the outlier tile times the activations: a thread per (row, four tokens)
+    const unsigned *wt = reinterpret_cast<const unsigned *>(o_tile), *xt = reinterpret_cast<const unsigned *>(o_x);
+    const int ntg = (plan.batch + 3) >> 2;
+    for (int i = (int)threadIdx.x; i < o_rows * ntg; i += MW * 64) {
+      const int tg = i / o_rows, r = i - tg * o_rows;
+      float a[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      for (int c2 = 0; c2 < plan.o_pitch; ++c2) {
+        const unsigned wd = wt[r * plan.o_pitch + c2];
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) a[tt] = dot2(wd, xt[(tg * 4 + tt) * plan.o_pitch + c2], a[tt]);
+      }
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) {
+        const int t = tg * 4 + tt;
+        if (t < plan.batch) {
+          if (plan.part) plan.part[((long long)plan.ksplit * plan.batch + t) * p.out_features + o_row_lo + r] = a[tt];
+          else o_sum[t * OROWS + r] = a[tt];
+        }
+      }
+    }
+    if ((int)threadIdx.x < plan.batch) {                 // activation sums over the outlier columns
+      float sx = 0.0f;
+      for (int c2 = 0; c2 < plan.o_pitch; ++c2) sx += half_pair_sum(xt[(int)threadIdx.x * plan.o_pitch + c2]);
+      if (!plan.part) o_xs[threadIdx.x] = sx;
+      else if (blockIdx.x == 0) plan.part_xs[plan.ksplit * 16 + (int)threadIdx.x] = sx;
+    }
+  }
 
   for (int k0 = 0; k0 < my_n; k0 += DEPTH) {
 #pragma unroll
@@ -224,7 +302,12 @@ __global__ __launch_bounds__(MW * 64) void gemv_down_mfma_kernel(Params p, DownM
 #pragma unroll
           for (int gg = 0; gg < 4; ++gg) xsum += xsb[((w * NTP + tp) * 2 + tl) * 4 + gg];
       }
-      const float sv[4] = {s.x, s.y, s.z, s.w};
+      float sv[4] = {s.x, s.y, s.z, s.w};
+      if (p.Q && !plan.part) {                           // the block's own outlier sums, left in LDS before the main loop
+        xsum += o_xs[t];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sv[r] += o_sum[t * OROWS + (4 * g + r) * 6 + j];
+      }
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int stream = blk * 16 + 4 * g + r, o = stream * 6 + j;
@@ -253,7 +336,7 @@ int cu_count() {
 }
 
 template <int RES_BITS, int NTP>
-int launch_one(const Params &p, const DownMfmaPlan &plan, unsigned grid, const __half *x, long long ldx, __half *y, long long ldy,
+int launch_one(const Params &p, DownMfmaPlan &plan, unsigned grid, const __half *x, long long ldx, __half *y, long long ldy,
                hipStream_t s) {
   static bool configured = false;
   auto kernel = gemv_down_mfma_kernel<RES_BITS, NTP>;
@@ -265,6 +348,9 @@ int launch_one(const Params &p, const DownMfmaPlan &plan, unsigned grid, const _
   unsigned lds_bytes = Layout<RES_BITS>::BYTES;
   const unsigned meet = (unsigned)(NTP * MW) * 1024u + (unsigned)(MW * NTP * 8) * 4u;
   if (lds_bytes < meet) lds_bytes = meet;
+  plan.lds_o = lds_bytes;
+  if (p.Q) lds_bytes += (unsigned)((OROWS + 16) * plan.o_pitch + 16 * OROWS + 16) * 4u;
+  if (lds_bytes > 160u * 1024u) return VQ_ERR_UNSUPPORTED;                  // too many outlier columns to hold beside the tables
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(MW * 64), lds_bytes, s, p, plan, x, ldx, y, ldy);
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
@@ -273,7 +359,8 @@ int launch_one(const Params &p, const DownMfmaPlan &plan, unsigned grid, const _
 
 // Whether the kernel above takes this layer and these buffers (the caller has checked gemv_down_applicable()).
 bool gemv_down_mfma_applicable(const Params &p, const __half *x, long long ldx, int batch) {
-  if (p.orientation != 1 || p.v != 6 || p.bits != 12 || p.Q != 0) return false;
+  if (p.orientation != 1 || p.v != 6 || p.bits != 12 || p.Q > 512) return false;
+  if (p.Q && (long long)p.S_out * p.stride_out >= (1LL << 31)) return false;
   if (p.n_groups > 1 && ((p.Pg & 7) || p.n_groups > 256)) return false;     // a group starts on a dword of the index streams
   if (p.k_res && p.bits_res != 12 && p.bits_res != 8) return false;
   if (batch < 1 || batch > 16) return false;
@@ -312,6 +399,8 @@ int launch_gemv_down_mfma(const Params &p, const __half *x, long long ldx, int b
   plan.batch = batch;
   plan.x_bytes = (unsigned)(((long long)(batch - 1) * ldx + p.in_features) * 2);
   plan.part = part; plan.part_xs = part_xs;
+  plan.o_pitch = ((p.Q + 1) / 2) | 1;
+  plan.o_rpw = (int)((p.out_features + (long long)blocks * plan.ksplit - 1) / ((long long)blocks * plan.ksplit));   // <= 96: a block has 96 rows
   const long long grid = (long long)blocks * plan.ksplit;
   if (grid > 0x7FFFFFFFLL) return VQ_ERR_UNSUPPORTED;
   const int rb = p.k_res ? p.bits_res : 0;

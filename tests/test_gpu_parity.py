@@ -224,19 +224,19 @@ def test_gemv_workspace_is_not_asked_for_without_groups(gpu_lib):
         assert gpu_lib.vq_gemv_workspace_bytes(dl.desc, 4) == 0, name
 
 
-NATIVE_PLAIN = [n for n, kw in SMALL.items() if n.startswith("down_fast") and not kw.get("group_vectors") and not kw.get("n_outlier_cols")]
+NATIVE_PLAIN = [n for n, kw in SMALL.items() if n.startswith("down_fast") and not kw.get("group_vectors") and kw.get("n_outlier_cols", 0) % 2 == 0]
 
 
 @pytest.mark.parametrize("name", NATIVE_PLAIN)
-@pytest.mark.parametrize("batch", [3, 6, 16])
+@pytest.mark.parametrize("batch", [2, 3, 6, 16])
 def test_gemv_native_orientation_column_parts_with_workspace(gpu_lib, name, batch):
-    """Vectors down the output dimension, one codebook group, three rows or more: with a workspace the matrix-core kernel
+    """Vectors down the output dimension, one codebook group, two rows or more: with a workspace the matrix-core kernel
     cuts the columns into parts that run side by side and a second kernel adds them up."""
     import torch
     L = small_layer(name)
     dl = gpu_lib.DeviceLayer(L)
     need = gpu_lib.vq_gemv_workspace_bytes(dl.desc, batch)
-    if L.in_features < 2 * 8 * 32 or L.out_features > 16 * 6 * 128:
+    if L.in_features - L.n_outlier_cols < 2 * 8 * 32 or L.out_features > 16 * 6 * 128:
         assert need == 0, name          # a part needs a window of 32 columns per wave; more blocks of 16 streams than half the chip need no parts
         return
     assert need >= 2 * batch * L.out_features * 4, name
@@ -247,4 +247,4 @@ def test_gemv_native_orientation_column_parts_with_workspace(gpu_lib, name, batc
     torch.cuda.synchronize()
     _check_matmul(y, oracle.gemv(L, x_np), "%s batch %d with workspace" % (name, batch))
     assert (ws[need:] == 0xFF).all()
-    assert gpu_lib.vq_gemv_workspace_bytes(dl.desc, 1) == 0      # one or two rows stay on the kernel that needs none
+    assert gpu_lib.vq_gemv_workspace_bytes(dl.desc, 1) == 0      # a single row stays on the kernel that needs none
