@@ -355,11 +355,15 @@ def detail(vq, s, np, torch, use_graph, skip):
     # the headline shape stored in the paper's own orientation (vectors down the output dimension)
     Ld = s.make_layer(1, "up", L1.out_features, L1.in_features, 6, 4096, orientation=1)
     for batch in (1, 4, 16):
-        r = bench_gemv(vq, Ld, s.make_activations(1, Ld, batch), steps, warmup, use_graph)
-        sec = r["event_s"] / steps
-        alg = Ld.algorithmic_bytes(batch)
-        out.append({"op": "vq_gemv", "cfg": "1 with vectors down the output dimension (orientation 1)", "batch": batch,
-                    "us": round(sec * 1e6, 3), "GB/s": round(alg / sec / 1e9, 1), "frac_hbm_peak": round(alg / sec / 1e9 / HBM_PEAK_GBPS, 4)})
+        for with_ws in (False, True):
+            if with_ws and not vq.vq_gemv_workspace_bytes(vq.DeviceLayer(Ld).desc, batch):
+                continue                    # no kernel would use one for this batch
+            r = bench_gemv(vq, Ld, s.make_activations(1, Ld, batch), steps, warmup, use_graph, workspace=with_ws)
+            sec = r["event_s"] / steps
+            alg = Ld.algorithmic_bytes(batch)
+            out.append({"op": "vq_gemv_with_workspace" if with_ws else "vq_gemv",
+                        "cfg": "1 with vectors down the output dimension (orientation 1)", "batch": batch,
+                        "us": round(sec * 1e6, 3), "GB/s": round(alg / sec / 1e9, 1), "frac_hbm_peak": round(alg / sec / 1e9 / HBM_PEAK_GBPS, 4)})
     del Ld
     # codebook groups on the headline shape: "group num" 4 and 16 of the paper's parameter table, as group sizes
     # rounded up to 8 vectors
