@@ -19,7 +19,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=o
 # Kernels in these files load registers asynchronously from inline assembly and wait for them with counted
 # s_waitcnt.  The compiler does not know such a register is pending: if it spilled one, it would save the old
 # contents.  Their kernels must therefore not spill at all; the build reads the compiler's resource remarks.
-NO_SPILL = {"vq_gemv_mfma.hip", "vq_gemm_fused.hip"}
+NO_SPILL = {"vq_gemv_mfma.hip", "vq_gemm_fused.hip", "vq_gemv_down.hip", "vq_gemv_down_mfma.hip"}
 # One exception, checked in the generated code of this image's compiler (ROCm 7.2): the 512-token GEMM tile saves
 # five address registers at kernel entry, before its first asynchronous load, and reloads them in the epilogue.
 SPILLS_ALLOWED = {"gemm_v8_kernelILi512E": 5}

@@ -147,25 +147,14 @@ __global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPla
       for (int t = 0; t < B; ++t) part_o[uu][t] = __fmaf_rn(w, pre.xo[t], part_o[uu][t]);
     }
   };
+  // the table loads, all at once, before everything else of the start-up; stored at its end
+  TableStage<RES_BITS, DW * 64> tables{};
+  tables.issue(p, 0, false);                             // (p.cb and p.cb_res already point at this workgroup's group)
   OutPre pre0;
   if (p.Q) out_issue(wv, lane, pre0);
 
   // ---- tables into LDS (16-byte entries, zero past k), activation rows (zero past the last column), their sums
   {
-    const unsigned *src = reinterpret_cast<const unsigned *>(p.cb);
-    for (int e = threadIdx.x; e < 4096; e += DW * 64) {
-      uint4v val = {0u, 0u, 0u, 0u};
-      if (e < p.k) { val.x = src[e * 3]; val.y = src[e * 3 + 1]; val.z = src[e * 3 + 2]; }
-      *reinterpret_cast<uint4v *>(lds + LY::MAIN_OFF + e * 16) = val;
-    }
-    if (RES_BITS) {
-      const unsigned *rsrc = reinterpret_cast<const unsigned *>(p.cb_res);
-      for (int e = threadIdx.x; e < (1 << RB); e += DW * 64) {
-        uint4v val = {0u, 0u, 0u, 0u};
-        if (e < p.k_res) { val.x = rsrc[e * 3]; val.y = rsrc[e * 3 + 1]; val.z = rsrc[e * 3 + 2]; }
-        *reinterpret_cast<uint4v *>(lds + LY::RES_OFF + LY::RES_ADD + e * 16) = val;
-      }
-    }
     float *xsum = reinterpret_cast<float *>(lds + plan.lds_xsum);             // [B][DW]
 #pragma unroll
     for (int t = 0; t < B; ++t) {
@@ -233,6 +222,8 @@ __global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPla
       }
     }
   }
+  wait_vmem_at_most<0>();
+  tables.store(p, lds, 0u, false);
   __syncthreads();
 
   const unsigned st_main = (unsigned)p.stride, st_res = (unsigned)p.stride_res;

@@ -80,23 +80,10 @@ __global__ __launch_bounds__(MW * 64) void gemv_down_mfma_kernel(Params p, DownM
   const bool need_xs = plan.part == nullptr || blk == 0;
 
   // ---- tables into LDS: 16-byte entries, zero past k (an index past k, or read beyond a stream's end, meets zeros or a
-  // finite entry and a zero activation)
-  {
-    const unsigned *src = reinterpret_cast<const unsigned *>(p.cb + (long long)grp * p.k * 6);
-    for (int e = threadIdx.x; e < 4096; e += MW * 64) {
-      uint4v val = {0u, 0u, 0u, 0u};
-      if (e < p.k) { val.x = src[e * 3]; val.y = src[e * 3 + 1]; val.z = src[e * 3 + 2]; }
-      *reinterpret_cast<uint4v *>(lds + LY::MAIN_OFF + e * 16) = val;
-    }
-    if (RES_BITS) {
-      const unsigned *rsrc = reinterpret_cast<const unsigned *>(p.cb_res + (long long)grp * p.k_res * 6);
-      for (int e = threadIdx.x; e < (1 << RB); e += MW * 64) {
-        uint4v val = {0u, 0u, 0u, 0u};
-        if (e < p.k_res) { val.x = rsrc[e * 3]; val.y = rsrc[e * 3 + 1]; val.z = rsrc[e * 3 + 2]; }
-        *reinterpret_cast<uint4v *>(lds + LY::RES_OFF + LY::RES_ADD + e * 16) = val;
-      }
-    }
-  }
+  // finite entry and a zero activation).  All their loads are asked for here, at once; they are stored after everything
+  // else of the start-up has been asked for as well (a loop of load-and-store rounds costs a trip to L2 per round).
+  TableStage<RES_BITS, MW * 64> tables{};
+  tables.issue(p, grp, false);
 
   // ---- outlier columns (Sec. 3.2.3; any v_out and k_out; their index streams belong to blocks of v_out rows): few columns, so
   // the workgroup's rows of them are restored into a dense tile in LDS -- every (row, column) is independent: one trip to the
@@ -188,6 +175,9 @@ __global__ __launch_bounds__(MW * 64) void gemv_down_mfma_kernel(Params p, DownM
   uint4v xr[DEPTH][NTP];
 #pragma unroll
   for (int d = 0; d < DEPTH; ++d) load_unit(win[d], wres[d], xr[d]);
+  // the table loads are older than the ring's (loads return in order): at most the ring's may still be on their way
+  wait_vmem_at_most<DEPTH * (1 + (RES_BITS ? 1 : 0) + NTP)>();
+  tables.store(p, lds, 0u, false);
 
   float4v acc[NTP];
   float xs[NTP];

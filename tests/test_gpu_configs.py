@@ -120,14 +120,17 @@ def test_headline_shape_with_codebook_groups(gpu_lib, group_vectors):
             _matmul_ok(y, ref, "grouped headline shape, %d vectors a group, batch %d, workspace %s" % (group_vectors, batch, workspace))
 
 
-@pytest.mark.parametrize("extra", [dict(), dict(k_res=4096, n_outlier_cols=40, v_out=4, k_out=4096)])
+@pytest.mark.parametrize("extra", [dict(), dict(k_res=4096, n_outlier_cols=40, v_out=4, k_out=4096), dict(group_vectors=256, k_res=256)])
 def test_headline_shape_in_the_papers_orientation(gpu_lib, extra):
-    """The 11008 x 4096 layer with vectors down the output dimension, as bench.py's detail lines time it."""
+    """The 11008 x 4096 layer with vectors down the output dimension, as bench.py's detail lines time it: the vector-ALU
+    kernel (one row), the matrix-core kernel alone and with the column parts of the workspace route."""
     import torch
     L = s.make_layer(1, "up", 11008, 4096, 6, 4096, orientation=1, **extra)
     dl = _dequant_exact(gpu_lib, L)
-    for batch in (1, 4, 7):
+    for batch in (1, 4, 7, 16):
         x = s.make_activations(1, L, batch)
-        y = gpu_lib.gemv(dl, torch.from_numpy(x).cuda())
-        torch.cuda.synchronize()
-        _matmul_ok(y, oracle.gemv(L, x), "headline shape, orientation 1, batch %d, %s" % (batch, extra))
+        ref = oracle.gemv(L, x)
+        for workspace in (None, "fast"):
+            y = gpu_lib.gemv(dl, torch.from_numpy(x).cuda(), workspace=workspace)
+            torch.cuda.synchronize()
+            _matmul_ok(y, ref, "headline shape, orientation 1, batch %d, %s, workspace %s" % (batch, extra, workspace))
