@@ -141,7 +141,9 @@ static bool down_mfma_parts_wanted(const Params &p, const __half *x, long long l
 // Without a workspace a block of 16 streams is one workgroup over all the columns: with few blocks and three or four rows the
 // other kernel, which spreads single streams over the chip, is still ahead (4096 x 11008, 43 blocks: 26 against 34 us).
 static bool down_mfma_alone_wanted(const Params &p, const __half *x, long long ldx, int batch) {
-  return p.n_groups == 1 && down_mfma_wanted(p, x, ldx, batch) && (batch >= 5 || (batch >= 3 && p.S >= 64 * 16) || forced_kernel() == 'm');
+  if (!down_mfma_wanted(p, x, ldx, batch)) return false;
+  if (p.n_groups > 1) return true;                        // the only fast kernel of this orientation that walks codebook groups by itself
+  return batch >= 5 || (batch >= 3 && p.S >= 64 * 16) || forced_kernel() == 'm';
 }
 
 int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {

@@ -1,7 +1,6 @@
 // vq_gemv on the matrix cores for layers whose vectors run down the output dimension (orientation 1: the paper's own
 // layout, Sec. 3.1 and Algorithm 1), v = 6, 12-bit indices, optional 12- or 8-bit residual codebook, outlier columns,
-// any batch up to 16 in one launch (App. "Our Dequantization Implementation", second phase); several codebook groups
-// when the caller lends a workspace.
+// any batch up to 16 in one launch (App. "Our Dequantization Implementation", second phase), one or more codebook groups.
 //
 // In this layout a gathered centroid meets ONE activation and feeds six output rows, y[6p + j] += C[I[p][n]][j] * x[n]:
 // on the vector ALUs that is six multiply-adds per gather and token, and from four tokens on the kernel of
@@ -24,7 +23,8 @@
 // are cut into parts, every (block, part) is a workgroup, the binary32 sums go to the workspace [part][token][row] and
 // the kernel that adds up codebook groups (vq_gemv_mfma.hip) adds up the parts.  Codebook groups (Sec. 3.1: ranges of
 // columns with tables of their own) are parts by nature -- a part stages the tables of its group -- and are cut further
-// the same way.
+// the same way; without a workspace the workgroup of a block walks the groups one after the other, swapping the tables
+// in LDS, with its sums running on.
 #include "vq_common.hpp"
 #include "vq_v6.hpp"
 
@@ -58,32 +58,27 @@ __device__ __forceinline__ float4v mfma16(uint4v a, uint4v b, float4v c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, a), __builtin_bit_cast(half8v, b), c, 0, 0, 0);
 }
 
-template <int RES_BITS, int NTP>
+// WALK: the instantiation for layers with codebook groups and no workspace, whose workgroups walk all groups; the others
+// take one group (or the only one) and have no loop around the start-up (with the loop in every instantiation the
+// single-group ones lost up to 4 us on a 4096 x 4096 layer in 16 groups: registers held across the loop edge).
+template <int RES_BITS, int NTP, bool WALK>
 __global__ __launch_bounds__(MW * 64) void gemv_down_mfma_kernel(Params p, DownMfmaPlan plan, const __half *__restrict__ x, long long ldx,
                                                                  __half *__restrict__ y, long long ldy) {
   typedef Layout<RES_BITS> LY;
   constexpr int RB = RES_BITS ? RES_BITS : 8;
   constexpr int NR = RES_BITS == 12 ? 3 : 2;             // dwords of a lane's residual indices
-  constexpr int DEPTH = NTP >= 4 ? 2 : 4;                // windows whose index words and activations are in flight or in registers
+  constexpr int DEPTH = NTP >= 4 ? 2 : 4;
+  constexpr bool LATE_X = NTP >= 8;                      // registers: refill a slot's activations only after the window's last product                // windows whose index words and activations are in flight or in registers
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = lane & 15, g = lane >> 4;                // A: stream n of the block, column group g.  B and D: column n = (token, j)
   const int blk = (int)blockIdx.x / plan.ksplit, part_i = (int)blockIdx.x - blk * plan.ksplit;
-  // the part's codebook group, its stream positions [pos_lo, pos_hi) -- pos_lo a multiple of 8, a dword boundary of the
-  // streams -- and its windows, counted from pos_lo; a part past a short last group has none and leaves zeros
-  const int grp = part_i / plan.sub, sub_i = part_i - grp * plan.sub;
-  const int pos_lo = grp * p.Pg, pos_hi = min(p.P, pos_lo + p.Pg);
-  const int windows = (pos_hi - pos_lo + 31) >> 5;
-  const int w_lo = sub_i * plan.wpp, w_hi = min(windows, w_lo + plan.wpp);
-  const int my_n = w_hi - w_lo > wv ? (w_hi - w_lo - wv + MW - 1) / MW : 0;  // this wave's windows: w_lo + wv + i * MW
+  // A part belongs to one codebook group; without a workspace the workgroup walks all groups, one set of tables after the
+  // other in LDS, and its sums simply keep running (the tables change with the column, the output rows do not).
+  const int g_lo = plan.part ? part_i / plan.sub : 0, g_hi = WALK ? p.n_groups : g_lo + 1;
+  const int sub_i = plan.part ? part_i - g_lo * plan.sub : 0;
   const bool need_xs = plan.part == nullptr || blk == 0;
-
-  // ---- tables into LDS: 16-byte entries, zero past k (an index past k, or read beyond a stream's end, meets zeros or a
-  // finite entry and a zero activation).  All their loads are asked for here, at once; they are stored after everything
-  // else of the start-up has been asked for as well (a loop of load-and-store rounds costs a trip to L2 per round).
-  TableStage<RES_BITS, MW * 64> tables{};
-  tables.issue(p, grp, false);
 
   // ---- outlier columns (Sec. 3.2.3; any v_out and k_out; their index streams belong to blocks of v_out rows): few columns, so
   // the workgroup's rows of them are restored into a dense tile in LDS -- every (row, column) is independent: one trip to the
@@ -96,39 +91,6 @@ __global__ __launch_bounds__(MW * 64) void gemv_down_mfma_kernel(Params p, DownM
   unsigned short *o_tile = reinterpret_cast<unsigned short *>(lds + plan.lds_o);
   unsigned short *o_x = o_tile + OROWS * Q2;
   float *o_sum = reinterpret_cast<float *>(o_x + 16 * Q2), *o_xs = o_sum + 16 * OROWS;
-  if (p.Q) {
-    const __amdgpu_buffer_rsrc_t r_oidx = make_rsrc(p.idx_out, (unsigned)p.S_out * (unsigned)p.stride_out);
-    const __amdgpu_buffer_rsrc_t r_ocb = make_rsrc(p.cb_out, (unsigned)(p.k_out * p.v_out) * 2u);
-    constexpr int OU = 4;                                // entries a thread has in flight
-    const int total = o_rows * Q2;
-    for (int e0 = (int)threadIdx.x; e0 < total; e0 += MW * 64 * OU) {
-      unsigned w0[OU], w1[OU], sh[OU], jo[OU];
-      bool ok[OU];
-#pragma unroll
-      for (int uu = 0; uu < OU; ++uu) {
-        const int e = e0 + uu * MW * 64, r = e / Q2, c = e - r * Q2;
-        ok[uu] = e < total && c < p.Q;
-        const int o = o_row_lo + (ok[uu] ? r : 0), sq = o / p.v_out;
-        const unsigned bit = (unsigned)(ok[uu] ? c : 0) * (unsigned)p.bits_out;
-        const unsigned woff = (unsigned)sq * (unsigned)p.stride_out + (bit >> 5) * 4u;
-        jo[uu] = (unsigned)(o - sq * p.v_out); sh[uu] = bit & 31u;
-        w0[uu] = __builtin_amdgcn_raw_buffer_load_b32(r_oidx, woff, 0, 0);
-        w1[uu] = __builtin_amdgcn_raw_buffer_load_b32(r_oidx, woff + 4u, 0, 0);
-      }
-#pragma unroll
-      for (int uu = 0; uu < OU; ++uu) {
-        const unsigned i = min(__builtin_amdgcn_alignbit(w1[uu], w0[uu], sh[uu]) & ((1u << p.bits_out) - 1u), (unsigned)p.k_out - 1u);
-        const unsigned short wh = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r_ocb, (i * (unsigned)p.v_out + jo[uu]) * 2u, 0, 0);
-        const int e = e0 + uu * MW * 64;
-        if (e < total) o_tile[e] = ok[uu] ? wh : (unsigned short)0;
-      }
-    }
-    for (int e = (int)threadIdx.x; e < 16 * Q2; e += MW * 64) {
-      const int t = e / Q2, c = e - t * Q2;
-      o_x[e] = t < plan.batch && c < p.Q ? __half_as_ushort(x[(long long)t * ldx + c]) : (unsigned short)0;
-    }
-  }
-
   // ---- this lane's side of operand B: token tl of a pair and row j of a block of six; columns 12..15 stay zero
   const int tl = n >= 6 ? 1 : 0, j = n - 6 * tl;
   const bool col_on = n < 12;
@@ -141,132 +103,199 @@ __global__ __launch_bounds__(MW * 64) void gemv_down_mfma_kernel(Params p, DownM
     sel[d][0] = !mine ? 0x0c0c0c0cu : (j & 1) ? 0x01000c0cu : 0x0c0c0100u;
     sel[d][1] = !mine ? 0x0c0c0c0cu : (j & 1) ? 0x03020c0cu : 0x0c0c0302u;
   }
-  // byte offset of this lane's first activation of window 0, per token pair; a token past the batch (and the idle columns)
-  // reads out of range, i.e. zeros
-  const int col0 = p.n_out + pos_lo;                     // column of x that meets the part's window 0
-  unsigned xoff[NTP];
-#pragma unroll
-  for (int tp = 0; tp < NTP; ++tp) {
-    const int t = 2 * tp + tl;
-    xoff[tp] = col_on && t < plan.batch ? (unsigned)(((long long)t * ldx + col0 + 8 * g) * 2) : 0x80000000u;
-  }
-
   const unsigned st_main = (unsigned)p.stride, st_res = (unsigned)p.stride_res;
   const __amdgpu_buffer_rsrc_t r_main = make_rsrc(p.idx, (unsigned)p.S * st_main);
   const __amdgpu_buffer_rsrc_t r_res = make_rsrc(RES_BITS ? p.idx_res : p.idx, RES_BITS ? (unsigned)p.S * st_res : 0u);
   const __amdgpu_buffer_rsrc_t r_x = make_rsrc(x, plan.x_bytes);
-  // a stream past the last one reads out of range: index 0, whose products land in rows that are never stored
-  const unsigned srow_main = (unsigned)(blk * 16 + n) * st_main + (unsigned)(pos_lo >> 3) * 12u;
-  const unsigned srow_res = (unsigned)(blk * 16 + n) * st_res + (unsigned)(pos_lo >> 3) * (unsigned)RB;
-
-  int lw = w_lo + wv;                                    // the loader's window, DEPTH windows ahead of the consumer
-  auto load_unit = [&](Window<3> &wm, Window<NR> &wr, uint4v (&xx)[NTP]) {
-    const unsigned wq = (unsigned)(lw < w_hi ? lw : w_lo);                   // past the end: any window in range, never used
-    lw += MW;
-    load_window(wm, r_main, srow_main + (wq * 4u + (unsigned)g) * 12u, 0u);
-    if (RES_BITS == 12) load_window(wr, r_res, srow_res + (wq * 4u + (unsigned)g) * 12u, 0u);
-    if (RES_BITS == 8) load_window(wr, r_res, srow_res + (wq * 4u + (unsigned)g) * 8u, 0u);
-#pragma unroll
-    for (int tp = 0; tp < NTP; ++tp) xx[tp] = __builtin_amdgcn_raw_buffer_load_b128(r_x, xoff[tp] + wq * 64u, 0, 0);
-  };
-
-  Window<3> win[DEPTH];
-  Window<NR> wres[DEPTH];
-  uint4v xr[DEPTH][NTP];
-#pragma unroll
-  for (int d = 0; d < DEPTH; ++d) load_unit(win[d], wres[d], xr[d]);
-  // the table loads are older than the ring's (loads return in order): at most the ring's may still be on their way
-  wait_vmem_at_most<DEPTH * (1 + (RES_BITS ? 1 : 0) + NTP)>();
-  tables.store(p, lds, 0u, false);
-
   float4v acc[NTP];
   float xs[NTP];
 #pragma unroll
   for (int tp = 0; tp < NTP; ++tp) { acc[tp] = float4v{0.0f, 0.0f, 0.0f, 0.0f}; xs[tp] = 0.0f; }
 
-  __syncthreads();                                       // the tables are in
+  for (int grp = g_lo; grp < g_hi; ++grp) {
+    // the group's stream positions [pos_lo, pos_hi) -- pos_lo a multiple of 8, a dword boundary of the streams -- and the
+    // part's windows, counted from pos_lo; a part past a short last group has none and leaves zeros
+    const int pos_lo = grp * p.Pg, pos_hi = min(p.P, pos_lo + p.Pg);
+    const int windows = (pos_hi - pos_lo + 31) >> 5;
+    const int w_lo = sub_i * plan.wpp, w_hi = min(windows, w_lo + plan.wpp);
+    const int my_n = w_hi - w_lo > wv ? (w_hi - w_lo - wv + MW - 1) / MW : 0;  // this wave's windows: w_lo + wv + i * MW
+    if (WALK && grp > g_lo) __syncthreads();             // every wave is done with the tables of the group before
 
-  if (p.Q) {                                             // the outlier tile times the activations: a thread per (row, four tokens)
-    const unsigned *wt = reinterpret_cast<const unsigned *>(o_tile), *xt = reinterpret_cast<const unsigned *>(o_x);
-    const int ntg = (plan.batch + 3) >> 2;
-    for (int i = (int)threadIdx.x; i < o_rows * ntg; i += MW * 64) {
-      const int tg = i / o_rows, r = i - tg * o_rows;
-      float a[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-      for (int c2 = 0; c2 < plan.o_pitch; ++c2) {
-        const unsigned wd = wt[r * plan.o_pitch + c2];
+    // ---- tables into LDS: 16-byte entries, zero past k (an index past k, or read beyond a stream's end, meets zeros or a
+    // finite entry and a zero activation).  All their loads are asked for here, at once; they are stored after everything
+    // else of the start-up has been asked for as well (a loop of load-and-store rounds costs a trip to L2 per round).
+    // (The thread id is made opaque in every round, or the table addresses derived from it would stay in registers
+    // through the main loop for the next group.)
+    unsigned tid = threadIdx.x;
+    if (WALK) asm volatile("" : "+v"(tid));
+    TableStage<RES_BITS, MW * 64> tables{};
+    tables.issue(p, grp, false, tid);
+    if (grp == g_lo && p.Q) {
+      {
+        const __amdgpu_buffer_rsrc_t r_oidx = make_rsrc(p.idx_out, (unsigned)p.S_out * (unsigned)p.stride_out);
+        const __amdgpu_buffer_rsrc_t r_ocb = make_rsrc(p.cb_out, (unsigned)(p.k_out * p.v_out) * 2u);
+        constexpr int OU = 4;                                // entries a thread has in flight
+        const int total = o_rows * Q2;
+        for (int e0 = (int)threadIdx.x; e0 < total; e0 += MW * 64 * OU) {
+          unsigned w0[OU], w1[OU], sh[OU], jo[OU];
+          bool ok[OU];
 #pragma unroll
-        for (int tt = 0; tt < 4; ++tt) a[tt] = dot2(wd, xt[(tg * 4 + tt) * plan.o_pitch + c2], a[tt]);
-      }
+          for (int uu = 0; uu < OU; ++uu) {
+            const int e = e0 + uu * MW * 64, r = e / Q2, c = e - r * Q2;
+            ok[uu] = e < total && c < p.Q;
+            const int o = o_row_lo + (ok[uu] ? r : 0), sq = o / p.v_out;
+            const unsigned bit = (unsigned)(ok[uu] ? c : 0) * (unsigned)p.bits_out;
+            const unsigned woff = (unsigned)sq * (unsigned)p.stride_out + (bit >> 5) * 4u;
+            jo[uu] = (unsigned)(o - sq * p.v_out); sh[uu] = bit & 31u;
+            w0[uu] = __builtin_amdgcn_raw_buffer_load_b32(r_oidx, woff, 0, 0);
+            w1[uu] = __builtin_amdgcn_raw_buffer_load_b32(r_oidx, woff + 4u, 0, 0);
+          }
 #pragma unroll
-      for (int tt = 0; tt < 4; ++tt) {
-        const int t = tg * 4 + tt;
-        if (t < plan.batch) {
-          if (plan.part) plan.part[((long long)plan.ksplit * plan.batch + t) * p.out_features + o_row_lo + r] = a[tt];
-          else o_sum[t * OROWS + r] = a[tt];
-        }
-      }
-    }
-    if ((int)threadIdx.x < plan.batch) {                 // activation sums over the outlier columns
-      float sx = 0.0f;
-      for (int c2 = 0; c2 < plan.o_pitch; ++c2) sx += half_pair_sum(xt[(int)threadIdx.x * plan.o_pitch + c2]);
-      if (!plan.part) o_xs[threadIdx.x] = sx;
-      else if (blockIdx.x == 0) plan.part_xs[plan.ksplit * 16 + (int)threadIdx.x] = sx;
-    }
-  }
-
-  for (int k0 = 0; k0 < my_n; k0 += DEPTH) {
-#pragma unroll
-    for (int d = 0; d < DEPTH; ++d) {
-      const int k = k0 + d;
-      if (k < my_n) {
-        const int w = w_lo + wv + k * MW;
-        const Window<3> cm = win[d];
-        const Window<NR> cr = wres[d];
-        uint4v xv[NTP];
-#pragma unroll
-        for (int tp = 0; tp < NTP; ++tp) xv[tp] = xr[d][tp];
-        load_unit(win[d], wres[d], xr[d]);               // refill the slot; the copies above are what this window uses
-        uint4v e[VPL], f[RES_BITS ? VPL : 1];
-#pragma unroll
-        for (int u = 0; u < VPL; ++u) lds_gather16<LY::MAIN_OFF>(e[u], field_addr<12, LY::MAIN_SH>(cm, u));
-        if (RES_BITS) {
-#pragma unroll
-          for (int u = 0; u < VPL; ++u) lds_gather16<LY::RES_OFF>(f[u], field_addr<RB, LY::RES_SH>(cr, u) + LY::RES_ADD);
-        }
-        if (w == windows - 1) {                          // the window that holds the end of the stream or of the group: zero what lies past it
-          const int left = pos_hi - pos_lo - (w * 32 + g * 8);               // of this lane's eight positions
-#pragma unroll
-          for (int tp = 0; tp < NTP; ++tp) {
-            unsigned xd[4] = {xv[tp].x, xv[tp].y, xv[tp].z, xv[tp].w};
-#pragma unroll
-            for (int q = 0; q < 4; ++q) xd[q] = left >= 2 * q + 2 ? xd[q] : left == 2 * q + 1 ? xd[q] & 0xFFFFu : 0u;
-            xv[tp].x = xd[0]; xv[tp].y = xd[1]; xv[tp].z = xd[2]; xv[tp].w = xd[3];
+          for (int uu = 0; uu < OU; ++uu) {
+            const unsigned i = min(__builtin_amdgcn_alignbit(w1[uu], w0[uu], sh[uu]) & ((1u << p.bits_out) - 1u), (unsigned)p.k_out - 1u);
+            const unsigned short wh = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r_ocb, (i * (unsigned)p.v_out + jo[uu]) * 2u, 0, 0);
+            const int e = e0 + uu * MW * 64;
+            if (e < total) o_tile[e] = ok[uu] ? wh : (unsigned short)0;
           }
         }
-        if (need_xs) {
-#pragma unroll
-          for (int tp = 0; tp < NTP; ++tp)
-            xs[tp] = dot2(xv[tp].x, 0x3C003C00u, dot2(xv[tp].y, 0x3C003C00u, dot2(xv[tp].z, 0x3C003C00u, dot2(xv[tp].w, 0x3C003C00u, xs[tp]))));
+        for (int e = (int)threadIdx.x; e < 16 * Q2; e += MW * 64) {
+          const int t = e / Q2, c = e - t * Q2;
+          o_x[e] = t < plan.batch && c < p.Q ? __half_as_ushort(x[(long long)t * ldx + c]) : (unsigned short)0;
         }
-        lds_gather_wait();
+      }
+
+    }
+
+    // byte offset of this lane's first activation of window 0, per token pair; a token past the batch (and the idle columns)
+    // reads out of range, i.e. zeros
+    const int col0 = p.n_out + pos_lo;                     // column of x that meets the part's window 0
+    unsigned xoff[NTP];
 #pragma unroll
-        for (int u = 0; u < VPL; ++u) { settle(e[u]); if (RES_BITS) settle(f[u]); }
+    for (int tp = 0; tp < NTP; ++tp) {
+      const int t = 2 * tp + tl;
+      xoff[tp] = col_on && t < plan.batch ? (unsigned)(((long long)t * ldx + col0 + 8 * g) * 2) : 0x80000000u;
+    }
+
+    // a stream past the last one reads out of range: index 0, whose products land in rows that are never stored
+    const unsigned srow_main = (unsigned)(blk * 16 + n) * st_main + (unsigned)(pos_lo >> 3) * 12u;
+    const unsigned srow_res = (unsigned)(blk * 16 + n) * st_res + (unsigned)(pos_lo >> 3) * (unsigned)RB;
+
+    // The loaders run DEPTH windows ahead of the consumer.  A slot's index words are refilled as soon as the gather
+    // addresses have been formed from them; so are its activations, from a copy, except with 16 tokens, where the copy
+    // would not fit the registers and the refill waits for the window's last product.
+    int lw = w_lo + wv, lwx = w_lo + wv;
+    auto load_idx = [&](Window<3> &wm, Window<NR> &wr) {
+      const unsigned wq = (unsigned)(lw < w_hi ? lw : w_lo);                   // past the end: any window in range, never used
+      lw += MW;
+      load_window(wm, r_main, srow_main + (wq * 4u + (unsigned)g) * 12u, 0u);
+      if (RES_BITS == 12) load_window(wr, r_res, srow_res + (wq * 4u + (unsigned)g) * 12u, 0u);
+      if (RES_BITS == 8) load_window(wr, r_res, srow_res + (wq * 4u + (unsigned)g) * 8u, 0u);
+    };
+    auto load_x = [&](uint4v (&xx)[NTP]) {
+      const unsigned wq = (unsigned)(lwx < w_hi ? lwx : w_lo);
+      lwx += MW;
 #pragma unroll
-        for (int u = 0; u < VPL; ++u) {
+      for (int tp = 0; tp < NTP; ++tp) xx[tp] = __builtin_amdgcn_raw_buffer_load_b128(r_x, xoff[tp] + wq * 64u, 0, 0);
+    };
+
+    Window<3> win[DEPTH];
+    Window<NR> wres[DEPTH];
+    uint4v xr[DEPTH][NTP];
 #pragma unroll
-          for (int tp = 0; tp < NTP; ++tp) {
-            const unsigned xd = (u >> 1) == 0 ? xv[tp].x : (u >> 1) == 1 ? xv[tp].y : (u >> 1) == 2 ? xv[tp].z : xv[tp].w;
-            uint4v b;
-            b.x = __builtin_amdgcn_perm(xd, xd, sel[0][u & 1]);
-            b.y = __builtin_amdgcn_perm(xd, xd, sel[1][u & 1]);
-            b.z = __builtin_amdgcn_perm(xd, xd, sel[2][u & 1]);
-            b.w = 0u;
-            acc[tp] = mfma16(e[u], b, acc[tp]);
-            if (RES_BITS) acc[tp] = mfma16(f[u], b, acc[tp]);
+    for (int d = 0; d < DEPTH; ++d) { load_idx(win[d], wres[d]); load_x(xr[d]); }
+    // the table loads are older than the ring's (loads return in order): at most the ring's may still be on their way
+    wait_vmem_at_most<DEPTH * (1 + (RES_BITS ? 1 : 0) + NTP)>();
+    tables.store(p, lds, 0u, false, tid);
+    __syncthreads();                                     // the tables are in
+
+    if (grp == g_lo && p.Q) {
+      {                                                  // the outlier tile times the activations: a thread per (row, four tokens)
+        const unsigned *wt = reinterpret_cast<const unsigned *>(o_tile), *xt = reinterpret_cast<const unsigned *>(o_x);
+        const int ntg = (plan.batch + 3) >> 2;
+        for (int i = (int)threadIdx.x; i < o_rows * ntg; i += MW * 64) {
+          const int tg = i / o_rows, r = i - tg * o_rows;
+          float a[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+          for (int c2 = 0; c2 < plan.o_pitch; ++c2) {
+            const unsigned wd = wt[r * plan.o_pitch + c2];
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt) a[tt] = dot2(wd, xt[(tg * 4 + tt) * plan.o_pitch + c2], a[tt]);
           }
+#pragma unroll
+          for (int tt = 0; tt < 4; ++tt) {
+            const int t = tg * 4 + tt;
+            if (t < plan.batch) {
+              if (plan.part) plan.part[((long long)plan.ksplit * plan.batch + t) * p.out_features + o_row_lo + r] = a[tt];
+              else o_sum[t * OROWS + r] = a[tt];
+            }
+          }
+        }
+        if ((int)threadIdx.x < plan.batch) {                 // activation sums over the outlier columns
+          float sx = 0.0f;
+          for (int c2 = 0; c2 < plan.o_pitch; ++c2) sx += half_pair_sum(xt[(int)threadIdx.x * plan.o_pitch + c2]);
+          if (!plan.part) o_xs[threadIdx.x] = sx;
+          else if (blockIdx.x == 0) plan.part_xs[plan.ksplit * 16 + (int)threadIdx.x] = sx;
+        }
+      }
+
+    }
+
+    for (int k0 = 0; k0 < my_n; k0 += DEPTH) {
+#pragma unroll
+      for (int d = 0; d < DEPTH; ++d) {
+        const int k = k0 + d;
+        if (k < my_n) {
+          const int w = w_lo + wv + k * MW;
+          const Window<3> cm = win[d];
+          const Window<NR> cr = wres[d];
+          uint4v xv[NTP];
+#pragma unroll
+          for (int tp = 0; tp < NTP; ++tp) xv[tp] = xr[d][tp];
+          load_idx(win[d], wres[d]);                     // refill the slot; the copies above are what this window uses
+          if (!LATE_X) load_x(xr[d]);
+          uint4v e[VPL], f[RES_BITS ? VPL : 1];
+#pragma unroll
+          for (int u = 0; u < VPL; ++u) lds_gather16<LY::MAIN_OFF>(e[u], field_addr<12, LY::MAIN_SH>(cm, u));
+          if (RES_BITS) {
+#pragma unroll
+            for (int u = 0; u < VPL; ++u) lds_gather16<LY::RES_OFF>(f[u], field_addr<RB, LY::RES_SH>(cr, u) + LY::RES_ADD);
+          }
+          if (w == windows - 1) {                          // the window that holds the end of the stream or of the group: zero what lies past it
+            const int left = pos_hi - pos_lo - (w * 32 + g * 8);               // of this lane's eight positions
+#pragma unroll
+            for (int tp = 0; tp < NTP; ++tp) {
+              unsigned xd[4] = {xv[tp].x, xv[tp].y, xv[tp].z, xv[tp].w};
+#pragma unroll
+              for (int q = 0; q < 4; ++q) xd[q] = left >= 2 * q + 2 ? xd[q] : left == 2 * q + 1 ? xd[q] & 0xFFFFu : 0u;
+              xv[tp].x = xd[0]; xv[tp].y = xd[1]; xv[tp].z = xd[2]; xv[tp].w = xd[3];
+            }
+          }
+          if (need_xs) {
+#pragma unroll
+            for (int tp = 0; tp < NTP; ++tp)
+              xs[tp] = dot2(xv[tp].x, 0x3C003C00u, dot2(xv[tp].y, 0x3C003C00u, dot2(xv[tp].z, 0x3C003C00u, dot2(xv[tp].w, 0x3C003C00u, xs[tp]))));
+          }
+          lds_gather_wait();
+#pragma unroll
+          for (int u = 0; u < VPL; ++u) { settle(e[u]); if (RES_BITS) settle(f[u]); }
+#pragma unroll
+          for (int u = 0; u < VPL; ++u) {
+#pragma unroll
+            for (int tp = 0; tp < NTP; ++tp) {
+              const unsigned xd = (u >> 1) == 0 ? xv[tp].x : (u >> 1) == 1 ? xv[tp].y : (u >> 1) == 2 ? xv[tp].z : xv[tp].w;
+              uint4v b;
+              b.x = __builtin_amdgcn_perm(xd, xd, sel[0][u & 1]);
+              b.y = __builtin_amdgcn_perm(xd, xd, sel[1][u & 1]);
+              b.z = __builtin_amdgcn_perm(xd, xd, sel[2][u & 1]);
+              b.w = 0u;
+              acc[tp] = mfma16(e[u], b, acc[tp]);
+              if (RES_BITS) acc[tp] = mfma16(f[u], b, acc[tp]);
+            }
+          }
+          if (LATE_X) load_x(xr[d]);
         }
       }
     }
+
   }
 
   // ---- the waves meet: sums per token pair, 1 KB per wave and pair, in the space of the tables
@@ -325,11 +354,11 @@ int cu_count() {
   return g_cus_dm;
 }
 
-template <int RES_BITS, int NTP>
+template <int RES_BITS, int NTP, bool WALK>
 int launch_one(const Params &p, DownMfmaPlan &plan, unsigned grid, const __half *x, long long ldx, __half *y, long long ldy,
                hipStream_t s) {
   static bool configured = false;
-  auto kernel = gemv_down_mfma_kernel<RES_BITS, NTP>;
+  auto kernel = gemv_down_mfma_kernel<RES_BITS, NTP, WALK>;
   if (!configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
       return VQ_ERR_HIP;
@@ -374,17 +403,16 @@ static int parts_per_group(const Params &p) {
 }
 int gemv_down_mfma_parts(const Params &p) { return p.n_groups * parts_per_group(p); }
 
-// part == nullptr: one launch that stores y.  Else parts = gemv_down_mfma_parts(p) > 1 and the sums go to
+// part == nullptr: one launch that stores y (a layer with codebook groups: every workgroup walks all of them).  Else parts = gemv_down_mfma_parts(p) > 1 and the sums go to
 // part[parts][batch][out_features], part_xs[parts * 16]; the caller adds them up.
 int launch_gemv_down_mfma(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s,
                           float *part, float *part_xs, int parts) {
   DownMfmaPlan plan{};
   const int blocks = (p.S + 15) / 16, windows = (min(p.P, p.Pg) + 31) / 32;                // windows of the widest group
   if (blocks < 1 || windows < 1) return VQ_ERR_UNSUPPORTED;
-  if (!part && p.n_groups > 1) return VQ_ERR_UNSUPPORTED;                   // groups meet in the workspace only
   plan.ksplit = part ? parts : 1;
-  if (plan.ksplit % p.n_groups) return VQ_ERR_UNSUPPORTED;
-  plan.sub = plan.ksplit / p.n_groups;
+  if (part && plan.ksplit % p.n_groups) return VQ_ERR_UNSUPPORTED;
+  plan.sub = part ? plan.ksplit / p.n_groups : 1;      // without a workspace: one workgroup per block walks all groups and all windows
   plan.wpp = (windows + plan.sub - 1) / plan.sub;
   plan.batch = batch;
   plan.x_bytes = (unsigned)(((long long)(batch - 1) * ldx + p.in_features) * 2);
@@ -395,7 +423,9 @@ int launch_gemv_down_mfma(const Params &p, const __half *x, long long ldx, int b
   if (grid > 0x7FFFFFFFLL) return VQ_ERR_UNSUPPORTED;
   const int rb = p.k_res ? p.bits_res : 0;
   const int ntp = (batch + 1) / 2;
-#define VQ_CASE(R, N, LO) if (rb == R && ntp > LO && ntp <= N) return launch_one<R, N>(p, plan, (unsigned)grid, x, ldx, y, ldy, s);
+  const bool walk = !part && p.n_groups > 1;
+#define VQ_CASE(R, N, LO) if (rb == R && ntp > LO && ntp <= N) \
+    return walk ? launch_one<R, N, true>(p, plan, (unsigned)grid, x, ldx, y, ldy, s) : launch_one<R, N, false>(p, plan, (unsigned)grid, x, ldx, y, ldy, s);
   VQ_CASE(0, 1, 0) VQ_CASE(0, 2, 1) VQ_CASE(0, 4, 2) VQ_CASE(0, 8, 4)
   VQ_CASE(8, 1, 0) VQ_CASE(8, 2, 1) VQ_CASE(8, 4, 2) VQ_CASE(8, 8, 4)
   VQ_CASE(12, 1, 0) VQ_CASE(12, 2, 1) VQ_CASE(12, 4, 2) VQ_CASE(12, 8, 4)
