@@ -135,7 +135,7 @@ int vq_gemv_with_workspace(const vq_layer_desc *desc, const void *x, int64_t ldx
  * descs: host array of n_layers descriptor pointers, all with the same in_features; y, ldy: host arrays of
  * n_layers device pointers / leading dimensions (ldy[i] >= out_features of layer i); the outputs must not overlap
  * each other or x.  n_layers in [1, 8].  Layers that the fused kernel does not take together (different residual
- * kinds, codebook groups, shapes outside the fast kernels) are launched one after the other on the same stream:
+ * kinds, codebook groups, both orientations, shapes outside the fast kernels) are launched one after the other on the same stream:
  * the results are the same.  Errors as for vq_gemv; nothing is launched when any argument is rejected.       */
 int vq_gemv_multi(const vq_layer_desc *const *descs, int32_t n_layers, const void *x, int64_t ldx, int32_t batch,
                   void *const *y, const int64_t *ldy, void *hip_stream);

@@ -258,6 +258,8 @@ int launch_gemv_ws(const Params &p, const __half *x, long long ldx, int batch, _
 int launch_gemv_mfma_multi(const Params *ps, int n, const __half *x, long long ldx, int batch, __half *const *ys,
                            const long long *ldys, hipStream_t s);
 int launch_gemv_fast_multi(const Params *ps, int n, const __half *x, __half *const *ys, hipStream_t s);
+int launch_gemv_down_mfma_multi(const Params *ps, int n, const __half *x, long long ldx, int batch, __half *const *ys,
+                                const long long *ldys, hipStream_t s);
 
 // Several layers on the same activations: one launch of the dot-product kernel (one row) or of the matrix-core kernel
 // (more rows; VQ_GEMV_KERNEL=m: always) when all of them take it together, else (and with VQ_GEMV_MULTI=0, for measurement and tests) one vq_gemv after the other.
@@ -265,6 +267,14 @@ int launch_gemv_multi(const Params *ps, int n, const __half *x, long long ldx, i
                       hipStream_t s) {
   const char *env = getenv("VQ_GEMV_MULTI");
   bool fused = n >= 2 && !(env && env[0] == '0') && forced_kernel() != 'g' && forced_kernel() != 'd';
+  // layers with vectors down the output dimension: the matrix-core kernel of that orientation, any batch (a block of 16
+  // streams per workgroup over all columns; the blocks of all the layers together are what fills the chip)
+  bool down = fused;
+  for (int i = 0; down && i < n; ++i) down = ps[i].orientation == 1 && ps[i].n_groups == 1 && down_mfma_wanted(ps[i], x, ldx, batch);
+  if (down) {
+    const int rc = launch_gemv_down_mfma_multi(ps, n, x, ldx, batch, ys, ldys, s);
+    if (rc != VQ_ERR_UNSUPPORTED) return rc;
+  }
   for (int i = 0; fused && i < n; ++i) fused = gemv_fast_applicable(ps[i], x, ldx);
   if (fused && batch == 1 && forced_kernel() != 'm') {     // a single row: the dot-product kernel is the faster body
     const int rc = launch_gemv_fast_multi(ps, n, x, ys, s);

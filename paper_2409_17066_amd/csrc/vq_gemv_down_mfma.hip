@@ -61,9 +61,10 @@ __device__ __forceinline__ float4v mfma16(uint4v a, uint4v b, float4v c) {
 // WALK: the instantiation for layers with codebook groups and no workspace, whose workgroups walk all groups; the others
 // take one group (or the only one) and have no loop around the start-up (with the loop in every instantiation the
 // single-group ones lost up to 4 us on a 4096 x 4096 layer in 16 groups: registers held across the loop edge).
+// `wg` is the workgroup's number within its layer (a launch may hold the workgroups of several layers).
 template <int RES_BITS, int NTP, bool WALK>
-__global__ __launch_bounds__(MW * 64) void gemv_down_mfma_kernel(Params p, DownMfmaPlan plan, const __half *__restrict__ x, long long ldx,
-                                                                 __half *__restrict__ y, long long ldy) {
+__device__ __forceinline__ void gemv_down_mfma_body(const Params &p, const DownMfmaPlan &plan, const __half *__restrict__ x, long long ldx,
+                                                    __half *__restrict__ y, long long ldy, int wg) {
   typedef Layout<RES_BITS> LY;
   constexpr int RB = RES_BITS ? RES_BITS : 8;
   constexpr int NR = RES_BITS == 12 ? 3 : 2;             // dwords of a lane's residual indices
@@ -73,7 +74,7 @@ __global__ __launch_bounds__(MW * 64) void gemv_down_mfma_kernel(Params p, DownM
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = lane & 15, g = lane >> 4;                // A: stream n of the block, column group g.  B and D: column n = (token, j)
-  const int blk = (int)blockIdx.x / plan.ksplit, part_i = (int)blockIdx.x - blk * plan.ksplit;
+  const int blk = wg / plan.ksplit, part_i = wg - blk * plan.ksplit;
   // A part belongs to one codebook group; without a workspace the workgroup walks all groups, one set of tables after the
   // other in LDS, and its sums simply keep running (the tables change with the column, the output rows do not).
   const int g_lo = plan.part ? part_i / plan.sub : 0, g_hi = WALK ? p.n_groups : g_lo + 1;
@@ -85,7 +86,7 @@ __global__ __launch_bounds__(MW * 64) void gemv_down_mfma_kernel(Params p, DownM
   // index streams, one to the table, for all of them at once -- and multiplied from there once the barrier below has passed.
   // Without a workspace the rows are the block's own and their sums wait in LDS for the end; with one, the outlier columns
   // are one more part of the workspace and every workgroup of the launch takes a share of ALL rows.
-  const int o_row_lo = plan.part ? (int)blockIdx.x * plan.o_rpw : blk * OROWS;
+  const int o_row_lo = plan.part ? wg * plan.o_rpw : blk * OROWS;
   const int o_rows = p.Q ? max(0, min(plan.part ? plan.o_rpw : OROWS, p.out_features - o_row_lo)) : 0;
   const int Q2 = 2 * plan.o_pitch;                       // halves per tile row
   unsigned short *o_tile = reinterpret_cast<unsigned short *>(lds + plan.lds_o);
@@ -233,7 +234,7 @@ __global__ __launch_bounds__(MW * 64) void gemv_down_mfma_kernel(Params p, DownM
           float sx = 0.0f;
           for (int c2 = 0; c2 < plan.o_pitch; ++c2) sx += half_pair_sum(xt[(int)threadIdx.x * plan.o_pitch + c2]);
           if (!plan.part) o_xs[threadIdx.x] = sx;
-          else if (blockIdx.x == 0) plan.part_xs[plan.ksplit * 16 + (int)threadIdx.x] = sx;
+          else if (wg == 0) plan.part_xs[plan.ksplit * 16 + (int)threadIdx.x] = sx;
         }
       }
 
@@ -344,6 +345,36 @@ __global__ __launch_bounds__(MW * 64) void gemv_down_mfma_kernel(Params p, DownM
   }
 }
 
+template <int RES_BITS, int NTP, bool WALK>
+__global__ __launch_bounds__(MW * 64) void gemv_down_mfma_kernel(Params p, DownMfmaPlan plan, const __half *__restrict__ x, long long ldx,
+                                                                 __half *__restrict__ y, long long ldy) {
+  gemv_down_mfma_body<RES_BITS, NTP, WALK>(p, plan, x, ldx, y, ldy, (int)blockIdx.x);
+}
+
+// Several layers that read the same activations (the query, key and value projections of a decoder layer; its gate and up
+// projections) in one launch: every workgroup belongs to one layer and runs the body above on one of its blocks of 16
+// streams, over all columns.  This is where the coarse blocks stop hurting without a workspace: the blocks of all the
+// layers are in flight together (three 4096 x 4096 layers: 129 workgroups instead of three times 43).
+constexpr int DMULTI_MAX = 8;
+struct DownMultiLayer {
+  Params p;
+  DownMfmaPlan plan;
+  __half *y;
+  long long ldy;
+};
+struct DownMultiArgs {
+  int n;
+  int first_wg[DMULTI_MAX + 1];                          // layer i owns workgroups [first_wg[i], first_wg[i + 1])
+  DownMultiLayer layer[DMULTI_MAX];
+};
+
+template <int RES_BITS, int NTP>
+__global__ __launch_bounds__(MW * 64) void gemv_down_mfma_multi_kernel(DownMultiArgs a, const __half *__restrict__ x, long long ldx) {
+  int i = 0;
+  while (i + 1 < a.n && (int)blockIdx.x >= a.first_wg[i + 1]) ++i;
+  gemv_down_mfma_body<RES_BITS, NTP, false>(a.layer[i].p, a.layer[i].plan, x, ldx, a.layer[i].y, a.layer[i].ldy, (int)blockIdx.x - a.first_wg[i]);
+}
+
 int g_cus_dm = 0;
 int cu_count() {
   if (!g_cus_dm) {
@@ -352,6 +383,36 @@ int cu_count() {
     g_cus_dm = n;
   }
   return g_cus_dm;
+}
+
+// LDS of one layer: tables (or the meeting place of the waves, which takes their space at the end), then the outlier tile
+template <int RES_BITS, int NTP>
+unsigned place_lds(const Params &p, DownMfmaPlan &plan) {
+  unsigned lds_bytes = Layout<RES_BITS>::BYTES;
+  const unsigned meet = (unsigned)(NTP * MW) * 1024u + (unsigned)(MW * NTP * 8) * 4u;
+  if (lds_bytes < meet) lds_bytes = meet;
+  plan.lds_o = lds_bytes;
+  if (p.Q) lds_bytes += (unsigned)((OROWS + 16) * plan.o_pitch + 16 * OROWS + 16) * 4u;
+  return lds_bytes;
+}
+
+template <int RES_BITS, int NTP>
+int launch_multi(DownMultiArgs &a, const __half *x, long long ldx, hipStream_t s) {
+  static bool configured = false;
+  auto kernel = gemv_down_mfma_multi_kernel<RES_BITS, NTP>;
+  if (!configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+      return VQ_ERR_HIP;
+    configured = true;
+  }
+  unsigned lds_bytes = 0;
+  for (int i = 0; i < a.n; ++i) {
+    const unsigned b = place_lds<RES_BITS, NTP>(a.layer[i].p, a.layer[i].plan);
+    if (b > lds_bytes) lds_bytes = b;
+  }
+  if (lds_bytes > 160u * 1024u) return VQ_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(kernel, dim3((unsigned)a.first_wg[a.n]), dim3(MW * 64), lds_bytes, s, a, x, ldx);
+  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
 
 template <int RES_BITS, int NTP, bool WALK>
@@ -364,11 +425,7 @@ int launch_one(const Params &p, DownMfmaPlan &plan, unsigned grid, const __half 
       return VQ_ERR_HIP;
     configured = true;
   }
-  unsigned lds_bytes = Layout<RES_BITS>::BYTES;
-  const unsigned meet = (unsigned)(NTP * MW) * 1024u + (unsigned)(MW * NTP * 8) * 4u;
-  if (lds_bytes < meet) lds_bytes = meet;
-  plan.lds_o = lds_bytes;
-  if (p.Q) lds_bytes += (unsigned)((OROWS + 16) * plan.o_pitch + 16 * OROWS + 16) * 4u;
+  const unsigned lds_bytes = place_lds<RES_BITS, NTP>(p, plan);
   if (lds_bytes > 160u * 1024u) return VQ_ERR_UNSUPPORTED;                  // too many outlier columns to hold beside the tables
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(MW * 64), lds_bytes, s, p, plan, x, ldx, y, ldy);
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
@@ -403,11 +460,7 @@ static int parts_per_group(const Params &p) {
 }
 int gemv_down_mfma_parts(const Params &p) { return p.n_groups * parts_per_group(p); }
 
-// part == nullptr: one launch that stores y (a layer with codebook groups: every workgroup walks all of them).  Else parts = gemv_down_mfma_parts(p) > 1 and the sums go to
-// part[parts][batch][out_features], part_xs[parts * 16]; the caller adds them up.
-int launch_gemv_down_mfma(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s,
-                          float *part, float *part_xs, int parts) {
-  DownMfmaPlan plan{};
+static int make_plan(const Params &p, long long ldx, int batch, float *part, float *part_xs, int parts, DownMfmaPlan &plan, long long *grid_out) {
   const int blocks = (p.S + 15) / 16, windows = (min(p.P, p.Pg) + 31) / 32;                // windows of the widest group
   if (blocks < 1 || windows < 1) return VQ_ERR_UNSUPPORTED;
   plan.ksplit = part ? parts : 1;
@@ -421,11 +474,54 @@ int launch_gemv_down_mfma(const Params &p, const __half *x, long long ldx, int b
   plan.o_rpw = (int)((p.out_features + (long long)blocks * plan.ksplit - 1) / ((long long)blocks * plan.ksplit));   // <= 96: a block has 96 rows
   const long long grid = (long long)blocks * plan.ksplit;
   if (grid > 0x7FFFFFFFLL) return VQ_ERR_UNSUPPORTED;
+  *grid_out = grid;
+  return VQ_OK;
+}
+
+// part == nullptr: one launch that stores y (a layer with codebook groups: every workgroup walks all of them).  Else
+// parts = gemv_down_mfma_parts(p) > 1 and the sums go to part[parts][batch][out_features], part_xs[parts * 16]; the caller
+// adds them up.
+int launch_gemv_down_mfma(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s,
+                          float *part, float *part_xs, int parts) {
+  DownMfmaPlan plan{};
+  long long grid = 0;
+  const int rc_plan = make_plan(p, ldx, batch, part, part_xs, parts, plan, &grid);
+  if (rc_plan != VQ_OK) return rc_plan;
   const int rb = p.k_res ? p.bits_res : 0;
   const int ntp = (batch + 1) / 2;
   const bool walk = !part && p.n_groups > 1;
 #define VQ_CASE(R, N, LO) if (rb == R && ntp > LO && ntp <= N) \
     return walk ? launch_one<R, N, true>(p, plan, (unsigned)grid, x, ldx, y, ldy, s) : launch_one<R, N, false>(p, plan, (unsigned)grid, x, ldx, y, ldy, s);
+  VQ_CASE(0, 1, 0) VQ_CASE(0, 2, 1) VQ_CASE(0, 4, 2) VQ_CASE(0, 8, 4)
+  VQ_CASE(8, 1, 0) VQ_CASE(8, 2, 1) VQ_CASE(8, 4, 2) VQ_CASE(8, 8, 4)
+  VQ_CASE(12, 1, 0) VQ_CASE(12, 2, 1) VQ_CASE(12, 4, 2) VQ_CASE(12, 8, 4)
+#undef VQ_CASE
+  return VQ_ERR_UNSUPPORTED;
+}
+
+// n layers (2 .. 8) of one codebook group each on the same activations in one launch, without a workspace.  VQ_ERR_UNSUPPORTED
+// when they do not fit one kernel instantiation (different residual kinds, different in_features); the caller then launches
+// them one by one.  The caller has checked gemv_down_mfma_applicable() for each.
+int launch_gemv_down_mfma_multi(const Params *ps, int n, const __half *x, long long ldx, int batch, __half *const *ys,
+                                const long long *ldys, hipStream_t s) {
+  if (n < 2 || n > DMULTI_MAX) return VQ_ERR_UNSUPPORTED;
+  DownMultiArgs a{};
+  a.n = n;
+  const int rb = ps[0].k_res ? ps[0].bits_res : 0;
+  long long total = 0;
+  for (int i = 0; i < n; ++i) {
+    if (ps[i].in_features != ps[0].in_features || ps[i].n_groups > 1 || (ps[i].k_res ? ps[i].bits_res : 0) != rb) return VQ_ERR_UNSUPPORTED;
+    long long grid = 0;
+    const int rc = make_plan(ps[i], ldx, batch, nullptr, nullptr, 1, a.layer[i].plan, &grid);
+    if (rc != VQ_OK) return rc;
+    a.layer[i].p = ps[i]; a.layer[i].y = ys[i]; a.layer[i].ldy = ldys[i];
+    a.first_wg[i] = (int)total;
+    total += grid;
+    if (total > 0x7FFFFFFFLL) return VQ_ERR_UNSUPPORTED;
+  }
+  a.first_wg[n] = (int)total;
+  const int ntp = (batch + 1) / 2;
+#define VQ_CASE(R, N, LO) if (rb == R && ntp > LO && ntp <= N) return launch_multi<R, N>(a, x, ldx, s);
   VQ_CASE(0, 1, 0) VQ_CASE(0, 2, 1) VQ_CASE(0, 4, 2) VQ_CASE(0, 8, 4)
   VQ_CASE(8, 1, 0) VQ_CASE(8, 2, 1) VQ_CASE(8, 4, 2) VQ_CASE(8, 8, 4)
   VQ_CASE(12, 1, 0) VQ_CASE(12, 2, 1) VQ_CASE(12, 4, 2) VQ_CASE(12, 8, 4)

@@ -100,6 +100,18 @@ MULTI = {
     "with_groups": [dict(out_features=70, in_features=1000, v=6, k=4096, group_vectors=64), dict(out_features=33, in_features=1000, v=6, k=4096)],
     "generic_shapes": [dict(out_features=200, in_features=520, v=8, k=65536), dict(out_features=37, in_features=520, v=5, k=37, k_res=11)],
     "single": [dict(out_features=261, in_features=1030, v=6, k=4096)],
+    # layers with vectors down the output dimension: one launch of that orientation's matrix-core kernel for any batch
+    "down_qkv": [dict(out_features=261, in_features=1032, v=6, k=4096, orientation=1), dict(out_features=70, in_features=1032, v=6, k=4096, orientation=1),
+                 dict(out_features=133, in_features=1032, v=6, k=3000, orientation=1)],
+    "down_gate_up_res12_outlier": [dict(out_features=133, in_features=1208, v=6, k=4096, k_res=4096, orientation=1),
+                                   dict(out_features=1150, in_features=1208, v=6, k=4096, k_res=4096, n_outlier_cols=24, v_out=4, k_out=4096,
+                                        with_bias=False, orientation=1)],
+    "down_res8_many_streams": [dict(out_features=20501, in_features=200, v=6, k=4096, k_res=256, orientation=1),
+                               dict(out_features=5, in_features=200, v=6, k=4096, k_res=256, orientation=1)],
+    # ... and sets that run one after the other: both orientations, codebook groups
+    "down_and_rowwise": [dict(out_features=70, in_features=1000, v=6, k=4096, orientation=1), dict(out_features=70, in_features=1000, v=6, k=4096)],
+    "down_with_groups": [dict(out_features=70, in_features=1000, v=6, k=4096, group_vectors=64, orientation=1),
+                         dict(out_features=33, in_features=1000, v=6, k=4096, orientation=1)],
 }
 
 

@@ -134,6 +134,7 @@ def test_non_default_stream(gpu_lib):
 
 
 FUSED_SETS = ("qkv_v6", "gate_up_res12", "res8_outlier_pair", "many_rows", "eight_layers")
+DOWN_FUSED_SETS = ("down_qkv", "down_gate_up_res12_outlier", "down_res8_many_streams")      # orientation 1: the same body for every batch
 
 
 @pytest.mark.parametrize("name", list(MULTI))
@@ -157,7 +158,7 @@ def test_gemv_multi(gpu_lib, monkeypatch, name, batch):
         assert (o[:, L.out_features:] == -7.0).all()
         alone = gpu_lib.gemv(dl, x)
         torch.cuda.synchronize()
-        if name in FUSED_SETS and batch > 1:       # one row runs the dot-product body, whose split (and so its summation
+        if (name in FUSED_SETS and batch > 1) or name in DOWN_FUSED_SETS:       # one row runs the dot-product body, whose split (and so its summation
             assert torch.equal(alone, y), L.name   # order) depends on the rows per workgroup; the others go one by one
 
 
