@@ -365,6 +365,39 @@ def detail(vq, s, np, torch, use_graph, skip):
                         "cfg": "1 with vectors down the output dimension (orientation 1)", "batch": batch,
                         "us": round(sec * 1e6, 3), "GB/s": round(alg / sec / 1e9, 1), "frac_hbm_peak": round(alg / sec / 1e9 / HBM_PEAK_GBPS, 4)})
     del Ld
+    # the cfg2 decoder layer stored in that orientation, as a chain on one stream: 4 launches (q+k+v and gate+up through
+    # vq_gemv_multi) against 7
+    c2 = s.CONFIGS[2]
+    layers_d = {name: s.make_layer(2, name, out_f, in_f, c2["v"], c2["k"], c2.get("k_res", 0), layer_ordinal=i, orientation=1)
+                for i, (name, out_f, in_f) in enumerate(c2["layers"])}
+    rots_d = {n: Rotation(vq, L, min_bytes=ROTATE_BYTES // 4) for n, L in layers_d.items()}
+    for batch in (1, 16):
+        xs = {n: torch.from_numpy(s.make_activations(2, layers_d[n], batch)).cuda() for n in ("q", "o", "gate", "down")}
+        ys = {n: torch.empty((batch, L.out_features), dtype=torch.float16, device="cuda") for n, L in layers_d.items()}
+        alg = sum(L.algorithmic_bytes(batch) for L in layers_d.values())
+        # single layers get a workspace on loan (column parts on the matrix cores; none is asked for at batch 1)
+        need_d = {n: vq.vq_gemv_workspace_bytes(rots_d[n].descs[0], batch) for n in layers_d}
+        ws_d = torch.empty(max(max(need_d.values()), 256), dtype=torch.uint8, device="cuda")
+        for fused in (True, False):
+            def chain_d(i):
+                st = torch.cuda.current_stream().cuda_stream
+                for group in ((("q", "k", "v"), ("o",), ("gate", "up"), ("down",)) if fused else tuple((n,) for n in layers_d)):
+                    x = xs[{"k": "q", "v": "q", "up": "gate"}.get(group[0], group[0])]
+                    descs = [rots_d[n].descs[i % rots_d[n].copies] for n in group]
+                    if len(group) == 1:
+                        n = group[0]
+                        rc = vq.vq_gemv_with_workspace(descs[0], x.data_ptr(), x.stride(0), batch, ys[n].data_ptr(), ys[n].stride(0),
+                                                       ws_d.data_ptr(), need_d[n], st)
+                    else:
+                        rc = vq.vq_gemv_multi(descs, x.data_ptr(), x.stride(0), batch, [ys[n].data_ptr() for n in group],
+                                              [ys[n].stride(0) for n in group], st)
+                    if rc != 0:
+                        raise vq.VQError(rc, "vq_gemv_multi")
+            wall, ev = timed(chain_d, 100, 10, use_graph)
+            us = ev / 100 * 1e6
+            out.append({"op": "cfg2 decoder layer in orientation 1 as a chain of %d launches (single layers with a workspace)" % (4 if fused else 7), "cfg": 2, "batch": batch,
+                        "us": round(us, 2), "GB/s": round(alg / us / 1e3, 1), "frac_hbm_peak": round(alg / us / 1e3 / HBM_PEAK_GBPS, 4)})
+    del rots_d, xs, ys, layers_d, ws_d
     # codebook groups on the headline shape: "group num" 4 and 16 of the paper's parameter table, as group sizes
     # rounded up to 8 vectors
     for group_vectors in (176, 48):
