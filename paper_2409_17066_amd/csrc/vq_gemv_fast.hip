@@ -140,10 +140,11 @@ __device__ __forceinline__ void gemv_v6_body(const Params &p, const GemvPlan &pl
   Window<NR> wr[DEPTH];
   const int c0 = is_main ? p.n_out + first_vec * 6 : first_vec * 4;
 
-  for (int chunk0 = 0; chunk0 < rows_here; chunk0 += plan.rc) {
-    const int rows_chunk = min(plan.rc, rows_here - chunk0);
-    const int row_end = (is_main || is_out) ? rows_chunk : 0;     // rows start, start+step, ... below row_end are this wave's
-    // ---- put the first DEPTH rows of index windows in flight
+  // the codebook loads go out first: they are hits in L2 (for all but the first workgroups) and, as loads return in order,
+  // can be stored as soon as they are back, while the index rows asked for after them are still on their way from HBM
+  // ---- put the first DEPTH rows of a chunk's index windows in flight
+  auto first_rows = [&](int chunk0) {
+    const int row_end = (is_main || is_out) ? min(plan.rc, rows_here - chunk0) : 0;
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)
       if (start + d * step < row_end) {
@@ -151,6 +152,18 @@ __device__ __forceinline__ void gemv_v6_body(const Params &p, const GemvPlan &pl
         load_window(wm[d], r_main, r * st_main, dw_main);
         if (RES_BITS && is_main) load_window(wr[d], r_res, r * st_res, dw_res);
       }
+  };
+  {
+    TableRegs tabs;
+    tables_load<RES_BITS>(tabs, p, plan.Wo != 0);
+    first_rows(0);
+    tables_store<RES_BITS>(tabs, lds, plan, plan.Wo != 0);       // (the barrier that publishes them is the activations', below)
+  }
+
+  for (int chunk0 = 0; chunk0 < rows_here; chunk0 += plan.rc) {
+    const int rows_chunk = min(plan.rc, rows_here - chunk0);
+    const int row_end = (is_main || is_out) ? rows_chunk : 0;     // rows start, start+step, ... below row_end are this wave's
+    if (chunk0 != 0) first_rows(chunk0);
     VQ_STAMP(1);
 
     // scale and bias of the row this thread finishes at the end of the chunk
@@ -161,12 +174,6 @@ __device__ __forceinline__ void gemv_v6_body(const Params &p, const GemvPlan &pl
     const float ep_bias = (ep_on && p.bias) ? __half2float(p.bias[ep_o]) : 0.0f;
 
     if (chunk0 == 0) {
-      // ---- codebooks into LDS
-      {
-        TableRegs tabs;
-        tables_load<RES_BITS>(tabs, p, plan.Wo != 0);
-        tables_store<RES_BITS>(tabs, lds, plan, plan.Wo != 0);
-      }
       VQ_STAMP(2);
       // ---- activations: batch rows are copied into LDS by asynchronous, range-checked 16-byte loads that write
       // LDS directly (zeros past in_features, which is even here, so padded vectors and idle lanes multiply by
