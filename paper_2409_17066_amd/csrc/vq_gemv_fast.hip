@@ -160,6 +160,55 @@ __device__ __forceinline__ void gemv_v6_body(const Params &p, const GemvPlan &pl
     tables_store<RES_BITS>(tabs, lds, plan, plan.Wo != 0);       // (the barrier that publishes them is the activations', below)
   }
 
+  VQ_STAMP(2);
+  // ---- activations: batch rows are copied into LDS by asynchronous, range-checked 16-byte loads that write
+  // LDS directly (zeros past in_features, which is even here, so padded vectors and idle lanes multiply by
+  // zero); wave w copies 1 KB pieces w, w+16, ...  plan.x_regions rows fit at a time (all of them when LDS
+  // allows); each lane then moves its own vectors to registers, where they stay for the whole kernel.
+#pragma unroll
+  for (int b0 = 0; b0 < B; ++b0) {
+    const int region = b0 % plan.x_regions;
+    if (region == 0) {
+      if (b0 != 0) __syncthreads();                       // everyone has read the previous group of rows
+#pragma unroll
+      for (int bb = 0; bb < B; ++bb) {
+        if (bb >= b0 && bb < b0 + plan.x_regions) {
+          const __amdgpu_buffer_rsrc_t rx = make_rsrc(x + bb * ldx, (unsigned)p.in_features * 2u);
+          for (unsigned piece = (unsigned)wv * 1024u; piece < plan.x_bytes; piece += NW * 1024u)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void *)(lds + plan.lds_x + (bb - b0) * plan.x_bytes + piece),
+                                                     16, piece + lane * 16u, 0, 0, 0);
+        }
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the direct-to-LDS copies have landed
+      VQ_STAMP(3);
+      __syncthreads();
+    }
+    const int b = b0;
+    const unsigned char *xl = lds + plan.lds_x + region * plan.x_bytes;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (is_main) {
+#pragma unroll
+        for (int h = 0; h < 3; ++h) xr[b][u][h] = *reinterpret_cast<const unsigned *>(xl + (c0 + u * 6 + h * 2) * 2);
+      } else {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int c = c0 + u * 4 + h * 2;
+          const unsigned v = *reinterpret_cast<const unsigned *>(xl + (is_out ? c : 0) * 2);
+          xr[b][u][h] = (is_out && c < p.n_out) ? v : 0u;      // outlier lanes past the last outlier vector
+        }
+        xr[b][u][2] = 0u;
+      }
+    }
+    float s0 = 0.0f;
+    for (unsigned o = threadIdx.x * 16u; o < plan.x_bytes; o += NW * 64 * 16u) {
+      const uint4v v = *reinterpret_cast<const uint4v *>(xl + o);
+      s0 += half_pair_sum(v.x) + half_pair_sum(v.y) + half_pair_sum(v.z) + half_pair_sum(v.w);
+    }
+    const float s = wave_reduce_to_lane63(s0);
+    if (lane == 63) xsum[b * NW + wv] = s;
+  }
+
   for (int chunk0 = 0; chunk0 < rows_here; chunk0 += plan.rc) {
     const int rows_chunk = min(plan.rc, rows_here - chunk0);
     const int row_end = (is_main || is_out) ? rows_chunk : 0;     // rows start, start+step, ... below row_end are this wave's
@@ -173,56 +222,6 @@ __device__ __forceinline__ void gemv_v6_body(const Params &p, const GemvPlan &pl
     const float ep_scale = (ep_on && p.scale) ? __half2float(p.scale[ep_o]) : 1.0f;
     const float ep_bias = (ep_on && p.bias) ? __half2float(p.bias[ep_o]) : 0.0f;
 
-    if (chunk0 == 0) {
-      VQ_STAMP(2);
-      // ---- activations: batch rows are copied into LDS by asynchronous, range-checked 16-byte loads that write
-      // LDS directly (zeros past in_features, which is even here, so padded vectors and idle lanes multiply by
-      // zero); wave w copies 1 KB pieces w, w+16, ...  plan.x_regions rows fit at a time (all of them when LDS
-      // allows); each lane then moves its own vectors to registers, where they stay for the whole kernel.
-#pragma unroll
-      for (int b0 = 0; b0 < B; ++b0) {
-        const int region = b0 % plan.x_regions;
-        if (region == 0) {
-          if (b0 != 0) __syncthreads();                       // everyone has read the previous group of rows
-#pragma unroll
-          for (int bb = 0; bb < B; ++bb) {
-            if (bb >= b0 && bb < b0 + plan.x_regions) {
-              const __amdgpu_buffer_rsrc_t rx = make_rsrc(x + bb * ldx, (unsigned)p.in_features * 2u);
-              for (unsigned piece = (unsigned)wv * 1024u; piece < plan.x_bytes; piece += NW * 1024u)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void *)(lds + plan.lds_x + (bb - b0) * plan.x_bytes + piece),
-                                                         16, piece + lane * 16u, 0, 0, 0);
-            }
-          }
-          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the direct-to-LDS copies have landed
-          VQ_STAMP(3);
-          __syncthreads();
-        }
-        const int b = b0;
-        const unsigned char *xl = lds + plan.lds_x + region * plan.x_bytes;
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          if (is_main) {
-#pragma unroll
-            for (int h = 0; h < 3; ++h) xr[b][u][h] = *reinterpret_cast<const unsigned *>(xl + (c0 + u * 6 + h * 2) * 2);
-          } else {
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-              const int c = c0 + u * 4 + h * 2;
-              const unsigned v = *reinterpret_cast<const unsigned *>(xl + (is_out ? c : 0) * 2);
-              xr[b][u][h] = (is_out && c < p.n_out) ? v : 0u;      // outlier lanes past the last outlier vector
-            }
-            xr[b][u][2] = 0u;
-          }
-        }
-        float s0 = 0.0f;
-        for (unsigned o = threadIdx.x * 16u; o < plan.x_bytes; o += NW * 64 * 16u) {
-          const uint4v v = *reinterpret_cast<const uint4v *>(xl + o);
-          s0 += half_pair_sum(v.x) + half_pair_sum(v.y) + half_pair_sum(v.z) + half_pair_sum(v.w);
-        }
-        const float s = wave_reduce_to_lane63(s0);
-        if (lane == 63) xsum[b * NW + wv] = s;
-      }
-    }
     VQ_STAMP(4);
 
     for (int rl0 = start; rl0 < row_end; rl0 += DEPTH * step) {
