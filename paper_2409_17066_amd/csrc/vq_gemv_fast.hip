@@ -153,12 +153,21 @@ __device__ __forceinline__ void gemv_v6_body(const Params &p, const GemvPlan &pl
         if (RES_BITS && is_main) load_window(wr[d], r_res, r * st_res, dw_res);
       }
   };
-  {
-    TableRegs tabs;
-    tables_load<RES_BITS>(tabs, p, plan.Wo != 0);
-    first_rows(0);
-    tables_store<RES_BITS>(tabs, lds, plan, plan.Wo != 0);       // (the barrier that publishes them is the activations', below)
-  }
+  // The same for the first chunk, with every load issued whatever the wave's role and rows (a row past the wave's last one
+  // is replaced by the workgroup's last row: the load stays an ordinary one that returns in order): the start-up below
+  // waits for "all but the last FIRST_LOADS loads", which must be exactly these.
+  constexpr int FIRST_LOADS = DEPTH * (RES_BITS ? 2 : 1);
+  static_assert(NM <= 4 && NR <= 4, "one load instruction per window");
+  auto first_rows_all = [&]() {
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+      const unsigned r = (unsigned)min(start + d * step, rows_here - 1);
+      load_window(wm[d], r_main, r * st_main, dw_main);
+      if (RES_BITS) load_window(wr[d], r_res, r * st_res, dw_res);
+    }
+  };
+  TableRegs tabs;
+  tables_load<RES_BITS>(tabs, p, plan.Wo != 0);
 
   VQ_STAMP(2);
   // ---- activations: batch rows are copied into LDS by asynchronous, range-checked 16-byte loads that write
@@ -179,9 +188,21 @@ __device__ __forceinline__ void gemv_v6_body(const Params &p, const GemvPlan &pl
                                                      16, piece + lane * 16u, 0, 0, 0);
         }
       }
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the direct-to-LDS copies have landed
-      VQ_STAMP(3);
-      __syncthreads();
+      if (b0 == 0) {
+        // The first index rows go out behind the codebooks and the first activation rows -- those are hits in L2 -- and
+        // are not waited for here: the rest of the start-up runs while they are on their way from HBM.  (Loads return
+        // in order; the empty statements keep the compiler from moving the index loads across them.)
+        asm volatile("" ::: "memory");
+        first_rows_all();
+        asm volatile("" ::: "memory");
+        tables_store<RES_BITS>(tabs, lds, plan, plan.Wo != 0);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(FIRST_LOADS) : "memory");   // codebooks and direct-to-LDS copies have landed
+        VQ_STAMP(3);
+        lds_barrier();                                   // (a full barrier would wait for the index rows as well)
+      } else {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the direct-to-LDS copies have landed
+        __syncthreads();
+      }
     }
     const int b = b0;
     const unsigned char *xl = lds + plan.lds_x + region * plan.x_bytes;
