@@ -222,10 +222,6 @@ __global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPla
       }
     }
   }
-  wait_vmem_at_most<0>();
-  tables.store(p, lds, 0u, false);
-  __syncthreads();
-
   const unsigned st_main = (unsigned)p.stride, st_res = (unsigned)p.stride_res;
   const __amdgpu_buffer_rsrc_t r_main = make_rsrc(p.idx, idx_left);
   const __amdgpu_buffer_rsrc_t r_res = make_rsrc(RES_BITS ? p.idx_res : p.idx, res_left);
@@ -251,6 +247,13 @@ __global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPla
   Window<NR> wres[DEPTH];
 #pragma unroll
   for (int d = 0; d < DEPTH; ++d) load_unit(win[d], wres[d]);
+
+  // The ring's loads (from HBM) have gone out behind everything else of the start-up and are not waited for here: loads
+  // return in order, so "all but the ring's" means the tables are in, and the barrier waits for LDS traffic only.
+  wait_vmem_at_most<DEPTH * (RES_BITS ? 2 : 1)>();
+  tables.store(p, lds, 0u, false);
+  lds_barrier();
+
 
   float acc[B][6];
 #pragma unroll

@@ -207,7 +207,7 @@ __device__ __forceinline__ void gemv_down_mfma_body(const Params &p, const DownM
     // the table loads are older than the ring's (loads return in order): at most the ring's may still be on their way
     wait_vmem_at_most<DEPTH * (1 + (RES_BITS ? 1 : 0) + NTP)>();
     tables.store(p, lds, 0u, false, tid);
-    __syncthreads();                                     // the tables are in
+    lds_barrier();                                       // the tables are in (a full barrier would also wait for the ring's loads from HBM)
 
     if (grp == g_lo && p.Q) {
       {                                                  // the outlier tile times the activations: a thread per (row, four tokens)
