@@ -7,10 +7,11 @@
 // vq_gemv_down.hip is bound by them.  One v_mfma_f32_16x16x32_f16 takes their place.  Its 32 "k" slots are four groups
 // of eight; a group is one column n of the layer, and the eight slots are the six elements j' of the centroid of that
 // column plus two zeros -- exactly the 16-byte table entry in LDS, as operand A of the stream (l & 15).  Operand B is
-// built to match: its 16 columns are (token, j) pairs, two tokens by six rows, and the value in slot (n, j') of column
-// (t, j) is x[t][n] where j' = j and zero elsewhere.  The product then is D[stream][(t, j)] = sum over the four columns of
-// C[I[stream][n]][j] * x[t][n]: 16 streams x 4 columns x 2 tokens per instruction, a tenth of its multiply-adds put to
-// use, and still several times the rate of the vector ALUs.  A lane builds one B operand with three byte permutes
+// built to match: its 16 columns are (token, j) pairs -- the 6 x batch pairs of a launch are dealt out 16 to an
+// instruction, ceil(6 batch / 16) instructions per step -- and the value in slot (n, j') of column (t, j) is x[t][n] where
+// j' = j and zero elsewhere.  The product then is D[stream][(t, j)] = sum over the four columns of
+// C[I[stream][n]][j] * x[t][n]: 16 streams x 4 columns x 2 2/3 tokens per instruction, an eighth of its multiply-adds put
+// to use, and still several times the rate of the vector ALUs.  A lane builds one B operand with three byte permutes
 // (v_perm_b32 with per-lane selectors that place one half of an activation dword and zero the rest).
 //
 // Work split: a workgroup of eight waves owns one block of 16 index streams (96 output rows) and one part of the
@@ -62,14 +63,15 @@ __device__ __forceinline__ float4v mfma16(uint4v a, uint4v b, float4v c) {
 // take one group (or the only one) and have no loop around the start-up (with the loop in every instantiation the
 // single-group ones lost up to 4 us on a 4096 x 4096 layer in 16 groups: registers held across the loop edge).
 // `wg` is the workgroup's number within its layer (a launch may hold the workgroups of several layers).
+// NTP: instructions per step, each with 16 of the 6 x batch (token, row) pairs as operand columns.
 template <int RES_BITS, int NTP, bool WALK>
 __device__ __forceinline__ void gemv_down_mfma_body(const Params &p, const DownMfmaPlan &plan, const __half *__restrict__ x, long long ldx,
                                                     __half *__restrict__ y, long long ldy, int wg) {
   typedef Layout<RES_BITS> LY;
   constexpr int RB = RES_BITS ? RES_BITS : 8;
   constexpr int NR = RES_BITS == 12 ? 3 : 2;             // dwords of a lane's residual indices
-  constexpr int DEPTH = NTP >= 4 ? 2 : 4;
-  constexpr bool LATE_X = NTP >= 8;                      // registers: refill a slot's activations only after the window's last product                // windows whose index words and activations are in flight or in registers
+  constexpr int DEPTH = NTP >= 3 ? 2 : 4;
+  constexpr bool LATE_X = NTP >= 6;                      // registers: refill a slot's activations only after the window's last product                // windows whose index words and activations are in flight or in registers
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -92,17 +94,24 @@ __device__ __forceinline__ void gemv_down_mfma_body(const Params &p, const DownM
   unsigned short *o_tile = reinterpret_cast<unsigned short *>(lds + plan.lds_o);
   unsigned short *o_x = o_tile + OROWS * Q2;
   float *o_sum = reinterpret_cast<float *>(o_x + 16 * Q2), *o_xs = o_sum + 16 * OROWS;
-  // ---- this lane's side of operand B: token tl of a pair and row j of a block of six; columns 12..15 stay zero
-  const int tl = n >= 6 ? 1 : 0, j = n - 6 * tl;
-  const bool col_on = n < 12;
+  // ---- this lane's side of operand B
+  // (operand column n of instruction m is pair 16 m + n of the 6 x batch (token, row j) pairs: token (16 m + n) / 6, row
+  // (16 m + n) % 6 = (n + 4 (m % 3)) % 6 -- three patterns of rows; pairs past the batch read zero activations)
+  auto token_of = [&](int m) { return (16 * m + n) / 6; };
+  auto row_of = [&](int m) { return (16 * m + n) % 6; };
   // byte selectors that move the low (even column) or high (odd column) half of an activation dword into half (j & 1) of
   // dword (j >> 1) of the operand, zeros (selector byte 0x0c) everywhere else
-  unsigned sel[3][2];
+  constexpr int NPAT = NTP < 3 ? NTP : 3;
+  unsigned sel[NPAT][3][2];
 #pragma unroll
-  for (int d = 0; d < 3; ++d) {
-    const bool mine = col_on && d == (j >> 1);
-    sel[d][0] = !mine ? 0x0c0c0c0cu : (j & 1) ? 0x01000c0cu : 0x0c0c0100u;
-    sel[d][1] = !mine ? 0x0c0c0c0cu : (j & 1) ? 0x03020c0cu : 0x0c0c0302u;
+  for (int pm = 0; pm < NPAT; ++pm) {
+    const int j = row_of(pm);
+#pragma unroll
+    for (int d = 0; d < 3; ++d) {
+      const bool mine = d == (j >> 1);
+      sel[pm][d][0] = !mine ? 0x0c0c0c0cu : (j & 1) ? 0x01000c0cu : 0x0c0c0100u;
+      sel[pm][d][1] = !mine ? 0x0c0c0c0cu : (j & 1) ? 0x03020c0cu : 0x0c0c0302u;
+    }
   }
   const unsigned st_main = (unsigned)p.stride, st_res = (unsigned)p.stride_res;
   const __amdgpu_buffer_rsrc_t r_main = make_rsrc(p.idx, (unsigned)p.S * st_main);
@@ -173,8 +182,8 @@ __device__ __forceinline__ void gemv_down_mfma_body(const Params &p, const DownM
     unsigned xoff[NTP];
 #pragma unroll
     for (int tp = 0; tp < NTP; ++tp) {
-      const int t = 2 * tp + tl;
-      xoff[tp] = col_on && t < plan.batch ? (unsigned)(((long long)t * ldx + col0 + 8 * g) * 2) : 0x80000000u;
+      const int t = token_of(tp);
+      xoff[tp] = t < plan.batch ? (unsigned)(((long long)t * ldx + col0 + 8 * g) * 2) : 0x80000000u;
     }
 
     // a stream past the last one reads out of range: index 0, whose products land in rows that are never stored
@@ -284,9 +293,9 @@ __device__ __forceinline__ void gemv_down_mfma_body(const Params &p, const DownM
             for (int tp = 0; tp < NTP; ++tp) {
               const unsigned xd = (u >> 1) == 0 ? xv[tp].x : (u >> 1) == 1 ? xv[tp].y : (u >> 1) == 2 ? xv[tp].z : xv[tp].w;
               uint4v b;
-              b.x = __builtin_amdgcn_perm(xd, xd, sel[0][u & 1]);
-              b.y = __builtin_amdgcn_perm(xd, xd, sel[1][u & 1]);
-              b.z = __builtin_amdgcn_perm(xd, xd, sel[2][u & 1]);
+              b.x = __builtin_amdgcn_perm(xd, xd, sel[tp % 3][0][u & 1]);
+              b.y = __builtin_amdgcn_perm(xd, xd, sel[tp % 3][1][u & 1]);
+              b.z = __builtin_amdgcn_perm(xd, xd, sel[tp % 3][2][u & 1]);
               b.w = 0u;
               acc[tp] = mfma16(e[u], b, acc[tp]);
               if (RES_BITS) acc[tp] = mfma16(f[u], b, acc[tp]);
@@ -302,25 +311,25 @@ __device__ __forceinline__ void gemv_down_mfma_body(const Params &p, const DownM
   // ---- the waves meet: sums per token pair, 1 KB per wave and pair, in the space of the tables
   __syncthreads();
   float4v *pbuf = reinterpret_cast<float4v *>(lds);                           // [NTP][MW][64]
-  float *xsb = reinterpret_cast<float *>(lds + NTP * MW * 1024);              // [MW][NTP][2][4]
+  float *xsb = reinterpret_cast<float *>(lds + NTP * MW * 1024);              // [MW][16 tokens][4]
 #pragma unroll
   for (int tp = 0; tp < NTP; ++tp) {
     pbuf[(tp * MW + wv) * 64 + lane] = acc[tp];
-    if (col_on && j == 0) xsb[((wv * NTP + tp) * 2 + tl) * 4 + g] = xs[tp];
+    if (row_of(tp) == 0 && token_of(tp) < plan.batch) xsb[(wv * 16 + token_of(tp)) * 4 + g] = xs[tp];
   }
   __syncthreads();
   if (wv < NTP) {                                        // wave tp finishes token pair tp
-    const int tp = wv, t = 2 * tp + tl;
+    const int tp = wv, t = token_of(tp), j = row_of(tp);
     float4v s = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
     for (int w = 0; w < MW; ++w) s += pbuf[(tp * MW + w) * 64 + lane];
-    if (col_on && t < plan.batch) {
+    if (t < plan.batch) {
       float xsum = 0.0f;
       if (need_xs) {
 #pragma unroll
         for (int w = 0; w < MW; ++w)
 #pragma unroll
-          for (int gg = 0; gg < 4; ++gg) xsum += xsb[((w * NTP + tp) * 2 + tl) * 4 + gg];
+          for (int gg = 0; gg < 4; ++gg) xsum += xsb[(w * 16 + t) * 4 + gg];
       }
       float sv[4] = {s.x, s.y, s.z, s.w};
       if (p.Q && !plan.part) {                           // the block's own outlier sums, left in LDS before the main loop
@@ -389,7 +398,7 @@ int cu_count() {
 template <int RES_BITS, int NTP>
 unsigned place_lds(const Params &p, DownMfmaPlan &plan) {
   unsigned lds_bytes = Layout<RES_BITS>::BYTES;
-  const unsigned meet = (unsigned)(NTP * MW) * 1024u + (unsigned)(MW * NTP * 8) * 4u;
+  const unsigned meet = (unsigned)(NTP * MW) * 1024u + (unsigned)(MW * 16 * 4) * 4u;
   if (lds_bytes < meet) lds_bytes = meet;
   plan.lds_o = lds_bytes;
   if (p.Q) lds_bytes += (unsigned)((OROWS + 16) * plan.o_pitch + 16 * OROWS + 16) * 4u;
@@ -488,13 +497,13 @@ int launch_gemv_down_mfma(const Params &p, const __half *x, long long ldx, int b
   const int rc_plan = make_plan(p, ldx, batch, part, part_xs, parts, plan, &grid);
   if (rc_plan != VQ_OK) return rc_plan;
   const int rb = p.k_res ? p.bits_res : 0;
-  const int ntp = (batch + 1) / 2;
+  const int ntp = (6 * batch + 15) / 16;                // instructions whose 16 operand columns hold the 6 x batch (token, row) pairs
   const bool walk = !part && p.n_groups > 1;
 #define VQ_CASE(R, N, LO) if (rb == R && ntp > LO && ntp <= N) \
     return walk ? launch_one<R, N, true>(p, plan, (unsigned)grid, x, ldx, y, ldy, s) : launch_one<R, N, false>(p, plan, (unsigned)grid, x, ldx, y, ldy, s);
-  VQ_CASE(0, 1, 0) VQ_CASE(0, 2, 1) VQ_CASE(0, 4, 2) VQ_CASE(0, 8, 4)
-  VQ_CASE(8, 1, 0) VQ_CASE(8, 2, 1) VQ_CASE(8, 4, 2) VQ_CASE(8, 8, 4)
-  VQ_CASE(12, 1, 0) VQ_CASE(12, 2, 1) VQ_CASE(12, 4, 2) VQ_CASE(12, 8, 4)
+  VQ_CASE(0, 1, 0) VQ_CASE(0, 2, 1) VQ_CASE(0, 3, 2) VQ_CASE(0, 4, 3) VQ_CASE(0, 6, 4)
+  VQ_CASE(8, 1, 0) VQ_CASE(8, 2, 1) VQ_CASE(8, 3, 2) VQ_CASE(8, 4, 3) VQ_CASE(8, 6, 4)
+  VQ_CASE(12, 1, 0) VQ_CASE(12, 2, 1) VQ_CASE(12, 3, 2) VQ_CASE(12, 4, 3) VQ_CASE(12, 6, 4)
 #undef VQ_CASE
   return VQ_ERR_UNSUPPORTED;
 }
@@ -520,11 +529,11 @@ int launch_gemv_down_mfma_multi(const Params *ps, int n, const __half *x, long l
     if (total > 0x7FFFFFFFLL) return VQ_ERR_UNSUPPORTED;
   }
   a.first_wg[n] = (int)total;
-  const int ntp = (batch + 1) / 2;
+  const int ntp = (6 * batch + 15) / 16;
 #define VQ_CASE(R, N, LO) if (rb == R && ntp > LO && ntp <= N) return launch_multi<R, N>(a, x, ldx, s);
-  VQ_CASE(0, 1, 0) VQ_CASE(0, 2, 1) VQ_CASE(0, 4, 2) VQ_CASE(0, 8, 4)
-  VQ_CASE(8, 1, 0) VQ_CASE(8, 2, 1) VQ_CASE(8, 4, 2) VQ_CASE(8, 8, 4)
-  VQ_CASE(12, 1, 0) VQ_CASE(12, 2, 1) VQ_CASE(12, 4, 2) VQ_CASE(12, 8, 4)
+  VQ_CASE(0, 1, 0) VQ_CASE(0, 2, 1) VQ_CASE(0, 3, 2) VQ_CASE(0, 4, 3) VQ_CASE(0, 6, 4)
+  VQ_CASE(8, 1, 0) VQ_CASE(8, 2, 1) VQ_CASE(8, 3, 2) VQ_CASE(8, 4, 3) VQ_CASE(8, 6, 4)
+  VQ_CASE(12, 1, 0) VQ_CASE(12, 2, 1) VQ_CASE(12, 3, 2) VQ_CASE(12, 4, 3) VQ_CASE(12, 6, 4)
 #undef VQ_CASE
   return VQ_ERR_UNSUPPORTED;
 }
