@@ -143,7 +143,8 @@ static bool down_mfma_parts_wanted(const Params &p, const __half *x, long long l
 static bool down_mfma_alone_wanted(const Params &p, const __half *x, long long ldx, int batch) {
   if (!down_mfma_wanted(p, x, ldx, batch)) return false;
   if (p.n_groups > 1) return true;                        // the only fast kernel of this orientation that walks codebook groups by itself
-  return batch >= 5 || (batch >= 3 && p.S >= 64 * 16) || forced_kernel() == 'm';
+  // (with a 12-bit residual stream the other kernel pays twice per row, and three rows are enough: 4096 x 11008, 54 against 46 us)
+  return batch >= 5 || (batch >= 3 && (p.S >= 64 * 16 || (p.k_res && p.bits_res == 12))) || forced_kernel() == 'm';
 }
 
 int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
