@@ -28,7 +28,7 @@ ROTATE_BYTES = 640 << 20        # footprint of the rotated index copies (> 2 x t
 # HBM traffic per launch from `rocprofv3 --pmc` (FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by
 # what the same counter reads for a 1 GiB device copy in the same run: FETCH_SIZE x 2.0, WRITE_SIZE x 1.0);
 # figures and commands in profiles/gemv_v6_cfg1_batch1.txt.  Keyed by benchmark configuration.
-MEASURED_TRAFFIC_BYTES = {1: int((5933.9 * 2.0 + 29.0 * 1.0) * 1024)}
+MEASURED_TRAFFIC_BYTES = {1: int((5932.2 * 2.0 + 29.0 * 1.0) * 1024)}
 
 
 def parse():
