@@ -249,3 +249,23 @@ def test_gemv_native_orientation_column_parts_with_workspace(gpu_lib, name, batc
     _check_matmul(y, oracle.gemv(L, x_np), "%s batch %d with workspace" % (name, batch))
     assert (ws[need:] == 0xFF).all()
     assert gpu_lib.vq_gemv_workspace_bytes(dl.desc, 1) == 0      # a single row stays on the kernel that needs none
+
+
+@pytest.mark.parametrize("workspace", [None, "fast"])
+@pytest.mark.parametrize("batch", [1, 3, 5, 16])
+@pytest.mark.parametrize("name,pad_x,pad_y", [("down_fast_res12", 8, 1), ("down_fast_outlier", 24, 6), ("down_fast_parts", 16, 3),
+                                               ("down_fast_groups_outlier_tall", 8, 5)])
+def test_native_orientation_strided_buffers_and_untouched_padding(gpu_lib, name, pad_x, pad_y, batch, workspace):
+    """Vectors down the output dimension, fast kernels (row stride of x a multiple of 8): NaN in the caller's padding of x
+    must never reach a sum, and sentinels in the padding of y must survive; with and without the workspace route."""
+    import torch
+    L = small_layer(name)
+    dl = gpu_lib.DeviceLayer(L)
+    x = s.make_activations(300, L, batch)
+    xb = torch.full((batch, L.in_features + pad_x), float("nan"), dtype=torch.float16, device="cuda")
+    xb[:, : L.in_features] = torch.from_numpy(x).cuda()
+    yb = torch.full((batch, L.out_features + pad_y), 7.0, dtype=torch.float16, device="cuda")
+    gpu_lib.gemv(dl, xb, out=yb, workspace=workspace)
+    torch.cuda.synchronize()
+    _check_matmul(yb[:, : L.out_features], oracle.gemv(L, x), "strided %s batch %d workspace %s" % (name, batch, workspace))
+    assert (yb[:, L.out_features:] == 7.0).all()
