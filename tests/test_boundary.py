@@ -136,6 +136,25 @@ def test_gemv_with_workspace_rejects_bad_arguments_before_any_launch():
     assert vq.vq_gemv_workspace_bytes(_desc(in_features=6 * 64, idx_row_stride=96, v=6, k=4096, group_vectors=12), 2) == 0
 
 
+def test_gemv_workspace_for_vectors_down_the_output_dimension():
+    """Orientation 1 on the matrix cores cuts the columns into parts when a workspace is there: asked for from two rows
+    on (one row stays on the kernel that needs none), sized parts x (rows x tokens + 16) floats, parts >= 2."""
+    d = _desc(orientation=1, out_features=96, in_features=1024, idx_row_stride=1536, v=6, k=4096)
+    assert vq.vq_validate(d) == vq.VQ_OK
+    assert vq.vq_gemv_workspace_bytes(d, 1) == 0
+    for batch in (2, 5, 16):
+        need = vq.vq_gemv_workspace_bytes(d, batch)
+        assert need >= 2 * (batch * 96 + 16) * 4 and need % 256 == 0, batch
+    # streams too short to cut (a part needs a 32-column window per wave), odd numbers of outlier columns: no workspace
+    assert vq.vq_gemv_workspace_bytes(_desc(orientation=1, out_features=96, in_features=256, idx_row_stride=384, v=6, k=4096), 4) == 0
+    odd = _desc(orientation=1, out_features=96, in_features=1024 + 7, idx_row_stride=1536, v=6, k=4096, n_outlier_cols=7, v_out=4, k_out=16,
+                codebook_out=0x3000, idx_out=0x4000, idx_out_row_stride=16)
+    assert vq.vq_validate(odd) == vq.VQ_OK and vq.vq_gemv_workspace_bytes(odd, 4) == 0
+    # codebook groups are parts by themselves, from one row on
+    grouped = _desc(orientation=1, out_features=96, in_features=1024, idx_row_stride=1536, v=6, k=4096, group_vectors=256)
+    assert vq.vq_gemv_workspace_bytes(grouped, 1) >= 4 * (96 + 16) * 4
+
+
 def test_assign_rejects_bad_arguments_before_any_launch():
     ok = dict(W_ptr=0x8000, B_ptr=None, ld=30, rows=8, cols=30, codebook_ptr=0x1000, v=6, k=256, idx_ptr=0x2000, idx_row_stride=16)
     assert vq.vq_assign(**dict(ok, W_ptr=None)) == vq.VQ_ERR_NULL
