@@ -282,6 +282,153 @@ __global__ __launch_bounds__((BM / 64 + 4) * 64) void gemm_v8_kernel(Params p, c
     }
 }
 
+// Dense product for many tokens: Y = X * Wd^T with both operands FP16 in memory (Wd is what vq_dequant wrote).  The tiling
+// above spends as many LDS cycles on operand reads as matrix-core cycles on the products (a wave's 64 x 128 block reads
+// 0.75 KB per MFMA).  Here a workgroup of four waves owns 256 tokens x 256 channels, a wave 128 x 128: 16 operand reads
+// feed 32 MFMAs (0.5 KB each), and the 256 accumulator registers that takes are there because a wave has its SIMD to
+// itself (512 registers).  No producer waves: every wave starts the asynchronous global->LDS copies of its share of both
+// tiles three steps ahead (same swizzled 64-byte rows as above).  With one wave per SIMD nothing else hides LDS latency,
+// so the loop is pipelined by half steps: the operands of the next half step are read before the products of the current
+// one are issued, and the barrier of a step sits between its two halves.
+constexpr int DT = 256;       // tokens and channels per workgroup
+constexpr int DNS = 4;        // stages of both tiles in LDS
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_dense256_kernel(const __half *__restrict__ X, long long ldx, int tokens,
+                                                            const __half *__restrict__ Wd, long long ldw, int out_features, int in_features,
+                                                            __half *__restrict__ Y, long long ldy) {
+  constexpr unsigned TILE = DT * 64u;           // bytes of one tile of one stage: 256 rows x 32 halfs
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [DNS][X tile | W tile]
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+  const int n0 = blockIdx.x * DT, m0 = blockIdx.y * DT;
+  const int ksteps = in_features / BK;
+  // range-checked against the end of the last row: rows past the matrix read zeros
+  const __amdgpu_buffer_rsrc_t r_x = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<__half *>(X), 0, (unsigned)(((long long)(tokens - 1) * ldx + in_features) * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t r_w = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<__half *>(Wd), 0, (unsigned)(((long long)(out_features - 1) * ldw + in_features) * 2), 0x00020000);
+
+  // this wave's share of a step's copies: pieces 4 wave .. 4 wave + 3 (16 rows x 64 bytes each) of both tiles
+  // (byte offsets of the lane's four pieces at step 0, worked out once; a step adds 64 bytes)
+  unsigned gx0[4], gw0[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const unsigned piece = (unsigned)(wave * 4 + i);
+    const unsigned r = piece * 16u + ((unsigned)lane >> 2), cs = (unsigned)lane & 3u;   // LDS slot (r, cs) holds chunk cs ^ swz(r)
+    const unsigned c = cs ^ swz(r);
+    gx0[i] = (unsigned)(((long long)(m0 + (int)r) * ldx + c * 8) * 2);
+    gw0[i] = (unsigned)(((long long)(n0 + (int)r) * ldw + c * 8) * 2);
+  }
+  auto copy_tiles = [&](int kt) {
+    unsigned char *stage = smem + (unsigned)(kt % DNS) * (2u * TILE);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const unsigned piece = (unsigned)(wave * 4 + i);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r_x, (__attribute__((address_space(3))) void *)(stage + piece * 1024u), 16, gx0[i] + (unsigned)kt * (BK * 2u), 0, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r_w, (__attribute__((address_space(3))) void *)(stage + TILE + piece * 1024u), 16, gw0[i] + (unsigned)kt * (BK * 2u), 0, 0, 0);
+    }
+  };
+  // operand addresses: row (block base + lane & 31), whose swizzle depends on the lane only, chunk ks / 8 + (lane >> 5):
+  // one base per tile and half step, blocks 2 KB apart
+  const unsigned sw = ((unsigned)(lane & 31) >> 2) & 3u;
+  const unsigned xo[2] = {(unsigned)(wm + (lane & 31)) * 64u + ((((unsigned)lane >> 5) ^ sw) << 4),
+                          (unsigned)(wm + (lane & 31)) * 64u + (((2u + ((unsigned)lane >> 5)) ^ sw) << 4)};
+  const unsigned wo[2] = {TILE + (unsigned)(wn + (lane & 31)) * 64u + ((((unsigned)lane >> 5) ^ sw) << 4),
+                          TILE + (unsigned)(wn + (lane & 31)) * 64u + (((2u + ((unsigned)lane >> 5)) ^ sw) << 4)};
+  // The reads are issued from inline assembly, in program order, and waited for by count: left to itself the compiler
+  // gives both sets of operands the same registers and so has to issue a set's reads after the other set's products.
+  const unsigned lds0 = (unsigned)reinterpret_cast<size_t>((const __attribute__((address_space(3))) void *)smem);
+  auto read_operands = [&](int kt, int ks, half8 (&af)[4], half8 (&bf)[4]) {
+    const unsigned stage = lds0 + (unsigned)(kt % DNS) * (2u * TILE);
+    unsigned xa = stage + xo[ks >> 4], wa = stage + wo[ks >> 4];
+    asm volatile("" : "+v"(xa), "+v"(wa));      // both addresses in registers of their own before the first read goes out
+    asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:2048\n\tds_read_b128 %2, %4 offset:4096\n\tds_read_b128 %3, %4 offset:6144"
+                 : "=&v"(af[0]), "=&v"(af[1]), "=&v"(af[2]), "=&v"(af[3]) : "v"(xa) : "memory");
+    asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:2048\n\tds_read_b128 %2, %4 offset:4096\n\tds_read_b128 %3, %4 offset:6144"
+                 : "=&v"(bf[0]), "=&v"(bf[1]), "=&v"(bf[2]), "=&v"(bf[3]) : "v"(wa) : "memory");
+  };
+  auto operands_in = [&](half8 (&af)[4], half8 (&bf)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { settle(af[i]); settle(bf[i]); }
+  };
+  float16v acc[4][4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.0f;
+  auto multiply = [&](const half8 (&af)[4], const half8 (&bf)[4]) {
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[a], bf[c], acc[a][c], 0, 0, 0);
+  };
+
+  // copies run DNS - 1 steps ahead; a wave waits for its own by count (eight per step), the barrier covers the others'
+#pragma unroll
+  for (int j = 0; j < DNS - 1; ++j)
+    if (j < ksteps) copy_tiles(j);
+  if (ksteps >= 3) wait_vmem_at_most<16>(); else wait_vmem_at_most<0>();
+  step_barrier();
+  half8 a0[4], b0[4], a1[4], b1[4];
+  read_operands(0, 0, a0, b0);
+  for (int kt = 0; kt < ksteps; ++kt) {
+    if (kt + DNS - 1 < ksteps) copy_tiles(kt + DNS - 1);     // into the stage of step kt - 1: everyone has passed that step's barrier
+    read_operands(kt, 16, a1, b1);
+    asm volatile("s_waitcnt lgkmcnt(8)" ::: "memory");        // LDS reads return in order: all but the eight just issued are in
+    operands_in(a0, b0);
+    multiply(a0, b0);
+    // this wave's copies of step kt + 1 went out at step kt - 2; the steps since have issued eight each
+    if (kt + DNS - 1 < ksteps) wait_vmem_at_most<16>(); else wait_vmem_at_most<0>();
+    step_barrier();                                           // (waits for the operand reads above as well: they are LDS traffic)
+    // (statements from inline assembly keep their order: the reads of the next half step go out first, then the products
+    // of this one, which the compiler may not move ahead of the statement that hands it their operands)
+    read_operands(kt + 1 < ksteps ? kt + 1 : kt, 0, a0, b0);  // (past the end: any stage, never used; keeps the loop one straight line)
+    operands_in(a1, b1);
+    multiply(a1, b1);
+  }
+
+  // ---- store: lane holds channel (lane & 31) of block c and 16 token rows of block a.  Range-checked 2-byte buffer stores
+  // with 32-bit offsets (256 64-bit addresses would not fit the registers): rows past the last token fall off the end of
+  // the buffer, channels past the last one are sent there on purpose.
+  const __amdgpu_buffer_rsrc_t r_y = __builtin_amdgcn_make_buffer_rsrc(Y, 0, (unsigned)(((long long)(tokens - 1) * ldy + out_features) * 2), 0x00020000);
+  const unsigned ldy2 = (unsigned)ldy * 2u;
+  const unsigned y_lane = (unsigned)(m0 + wm + 4 * (lane >> 5)) * ldy2 + (unsigned)(n0 + wn + (lane & 31)) * 2u;
+#pragma unroll
+  for (int a = 0; a < 4; ++a) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const bool o_on = n0 + wn + c * 32 + (lane & 31) < out_features;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const unsigned off = y_lane + (unsigned)(a * 32 + 8 * (r >> 2) + (r & 3)) * ldy2 + (unsigned)(c * 64);
+        const __half h = __float2half_rn(acc[a][c][r]);
+        __builtin_amdgcn_raw_buffer_store_b16((short)__half_as_ushort(h), r_y, o_on ? off : 0xFFFFFFF0u, 0, 0);
+      }
+    }
+    asm volatile("" ::: "memory");
+  }
+}
+
+int launch_dense256(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy, const __half *Wd, long long ldw,
+                    hipStream_t s) {
+  static bool configured = false;
+  const unsigned lds = DNS * 2u * DT * 64u;
+  if (!configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_dense256_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+      return VQ_ERR_HIP;
+    configured = true;
+  }
+  if (((long long)(p.out_features - 1) * ldw + p.in_features) * 2 >= (1LL << 32)) return VQ_ERR_UNSUPPORTED;   // 32-bit buffer offsets
+  if (((long long)(tokens + DT) * ldy + p.out_features + DT) * 2 >= 0xFFFFFFF0LL) return VQ_ERR_UNSUPPORTED;
+  const unsigned gx = (unsigned)((p.out_features + DT - 1) / DT), gy = (unsigned)((tokens + DT - 1) / DT);
+  if (gy > 65535u) return VQ_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(gemm_dense256_kernel, dim3(gx, gy), dim3(256), lds, s, X, ldx, tokens, Wd, ldw, p.out_features, p.in_features, Y, ldy);
+  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
 template <int BM, bool DENSE>
 int launch_fused(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy, const __half *Wd, long long ldw,
                  hipStream_t s) {
@@ -312,6 +459,14 @@ int launch_gemm_fused(const Params &p, const __half *X, long long ldx, int token
   static const int force_bm = [] { const char *e = getenv("VQ_GEMM_BM"); return e ? atoi(e) : 0; }();
   if (((long long)(tokens - 1) * ldx + p.in_features) * 2 >= (1LL << 32)) return VQ_ERR_UNSUPPORTED;   // 32-bit buffer offsets
   if (Wd) {
+    // enough 256 x 256 tiles to fill the chip: the four-wave kernel (VQ_GEMM_DENSE=1 / =0: always / never, for measurement and tests)
+    const char *env_dense = getenv("VQ_GEMM_DENSE");       // read at every call so that one process can test both
+    const int force_dense = env_dense ? atoi(env_dense) : -1;
+    const long long tiles256 = (long long)((p.out_features + DT - 1) / DT) * ((tokens + DT - 1) / DT);
+    if (force_dense == 1 || (force_dense != 0 && !force_bm && tiles256 >= 200)) {
+      const int rc = launch_dense256(p, X, ldx, tokens, Y, ldy, Wd, ldw, s);
+      if (rc != VQ_ERR_UNSUPPORTED) return rc;
+    }
     // no gathers to amortise: the tile height only has to fill the chip (out/128 x tokens/BM workgroups)
     const long long col_blocks = (p.out_features + BN - 1) / BN;
     const int bm = force_bm ? force_bm : (col_blocks * ((tokens + 511) / 512) >= 200 ? 512 : col_blocks * ((tokens + 255) / 256) >= 200 ? 256 : 128);

@@ -50,13 +50,16 @@ def test_gemv_small(gpu_lib, monkeypatch, name, batch, kernel):
 
 @pytest.mark.parametrize("name", list(SMALL))
 @pytest.mark.parametrize("tokens", [1, 37, 130, 300])
-@pytest.mark.parametrize("workspace", [None, "fast"])
+@pytest.mark.parametrize("workspace", [None, "fast", "fast, 256 x 256 tiles"])
 def test_gemm_small(gpu_lib, monkeypatch, name, tokens, workspace):
     """Without a workspace (weights restored on the fly) and with the one that lets vq_gemm restore W once (that
-    route forced: by itself the library keeps small token counts on the on-the-fly kernel where it has one)."""
+    route forced: by itself the library keeps small token counts on the on-the-fly kernel where it has one), the dense
+    product by the kernel with producer waves and by the four-wave kernel with 256 x 256 tiles."""
     import torch
-    if workspace == "fast":
+    if workspace is not None:
         monkeypatch.setenv("VQ_GEMM_KERNEL", "w")
+        monkeypatch.setenv("VQ_GEMM_DENSE", "1" if "256" in workspace else "0")      # the dense product's two kernels
+        workspace = "fast"
     L = small_layer(name)
     dl = gpu_lib.DeviceLayer(L)
     if workspace == "fast" and gpu_lib.vq_gemm_fast_workspace_bytes(dl.desc, tokens) == 0:
