@@ -97,7 +97,10 @@ constexpr int window_dwords(int bits, int u) { return (32 - 4 + bits * u + 31) /
 template <int RES_BITS, int B, int U, int L1R>
 __device__ __forceinline__ void gemv_v6_body(const Params &p, const GemvPlan &plan, const __half *__restrict__ x, long long ldx,
                                              __half *__restrict__ y, long long ldy, int wg) {
-  constexpr int DEPTH = RES_BITS ? 3 : 4;        // rows of index windows a wave keeps in flight (register budget)
+  // rows of index windows a wave keeps in flight, and copies of the row body in the unrolled loop.  Measured on the
+  // 11008 x 4096 layer (9 rows a wave), one row of activations: 2 / 3 / 4 / 5 / 8 in flight -> 7.9 / 7.8 / 8.1 / 8.6 / 9.6 us;
+  // what is in flight beyond the latency of HBM buys nothing, and a body copy that the last round does not use costs.
+  constexpr int DEPTH = RES_BITS || B == 1 ? 3 : 4;
   constexpr int NM = window_dwords(12, U);
   constexpr int RB = RES_BITS ? RES_BITS : 8;
   constexpr int NR = window_dwords(RB, U);
