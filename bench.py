@@ -395,7 +395,7 @@ def detail(vq, s, np, torch, use_graph, skip):
                         raise vq.VQError(rc, "vq_gemv_multi")
             wall, ev = timed(chain_d, 100, 10, use_graph)
             us = ev / 100 * 1e6
-            out.append({"op": "cfg2 decoder layer in orientation 1 as a chain of %d launches (single layers with a workspace)" % (4 if fused else 7), "cfg": 2, "batch": batch,
+            out.append({"op": "cfg2 decoder layer in orientation 1 as a chain of %d calls (%ssingle layers through vq_gemv_with_workspace)" % (4 if fused else 7, "q+k+v and gate+up through vq_gemv_multi, " if fused else ""), "cfg": 2, "batch": batch,
                         "us": round(us, 2), "GB/s": round(alg / us / 1e3, 1), "frac_hbm_peak": round(alg / us / 1e3 / HBM_PEAK_GBPS, 4)})
     del rots_d, xs, ys, layers_d, ws_d
     # codebook groups on the headline shape: "group num" 4 and 16 of the paper's parameter table, as group sizes
