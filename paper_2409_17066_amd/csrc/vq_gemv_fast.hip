@@ -101,8 +101,10 @@ __device__ __forceinline__ void gemv_v6_body(const Params &p, const GemvPlan &pl
   // 11008 x 4096 layer (9 rows a wave), one row of activations: 2 / 3 / 4 / 5 / 8 in flight -> 7.9 / 7.8 / 8.1 / 8.6 / 9.6 us;
   // what is in flight beyond the latency of HBM buys nothing, and a body copy that the last round does not use costs.
   // With a residual stream (two windows a row, a longer row body) two rows are enough: 4096 x 4096 8.1 -> 7.9 us,
-  // 11008 x 4096 12.9 -> 12.7 us, 8192 x 28672 37.0 -> 36.4 us.
-  constexpr int DEPTH = (RES_BITS && B == 1) ? 2 : (RES_BITS || B == 1 ? 3 : 4);
+  // 11008 x 4096 12.9 -> 12.7 us, 8192 x 28672 37.0 -> 36.4 us.  (Seven other layer shapes without a residual stream, one
+  // row: three in flight are 3-7 % ahead of four on every one, two are level with three; more rows per launch: three
+  // are 1-2 % ahead of four.)
+  constexpr int DEPTH = (RES_BITS && B == 1) ? 2 : 3;
   constexpr int NM = window_dwords(12, U);
   constexpr int RB = RES_BITS ? RES_BITS : 8;
   constexpr int NR = window_dwords(RB, U);
