@@ -70,8 +70,11 @@ __device__ __forceinline__ void gemv_down_mfma_body(const Params &p, const DownM
   typedef Layout<RES_BITS> LY;
   constexpr int RB = RES_BITS ? RES_BITS : 8;
   constexpr int NR = RES_BITS == 12 ? 3 : 2;             // dwords of a lane's residual indices
-  constexpr int DEPTH = NTP >= 3 ? 2 : 4;
-  constexpr bool LATE_X = NTP >= 6;                      // registers: refill a slot's activations only after the window's last product                // windows whose index words and activations are in flight or in registers
+  // (measured: a ring deeper than this only adds start-up loads -- a wave of a column part has few windows -- and the
+  // refill of a slot already runs a window ahead of its use; 4 deep -> 1 deep: 4096 x 4096 with residual and workspace,
+  // batch 4, 14.1 -> 12.9 us; q+k+v fused, batch 4, 24.4 -> 22.1 us)
+  constexpr int DEPTH = (NTP == 1 && RES_BITS == 0) ? 2 : 1;
+  constexpr bool LATE_X = NTP >= 6;                      // registers: refill a slot's activations only after the window's last product
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
