@@ -441,8 +441,9 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_kernel(Params p, MfmaPla
 // A layer with codebook groups when the caller lends a workspace: every workgroup takes one group (its tables go into
 // LDS once) and a share of the rows, the binary32 sums go to the workspace [group][token][row], and the kernel below
 // adds the groups up.  Without a workspace the workgroups cannot meet, and each walks all groups (the kernel above).
+// (Two waves per SIMD in every instantiation: eight waves in one workgroup, or two workgroups of four.)
 template <int RES_BITS, int MW, int NB>
-__global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_groups_kernel(Params p, MfmaPlan plan, const __half *__restrict__ x, long long ldx,
+__global__ __launch_bounds__(MW * 64) __attribute__((amdgpu_waves_per_eu(2))) void gemv_v6_mfma_groups_kernel(Params p, MfmaPlan plan, const __half *__restrict__ x, long long ldx,
                                                                        int batch, float *__restrict__ part, float *__restrict__ part_xs,
                                                                        int wgs_per_group) {
   warm_kernel_arguments();
@@ -521,6 +522,7 @@ int launch_one(const Params &p, const MfmaPlan &plan, unsigned lds_bytes, unsign
 #define VQ_MFMA_WAVES 8
 #endif
 constexpr int MW = VQ_MFMA_WAVES;
+constexpr int NARROW_WAVES = 4;            // workgroup size for layers whose codebook groups are narrow (see narrow_groups)
 
 }  // namespace
 
@@ -541,15 +543,16 @@ struct Planned {
 
 // Work split and LDS layout of one layer when every workgroup takes `blocks_per_wg` 16-row blocks.  nb_force > 0
 // fixes the blocks per chunk (several layers in one launch share one kernel instantiation).
+// `waves` and `lds_cap`: the workgroup's size and its share of the compute unit's LDS (the defaults: one workgroup of
+// MW waves per compute unit).
 int make_plan(const Params &p, int batch, long long ldx, const __half *y, long long ldy, int blocks_per_wg, int nb_force, Planned *out,
-              bool partial = false) {
+              bool partial = false, int waves = MW, unsigned lds_cap = 160u * 1024u) {
   MfmaPlan plan{};
   if (p.in_features < 64) return VQ_ERR_UNSUPPORTED;      // idle lanes load the first 100 bytes of the first activation row
   const int rb = p.k_res ? p.bits_res : 0;
   unsigned off = rb == 0 ? Layout<0>::BYTES : rb == 8 ? Layout<8>::BYTES : Layout<12>::BYTES;
   plan.lds_out = off; off += p.Q ? 4096u * 8u : 0u;
-  plan.lds_xs = off; off += MW * 16u * 4u;
-  const unsigned lds_cap = 160u * 1024u;
+  plan.lds_xs = off; off += (unsigned)waves * 16u * 4u;
   const int blocks_total = (p.out_features + 15) / 16;
   plan.rows_per_wg = blocks_per_wg * 16;
   out->grid = (unsigned)((blocks_total + blocks_per_wg - 1) / blocks_per_wg);
@@ -558,8 +561,8 @@ int make_plan(const Params &p, int batch, long long ldx, const __half *y, long l
   if (grouped && (p.Pg & 7)) return VQ_ERR_UNSUPPORTED;   // a group must start on a dword of the 12- and 8-bit streams
   plan.lds_yacc = off; off += grouped && !partial ? (unsigned)blocks_per_wg * 1024u : 0u;
   plan.lds_part = off;
-  if (off + MW * 1024u > lds_cap) return VQ_ERR_UNSUPPORTED;
-  const int fit = (int)((lds_cap - off) / (MW * 1024u));                 // 16-row partial blocks that fit
+  if (off + (unsigned)waves * 1024u > lds_cap) return VQ_ERR_UNSUPPORTED;
+  const int fit = (int)((lds_cap - off) / ((unsigned)waves * 1024u));    // 16-row partial blocks that fit
   // Blocks per chunk: as many as the kernel's 256 registers allow -- four, or three with a residual index stream in the
   // prefetch ring.  More would spill, which these kernels must not (see the build script).
   static const int nb_cap = [] { const char *e = getenv("VQ_MFMA_NB"); return e ? atoi(e) : NBMAX; }();
@@ -569,7 +572,7 @@ int make_plan(const Params &p, int batch, long long ldx, const __half *y, long l
   if (nb_force > 0) { if (nb_force > plan.nb) return VQ_ERR_UNSUPPORTED; plan.nb = nb_force; }
   if (plan.nb < 1) return VQ_ERR_UNSUPPORTED;
   plan.part_bufs = (fit >= 2 * plan.nb && blocks_per_wg > plan.nb) ? 2 : 1;
-  off += (unsigned)(plan.part_bufs * plan.nb) * (MW * 1024u);
+  off += (unsigned)(plan.part_bufs * plan.nb) * ((unsigned)waves * 1024u);
   const long long max_stride = max(p.stride, max(p.stride_res, p.stride_out));
   if ((long long)(plan.rows_per_wg + 16 * NBMAX * 8) * max_stride >= (1LL << 31)) return VQ_ERR_UNSUPPORTED;   // 32-bit buffer offsets
   const long long x_bytes = ((long long)(batch - 1) * ldx + p.in_features) * 2;
@@ -578,6 +581,17 @@ int make_plan(const Params &p, int batch, long long ldx, const __half *y, long l
   plan.y_wide = ((reinterpret_cast<uintptr_t>(y) & 7) == 0 && (ldy & 3) == 0) ? 1 : 0;
   out->plan = plan; out->lds_bytes = off; out->rb = rb; out->grouped = grouped;
   return VQ_OK;
+}
+
+// A codebook group of at most 128 vectors gives work to four waves at most (a wave takes 32 vectors of a row at a
+// time): such layers run in workgroups of four waves, two to a compute unit, each with its own copy of its group's
+// tables -- when two copies fit the LDS, i.e. without a 12-bit residual table and without the outlier table.  Only
+// with a workspace, where a workgroup loads one group's tables: when every workgroup walks all groups the table
+// loads dominate, and twice as many workgroups doing them was measured slower (15 groups of 48 vectors on an
+// 11008 x 4096 layer, batch 4: 66 us against 55 us).
+bool narrow_groups(const Params &p) {
+  static const int mode = [] { const char *e = getenv("VQ_MFMA_NARROW"); return e ? atoi(e) : -1; }();
+  return mode != 0 && p.n_groups > 1 && (p.Pg + 31) / 32 <= NARROW_WAVES && !(p.k_res && p.bits_res == 12) && p.Q == 0;
 }
 
 template <int RES_BITS, int NB>
@@ -627,20 +641,33 @@ size_t gemv_mfma_groups_workspace_bytes(const Params &p, int batch) {
 // The caller has checked gemv_fast_applicable() and that the workspace holds gemv_mfma_groups_workspace_bytes().
 int launch_gemv_mfma_groups(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, void *workspace,
                             hipStream_t s) {
-  const int wgs_per_group = cu_count() / p.n_groups;
-  if (wgs_per_group < 1) return VQ_ERR_UNSUPPORTED;
   const int blocks_total = (p.out_features + 15) / 16;
+  bool narrow = narrow_groups(p) && 2 * cu_count() / p.n_groups >= 1;
   Planned pl;
-  const int rc = make_plan(p, batch, ldx, y, ldy, (blocks_total + wgs_per_group - 1) / wgs_per_group, 0, &pl, true);
-  if (rc != VQ_OK) return rc;
+  int rc = VQ_ERR_UNSUPPORTED;
+  if (narrow) {
+    const int wgs_per_group = 2 * cu_count() / p.n_groups;
+    rc = make_plan(p, batch, ldx, y, ldy, (blocks_total + wgs_per_group - 1) / wgs_per_group, 0, &pl, true, NARROW_WAVES, 80u * 1024u);
+    if (rc != VQ_OK) narrow = false;
+  }
+  if (!narrow) {
+    const int wgs_per_group = cu_count() / p.n_groups;
+    if (wgs_per_group < 1) return VQ_ERR_UNSUPPORTED;
+    rc = make_plan(p, batch, ldx, y, ldy, (blocks_total + wgs_per_group - 1) / wgs_per_group, 0, &pl, true);
+    if (rc != VQ_OK) return rc;
+  }
   float *part = static_cast<float *>(workspace);
   float *part_xs = part + (size_t)p.n_groups * (size_t)batch * (size_t)p.out_features;
   const unsigned grid = pl.grid * (unsigned)p.n_groups;            // pl.grid workgroups per group
   const void *kernel = nullptr;
 #define VQ_CASE(RBITS, NBLK) \
-  if (pl.rb == RBITS && pl.plan.nb == NBLK && NBLK <= (RBITS == 12 ? 2 : 3)) \
+  if (!narrow && pl.rb == RBITS && pl.plan.nb == NBLK && NBLK <= (RBITS == 12 ? 2 : 3)) \
     kernel = reinterpret_cast<const void *>(gemv_v6_mfma_groups_kernel<RBITS, MW, (NBLK <= (RBITS == 12 ? 2 : 3) ? NBLK : 1)>);
   VQ_CASE(0, 1) VQ_CASE(0, 2) VQ_CASE(0, 3) VQ_CASE(8, 1) VQ_CASE(8, 2) VQ_CASE(8, 3) VQ_CASE(12, 1) VQ_CASE(12, 2)
+#undef VQ_CASE
+#define VQ_CASE(RBITS, NBLK) \
+  if (narrow && pl.rb == RBITS && pl.plan.nb == NBLK) kernel = reinterpret_cast<const void *>(gemv_v6_mfma_groups_kernel<RBITS, NARROW_WAVES, NBLK>);
+  VQ_CASE(0, 1) VQ_CASE(0, 2) VQ_CASE(0, 3) VQ_CASE(8, 1) VQ_CASE(8, 2)
 #undef VQ_CASE
   if (!kernel) return VQ_ERR_UNSUPPORTED;
   if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return VQ_ERR_HIP;
@@ -648,7 +675,7 @@ int launch_gemv_mfma_groups(const Params &p, const __half *x, long long ldx, int
   MfmaPlan plan = pl.plan;
   int wpg = (int)pl.grid;
   void *args[] = {&pc, &plan, &x, &ldx, &batch, &part, &part_xs, &wpg};
-  if (hipLaunchKernel(kernel, dim3(grid), dim3(MW * 64), args, pl.lds_bytes, s) != hipSuccess) return VQ_ERR_HIP;
+  if (hipLaunchKernel(kernel, dim3(grid), dim3((narrow ? NARROW_WAVES : MW) * 64), args, pl.lds_bytes, s) != hipSuccess) return VQ_ERR_HIP;
   hipLaunchKernelGGL(gemv_groups_finish_kernel, dim3((unsigned)((p.out_features + 255) / 256), (unsigned)batch), dim3(256), 0, s, part, part_xs, p.n_groups,
                      batch, p.out_features, p.scale, p.bias, y, ldy);
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;

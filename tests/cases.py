@@ -41,6 +41,7 @@ SMALL = {
     "grp_v6_chunks_res12": dict(out_features=12303, in_features=390, v=6, k=4096, k_res=4096, group_vectors=24),
     "grp_v6_passes": dict(out_features=40, in_features=7000, v=6, k=4096, k_res=4096, group_vectors=600),
     "grp_v6_sixteen": dict(out_features=300, in_features=4096, v=6, k=4096, group_vectors=48),
+    "grp_v6_narrow_res8": dict(out_features=3000, in_features=1150, v=6, k=4096, k_res=256, group_vectors=32),
     "grp_v6_small_tables": dict(out_features=70, in_features=391, v=6, k=3000, k_res=200, group_vectors=8),
     "grp_v6_unaligned": dict(out_features=70, in_features=800, v=6, k=4096, k_res=256, group_vectors=20),
     "grp_v6_dense_gemm": dict(out_features=203, in_features=1024, v=6, k=4096, k_res=4096, n_outlier_cols=16, v_out=4, k_out=4096, group_vectors=56),
