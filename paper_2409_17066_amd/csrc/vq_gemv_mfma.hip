@@ -453,18 +453,42 @@ __global__ __launch_bounds__(MW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 }
 
 // y[t][o] = fp16(scale[o] * sum_g part[g][t][o] + bias[o] * sum_g part_xs[g][t]), groups in ascending order.
-__global__ __launch_bounds__(256) void gemv_groups_finish_kernel(const float *__restrict__ part, const float *__restrict__ part_xs, int n_groups,
-                                                                 int batch, int out_features, const __half *__restrict__ scale,
-                                                                 const __half *__restrict__ bias, __half *__restrict__ y, long long ldy) {
-  const int o = blockIdx.x * 256 + threadIdx.x, t = blockIdx.y;          // one token per grid row
+// The sums were written by other compute units a moment ago and come from beyond this one's caches: the loads of
+// FINISH_AHEAD groups are issued together (a group past the last repeats the last and is not added), the additions
+// keep their order.
+constexpr int FINISH_THREADS = 128;
+template <int FINISH_AHEAD>
+__global__ __launch_bounds__(FINISH_THREADS) void gemv_groups_finish_kernel(const float *__restrict__ part, const float *__restrict__ part_xs,
+                                                                            int n_groups, int batch, int out_features,
+                                                                            const __half *__restrict__ scale, const __half *__restrict__ bias,
+                                                                            __half *__restrict__ y, long long ldy) {
+  const int o = blockIdx.x * FINISH_THREADS + threadIdx.x, t = blockIdx.y;          // one token per grid row
   if (o >= out_features) return;
   const float sc = scale ? __half2float(scale[o]) : 1.0f, bi = bias ? __half2float(bias[o]) : 0.0f;
   float sum = 0.0f, xs = 0.0f;
-  for (int gi = 0; gi < n_groups; ++gi) {
-    sum += part[((long long)gi * batch + t) * out_features + o];
-    xs += part_xs[gi * 16 + t];
+  for (int g0 = 0; g0 < n_groups; g0 += FINISH_AHEAD) {
+    float v[FINISH_AHEAD], w[FINISH_AHEAD];
+#pragma unroll
+    for (int i = 0; i < FINISH_AHEAD; ++i) {
+      const int gi = min(g0 + i, n_groups - 1);
+      v[i] = part[((long long)gi * batch + t) * out_features + o];
+      w[i] = part_xs[gi * 16 + t];
+    }
+#pragma unroll
+    for (int i = 0; i < FINISH_AHEAD; ++i)
+      if (g0 + i < n_groups) { sum += v[i]; xs += w[i]; }
   }
   y[(long long)t * ldy + o] = __float2half_rn(__fmaf_rn(sc, sum, bi * xs));
+}
+
+void launch_finish(const float *part, const float *part_xs, int n_groups, int batch, const Params &p, __half *y, long long ldy, hipStream_t s) {
+  const dim3 grid((unsigned)((p.out_features + FINISH_THREADS - 1) / FINISH_THREADS), (unsigned)batch), block(FINISH_THREADS);
+  if (n_groups <= 2)
+    hipLaunchKernelGGL(gemv_groups_finish_kernel<2>, grid, block, 0, s, part, part_xs, n_groups, batch, p.out_features, p.scale, p.bias, y, ldy);
+  else if (n_groups <= 4)
+    hipLaunchKernelGGL(gemv_groups_finish_kernel<4>, grid, block, 0, s, part, part_xs, n_groups, batch, p.out_features, p.scale, p.bias, y, ldy);
+  else
+    hipLaunchKernelGGL(gemv_groups_finish_kernel<8>, grid, block, 0, s, part, part_xs, n_groups, batch, p.out_features, p.scale, p.bias, y, ldy);
 }
 
 // Several layers that read the same activations (the query, key and value projections of a decoder layer; its gate
@@ -676,16 +700,14 @@ int launch_gemv_mfma_groups(const Params &p, const __half *x, long long ldx, int
   int wpg = (int)pl.grid;
   void *args[] = {&pc, &plan, &x, &ldx, &batch, &part, &part_xs, &wpg};
   if (hipLaunchKernel(kernel, dim3(grid), dim3((narrow ? NARROW_WAVES : MW) * 64), args, pl.lds_bytes, s) != hipSuccess) return VQ_ERR_HIP;
-  hipLaunchKernelGGL(gemv_groups_finish_kernel, dim3((unsigned)((p.out_features + 255) / 256), (unsigned)batch), dim3(256), 0, s, part, part_xs, p.n_groups,
-                     batch, p.out_features, p.scale, p.bias, y, ldy);
+  launch_finish(part, part_xs, p.n_groups, batch, p, y, ldy, s);
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
 
 // y = scale * (sum over the groups) + bias * (sum of their activation sums), for any kernel that left per-group sums in a workspace.
 int launch_groups_finish(const float *part, const float *part_xs, int n_groups, int batch, const Params &p, __half *y, long long ldy,
                          hipStream_t s) {
-  hipLaunchKernelGGL(gemv_groups_finish_kernel, dim3((unsigned)((p.out_features + 255) / 256), (unsigned)batch), dim3(256), 0, s, part, part_xs,
-                     n_groups, batch, p.out_features, p.scale, p.bias, y, ldy);
+  launch_finish(part, part_xs, n_groups, batch, p, y, ldy, s);
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
 
