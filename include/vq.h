@@ -115,7 +115,8 @@ int vq_gemv(const vq_layer_desc *desc, const void *x, int64_t ldx, int32_t batch
  * every workgroup takes one group, whose tables it loads once, and a share of the rows, writes binary32 sums to the
  * workspace, and a second kernel adds the groups up in ascending order and applies scale and bias -- instead of every
  * workgroup walking all groups and swapping its tables for each.  Layers of orientation 1 with one group use it from
- * three rows on: the matrix-core kernel of that orientation works in blocks of 16 index streams (96 output rows), too few
+ * two rows on (from one row when a row of x does not fit the one-row kernel's LDS beside the tables: about 15000
+ * columns with a 12-bit residual table): the matrix-core kernel of that orientation works in blocks of 16 index streams (96 output rows), too few
  * to fill the chip on most layers, so with a workspace it also cuts the columns into parts, one workgroup per (block,
  * part), and the same second kernel adds the parts up.  vq_gemv_workspace_bytes returns 0 when no kernel
  * would use a workspace for this layer.  With workspace NULL or smaller than that, and for every other layer, the

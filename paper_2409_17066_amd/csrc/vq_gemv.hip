@@ -111,6 +111,7 @@ int launch_gemv_fast(const Params &p, const __half *x, long long ldx, int batch,
 
 int launch_gemv_mfma(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
 bool gemv_down_applicable(const Params &p, const __half *x, long long ldx);
+bool gemv_down_fits(const Params &p);
 int launch_gemv_down(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s,
                      float *part = nullptr, float *part_xs = nullptr, int part_batch = 0);
 int launch_groups_finish(const float *part, const float *part_xs, int n_groups, int batch, const Params &p, __half *y, long long ldy,
@@ -135,8 +136,9 @@ static bool down_mfma_wanted(const Params &p, const __half *x, long long ldx, in
 // With a workspace (column parts, one workgroup per block of 16 streams and part): from two rows on, and for any batch
 // when there are codebook groups (measured, 4096 x 4096: one row 12.8 against 10.5 us, two rows 13.0 against 12.7 us and
 // level from there; 16 groups, one row: 15.5 against 17.4 us).
+// (and for one row of a layer whose activations do not fit the other kernel's LDS beside the tables)
 static bool down_mfma_parts_wanted(const Params &p, const __half *x, long long ldx, int batch) {
-  return down_mfma_wanted(p, x, ldx, batch) && (batch >= 2 || p.n_groups > 1 || forced_kernel() == 'm');
+  return down_mfma_wanted(p, x, ldx, batch) && (batch >= 2 || p.n_groups > 1 || forced_kernel() == 'm' || !gemv_down_fits(p));
 }
 // Without a workspace a block of 16 streams is one workgroup over all the columns: with few blocks and three or four rows the
 // other kernel, which spreads single streams over the chip, is still ahead (4096 x 11008, 43 blocks: 26 against 34 us).
@@ -172,6 +174,10 @@ int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __ha
       }
       if (rc == VQ_OK) return VQ_OK;
       if (rc != VQ_ERR_UNSUPPORTED || done != 0) return rc;
+      if (down_mfma_wanted(p, x, ldx, batch)) {   // a row too long for that kernel's LDS (28672 columns beside two 64 KB tables)
+        rc = launch_gemv_down_mfma(p, x, ldx, batch, y, ldy, s, nullptr, nullptr, 1);
+        if (rc != VQ_ERR_UNSUPPORTED) return rc;
+      }
     }
     hipLaunchKernelGGL(gemv_down_kernel, dim3((unsigned)((p.S + 3) / 4)), dim3(256), 0, s, p, x, ldx, batch, y, ldy);
     return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;

@@ -386,11 +386,9 @@ bool gemv_down_applicable(const Params &p, const __half *x, long long ldx) {
   return (long long)p.S * max_stride < (1LL << 31);                          // 32-bit buffer offsets
 }
 
-// Launch for one group of 1, 2 or 4 batch rows.  VQ_ERR_UNSUPPORTED when the rows do not fit LDS beside the tables.
-// part != nullptr: a layer with codebook groups; the sums go to the workspace part[group][part_batch][out_features] (and
-// part_xs[group * 16 + token]), both already moved to this launch's first token.
-int launch_gemv_down(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s,
-                     float *part, float *part_xs, int part_batch) {
+namespace {
+// Work split and LDS layout for one group of `batch` rows; VQ_ERR_UNSUPPORTED when the rows do not fit LDS beside the tables.
+int make_plan(const Params &p, int batch, float *part, float *part_xs, int part_batch, DownPlan *out, unsigned *lds_bytes, unsigned *grid_out) {
   DownPlan plan{};
   if ((p.n_groups > 1) != (part != nullptr)) return VQ_ERR_UNSUPPORTED;
   plan.part = part; plan.part_xs = part_xs; plan.part_batch = part_batch;
@@ -398,6 +396,7 @@ int launch_gemv_down(const Params &p, const __half *x, long long ldx, int batch,
   unsigned off = rb == 0 ? Layout<0>::BYTES : rb == 8 ? Layout<8>::BYTES : Layout<12>::BYTES;
   plan.passes = (min(p.P, p.Pg) + 511) / 512;            // of the widest codebook group
   plan.x_row_bytes = (unsigned)plan.passes * 1024u;
+  if ((unsigned long long)plan.x_row_bytes * (unsigned)batch > 160u * 1024u) return VQ_ERR_UNSUPPORTED;
   plan.lds_x = off; off += plan.x_row_bytes * (unsigned)batch;
   plan.lds_xsum = off; off += (unsigned)(batch * DW) * 4u;
   plan.lds_part = off; off += (unsigned)(DW * 6 * batch) * 4u;
@@ -416,6 +415,28 @@ int launch_gemv_down(const Params &p, const __half *x, long long ldx, int batch,
   off += p.Q ? (unsigned)((plan.iters * (DW >> plan.ws_log2) * 6 + 1) * batch) * 4u : 0u;
   if (off > 160u * 1024u) return VQ_ERR_UNSUPPORTED;
   if (part) { plan.wgs_per_group = (int)grid; grid *= (unsigned)p.n_groups; }
+  *out = plan; *lds_bytes = off; *grid_out = grid;
+  return VQ_OK;
+}
+}  // namespace
+
+// Whether one row of a layer without codebook groups fits the kernel above (its activations beside the tables in LDS).
+bool gemv_down_fits(const Params &p) {
+  DownPlan plan;
+  unsigned off, grid;
+  return p.n_groups == 1 && make_plan(p, 1, nullptr, nullptr, 0, &plan, &off, &grid) == VQ_OK;
+}
+
+// Launch for one group of 1, 2 or 4 batch rows.  VQ_ERR_UNSUPPORTED when the rows do not fit LDS beside the tables.
+// part != nullptr: a layer with codebook groups; the sums go to the workspace part[group][part_batch][out_features] (and
+// part_xs[group * 16 + token]), both already moved to this launch's first token.
+int launch_gemv_down(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s,
+                     float *part, float *part_xs, int part_batch) {
+  DownPlan plan;
+  unsigned off, grid;
+  const int rc = make_plan(p, batch, part, part_xs, part_batch, &plan, &off, &grid);
+  if (rc != VQ_OK) return rc;
+  const int rb = p.k_res ? p.bits_res : 0;
 #define VQ_CASE(R, BB) if (rb == R && batch == BB) return launch_one<R, BB>(p, plan, off, grid, x, ldx, y, ldy, s);
   VQ_CASE(0, 1) VQ_CASE(12, 1) VQ_CASE(8, 1)
   VQ_CASE(0, 2) VQ_CASE(12, 2) VQ_CASE(8, 2)

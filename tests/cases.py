@@ -73,6 +73,7 @@ SMALL = {
                                      group_vectors=200, orientation=1),
     "down_fast_groups_outlier_tall": dict(out_features=5003, in_features=1240, v=6, k=4096, k_res=4096, n_outlier_cols=40, v_out=8,
                                           k_out=300, group_vectors=200, orientation=1),
+    "down_fast_long_rows_res12": dict(out_features=66, in_features=16000, v=6, k=4096, k_res=4096, orientation=1),
     "down_fast_groups_many": dict(out_features=5000, in_features=4096, v=6, k=4096, group_vectors=600, orientation=1),
     "down_dense_gemm": dict(out_features=203, in_features=1024, v=6, k=4096, k_res=4096, n_outlier_cols=16, v_out=4, k_out=4096, orientation=1),
 }

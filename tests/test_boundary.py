@@ -153,6 +153,11 @@ def test_gemv_workspace_for_vectors_down_the_output_dimension():
     # codebook groups are parts by themselves, from one row on
     grouped = _desc(orientation=1, out_features=96, in_features=1024, idx_row_stride=1536, v=6, k=4096, group_vectors=256)
     assert vq.vq_gemv_workspace_bytes(grouped, 1) >= 4 * (96 + 16) * 4
+    # so is a row too long for the one-row kernel's LDS (28672 activations beside two 64 KB tables)
+    long_rows = _desc(orientation=1, out_features=96, in_features=28672, idx_row_stride=43008, v=6, k=4096, k_res=4096,
+                      codebook_res=0x5000, idx_res=0x6000, idx_res_row_stride=43008)
+    assert vq.vq_validate(long_rows) == vq.VQ_OK
+    assert vq.vq_gemv_workspace_bytes(long_rows, 1) >= 2 * (96 + 16) * 4
 
 
 def test_assign_rejects_bad_arguments_before_any_launch():

@@ -251,7 +251,17 @@ def test_gemv_native_orientation_column_parts_with_workspace(gpu_lib, name, batc
     torch.cuda.synchronize()
     _check_matmul(y, oracle.gemv(L, x_np), "%s batch %d with workspace" % (name, batch))
     assert (ws[need:] == 0xFF).all()
-    assert gpu_lib.vq_gemv_workspace_bytes(dl.desc, 1) == 0      # a single row stays on the kernel that needs none
+    need1 = gpu_lib.vq_gemv_workspace_bytes(dl.desc, 1)
+    if name != "down_fast_long_rows_res12":
+        assert need1 == 0                # a single row stays on the kernel that needs none
+        return
+    # ... unless the row is too long for that kernel's LDS beside the tables: then one row runs in column parts as well,
+    # and without a workspace on the matrix-core kernel alone
+    assert need1 >= 2 * L.out_features * 4
+    for workspace in (ws[:need1], None):
+        y1 = gpu_lib.gemv(dl, x[:1], workspace=workspace)
+        torch.cuda.synchronize()
+        _check_matmul(y1, oracle.gemv(L, x_np[:1]), "%s one row, workspace %s" % (name, workspace is not None))
 
 
 @pytest.mark.parametrize("workspace", [None, "fast"])
