@@ -286,6 +286,14 @@ def detail(vq, s, np, torch, use_graph, skip):
     del rots, xs, ys
     # prefill GEMM and dequant on the 8192 x 8192, v=8, k=65536 layer
     _, L4 = next(s.config_layers(4))
+    # (first the decode-sized product on that layer: its 1 MB table stays in L2 and is gathered from there)
+    for batch in (1, 4, 16):
+        r = bench_gemv(vq, L4, s.make_activations(4, L4, batch), 200, 20, use_graph)
+        sec = r["event_s"] / 200
+        alg = L4.algorithmic_bytes(batch)
+        out.append({"op": "vq_gemv", "cfg": "4 (decode rows on the prefill layer)", "layer": L4.name, "batch": batch, "us": round(sec * 1e6, 3),
+                    "GB/s": round(alg / sec / 1e9, 1), "frac_hbm_peak": round(alg / sec / 1e9 / HBM_PEAK_GBPS, 4),
+                    "TFLOP/s": round(2.0 * batch * L4.out_features * L4.in_features / sec / 1e12, 2)})
     dl = vq.DeviceLayer(L4)
     for tokens in s.CONFIGS[4]["rows"]:
         X = torch.from_numpy(s.make_activations(4, L4, tokens)).cuda()
