@@ -114,6 +114,8 @@ bool gemv_down_applicable(const Params &p, const __half *x, long long ldx);
 bool gemv_down_fits(const Params &p);
 bool gemv_v8_applicable(const Params &p, const __half *x, long long ldx);
 int launch_gemv_v8(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
+bool gemv_v8_down_applicable(const Params &p);
+int launch_gemv_v8_down(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
 int launch_gemv_down(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s,
                      float *part = nullptr, float *part_xs = nullptr, int part_batch = 0);
 int launch_groups_finish(const float *part, const float *part_xs, int n_groups, int batch, const Params &p, __half *y, long long ldy,
@@ -180,6 +182,16 @@ int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __ha
         rc = launch_gemv_down_mfma(p, x, ldx, batch, y, ldy, s, nullptr, nullptr, 1);
         if (rc != VQ_ERR_UNSUPPORTED) return rc;
       }
+    }
+    if (!force_generic() && gemv_v8_down_applicable(p)) {
+      // 8-component vectors, tables read through L2: batch rows in launches of 4, 2 or 1
+      int done = 0, rc = VQ_OK;
+      while (done < batch && rc == VQ_OK) {
+        const int g = batch - done >= 4 ? 4 : batch - done >= 2 ? 2 : 1;
+        rc = launch_gemv_v8_down(p, x + done * ldx, ldx, g, y + done * ldy, ldy, s);
+        if (rc == VQ_OK) done += g;
+      }
+      if (rc != VQ_ERR_UNSUPPORTED || done != 0) return rc;
     }
     hipLaunchKernelGGL(gemv_down_kernel, dim3((unsigned)((p.S + 3) / 4)), dim3(256), 0, s, p, x, ldx, batch, y, ldy);
     return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;

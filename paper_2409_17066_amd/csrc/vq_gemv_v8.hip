@@ -93,6 +93,92 @@ int launch_one(const Params &p, const __half *x, long long ldx, __half *y, long 
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
 
+// The same for layers stored with vectors down the output dimension (Sec. 3.1, Algorithm 1: W[8s + j][c] =
+// C[idx[s][c]][j]): one workgroup per index stream, i.e. per 8 output rows; its DWAVES waves take contiguous quarters of
+// the columns, a lane keeps 8 sums per token (the entry's components as binary32, times the lane's activation), the
+// waves' sums meet in LDS.
+constexpr int DWAVES = 4;
+
+template <int B, int IB, int RB>
+__global__ __launch_bounds__(DWAVES * 64) void gemv_v8_down_kernel(Params p, const __half *__restrict__ x, long long ldx, __half *__restrict__ y,
+                                                                   long long ldy) {
+  __shared__ float red[DWAVES][B][9];            // per wave and token: 8 row sums and the activation sum
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int stream = blockIdx.x;                 // the grid has p.S workgroups
+  const uint8_t *irow = p.idx + (long long)stream * p.stride;
+  const uint8_t *rrow = RB ? p.idx_res + (long long)stream * p.stride_res : nullptr;
+  const bool with_bias = p.bias != nullptr;
+  const int per = (p.P + DWAVES * CHAINS * 64 - 1) / (DWAVES * CHAINS * 64) * (CHAINS * 64);   // columns per wave, whole steps
+  const int c0 = min(p.P, wv * per), c1 = min(p.P, c0 + per);
+  float acc[B][8], xs[B];
+#pragma unroll
+  for (int t = 0; t < B; ++t) {
+    xs[t] = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[t][j] = 0.0f;
+  }
+  for (int base = c0; base < c1; base += CHAINS * 64) {
+    half8v e[CHAINS], f[CHAINS];
+    int cc[CHAINS];
+    bool on[CHAINS];
+    unsigned i[CHAINS], r[CHAINS];
+#pragma unroll
+    for (int u = 0; u < CHAINS; ++u) {
+      const int c = base + u * 64 + lane;
+      on[u] = c < c1;
+      cc[u] = on[u] ? c : c1 - 1;                // c1 > c0 inside the loop: a column of this wave
+      i[u] = load_idx<IB>(irow, cc[u]);
+      if (RB) r[u] = load_idx<RB ? RB : 1>(rrow, cc[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < CHAINS; ++u) {
+      const long long group = p.n_groups > 1 ? cc[u] / p.Pg : 0;
+      e[u] = *reinterpret_cast<const half8v *>(p.cb + (group * p.k + min(i[u], (unsigned)p.k - 1u)) * 8);
+      if (RB) f[u] = *reinterpret_cast<const half8v *>(p.cb_res + (group * p.k_res + min(r[u], (unsigned)p.k_res - 1u)) * 8);
+    }
+#pragma unroll
+    for (int u = 0; u < CHAINS; ++u) {
+      float d[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) d[j] = RB ? (float)e[u][j] + (float)f[u][j] : (float)e[u][j];
+#pragma unroll
+      for (int t = 0; t < B; ++t) {
+        const float xv = on[u] ? __half2float(x[(long long)t * ldx + cc[u]]) : 0.0f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[t][j] = __fmaf_rn(d[j], xv, acc[t][j]);
+        xs[t] += xv;
+      }
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < B; ++t) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float sum = wave_sum(acc[t][j]);
+      if (lane == 0) red[wv][t][j] = sum;
+    }
+    const float xsum = wave_sum(xs[t]);
+    if (lane == 0) red[wv][t][8] = xsum;
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < B * 8) {
+    const int t = (int)threadIdx.x >> 3, j = (int)threadIdx.x & 7, o = stream * 8 + j;
+    float sum = 0.0f, xsum = 0.0f;
+#pragma unroll
+    for (int w = 0; w < DWAVES; ++w) { sum += red[w][t][j]; xsum += red[w][t][8]; }
+    if (o < p.out_features) {
+      const float sc = p.scale ? __half2float(p.scale[o]) : 1.0f, bi = with_bias ? __half2float(p.bias[o]) : 0.0f;
+      y[(long long)t * ldy + o] = __float2half_rn(__fmaf_rn(sc, sum, bi * xsum));
+    }
+  }
+}
+
+template <int B, int IB, int RB>
+int launch_one_down(const Params &p, const __half *x, long long ldx, __half *y, long long ldy, hipStream_t s) {
+  hipLaunchKernelGGL((gemv_v8_down_kernel<B, IB, RB>), dim3((unsigned)p.S), dim3(DWAVES * 64), 0, s, p, x, ldx, y, ldy);
+  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
 int index_bytes(int bits) { return bits == 8 ? 1 : bits == 16 ? 2 : 0; }
 
 }  // namespace
@@ -113,6 +199,25 @@ int launch_gemv_v8(const Params &p, const __half *x, long long ldx, int batch, _
 #define VQ_CASE(BB, IB, RB) if (batch == BB && ib == IB && rb == RB) return launch_one<BB, IB, RB>(p, x, ldx, y, ldy, s);
 #define VQ_CASES(BB) VQ_CASE(BB, 2, 0) VQ_CASE(BB, 2, 2) VQ_CASE(BB, 2, 1) VQ_CASE(BB, 1, 0) VQ_CASE(BB, 1, 1) VQ_CASE(BB, 1, 2)
   VQ_CASES(1) VQ_CASES(2) VQ_CASES(4) VQ_CASES(8)
+#undef VQ_CASES
+#undef VQ_CASE
+  return VQ_ERR_UNSUPPORTED;
+}
+
+// Layers of 8-component vectors down the output dimension, byte-aligned indices, no outlier columns.
+bool gemv_v8_down_applicable(const Params &p) {
+  if (p.orientation != 1 || p.v != 8 || p.Q != 0 || p.n_out != 0 || p.S < 1 || p.P < 1) return false;
+  if (!index_bytes(p.bits) || (p.k_res && !index_bytes(p.bits_res))) return false;
+  if ((reinterpret_cast<uintptr_t>(p.cb) & 15) || (p.k_res && (reinterpret_cast<uintptr_t>(p.cb_res) & 15))) return false;
+  return (p.stride & 1) == 0 && (!p.k_res || (p.stride_res & 1) == 0);
+}
+
+// batch = 1, 2 or 4 rows of x.  The caller has checked gemv_v8_down_applicable().
+int launch_gemv_v8_down(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
+  const int ib = index_bytes(p.bits), rb = p.k_res ? index_bytes(p.bits_res) : 0;
+#define VQ_CASE(BB, IB, RB) if (batch == BB && ib == IB && rb == RB) return launch_one_down<BB, IB, RB>(p, x, ldx, y, ldy, s);
+#define VQ_CASES(BB) VQ_CASE(BB, 2, 0) VQ_CASE(BB, 2, 2) VQ_CASE(BB, 2, 1) VQ_CASE(BB, 1, 0) VQ_CASE(BB, 1, 1) VQ_CASE(BB, 1, 2)
+  VQ_CASES(1) VQ_CASES(2) VQ_CASES(4)
 #undef VQ_CASES
 #undef VQ_CASE
   return VQ_ERR_UNSUPPORTED;
