@@ -198,7 +198,10 @@ int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __ha
   }
   const bool fast = !force_generic() && gemv_fast_applicable(p, x, ldx);
   const bool many_rows = p.out_features > 16 * 256;
-  if (fast && forced_kernel() != 'd' && (batch >= 3 || (batch == 2 && many_rows) || forced_kernel() == 'm' || p.n_groups > 1)) {
+  // (and layers with outlier columns, whose part of the dot-product kernels is the slower one: 11008 x 4096 with 128 of
+  // them, one row: 10.7 against 17.1 us; from 16384 columns on a single row is level or a little behind)
+  const bool outliers_first = p.Q > 0 && (batch >= 2 || p.in_features < 16384);
+  if (fast && forced_kernel() != 'd' && (batch >= 3 || (batch == 2 && many_rows) || forced_kernel() == 'm' || p.n_groups > 1 || outliers_first)) {
     const int rc = launch_gemv_mfma(p, x, ldx, batch, y, ldy, s);
     if (rc != VQ_ERR_UNSUPPORTED) return rc;
   }

@@ -48,6 +48,7 @@ struct MfmaPlan {
   int y_wide;                    // y rows allow 8-byte stores
   unsigned lds_sb;               // scale | bias << 16 of the workgroup's rows
   unsigned lds_yacc;             // grouped layers: binary32 sums of the groups so far, 1 KB per 16-row block
+  int out_global;                // 1: the outlier table stays in global memory (no room beside two 64 KB tables) and is gathered from there
 };
 
 // Which codebook groups a workgroup walks, and where their sums go: the finished fp16 outputs (part == nullptr), or --
@@ -207,7 +208,7 @@ __device__ __forceinline__ void gemv_v6_mfma_body(const Params &p, const MfmaPla
     // in registers through the main loop for the next group)
     unsigned tid = threadIdx.x;
     if (GROUPED) asm volatile("" : "+v"(tid));
-    tables.issue(p, grp, grp == 0, tid);
+    tables.issue(p, grp, grp == 0 && !plan.out_global, tid);
 #pragma unroll
     for (int j = 0; j < PA; ++j) {
 #pragma unroll
@@ -218,7 +219,7 @@ __device__ __forceinline__ void gemv_v6_mfma_body(const Params &p, const MfmaPla
     for (int d = 0; d < XD; ++d) issue_x(bxs[d], d % eff_passes);
     VQ_STAMP(1);
     wait_vmem_at_most<R * S + 8 * XD>();         // the tables are in; the index words may still be on their way
-    tables.store(p, lds, plan.lds_out, grp == 0, tid);
+    tables.store(p, lds, plan.lds_out, grp == 0 && !plan.out_global, tid);
   }
   // scale and bias of the workgroup's rows, one dword per row, for the reductions at the chunk ends
   for (int r = (int)threadIdx.x; r < (grp == (GROUPED ? gr.begin : 0) && !partial ? plan.rows_per_wg : 0); r += MW * 64) {
@@ -276,7 +277,14 @@ __device__ __forceinline__ void gemv_v6_mfma_body(const Params &p, const MfmaPla
                 Window<3> cw; cw.w[0] = wo[b].x; cw.w[1] = wo[b].y; cw.w[2] = wo[b].z;
                 uint2v e[VPL];
 #pragma unroll
-                for (int u = 0; u < VPL; ++u) lds_gather8(e[u], field_addr<12, 3>(cw, u) + a_out);
+                for (int u = 0; u < VPL; ++u) {
+                  if (plan.out_global) {       // (an index past a short table is clamped into it)
+                    const unsigned off = min(field_addr<12, 3>(cw, u), (unsigned)(p.k_out - 1) * 8u);
+                    e[u] = *reinterpret_cast<const uint2v *>(reinterpret_cast<const unsigned char *>(p.cb_out) + off);
+                  } else {
+                    lds_gather8(e[u], field_addr<12, 3>(cw, u) + a_out);
+                  }
+                }
                 lds_gather_wait();
 #pragma unroll
                 for (int u = 0; u < VPL; ++u) settle(e[u]);
@@ -575,7 +583,9 @@ int make_plan(const Params &p, int batch, long long ldx, const __half *y, long l
   if (p.in_features < 64) return VQ_ERR_UNSUPPORTED;      // idle lanes load the first 100 bytes of the first activation row
   const int rb = p.k_res ? p.bits_res : 0;
   unsigned off = rb == 0 ? Layout<0>::BYTES : rb == 8 ? Layout<8>::BYTES : Layout<12>::BYTES;
-  plan.lds_out = off; off += p.Q ? 4096u * 8u : 0u;
+  // the 32 KB outlier table goes into LDS too, unless two 64 KB tables are already there
+  plan.out_global = p.Q && rb == 12 ? 1 : 0;
+  plan.lds_out = off; off += p.Q && !plan.out_global ? 4096u * 8u : 0u;
   plan.lds_xs = off; off += (unsigned)waves * 16u * 4u;
   const int blocks_total = (p.out_features + 15) / 16;
   plan.rows_per_wg = blocks_per_wg * 16;

@@ -48,6 +48,7 @@ SMALL = {
     "grp_v6_narrow_res8": dict(out_features=3000, in_features=1150, v=6, k=4096, k_res=256, group_vectors=32),
     "grp_v6_small_tables": dict(out_features=70, in_features=391, v=6, k=3000, k_res=200, group_vectors=8),
     "grp_v6_unaligned": dict(out_features=70, in_features=800, v=6, k=4096, k_res=256, group_vectors=20),
+    "v6_res12_outliers_tall": dict(out_features=2500, in_features=1136, v=6, k=4096, k_res=4096, n_outlier_cols=136, v_out=4, k_out=300),   # outlier table left in global memory
     "grp_v6_dense_gemm": dict(out_features=203, in_features=1024, v=6, k=4096, k_res=4096, n_outlier_cols=16, v_out=4, k_out=4096, group_vectors=56),
     "grp_v8": dict(out_features=200, in_features=768, v=8, k=65536, group_vectors=40),
     "grp_odd": dict(out_features=37, in_features=203, v=5, k=37, k_res=11, n_outlier_cols=9, v_out=3, k_out=5, group_vectors=7),
