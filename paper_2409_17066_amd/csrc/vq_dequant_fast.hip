@@ -503,13 +503,15 @@ int launch_dequant_fast(const Params &p, __half *W, long long ldw, hipStream_t s
   plan.lds_res = offb; offb += p.k_res ? (1u << p.bits_res) * 16u : 0u;
   plan.lds_out = offb; offb += p.n_out ? 4096u * 8u : 0u;
   plan.lds_strip = offb; offb += NW * 768u;
-  if (offb > 160u * 1024u) return VQ_ERR_UNSUPPORTED;
   plan.main_chunks = (p.P + 63) / 64;
   plan.out_chunks = p.n_out ? (p.Q + 63) / 64 : 0;
   plan.total_chunks = (long long)(plan.main_chunks + plan.out_chunks) * p.out_features;
   plan.wide = (aligned16 && (p.n_out & 7) == 0) ? 1 : 0;
   static const bool strip_only = [] { const char *e = getenv("VQ_DEQUANT_KERNEL"); return e && e[0] == 's'; }();   // 's': never the wide kernel
-  if (plan.wide && p.n_groups == 1 && !strip_only && (long long)p.out_features * max(p.stride, p.stride_res) < (1LL << 31)) {
+  const bool wide_route = plan.wide && p.n_groups == 1 && !strip_only && (long long)p.out_features * max(p.stride, p.stride_res) < (1LL << 31);
+  // (the wide route keeps no outlier table in LDS: it also takes a 12-bit residual table together with outlier columns)
+  if (offb > 160u * 1024u && !wide_route) return VQ_ERR_UNSUPPORTED;
+  if (wide_route) {
     // aligned rows: the main columns by the wide kernel, the few outlier columns by the generic kernel
     const unsigned lds_res = 4096u * 16u, lds_strip = lds_res + (p.k_res ? (1u << p.bits_res) * 16u : 0u);
     const int waves = lds_strip + 16u * 3072u <= 160u * 1024u ? 16 : 8;
