@@ -192,30 +192,44 @@ __global__ __launch_bounds__(NW * 64) void dequant_v6_kernel(Params p, DqPlan pl
   }
 }
 
-__device__ __forceinline__ unsigned restore_pair_nores(unsigned main, float s, float b, bool lo_on, bool hi_on) {
-  const float lo = __half2float(__ushort_as_half((unsigned short)(main & 0xFFFFu)));
-  const float hi = __half2float(__ushort_as_half((unsigned short)(main >> 16)));
+__device__ __forceinline__ unsigned restore_pair_v8(unsigned main, unsigned res, bool has_res, float s, float b, bool lo_on, bool hi_on) {
+  float lo = __half2float(__ushort_as_half((unsigned short)(main & 0xFFFFu)));
+  float hi = __half2float(__ushort_as_half((unsigned short)(main >> 16)));
+  if (has_res) {
+    lo = __fadd_rn(lo, __half2float(__ushort_as_half((unsigned short)(res & 0xFFFFu))));
+    hi = __fadd_rn(hi, __half2float(__ushort_as_half((unsigned short)(res >> 16))));
+  }
   const unsigned rl = lo_on ? (unsigned)__half_as_ushort(restore(lo, s, b)) : 0u;
   const unsigned rh = hi_on ? (unsigned)__half_as_ushort(restore(hi, s, b)) : 0u;
   return rl | (rh << 16);
 }
 
-// v = 8, 16-bit indices, no residual, no outlier columns.  One lane per vector.
+// v = 8, indices of IB bytes, a residual table with indices of RB bytes (0: none), no outlier columns.  One lane per
+// vector; the 16-byte table entries come through L2.
+template <int IB, int RB>
 __global__ __launch_bounds__(256) void dequant_v8_kernel(Params p, __half *__restrict__ W, long long ldw, int wide, int blocks_per_row) {
   const int o = blockIdx.x / blocks_per_row;
   const int pp = (blockIdx.x % blocks_per_row) * 256 + threadIdx.x;
   if (pp >= p.P) return;
-  const unsigned short raw = reinterpret_cast<const unsigned short *>(p.idx + (long long)o * p.stride)[pp];
-  const unsigned i = min((unsigned)raw, (unsigned)p.k - 1u);
-  const uint4v e = reinterpret_cast<const uint4v *>(p.cb)[(size_t)(pp / p.Pg) * (size_t)p.k + i];   // its group's table
+  const uint8_t *irow = p.idx + (long long)o * p.stride;
+  const unsigned raw = IB == 2 ? (unsigned)reinterpret_cast<const unsigned short *>(irow)[pp] : (unsigned)irow[pp];
+  const unsigned i = min(raw, (unsigned)p.k - 1u);
+  const size_t group = (size_t)(pp / p.Pg);                                                          // its group's tables
+  const uint4v e = reinterpret_cast<const uint4v *>(p.cb)[group * (size_t)p.k + i];
+  uint4v f = {0u, 0u, 0u, 0u};
+  if (RB) {
+    const uint8_t *rrow = p.idx_res + (long long)o * p.stride_res;
+    const unsigned rraw = RB == 2 ? (unsigned)reinterpret_cast<const unsigned short *>(rrow)[pp] : (unsigned)rrow[pp];
+    f = reinterpret_cast<const uint4v *>(p.cb_res)[group * (size_t)p.k_res + min(rraw, (unsigned)p.k_res - 1u)];
+  }
   const float s = p.scale ? __half2float(p.scale[o]) : 1.0f;
   const float b = p.bias ? __half2float(p.bias[o]) : 0.0f;
   const int c0 = pp * 8, valid = min(8, p.in_features - c0);
   uint4v w;
-  w.x = restore_pair_nores(e.x, s, b, 0 < valid, 1 < valid);
-  w.y = restore_pair_nores(e.y, s, b, 2 < valid, 3 < valid);
-  w.z = restore_pair_nores(e.z, s, b, 4 < valid, 5 < valid);
-  w.w = restore_pair_nores(e.w, s, b, 6 < valid, 7 < valid);
+  w.x = restore_pair_v8(e.x, f.x, RB != 0, s, b, 0 < valid, 1 < valid);
+  w.y = restore_pair_v8(e.y, f.y, RB != 0, s, b, 2 < valid, 3 < valid);
+  w.z = restore_pair_v8(e.z, f.z, RB != 0, s, b, 4 < valid, 5 < valid);
+  w.w = restore_pair_v8(e.w, f.w, RB != 0, s, b, 6 < valid, 7 < valid);
   __half *dst = W + (long long)o * ldw + c0;
   if (wide && valid == 8) {
     *reinterpret_cast<uint4v *>(dst) = w;
@@ -487,11 +501,17 @@ int launch_dequant_fast(const Params &p, __half *W, long long ldw, hipStream_t s
   static const bool off = [] { const char *e = getenv("VQ_DEQUANT_KERNEL"); return e && e[0] == 'g'; }();
   if (off || p.orientation != 0) return VQ_ERR_UNSUPPORTED;
   const bool aligned16 = (reinterpret_cast<uintptr_t>(W) & 15) == 0 && (ldw & 7) == 0;
-  if (p.v == 8 && p.bits == 16 && p.k_res == 0 && p.n_out == 0) {
+  const int ib = p.bits == 16 ? 2 : p.bits == 8 ? 1 : 0, rbytes = !p.k_res ? 0 : p.bits_res == 16 ? 2 : p.bits_res == 8 ? 1 : -1;
+  if (p.v == 8 && ib && rbytes >= 0 && p.n_out == 0 && (reinterpret_cast<uintptr_t>(p.cb) & 15) == 0 &&
+      (!p.k_res || (reinterpret_cast<uintptr_t>(p.cb_res) & 15) == 0) && (p.stride & 1) == 0 && (!p.k_res || (p.stride_res & 1) == 0)) {
     const int bpr = (p.P + 255) / 256;
     const long long blocks = (long long)bpr * p.out_features;
     if (blocks > 0x7fffffffLL) return VQ_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(dequant_v8_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, W, ldw, aligned16 ? 1 : 0, bpr);
+    const int wide = aligned16 ? 1 : 0;
+#define VQ_CASE(IB, RB) \
+    if (ib == IB && rbytes == RB) hipLaunchKernelGGL((dequant_v8_kernel<IB, RB>), dim3((unsigned)blocks), dim3(256), 0, s, p, W, ldw, wide, bpr);
+    VQ_CASE(2, 0) VQ_CASE(2, 1) VQ_CASE(2, 2) VQ_CASE(1, 0) VQ_CASE(1, 1) VQ_CASE(1, 2)
+#undef VQ_CASE
     return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
   }
   if (p.v != 6 || p.bits != 12) return VQ_ERR_UNSUPPORTED;
