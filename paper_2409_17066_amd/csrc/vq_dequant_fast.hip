@@ -470,13 +470,60 @@ int launch_v6(const Params &p, DqPlan plan, unsigned lds_bytes, __half *W, long 
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
 
+// Orientation 1 with v = 8 (W[8s + j][c] = C[idx[s][c]][j]; Sec. 3.1, Algorithm 1), byte-aligned indices: one lane per
+// (stream, main column); its entry's eight components go to eight rows of one column, so a wave writes 128 contiguous
+// bytes of each of the eight rows.
+template <int IB, int RB>
+__global__ __launch_bounds__(256) void dequant_down_v8_kernel(Params p, __half *__restrict__ W, long long ldw, int blocks_per_stream) {
+  const int stream = blockIdx.x / blocks_per_stream;
+  const int pos = (blockIdx.x % blocks_per_stream) * 256 + threadIdx.x;
+  if (pos >= p.P) return;
+  const uint8_t *irow = p.idx + (long long)stream * p.stride;
+  const unsigned raw = IB == 2 ? (unsigned)reinterpret_cast<const unsigned short *>(irow)[pos] : (unsigned)irow[pos];
+  const size_t group = (size_t)(pos / p.Pg);
+  const uint4v e = reinterpret_cast<const uint4v *>(p.cb)[group * (size_t)p.k + min(raw, (unsigned)p.k - 1u)];
+  uint4v f = {0u, 0u, 0u, 0u};
+  if (RB) {
+    const uint8_t *rrow = p.idx_res + (long long)stream * p.stride_res;
+    const unsigned rraw = RB == 2 ? (unsigned)reinterpret_cast<const unsigned short *>(rrow)[pos] : (unsigned)rrow[pos];
+    f = reinterpret_cast<const uint4v *>(p.cb_res)[group * (size_t)p.k_res + min(rraw, (unsigned)p.k_res - 1u)];
+  }
+  const unsigned de[4] = {e.x, e.y, e.z, e.w}, df[4] = {f.x, f.y, f.z, f.w};
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int o = stream * 8 + j;
+    if (o < p.out_features) {
+      float d = __half2float(__ushort_as_half((unsigned short)(de[j >> 1] >> ((j & 1) * 16))));
+      if (RB) d = __fadd_rn(d, __half2float(__ushort_as_half((unsigned short)(df[j >> 1] >> ((j & 1) * 16)))));
+      const float sc = p.scale ? __half2float(p.scale[o]) : 1.0f, bi = p.bias ? __half2float(p.bias[o]) : 0.0f;
+      W[(long long)o * ldw + p.n_out + pos] = restore(d, sc, bi);
+    }
+  }
+}
+
 }  // namespace
 
-// Main columns of a layer of orientation 1 (v = 6, 12-bit indices, one codebook group); VQ_ERR_UNSUPPORTED otherwise.
+// Main columns of a layer of orientation 1 (v = 6, 12-bit indices, one codebook group; or v = 8, 8- or 16-bit indices, any
+// number of groups); VQ_ERR_UNSUPPORTED otherwise.
 // The outlier columns, if any, are the caller's (generic kernel).
 int launch_dequant_down_fast(const Params &p, __half *W, long long ldw, hipStream_t s) {
   static const bool off = [] { const char *e = getenv("VQ_DEQUANT_KERNEL"); return e && e[0] == 'g'; }();
-  if (off || p.orientation != 1 || p.v != 6 || p.bits != 12 || p.n_groups != 1) return VQ_ERR_UNSUPPORTED;
+  if (off || p.orientation != 1) return VQ_ERR_UNSUPPORTED;
+  {
+    const int ib = p.bits == 16 ? 2 : p.bits == 8 ? 1 : 0, rbytes = !p.k_res ? 0 : p.bits_res == 16 ? 2 : p.bits_res == 8 ? 1 : -1;
+    if (p.v == 8 && ib && rbytes >= 0 && (reinterpret_cast<uintptr_t>(p.cb) & 15) == 0 && (!p.k_res || (reinterpret_cast<uintptr_t>(p.cb_res) & 15) == 0) &&
+        (p.stride & 1) == 0 && (!p.k_res || (p.stride_res & 1) == 0)) {
+      const int bps = (p.P + 255) / 256;
+      const long long blocks = (long long)bps * p.S;
+      if (blocks > 0x7fffffffLL) return VQ_ERR_UNSUPPORTED;
+#define VQ_CASE(IB, RB) \
+      if (ib == IB && rbytes == RB) hipLaunchKernelGGL((dequant_down_v8_kernel<IB, RB>), dim3((unsigned)blocks), dim3(256), 0, s, p, W, ldw, bps);
+      VQ_CASE(2, 0) VQ_CASE(2, 1) VQ_CASE(2, 2) VQ_CASE(1, 0) VQ_CASE(1, 1) VQ_CASE(1, 2)
+#undef VQ_CASE
+      return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+    }
+  }
+  if (p.v != 6 || p.bits != 12 || p.n_groups != 1) return VQ_ERR_UNSUPPORTED;
   if (p.k_res && p.bits_res != 12 && p.bits_res != 8) return VQ_ERR_UNSUPPORTED;
   if ((long long)p.S * max(p.stride, p.stride_res) >= (1LL << 31)) return VQ_ERR_UNSUPPORTED;      // 32-bit buffer offsets
   const unsigned lds_res = 4096u * 16u;

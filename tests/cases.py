@@ -58,6 +58,7 @@ SMALL = {
     "down_v6_res_outlier": dict(out_features=150, in_features=1207, v=6, k=4096, k_res=256, n_outlier_cols=25, v_out=4, k_out=4096, orientation=1),
     "down_v8_k65536": dict(out_features=200, in_features=520, v=8, k=65536, orientation=1),
     "down_v8_k256_res65536": dict(out_features=203, in_features=1100, v=8, k=256, k_res=65536, orientation=1),   # a ragged last stream; one wave without columns
+    "down_v8_outliers": dict(out_features=100, in_features=612, v=8, k=65536, k_res=256, n_outlier_cols=12, v_out=4, k_out=16, orientation=1),
     "down_v8_groups_res256": dict(out_features=64, in_features=3001, v=8, k=65536, k_res=256, group_vectors=300, orientation=1, with_bias=False),
     "down_groups": dict(out_features=133, in_features=1000, v=6, k=4096, k_res=4096, group_vectors=100, orientation=1),
     "down_odd": dict(out_features=37, in_features=203, v=5, k=37, k_res=11, n_outlier_cols=9, v_out=3, k_out=5, orientation=1),
