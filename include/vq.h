@@ -172,7 +172,10 @@ int vq_assign_down(const void *W, const void *B, int64_t ld, int32_t rows, int32
  *  - if it holds vq_gemm_fast_workspace_bytes(desc, tokens) bytes (non-zero when in_features is a
  *    multiple of 256), the call restores W into it once (as vq_dequant does) and multiplies from
  *    there, which is the faster route on this GPU; with less, the restored weights go straight from
- *    on-chip tiles into the matrix cores and W is never written to memory.                          */
+ *    on-chip tiles into the matrix cores and W is never written to memory.
+ * Small token counts (too few tiles to fill the chip), and layers whose only tile kernel without a
+ * workspace is the generic one, are computed as vq_gemv computes them, sixteen rows of X at a time,
+ * where that is the faster way on this GPU: same result bar, nothing for the caller to do.          */
 int vq_gemm(const vq_layer_desc *desc, const void *X, int64_t ldx, int32_t tokens,
             void *Y, int64_t ldy, void *workspace, size_t workspace_bytes, void *hip_stream);
 size_t vq_gemm_workspace_bytes(const vq_layer_desc *desc, int32_t tokens);

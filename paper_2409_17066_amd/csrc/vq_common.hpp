@@ -33,6 +33,7 @@ int make_params(const vq_layer_desc *d, Params *p);
 int launch_dequant(const Params &p, __half *W, long long ldw, hipStream_t s);
 int launch_dequant_outliers(const Params &p, __half *W, long long ldw, hipStream_t s);   // generic kernel, outlier columns of a row-wise layer only
 int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
+bool gemv_has_fast_kernel(const Params &p, const __half *x, long long ldx);
 size_t gemv_workspace_bytes(const Params &p, const __half *x, long long ldx, int batch);
 int launch_gemv_ws(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, void *workspace,
                    size_t workspace_bytes, hipStream_t s);

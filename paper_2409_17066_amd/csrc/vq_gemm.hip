@@ -181,6 +181,24 @@ int launch_gemm(const Params &p, const __half *X, long long ldx, int tokens, __h
   // measured on the 8192 x 8192 v=8 layer: up to 512 tokens restoring on the fly is still ahead (167 vs 184 us), from
   // 1024 tokens on the restored matrix wins (215 vs 267 us, 365 vs 407 us at 2048); VQ_GEMM_KERNEL=w takes it always
   const bool worth_it = forced == 'w' || !gemm_fused_applicable(p) || tokens > 512;
+  const bool have_ws = fast && workspace && workspace_bytes >= fast && (reinterpret_cast<uintptr_t>(workspace) & 15) == 0;
+  // Layers that only the generic tile kernel would take (no workspace and not the v = 8 layout of the fused kernel), and
+  // token counts too small for the restored-matrix route to fill the chip with tiles, go through vq_gemv's kernels sixteen
+  // rows at a time where that was measured faster.  Row-wise v = 6 layers (the matrix-core GEMV, whose sixteen rows cost
+  // little more than one): always without a workspace, up to 96 tokens with one -- 4096 x 4096, 64 tokens 42 us against
+  // 83 us with a workspace and 667 us without; 512 tokens without a workspace 322 against 700 us.  The other layers with
+  // a specialised GEMV kernel (v = 8; orientation 1), whose cost grows faster with the rows: only without a workspace and
+  // up to 128 tokens (v = 8, k = 65536 with a residual, 64 tokens: 191 against 848 us; 512 tokens would be 1480 against 880).
+  // VQ_GEMM_KERNEL=r: always.
+  const bool rows_cheap = p.orientation == 0 && p.v == 6;
+  if (forced == 'r' || (forced == '\0' && !gemm_fused_applicable(p) && gemv_has_fast_kernel(p, X, ldx) &&
+                        (rows_cheap ? (!have_ws || tokens <= 96) : (!have_ws && tokens <= 128)))) {
+    for (int t0 = 0; t0 < tokens; t0 += 16) {
+      const int rc = launch_gemv(p, X + (long long)t0 * ldx, ldx, tokens - t0 < 16 ? tokens - t0 : 16, Y + (long long)t0 * ldy, ldy, s);
+      if (rc != VQ_OK) return rc;
+    }
+    return VQ_OK;
+  }
   if (forced != 'g' && forced != 'f' && worth_it && fast && workspace && workspace_bytes >= fast &&
       (reinterpret_cast<uintptr_t>(workspace) & 15) == 0) {
     __half *Wd = static_cast<__half *>(workspace);

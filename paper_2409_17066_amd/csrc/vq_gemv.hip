@@ -153,6 +153,14 @@ static bool down_mfma_alone_wanted(const Params &p, const __half *x, long long l
   return batch >= 5 || (batch >= 3 && (p.S >= 64 * 16 || (p.k_res && p.bits_res == 12))) || forced_kernel() == 'm';
 }
 
+// Whether vq_gemv has one of its specialised kernels for this layer and these activations (vq_gemm sends small token
+// counts, and layers its own kernels do not take, through vq_gemv sixteen rows at a time).
+bool gemv_has_fast_kernel(const Params &p, const __half *x, long long ldx) {
+  if (forced_kernel() != '\0') return false;
+  if (p.orientation == 1) return down_mfma_wanted(p, x, ldx, 16) || gemv_v8_down_applicable(p);
+  return gemv_fast_applicable(p, x, ldx) || gemv_v8_applicable(p, x, ldx);
+}
+
 int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
   // Matrix-core kernel: one launch for any batch, at about the cost of a batch-1 launch of the dot-product
   // kernels; those are still a little faster for one row (and for two rows of a layer with few output rows

@@ -480,7 +480,10 @@ static int make_plan(const Params &p, long long ldx, int batch, float *part, flo
   plan.sub = part ? plan.ksplit / p.n_groups : 1;      // without a workspace: one workgroup per block walks all groups and all windows
   plan.wpp = (windows + plan.sub - 1) / plan.sub;
   plan.batch = batch;
-  plan.x_bytes = (unsigned)(((long long)(batch - 1) * ldx + p.in_features) * 2);
+  // (a whole number of dwords: the buffer's range check drops a dword that straddles the end, and with it the last
+  // column of the last row when in_features is odd; ldx is a multiple of 8 here, so the half after it is the caller's
+  // padding, and the kernel masks it like every position past the stream's end)
+  plan.x_bytes = (unsigned)((((long long)(batch - 1) * ldx + p.in_features) * 2 + 3) & ~3LL);
   plan.part = part; plan.part_xs = part_xs;
   plan.o_pitch = ((p.Q + 1) / 2) | 1;
   plan.o_rpw = (int)((p.out_features + (long long)blocks * plan.ksplit - 1) / ((long long)blocks * plan.ksplit));   // <= 96: a block has 96 rows

@@ -267,7 +267,8 @@ def test_gemv_native_orientation_column_parts_with_workspace(gpu_lib, name, batc
 @pytest.mark.parametrize("workspace", [None, "fast"])
 @pytest.mark.parametrize("batch", [1, 3, 5, 16])
 @pytest.mark.parametrize("name,pad_x,pad_y", [("down_fast_res12", 8, 1), ("down_fast_outlier", 24, 6), ("down_fast_parts", 16, 3),
-                                               ("down_fast_groups_outlier_tall", 8, 5)])
+                                               ("down_fast_groups_outlier_tall", 8, 5),
+                                               ("down_v6", 1, 3)])       # 391 columns: the last row ends inside a dword
 def test_native_orientation_strided_buffers_and_untouched_padding(gpu_lib, name, pad_x, pad_y, batch, workspace):
     """Vectors down the output dimension, fast kernels (row stride of x a multiple of 8): NaN in the caller's padding of x
     must never reach a sum, and sentinels in the padding of y must survive; with and without the workspace route."""
