@@ -283,3 +283,37 @@ def test_native_orientation_strided_buffers_and_untouched_padding(gpu_lib, name,
     torch.cuda.synchronize()
     _check_matmul(yb[:, : L.out_features], oracle.gemv(L, x), "strided %s batch %d workspace %s" % (name, batch, workspace))
     assert (yb[:, L.out_features:] == 7.0).all()
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_eight_component_layers_random_shapes(gpu_lib, seed):
+    """Layers of 8-component vectors in both orientations with random sizes, table sizes (8- and 16-bit indices), residual
+    tables and codebook groups: vq_dequant bit for bit, vq_gemv on padded buffers (NaN in x's padding, sentinels in y's)."""
+    import torch
+    rng = np.random.default_rng(4321 + seed)
+    orientation = seed % 2
+    out, P = int(rng.integers(1, 1500)), int(rng.integers(1, 700))
+    k = int(rng.choice([65536, 256, 40000, 200, 17]))
+    kw = {}
+    r = int(rng.integers(0, 3))
+    if r == 1:
+        kw["k_res"] = int(rng.choice([256, 100]))
+    if r == 2:
+        kw["k_res"] = int(rng.choice([65536, 5000]))
+    if rng.integers(0, 3) == 0:
+        kw["group_vectors"] = int(rng.integers(1, max(2, P)))
+    in_features = P * 8 if orientation == 0 else int(rng.integers(1, 3000))
+    L = s.make_layer(9200 + seed, "v8_random_%d" % seed, out, in_features, 8, k, orientation=orientation, **kw)
+    dl = gpu_lib.DeviceLayer(L)
+    W = gpu_lib.dequant(dl)
+    torch.cuda.synchronize()
+    assert np.array_equal(W.cpu().numpy().view(np.uint16), oracle.dequant(L).view(np.uint16)), (out, in_features, k, kw)
+    for batch in (1, 2, int(rng.integers(3, 17))):
+        x = s.make_activations(9200 + seed, L, batch)
+        xb = torch.full((batch, (in_features + 7) // 8 * 8 + 8), float("nan"), dtype=torch.float16, device="cuda")
+        xb[:, :in_features] = torch.from_numpy(x).cuda()
+        yb = torch.full((batch, out + 3), 7.0, dtype=torch.float16, device="cuda")
+        gpu_lib.gemv(dl, xb, out=yb)
+        torch.cuda.synchronize()
+        _check_matmul(yb[:, :out], oracle.gemv(L, x), "v = 8, orientation %d, %d x %d, k %d, %s, batch %d" % (orientation, out, in_features, k, kw, batch))
+        assert (yb[:, out:] == 7.0).all()
