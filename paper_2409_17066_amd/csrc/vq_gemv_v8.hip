@@ -34,63 +34,100 @@ template <int BYTES> __device__ __forceinline__ unsigned load_idx(const uint8_t 
 
 constexpr int WAVES = 4, CHAINS = 4;
 
-// B rows of x; IB / RB: bytes per main / residual index (RB = 0: no residual table).
-template <int B, int IB, int RB>
+// B rows of x; IB / RB: bytes per main / residual index (RB = 0: no residual table); R output rows per wave.  With
+// R = 2 a wave walks two rows at once, CHAINS / 2 chains each: as many gathers in flight, but every activation it
+// loads serves both rows -- x is otherwise re-read once per output row, which is what four and more tokens pay for.
+template <int B, int IB, int RB, int R>
 __global__ __launch_bounds__(WAVES * 64) void gemv_v8_kernel(Params p, const __half *__restrict__ x, long long ldx, __half *__restrict__ y,
                                                              long long ldy) {
+  constexpr int NC = CHAINS / R;
   const int lane = threadIdx.x & 63;
-  const int o = blockIdx.x * WAVES + (threadIdx.x >> 6);
-  if (o >= p.out_features) return;
-  const uint8_t *irow = p.idx + (long long)o * p.stride;
-  const uint8_t *rrow = RB ? p.idx_res + (long long)o * p.stride_res : nullptr;
+  const int o0 = (blockIdx.x * WAVES + (threadIdx.x >> 6)) * R;
+  if (o0 >= p.out_features) return;
+  const uint8_t *irow[R], *rrow[R];
+#pragma unroll
+  for (int q = 0; q < R; ++q) {                   // a row past the last one repeats the last and is not stored
+    const int o = min(o0 + q, p.out_features - 1);
+    irow[q] = p.idx + (long long)o * p.stride;
+    rrow[q] = RB ? p.idx_res + (long long)o * p.stride_res : nullptr;
+  }
   const half8v ones = {1, 1, 1, 1, 1, 1, 1, 1}, zeros = {0, 0, 0, 0, 0, 0, 0, 0};
   const bool with_bias = p.bias != nullptr;
-  float acc[B], xs[B];
+  float acc[R][B], xs[B];
 #pragma unroll
-  for (int t = 0; t < B; ++t) { acc[t] = 0.0f; xs[t] = 0.0f; }
-  for (int base = 0; base < p.P; base += CHAINS * 64) {
-    half8v e[CHAINS], f[CHAINS];
-    int pvc[CHAINS];
-    bool on[CHAINS];
-    unsigned i[CHAINS], r[CHAINS];
+  for (int t = 0; t < B; ++t) {
+    xs[t] = 0.0f;
 #pragma unroll
-    for (int u = 0; u < CHAINS; ++u) {            // the step's index loads first, all of them ...
+    for (int q = 0; q < R; ++q) acc[q][t] = 0.0f;
+  }
+  for (int base = 0; base < p.P; base += NC * 64) {
+    half8v e[NC][R], f[NC][R];
+    int pvc[NC];
+    bool on[NC];
+    unsigned i[NC][R], r[NC][R];
+#pragma unroll
+    for (int u = 0; u < NC; ++u) {                // the step's index loads first, all of them ...
       const int pv = base + u * 64 + lane;
       on[u] = pv < p.P;
       pvc[u] = on[u] ? pv : p.P - 1;
-      i[u] = load_idx<IB>(irow, pvc[u]);
-      if (RB) r[u] = load_idx<RB ? RB : 1>(rrow, pvc[u]);
+#pragma unroll
+      for (int q = 0; q < R; ++q) {
+        i[u][q] = load_idx<IB>(irow[q], pvc[u]);
+        if (RB) r[u][q] = load_idx<RB ? RB : 1>(rrow[q], pvc[u]);
+      }
     }
 #pragma unroll
-    for (int u = 0; u < CHAINS; ++u) {            // ... then its gathers (indices past a short table are clamped into it)
+    for (int u = 0; u < NC; ++u) {                // ... then its gathers (indices past a short table are clamped into it)
       const long long group = p.n_groups > 1 ? pvc[u] / p.Pg : 0;
-      e[u] = *reinterpret_cast<const half8v *>(p.cb + (group * p.k + min(i[u], (unsigned)p.k - 1u)) * 8);
-      if (RB) f[u] = *reinterpret_cast<const half8v *>(p.cb_res + (group * p.k_res + min(r[u], (unsigned)p.k_res - 1u)) * 8);
+#pragma unroll
+      for (int q = 0; q < R; ++q) {
+        e[u][q] = *reinterpret_cast<const half8v *>(p.cb + (group * p.k + min(i[u][q], (unsigned)p.k - 1u)) * 8);
+        if (RB) f[u][q] = *reinterpret_cast<const half8v *>(p.cb_res + (group * p.k_res + min(r[u][q], (unsigned)p.k_res - 1u)) * 8);
+      }
     }
 #pragma unroll
-    for (int u = 0; u < CHAINS; ++u) {
+    for (int u = 0; u < NC; ++u) {
 #pragma unroll
       for (int t = 0; t < B; ++t) {
         half8v xv = *reinterpret_cast<const half8v *>(x + (long long)t * ldx + (long long)pvc[u] * 8);
         if (!on[u]) xv = zeros;
-        acc[t] = dot8(e[u], xv, acc[t]);
-        if (RB) acc[t] = dot8(f[u], xv, acc[t]);
+#pragma unroll
+        for (int q = 0; q < R; ++q) {
+          acc[q][t] = dot8(e[u][q], xv, acc[q][t]);
+          if (RB) acc[q][t] = dot8(f[u][q], xv, acc[q][t]);
+        }
         if (with_bias) xs[t] = dot8(ones, xv, xs[t]);
       }
     }
   }
-  const float sc = p.scale ? __half2float(p.scale[o]) : 1.0f, bi = with_bias ? __half2float(p.bias[o]) : 0.0f;
 #pragma unroll
   for (int t = 0; t < B; ++t) {
-    const float sum = wave_sum(acc[t]), xsum = with_bias ? wave_sum(xs[t]) : 0.0f;
-    if (lane == 0) y[(long long)t * ldy + o] = __float2half_rn(__fmaf_rn(sc, sum, bi * xsum));
+    const float xsum = with_bias ? wave_sum(xs[t]) : 0.0f;
+#pragma unroll
+    for (int q = 0; q < R; ++q) {
+      const float sum = wave_sum(acc[q][t]);
+      const int o = o0 + q;
+      if (lane == 0 && o < p.out_features) {
+        const float sc = p.scale ? __half2float(p.scale[o]) : 1.0f, bi = with_bias ? __half2float(p.bias[o]) : 0.0f;
+        y[(long long)t * ldy + o] = __float2half_rn(__fmaf_rn(sc, sum, bi * xsum));
+      }
+    }
   }
 }
 
+template <int B, int IB, int RB, int R>
+int launch_rows(const Params &p, const __half *x, long long ldx, __half *y, long long ldy, hipStream_t s) {
+  hipLaunchKernelGGL((gemv_v8_kernel<B, IB, RB, R>), dim3((unsigned)((p.out_features + WAVES * R - 1) / (WAVES * R))), dim3(WAVES * 64), 0, s, p, x, ldx,
+                     y, ldy);
+  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+// Two rows per wave from four tokens and 8192 columns on, where the re-reading of x weighs more than the halved number of
+// waves (batch 8: 8192 x 8192 74 -> 66 us, 8192 x 28672 242 -> 203 us; 4096 x 4096 would go from 22.3 to 23.5 us).
 template <int B, int IB, int RB>
 int launch_one(const Params &p, const __half *x, long long ldx, __half *y, long long ldy, hipStream_t s) {
-  hipLaunchKernelGGL((gemv_v8_kernel<B, IB, RB>), dim3((unsigned)((p.out_features + WAVES - 1) / WAVES)), dim3(WAVES * 64), 0, s, p, x, ldx, y, ldy);
-  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+  if (B >= 4 && p.in_features >= 8192) return launch_rows<B, IB, RB, (B >= 4 ? 2 : 1)>(p, x, ldx, y, ldy, s);
+  return launch_rows<B, IB, RB, 1>(p, x, ldx, y, ldy, s);
 }
 
 // The same for layers stored with vectors down the output dimension (Sec. 3.1, Algorithm 1: W[8s + j][c] =

@@ -11,6 +11,7 @@ SMALL = {
     "v8_fused_path": dict(out_features=200, in_features=768, v=8, k=65536),                # in % 256 == 0: the fused MFMA kernel
     "v8_k256": dict(out_features=131, in_features=2056, v=8, k=256),                         # 8-bit indices; 257 vectors: one past a step of 256
     "v8_k65536_res256": dict(out_features=203, in_features=4096, v=8, k=65536, k_res=256),   # the residual setting of the 2-bit tables
+    "v8_long_rows": dict(out_features=203, in_features=8200, v=8, k=65536, k_res=256),        # from 8192 columns on a wave takes two rows (203: a last wave with one)
     "v8_k65536_res65536": dict(out_features=77, in_features=1536, v=8, k=65536, k_res=65536),
     "v8_k200_res40000": dict(out_features=2050, in_features=264, v=8, k=200, k_res=40000, with_scale=False),
     "v8_k65536_unscaled": dict(out_features=129, in_features=264, v=8, k=65536, with_scale=False, with_bias=False),
