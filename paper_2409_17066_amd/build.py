@@ -12,21 +12,21 @@ except ImportError:                      # run as a script
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvq.so")
-SOURCES = ["vq_api.hip", "vq_dequant.hip", "vq_dequant_fast.hip", "vq_gemv.hip", "vq_gemv_fast.hip", "vq_gemv_mfma.hip", "vq_gemm.hip", "vq_gemm_fused.hip", "vq_assign.hip", "vq_gemv_down.hip", "vq_gemv_down_mfma.hip", "vq_gemv_v8.hip"]
+SOURCES = ["vq_api.hip", "vq_dequant.hip", "vq_dequant_fast.hip", "vq_gemv.hip", "vq_gemv_fast.hip", "vq_gemv_res8.hip", "vq_gemv_mfma.hip", "vq_gemm.hip", "vq_gemm_fused.hip", "vq_assign.hip", "vq_gemv_down.hip", "vq_gemv_down_mfma.hip", "vq_gemv_v8.hip"]
 # packed-FP32 VALU forms are switched off for every device compile (they are not trusted on the test machines)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument"]
 # Kernels in these files load registers asynchronously from inline assembly and wait for them with counted
 # s_waitcnt.  The compiler does not know such a register is pending: if it spilled one, it would save the old
 # contents.  Their kernels must therefore not spill at all; the build reads the compiler's resource remarks.
-NO_SPILL = {"vq_gemv_mfma.hip", "vq_gemm_fused.hip", "vq_gemv_down.hip", "vq_gemv_down_mfma.hip"}
+NO_SPILL = {"vq_gemv_mfma.hip", "vq_gemm_fused.hip", "vq_gemv_down.hip", "vq_gemv_down_mfma.hip", "vq_gemv_fast.hip", "vq_gemv_res8.hip"}
 # One exception, checked in the generated code of this image's compiler (ROCm 7.2): the 512-token GEMM tile saves
 # five address registers at kernel entry, before its first asynchronous load, and reloads them in the epilogue.
 SPILLS_ALLOWED = {"gemm_v8_kernelILi512E": 5}
 REMARKS = ["-Rpass-analysis=kernel-resource-usage"]
 # The same files, and the dot-product GEMV with its hand-issued LDS reads, get their device assembly audited for
 # instructions that touch a register while an inline-assembly load into it is pending (check_async.py).
-AUDITED = ["vq_gemv_mfma.hip", "vq_gemm_fused.hip", "vq_gemv_fast.hip", "vq_gemv_down.hip", "vq_gemv_down_mfma.hip"]
+AUDITED = ["vq_gemv_mfma.hip", "vq_gemm_fused.hip", "vq_gemv_fast.hip", "vq_gemv_res8.hip", "vq_gemv_down.hip", "vq_gemv_down_mfma.hip"]
 
 
 def check_no_spills(src: str, remarks: str) -> None:

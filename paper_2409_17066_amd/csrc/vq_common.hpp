@@ -75,10 +75,12 @@ __device__ __forceinline__ __half restore(float d, float scale, float bias) {
 // compiler loads arguments lazily, a few at a time, each group waiting for its own miss in the scalar cache
 // (the segment is written by the host just before the launch); issuing one load per line up front overlaps
 // those misses, and the later argument loads hit.
-__device__ __forceinline__ void warm_kernel_arguments() {      // first four lines = 256 bytes
+template <int LINES = 4>
+__device__ __forceinline__ void warm_kernel_arguments() {      // the first LINES (4 or 5) lines of 64 bytes
 #if defined(__HIP_DEVICE_COMPILE__)
   const auto ka = __builtin_amdgcn_kernarg_segment_ptr();
-  unsigned a, b, c, d;
+  unsigned a, b, c, d, e;
+  if constexpr (LINES >= 5) asm volatile("s_load_dword %0, %1, 0x100" : "=&s"(e) : "s"(ka) : "memory");
   asm volatile("s_load_dword %0, %4, 0x0\n\ts_load_dword %1, %4, 0x40\n\ts_load_dword %2, %4, 0x80\n\t"
                "s_load_dword %3, %4, 0xc0\n\ts_waitcnt lgkmcnt(0)"
                : "=&s"(a), "=&s"(b), "=&s"(c), "=&s"(d) : "s"(ka) : "memory");

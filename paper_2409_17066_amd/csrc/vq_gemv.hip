@@ -107,6 +107,8 @@ __global__ __launch_bounds__(256) void gemv_down_kernel(Params p, const __half *
 }
 
 bool gemv_fast_applicable(const Params &p, const __half *x, long long ldx);
+bool gemv_res8_applicable(const Params &p, const __half *x);
+int launch_gemv_res8(const Params &p, const __half *x, __half *y, hipStream_t s);
 int launch_gemv_fast(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
 
 int launch_gemv_mfma(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
@@ -203,6 +205,14 @@ int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __ha
     }
     hipLaunchKernelGGL(gemv_down_kernel, dim3((unsigned)((p.S + 3) / 4)), dim3(256), 0, s, p, x, ldx, batch, y, ldy);
     return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+  }
+  // one activation row of a long-row layer with an 8-bit residual stream (the 8192 x 28672 layer of the 70B setting): the
+  // kernel that replicates the residual table in LDS and keeps the activations out of it.  Measured against the other
+  // dot-product kernel: 28672 columns 33.5 against 37.0 us; 8192 columns 16.0 against 14.7 us, hence the threshold
+  // (VQ_GEMV_KERNEL=d takes it for every layer it accepts, for the tests).
+  if (batch == 1 && gemv_res8_applicable(p, x) && ((forced_kernel() == '\0' && p.in_features >= 16384) || forced_kernel() == 'd')) {
+    const int rc = launch_gemv_res8(p, x, y, s);
+    if (rc != VQ_ERR_UNSUPPORTED) return rc;
   }
   const bool fast = !force_generic() && gemv_fast_applicable(p, x, ldx);
   const bool many_rows = p.out_features > 16 * 256;
