@@ -126,6 +126,18 @@ size_t vq_gemv_workspace_bytes(const vq_layer_desc *desc, int32_t batch);
 int vq_gemv_with_workspace(const vq_layer_desc *desc, const void *x, int64_t ldx, int32_t batch, void *y, int64_t ldy,
                            void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* vq_gemv_with_workspace for callers that cannot allocate device memory or hand a workspace over: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The workspace is a device array inside this library,
+ * VQ_GEMV_STATIC_WORKSPACE_BYTES per GPU, which the GPU holds from the library's load to the end of the process; the call
+ * allocates and frees nothing.  A layer and batch whose vq_gemv_workspace_bytes exceeds that size is refused with
+ * VQ_ERR_WORKSPACE (nothing is launched); otherwise arguments, results and errors are those of vq_gemv_with_workspace
+ * with a workspace of the size it asks for.  The kernels write every workspace element before they read it, so nothing
+ * has to be cleared between calls.  All calls on one GPU share that GPU's array: calls that overlap in time on one GPU
+ * (different streams or threads) race on it and must be ordered by the caller.                                     */
+#define VQ_GEMV_STATIC_WORKSPACE_BYTES (16u << 20)
+int vq_gemv_static_workspace(const vq_layer_desc *desc, const void *x, int64_t ldx, int32_t batch, void *y, int64_t ldy,
+                             void *hip_stream);
+
 /* vq_gemv for several layers that read the same activations -- the query, key and value projections of a
  * decoder layer, or its gate and up projections -- as one launch: y[i][b][o] = sum_c W_i[o][c] * x[b][c] for
  * i < n_layers, each result to vq_gemv's bar for that layer (the same kernel bodies run; deterministic run to run).

@@ -57,6 +57,7 @@ def load():
     L.vq_gemv_workspace_bytes.restype = ctypes.c_size_t
     L.vq_gemv_with_workspace.argtypes = [P, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
                                          ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    L.vq_gemv_static_workspace.argtypes = L.vq_gemv.argtypes
     L.vq_gemv_multi.argtypes = [ctypes.POINTER(P), ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32,
                                 ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_int64), ctypes.c_void_p]
     L.vq_assign.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
@@ -71,13 +72,13 @@ def load():
     L.vq_status_string.argtypes = [ctypes.c_int]
     L.vq_status_string.restype = ctypes.c_char_p
     L.vq_version.restype = ctypes.c_int
-    for f in (L.vq_validate, L.vq_dequant, L.vq_gemv, L.vq_gemv_with_workspace, L.vq_gemv_multi, L.vq_gemm, L.vq_assign, L.vq_assign_down):
+    for f in (L.vq_validate, L.vq_dequant, L.vq_gemv, L.vq_gemv_with_workspace, L.vq_gemv_static_workspace, L.vq_gemv_multi, L.vq_gemm, L.vq_assign, L.vq_assign_down):
         f.restype = ctypes.c_int
     _lib = L
     return L
 
 
-EXPORTED = ["vq_validate", "vq_dequant", "vq_gemv", "vq_gemv_workspace_bytes", "vq_gemv_with_workspace", "vq_gemv_multi", "vq_gemm", "vq_gemm_workspace_bytes", "vq_gemm_fast_workspace_bytes",
+EXPORTED = ["vq_validate", "vq_dequant", "vq_gemv", "vq_gemv_workspace_bytes", "vq_gemv_with_workspace", "vq_gemv_static_workspace", "vq_gemv_multi", "vq_gemm", "vq_gemm_workspace_bytes", "vq_gemm_fast_workspace_bytes",
             "vq_assign", "vq_assign_down", "vq_status_string", "vq_version"]
 
 
@@ -101,6 +102,13 @@ def vq_gemv_workspace_bytes(desc, batch):
 def vq_gemv_with_workspace(desc, x_ptr, ldx, batch, y_ptr, ldy, workspace_ptr=None, workspace_bytes=0, stream=None):
     return load().vq_gemv_with_workspace(ctypes.byref(desc) if desc is not None else None, x_ptr, ldx, batch, y_ptr, ldy,
                                          workspace_ptr, workspace_bytes, stream)
+
+
+def vq_gemv_static_workspace(desc, x_ptr, ldx, batch, y_ptr, ldy, stream=None):
+    return load().vq_gemv_static_workspace(ctypes.byref(desc) if desc is not None else None, x_ptr, ldx, batch, y_ptr, ldy, stream)
+
+
+VQ_GEMV_STATIC_WORKSPACE_BYTES = 16 << 20
 
 
 def vq_gemv_multi(descs, x_ptr, ldx, batch, y_ptrs, ldys, stream=None):

@@ -1,5 +1,6 @@
 // C-ABI entry points: descriptor validation and dispatch.  All device work is in the kernel files.
 #include "vq_common.hpp"
+#include <mutex>
 
 namespace vq {
 
@@ -119,6 +120,50 @@ extern "C" int vq_gemv_with_workspace(const vq_layer_desc *desc, const void *x, 
   if (!aligned(x, 2) || !aligned(y, 2)) return VQ_ERR_ALIGNMENT;
   if (workspace && workspace_bytes && !aligned(workspace, 256)) return VQ_ERR_ALIGNMENT;
   return vq::launch_gemv_ws(p, static_cast<const __half *>(x), ldx, batch, static_cast<__half *>(y), ldy, workspace, workspace_bytes,
+                            static_cast<hipStream_t>(hip_stream));
+}
+
+// ---- vq_gemv_with_workspace for callers that cannot allocate: the workspace is a device array of this library.
+// In host code the array's name is only a handle for hipGetSymbolAddress; what kernels and the launchers get is the
+// device address that call returns, looked up once per device (every device holds its own copy of the array).
+namespace vq {
+static __device__ __align__(256) unsigned char scratch[VQ_GEMV_STATIC_WORKSPACE_BYTES];
+namespace {
+constexpr int MAX_DEVICES = 64;
+void *g_scratch_ptr[MAX_DEVICES];
+std::mutex g_scratch_mutex;
+
+int static_workspace(void **ptr) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return VQ_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *q = nullptr;
+    if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) return VQ_ERR_HIP;
+    g_scratch_ptr[dev] = q;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return VQ_OK;
+}
+}  // namespace
+}  // namespace vq
+
+extern "C" int vq_gemv_static_workspace(const vq_layer_desc *desc, const void *x, int64_t ldx, int32_t batch, void *y, int64_t ldy,
+                                        void *hip_stream) {
+  vq::Params p;
+  int rc = vq::make_params(desc, &p);
+  if (rc != VQ_OK) return rc;
+  if (!x || !y) return VQ_ERR_NULL;
+  if (batch < 1 || batch > 16 || ldx < p.in_features || ldy < p.out_features) return VQ_ERR_SHAPE;
+  if (!aligned(x, 2) || !aligned(y, 2)) return VQ_ERR_ALIGNMENT;
+  const size_t need = vq::gemv_workspace_bytes(p, static_cast<const __half *>(x), ldx, batch);
+  if (need > (size_t)VQ_GEMV_STATIC_WORKSPACE_BYTES) return VQ_ERR_WORKSPACE;
+  void *ws = nullptr;
+  if (need) {
+    rc = vq::static_workspace(&ws);
+    if (rc != VQ_OK) return rc;
+  }
+  return vq::launch_gemv_ws(p, static_cast<const __half *>(x), ldx, batch, static_cast<__half *>(y), ldy, ws, need,
                             static_cast<hipStream_t>(hip_stream));
 }
 
