@@ -23,12 +23,22 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor figure
 MFMA_FP16_PEAK_TFLOPS = 2500.0  # dense FP16 matrix-core peak, vendor figure
 FP32_VECTOR_PEAK_TFLOPS = 157.3   # published fp32 vector peak (packed FMA on 256 compute units at 2.4 GHz)
+LEAD_SECONDS = 0.012            # least duration of the untimed lead-in (host estimate from the warm-up launches)
+EAGER_BELOW = 200               # fewer timed steps than this are launched one by one (queued behind the lead-in)
 ROTATE_BYTES = 640 << 20        # footprint of the rotated index copies (> 2 x the 256 MB Infinity Cache)
 
-# HBM traffic per launch from `rocprofv3 --pmc` (FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by
-# what the same counter reads for a 1 GiB device copy in the same run: FETCH_SIZE x 2.0, WRITE_SIZE x 1.0);
-# figures and commands in profiles/gemv_v6_cfg1_batch1.txt.  Keyed by benchmark configuration.
-MEASURED_TRAFFIC_BYTES = {1: int((5932.2 * 2.0 + 29.0 * 1.0) * 1024)}
+PROFILES = os.path.join(ROOT, "profiles")
+
+
+def measured_traffic_bytes(cfg):
+    """HBM bytes per launch of the headline kernel from the tracked rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE,
+    each scaled by what the same counter reads for a 1 GiB device copy), or None when there is no such summary."""
+    import re
+    path = os.path.join(PROFILES, "gemv_cfg%d_batch1_traffic.txt" % cfg)
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_bytes_per_launch:\s*(\d+)", open(path).read(), re.M)
+    return int(m.group(1)) if m else None
 
 
 def parse():
@@ -71,29 +81,52 @@ class Rotation:
         self.copies = copies
 
 
-def timed(launch, steps, warmup, use_graph=True):
-    """Run `warmup` untimed and `steps` timed calls of launch(i).  Returns (wall seconds, event seconds)."""
+def timed(launch, steps, warmup, use_graph=True, lead=0):
+    """Run `warmup` untimed and `steps` timed calls of launch(i).  Returns (wall seconds, event seconds); the event time
+    (HIP events on the launching stream around exactly `steps` launches) is the one every reported figure uses.
+    The timed launches are i = n .. n + steps - 1 and follow, without a gap, an untimed run of launches 0 .. n - 1,
+    n >= max(steps, lead).  With `lead` = the number of index copies that launch(i) rotates over (together more than
+    512 MiB), every timed launch reads a copy whose last use lies a full rotation back -- more than twice the 256 MB
+    Infinity Cache of other data in between, whatever `steps` is -- and starts on a GPU that is already running.
+    Both runs are replays of HIP graphs uploaded beforehand; a few steps are launched one by one instead, queued
+    behind the lead-in (a graph replay costs 11-14 us on the GPU's own time line, which twenty steps cannot amortise)."""
     import torch
     stream = torch.cuda.current_stream()
+    t0 = time.perf_counter()
     for i in range(warmup):
         launch(i)
     torch.cuda.synchronize()
-    graph = None
+    # the lead-in also runs long enough for the clocks to settle: measured on the 11008 x 4096 layer, the launches of the
+    # first few milliseconds after an idle spell take up to 6 % longer than those of a long run
+    per_launch = (time.perf_counter() - t0) / max(warmup, 1) if warmup >= 5 else 50e-6
+    n_lead = max(steps, lead, min(4000, int(LEAD_SECONDS / max(per_launch, 2e-6))))
+    lead_graph = timed_graph = None
     if use_graph:
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
-            for i in range(steps):
+        lead_graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        with torch.cuda.graph(lead_graph, stream=side):
+            for i in range(n_lead):
                 launch(i)
-        graph.replay()                 # untimed: uploads the graph
+        if steps >= EAGER_BELOW:
+            timed_graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(timed_graph, stream=side):
+                for i in range(n_lead, n_lead + steps):
+                    launch(i)
+            timed_graph.replay()       # untimed: uploads the graph
+        lead_graph.replay()
         torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
+    if lead_graph is not None:
+        lead_graph.replay()
+    else:
+        for i in range(n_lead):
+            launch(i)
     t0 = time.perf_counter()
     e0.record(stream)
-    if graph is not None:
-        graph.replay()
+    if timed_graph is not None:
+        timed_graph.replay()
     else:
-        for i in range(steps):
+        for i in range(n_lead, n_lead + steps):
             launch(i)
     e1.record(stream)
     torch.cuda.synchronize()
@@ -119,7 +152,7 @@ def bench_gemv(vq, layer, x_np, steps, warmup, use_graph, rotate=True, workspace
             rc = vq.vq_gemv(rot.descs[i % rot.copies], xp, ldx, batch, yp, ldy, st)
         if rc != 0:
             raise vq.VQError(rc, "vq_gemv")
-    wall, ev = timed(launch, steps, warmup, use_graph)
+    wall, ev = timed(launch, steps, warmup, use_graph, lead=rot.copies)
     return dict(wall_s=wall, event_s=ev, copies=rot.copies, y=y)
 
 
@@ -146,20 +179,21 @@ def main():
     alg = layer.algorithmic_bytes(1)
     sec = r["event_s"] / args.steps
     gbps = alg / sec / 1e9
-    wall_gbps = alg * args.steps / r["wall_s"] / 1e9
     workload = "cfg%d %s %dx%d v%d k%d%s%s batch1 gemv" % (
         cfg, layer.name, layer.out_features, layer.in_features, layer.v, layer.k,
         " res%d" % layer.k_res if layer.k_res else "", " outlier%d" % layer.n_outlier_cols if layer.n_outlier_cols else "")
+    # one clock for every figure of the line: HIP events on the launching stream around exactly `steps` launches
     result = {
         "metric": "batch-1 VQ-GEMV effective HBM bandwidth (algorithmic bytes / time)",
-        "value": round(wall_gbps, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(r["wall_s"] / args.steps * 1e3, 6), "us_per_step": round(r["wall_s"] / args.steps * 1e6, 3),
+        "value": round(gbps, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 6), "us_per_step": round(sec * 1e6, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16 in, f32 accumulate",
         "data": "synthetic (seeded Gaussian tables, uniform indices; stands in for quantized Llama-2 layers)",
         "config": {"workload": workload, "algorithmic_bytes": alg, "index_copies_rotated": r["copies"],
-                   "launch": "hip graph replay" if use_graph else "eager"},
+                   "launch": "hip graph replay" if use_graph else "eager", "clock": "HIP events on the launching stream",
+                   "host_wall_us_per_step": round(r["wall_s"] / args.steps * 1e6, 3)},
         "roofline": {"bound": "hbm", "achieved": round(gbps, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg),
+                     "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": measured_traffic_bytes(cfg),
                      "kernel_us": round(sec * 1e6, 3)},
     }
 
@@ -231,9 +265,14 @@ def detail(vq, s, np, torch, use_graph, skip):
         alg = layer.algorithmic_bytes(batch)
         cfg2_bytes[layer.name, batch] = alg
         flops = 2.0 * batch * layer.out_features * layer.in_features
-        out.append({"op": "vq_gemv", "cfg": cfg, "layer": layer.name, "batch": batch, "us": round(sec * 1e6, 3),
-                    "GB/s": round(alg / sec / 1e9, 1), "frac_hbm_peak": round(alg / sec / 1e9 / HBM_PEAK_GBPS, 4),
-                    "TFLOP/s": round(flops / sec / 1e12, 2)})
+        line = {"op": "vq_gemv", "cfg": cfg, "layer": layer.name, "batch": batch, "us": round(sec * 1e6, 3),
+                "GB/s": round(alg / sec / 1e9, 1), "frac_hbm_peak": round(alg / sec / 1e9 / HBM_PEAK_GBPS, 4),
+                "TFLOP/s": round(flops / sec / 1e12, 2)}
+        if batch == 1 and cfg in (1, 3):       # the two layers the target is written for: a roofline block of their own
+            line["roofline"] = {"bound": "hbm", "achieved": round(alg / sec / 1e9, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                "frac": round(alg / sec / 1e9 / HBM_PEAK_GBPS, 4), "traffic": measured_traffic_bytes(cfg),
+                                "kernel_us": round(sec * 1e6, 3), "algorithmic_bytes": alg}
+        out.append(line)
 
     for cfg in (1, 2, 3):
         spec = s.CONFIGS[cfg]

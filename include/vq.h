@@ -1,9 +1,9 @@
 /* vq.h -- C ABI of the MI355X (gfx950) vector-quantized linear layer.
  *
  * The layer stores, per length-v weight vector, an index into a codebook of k
- * FP16 centroids (paper Sec. 2.2 "Vector Quantization": weights are restored
- * "from the lookup table by index and centroid"; index bits = log2(k) per
- * vector).  Optional extras, all from the paper's parameter list
+ * FP16 centroids (paper Sec. 2.2 "Vector Quantization": a weight vector is
+ * restored by reading the centroid its index names out of the lookup table;
+ * index bits = log2(k) per vector).  Optional extras, all from the paper's parameter list
  * (App. "Parameter Description": v0,k0 / v1,k1 / k2):
  *   - a residual codebook of k_res entries with the same v, whose centroid is
  *     ADDED to the main one (Sec. 3.2.2 "Residual Vector Quantization");
@@ -36,7 +36,13 @@
  * nothing is allocated, freed or retained.  Output elements outside the
  * logical extents (columns >= in_features of W, columns >= out_features of y)
  * are not written.  Return value: VQ_OK or a negative vq_status; no exception
- * crosses the boundary.  Thread-safe.
+ * crosses the boundary.  Thread-safe: the library keeps no mutable state beyond
+ * once-per-process initialisations (compute-unit count, per-kernel LDS limits,
+ * the device address of vq_gemv_static_workspace's array), all of them guarded.
+ * The environment variable VQ_SWITCHES ("name=value,..."; read once at the
+ * start of every call) forces kernel choices for tests and measurements:
+ * gemv=g|m|d (generic / matrix-core / dot-product kernels), groups=loop, multi=0,
+ * gemm=g|f|w|r, dense=0|1, dequant=g|s; unset, every choice is the library's own.
  */
 #ifndef VQ_H
 #define VQ_H
@@ -61,7 +67,7 @@ typedef struct vq_layer_desc {
   int32_t out_features, in_features;       /* M, N (logical, unpadded); 1 .. 2^24                  */
   int32_t v, k;                            /* main codebook: v in [1,16], k in [2,65536]           */
   int32_t k_res;                           /* residual entries, 0 = none; same v                   */
-  int32_t n_outlier_cols, v_out, k_out;    /* 0 = none; n % v_out == 0; n <= in_features           */
+  int32_t n_outlier_cols, v_out, k_out;    /* 0 = none; n % v_out == 0; n < in_features            */
   const void *codebook;                    /* fp16 [k][v] row-major, 16-byte aligned               */
   const void *codebook_res;                /* fp16 [k_res][v]                                      */
   const void *codebook_out;                /* fp16 [k_out][v_out]                                  */
@@ -86,8 +92,9 @@ typedef struct vq_layer_desc {
    * q < ceil(out_features / v_out), belongs to rows [q v_out, q v_out + v_out) and holds one index per outlier column
    * (n_outlier_cols need not be a multiple of v_out).  Codebook groups are ranges of group_vectors stream positions,
    * i.e. of main columns.  Scale and bias stay per output row.  This field occupies what used to be padding after
-   * group_vectors: descriptors that were zeroed as a whole keep orientation 0.  Layers of orientation 1 run on the
-   * generic kernels (and through vq_gemm's restore-then-multiply route).                                          */
+   * group_vectors: descriptors that were zeroed as a whole keep orientation 0.  Layers of orientation 1 with v = 6 /
+   * 12-bit indices or v = 8 / 8- or 16-bit indices have fast vq_gemv and vq_dequant kernels of their own; others, and
+   * vq_gemm without a workspace, run on the generic kernels.                                                        */
   int32_t orientation;
 } vq_layer_desc;
 
@@ -103,8 +110,11 @@ int vq_validate(const vq_layer_desc *desc);
 int vq_dequant(const vq_layer_desc *desc, void *W, int64_t ldw, void *hip_stream);
 
 /* Decode-phase fused restore + matrix-vector product ("QGemv", App. "Our Dequantization
- * Implementation", second phase): y[b][o] = sum_c W[o][c] * x[b][c], binary32 accumulation on the
- * vector ALUs, fp16 result.  x: fp16 [batch][ldx], ldx >= in_features; y: fp16 [batch][ldy],
+ * Implementation", second phase): y[b][o] = sum_c W[o][c] * x[b][c], binary32 accumulation, fp16
+ * result.  One or two activation rows run on the vector ALUs (v_dot2_f32_f16, DPP reductions); from
+ * three rows on, and for layers with codebook groups or outlier columns, the fp16 matrix cores do the
+ * multiplications (the LDS lookups cost the same and the vector ALUs stop binding); VQ_SWITCHES gemv=d
+ * keeps every batch on the vector ALUs.  x: fp16 [batch][ldx], ldx >= in_features; y: fp16 [batch][ldy],
  * ldy >= out_features; batch in [1,16]; x and y 2-byte aligned (a 16-byte aligned x with ldx % 8 == 0
  * lets the fastest kernels run).  y must not alias x.                                               */
 int vq_gemv(const vq_layer_desc *desc, const void *x, int64_t ldx, int32_t batch,

@@ -1,8 +1,46 @@
 // C-ABI entry points: descriptor validation and dispatch.  All device work is in the kernel files.
 #include "vq_common.hpp"
+#include <cstdlib>
+#include <cstring>
 #include <mutex>
 
 namespace vq {
+
+int cu_count() {
+  static const int n = [] {
+    int dev = 0, c = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&c, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || c < 1) c = 256;
+    return c;
+  }();
+  return n;
+}
+
+namespace {
+thread_local Switches g_switches;
+}
+const Switches &switches() { return g_switches; }
+
+// VQ_SWITCHES = "name=value,name=value": unknown names are ignored.
+void read_switches() {
+  Switches sw;
+  const char *e = getenv("VQ_SWITCHES");
+  while (e && *e) {
+    const char *eq = strchr(e, '='), *end = strchr(e, ',');
+    if (!end) end = e + strlen(e);
+    if (eq && eq < end) {
+      const size_t n = (size_t)(eq - e);
+      const char v = eq[1] == ',' ? '\0' : eq[1];
+      if (n == 4 && !strncmp(e, "gemv", 4)) sw.gemv = v;
+      else if (n == 4 && !strncmp(e, "gemm", 4)) sw.gemm = v;
+      else if (n == 7 && !strncmp(e, "dequant", 7)) sw.dequant = v;
+      else if (n == 6 && !strncmp(e, "groups", 6)) sw.groups_loop = v == 'l';
+      else if (n == 5 && !strncmp(e, "multi", 5)) sw.multi_off = v == '0';
+      else if (n == 5 && !strncmp(e, "dense", 5)) sw.dense = v == '0' ? 0 : v == '1' ? 1 : -1;
+    }
+    e = *end ? end + 1 : end;
+  }
+  g_switches = sw;
+}
 
 static bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -82,6 +120,7 @@ using vq::aligned;
 extern "C" int vq_validate(const vq_layer_desc *desc) { return vq::make_params(desc, nullptr); }
 
 extern "C" int vq_dequant(const vq_layer_desc *desc, void *W, int64_t ldw, void *hip_stream) {
+  vq::read_switches();
   vq::Params p;
   int rc = vq::make_params(desc, &p);
   if (rc != VQ_OK) return rc;
@@ -93,6 +132,7 @@ extern "C" int vq_dequant(const vq_layer_desc *desc, void *W, int64_t ldw, void 
 
 extern "C" int vq_gemv(const vq_layer_desc *desc, const void *x, int64_t ldx, int32_t batch,
                        void *y, int64_t ldy, void *hip_stream) {
+  vq::read_switches();
   vq::Params p;
   int rc = vq::make_params(desc, &p);
   if (rc != VQ_OK) return rc;
@@ -104,6 +144,7 @@ extern "C" int vq_gemv(const vq_layer_desc *desc, const void *x, int64_t ldx, in
 }
 
 extern "C" size_t vq_gemv_workspace_bytes(const vq_layer_desc *desc, int32_t batch) {
+  vq::read_switches();
   vq::Params p;
   if (vq::make_params(desc, &p) != VQ_OK || batch < 1 || batch > 16) return 0;
   // the size does not depend on x; the fast kernels' conditions on x are checked again at the call
@@ -112,6 +153,7 @@ extern "C" size_t vq_gemv_workspace_bytes(const vq_layer_desc *desc, int32_t bat
 
 extern "C" int vq_gemv_with_workspace(const vq_layer_desc *desc, const void *x, int64_t ldx, int32_t batch, void *y, int64_t ldy,
                                       void *workspace, size_t workspace_bytes, void *hip_stream) {
+  vq::read_switches();
   vq::Params p;
   int rc = vq::make_params(desc, &p);
   if (rc != VQ_OK) return rc;
@@ -150,6 +192,7 @@ int static_workspace(void **ptr) {
 
 extern "C" int vq_gemv_static_workspace(const vq_layer_desc *desc, const void *x, int64_t ldx, int32_t batch, void *y, int64_t ldy,
                                         void *hip_stream) {
+  vq::read_switches();
   vq::Params p;
   int rc = vq::make_params(desc, &p);
   if (rc != VQ_OK) return rc;
@@ -169,6 +212,7 @@ extern "C" int vq_gemv_static_workspace(const vq_layer_desc *desc, const void *x
 
 extern "C" int vq_gemv_multi(const vq_layer_desc *const *descs, int32_t n_layers, const void *x, int64_t ldx, int32_t batch,
                              void *const *y, const int64_t *ldy, void *hip_stream) {
+  vq::read_switches();
   constexpr int MAX_LAYERS = 8;
   if (!descs || !y || !ldy || !x) return VQ_ERR_NULL;
   if (n_layers < 1 || n_layers > MAX_LAYERS || batch < 1 || batch > 16) return VQ_ERR_SHAPE;
@@ -187,12 +231,14 @@ extern "C" int vq_gemv_multi(const vq_layer_desc *const *descs, int32_t n_layers
 }
 
 extern "C" size_t vq_gemm_workspace_bytes(const vq_layer_desc *desc, int32_t tokens) {
+  vq::read_switches();
   vq::Params p;
   if (vq::make_params(desc, &p) != VQ_OK || tokens < 1) return 0;
   return vq::gemm_workspace_bytes(p, tokens);
 }
 
 extern "C" size_t vq_gemm_fast_workspace_bytes(const vq_layer_desc *desc, int32_t tokens) {
+  vq::read_switches();
   vq::Params p;
   if (vq::make_params(desc, &p) != VQ_OK || tokens < 1) return 0;
   return vq::gemm_fast_workspace_bytes(p, tokens);
@@ -200,6 +246,7 @@ extern "C" size_t vq_gemm_fast_workspace_bytes(const vq_layer_desc *desc, int32_
 
 extern "C" int vq_gemm(const vq_layer_desc *desc, const void *X, int64_t ldx, int32_t tokens,
                        void *Y, int64_t ldy, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  vq::read_switches();
   vq::Params p;
   int rc = vq::make_params(desc, &p);
   if (rc != VQ_OK) return rc;

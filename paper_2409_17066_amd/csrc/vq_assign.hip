@@ -177,13 +177,8 @@ template <int V>
 int launch_v(const __half *W, const __half *B, long long ld, int rows, int p_full, int p_all, const __half *codebook, int k, int bits,
              unsigned char *idx, long long idx_stride, hipStream_t s, int down_rows = 0) {
   constexpr int VB = V <= 8 ? 8 : 4;       // vectors a lane holds at once: each centroid read from LDS serves VB x 64 distances
-  static bool configured = false;
   auto kernel = assign_kernel<V, VB>;
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-      return VQ_ERR_HIP;
-    configured = true;
-  }
+  VQ_ALLOW_FULL_LDS(kernel);
   const int chunk = min(k, (int)(LDS_TABLE_BYTES / (table_stride(V) * sizeof(float))));
   // vectors per lane: the fewest (most lanes) whose bits fill whole dwords
   const int seg_len = bits % 4 == 0 ? 8 : bits % 2 == 0 ? 16 : 32;

@@ -24,6 +24,33 @@ struct Params {
   const __half *scale, *bias;
 };
 
+// Lets a kernel use the whole 160 KB of LDS: once per kernel and process (a function-local static: thread-safe).
+#define VQ_ALLOW_FULL_LDS(kernel)                                                                                        \
+  do {                                                                                                                   \
+    static const hipError_t vq_cfg_ = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),                        \
+                                                          hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);       \
+    if (vq_cfg_ != hipSuccess) return VQ_ERR_HIP;                                                                        \
+  } while (0)
+
+// Compute units of the current device (looked up once; 256 when the runtime does not say).
+int cu_count();
+
+// Test and measurement switches, all in the environment variable VQ_SWITCHES as name=value pairs separated by commas; read
+// once at the start of every entry-point call (one getenv), so that one process can walk through all of them:
+//   gemv=g|m|d   generic kernels only / the matrix-core kernels wherever they take the layer / the dot-product kernels
+//   groups=loop  layers with codebook groups: every workgroup walks all groups even when a workspace is there
+//   multi=0      vq_gemv_multi as one vq_gemv after the other
+//   gemm=g|f|b|r vq_gemm: generic tile kernel / on-the-fly kernel / restore-then-multiply / rows through vq_gemv
+//   dense=0|1    the dense product of the restore-then-multiply route: never / always the 256 x 256 tile kernel
+//   dequant=g|s  vq_dequant: generic kernel / never the wide-store kernel
+struct Switches {
+  char gemv = 0, gemm = 0, dequant = 0;
+  bool groups_loop = false, multi_off = false;
+  int dense = -1;
+};
+const Switches &switches();
+void read_switches();
+
 inline int index_bits(int k) { int b = 1; while ((1 << b) < k) ++b; return b; }
 
 // Host-side validation shared by the entry points; fills `p` on success.

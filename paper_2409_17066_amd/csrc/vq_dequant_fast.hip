@@ -431,27 +431,13 @@ __global__ __launch_bounds__(NW * 64) void dequant_down_v6_kernel(Params p, unsi
   }
 }
 
-int g_cus = 0;
-int cu_count() {
-  if (!g_cus) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
-    g_cus = n;
-  }
-  return g_cus;
-}
 
 template <int RES_BITS>
 int launch_v6(const Params &p, DqPlan plan, unsigned lds_bytes, __half *W, long long ldw, hipStream_t s) {
   const int cus = cu_count();
   if (p.n_groups > cus) return VQ_ERR_UNSUPPORTED;
-  static bool configured = false;
   auto kernel = dequant_v6_kernel<RES_BITS>;
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-      return VQ_ERR_HIP;
-    configured = true;
-  }
+  VQ_ALLOW_FULL_LDS(kernel);
   // the kernel needs few registers, so as many workgroups per compute unit as their LDS allows (at most two: 32 waves)
   const long long slots = (long long)cus * (2u * lds_bytes <= 160u * 1024u ? 2 : 1);
   if (p.n_groups > 1) {
@@ -507,7 +493,7 @@ __global__ __launch_bounds__(256) void dequant_down_v8_kernel(Params p, __half *
 // number of groups); VQ_ERR_UNSUPPORTED otherwise.
 // The outlier columns, if any, are the caller's (generic kernel).
 int launch_dequant_down_fast(const Params &p, __half *W, long long ldw, hipStream_t s) {
-  static const bool off = [] { const char *e = getenv("VQ_DEQUANT_KERNEL"); return e && e[0] == 'g'; }();
+  const bool off = switches().dequant == 'g';
   if (off || p.orientation != 1) return VQ_ERR_UNSUPPORTED;
   {
     const int ib = p.bits == 16 ? 2 : p.bits == 8 ? 1 : 0, rbytes = !p.k_res ? 0 : p.bits_res == 16 ? 2 : p.bits_res == 8 ? 1 : -1;
@@ -545,7 +531,7 @@ int launch_dequant_down_fast(const Params &p, __half *W, long long ldw, hipStrea
 
 // Returns VQ_ERR_UNSUPPORTED when no fast kernel takes the layer (the caller then uses the generic kernel).
 int launch_dequant_fast(const Params &p, __half *W, long long ldw, hipStream_t s) {
-  static const bool off = [] { const char *e = getenv("VQ_DEQUANT_KERNEL"); return e && e[0] == 'g'; }();
+  const bool off = switches().dequant == 'g';
   if (off || p.orientation != 0) return VQ_ERR_UNSUPPORTED;
   const bool aligned16 = (reinterpret_cast<uintptr_t>(W) & 15) == 0 && (ldw & 7) == 0;
   const int ib = p.bits == 16 ? 2 : p.bits == 8 ? 1 : 0, rbytes = !p.k_res ? 0 : p.bits_res == 16 ? 2 : p.bits_res == 8 ? 1 : -1;
@@ -574,7 +560,7 @@ int launch_dequant_fast(const Params &p, __half *W, long long ldw, hipStream_t s
   plan.out_chunks = p.n_out ? (p.Q + 63) / 64 : 0;
   plan.total_chunks = (long long)(plan.main_chunks + plan.out_chunks) * p.out_features;
   plan.wide = (aligned16 && (p.n_out & 7) == 0) ? 1 : 0;
-  static const bool strip_only = [] { const char *e = getenv("VQ_DEQUANT_KERNEL"); return e && e[0] == 's'; }();   // 's': never the wide kernel
+  const bool strip_only = switches().dequant == 's';            // 's': never the wide kernel
   const bool wide_route = plan.wide && p.n_groups == 1 && !strip_only && (long long)p.out_features * max(p.stride, p.stride_res) < (1LL << 31);
   // (the wide route keeps no outlier table in LDS: it also takes a 12-bit residual table together with outlier columns)
   if (offb > 160u * 1024u && !wide_route) return VQ_ERR_UNSUPPORTED;

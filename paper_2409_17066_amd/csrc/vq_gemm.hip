@@ -172,14 +172,13 @@ int launch_gemm_fused(const Params &p, const __half *X, long long ldx, int token
 //     full lines.  Any layer the library can dequantize qualifies (in_features a multiple of 256).
 //  2. v = 8 / 16-bit indices: restore on the fly inside the MFMA kernel (no workspace, W never in memory).
 //  3. the generic tile kernel.
-// VQ_GEMM_KERNEL=g forces 3, =f skips 1, =w takes 1 whenever a workspace is there (measurement and tests).
+// Switch gemm=g forces 3, =f skips 1, =w takes 1 whenever a workspace is there (measurement and tests).
 int launch_gemm(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy,
                 void *workspace, size_t workspace_bytes, hipStream_t s) {
-  const char *env = getenv("VQ_GEMM_KERNEL");          // read at every call so that one process can test every route
-  const char forced = env ? env[0] : '\0';
+  const char forced = switches().gemm;
   const size_t fast = gemm_fast_workspace_bytes(p, tokens);
   // measured on the 8192 x 8192 v=8 layer: up to 512 tokens restoring on the fly is still ahead (167 vs 184 us), from
-  // 1024 tokens on the restored matrix wins (215 vs 267 us, 365 vs 407 us at 2048); VQ_GEMM_KERNEL=w takes it always
+  // 1024 tokens on the restored matrix wins (215 vs 267 us, 365 vs 407 us at 2048); gemm=w takes it always
   const bool worth_it = forced == 'w' || !gemm_fused_applicable(p) || tokens > 512;
   const bool have_ws = fast && workspace && workspace_bytes >= fast && (reinterpret_cast<uintptr_t>(workspace) & 15) == 0;
   // Layers that only the generic tile kernel would take (no workspace and not the v = 8 layout of the fused kernel), and
@@ -189,7 +188,7 @@ int launch_gemm(const Params &p, const __half *X, long long ldx, int tokens, __h
   // 83 us with a workspace and 667 us without; 512 tokens without a workspace 322 against 700 us.  The other layers with
   // a specialised GEMV kernel (v = 8; orientation 1), whose cost grows faster with the rows: only without a workspace and
   // up to 128 tokens (v = 8, k = 65536 with a residual, 64 tokens: 191 against 848 us; 512 tokens would be 1480 against 880).
-  // VQ_GEMM_KERNEL=r: always.
+  // gemm=r: always.
   const bool rows_cheap = p.orientation == 0 && p.v == 6;
   if (forced == 'r' || (forced == '\0' && !gemm_fused_applicable(p) && gemv_has_fast_kernel(p, X, ldx) &&
                         (rows_cheap ? (!have_ws || tokens <= 96) : (!have_ws && tokens <= 128)))) {

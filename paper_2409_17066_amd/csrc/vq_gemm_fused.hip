@@ -414,13 +414,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
 int launch_dense256(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy, const __half *Wd, long long ldw,
                     hipStream_t s) {
-  static bool configured = false;
   const unsigned lds = DNS * 2u * DT * 64u;
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_dense256_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-      return VQ_ERR_HIP;
-    configured = true;
-  }
+  VQ_ALLOW_FULL_LDS(gemm_dense256_kernel);
   if (((long long)(p.out_features - 1) * ldw + p.in_features) * 2 >= (1LL << 32)) return VQ_ERR_UNSUPPORTED;   // 32-bit buffer offsets
   if (((long long)(tokens + DT) * ldy + p.out_features + DT) * 2 >= 0xFFFFFFF0LL) return VQ_ERR_UNSUPPORTED;
   const unsigned gx = (unsigned)((p.out_features + DT - 1) / DT), gy = (unsigned)((tokens + DT - 1) / DT);
@@ -432,14 +427,9 @@ int launch_dense256(const Params &p, const __half *X, long long ldx, int tokens,
 template <int BM, bool DENSE>
 int launch_fused(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy, const __half *Wd, long long ldw,
                  hipStream_t s) {
-  static bool configured = false;
   auto kernel = gemm_v8_kernel<BM, DENSE>;
   const unsigned lds = NSX * BM * 64u + 2u * BN * LDT * 2u;
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-      return VQ_ERR_HIP;
-    configured = true;
-  }
+  VQ_ALLOW_FULL_LDS(kernel);
   const unsigned gx = (unsigned)((p.out_features + BN - 1) / BN), gy = (unsigned)((tokens + BM - 1) / BM);
   if (gy > 65535u) return VQ_ERR_UNSUPPORTED;
   hipLaunchKernelGGL(kernel, dim3(gx, gy), dim3((BM / 64 + 4) * 64), lds, s, p, X, ldx, tokens, Y, ldy, Wd, ldw);
@@ -456,25 +446,23 @@ bool gemm_fused_applicable(const Params &p) {
 // (16-byte aligned rows) and the producers copy its tiles.
 int launch_gemm_fused(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy, const __half *Wd,
                       long long ldw, hipStream_t s) {
-  static const int force_bm = [] { const char *e = getenv("VQ_GEMM_BM"); return e ? atoi(e) : 0; }();
   if (((long long)(tokens - 1) * ldx + p.in_features) * 2 >= (1LL << 32)) return VQ_ERR_UNSUPPORTED;   // 32-bit buffer offsets
   if (Wd) {
-    // enough 256 x 256 tiles to fill the chip: the four-wave kernel (VQ_GEMM_DENSE=1 / =0: always / never, for measurement and tests)
-    const char *env_dense = getenv("VQ_GEMM_DENSE");       // read at every call so that one process can test both
-    const int force_dense = env_dense ? atoi(env_dense) : -1;
+    // enough 256 x 256 tiles to fill the chip: the four-wave kernel (switch dense=1 / =0: always / never, for measurement and tests)
+    const int force_dense = switches().dense;
     const long long tiles256 = (long long)((p.out_features + DT - 1) / DT) * ((tokens + DT - 1) / DT);
-    if (force_dense == 1 || (force_dense != 0 && !force_bm && tiles256 >= 200)) {
+    if (force_dense == 1 || (force_dense != 0 && tiles256 >= 200)) {
       const int rc = launch_dense256(p, X, ldx, tokens, Y, ldy, Wd, ldw, s);
       if (rc != VQ_ERR_UNSUPPORTED) return rc;
     }
     // no gathers to amortise: the tile height only has to fill the chip (out/128 x tokens/BM workgroups)
     const long long col_blocks = (p.out_features + BN - 1) / BN;
-    const int bm = force_bm ? force_bm : (col_blocks * ((tokens + 511) / 512) >= 200 ? 512 : col_blocks * ((tokens + 255) / 256) >= 200 ? 256 : 128);
+    const int bm = (col_blocks * ((tokens + 511) / 512) >= 200 ? 512 : col_blocks * ((tokens + 255) / 256) >= 200 ? 256 : 128);
     if (bm == 512) return launch_fused<512, true>(p, X, ldx, tokens, Y, ldy, Wd, ldw, s);
     if (bm == 128) return launch_fused<128, true>(p, X, ldx, tokens, Y, ldy, Wd, ldw, s);
     return launch_fused<256, true>(p, X, ldx, tokens, Y, ldy, Wd, ldw, s);
   }
-  const int bm = force_bm ? force_bm : (tokens > 512 ? 512 : 256);
+  const int bm = (tokens > 512 ? 512 : 256);
   if (bm == 512) return launch_fused<512, false>(p, X, ldx, tokens, Y, ldy, nullptr, 0, s);
   if (bm == 128) return launch_fused<128, false>(p, X, ldx, tokens, Y, ldy, nullptr, 0, s);
   return launch_fused<256, false>(p, X, ldx, tokens, Y, ldy, nullptr, 0, s);

@@ -127,12 +127,9 @@ int gemv_down_mfma_parts(const Params &p);
 int launch_gemv_down_mfma(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s,
                           float *part, float *part_xs, int parts);
 
-// VQ_GEMV_KERNEL=g forces the generic kernel, =m the matrix-core kernel, =d the dot-product kernels
-// (testing and measurement; unset: chosen by batch).  Read at every call so that one process can test them all.
-static char forced_kernel() {
-  const char *e = getenv("VQ_GEMV_KERNEL");
-  return e ? e[0] : '\0';
-}
+// Switch gemv=g forces the generic kernel, =m the matrix-core kernel, =d the dot-product kernels (testing and
+// measurement; unset: chosen by batch and shape).
+static char forced_kernel() { return switches().gemv; }
 static bool force_generic() { return forced_kernel() == 'g'; }
 
 static bool down_mfma_wanted(const Params &p, const __half *x, long long ldx, int batch) {
@@ -170,7 +167,7 @@ int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __ha
   // it is the one that swaps the tables in LDS group by group.
   if (p.orientation == 1) {
     // from three to five rows on the matrix-core kernel of this orientation is ahead (six multiply-adds per gather and row
-    // bind the other one); VQ_GEMV_KERNEL=m sends every batch there, =d none
+    // bind the other one); gemv=m sends every batch there, =d none
     if (down_mfma_alone_wanted(p, x, ldx, batch)) {
       const int rc = launch_gemv_down_mfma(p, x, ldx, batch, y, ldy, s, nullptr, nullptr, 1);
       if (rc != VQ_ERR_UNSUPPORTED) return rc;
@@ -209,7 +206,7 @@ int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __ha
   // one activation row of a long-row layer with an 8-bit residual stream (the 8192 x 28672 layer of the 70B setting): the
   // kernel that replicates the residual table in LDS and keeps the activations out of it.  Measured against the other
   // dot-product kernel: 28672 columns 33.5 against 37.0 us; 8192 columns 16.0 against 14.7 us, hence the threshold
-  // (VQ_GEMV_KERNEL=d takes it for every layer it accepts, for the tests).
+  // (gemv=d takes it for every layer it accepts, for the tests).
   if (batch == 1 && gemv_res8_applicable(p, x) && ((forced_kernel() == '\0' && p.in_features >= 16384) || forced_kernel() == 'd')) {
     const int rc = launch_gemv_res8(p, x, y, s);
     if (rc != VQ_ERR_UNSUPPORTED) return rc;
@@ -262,7 +259,7 @@ int launch_gemv_mfma_groups(const Params &p, const __half *x, long long ldx, int
                             hipStream_t s);
 
 // A workspace serves layers with codebook groups on the matrix-core kernel: one group per workgroup, then a sum over
-// the groups.  VQ_GEMV_GROUPS=loop keeps every workgroup walking all groups (measurement and tests).
+// the groups.  groups=loop keeps every workgroup walking all groups (measurement and tests).
 size_t gemv_workspace_bytes(const Params &p, const __half *x, long long ldx, int batch) {
   if (force_generic()) return 0;
   if (p.orientation == 1 && down_mfma_parts_wanted(p, x, ldx, batch)) {   // the matrix cores: the workspace lets parts of the columns run side by side
@@ -278,7 +275,6 @@ size_t gemv_workspace_bytes(const Params &p, const __half *x, long long ldx, int
 
 int launch_gemv_ws(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, void *workspace,
                    size_t workspace_bytes, hipStream_t s) {
-  const char *env = getenv("VQ_GEMV_GROUPS");
   const size_t need = gemv_workspace_bytes(p, x, ldx, batch);
   if (need && workspace && workspace_bytes >= need && p.orientation == 1 && down_mfma_parts_wanted(p, x, ldx, batch)) {
     const int parts = gemv_down_mfma_parts(p), slots = parts + (p.Q ? 1 : 0);
@@ -300,7 +296,7 @@ int launch_gemv_ws(const Params &p, const __half *x, long long ldx, int batch, _
     }
     if (rc == VQ_OK) return launch_groups_finish(part, part_xs, slots, batch, p, y, ldy, s);
     if (rc != VQ_ERR_UNSUPPORTED || done != 0) return rc;
-  } else if (need && workspace && workspace_bytes >= need && !(env && env[0] == 'l')) {
+  } else if (need && workspace && workspace_bytes >= need && !switches().groups_loop) {
     const int rc = launch_gemv_mfma_groups(p, x, ldx, batch, y, ldy, workspace, s);
     if (rc != VQ_ERR_UNSUPPORTED) return rc;
   }
@@ -314,11 +310,10 @@ int launch_gemv_down_mfma_multi(const Params *ps, int n, const __half *x, long l
                                 const long long *ldys, hipStream_t s);
 
 // Several layers on the same activations: one launch of the dot-product kernel (one row) or of the matrix-core kernel
-// (more rows; VQ_GEMV_KERNEL=m: always) when all of them take it together, else (and with VQ_GEMV_MULTI=0, for measurement and tests) one vq_gemv after the other.
+// (more rows; gemv=m: always) when all of them take it together, else (and with multi=0, for measurement and tests) one vq_gemv after the other.
 int launch_gemv_multi(const Params *ps, int n, const __half *x, long long ldx, int batch, __half *const *ys, const long long *ldys,
                       hipStream_t s) {
-  const char *env = getenv("VQ_GEMV_MULTI");
-  bool fused = n >= 2 && !(env && env[0] == '0') && forced_kernel() != 'g' && forced_kernel() != 'd';
+  bool fused = n >= 2 && !switches().multi_off && forced_kernel() != 'g' && forced_kernel() != 'd';
   // layers with vectors down the output dimension: the matrix-core kernel of that orientation, any batch (a block of 16
   // streams per workgroup over all columns; the blocks of all the layers together are what fills the chip)
   bool down = fused;

@@ -350,26 +350,12 @@ __global__ __launch_bounds__(DW * 64) void gemv_down_v6_kernel(Params p, DownPla
   }
 }
 
-int g_cus_down = 0;
-int cu_count() {
-  if (!g_cus_down) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
-    g_cus_down = n;
-  }
-  return g_cus_down;
-}
 
 template <int RES_BITS, int B>
 int launch_one(const Params &p, const DownPlan &plan, unsigned lds_bytes, unsigned grid, const __half *x, long long ldx, __half *y,
                long long ldy, hipStream_t s) {
-  static bool configured = false;
   auto kernel = gemv_down_v6_kernel<RES_BITS, B>;
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-      return VQ_ERR_HIP;
-    configured = true;
-  }
+  VQ_ALLOW_FULL_LDS(kernel);
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(DW * 64), lds_bytes, s, p, plan, x, ldx, y, ldy);
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }

@@ -387,15 +387,6 @@ __global__ __launch_bounds__(MW * 64) void gemv_down_mfma_multi_kernel(DownMulti
   gemv_down_mfma_body<RES_BITS, NTP, false>(a.layer[i].p, a.layer[i].plan, x, ldx, a.layer[i].y, a.layer[i].ldy, (int)blockIdx.x - a.first_wg[i]);
 }
 
-int g_cus_dm = 0;
-int cu_count() {
-  if (!g_cus_dm) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
-    g_cus_dm = n;
-  }
-  return g_cus_dm;
-}
 
 // LDS of one layer: tables (or the meeting place of the waves, which takes their space at the end), then the outlier tile
 template <int RES_BITS, int NTP>
@@ -410,13 +401,8 @@ unsigned place_lds(const Params &p, DownMfmaPlan &plan) {
 
 template <int RES_BITS, int NTP>
 int launch_multi(DownMultiArgs &a, const __half *x, long long ldx, hipStream_t s) {
-  static bool configured = false;
   auto kernel = gemv_down_mfma_multi_kernel<RES_BITS, NTP>;
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-      return VQ_ERR_HIP;
-    configured = true;
-  }
+  VQ_ALLOW_FULL_LDS(kernel);
   unsigned lds_bytes = 0;
   for (int i = 0; i < a.n; ++i) {
     const unsigned b = place_lds<RES_BITS, NTP>(a.layer[i].p, a.layer[i].plan);
@@ -430,13 +416,8 @@ int launch_multi(DownMultiArgs &a, const __half *x, long long ldx, hipStream_t s
 template <int RES_BITS, int NTP, bool WALK>
 int launch_one(const Params &p, DownMfmaPlan &plan, unsigned grid, const __half *x, long long ldx, __half *y, long long ldy,
                hipStream_t s) {
-  static bool configured = false;
   auto kernel = gemv_down_mfma_kernel<RES_BITS, NTP, WALK>;
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-      return VQ_ERR_HIP;
-    configured = true;
-  }
+  VQ_ALLOW_FULL_LDS(kernel);
   const unsigned lds_bytes = place_lds<RES_BITS, NTP>(p, plan);
   if (lds_bytes > 160u * 1024u) return VQ_ERR_UNSUPPORTED;                  // too many outlier columns to hold beside the tables
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(MW * 64), lds_bytes, s, p, plan, x, ldx, y, ldy);

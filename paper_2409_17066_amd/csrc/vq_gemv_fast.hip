@@ -15,12 +15,6 @@
 
 namespace vq {
 
-#ifdef VQ_PROFILE
-__device__ unsigned long long g_prof[1024 * 16 * 8];
-#define VQ_STAMP(i) do { if (lane == 0) g_prof[(blockIdx.x * 16 + wv) * 8 + (i)] = wall_clock64(); } while (0)
-#else
-#define VQ_STAMP(i) do { } while (0)
-#endif
 
 namespace {
 
@@ -91,10 +85,8 @@ __device__ __forceinline__ void tables_store(const TableRegs &t, unsigned char *
 constexpr int window_dwords(int bits, int u) { return (32 - 4 + bits * u + 31) / 32; }   // worst start bit is 28 (12-bit) or 24 (8-bit)
 
 // U: vectors per lane (compile time, so the lookups of a row carry no branches and overlap freely).
-// L1R: of a lane's U residual lookups, how many go to the residual table in memory (through the vector L1,
-// which gathers in parallel with LDS) instead of its LDS copy; only used for small residual tables.
 // `wg`: the workgroup's number within its layer (a launch may hold the workgroups of several layers).
-template <int RES_BITS, int B, int U, int L1R>
+template <int RES_BITS, int B, int U>
 __device__ __forceinline__ void gemv_v6_body(const Params &p, const GemvPlan &plan, const __half *__restrict__ x, long long ldx,
                                              __half *__restrict__ y, long long ldy, int wg) {
   // rows of index windows a wave keeps in flight, and copies of the row body in the unrolled loop.  Measured on the
@@ -119,7 +111,6 @@ __device__ __forceinline__ void gemv_v6_body(const Params &p, const GemvPlan &pl
   float *xsum = reinterpret_cast<float *>(lds + plan.lds_xsum);     // [B][NW]
   typedef Layout<RES_BITS> LY;
   const unsigned a_out = lds_address(lds) + plan.lds_out;
-  VQ_STAMP(0);
 
   // ---- role of this wave: main slice `slice` of row stream `start`, or outlier slice, or idle
   const unsigned role = plan.role[wv];          // worked out on the host: no divisions here
@@ -176,7 +167,6 @@ __device__ __forceinline__ void gemv_v6_body(const Params &p, const GemvPlan &pl
   TableRegs tabs;
   tables_load<RES_BITS>(tabs, p, plan.Wo != 0);
 
-  VQ_STAMP(2);
   // ---- activations: batch rows are copied into LDS by asynchronous, range-checked 16-byte loads that write
   // LDS directly (zeros past in_features, which is even here, so padded vectors and idle lanes multiply by
   // zero); wave w copies 1 KB pieces w, w+16, ...  plan.x_regions rows fit at a time (all of them when LDS
@@ -204,7 +194,6 @@ __device__ __forceinline__ void gemv_v6_body(const Params &p, const GemvPlan &pl
         asm volatile("" ::: "memory");
         tables_store<RES_BITS>(tabs, lds, plan, plan.Wo != 0);
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(FIRST_LOADS) : "memory");   // codebooks and direct-to-LDS copies have landed
-        VQ_STAMP(3);
         lds_barrier();                                   // (a full barrier would wait for the index rows as well)
       } else {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the direct-to-LDS copies have landed
@@ -241,7 +230,6 @@ __device__ __forceinline__ void gemv_v6_body(const Params &p, const GemvPlan &pl
     const int rows_chunk = min(plan.rc, rows_here - chunk0);
     const int row_end = (is_main || is_out) ? rows_chunk : 0;     // rows start, start+step, ... below row_end are this wave's
     if (chunk0 != 0) first_rows(chunk0);
-    VQ_STAMP(1);
 
     // scale and bias of the row this thread finishes at the end of the chunk
     const int ep_rl = (int)threadIdx.x / B, ep_b = (int)threadIdx.x - ep_rl * B;
@@ -250,7 +238,6 @@ __device__ __forceinline__ void gemv_v6_body(const Params &p, const GemvPlan &pl
     const float ep_scale = (ep_on && p.scale) ? __half2float(p.scale[ep_o]) : 1.0f;
     const float ep_bias = (ep_on && p.bias) ? __half2float(p.bias[ep_o]) : 0.0f;
 
-    VQ_STAMP(4);
 
     for (int rl0 = start; rl0 < row_end; rl0 += DEPTH * step) {
 #pragma unroll
@@ -261,12 +248,6 @@ __device__ __forceinline__ void gemv_v6_body(const Params &p, const GemvPlan &pl
           Window<NR> cr;
           normalize_from(cm, wm[d], sh_main);
           if (RES_BITS && is_main) normalize_from(cr, wr[d], sh_res);
-          uint3v g[L1R > 0 ? L1R : 1];
-          if (L1R > 0 && is_main) {             // memory-side residual gathers go out before the refill loads
-#pragma unroll
-            for (int u = 0; u < L1R; ++u)
-              g[u] = __builtin_amdgcn_raw_buffer_load_b96(r_cbres, field<RB>(cr, u) * 12u, 0, 0);
-          }
           if (rl + DEPTH * step < row_end) {  // refill this slot with the row DEPTH steps ahead
             const unsigned r = (unsigned)(chunk0 + rl + DEPTH * step);
             load_window(wm[d], r_main, r * st_main, dw_main);
@@ -296,25 +277,17 @@ __device__ __forceinline__ void gemv_v6_body(const Params &p, const GemvPlan &pl
             if (RES_BITS) {
               uint4v f[U];
 #pragma unroll
-              for (int u = L1R; u < U; ++u) lds_gather16<LY::RES_OFF>(f[u], field_addr<RB, LY::RES_SH>(cr, u) + LY::RES_ADD);
+              for (int u = 0; u < U; ++u) lds_gather16<LY::RES_OFF>(f[u], field_addr<RB, LY::RES_SH>(cr, u) + LY::RES_ADD);
               lds_gather_wait();
 #pragma unroll
-              for (int u = L1R; u < U; ++u) settle(f[u]);
+              for (int u = 0; u < U; ++u) settle(f[u]);
 #pragma unroll
-              for (int u = L1R; u < U; ++u)
+              for (int u = 0; u < U; ++u)
 #pragma unroll
                 for (int b = 0; b < B; ++b) {
                   acc[b] = dot2(f[u].x, xr[b][u][0], acc[b]);
                   acc[b] = dot2(f[u].y, xr[b][u][1], acc[b]);
                   acc[b] = dot2(f[u].z, xr[b][u][2], acc[b]);
-                }
-#pragma unroll
-              for (int u = 0; u < L1R; ++u)
-#pragma unroll
-                for (int b = 0; b < B; ++b) {
-                  acc[b] = dot2(g[u].x, xr[b][u][0], acc[b]);
-                  acc[b] = dot2(g[u].y, xr[b][u][1], acc[b]);
-                  acc[b] = dot2(g[u].z, xr[b][u][2], acc[b]);
                 }
             }
           } else {
@@ -341,9 +314,7 @@ __device__ __forceinline__ void gemv_v6_body(const Params &p, const GemvPlan &pl
         }
       }
     }
-    VQ_STAMP(5);
     __syncthreads();
-    VQ_STAMP(6);
     // ---- combine slices, apply scale and bias, store
     if (ep_on) {
       float s = 0.0f;
@@ -353,15 +324,14 @@ __device__ __forceinline__ void gemv_v6_body(const Params &p, const GemvPlan &pl
       y[ep_b * ldy + ep_o] = __float2half_rn(__fmaf_rn(ep_scale, s, ep_bias * xs));
     }
     __syncthreads();
-    VQ_STAMP(7);
   }
 }
 
-template <int RES_BITS, int B, int U, int L1R>
+template <int RES_BITS, int B, int U>
 __global__ __launch_bounds__(NW * 64) void gemv_v6_kernel(Params p, GemvPlan plan, const __half *__restrict__ x, long long ldx,
                                                           __half *__restrict__ y, long long ldy) {
   warm_kernel_arguments();                      // Params + GemvPlan + four scalars: about 250 bytes
-  gemv_v6_body<RES_BITS, B, U, L1R>(p, plan, x, ldx, y, ldy, (int)blockIdx.x);
+  gemv_v6_body<RES_BITS, B, U>(p, plan, x, ldx, y, ldy, (int)blockIdx.x);
 }
 
 // Several layers on one activation row in one launch (the query, key and value projections; gate and up): every
@@ -385,30 +355,14 @@ __global__ __launch_bounds__(NW * 64) void gemv_v6_multi_kernel(MultiArgs a, con
   int i = 0;
   while (i + 1 < a.n && (int)blockIdx.x >= a.first_wg[i + 1]) ++i;
   const MultiLayer &l = a.layer[i];
-  gemv_v6_body<RES_BITS, 1, U, 0>(l.p, l.plan, x, 0, l.y, 0, (int)blockIdx.x - a.first_wg[i]);
+  gemv_v6_body<RES_BITS, 1, U>(l.p, l.plan, x, 0, l.y, 0, (int)blockIdx.x - a.first_wg[i]);
 }
 
-int g_cu_count = 0;
-
-int cu_count() {
-  if (g_cu_count == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
-    g_cu_count = n;
-  }
-  return g_cu_count;
-}
-
-template <int RES_BITS, int B, int U, int L1R = 0>
+template <int RES_BITS, int B, int U>
 int launch_one(const Params &p, const GemvPlan &plan, unsigned lds_bytes, unsigned grid, const __half *x, long long ldx,
                __half *y, long long ldy, hipStream_t s) {
-  static bool configured = false;
-  auto kernel = gemv_v6_kernel<RES_BITS, B, U, L1R>;
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-      return VQ_ERR_HIP;
-    configured = true;
-  }
+  auto kernel = gemv_v6_kernel<RES_BITS, B, U>;
+  VQ_ALLOW_FULL_LDS(kernel);
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(NW * 64), lds_bytes, s, p, plan, x, ldx, y, ldy);
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
@@ -417,12 +371,6 @@ template <int RES_BITS, int B>
 int launch_u(int U, const Params &p, const GemvPlan &plan, unsigned lds_bytes, unsigned grid, const __half *x, long long ldx,
              __half *y, long long ldy, hipStream_t s) {
   if (U == 4) return launch_one<RES_BITS, B, 4>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
-  if constexpr (RES_BITS == 8 && B == 1) {
-    static const int l1r = [] { const char *e = getenv("VQ_GEMV_L1R"); return e ? atoi(e) : 0; }();
-    if (U == 5 && l1r == 1) return launch_one<8, 1, 5, 1>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
-    if (U == 5 && l1r == 2) return launch_one<8, 1, 5, 2>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
-    if (U == 5 && l1r == 3) return launch_one<8, 1, 5, 3>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
-  }
   // (the combinations u_allowed() admits, no others: each costs build time and library size)
   if constexpr (B <= 2) {
     if (U == 5) return launch_one<RES_BITS, B, 5>(p, plan, lds_bytes, grid, x, ldx, y, ldy, s);
@@ -438,11 +386,6 @@ int launch_u(int U, const Params &p, const GemvPlan &plan, unsigned lds_bytes, u
 
 }  // namespace
 
-#ifdef VQ_PROFILE
-extern "C" int vq_debug_read_profile(unsigned long long *dst, size_t count) {
-  return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_prof), count * sizeof(unsigned long long));
-}
-#endif
 
 // Whether the fast kernels take this layer and these buffers.
 bool gemv_fast_applicable(const Params &p, const __half *x, long long ldx) {
@@ -527,13 +470,8 @@ int make_plan(const Params &p, int batch, int rows_per_wg, int u_force, GemvPlan
 
 template <int RES_BITS, int U>
 int launch_multi(const MultiArgs &a, unsigned lds_bytes, unsigned grid, const __half *x, hipStream_t s) {
-  static bool configured = false;
   auto kernel = gemv_v6_multi_kernel<RES_BITS, U>;
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-      return VQ_ERR_HIP;
-    configured = true;
-  }
+  VQ_ALLOW_FULL_LDS(kernel);
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(NW * 64), lds_bytes, s, a, x);
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }

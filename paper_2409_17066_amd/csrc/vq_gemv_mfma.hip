@@ -26,12 +26,6 @@
 #include <cstdlib>
 
 namespace vq {
-#ifdef VQ_PROFILE
-__device__ unsigned long long g_prof_m[1024 * 16 * 8];
-#define VQ_STAMP(i) do { if (lane == 0) g_prof_m[(blockIdx.x * 16 + wv) * 8 + (i)] = wall_clock64(); } while (0)
-#else
-#define VQ_STAMP(i) do { } while (0)
-#endif
 namespace {
 
 using namespace v6;
@@ -92,7 +86,6 @@ __device__ __forceinline__ void gemv_v6_mfma_body(const Params &p, const MfmaPla
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = lane & 15, g = lane >> 4;       // A: row n of the block, vector group g.  B: token n.  D: token n, rows 4g..4g+3
-  VQ_STAMP(0);
   const int row0 = wg * plan.rows_per_wg;
   const int rows_here = min(p.out_features - row0, plan.rows_per_wg);
   const int n_blocks = (rows_here + 15) >> 4;
@@ -217,7 +210,6 @@ __device__ __forceinline__ void gemv_v6_mfma_body(const Params &p, const MfmaPla
     }
 #pragma unroll
     for (int d = 0; d < XD; ++d) issue_x(bxs[d], d % eff_passes);
-    VQ_STAMP(1);
     wait_vmem_at_most<R * S + 8 * XD>();         // the tables are in; the index words may still be on their way
     tables.store(p, lds, plan.lds_out, grp == 0 && !plan.out_global, tid);
   }
@@ -227,9 +219,7 @@ __device__ __forceinline__ void gemv_v6_mfma_body(const Params &p, const MfmaPla
     const unsigned short bi = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r_bias, (unsigned)(row0 + r) * 2u, 0, 0);
     *reinterpret_cast<unsigned *>(lds + plan.lds_sb + (unsigned)r * 4u) = (unsigned)sc | ((unsigned)bi << 16);
   }
-  VQ_STAMP(2);
   lds_barrier();
-  VQ_STAMP(3);
   // The counted waits assume the steady pattern of loads that only the loop below issues: everything issued so
   // far has to be in first.
   wait_vmem_at_most<0>();
@@ -367,13 +357,11 @@ __device__ __forceinline__ void gemv_v6_mfma_body(const Params &p, const MfmaPla
 
         if (pass == eff_passes - 1) {
           // ---- chunk end: partial sums to LDS; wave b adds up block b, applies scale and bias, stores
-          VQ_STAMP(4);
           unsigned char *pbase = lds + plan.lds_part + (unsigned)(buf * NB) * (MW * 1024u);
 #pragma unroll
           for (int b = 0; b < NB; ++b)
             if (b < nb_c) *reinterpret_cast<float4v *>(pbase + (unsigned)(b * MW + wv) * 1024u + lane * 16u) = acc[b];
           lds_barrier();
-          VQ_STAMP(5);
           if (wv < nb_c) {
             float4v s = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
@@ -424,7 +412,6 @@ __device__ __forceinline__ void gemv_v6_mfma_body(const Params &p, const MfmaPla
             }
             }
           }
-          VQ_STAMP(6);
           if (plan.part_bufs == 1) lds_barrier(); else buf ^= 1;
           pass = 0; ++c;
         } else {
@@ -525,27 +512,12 @@ __global__ __launch_bounds__(MW * 64) void gemv_v6_mfma_multi_kernel(MultiArgs a
   gemv_v6_mfma_body<RES_BITS, MW, NB, false>(l.p, l.plan, x, ldx, batch, l.y, l.ldy, (int)blockIdx.x - a.first_wg[i]);
 }
 
-int g_cu_count = 0;
-
-int cu_count() {
-  if (g_cu_count == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
-    g_cu_count = n;
-  }
-  return g_cu_count;
-}
 
 template <int RES_BITS, int MW, int NB, bool GROUPED>
 int launch_one(const Params &p, const MfmaPlan &plan, unsigned lds_bytes, unsigned grid, const __half *x, long long ldx, int batch,
                __half *y, long long ldy, hipStream_t s) {
-  static bool configured = false;
   auto kernel = gemv_v6_mfma_kernel<RES_BITS, MW, NB, GROUPED>;
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-      return VQ_ERR_HIP;
-    configured = true;
-  }
+  VQ_ALLOW_FULL_LDS(kernel);
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(MW * 64), lds_bytes, s, p, plan, x, ldx, batch, y, ldy);
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
@@ -558,11 +530,6 @@ constexpr int NARROW_WAVES = 4;            // workgroup size for layers whose co
 
 }  // namespace
 
-#ifdef VQ_PROFILE
-extern "C" int vq_debug_read_profile_m(unsigned long long *dst, size_t count) {
-  return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_prof_m), count * sizeof(unsigned long long));
-}
-#endif
 
 namespace {
 
@@ -599,10 +566,9 @@ int make_plan(const Params &p, int batch, long long ldx, const __half *y, long l
   const int fit = (int)((lds_cap - off) / ((unsigned)waves * 1024u));    // 16-row partial blocks that fit
   // Blocks per chunk: as many as the kernel's 256 registers allow -- four, or three with a residual index stream in the
   // prefetch ring.  More would spill, which these kernels must not (see the build script).
-  static const int nb_cap = [] { const char *e = getenv("VQ_MFMA_NB"); return e ? atoi(e) : NBMAX; }();
   // (with codebook groups one fewer: the group loop costs registers of its own)
   const int nb_regs = grouped ? (rb == 12 ? 2 : 3) : (rb ? 3 : NBMAX);
-  plan.nb = min(min(min(nb_regs, nb_cap), blocks_per_wg), fit);
+  plan.nb = min(min(nb_regs, blocks_per_wg), fit);
   if (nb_force > 0) { if (nb_force > plan.nb) return VQ_ERR_UNSUPPORTED; plan.nb = nb_force; }
   if (plan.nb < 1) return VQ_ERR_UNSUPPORTED;
   plan.part_bufs = (fit >= 2 * plan.nb && blocks_per_wg > plan.nb) ? 2 : 1;
@@ -624,19 +590,13 @@ int make_plan(const Params &p, int batch, long long ldx, const __half *y, long l
 // loads dominate, and twice as many workgroups doing them was measured slower (15 groups of 48 vectors on an
 // 11008 x 4096 layer, batch 4: 66 us against 55 us).
 bool narrow_groups(const Params &p) {
-  static const int mode = [] { const char *e = getenv("VQ_MFMA_NARROW"); return e ? atoi(e) : -1; }();
-  return mode != 0 && p.n_groups > 1 && (p.Pg + 31) / 32 <= NARROW_WAVES && !(p.k_res && p.bits_res == 12) && p.Q == 0;
+  return p.n_groups > 1 && (p.Pg + 31) / 32 <= NARROW_WAVES && !(p.k_res && p.bits_res == 12) && p.Q == 0;
 }
 
 template <int RES_BITS, int NB>
 int launch_multi(const MultiArgs &a, unsigned lds_bytes, unsigned grid, const __half *x, long long ldx, int batch, hipStream_t s) {
-  static bool configured = false;
   auto kernel = gemv_v6_mfma_multi_kernel<RES_BITS, MW, NB>;
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-      return VQ_ERR_HIP;
-    configured = true;
-  }
+  VQ_ALLOW_FULL_LDS(kernel);
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(MW * 64), lds_bytes, s, a, x, ldx, batch);
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }

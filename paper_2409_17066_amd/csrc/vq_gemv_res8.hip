@@ -370,14 +370,6 @@ __global__ __launch_bounds__(NW * 64) void gemv_res8_kernel(Params p, Res8Plan p
   gemv_res8_body<U>(p, plan, x, y, (int)blockIdx.x);
 }
 
-int cu_count_res8() {
-  static const int n = [] {
-    int dev = 0, c = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&c, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || c < 1) c = 256;
-    return c;
-  }();
-  return n;
-}
 
 template <int U>
 int launch_one(const Params &p, const Res8Plan &plan, unsigned lds_bytes, unsigned grid, const __half *x, __half *y, hipStream_t s) {
@@ -403,7 +395,7 @@ bool gemv_res8_applicable(const Params &p, const __half *x) {
 int launch_gemv_res8(const Params &p, const __half *x, __half *y, hipStream_t s) {
   static const int kU[] = {4, 5, 6};
   Res8Plan plan{};
-  const int g = min(cu_count_res8(), p.out_features);
+  const int g = min(cu_count(), p.out_features);
   plan.rows_per_wg = min((p.out_features + g - 1) / g, MAX_ROWS_PER_WG);
   const unsigned grid = (unsigned)((p.out_features + plan.rows_per_wg - 1) / plan.rows_per_wg);
   const long long max_stride = max(p.stride, max(p.stride_res, p.stride_out));

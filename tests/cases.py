@@ -34,6 +34,9 @@ SMALL = {
     "v6_chunks_res12": dict(out_features=12303, in_features=198, v=6, k=4096, k_res=4096),
     "v6_passes": dict(out_features=40, in_features=7000, v=6, k=4096, k_res=4096),
     "v6_passes_res8": dict(out_features=37, in_features=9100, v=6, k=4096, k_res=256),
+    # tables shorter than their index widths allow (the one-row kernel for 8-bit residual streams clamps its table loads), an
+    # outlier table in the padding of the other two, more rows than one round of its ring
+    "v6_short_tables_res8_outlier": dict(out_features=2300, in_features=2500, v=6, k=3000, k_res=200, n_outlier_cols=40, v_out=4, k_out=2100),
     # in_features a multiple of 256: vq_gemm's restore-then-multiply route (with a workspace) takes any layer
     "v6_dense_gemm": dict(out_features=203, in_features=1024, v=6, k=4096, k_res=4096, n_outlier_cols=16, v_out=4, k_out=4096),
     # codebook groups: a table (and residual table) per range of vectors.  Group sizes that are multiples of 8 vectors run

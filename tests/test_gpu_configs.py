@@ -41,7 +41,7 @@ def _matmul_ok(y, ref, what):
     assert np.isfinite(y).all() and err <= TOL * rms, "%s: err %.3e rms %.3e" % (what, err, rms)
 
 
-@pytest.mark.parametrize("cfg,name", [(0, "tiny"), (1, "up"), (2, "q"), (2, "gate"), (2, "down"), (3, "down70b"), (4, "prefill")])
+@pytest.mark.parametrize("cfg,name", [(0, "tiny"), (1, "up"), (2, "q"), (2, "o"), (2, "gate"), (2, "down"), (3, "down70b"), (4, "prefill")])
 def test_config_dequant_and_gemv(gpu_lib, layers, monkeypatch, cfg, name):
     import torch
     ordinal, L = layers(cfg, name)
@@ -54,10 +54,10 @@ def test_config_dequant_and_gemv(gpu_lib, layers, monkeypatch, cfg, name):
         xd = torch.from_numpy(x).cuda()
         for kernel in ("auto", "m", "d"):              # default dispatch, matrix-core kernel, dot-product kernels
             if kernel != "auto":
-                monkeypatch.setenv("VQ_GEMV_KERNEL", kernel)
+                monkeypatch.setenv("VQ_SWITCHES", "gemv=" + kernel)
             y = gpu_lib.gemv(dl, xd)
             torch.cuda.synchronize()
-            monkeypatch.delenv("VQ_GEMV_KERNEL", raising=False)
+            monkeypatch.delenv("VQ_SWITCHES", raising=False)
             _matmul_ok(y, ref, "cfg%d %s batch %d kernel %s" % (cfg, name, batch, kernel))
 
 

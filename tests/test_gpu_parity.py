@@ -20,6 +20,25 @@ def _check_matmul(y_gpu, y_ref, what):
 
 
 @pytest.mark.parametrize("name", list(SMALL))
+@pytest.mark.parametrize("pad", [8, 16, 24])
+def test_dequant_leaves_the_padding_of_aligned_rows_alone(gpu_lib, name, pad):
+    """Leading dimensions that keep every row 16-byte aligned (the layouts the kernels with 16-byte stores take): the
+    logical columns bit-exact, the columns [in_features, ldw) still holding the caller's sentinel."""
+    import torch
+    L = small_layer(name)
+    dl = gpu_lib.DeviceLayer(L)
+    ldw = (L.in_features + 7) // 8 * 8 + pad
+    W = torch.full((L.out_features, ldw), -3.5, dtype=torch.float16, device="cuda")
+    rc = gpu_lib.vq_dequant(dl.desc, W.data_ptr(), ldw, torch.cuda.current_stream().cuda_stream)
+    assert rc == 0
+    torch.cuda.synchronize()
+    got = W.cpu().numpy()
+    want = oracle.dequant(L, L.in_features)
+    assert np.array_equal(got[:, :L.in_features].view(np.uint16), want.view(np.uint16)), name
+    assert (got[:, L.in_features:] == np.float16(-3.5)).all(), name
+
+
+@pytest.mark.parametrize("name", list(SMALL))
 def test_dequant_bit_exact_small(gpu_lib, name):
     import torch
     L = small_layer(name)
@@ -39,7 +58,7 @@ def test_gemv_small(gpu_lib, monkeypatch, name, batch, kernel):
     (layers they do not take fall through to the generic kernel)."""
     import torch
     if kernel != "auto":
-        monkeypatch.setenv("VQ_GEMV_KERNEL", kernel)
+        monkeypatch.setenv("VQ_SWITCHES", "gemv=" + kernel)
     L = small_layer(name)
     dl = gpu_lib.DeviceLayer(L)
     x = s.make_activations(300, L, batch)
@@ -48,22 +67,25 @@ def test_gemv_small(gpu_lib, monkeypatch, name, batch, kernel):
     _check_matmul(y, oracle.gemv(L, x), "%s batch %d" % (name, batch))
 
 
-@pytest.mark.parametrize("name", list(SMALL))
+# (the restore-then-multiply route exists for layers whose in_features is a multiple of 256: only those get its cases)
+GEMM_CASES = [(name, ws) for name in SMALL for ws in (None, "fast", "fast, 256 x 256 tiles")
+              if ws is None or SMALL[name]["in_features"] % 256 == 0]
+
+
+@pytest.mark.parametrize("name,workspace", GEMM_CASES)
 @pytest.mark.parametrize("tokens", [1, 37, 130, 300])
-@pytest.mark.parametrize("workspace", [None, "fast", "fast, 256 x 256 tiles"])
 def test_gemm_small(gpu_lib, monkeypatch, name, tokens, workspace):
     """Without a workspace (weights restored on the fly) and with the one that lets vq_gemm restore W once (that
     route forced: by itself the library keeps small token counts on the on-the-fly kernel where it has one), the dense
     product by the kernel with producer waves and by the four-wave kernel with 256 x 256 tiles."""
     import torch
     if workspace is not None:
-        monkeypatch.setenv("VQ_GEMM_KERNEL", "w")
-        monkeypatch.setenv("VQ_GEMM_DENSE", "1" if "256" in workspace else "0")      # the dense product's two kernels
+        monkeypatch.setenv("VQ_SWITCHES", "gemm=w,dense=" + ("1" if "256" in workspace else "0"))      # the dense product's two kernels
         workspace = "fast"
     L = small_layer(name)
     dl = gpu_lib.DeviceLayer(L)
-    if workspace == "fast" and gpu_lib.vq_gemm_fast_workspace_bytes(dl.desc, tokens) == 0:
-        pytest.skip("no restore-then-multiply route for this shape")
+    if workspace == "fast":
+        assert gpu_lib.vq_gemm_fast_workspace_bytes(dl.desc, tokens) > 0
     x = s.make_activations(300, L, tokens)
     ldx = (L.in_features + 7) // 8 * 8
     X = torch.zeros((tokens, ldx), dtype=torch.float16, device="cuda")
@@ -83,7 +105,7 @@ def test_gemv_strided_buffers_and_untouched_padding(gpu_lib, monkeypatch, name, 
     in the output padding (they must survive); odd output strides take the kernels' narrow store paths."""
     import torch
     if kernel != "auto":
-        monkeypatch.setenv("VQ_GEMV_KERNEL", kernel)
+        monkeypatch.setenv("VQ_SWITCHES", "gemv=" + kernel)
     L = small_layer(name)
     dl = gpu_lib.DeviceLayer(L)
     x = s.make_activations(300, L, batch)
@@ -155,7 +177,7 @@ def test_gemv_multi(gpu_lib, monkeypatch, name, batch):
     outs = [torch.full((batch, L.out_features + pad), -7.0, dtype=torch.float16, device="cuda") for L in layers]
     ys = gpu_lib.gemv_multi(dls, x, outs=[o[:, :L.out_features] for o, L in zip(outs, layers)])
     torch.cuda.synchronize()
-    monkeypatch.setenv("VQ_GEMV_KERNEL", "m")
+    monkeypatch.setenv("VQ_SWITCHES", "gemv=m")
     for L, dl, y, o in zip(layers, dls, ys, outs):
         _check_matmul(y, oracle.gemv(L, x_np), "%s / %s batch %d" % (name, L.name, batch))
         assert (o[:, L.out_features:] == -7.0).all()
@@ -168,7 +190,7 @@ def test_gemv_multi(gpu_lib, monkeypatch, name, batch):
 @pytest.mark.parametrize("name", FUSED_SETS)
 def test_gemv_multi_single_row_with_the_matrix_core_body(gpu_lib, monkeypatch, name):
     import torch
-    monkeypatch.setenv("VQ_GEMV_KERNEL", "m")
+    monkeypatch.setenv("VQ_SWITCHES", "gemv=m")
     layers = multi_layers(name)
     dls = [gpu_lib.DeviceLayer(L) for L in layers]
     x_np = s.make_activations(400, layers[0], 1)
@@ -184,8 +206,7 @@ def test_gemv_multi_one_by_one_matches_fused(gpu_lib, monkeypatch):
     dls = [gpu_lib.DeviceLayer(L) for L in layers]
     x = torch.from_numpy(s.make_activations(400, layers[0], 4)).cuda()
     fused = [y.clone() for y in gpu_lib.gemv_multi(dls, x)]
-    monkeypatch.setenv("VQ_GEMV_MULTI", "0")
-    monkeypatch.setenv("VQ_GEMV_KERNEL", "m")
+    monkeypatch.setenv("VQ_SWITCHES", "multi=0,gemv=m")
     apart = gpu_lib.gemv_multi(dls, x)
     torch.cuda.synchronize()
     for a, b in zip(fused, apart):
