@@ -33,6 +33,7 @@ class _Layer(ctypes.Structure):
         ("idx_out", ctypes.c_void_p), ("idx_out_row_stride", ctypes.c_int64),
         ("scale", ctypes.c_void_p), ("bias", ctypes.c_void_p),
         ("group_vectors", ctypes.c_int32), ("orientation", ctypes.c_int32),
+        ("col_perm", ctypes.c_void_p),
     ]
 
 
@@ -82,7 +83,8 @@ def _describe(layer):
         codebook=_c(layer.codebook, np.float16), codebook_res=_c(layer.codebook_res, np.float16),
         codebook_out=_c(layer.codebook_out, np.float16), idx=_c(layer.idx, np.uint8),
         idx_res=_c(layer.idx_res, np.uint8), idx_out=_c(layer.idx_out, np.uint8),
-        scale=_c(layer.scale, np.float16), bias=_c(layer.bias, np.float16))
+        scale=_c(layer.scale, np.float16), bias=_c(layer.bias, np.float16),
+        col_perm=_c(getattr(layer, "col_perm", None), np.int32))
 
     def stride(a):
         return a.shape[1] if a is not None else 0
@@ -91,7 +93,7 @@ def _describe(layer):
                _ptr(keep["codebook"]), _ptr(keep["codebook_res"]), _ptr(keep["codebook_out"]),
                _ptr(keep["idx"]), stride(keep["idx"]), _ptr(keep["idx_res"]), stride(keep["idx_res"]),
                _ptr(keep["idx_out"]), stride(keep["idx_out"]), _ptr(keep["scale"]), _ptr(keep["bias"]),
-               int(getattr(layer, "group_vectors", 0)), int(getattr(layer, "orientation", 0)))
+               int(getattr(layer, "group_vectors", 0)), int(getattr(layer, "orientation", 0)), _ptr(keep["col_perm"]))
     return d, keep
 
 

@@ -118,7 +118,7 @@ struct RowDecoder {
         }
       }
       const float w32 = std::fmaf(s, d, bias);          // scale*d + bias, one rounding
-      w16[c] = vq_oracle_float_to_half(w32);
+      w16[L->col_perm ? L->col_perm[c] : c] = vq_oracle_float_to_half(w32);     // stored column c is the layer's column col_perm[c]
     }
     return VQO_OK;
   }
@@ -132,6 +132,14 @@ int check_layer(const vq_oracle_layer *L) {
   if (L->n_outlier_cols) {
     if (!L->codebook_out || !L->idx_out || L->v_out < 1 || L->k_out < 1) return VQO_ERR_ARG;
     if ((L->orientation == 0 && L->n_outlier_cols % L->v_out) || L->n_outlier_cols > L->in_features) return VQO_ERR_ARG;
+  }
+  if (L->col_perm) {                                  // every column number exactly once
+    std::vector<char> seen(L->in_features, 0);
+    for (int64_t c = 0; c < L->in_features; ++c) {
+      const int32_t t = L->col_perm[c];
+      if (t < 0 || t >= L->in_features || seen[t]) return VQO_ERR_ARG;
+      seen[t] = 1;
+    }
   }
   return VQO_OK;
 }

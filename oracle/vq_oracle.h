@@ -9,7 +9,8 @@
  * "Vector Quantization"), the residual codebook's centroid is added to it
  * (Sec. 3.2.2, "Residual Vector Quantization"), a small set of outlier
  * columns uses a codebook of its own (Sec. 3.2.3, "Outlier Elimination";
- * parameters v0,k0,v1,k1,k2 of App. "Parameter Description"), the weight
+ * parameters v0,k0,v1,k1,k2 of App. "Parameter Description"; the columns are
+ * picked by the Hessian's diagonal, hence a column permutation), the weight
  * matrix may be split into groups that each have a codebook of their own
  * (Sec. 3.1, the paragraph on groups; "group num" in the parameter tables), and
  * the restored FP16 matrix multiplies the activations (App. "Our Dequantization
@@ -55,6 +56,13 @@ typedef struct vq_oracle_layer {
    * index per outlier column (n_outlier_cols need not be a multiple of v_out here).  Codebook groups are ranges of
    * group_vectors stream positions, i.e. of main columns.  Scale and bias stay per output row.                  */
   int32_t orientation;
+  /* Column order.  The columns that get the outlier codebook are the ones the Hessian's diagonal singles out (Sec.
+   * 3.2.3), wherever they lie, so the stored order of the columns is a permutation of the layer's: with col_perm != NULL
+   * (int32 [in_features], every column number exactly once) everything said above about "column c" describes STORED
+   * column c, which is column col_perm[c] of the layer: W[o][col_perm[c]] is the value restored for (o, c), and stored
+   * column c meets x[col_perm[c]].  The outlier columns of the layer are col_perm[0 .. n_outlier_cols).  NULL: the
+   * identity.                                                                                                  */
+  const int32_t *col_perm;
 } vq_oracle_layer;
 
 enum { VQO_OK = 0, VQO_ERR_ARG = -1, VQO_ERR_INDEX_RANGE = -2 };

@@ -238,6 +238,52 @@ def test_index_out_of_range_is_reported():
         oracle.dequant(L)
 
 
+def test_column_permutation_places_stored_columns():
+    """Sec. 3.2.3: the outlier columns are wherever the Hessian's diagonal puts them; the stored order is a permutation."""
+    kw = dict(out_features=4, in_features=50, k_res=16, n_outlier_cols=8, v_out=4, k_out=32)
+    L = _tiny(permute=True, **kw)
+    perm = L.col_perm
+    assert sorted(perm) == list(range(50)) and list(perm) != list(range(50))
+    stored = oracle.dequant(_tiny(**kw)).view(np.uint16)               # the same streams and tables without the permutation
+    W = oracle.dequant(L).view(np.uint16)
+    for c in range(50):
+        assert np.array_equal(W[:, perm[c]], stored[:, c]), c
+    # x = e_t picks column t of the layer: the token that is one at perm[c] returns stored column c
+    y = oracle.matmul(L, np.eye(50, dtype=np.float16))
+    assert np.array_equal(y[perm], oracle.dequant(_tiny(**kw)).astype(np.float64).T)
+    # the product with x equals the product of the stored-order layer with the gathered activations, term for term
+    x = s.make_activations(200, L, 3)
+    got, want = oracle.matmul(L, x), oracle.matmul(_tiny(**kw), np.ascontiguousarray(x[:, perm]))
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-300)              # same terms, other order of summation
+    # the outlier stream reaches exactly the columns perm[0 .. 8)
+    M = _tiny(permute=True, **kw)
+    M.raw_idx_out[:] = (M.raw_idx_out + 1) % M.k_out
+    _repack(M)
+    changed = (oracle.dequant(M).view(np.uint16) != W).any(axis=0)
+    assert set(np.flatnonzero(changed)) <= set(perm[:8].tolist()) and changed[perm[:8]].any()
+    # the identity is no permutation at all
+    I = _tiny(**kw)
+    I.col_perm = np.arange(50, dtype=np.int32)
+    assert np.array_equal(oracle.dequant(I).view(np.uint16), stored)
+
+
+def test_column_permutation_must_be_a_permutation():
+    L = _tiny(permute=True)
+    for bad in ("dup", "range", "neg"):
+        M = _tiny(permute=True)
+        M.col_perm = L.col_perm.copy()
+        if bad == "dup":
+            M.col_perm[3] = M.col_perm[4]
+        elif bad == "range":
+            M.col_perm[0] = 31
+        else:
+            M.col_perm[5] = -1
+        with pytest.raises(oracle.OracleError):
+            oracle.dequant(M)
+        with pytest.raises(oracle.OracleError):
+            oracle.matmul(M, s.make_activations(200, M, 1))
+
+
 # ---------------------------------------------------------------- naive definition (test-local)
 def _round_fraction(q: Fraction, precision: int, emin: int) -> Fraction:
     """Round an exact rational to a binary float with `precision` significand bits, min exponent emin, ties-to-even."""
@@ -280,6 +326,11 @@ def _naive_dequant(L):
                     d = _round_fraction(d + Fraction(float(r)), 24, -126)
             w32 = _round_fraction(sc * d + bi, 24, -126)
             W[o, c] = float(_round_fraction(w32, 11, -14))
+    if L.col_perm is not None:                 # what was computed is the stored order: stored column c is column col_perm[c]
+        placed = np.full_like(W, np.nan)
+        for c in range(L.in_features):
+            placed[:, int(L.col_perm[c])] = W[:, c]
+        W = placed
     return W
 
 
@@ -299,6 +350,11 @@ CASES = [
     dict(out_features=20, in_features=37, v=6, k=64, k_res=16, n_outlier_cols=5, v_out=4, k_out=32, orientation=1),
     dict(out_features=13, in_features=9, v=8, k=300, orientation=1, with_scale=False),
     dict(out_features=7, in_features=30, v=3, k=16, k_res=4, orientation=1, group_vectors=8, with_bias=False),
+    # stored column order is a permutation of the layer's (outlier columns scattered over the layer)
+    dict(out_features=3, in_features=47, v=6, k=4096, k_res=256, n_outlier_cols=8, v_out=4, k_out=4096, permute=True),
+    dict(out_features=4, in_features=29, v=6, k=64, permute=True),
+    dict(out_features=3, in_features=75, v=6, k=64, k_res=16, n_outlier_cols=8, v_out=4, k_out=32, group_vectors=8, permute=True),
+    dict(out_features=20, in_features=37, v=6, k=64, k_res=16, n_outlier_cols=5, v_out=4, k_out=32, orientation=1, permute=True),
 ]
 
 

@@ -40,6 +40,7 @@ class VQLayer:
     raw_idx: np.ndarray = None           # int32 [out][P]   (what was packed)
     raw_idx_res: np.ndarray = None
     raw_idx_out: np.ndarray = None
+    col_perm: np.ndarray = None          # int32 [in_features] or None: stored column c is column col_perm[c] of the layer
 
     # An index stream holds `vectors_per_row` indices.  Orientation 0: one stream per output row, a vector covers v
     # consecutive input columns.  Orientation 1 (the paper's: Sec. 3.1, a column is a stack of centroids): one stream per v
@@ -93,10 +94,11 @@ class VQLayer:
 def make_layer(config: int, name: str, out_features: int, in_features: int, v: int, k: int,
                k_res: int = 0, n_outlier_cols: int = 0, v_out: int = 0, k_out: int = 0,
                layer_ordinal: int = 0, with_scale: bool = True, with_bias: bool = True,
-               extra_stride: int = 0, group_vectors: int = 0, orientation: int = 0) -> VQLayer:
+               extra_stride: int = 0, group_vectors: int = 0, orientation: int = 0, permute: bool = False) -> VQLayer:
     """Build one layer from the seeded streams.  `extra_stride` adds 16-byte units of row padding; with
     `group_vectors` every range of that many vectors gets main (and residual) tables of its own, all drawn from
-    one stream, group after group."""
+    one stream, group after group; `permute` stores the columns in a seeded random order (the outlier columns
+    are then scattered over the layer, as columns picked by a Hessian's diagonal are)."""
     def seed(t):
         return g.tensor_seed(config, t, layer_ordinal)
 
@@ -115,6 +117,8 @@ def make_layer(config: int, name: str, out_features: int, in_features: int, v: i
         L.codebook_out = g.to_fp16(g.normal(seed(g.T_CODEBOOK_OUT), k_out * v_out, SIGMA_OUT)).reshape(k_out, v_out)
         L.raw_idx_out = g.random_indices(seed(g.T_IDX_OUT), L.outlier_streams, Q, k_out)
         L.idx_out = pack_indices(L.raw_idx_out, L.bits_out, row_stride_bytes(Q, L.bits_out) + 16 * extra_stride)
+    if permute:
+        L.col_perm = g.permutation(seed(g.T_PERM), in_features)
     if with_scale:
         L.scale = g.to_fp16(0.5 + g.uniform01(seed(g.T_SCALE), out_features))
     if with_bias:
@@ -128,7 +132,8 @@ def make_activations(config: int, layer: VQLayer, rows: int, layer_ordinal: int 
     s = g.tensor_seed(config, g.T_ACT, layer_ordinal, rows)
     x = g.normal(s, rows * layer.in_features, 1.0).reshape(rows, layer.in_features)
     if layer.n_outlier_cols and outlier_gain != 1.0:
-        x[:, : layer.n_outlier_cols] *= outlier_gain
+        cols = np.arange(layer.n_outlier_cols) if layer.col_perm is None else layer.col_perm[: layer.n_outlier_cols]
+        x[:, cols] *= outlier_gain
     return g.to_fp16(x)
 
 

@@ -14,7 +14,7 @@ _BASE_SEED = 0x5650545100
 # tensor ids inside one layer
 T_CODEBOOK, T_CODEBOOK_RES, T_CODEBOOK_OUT = 0, 1, 2
 T_IDX, T_IDX_RES, T_IDX_OUT = 3, 4, 5
-T_SCALE, T_BIAS, T_ACT = 6, 7, 8
+T_SCALE, T_BIAS, T_ACT, T_PERM = 6, 7, 8, 9
 
 
 def tensor_seed(config: int, tensor_id: int, layer_ordinal: int = 0, batch_or_tokens: int = 0) -> int:
@@ -60,3 +60,8 @@ def random_indices(seed: int, rows: int, per_row: int, k: int) -> np.ndarray:
         z = splitmix64(seed, (r1 - r0) * per_row, start=r0 * per_row)
         out[r0:r1] = (z % np.uint64(k)).astype(np.int32).reshape(r1 - r0, per_row)
     return out
+
+
+def permutation(seed: int, n: int) -> np.ndarray:
+    """A permutation of 0 .. n-1 as int32: the order that sorts the first n stream elements (ties by position)."""
+    return np.argsort(splitmix64(seed, n), kind="stable").astype(np.int32)
