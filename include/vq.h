@@ -7,9 +7,9 @@
  * (App. "Parameter Description": v0,k0 / v1,k1 / k2):
  *   - a residual codebook of k_res entries with the same v, whose centroid is
  *     ADDED to the main one (Sec. 3.2.2 "Residual Vector Quantization");
- *   - outlier columns: the first n_outlier_cols input columns are coded with a
- *     codebook of their own (v_out, k_out) and have no residual
- *     (Sec. 3.2.3 "Outlier Elimination").
+ *   - outlier columns: the first n_outlier_cols input columns (of the stored
+ *     order: see col_perm) are coded with a codebook of their own (v_out,
+ *     k_out) and have no residual (Sec. 3.2.3 "Outlier Elimination").
  * Per-output-channel FP16 scale and bias are applied to the restored weight:
  *     W[o][c] = fp16( fma( scale[o], d[o][c], bias[o] ) ),  d in binary32.
  * Inference is two-phase (App. "Our Dequantization Implementation"): prompts
@@ -96,9 +96,25 @@ typedef struct vq_layer_desc {
    * 12-bit indices or v = 8 / 8- or 16-bit indices have fast vq_gemv and vq_dequant kernels of their own; others, and
    * vq_gemm without a workspace, run on the generic kernels.                                                        */
   int32_t orientation;
+  /* Column order (Sec. 3.2.3: the columns that get the outlier codebook are the ones the Hessian's diagonal singles
+   * out, wherever they lie; Algorithm 2's outlier step).  NULL: the stored order of the columns is the layer's.
+   * Otherwise int32 [in_features] in device memory, 4-byte aligned, every column number exactly once: everything this
+   * header says about "column c" then describes STORED column c, which is column col_perm[c] of the layer --
+   * vq_dequant writes the value restored for (o, c) to W[o][col_perm[c]], the products multiply it with
+   * x[col_perm[c]] -- and the layer's outlier columns are col_perm[0 .. n_outlier_cols).  The library does not check
+   * that the array is a permutation: entries outside [0, in_features) read as zero activations and are not stored
+   * by vq_dequant, repeated entries give unspecified values in the columns involved; neither leaves the buffers.
+   * Kernels: vq_gemv gathers the activations itself in its one- and two-row kernels for v = 6 layers and in the
+   * generic kernels; with a workspace (vq_gemv_with_workspace, vq_gemv_static_workspace, vq_gemm) the activations are
+   * first gathered into it (vq_gemv_workspace_bytes / vq_gemm_fast_workspace_bytes count that copy) and every kernel of
+   * the library then runs as for an unpermuted layer; vq_dequant restores in stored order and then reorders each
+   * row in place through LDS.  A caller that sets struct_size to VQ_LAYER_DESC_SIZE_V2 (the layout up to
+   * `orientation`) gets the identity.                                                                             */
+  const int32_t *col_perm;
 } vq_layer_desc;
 
 #define VQ_LAYER_DESC_SIZE_V1 ((uint32_t)offsetof(vq_layer_desc, group_vectors))
+#define VQ_LAYER_DESC_SIZE_V2 ((uint32_t)offsetof(vq_layer_desc, col_perm))
 
 /* Host-only check of a descriptor (no GPU work): the status any entry point would return for it. */
 int vq_validate(const vq_layer_desc *desc);

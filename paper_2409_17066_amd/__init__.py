@@ -25,6 +25,7 @@ class vq_layer_desc(ctypes.Structure):
         ("idx_out", ctypes.c_void_p), ("idx_out_row_stride", ctypes.c_int64),
         ("scale", ctypes.c_void_p), ("bias", ctypes.c_void_p),
         ("group_vectors", ctypes.c_int32), ("orientation", ctypes.c_int32),
+        ("col_perm", ctypes.c_void_p),
     ]
 
 
@@ -174,7 +175,8 @@ class DeviceLayer:
             up("codebook", layer.codebook), up("codebook_res", layer.codebook_res), up("codebook_out", layer.codebook_out),
             up("idx", layer.idx), stride(layer.idx), up("idx_res", layer.idx_res), stride(layer.idx_res),
             up("idx_out", layer.idx_out), stride(layer.idx_out), up("scale", layer.scale), up("bias", layer.bias),
-            int(getattr(layer, "group_vectors", 0)), int(getattr(layer, "orientation", 0)))
+            int(getattr(layer, "group_vectors", 0)), int(getattr(layer, "orientation", 0)),
+            up("col_perm", getattr(layer, "col_perm", None)))
 
 
 def _stream():

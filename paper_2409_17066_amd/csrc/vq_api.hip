@@ -53,9 +53,13 @@ static int check_stream(const void *idx, long long stride, int per_row, int bits
 
 int make_params(const vq_layer_desc *d, Params *p) {
   if (!d) return VQ_ERR_NULL;
-  if (d->struct_size != sizeof(vq_layer_desc) && d->struct_size != VQ_LAYER_DESC_SIZE_V1) return VQ_ERR_SHAPE;
-  const int group_vectors = d->struct_size == sizeof(vq_layer_desc) ? d->group_vectors : 0;
-  const int orientation = d->struct_size == sizeof(vq_layer_desc) ? d->orientation : 0;
+  if (d->struct_size != sizeof(vq_layer_desc) && d->struct_size != VQ_LAYER_DESC_SIZE_V1 && d->struct_size != VQ_LAYER_DESC_SIZE_V2)
+    return VQ_ERR_SHAPE;
+  const bool v2 = d->struct_size != VQ_LAYER_DESC_SIZE_V1;
+  const int group_vectors = v2 ? d->group_vectors : 0;
+  const int orientation = v2 ? d->orientation : 0;
+  const int32_t *col_perm = d->struct_size == sizeof(vq_layer_desc) ? d->col_perm : nullptr;
+  if (col_perm && !aligned(col_perm, 4)) return VQ_ERR_ALIGNMENT;
   if (group_vectors < 0 || (orientation != 0 && orientation != 1)) return VQ_ERR_SHAPE;
   const int lim = 1 << 24;
   if (d->out_features < 1 || d->out_features > lim || d->in_features < 1 || d->in_features > lim) return VQ_ERR_SHAPE;
@@ -109,6 +113,7 @@ int make_params(const vq_layer_desc *d, Params *p) {
   q.idx_out = q.n_out ? static_cast<const uint8_t *>(d->idx_out) : nullptr; q.stride_out = q.n_out ? d->idx_out_row_stride : 0;
   q.scale = static_cast<const __half *>(d->scale);
   q.bias = static_cast<const __half *>(d->bias);
+  q.perm = col_perm;
   if (p) *p = q;
   return VQ_OK;
 }

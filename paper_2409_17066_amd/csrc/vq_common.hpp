@@ -22,6 +22,7 @@ struct Params {
   const uint8_t *idx, *idx_res, *idx_out;
   long long stride, stride_res, stride_out;   // bytes per row of each stream
   const __half *scale, *bias;
+  const int *perm;               // stored column c is column perm[c] of the layer (Sec. 3.2.3); nullptr: the identity
 };
 
 // Lets a kernel use the whole 160 KB of LDS: once per kernel and process (a function-local static: thread-safe).
@@ -72,6 +73,11 @@ int launch_assign(const __half *W, const __half *B, long long ld, int rows, int 
                   unsigned char *idx, long long idx_stride, hipStream_t s);
 int launch_assign_down(const __half *W, const __half *B, long long ld, int rows, int cols, const __half *codebook, int v, int k,
                        unsigned char *idx, long long idx_stride, hipStream_t s);
+// Column order (Sec. 3.2.3): dst[t][c] = src[t][perm[c]] for c < cols (entries outside [0, cols) give zero), dst rows
+// ld_dst halfs apart; and the inverse on a matrix restored in stored order: W[o][perm[c]] = W_stored[o][c], row by row
+// through LDS, in place (VQ_ERR_UNSUPPORTED when a row does not fit LDS).
+int launch_gather_cols(const __half *src, long long ld_src, int rows, int cols, const int *perm, __half *dst, long long ld_dst, hipStream_t s);
+int launch_place_cols(__half *W, long long ldw, int rows, int cols, const int *perm, hipStream_t s);
 size_t gemm_workspace_bytes(const Params &p, int tokens);
 size_t gemm_fast_workspace_bytes(const Params &p, int tokens);
 

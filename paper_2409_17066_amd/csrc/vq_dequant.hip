@@ -4,8 +4,15 @@
 
 namespace vq {
 
+// Where stored column c of a row goes (Sec. 3.2.3: the stored order of the columns may be a permutation of the layer's).
+// Entries outside the row are dropped.
+__device__ __forceinline__ void store_col(const Params &p, __half *wrow, int c, __half value) {
+  const int t = p.perm ? p.perm[c] : c;
+  if ((unsigned)t < (unsigned)p.in_features) wrow[t] = value;
+}
+
 // Any (v, k, residual, outlier) combination: one thread restores one vector.  Consecutive threads
-// take consecutive vectors of one row, so a wave's stores cover one contiguous span of the row.
+// take consecutive vectors of one row, so a wave's stores cover one contiguous span of the row (of its stored order).
 __global__ __launch_bounds__(256) void dequant_generic_kernel(Params p, __half *W, long long ldw, int blocks_per_row) {
   const int o = blockIdx.x / blocks_per_row;
   const int slot = (blockIdx.x % blocks_per_row) * 256 + threadIdx.x;
@@ -18,7 +25,7 @@ __global__ __launch_bounds__(256) void dequant_generic_kernel(Params p, __half *
     i = min(i, (unsigned)p.k_out - 1u);
     const __half *e = p.cb_out + (long long)i * p.v_out;
     const int c0 = slot * p.v_out;
-    for (int j = 0; j < p.v_out; ++j) wrow[c0 + j] = restore(__half2float(e[j]), s, b);
+    for (int j = 0; j < p.v_out; ++j) store_col(p, wrow, c0 + j, restore(__half2float(e[j]), s, b));
   } else {
     const int pp = slot - p.Q;
     unsigned i = load_index(p.idx + (long long)o * p.stride, pp, p.bits);
@@ -36,7 +43,7 @@ __global__ __launch_bounds__(256) void dequant_generic_kernel(Params p, __half *
       if (c0 + j >= p.in_features) break;
       float d = __half2float(e[j]);
       if (er) d = __fadd_rn(d, __half2float(er[j]));
-      wrow[c0 + j] = restore(d, s, b);
+      store_col(p, wrow, c0 + j, restore(d, s, b));
     }
   }
 }
@@ -71,7 +78,7 @@ __global__ __launch_bounds__(256) void dequant_down_kernel(Params p, __half *W, 
     if (o >= p.out_features) break;
     float d = __half2float(e[j]);
     if (er) d = __fadd_rn(d, __half2float(er[j]));
-    W[(long long)o * ldw + c] = restore(d, p.scale ? __half2float(p.scale[o]) : 1.0f, p.bias ? __half2float(p.bias[o]) : 0.0f);
+    store_col(p, W + (long long)o * ldw, c, restore(d, p.scale ? __half2float(p.scale[o]) : 1.0f, p.bias ? __half2float(p.bias[o]) : 0.0f));
   }
 }
 
@@ -90,10 +97,20 @@ int launch_dequant_fast(const Params &p, __half *W, long long ldw, hipStream_t s
 int launch_dequant_down_fast(const Params &p, __half *W, long long ldw, hipStream_t s);
 
 int launch_dequant(const Params &p, __half *W, long long ldw, hipStream_t s) {
+  if (p.perm && switches().dequant != 'g') {
+    // Permuted column order: restore in stored order with whatever kernel takes the layer, then move every row's values to
+    // their columns, in place, through LDS.  (Rows too long for LDS: the generic kernels below, which scatter their stores.)
+    Params q = p;
+    q.perm = nullptr;
+    if ((long long)p.in_features * 2 <= 160 * 1024) {
+      const int rc = launch_dequant(q, W, ldw, s);
+      return rc == VQ_OK ? launch_place_cols(W, ldw, p.out_features, p.in_features, p.perm, s) : rc;
+    }
+  }
   if (p.orientation == 1) {
     const int bps_main = (p.P + 255) / 256, bps_out = p.Q ? (p.Q + 255) / 256 : 1;
     long long main_blocks = (long long)bps_main * p.S;
-    const int rc = launch_dequant_down_fast(p, W, ldw, s);          // the main columns, when a fast kernel takes them
+    const int rc = p.perm ? VQ_ERR_UNSUPPORTED : launch_dequant_down_fast(p, W, ldw, s);          // the main columns, when a fast kernel takes them
     if (rc == VQ_OK) {
       if (!p.Q) return VQ_OK;
       main_blocks = 0;                                               // the generic kernel below: outlier streams only
@@ -105,7 +122,7 @@ int launch_dequant(const Params &p, __half *W, long long ldw, hipStream_t s) {
     hipLaunchKernelGGL(dequant_down_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, W, ldw, bps_main, main_blocks, bps_out);
     return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
   }
-  const int rc = launch_dequant_fast(p, W, ldw, s);
+  const int rc = p.perm ? VQ_ERR_UNSUPPORTED : launch_dequant_fast(p, W, ldw, s);
   if (rc != VQ_ERR_UNSUPPORTED) return rc;
   const int slots = p.P + p.Q;
   const int blocks_per_row = (slots + 255) / 256;

@@ -106,7 +106,15 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(Params p, const __half *
       const int row = chunk >> 2, col = (chunk & 3) * 8;
       const int t = m0 + row, c = k0 + col;
       uint4 val = make_uint4(0, 0, 0, 0);
-      if (t < tokens) {
+      if (t < tokens && p.perm) {                       // permuted column order: stored column c + i meets X[t][perm[c + i]]
+        __half tmp[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int u = c + i < p.in_features ? p.perm[c + i] : -1;
+          tmp[i] = (unsigned)u < (unsigned)p.in_features ? X[(long long)t * ldx + u] : __float2half_rn(0.0f);
+        }
+        val = *reinterpret_cast<uint4 *>(tmp);
+      } else if (t < tokens) {
         const __half *src = X + (long long)t * ldx + c;
         if (c + 8 <= p.in_features) {
           val = *reinterpret_cast<const uint4 *>(src);
@@ -155,9 +163,14 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(Params p, const __half *
 size_t gemm_workspace_bytes(const Params &, int) { return 0; }
 
 // Bytes of the FP16 weight matrix [out][in] that the two-step route below writes; 0 when that route does not apply.
-size_t gemm_fast_workspace_bytes(const Params &p, int) {
-  if (p.in_features % 256 != 0) return 0;                    // the dense kernel walks the columns in groups of 8 x 32
-  return (size_t)p.out_features * (size_t)p.in_features * sizeof(__half);
+// For a layer with a permuted column order (Sec. 3.2.3) the activations, gathered into stored order, come first: tokens
+// rows of in_features rounded up to 8 halfs, the whole rounded up to 256 bytes; every kernel then works in stored order.
+static size_t permuted_x_bytes(const Params &p, int tokens) { return ((size_t)tokens * (size_t)((p.in_features + 7) & ~7) * sizeof(__half) + 255) / 256 * 256; }
+
+size_t gemm_fast_workspace_bytes(const Params &p, int tokens) {
+  const size_t head = p.perm ? permuted_x_bytes(p, tokens) : 0;
+  if (p.in_features % 256 != 0) return head;                 // the dense kernel walks the columns in groups of 8 x 32
+  return head + (size_t)p.out_features * (size_t)p.in_features * sizeof(__half);
 }
 
 bool gemm_fused_applicable(const Params &p);
@@ -175,6 +188,24 @@ int launch_gemm_fused(const Params &p, const __half *X, long long ldx, int token
 // Switch gemm=g forces 3, =f skips 1, =w takes 1 whenever a workspace is there (measurement and tests).
 int launch_gemm(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy,
                 void *workspace, size_t workspace_bytes, hipStream_t s) {
+  if (p.perm && tokens <= 65535 && workspace && workspace_bytes >= permuted_x_bytes(p, tokens) && (reinterpret_cast<uintptr_t>(workspace) & 15) == 0 &&
+      switches().gemm != 'g') {
+    // room for the gathered activations: from here on the layer is an unpermuted one (the rest of the workspace is its own)
+    Params q = p;
+    q.perm = nullptr;
+    __half *Xp = static_cast<__half *>(workspace);
+    const long long ldxp = (p.in_features + 7) & ~7;
+    const int rc = launch_gather_cols(X, ldx, tokens, p.in_features, p.perm, Xp, ldxp, s);
+    if (rc != VQ_OK) return rc;
+    const size_t head = permuted_x_bytes(p, tokens);
+    return launch_gemm(q, Xp, ldxp, tokens, Y, ldy, static_cast<unsigned char *>(workspace) + head, workspace_bytes - head, s);
+  }
+  if (p.perm) {                                            // no room: the generic tile kernel looks every activation up
+    const unsigned gx = (unsigned)((p.out_features + BN - 1) / BN), gy = (unsigned)((tokens + BM - 1) / BM);
+    if (gy > 65535u) return VQ_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(gemm_tile_kernel, dim3(gx, gy), dim3(256), 0, s, p, X, ldx, tokens, Y, ldy);
+    return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+  }
   const char forced = switches().gemm;
   const size_t fast = gemm_fast_workspace_bytes(p, tokens);
   // measured on the 8192 x 8192 v=8 layer: up to 512 tokens restoring on the fly is still ahead (167 vs 184 us), from

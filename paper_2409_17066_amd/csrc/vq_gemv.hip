@@ -5,6 +5,14 @@
 
 namespace vq {
 
+// The activation that stored column c meets (Sec. 3.2.3: the stored order of the columns may be a permutation of the
+// layer's); entries outside the row count as zero.
+__device__ __forceinline__ float x_at(const Params &p, const __half *xrow, int c) {
+  if (!p.perm) return __half2float(xrow[c]);
+  const int t = p.perm[c];
+  return (unsigned)t < (unsigned)p.in_features ? __half2float(xrow[t]) : 0.0f;
+}
+
 // Any layer: one wave per output row, lanes stride over the row's vectors, tables read through the
 // cache hierarchy.  Slow but complete; the specialised kernels below take the common shapes.
 __global__ __launch_bounds__(256) void gemv_generic_kernel(Params p, const __half *__restrict__ x, long long ldx, int batch,
@@ -41,7 +49,7 @@ __global__ __launch_bounds__(256) void gemv_generic_kernel(Params p, const __hal
       const float w = __half2float(restore(d, s, b));
 #pragma unroll
       for (int t = 0; t < 16; ++t)
-        if (t < batch) acc[t] = __fmaf_rn(w, __half2float(x[t * ldx + c0 + j]), acc[t]);
+        if (t < batch) acc[t] = __fmaf_rn(w, x_at(p, x + t * ldx, c0 + j), acc[t]);
     }
   }
 #pragma unroll
@@ -82,7 +90,7 @@ __global__ __launch_bounds__(256) void gemv_down_kernel(Params p, const __half *
         unsigned r = min(load_index(p.idx_res + (long long)stream * p.stride_res, pos, p.bits_res), (unsigned)p.k_res - 1u);
         er = p.cb_res + (group * p.k_res + r) * p.v;
       }
-      const float xv = __half2float(xt[p.n_out + pos]);
+      const float xv = x_at(p, xt, p.n_out + pos);
 #pragma unroll
       for (int j = 0; j < 16; ++j)
         if (j < p.v && o0 + j < p.out_features) {
@@ -98,7 +106,7 @@ __global__ __launch_bounds__(256) void gemv_down_kernel(Params p, const __half *
         for (int pos = lane; pos < p.Q; pos += 64) {
           unsigned i = min(load_index(p.idx_out + (long long)sq * p.stride_out, pos, p.bits_out), (unsigned)p.k_out - 1u);
           const float w = __half2float(restore(__half2float(p.cb_out[(long long)i * p.v_out + jo]), sc[j], bi[j]));
-          acc[j] = __fmaf_rn(w, __half2float(xt[pos]), acc[j]);
+          acc[j] = __fmaf_rn(w, x_at(p, xt, pos), acc[j]);
         }
         const float r = wave_sum(acc[j]);
         if (lane == 0) y[(long long)t * ldy + o] = __float2half_rn(r);
@@ -161,6 +169,28 @@ bool gemv_has_fast_kernel(const Params &p, const __half *x, long long ldx) {
 }
 
 int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
+  if (p.perm) {
+    // Permuted column order without a workspace: the dot-product kernel for v = 6 that stages the activations in LDS
+    // gathers them while it does so; everything else runs on the generic kernels, which look every activation up.
+    if (p.orientation == 0 && !force_generic()) {
+      if (gemv_fast_applicable(p, x, ldx) && p.n_groups == 1) {
+        int done = 0, rc = VQ_OK, g_max = 4;
+        while (done < batch) {
+          int g = batch - done >= 4 ? 4 : batch - done >= 2 ? 2 : 1;
+          if (g > g_max) g = g_max;
+          rc = launch_gemv_fast(p, x + done * ldx, ldx, g, y + done * ldy, ldy, s);
+          if (rc == VQ_ERR_UNSUPPORTED && g > 1) { g_max = g / 2; continue; }
+          if (rc != VQ_OK) break;
+          done += g;
+        }
+        if (rc == VQ_OK) return VQ_OK;
+        if (rc != VQ_ERR_UNSUPPORTED || done != 0) return rc;
+      }
+    }
+    if (p.orientation == 1) hipLaunchKernelGGL(gemv_down_kernel, dim3((unsigned)((p.S + 3) / 4)), dim3(256), 0, s, p, x, ldx, batch, y, ldy);
+    else hipLaunchKernelGGL(gemv_generic_kernel, dim3((unsigned)((p.out_features + 3) / 4)), dim3(256), 0, s, p, x, ldx, batch, y, ldy);
+    return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+  }
   // Matrix-core kernel: one launch for any batch, at about the cost of a batch-1 launch of the dot-product
   // kernels; those are still a little faster for one row (and for two rows of a layer with few output rows
   // per compute unit), so they keep these cases.  Layers with codebook groups always go to the matrix-core kernel:
@@ -260,8 +290,24 @@ int launch_gemv_mfma_groups(const Params &p, const __half *x, long long ldx, int
 
 // A workspace serves layers with codebook groups on the matrix-core kernel: one group per workgroup, then a sum over
 // the groups.  groups=loop keeps every workgroup walking all groups (measurement and tests).
+// Layers with a permuted column order: the activations, gathered into stored order, come first in the workspace
+// (batch rows of in_features rounded up to 8 halfs, the whole rounded up to 256 bytes); the rest is what the layer needs
+// without the permutation.
+static size_t permuted_x_bytes(const Params &p, int rows) { return ((size_t)rows * (size_t)((p.in_features + 7) & ~7) * sizeof(__half) + 255) / 256 * 256; }
+// One row of a layer that the gathering dot-product kernel takes is faster without the extra launch, as long as the row
+// is short: every workgroup gathers the whole row (64 lookups a wave instruction), a gather kernel does it once.
+static bool permuted_in_kernel(const Params &p, const __half *x, long long ldx, int batch) {
+  return batch == 1 && p.orientation == 0 && p.n_groups == 1 && forced_kernel() != 'm' && p.in_features < 16384 && gemv_fast_applicable(p, x, ldx);
+}
+
 size_t gemv_workspace_bytes(const Params &p, const __half *x, long long ldx, int batch) {
   if (force_generic()) return 0;
+  if (p.perm) {
+    if (permuted_in_kernel(p, x, ldx, batch)) return 0;
+    Params q = p;
+    q.perm = nullptr;
+    return permuted_x_bytes(p, batch) + gemv_workspace_bytes(q, nullptr, (p.in_features + 7) & ~7, batch);
+  }
   if (p.orientation == 1 && down_mfma_parts_wanted(p, x, ldx, batch)) {   // the matrix cores: the workspace lets parts of the columns run side by side
     const int parts = gemv_down_mfma_parts(p);            // the outlier columns are one more set of sums to add up
     return parts > 1 ? ((size_t)(parts + (p.Q ? 1 : 0)) * ((size_t)batch * (size_t)p.out_features + 16) * sizeof(float) + 255) / 256 * 256 : 0;
@@ -276,6 +322,18 @@ size_t gemv_workspace_bytes(const Params &p, const __half *x, long long ldx, int
 int launch_gemv_ws(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, void *workspace,
                    size_t workspace_bytes, hipStream_t s) {
   const size_t need = gemv_workspace_bytes(p, x, ldx, batch);
+  if (p.perm) {
+    if (!need || !workspace || workspace_bytes < need) return launch_gemv(p, x, ldx, batch, y, ldy, s);
+    // gather the activations into stored order, then the layer is an unpermuted one
+    Params q = p;
+    q.perm = nullptr;
+    __half *xp = static_cast<__half *>(workspace);
+    const long long ldxp = (p.in_features + 7) & ~7;
+    const int rc = launch_gather_cols(x, ldx, batch, p.in_features, p.perm, xp, ldxp, s);
+    if (rc != VQ_OK) return rc;
+    const size_t head = permuted_x_bytes(p, batch);
+    return launch_gemv_ws(q, xp, ldxp, batch, y, ldy, static_cast<unsigned char *>(workspace) + head, workspace_bytes - head, s);
+  }
   if (need && workspace && workspace_bytes >= need && p.orientation == 1 && down_mfma_parts_wanted(p, x, ldx, batch)) {
     const int parts = gemv_down_mfma_parts(p), slots = parts + (p.Q ? 1 : 0);
     float *part = static_cast<float *>(workspace), *part_xs = part + (size_t)slots * (size_t)batch * (size_t)p.out_features;
@@ -314,6 +372,7 @@ int launch_gemv_down_mfma_multi(const Params *ps, int n, const __half *x, long l
 int launch_gemv_multi(const Params *ps, int n, const __half *x, long long ldx, int batch, __half *const *ys, const long long *ldys,
                       hipStream_t s) {
   bool fused = n >= 2 && !switches().multi_off && forced_kernel() != 'g' && forced_kernel() != 'd';
+  for (int i = 0; i < n; ++i) fused = fused && !ps[i].perm;      // permuted column orders: one layer after the other
   // layers with vectors down the output dimension: the matrix-core kernel of that orientation, any batch (a block of 16
   // streams per workgroup over all columns; the blocks of all the layers together are what fills the chip)
   bool down = fused;

@@ -180,9 +180,21 @@ __device__ __forceinline__ void gemv_v6_body(const Params &p, const GemvPlan &pl
       for (int bb = 0; bb < B; ++bb) {
         if (bb >= b0 && bb < b0 + plan.x_regions) {
           const __amdgpu_buffer_rsrc_t rx = make_rsrc(x + bb * ldx, (unsigned)p.in_features * 2u);
+          if (p.perm) {
+            // permuted column order (Sec. 3.2.3): stored column c meets x[perm[c]]; a thread gathers two columns at a time
+            // (ordinary loads, which the compiler waits for before the LDS write; entries outside the row count as zero)
+            const __amdgpu_buffer_rsrc_t rp = make_rsrc(p.perm, (unsigned)p.in_features * 4u);
+            for (unsigned c = threadIdx.x * 2u; c < plan.x_bytes / 2u; c += NW * 128u) {
+              const uint2v t = __builtin_amdgcn_raw_buffer_load_b64(rp, c * 4u, 0, 0);
+              const unsigned lo = c < (unsigned)p.in_features && t.x < (unsigned)p.in_features ? (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rx, t.x * 2u, 0, 0) : 0u;
+              const unsigned hi = c + 1u < (unsigned)p.in_features && t.y < (unsigned)p.in_features ? (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rx, t.y * 2u, 0, 0) : 0u;
+              *reinterpret_cast<unsigned *>(lds + plan.lds_x + (bb - b0) * plan.x_bytes + c * 2u) = lo | (hi << 16);
+            }
+          } else {
           for (unsigned piece = (unsigned)wv * 1024u; piece < plan.x_bytes; piece += NW * 1024u)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void *)(lds + plan.lds_x + (bb - b0) * plan.x_bytes + piece),
                                                      16, piece + lane * 16u, 0, 0, 0);
+          }
         }
       }
       if (b0 == 0) {

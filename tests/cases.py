@@ -88,6 +88,19 @@ SMALL = {
     "down_fast_long_rows_res12": dict(out_features=66, in_features=16000, v=6, k=4096, k_res=4096, orientation=1),
     "down_fast_groups_many": dict(out_features=5000, in_features=4096, v=6, k=4096, group_vectors=600, orientation=1),
     "down_dense_gemm": dict(out_features=203, in_features=1024, v=6, k=4096, k_res=4096, n_outlier_cols=16, v_out=4, k_out=4096, orientation=1),
+    # stored column order a permutation of the layer's (the outlier columns scattered over the layer): the kernels that
+    # gather the activations themselves, the generic ones, both orientations, groups, the long-row kernel, both vq_gemm routes
+    "perm_v6_k4096": dict(out_features=261, in_features=1030, v=6, k=4096, permute=True),
+    "perm_v6_res12": dict(out_features=133, in_features=1000, v=6, k=4096, k_res=4096, permute=True),
+    "perm_v6_res8_outlier": dict(out_features=150, in_features=1208, v=6, k=4096, k_res=256, n_outlier_cols=24, v_out=4, k_out=4096, permute=True),
+    "perm_v6_res8_outlier_odd": dict(out_features=150, in_features=1207, v=6, k=4096, k_res=256, n_outlier_cols=24, v_out=4, k_out=4096, permute=True),
+    "perm_v6_long_res8_outlier": dict(out_features=300, in_features=16400, v=6, k=4096, k_res=256, n_outlier_cols=40, v_out=4, k_out=4096, permute=True),
+    "perm_v6_dense_gemm": dict(out_features=203, in_features=1024, v=6, k=4096, k_res=4096, n_outlier_cols=16, v_out=4, k_out=4096, permute=True),
+    "perm_grp_v6": dict(out_features=261, in_features=1030, v=6, k=4096, group_vectors=64, permute=True),
+    "perm_v8_fused_path": dict(out_features=200, in_features=768, v=8, k=65536, permute=True),
+    "perm_odd": dict(out_features=37, in_features=203, v=5, k=37, k_res=11, n_outlier_cols=9, v_out=3, k_out=5, permute=True),
+    "perm_down_fast_outlier": dict(out_features=150, in_features=1208, v=6, k=4096, k_res=256, n_outlier_cols=24, v_out=4, k_out=4096, orientation=1, permute=True),
+    "perm_down_v8": dict(out_features=200, in_features=520, v=8, k=65536, orientation=1, permute=True),
 }
 
 

@@ -134,3 +134,20 @@ def test_headline_shape_in_the_papers_orientation(gpu_lib, extra):
             y = gpu_lib.gemv(dl, torch.from_numpy(x).cuda(), workspace=workspace)
             torch.cuda.synchronize()
             _matmul_ok(y, ref, "headline shape, orientation 1, batch %d, %s, workspace %s" % (batch, extra, workspace))
+
+
+def test_config3_with_scattered_outlier_columns(gpu_lib):
+    """The 8192 x 28672 layer of the 70B setting with its columns stored in a permuted order, so that the 288 outlier
+    columns lie scattered over the layer (Sec. 3.2.3): restored matrix bit-exact, products with and without a workspace."""
+    import torch
+    c = s.CONFIGS[3]
+    L = s.make_layer(3, "down70b", 8192, 28672, c["v"], c["k"], c["k_res"], c["n_outlier_cols"], c["v_out"], c["k_out"], permute=True)
+    assert sorted(L.col_perm[:288]) != list(range(288))
+    dl = _dequant_exact(gpu_lib, L)
+    for batch in (1, 8):
+        x = s.make_activations(3, L, batch, outlier_gain=c["outlier_gain"])
+        ref = oracle.gemv(L, x)
+        for workspace in (None, "fast"):
+            y = gpu_lib.gemv(dl, torch.from_numpy(x).cuda(), workspace=workspace)
+            torch.cuda.synchronize()
+            _matmul_ok(y, ref, "cfg3 with permuted columns, batch %d, workspace %s" % (batch, workspace))

@@ -243,6 +243,111 @@ def test_gemv_groups_with_workspace(gpu_lib, monkeypatch, name, batch):
     _check_matmul(plain, oracle.gemv(L, x_np), "%s batch %d" % (name, batch))
 
 
+PERMUTED = [n for n in SMALL if n.startswith("perm_")]
+
+
+@pytest.mark.parametrize("name", PERMUTED)
+@pytest.mark.parametrize("batch", [1, 2, 5, 16])
+def test_gemv_permuted_columns_with_workspace(gpu_lib, name, batch):
+    """Sec. 3.2.3: stored column order a permutation of the layer's.  With a workspace the activations are gathered into it
+    first and the layer's usual kernels run; one row of a short-row v = 6 layer is gathered inside the kernel instead and
+    asks for no workspace.  Also through the library's own static workspace."""
+    import torch
+    L = small_layer(name)
+    dl = gpu_lib.DeviceLayer(L)
+    need = gpu_lib.vq_gemv_workspace_bytes(dl.desc, batch)
+    in_kernel = batch == 1 and L.v == 6 and L.orientation == 0 and not L.group_vectors and L.in_features % 2 == 0 and L.in_features < 16384
+    assert (need == 0) == in_kernel, (name, batch, need)
+    x_np = s.make_activations(300, L, batch)
+    x = torch.full((batch, L.in_features + 4), float("nan"), dtype=torch.float16, device="cuda")
+    x[:, : L.in_features] = torch.from_numpy(x_np).cuda()
+    ws = torch.full((need + 256,), 0xFF, dtype=torch.uint8, device="cuda")
+    y = gpu_lib.gemv(dl, x, workspace=ws[:need] if need else ws[:256])
+    torch.cuda.synchronize()
+    ref = oracle.gemv(L, x_np)
+    _check_matmul(y, ref, "%s batch %d with workspace" % (name, batch))
+    assert (ws[need:] == 0xFF).all()
+    y2 = torch.empty_like(y)
+    rc = gpu_lib.vq_gemv_static_workspace(dl.desc, x.data_ptr(), x.stride(0), batch, y2.data_ptr(), y2.stride(0), torch.cuda.current_stream().cuda_stream)
+    assert rc == 0
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)
+    plain = gpu_lib.gemv(dl, x)                               # no workspace: gathered in the kernel, or the generic kernels
+    torch.cuda.synchronize()
+    _check_matmul(plain, ref, "%s batch %d" % (name, batch))
+
+
+@pytest.mark.parametrize("name", PERMUTED)
+def test_dequant_permuted_columns_by_the_scattering_kernels(gpu_lib, monkeypatch, name):
+    """The generic kernels, which store every value at its column themselves (rows too long for LDS take them)."""
+    import torch
+    monkeypatch.setenv("VQ_SWITCHES", "dequant=g")
+    L = small_layer(name)
+    W = gpu_lib.dequant(gpu_lib.DeviceLayer(L), L.in_features + 5)
+    torch.cuda.synchronize()
+    assert np.array_equal(W.cpu().numpy().view(np.uint16), oracle.dequant(L, L.in_features + 5).view(np.uint16)), name
+
+
+def test_permuted_unit_activation_reads_back_the_layers_column(gpu_lib):
+    """x = e_t returns column t of the LAYER (not of the stored order), outlier columns included."""
+    import torch
+    L = small_layer("perm_v6_res8_outlier")
+    dl = gpu_lib.DeviceLayer(L)
+    W = oracle.dequant(L).astype(np.float64)
+    cols = [int(L.col_perm[0]), int(L.col_perm[23]), int(L.col_perm[24]), int(L.col_perm[1207]), 0, 1207]
+    for ws in (None, "fast"):
+        for t in cols:
+            x = np.zeros((2, L.in_features), dtype=np.float16)
+            x[0, t] = 1.0
+            x[1, t] = -2.0
+            y = gpu_lib.gemv(dl, torch.from_numpy(x).cuda(), workspace=ws).float().cpu().numpy()
+            assert np.allclose(y[0], W[:, t], rtol=2e-3, atol=1e-7) and np.allclose(y[1], -2.0 * W[:, t], rtol=2e-3, atol=1e-7)
+
+
+def test_permutation_entries_outside_the_row_are_ignored(gpu_lib):
+    """The library does not check that col_perm is a permutation: an entry outside [0, in_features) must neither be
+    read nor written through.  Such a stored column then contributes nothing, which is the same layer with a zero
+    activation there."""
+    import torch
+    L = small_layer("perm_v6_res8_outlier")
+    x_np = s.make_activations(300, L, 3)
+    bad = [5, 30, 700]                                  # stored columns whose entries go out of range
+    ref_x = x_np.copy()
+    ref_x[:, L.col_perm[bad]] = 0
+    ref = oracle.gemv(L, ref_x)
+    want_W = oracle.dequant(L)
+    M = small_layer("perm_v6_res8_outlier")
+    M.col_perm = L.col_perm.copy()
+    M.col_perm[bad] = [-1, L.in_features, 2 ** 31 - 1]
+    dl = gpu_lib.DeviceLayer(M)
+    x = torch.from_numpy(x_np).cuda()
+    for ws in (None, "fast"):
+        for batch in (1, 3):
+            y = gpu_lib.gemv(dl, x[:batch], workspace=ws)
+            torch.cuda.synchronize()
+            _check_matmul(y, ref[:batch], "out-of-range entries, batch %d, workspace %s" % (batch, ws))
+    W = torch.full((M.out_features, M.in_features + 8), -3.5, dtype=torch.float16, device="cuda")
+    assert gpu_lib.vq_dequant(dl.desc, W.data_ptr(), W.stride(0), torch.cuda.current_stream().cuda_stream) == 0
+    torch.cuda.synchronize()
+    got = W.cpu().numpy()
+    keep = np.setdiff1d(np.arange(M.in_features), L.col_perm[bad])
+    assert np.array_equal(got[:, keep].view(np.uint16), want_W[:, keep].view(np.uint16))
+    assert (got[:, M.in_features:] == np.float16(-3.5)).all()
+
+
+def test_gemv_multi_with_permuted_layers(gpu_lib):
+    """Layers with a column permutation of their own run one after the other: same results as single calls."""
+    import torch
+    a, b = small_layer("perm_v6_k4096"), small_layer("v6_k4096")
+    dls = [gpu_lib.DeviceLayer(a), gpu_lib.DeviceLayer(b)]
+    for batch in (1, 4):
+        x_np = s.make_activations(300, a, batch)
+        ys = gpu_lib.gemv_multi(dls, torch.from_numpy(x_np).cuda())
+        torch.cuda.synchronize()
+        for L, y in zip((a, b), ys):
+            _check_matmul(y, oracle.gemv(L, x_np), "multi with a permuted layer, batch %d" % batch)
+
+
 def test_gemv_workspace_is_not_asked_for_without_groups(gpu_lib):
     for name in ("v6_k4096", "v8_k65536", "grp_v6_unaligned", "grp_odd"):
         dl = gpu_lib.DeviceLayer(small_layer(name))
