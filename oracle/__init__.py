@@ -57,6 +57,9 @@ def lib():
         L.vq_oracle_assign_down.argtypes = L.vq_oracle_assign.argtypes
         L.vq_oracle_matmul.argtypes = [ctypes.POINTER(_Layer), ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32,
                                        ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int]
+        L.vq_oracle_quantize_columns.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32,
+                                                 ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                                 ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         _lib = L
     return _lib
 
@@ -170,6 +173,36 @@ def assign(W: np.ndarray, codebook: np.ndarray, base: np.ndarray | None = None, 
     if rc:
         raise OracleError("assign failed: %d" % rc)
     return out
+
+
+def quantize_columns(W, Hinv, codebook, codebook_res=None, block=128, given=None):
+    """Algorithm 1's column loop.  W: [M][N], Hinv: [N][N] (any float dtype, widened to fp64); codebooks fp16 [k][v].
+    given: (idx, idx_res or None) to replay somebody else's choices instead of taking the nearest centroids.
+    Returns dict(idx, idx_res, What, T): int32 [ceil(M/v)][N] indices, fp64 [M][N] quantized weights and the columns as
+    they stood when they were quantized."""
+    W = np.ascontiguousarray(W, dtype=np.float64)
+    Hinv = np.ascontiguousarray(Hinv, dtype=np.float64)
+    M, N = W.shape
+    assert Hinv.shape == (N, N)
+    codebook = _c(codebook, np.float16)
+    codebook_res = _c(codebook_res, np.float16)
+    k, v = codebook.shape
+    k_res = 0 if codebook_res is None else codebook_res.shape[0]
+    S = -(-M // v)
+    g_idx = g_res = None
+    if given is not None:
+        g_idx = np.ascontiguousarray(given[0], dtype=np.int32)
+        g_res = None if given[1] is None else np.ascontiguousarray(given[1], dtype=np.int32)
+        assert g_idx.shape == (S, N) and (g_res is None) == (k_res == 0)
+    idx = np.zeros((S, N), dtype=np.int32)
+    idx_res = np.zeros((S, N), dtype=np.int32) if k_res else None
+    What = np.zeros((M, N), dtype=np.float64)
+    T = np.zeros((M, N), dtype=np.float64)
+    rc = lib().vq_oracle_quantize_columns(_ptr(W), _ptr(Hinv), M, N, _ptr(codebook), v, k, _ptr(codebook_res), k_res, int(block),
+                                          _ptr(g_idx), _ptr(g_res), _ptr(idx), _ptr(idx_res), _ptr(What), _ptr(T))
+    if rc:
+        raise OracleError("quantize_columns failed: %d" % rc)
+    return dict(idx=idx, idx_res=idx_res, What=What, T=T)
 
 
 # decode GEMV and prefill GEMM are the same definition at different token counts

@@ -276,3 +276,67 @@ extern "C" int vq_oracle_assign_down(const uint16_t *W, const uint16_t *B, int64
     return (int)VQO_OK;
   });
 }
+
+// Algorithm 1 (Sec. 3.1): the quantizer's column loop, in the algorithm's order and notation.  See the header.
+extern "C" int vq_oracle_quantize_columns(const double *W0, const double *Hinv, int32_t M, int32_t N, const uint16_t *codebook, int32_t v,
+                                          int32_t k, const uint16_t *codebook_res, int32_t k_res, int32_t B, const int32_t *given_idx,
+                                          const int32_t *given_idx_res, int32_t *idx, int32_t *idx_res, double *What, double *T) {
+  if (!W0 || !Hinv || !codebook || !idx || !What || M < 1 || N < 1 || v < 1 || k < 1 || B < 1) return VQO_ERR_ARG;
+  if (k_res && (!codebook_res || !idx_res)) return VQO_ERR_ARG;
+  std::vector<double> W(W0, W0 + (size_t)M * N);           // the working copy that takes the error updates
+  std::vector<double> E((size_t)M * N, 0.0);
+  std::vector<double> C((size_t)k * v), R((size_t)k_res * v);
+  for (size_t e = 0; e < C.size(); ++e) C[e] = (double)vq_oracle_half_to_float(codebook[e]);
+  for (size_t e = 0; e < R.size(); ++e) R[e] = (double)vq_oracle_half_to_float(codebook_res[e]);
+  // index of the nearest of `count` centroids to t[0 .. len)
+  auto nearest = [&](const std::vector<double> &table, int32_t count, const double *t, int len) {
+    int32_t best = 0;
+    double best_d = 0.0;
+    for (int32_t i = 0; i < count; ++i) {
+      double d = 0.0;
+      for (int j = 0; j < len; ++j) d += (t[j] - table[(size_t)i * v + j]) * (t[j] - table[(size_t)i * v + j]);
+      if (i == 0 || d < best_d) { best = i; best_d = d; }
+    }
+    return best;
+  };
+  std::vector<double> t(v), r(v);
+  for (int32_t s = 0; s < N; s += B) {                     // column blocks
+    const int32_t s_end = std::min(N, s + B);
+    for (int32_t n = s; n < s_end; ++n) {                  // one column at a time
+      for (int32_t m = 0, p = 0; m < M; m += v, ++p) {     // the column's vectors
+        const int len = std::min(v, M - m);
+        for (int j = 0; j < len; ++j) t[j] = W[(size_t)(m + j) * N + n];
+        const int32_t i = given_idx ? given_idx[(size_t)p * N + n] : nearest(C, k, t.data(), len);
+        if (i < 0 || i >= k) return VQO_ERR_INDEX_RANGE;
+        idx[(size_t)p * N + n] = i;
+        int32_t ir = 0;
+        if (k_res) {
+          for (int j = 0; j < len; ++j) r[j] = t[j] - C[(size_t)i * v + j];
+          ir = given_idx_res ? given_idx_res[(size_t)p * N + n] : nearest(R, k_res, r.data(), len);
+          if (ir < 0 || ir >= k_res) return VQO_ERR_INDEX_RANGE;
+          idx_res[(size_t)p * N + n] = ir;
+        }
+        for (int j = 0; j < len; ++j) {
+          double q = C[(size_t)i * v + j];
+          if (k_res) {
+            volatile float sum = (float)q + (float)R[(size_t)ir * v + j];       // what inference restores: binary32 sum, then binary16
+            q = (double)vq_oracle_half_to_float(vq_oracle_float_to_half(sum));
+          }
+          What[(size_t)(m + j) * N + n] = q;
+        }
+      }
+      for (int32_t o = 0; o < M; ++o) {
+        if (T) T[(size_t)o * N + n] = W[(size_t)o * N + n];
+        E[(size_t)o * N + n] = (W[(size_t)o * N + n] - What[(size_t)o * N + n]) / Hinv[(size_t)n * N + n];
+        for (int32_t c = n; c < s_end; ++c) W[(size_t)o * N + c] -= E[(size_t)o * N + n] * Hinv[(size_t)n * N + c];
+      }
+    }
+    for (int32_t o = 0; o < M; ++o)                        // all the remaining columns
+      for (int32_t c = s_end; c < N; ++c) {
+        double acc = 0.0;
+        for (int32_t n = s; n < s_end; ++n) acc += E[(size_t)o * N + n] * Hinv[(size_t)n * N + c];
+        W[(size_t)o * N + c] -= acc;
+      }
+  }
+  return VQO_OK;
+}

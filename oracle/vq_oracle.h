@@ -20,7 +20,10 @@
  * All pointers are HOST pointers.  Parity status: every function here is
  * pinned by tests that do not depend on the oracle itself (hand-written byte
  * streams, one-hot lookups, W*e_j = column j, an independent triple-loop
- * matmul on unpacked indices, the compiler's own FP16 conversions).
+ * matmul on unpacked indices, the compiler's own FP16 conversions; for the
+ * quantizer's column loop: a test-local restatement without blocks, the
+ * identity Hinv, independence of the block size, and the second-order loss
+ * identity of the Cholesky factor).
  */
 #ifndef VQ_ORACLE_H
 #define VQ_ORACLE_H
@@ -102,6 +105,27 @@ int vq_oracle_assign(const uint16_t *W, const uint16_t *B, int64_t ld, int32_t r
  * elements; out[p * cols + n], p < ceil(rows / v).  Same arithmetic, j ascending.                                  */
 int vq_oracle_assign_down(const uint16_t *W, const uint16_t *B, int64_t ld, int32_t rows, int32_t cols,
                           const uint16_t *codebook, int32_t v, int32_t k, int32_t *out, int n_threads);
+
+/* The column loop of the quantizer (Algorithm 1, Sec. 3.1 "VPTQ Algorithm"; the error update is the Delta W equation of
+ * that section): columns are quantized one at a time, every column as a stack of length-v vectors that each take their
+ * nearest centroid (Eq. 2; with a residual codebook, a second nearest centroid for what the first leaves, Sec. 3.2.2), the
+ * column's error divided by the diagonal entry of the matrix the algorithm calls H^-1 is spread over the columns of its
+ * block of B columns that are still to come, and at the end of a block over all later columns:
+ *     for s = 0, B, 2B, ...:   for n = s .. min(s + B, N) - 1:
+ *         What[:, n] = Q(W[:, n]);   E[:, n] = (W[:, n] - What[:, n]) / Hinv[n][n];
+ *         W[:, n : s + B] -= E[:, n] * Hinv[n][n : s + B]
+ *       W[:, s + B :] -= E[:, s : s + B] * Hinv[s : s + B][s + B :]
+ * Hinv is an input: the algorithm only reads rows of it (callers in the GPTQ tradition pass the upper Cholesky factor of
+ * the inverse Hessian, for which the sum of squared E is the second-order loss).  Everything is fp64: the paper fixes no
+ * precision.  The distance is sum_j (t_j - C[i][j])^2, j ascending, the smallest i among the smallest distances; the last
+ * vector of a column is cut at M and compared over its own elements.  What is what inference restores: the centroid, or
+ * with a residual codebook the binary32 sum of the two centroids rounded to binary16.
+ * W: [M][N] (not modified); Hinv: [N][N]; idx, idx_res (NULL without residual): int32 [ceil(M / v)][N]; What, T: [M][N],
+ * T[:, n] = column n as it stood when it was quantized (NULL: not wanted).  With given_idx (and given_idx_res) those
+ * choices are taken instead of the nearest centroids: the propagation that follows from somebody else's choices.      */
+int vq_oracle_quantize_columns(const double *W, const double *Hinv, int32_t M, int32_t N, const uint16_t *codebook, int32_t v, int32_t k,
+                               const uint16_t *codebook_res, int32_t k_res, int32_t B, const int32_t *given_idx,
+                               const int32_t *given_idx_res, int32_t *idx, int32_t *idx_res, double *What, double *T);
 
 #ifdef __cplusplus
 }

@@ -160,3 +160,24 @@ def config_layers(config: int, only: str | None = None):
         yield ordinal, make_layer(config, name, out_f, in_f, c["v"], c["k"], c.get("k_res", 0),
                                   c.get("n_outlier_cols", 0), c.get("v_out", 0), c.get("k_out", 0),
                                   layer_ordinal=ordinal)
+
+
+def make_hessian(config: int, n: int, samples: int = 0, damp: float = 0.01, mix: float = 0.6) -> np.ndarray:
+    """A synthetic layer Hessian, fp64 [n][n], symmetric positive definite: X^T X / samples of `samples` seeded Gaussian
+    activation rows (default 2 n) whose neighbouring channels are correlated (channel c = mix * channel c-1 + noise, with a
+    per-channel gain that makes a few channels much larger than the rest, as calibration activations are), plus `damp`
+    times the mean diagonal on the diagonal (the usual damping)."""
+    samples = samples or 2 * n
+    z = g.normal(g.tensor_seed(config, g.T_HESSIAN), samples * n, 1.0).reshape(samples, n)
+    for c in range(1, n):
+        z[:, c] += mix * z[:, c - 1]
+    gain = 1.0 + 9.0 * (g.uniform01(g.tensor_seed(config, g.T_HESSIAN, 1), n) > 0.97)
+    z *= gain
+    H = z.T @ z / samples
+    H += damp * np.mean(np.diag(H)) * np.eye(n)
+    return H
+
+
+def make_weights(config: int, rows: int, cols: int, sigma: float = SIGMA_MAIN) -> np.ndarray:
+    """Seeded Gaussian weights, fp64 [rows][cols] (values of fp16 numbers)."""
+    return g.to_fp16(g.normal(g.tensor_seed(config, g.T_WEIGHT), rows * cols, sigma)).astype(np.float64).reshape(rows, cols)

@@ -14,7 +14,7 @@ _BASE_SEED = 0x5650545100
 # tensor ids inside one layer
 T_CODEBOOK, T_CODEBOOK_RES, T_CODEBOOK_OUT = 0, 1, 2
 T_IDX, T_IDX_RES, T_IDX_OUT = 3, 4, 5
-T_SCALE, T_BIAS, T_ACT, T_PERM = 6, 7, 8, 9
+T_SCALE, T_BIAS, T_ACT, T_PERM, T_HESSIAN, T_WEIGHT = 6, 7, 8, 9, 10, 11
 
 
 def tensor_seed(config: int, tensor_id: int, layer_ordinal: int = 0, batch_or_tokens: int = 0) -> int:
