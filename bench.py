@@ -399,6 +399,31 @@ def detail(vq, s, np, torch, use_graph, skip):
                 "TFLOP/s": round(flops / sec / 1e12, 1), "bound": "alu",
                 "frac_fp32_vector_peak": round(flops / sec / 1e12 / FP32_VECTOR_PEAK_TFLOPS, 4)})
     del Wenc, Cenc, idx_enc
+    # the quantizer's column loop (Algorithm 1) on a 4096 x 4096 matrix (the 7B attention projections), v=6, k=4096, blocks
+    # of 128 columns, a synthetic Hessian's Cholesky factor in the role of H^-1: the search is the same arithmetic as
+    # vq_assign, one column after the other; the end-of-block updates are binary32 matrix products on the matrix cores
+    nq = 4096
+    Uq = torch.from_numpy(np.ascontiguousarray(np.linalg.cholesky(np.linalg.inv(s.make_hessian(2, nq))).T, dtype=np.float32)).cuda()
+    W0q = torch.from_numpy(s.make_weights(2, nq, nq).astype(np.float32)).cuda()
+    Cq = torch.from_numpy(next(s.config_layers(1))[1].codebook).cuda()
+    Wq = W0q.clone()
+    vq.quantize_columns(Wq, Uq, Cq, None, block=128, want_T=False)
+    torch.cuda.synchronize()
+    best_q = None
+    for _ in range(2):
+        Wq.copy_(W0q)
+        t0 = torch.cuda.Event(enable_timing=True); t1 = torch.cuda.Event(enable_timing=True)
+        t0.record()
+        vq.quantize_columns(Wq, Uq, Cq, None, block=128, want_T=False)
+        t1.record(); torch.cuda.synchronize()
+        ms = t0.elapsed_time(t1)
+        best_q = ms if best_q is None else min(best_q, ms)
+    pairs = float(-(-nq // 6)) * nq * 4096
+    flops = pairs * (3 * 6 + 1) + float(nq) * nq * nq              # the searches, and the updates: M N^2 / 2 multiply-adds
+    out.append({"op": "vq_quantize_columns", "shape": "4096x4096 v6 k4096, blocks of 128 columns", "ms": round(best_q, 2),
+                "TFLOP/s": round(flops / best_q / 1e9, 1), "bound": "alu",
+                "frac_fp32_vector_peak": round(flops / best_q / 1e9 / FP32_VECTOR_PEAK_TFLOPS, 4)})
+    del Uq, W0q, Wq, Cq
     # the headline shape stored in the paper's own orientation (vectors down the output dimension)
     Ld = s.make_layer(1, "up", L1.out_features, L1.in_features, 6, 4096, orientation=1)
     for batch in (1, 4, 16):

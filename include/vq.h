@@ -200,6 +200,36 @@ int vq_assign(const void *W, const void *B, int64_t ld, int32_t rows, int32_t co
 int vq_assign_down(const void *W, const void *B, int64_t ld, int32_t rows, int32_t cols, const void *codebook, int32_t v,
                    int32_t k, void *idx, int64_t idx_row_stride, void *hip_stream);
 
+/* The column loop of the quantizer (Algorithm 1, Sec. 3.1 "VPTQ Algorithm"; its error update is the Delta W equation of
+ * that section): the columns of W are quantized one at a time, every column as a stack of length-v vectors (orientation 1
+ * of the descriptor) that each take their nearest centroid (Eq. 2) and, with a residual codebook, a second nearest centroid
+ * for what the first leaves (Sec. 3.2.2); then
+ *     E[:, n] = (W[:, n] - What[:, n]) / Hinv[n][n],   W[:, n+1 : s+B] -= E[:, n] * Hinv[n][n+1 : s+B]
+ * inside the block [s, s+B) of `block` columns that holds n, and W[:, s+B :] -= E[:, s : s+B] * Hinv[s : s+B][s+B :] at the
+ * end of every block.  Hinv is the matrix the algorithm calls H^-1, an input: binary32 [cols][ldh], only entries on and
+ * above the diagonal are read (callers in the GPTQ tradition pass the upper Cholesky factor of the inverse Hessian);
+ * its diagonal must not hold zeros.
+ * W: binary32 [rows][ldw], in: the weights, out: the quantized weights What -- the centroid, or with a residual codebook
+ * the binary32 sum of the two centroids rounded to binary16, i.e. what vq_dequant restores from the indices with scale 1
+ * and bias 0.  idx / idx_res: the packed index streams of orientation 1, [ceil(rows / v)][stride] bytes, one index per
+ * column, written as vq_assign_down writes them (same stride and alignment rules; idx_res and codebook_res NULL and
+ * k_res 0 without a residual codebook).  T, optional (NULL): binary32 [rows][ldt], column n as it stood when it was
+ * quantized.  block in [1, 128].  workspace: vq_quantize_columns_workspace_bytes(rows, v, k, k_res) bytes of device
+ * memory, 256-byte aligned, contents undefined afterwards, else VQ_ERR_WORKSPACE.
+ * Arithmetic: binary32 throughout.  The distance is the one of vq_assign (one subtraction and one fused multiply-add per
+ * element into a sum that starts at +0, elements ascending; the smallest index among the smallest distances; a cut-off
+ * last vector is compared over its own elements); the residual vector is one subtraction per element; E is one
+ * subtraction and one division; the update inside a block is one fused multiply-add per element and column; the update at
+ * the end of a block is a binary32 matrix product on the matrix cores, summed in the hardware's order, then one
+ * subtraction.  Several summation orders are legitimate, so results are deterministic run to run but need not equal
+ * another implementation's index for index: what holds is that every index is a nearest centroid of the column as this
+ * call propagated it (T), and that T follows from the call's own earlier choices by the recurrence above.            */
+size_t vq_quantize_columns_workspace_bytes(int32_t rows, int32_t v, int32_t k, int32_t k_res);
+int vq_quantize_columns(void *W, int64_t ldw, int32_t rows, int32_t cols, const void *Hinv, int64_t ldh, const void *codebook,
+                        int32_t v, int32_t k, const void *codebook_res, int32_t k_res, int32_t block, void *idx,
+                        int64_t idx_row_stride, void *idx_res, int64_t idx_res_row_stride, void *T, int64_t ldt, void *workspace,
+                        size_t workspace_bytes, void *hip_stream);
+
 /* Prompt-phase product for many tokens: Y[t][o] = sum_c W[o][c] * X[t][c] on the FP16 matrix cores,
  * binary32 accumulation, fp16 result (the paper's prompt phase, its section on inference throughput:
  * restore the weights, then multiply).  X: fp16 [tokens][ldx], 16-byte aligned, ldx % 8 == 0; Y: fp16

@@ -70,6 +70,13 @@ def load():
     L.vq_gemm_workspace_bytes.restype = ctypes.c_size_t
     L.vq_gemm_fast_workspace_bytes.argtypes = [P, ctypes.c_int32]
     L.vq_gemm_fast_workspace_bytes.restype = ctypes.c_size_t
+    L.vq_quantize_columns_workspace_bytes.argtypes = [ctypes.c_int32] * 4
+    L.vq_quantize_columns_workspace_bytes.restype = ctypes.c_size_t
+    L.vq_quantize_columns.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
+                                      ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                                      ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
+                                      ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    L.vq_quantize_columns.restype = ctypes.c_int
     L.vq_status_string.argtypes = [ctypes.c_int]
     L.vq_status_string.restype = ctypes.c_char_p
     L.vq_version.restype = ctypes.c_int
@@ -80,7 +87,7 @@ def load():
 
 
 EXPORTED = ["vq_validate", "vq_dequant", "vq_gemv", "vq_gemv_workspace_bytes", "vq_gemv_with_workspace", "vq_gemv_static_workspace", "vq_gemv_multi", "vq_gemm", "vq_gemm_workspace_bytes", "vq_gemm_fast_workspace_bytes",
-            "vq_assign", "vq_assign_down", "vq_status_string", "vq_version"]
+            "vq_assign", "vq_assign_down", "vq_quantize_columns", "vq_quantize_columns_workspace_bytes", "vq_status_string", "vq_version"]
 
 
 # ---- the C entry points, same names, raw pointers (ints) and sizes ---------------------------------------
@@ -133,6 +140,16 @@ def vq_assign(W_ptr, B_ptr, ld, rows, cols, codebook_ptr, v, k, idx_ptr, idx_row
 
 def vq_assign_down(W_ptr, B_ptr, ld, rows, cols, codebook_ptr, v, k, idx_ptr, idx_row_stride, stream=None):
     return load().vq_assign_down(W_ptr, B_ptr, ld, rows, cols, codebook_ptr, v, k, idx_ptr, idx_row_stride, stream)
+
+
+def vq_quantize_columns_workspace_bytes(rows, v, k, k_res):
+    return load().vq_quantize_columns_workspace_bytes(rows, v, k, k_res)
+
+
+def vq_quantize_columns(W_ptr, ldw, rows, cols, Hinv_ptr, ldh, codebook_ptr, v, k, codebook_res_ptr, k_res, block, idx_ptr, idx_row_stride,
+                        idx_res_ptr, idx_res_row_stride, T_ptr, ldt, workspace_ptr, workspace_bytes, stream=None):
+    return load().vq_quantize_columns(W_ptr, ldw, rows, cols, Hinv_ptr, ldh, codebook_ptr, v, k, codebook_res_ptr, k_res, block, idx_ptr,
+                                      idx_row_stride, idx_res_ptr, idx_res_row_stride, T_ptr, ldt, workspace_ptr, workspace_bytes, stream)
 
 
 def vq_gemm_workspace_bytes(desc, tokens):
@@ -249,6 +266,40 @@ def assign(W, codebook, base=None, cols=None, orientation=0):
     if rc != VQ_OK:
         raise VQError(rc, "vq_assign_down" if orientation else "vq_assign")
     return idx
+
+
+def quantize_columns(W, Hinv, codebook, codebook_res=None, block=128, want_T=True):
+    """Algorithm 1's column loop.  W: fp32 [rows][cols] device tensor (overwritten with the quantized weights), Hinv: fp32
+    [cols][cols], codebooks fp16 [k][v] device tensors -> (idx, idx_res or None, T or None): packed uint8 streams
+    [ceil(rows / v)][stride] of orientation 1 and the fp32 columns as they stood when they were quantized."""
+    import torch
+    assert W.is_cuda and W.dtype == torch.float32 and W.dim() == 2 and W.stride(1) == 1
+    assert Hinv.dtype == torch.float32 and Hinv.shape == (W.shape[1], W.shape[1]) and Hinv.stride(1) == 1
+    codebook = codebook.contiguous()
+    k, v = codebook.shape
+    k_res = 0
+    if codebook_res is not None:
+        codebook_res = codebook_res.contiguous()
+        k_res = codebook_res.shape[0]
+    rows, cols = W.shape
+    streams = -(-rows // v)
+
+    def stream_buffer(kk):
+        bits = max(1, (kk - 1).bit_length())
+        stride = (cols * bits + 127) // 128 * 16
+        return torch.full((streams, stride), 0xEE, dtype=torch.uint8, device="cuda"), stride
+    idx, stride = stream_buffer(k)
+    idx_res, stride_res = stream_buffer(k_res) if k_res else (None, 0)
+    T = torch.empty_like(W) if want_T else None
+    need = vq_quantize_columns_workspace_bytes(rows, v, k, k_res)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    rc = vq_quantize_columns(W.data_ptr(), W.stride(0), rows, cols, Hinv.data_ptr(), Hinv.stride(0), codebook.data_ptr(), v, k,
+                             codebook_res.data_ptr() if k_res else None, k_res, block, idx.data_ptr(), stride,
+                             idx_res.data_ptr() if k_res else None, stride_res, T.data_ptr() if want_T else None,
+                             T.stride(0) if want_T else 0, ws.data_ptr(), need, _stream())
+    if rc != VQ_OK:
+        raise VQError(rc, "vq_quantize_columns")
+    return idx, idx_res, T
 
 
 def gemm(dl: DeviceLayer, X, out=None, workspace=None):

@@ -294,6 +294,34 @@ extern "C" int vq_assign_down(const void *W, const void *B, int64_t ld, int32_t 
                                 static_cast<hipStream_t>(hip_stream));
 }
 
+extern "C" size_t vq_quantize_columns_workspace_bytes(int32_t rows, int32_t v, int32_t k, int32_t k_res) {
+  if (rows < 1 || rows > (1 << 24) || v < 1 || v > 16 || k < 2 || k > 65536 || (k_res != 0 && (k_res < 2 || k_res > 65536))) return 0;
+  return vq::quantize_columns_workspace_bytes(rows, v, k, k_res);
+}
+
+extern "C" int vq_quantize_columns(void *W, int64_t ldw, int32_t rows, int32_t cols, const void *Hinv, int64_t ldh, const void *codebook,
+                                   int32_t v, int32_t k, const void *codebook_res, int32_t k_res, int32_t block, void *idx,
+                                   int64_t idx_row_stride, void *idx_res, int64_t idx_res_row_stride, void *T, int64_t ldt, void *workspace,
+                                   size_t workspace_bytes, void *hip_stream) {
+  if (!W || !Hinv || !codebook || !idx) return VQ_ERR_NULL;
+  const int lim = 1 << 24;
+  if (rows < 1 || rows > lim || cols < 1 || cols > lim || ldw < cols || ldh < cols || v < 1 || v > 16 || k < 2 || k > 65536) return VQ_ERR_SHAPE;
+  if (k_res != 0 && (k_res < 2 || k_res > 65536)) return VQ_ERR_SHAPE;
+  if (k_res && (!codebook_res || !idx_res)) return VQ_ERR_NULL;
+  if (block < 1 || block > 128 || (T && ldt < cols)) return VQ_ERR_SHAPE;
+  if (idx_row_stride < (((long long)cols * vq::index_bits(k) + 31) / 32) * 4) return VQ_ERR_SHAPE;
+  if (k_res && idx_res_row_stride < (((long long)cols * vq::index_bits(k_res) + 31) / 32) * 4) return VQ_ERR_SHAPE;
+  if (!aligned(W, 4) || !aligned(Hinv, 4) || (T && !aligned(T, 4)) || !aligned(codebook, 2) || (k_res && !aligned(codebook_res, 2))) return VQ_ERR_ALIGNMENT;
+  if (!aligned(idx, 16) || idx_row_stride % 16 != 0 || (k_res && (!aligned(idx_res, 16) || idx_res_row_stride % 16 != 0))) return VQ_ERR_ALIGNMENT;
+  const size_t need = vq::quantize_columns_workspace_bytes(rows, v, k, k_res);
+  if (!workspace || workspace_bytes < need) return VQ_ERR_WORKSPACE;
+  if (!aligned(workspace, 256)) return VQ_ERR_ALIGNMENT;
+  return vq::launch_quantize_columns(static_cast<float *>(W), ldw, rows, cols, static_cast<const float *>(Hinv), ldh,
+                                     static_cast<const __half *>(codebook), v, k, static_cast<const __half *>(codebook_res), k_res, block,
+                                     static_cast<unsigned char *>(idx), idx_row_stride, static_cast<unsigned char *>(idx_res),
+                                     idx_res_row_stride, static_cast<float *>(T), ldt, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
 extern "C" const char *vq_status_string(int status) {
   switch (status) {
     case VQ_OK: return "ok";

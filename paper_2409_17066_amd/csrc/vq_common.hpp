@@ -78,6 +78,10 @@ int launch_assign_down(const __half *W, const __half *B, long long ld, int rows,
 // through LDS, in place (VQ_ERR_UNSUPPORTED when a row does not fit LDS).
 int launch_gather_cols(const __half *src, long long ld_src, int rows, int cols, const int *perm, __half *dst, long long ld_dst, hipStream_t s);
 int launch_place_cols(__half *W, long long ldw, int rows, int cols, const int *perm, hipStream_t s);
+size_t quantize_columns_workspace_bytes(int rows, int v, int k, int k_res);
+int launch_quantize_columns(float *W, long long ldw, int rows, int cols, const float *Hinv, long long ldh, const __half *cb, int v, int k,
+                            const __half *cb_res, int k_res, int block, unsigned char *idx, long long idx_stride, unsigned char *idx_res,
+                            long long idx_res_stride, float *T, long long ldt, void *workspace, hipStream_t st);
 size_t gemm_workspace_bytes(const Params &p, int tokens);
 size_t gemm_fast_workspace_bytes(const Params &p, int tokens);
 
