@@ -272,6 +272,21 @@ def detail(vq, s, np, torch, use_graph, skip):
             line["roofline"] = {"bound": "hbm", "achieved": round(alg / sec / 1e9, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                                 "frac": round(alg / sec / 1e9 / HBM_PEAK_GBPS, 4), "traffic": measured_traffic_bytes(cfg),
                                 "kernel_us": round(sec * 1e6, 3), "algorithmic_bytes": alg}
+        if batch > 1:
+            # the same call with the matrix cores switched off (VQ_SWITCHES gemv=d: the dot-product kernels on the vector ALUs,
+            # batch rows in groups of 4, 2 or 1), and against the larger of the HBM time and the vector-ALU time of its
+            # multiply-adds at the published fp32 vector peak
+            os.environ["VQ_SWITCHES"] = "gemv=d"
+            try:
+                rv = bench_gemv(vq, layer, x_np, steps, warmup, use_graph)
+            finally:
+                del os.environ["VQ_SWITCHES"]
+            sec_v = rv["event_s"] / steps
+            floor = max(alg / (HBM_PEAK_GBPS * 1e9), flops / (FP32_VECTOR_PEAK_TFLOPS * 1e12))
+            line["kernel"] = "matrix cores (default)"
+            line["us_vector_alu_kernels"] = round(sec_v * 1e6, 3)
+            line["frac_of_max_hbm_valu_time"] = round(floor / sec, 4)
+            line["frac_of_max_hbm_valu_time_vector_alu_kernels"] = round(floor / sec_v, 4)
         out.append(line)
 
     for cfg in (1, 2, 3):

@@ -2,12 +2,21 @@
 
 Such a load (buffer_load / global_load / ds_read inside an asm statement) leaves its destination registers
 pending until a later s_waitcnt; the compiler does not know that and is free to copy, spill or reuse them in
-between (it has done all three, typically right after the load or at the end of its basic block).  This script
-reads the device assembly of a source file and checks every basic block on its own: registers written by an
-inline-assembly load are pending until an s_waitcnt in the same block retires them (vector-memory loads and LDS
-reads each retire in issue order, so `vmcnt(N)` / `lgkmcnt(N)` keeps the youngest N), and any other instruction of
-the block that names a pending register is reported.  Nothing is carried across block boundaries, so this is a
-net for the mistakes seen in practice, not a proof; the build fails on a finding.
+between (it has done all three, typically right after the load, at the end of its basic block, or at a loop's
+back-edge).  This script reads the device assembly of a source file and follows, per kernel, the queue of
+outstanding loads through the control-flow graph: registers written by an inline-assembly load are pending until an
+s_waitcnt retires them (vector-memory loads and LDS reads each retire in issue order, so `vmcnt(N)` / `lgkmcnt(N)`
+keeps the youngest N; the compiler's own loads take their place in the queue with no registers attached), and any
+other instruction that names a pending register is reported.  A block starts from the merge of what its predecessors
+leave behind -- queues aligned at their youngest entry, register sets united position by position, which can only
+add pending registers -- iterated over the graph to a fixed point (queues are cut at the 64 loads the hardware's
+counters can tell apart).  Sound for the mistakes this guards against under two assumptions it cannot check: loads
+retire in issue order, and branch targets are the labels of the same function.  It is not complete: it follows every
+path through the graph, also those that no run takes because two branches test the same loop-invariant value (a wave
+either has vectors in a codebook group or has none, in every copy of an unrolled loop body), and on such a path a
+counted wait meets fewer loads than it counts on.  The build therefore fails on any finding in the files whose graphs
+come out clean, and for the two files with such paths (build.py names them) on any finding inside a single basic block,
+printing the number of cross-block findings for the reader to compare with the number recorded there.
 """
 import re
 import subprocess
@@ -101,25 +110,71 @@ def step(state, text, in_asm, report):
         if g:
             lds = lds[len(lds) - int(g.group(1)):] if int(g.group(1)) else ()
         return vm, lds
-    pending = frozenset().union(*vm, *lds) if (vm or lds) else frozenset()
-    hit = regs_of(text) & pending
+    pend_vm = frozenset().union(*vm) if vm else frozenset()
+    pend_lds = frozenset().union(*lds) if lds else frozenset()
+    v, d = VM_LOAD.match(text), LDS_LOAD.match(text)
+    named = regs_of(text)
+    if v or d:
+        # a load may name, as its destination, registers that an older load of the SAME queue still owes: they retire in
+        # order, so the younger value lands last; its address registers, and the other queue's registers, may not be pending
+        dest = regs_of((v or d).group(2))
+        rest = regs_of(text[(v or d).end(2):])
+        hit = (rest & (pend_vm | pend_lds)) | (dest & (pend_lds if v else pend_vm))
+    else:
+        hit = named & (pend_vm | pend_lds)
     if hit:
         report(text, sorted(hit))
-    v = VM_LOAD.match(text)
     if v and not text.rstrip().endswith(" lds"):
         vm = (vm + ((regs_of(v.group(2)) if in_asm else frozenset()),))[-QUEUE_CAP:]
-    else:
-        d = LDS_LOAD.match(text)
-        if d:
-            lds = (lds + ((regs_of(d.group(2)) if in_asm else frozenset()),))[-QUEUE_CAP:]
+    elif d:
+        lds = (lds + ((regs_of(d.group(2)) if in_asm else frozenset()),))[-QUEUE_CAP:]
     return vm, lds
 
 
-def audit(asm_text):
+def merge(a, b):
+    """Two queues of pending-register sets, youngest last: aligned at the youngest entry, united position by position."""
+    if len(a) < len(b):
+        a, b = b, a
+    pad = len(a) - len(b)
+    return a[:pad] + tuple(x | y for x, y in zip(a[pad:], b))
+
+
+def audit_blocks(asm_text):
+    """Every basic block on its own, starting with nothing pending: what no path can excuse."""
     problems = []
     for name, body in kernels(asm_text):
         for b in blocks_of(body):
             state = ((), ())
+            for text, in_asm in b["ins"]:
+                state = step(state, text, in_asm,
+                             lambda t, regs, _b=b: problems.append((name, _b["label"] or "(entry)", t, regs)))
+    return problems
+
+
+def audit(asm_text):
+    """The queues carried through the control-flow graph (see the module's text)."""
+    problems = []
+    for name, body in kernels(asm_text):
+        blocks = blocks_of(body)
+        if not blocks:
+            continue
+        entry = [None] * len(blocks)              # state at the start of each block; None: not reached yet
+        entry[0] = ((), ())
+        work = [0]
+        while work:
+            i = work.pop()
+            state = entry[i]
+            for text, in_asm in blocks[i]["ins"]:
+                state = step(state, text, in_asm, lambda t, regs: None)
+            for j in blocks[i]["succ"]:
+                new = state if entry[j] is None else (merge(entry[j][0], state[0]), merge(entry[j][1], state[1]))
+                if new != entry[j]:
+                    entry[j] = new
+                    work.append(j)
+        for i, b in enumerate(blocks):            # the states are final: report
+            if entry[i] is None:
+                continue
+            state = entry[i]
             for text, in_asm in b["ins"]:
                 state = step(state, text, in_asm,
                              lambda t, regs, _b=b: problems.append((name, _b["label"] or "(entry)", t, regs)))

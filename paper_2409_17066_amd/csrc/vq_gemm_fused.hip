@@ -303,6 +303,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
   const int n0 = blockIdx.x * DT, m0 = blockIdx.y * DT;
   const int ksteps = in_features / BK;
+  __builtin_assume(ksteps > 0);        // (the launcher's layers have whole groups of eight steps: no path around the loop, whose last step collects the reads in flight)
   // range-checked against the end of the last row: rows past the matrix read zeros
   const __amdgpu_buffer_rsrc_t r_x = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<__half *>(X), 0, (unsigned)(((long long)(tokens - 1) * ldx + in_features) * 2), 0x00020000);
@@ -388,6 +389,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     read_operands(kt + 1 < ksteps ? kt + 1 : kt, 0, a0, b0);  // (past the end: any stage, never used; keeps the loop one straight line)
     operands_in(a1, b1);
     multiply(a1, b1);
+    // the reads issued past the last step come in before the loop is left, while their registers are still the loop's
+    // (the empty statements that follow the wait name the registers, so they stay the operands' until the wait is over)
+    if (kt + 1 == ksteps) {
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      operands_in(a0, b0);
+    }
   }
 
   // ---- store: lane holds channel (lane & 31) of block c and 16 token rows of block a.  Range-checked 2-byte buffer stores

@@ -332,14 +332,14 @@ __device__ __forceinline__ void gemv_v6_mfma_body(const Params &p, const MfmaPla
               lds_gather16<LY::MAIN_OFF>(e[u], field_addr<12, LY::MAIN_SH>(cm, u));
             }
             load_slot(slot, b);                                  // refill with the pass PA ahead
+            // (waited for on every path, also where a ragged last chunk has no use for the block: no register may be
+            // handed back to the compiler with a load into it still on its way)
+            lds_gather_wait();
+#pragma unroll
+            for (int u = 0; u < VPL; ++u) settle(e[u]);
             if (b < nb_c) {
-              {
-                lds_gather_wait();
 #pragma unroll
-                for (int u = 0; u < VPL; ++u) settle(e[u]);
-#pragma unroll
-                for (int u = 0; u < VPL; ++u) acc[b] = mfma16(e[u], bx[u], acc[b]);
-              }
+              for (int u = 0; u < VPL; ++u) acc[b] = mfma16(e[u], bx[u], acc[b]);
               if (RES_BITS) {
                 uint4v f[VPL];
 #pragma unroll
