@@ -4,9 +4,14 @@
 A step is one batch-1 vq_gemv call (index unpack -> codebook lookups -> residual / outlier merge ->
 scale/bias -> matrix-vector product) on the Llama-2-7B-shaped 11008 x 4096 layer (v=6, k=4096,
 12-bit packed indices).  Consecutive steps rotate over distinct device copies of the index stream
-whose total size exceeds the 256 MB Infinity Cache, so every step streams its indices from HBM.
-`value` is algorithmic bytes per step / time per step.  The other layers (residual, outlier columns,
-batch > 1), the prefill vq_gemm and vq_dequant are timed briefly and reported under "detail".
+whose total size exceeds the 256 MB Infinity Cache, and the timed steps continue the rotation of an
+untimed lead-in that has just walked every copy, so every step streams its indices from HBM whatever
+--steps is.  `value`, `ms_per_step` and `roofline.achieved` are algorithmic bytes per step over the
+time HIP events on the launching stream measure around exactly --steps launches (one graph replay
+from 200 steps on, queued single launches below); `roofline.traffic` comes from the tracked
+rocprofv3 counter summary under profiles/.  The other layers (residual, outlier columns, batch > 1,
+the second target layer with a roofline block of its own), the prefill vq_gemm, vq_dequant,
+vq_assign and vq_quantize_columns are timed briefly and reported under "detail".
 
 Prints ONE JSON line.  Inputs are seeded synthetic tensors that stand in for real quantized
 checkpoints (same shapes and (v, k) settings; Gaussian tables, uniform indices).
