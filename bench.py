@@ -53,6 +53,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--config", type=int, default=1, help="benchmark configuration of the headline GEMV (1 or 3)")
     ap.add_argument("--no-detail", action="store_true", help="skip the secondary measurements")
+    ap.add_argument("--gemm-only", action="store_true", help="only the prefill vq_gemm lines of the detail (for counter runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
@@ -176,6 +177,11 @@ def main():
     vq.load()
     torch.cuda.set_device(0)
     use_graph = not args.no_graph
+    if args.gemm_only:
+        lines = []
+        gemm_lines(vq, s, torch, next(s.config_layers(4))[1], lines)
+        print(json.dumps({"detail": lines}))
+        return
     cfg = args.config
     spec = s.CONFIGS[cfg]
     _, layer = next(s.config_layers(cfg))
@@ -254,6 +260,33 @@ def main():
     if not args.no_detail:
         result["detail"] = detail(vq, s, np, torch, use_graph, skip=(cfg, 1))
     print(json.dumps(result))
+
+
+def gemm_lines(vq, s, torch, L4, out):
+    """The prefill product on the 8192 x 8192, v=8, k=65536 layer at the configuration's token counts, both routes."""
+    dl = vq.DeviceLayer(L4)
+    for tokens in s.CONFIGS[4]["rows"]:
+        X = torch.from_numpy(s.make_activations(4, L4, tokens)).cuda()
+        Y = torch.empty((tokens, L4.out_features), dtype=torch.float16, device="cuda")
+        flops = 2.0 * tokens * L4.out_features * L4.in_features
+        # two routes: weights restored on the fly (no workspace), and restored once into a workspace first
+        for route, need in (("on the fly", vq.vq_gemm_workspace_bytes(dl.desc, tokens)),
+                            ("restore, then multiply", vq.vq_gemm_fast_workspace_bytes(dl.desc, tokens))):
+            ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+
+            def launch(i):
+                rc = vq.vq_gemm(dl.desc, X.data_ptr(), X.stride(0), tokens, Y.data_ptr(), Y.stride(0), ws.data_ptr(), need,
+                                torch.cuda.current_stream().cuda_stream)
+                if rc != 0:
+                    raise vq.VQError(rc, "vq_gemm")
+            n = 10
+            wall, ev = timed(launch, n, 2, use_graph=False)
+            sec = ev / n
+            out.append({"op": "vq_gemm", "cfg": 4, "tokens": tokens, "route": route, "workspace_bytes": int(need),
+                        "us": round(sec * 1e6, 1), "TFLOP/s": round(flops / sec / 1e12, 1),
+                        "frac_mfma_peak": round(flops / sec / 1e12 / MFMA_FP16_PEAK_TFLOPS, 4)})
+            del ws
+    return dl
 
 
 def detail(vq, s, np, torch, use_graph, skip):
@@ -353,28 +386,7 @@ def detail(vq, s, np, torch, use_graph, skip):
         out.append({"op": "vq_gemv", "cfg": "4 (decode rows on the prefill layer)", "layer": L4.name, "batch": batch, "us": round(sec * 1e6, 3),
                     "GB/s": round(alg / sec / 1e9, 1), "frac_hbm_peak": round(alg / sec / 1e9 / HBM_PEAK_GBPS, 4),
                     "TFLOP/s": round(2.0 * batch * L4.out_features * L4.in_features / sec / 1e12, 2)})
-    dl = vq.DeviceLayer(L4)
-    for tokens in s.CONFIGS[4]["rows"]:
-        X = torch.from_numpy(s.make_activations(4, L4, tokens)).cuda()
-        Y = torch.empty((tokens, L4.out_features), dtype=torch.float16, device="cuda")
-        flops = 2.0 * tokens * L4.out_features * L4.in_features
-        # two routes: weights restored on the fly (no workspace), and restored once into a workspace first
-        for route, need in (("on the fly", vq.vq_gemm_workspace_bytes(dl.desc, tokens)),
-                            ("restore, then multiply", vq.vq_gemm_fast_workspace_bytes(dl.desc, tokens))):
-            ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
-
-            def launch(i):
-                rc = vq.vq_gemm(dl.desc, X.data_ptr(), X.stride(0), tokens, Y.data_ptr(), Y.stride(0), ws.data_ptr(), need,
-                                torch.cuda.current_stream().cuda_stream)
-                if rc != 0:
-                    raise vq.VQError(rc, "vq_gemm")
-            n = 10
-            wall, ev = timed(launch, n, 2, use_graph=False)
-            sec = ev / n
-            out.append({"op": "vq_gemm", "cfg": 4, "tokens": tokens, "route": route, "workspace_bytes": int(need),
-                        "us": round(sec * 1e6, 1), "TFLOP/s": round(flops / sec / 1e12, 1),
-                        "frac_mfma_peak": round(flops / sec / 1e12 / MFMA_FP16_PEAK_TFLOPS, 4)})
-            del ws
+    dl = gemm_lines(vq, s, torch, L4, out)
     W = torch.empty((L4.out_features, L4.in_features), dtype=torch.float16, device="cuda")
 
     def launch_dq(i):

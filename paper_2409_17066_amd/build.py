@@ -19,14 +19,14 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=o
 # Kernels in these files load registers asynchronously from inline assembly and wait for them with counted
 # s_waitcnt.  The compiler does not know such a register is pending: if it spilled one, it would save the old
 # contents.  Their kernels must therefore not spill at all; the build reads the compiler's resource remarks.
-NO_SPILL = {"vq_gemv_mfma.hip", "vq_gemm_fused.hip", "vq_gemv_down.hip", "vq_gemv_down_mfma.hip", "vq_gemv_fast.hip", "vq_gemv_res8.hip"}
+NO_SPILL = {"vq_gemv_mfma.hip", "vq_gemm_fused.hip", "vq_gemv_down.hip", "vq_gemv_down_mfma.hip", "vq_gemv_fast.hip", "vq_gemv_res8.hip", "vq_quantize.hip"}
 # One exception, checked in the generated code of this image's compiler (ROCm 7.2): the 512-token GEMM tile saves
 # five address registers at kernel entry, before its first asynchronous load, and reloads them in the epilogue.
 SPILLS_ALLOWED = {"gemm_v8_kernelILi512E": 5}
 REMARKS = ["-Rpass-analysis=kernel-resource-usage"]
 # The same files, and the dot-product GEMV with its hand-issued LDS reads, get their device assembly audited for
 # instructions that touch a register while an inline-assembly load into it is pending (check_async.py).
-AUDITED = ["vq_gemv_mfma.hip", "vq_gemm_fused.hip", "vq_gemv_fast.hip", "vq_gemv_res8.hip", "vq_gemv_down.hip", "vq_gemv_down_mfma.hip"]
+AUDITED = ["vq_gemv_mfma.hip", "vq_gemm_fused.hip", "vq_gemv_fast.hip", "vq_gemv_res8.hip", "vq_gemv_down.hip", "vq_gemv_down_mfma.hip", "vq_quantize.hip"]
 
 
 # Files whose control-flow graphs hold paths that no run takes (two branches on the same loop-invariant value, taken
