@@ -387,6 +387,30 @@ def detail(vq, s, np, torch, use_graph, skip):
                     "GB/s": round(alg / sec / 1e9, 1), "frac_hbm_peak": round(alg / sec / 1e9 / HBM_PEAK_GBPS, 4),
                     "TFLOP/s": round(2.0 * batch * L4.out_features * L4.in_features / sec / 1e12, 2)})
     dl = gemm_lines(vq, s, torch, L4, out)
+    # the same two routes on the v = 6 layers (tables in LDS): the headline layer and the 7B attention projection with its
+    # 12-bit residual, at 512 and 2048 tokens
+    for cfg6, name6 in ((1, "up"), (2, "q")):
+        _, L6 = next(s.config_layers(cfg6, only=name6))
+        dl6 = vq.DeviceLayer(L6)
+        for tokens in (512, 2048):
+            X = torch.from_numpy(s.make_activations(cfg6, L6, tokens)).cuda()
+            Y = torch.empty((tokens, L6.out_features), dtype=torch.float16, device="cuda")
+            flops = 2.0 * tokens * L6.out_features * L6.in_features
+            for route, need in (("on the fly", 0), ("restore, then multiply", vq.vq_gemm_fast_workspace_bytes(dl6.desc, tokens))):
+                ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+
+                def launch6(i):
+                    rc = vq.vq_gemm(dl6.desc, X.data_ptr(), X.stride(0), tokens, Y.data_ptr(), Y.stride(0), ws.data_ptr(), need,
+                                    torch.cuda.current_stream().cuda_stream)
+                    if rc != 0:
+                        raise vq.VQError(rc, "vq_gemm")
+                wall, ev = timed(launch6, 10, 2, use_graph=False)
+                sec = ev / 10
+                out.append({"op": "vq_gemm", "cfg": cfg6, "layer": name6, "tokens": tokens, "route": route, "workspace_bytes": int(need),
+                            "us": round(sec * 1e6, 1), "TFLOP/s": round(flops / sec / 1e12, 1),
+                            "frac_mfma_peak": round(flops / sec / 1e12 / MFMA_FP16_PEAK_TFLOPS, 4)})
+                del ws
+        del dl6, L6
     W = torch.empty((L4.out_features, L4.in_features), dtype=torch.float16, device="cuda")
 
     def launch_dq(i):

@@ -42,7 +42,7 @@
  * The environment variable VQ_SWITCHES ("name=value,..."; read once at the
  * start of every call) forces kernel choices for tests and measurements:
  * gemv=g|m|d (generic / matrix-core / dot-product kernels), groups=loop, multi=0,
- * gemm=g|f|w|r, dense=0|1, dequant=g|s; unset, every choice is the library's own.
+ * gemm=g|f|w|r|6, dense=0|1, dequant=g|s; unset, every choice is the library's own.
  */
 #ifndef VQ_H
 #define VQ_H
@@ -240,7 +240,9 @@ int vq_quantize_columns(void *W, int64_t ldw, int32_t rows, int32_t cols, const 
  *  - if it holds vq_gemm_fast_workspace_bytes(desc, tokens) bytes (non-zero when in_features is a
  *    multiple of 256), the call restores W into it once (as vq_dequant does) and multiplies from
  *    there, which is the faster route on this GPU; with less, the restored weights go straight from
- *    on-chip tiles into the matrix cores and W is never written to memory.
+ *    on-chip tiles into the matrix cores and W is never written to memory (kernels of their own for
+ *    v = 8 / 16-bit indices, gathered from L2, and for v = 6 / 12-bit indices without outlier columns or
+ *    codebook groups, whose tables sit in LDS; other layers restore through the generic tile kernel).
  * Small token counts (too few tiles to fill the chip), and layers whose only tile kernel without a
  * workspace is the generic one, are computed as vq_gemv computes them, sixteen rows of X at a time,
  * where that is the faster way on this GPU: same result bar, nothing for the caller to do.          */

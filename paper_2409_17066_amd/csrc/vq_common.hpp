@@ -41,7 +41,8 @@ int cu_count();
 //   gemv=g|m|d   generic kernels only / the matrix-core kernels wherever they take the layer / the dot-product kernels
 //   groups=loop  layers with codebook groups: every workgroup walks all groups even when a workspace is there
 //   multi=0      vq_gemv_multi as one vq_gemv after the other
-//   gemm=g|f|b|r vq_gemm: generic tile kernel / on-the-fly kernel / restore-then-multiply / rows through vq_gemv
+//   gemm=g|f|w|r|6 vq_gemm: generic tile kernel / no restore-then-multiply / restore-then-multiply whenever a workspace is
+//                there / rows through vq_gemv / the on-the-fly kernel for v = 6 layers at every token count
 //   dense=0|1    the dense product of the restore-then-multiply route: never / always the 256 x 256 tile kernel
 //   dequant=g|s  vq_dequant: generic kernel / never the wide-store kernel
 struct Switches {

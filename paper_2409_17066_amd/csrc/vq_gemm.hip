@@ -174,6 +174,8 @@ size_t gemm_fast_workspace_bytes(const Params &p, int tokens) {
 }
 
 bool gemm_fused_applicable(const Params &p);
+bool gemm_v6_applicable(const Params &p);
+int launch_gemm_v6(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy, hipStream_t s);
 int launch_gemm_fused(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy, const __half *Wd,
                       long long ldw, hipStream_t s);
 
@@ -184,8 +186,11 @@ int launch_gemm_fused(const Params &p, const __half *X, long long ldx, int token
 //     line out of L2 and a tile is gathered again for every token tile, while the restored matrix is read in
 //     full lines.  Any layer the library can dequantize qualifies (in_features a multiple of 256).
 //  2. v = 8 / 16-bit indices: restore on the fly inside the MFMA kernel (no workspace, W never in memory).
-//  3. the generic tile kernel.
-// Switch gemm=g forces 3, =f skips 1, =w takes 1 whenever a workspace is there (measurement and tests).
+//  3. v = 6 / 12-bit indices without outlier columns or groups: restore on the fly from tables in LDS (vq_gemm_v6.hip), when
+//     there is no workspace and more than 64 tokens (fewer go through vq_gemv's kernels, sixteen rows at a time).
+//  4. the generic tile kernel.
+// Switch gemm=g forces 4, =f skips 1, =w takes 1 whenever a workspace is there, =6 takes 3 for every token count
+// (measurement and tests).
 int launch_gemm(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy,
                 void *workspace, size_t workspace_bytes, hipStream_t s) {
   if (p.perm && tokens <= 65535 && workspace && workspace_bytes >= permuted_x_bytes(p, tokens) && (reinterpret_cast<uintptr_t>(workspace) & 15) == 0 &&
@@ -220,6 +225,10 @@ int launch_gemm(const Params &p, const __half *X, long long ldx, int tokens, __h
   // a specialised GEMV kernel (v = 8; orientation 1), whose cost grows faster with the rows: only without a workspace and
   // up to 128 tokens (v = 8, k = 65536 with a residual, 64 tokens: 191 against 848 us; 512 tokens would be 1480 against 880).
   // gemm=r: always.
+  if (gemm_v6_applicable(p) && (forced == '6' || (forced == '\0' && !have_ws && tokens > 64))) {
+    const int rc = launch_gemm_v6(p, X, ldx, tokens, Y, ldy, s);
+    if (rc != VQ_ERR_UNSUPPORTED) return rc;
+  }
   const bool rows_cheap = p.orientation == 0 && p.v == 6;
   if (forced == 'r' || (forced == '\0' && !gemm_fused_applicable(p) && gemv_has_fast_kernel(p, X, ldx) &&
                         (rows_cheap ? (!have_ws || tokens <= 96) : (!have_ws && tokens <= 128)))) {

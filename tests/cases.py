@@ -88,6 +88,11 @@ SMALL = {
     "down_fast_long_rows_res12": dict(out_features=66, in_features=16000, v=6, k=4096, k_res=4096, orientation=1),
     "down_fast_groups_many": dict(out_features=5000, in_features=4096, v=6, k=4096, group_vectors=600, orientation=1),
     "down_dense_gemm": dict(out_features=203, in_features=1024, v=6, k=4096, k_res=4096, n_outlier_cols=16, v_out=4, k_out=4096, orientation=1),
+    # vq_gemm's on-the-fly kernel for v = 6 (tables in LDS; in_features a multiple of 256, no outlier columns, one group):
+    # no residual, 8-bit and 12-bit residual streams, short tables, a ragged last channel block
+    "v6_gemm_plain": dict(out_features=300, in_features=768, v=6, k=4096),
+    "v6_gemm_res8": dict(out_features=200, in_features=512, v=6, k=3000, k_res=200),
+    "v6_gemm_res12": dict(out_features=133, in_features=1024, v=6, k=4096, k_res=4096, with_bias=False),
     # stored column order a permutation of the layer's (the outlier columns scattered over the layer): the kernels that
     # gather the activations themselves, the generic ones, both orientations, groups, the long-row kernel, both vq_gemm routes
     "perm_v6_k4096": dict(out_features=261, in_features=1030, v=6, k=4096, permute=True),

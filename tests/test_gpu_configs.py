@@ -151,3 +151,18 @@ def test_config3_with_scattered_outlier_columns(gpu_lib):
             y = gpu_lib.gemv(dl, torch.from_numpy(x).cuda(), workspace=workspace)
             torch.cuda.synchronize()
             _matmul_ok(y, ref, "cfg3 with permuted columns, batch %d, workspace %s" % (batch, workspace))
+
+
+@pytest.mark.parametrize("cfg,name,tokens", [(1, "up", 512), (2, "q", 300), (2, "down", 130)])
+def test_prefill_without_workspace_on_the_v6_layers(gpu_lib, layers, cfg, name, tokens):
+    """vq_gemm without a workspace on the 7B-shaped v = 6 layers (no residual; 12-bit residual): the kernel that restores W on
+    the fly from tables in LDS, every 16th output row plus the edges against the oracle."""
+    import torch
+    ordinal, L = layers(cfg, name)
+    dl = gpu_lib.DeviceLayer(L)
+    assert gpu_lib.vq_gemm_workspace_bytes(dl.desc, tokens) == 0
+    x = s.make_activations(cfg, L, tokens, layer_ordinal=ordinal)
+    Y = gpu_lib.gemm(dl, torch.from_numpy(x).cuda())
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([np.arange(0, L.out_features, 16), [L.out_features - 1, 127, 128, L.out_features - 128]])).astype(np.int32)
+    _matmul_ok(Y[:, torch.from_numpy(rows.astype(np.int64)).cuda()], oracle.gemm(L, x, rows=rows), "cfg%d %s T=%d on the fly" % (cfg, name, tokens))

@@ -97,6 +97,28 @@ def test_gemm_small(gpu_lib, monkeypatch, name, tokens, workspace):
     _check_matmul(Y, oracle.gemm(L, x), "%s tokens %d workspace %s" % (name, tokens, workspace))
 
 
+V6_GEMM = ["v6_gemm_plain", "v6_gemm_res8", "v6_gemm_res12", "single_row", "v6_exact_fit"]
+
+
+@pytest.mark.parametrize("name", V6_GEMM)
+@pytest.mark.parametrize("tokens", [1, 37, 130, 300, 700])
+def test_gemm_v6_on_the_fly(gpu_lib, monkeypatch, name, tokens):
+    """The kernel that restores v = 6 layers from tables in LDS, forced for every token count (by itself vq_gemm takes it
+    without a workspace from 65 tokens on), with NaN in the padding of X and a sentinel in the padding of Y."""
+    import torch
+    monkeypatch.setenv("VQ_SWITCHES", "gemm=6")
+    L = small_layer(name)
+    dl = gpu_lib.DeviceLayer(L)
+    x = s.make_activations(300, L, tokens)
+    X = torch.full((tokens, L.in_features + 8), float("nan"), dtype=torch.float16, device="cuda")
+    X[:, : L.in_features] = torch.from_numpy(x).cuda()
+    Y = torch.full((tokens, L.out_features + 3), 7.0, dtype=torch.float16, device="cuda")
+    gpu_lib.gemm(dl, X, out=Y)
+    torch.cuda.synchronize()
+    _check_matmul(Y[:, : L.out_features], oracle.gemm(L, x), "%s tokens %d on the fly" % (name, tokens))
+    assert (Y[:, L.out_features:] == 7.0).all()
+
+
 @pytest.mark.parametrize("kernel", ["auto", "m", "d"])
 @pytest.mark.parametrize("batch", [1, 4, 5, 16])
 @pytest.mark.parametrize("name,pad_x,pad_y", [("v6_res256_outlier", 10, 6), ("v6_k4096_res4096", 2, 1), ("v6_passes", 6, 3)])
