@@ -74,22 +74,24 @@ __global__ __launch_bounds__((BM / 64 + 4) * 64) void gemm_v8_kernel(Params p, c
     for (int j = 0; j < GD; ++j) issue_copy(greg[j], j);                      // steps 0 .. GD-1 (ksteps % GD == 0)
     wait_vmem_at_most<0>();
     store_w(0, greg[0]);
-    if (GD < ksteps) issue_copy(greg[0], GD);
+    // Every step issues its two loads, also where step kt + 1 + GD lies past the last one (the last step's words are loaded
+    // again and never looked at): the same number of loads separates every load from its use, so one counted wait serves
+    // all steps on every path.
+    issue_copy(greg[0], min(GD, ksteps - 1));
     step_barrier();
     for (int k0 = 0; k0 < ksteps; k0 += GD) {
 #pragma unroll
       for (int j = 0; j < GD; ++j) {
         const int kt = k0 + j;
-        if (kt + 1 < ksteps) {
-          // the loads of step kt+1 went out at the end of step kt-GD, followed by two loads in each of the GD-1 steps since
-          if (kt + GD < ksteps) wait_vmem_at_most<2 * (GD - 1)>(); else wait_vmem_at_most<0>();
-          const int sl = (j + 1) % GD;
-          store_w((kt & 1) ^ 1, greg[sl]);
-          if (kt + 1 + GD < ksteps) issue_copy(greg[sl], kt + 1 + GD);
-        }
+        // the loads of step kt+1 went out at the end of step kt-GD, followed by two loads in each of the GD-1 steps since
+        wait_vmem_at_most<2 * (GD - 1)>();
+        const int sl = (j + 1) % GD;
+        store_w((kt & 1) ^ 1, greg[sl]);                      // (after the last step: a tile nobody reads)
+        issue_copy(greg[sl], min(kt + 1 + GD, ksteps - 1));
         step_barrier();
       }
     }
+    wait_vmem_at_most<0>();
     return;
   }
   if (producer) {
@@ -122,38 +124,37 @@ __global__ __launch_bounds__((BM / 64 + 4) * 64) void gemm_v8_kernel(Params p, c
     };
     // Memory operations of a producer wave, in issue order: per step two centroid gathers (for step kt+1+GD), plus
     // GD/2 index loads at the start of every group of GD steps.  They complete in order.
+    // Every step and every group issues its loads, also past the end of the row (the last group and the last step are
+    // loaded again and never looked at), so the counted wait below is the same on every path.
     IdxGroup nxt, far;        // raw indices of the next group and of the group after it
     load_indices(0, far);
-    if (GD < ksteps) load_indices(GD, nxt);
+    load_indices(min(GD, ksteps - GD), nxt);
     wait_vmem_at_most<0>();
     settle_group(far); settle_group(nxt);
 #pragma unroll
     for (int j = 0; j < GD; ++j) issue_gather(greg[j], pick(far, j));        // steps 0 .. GD-1
     wait_vmem_at_most<0>();
     store_w(0, greg[0]);
-    if (GD < ksteps) issue_gather(greg[0], pick(nxt, 0));                    // slot 0 now carries step GD
+    issue_gather(greg[0], pick(nxt, 0));                                     // slot 0 now carries step GD
     step_barrier();
     for (int k0 = 0; k0 < ksteps; k0 += GD) {
-      if (k0 + 2 * GD < ksteps) load_indices(k0 + 2 * GD, far);             // first used at the last step of this group
+      load_indices(min(k0 + 2 * GD, ksteps - GD), far);                      // first used at the last step of this group
 #pragma unroll
       for (int j = 0; j < GD; ++j) {
         const int kt = k0 + j;                                    // ksteps % GD == 0: kt < ksteps
-        if (kt + 1 < ksteps) {
-          // The centroids of step kt+1 (slot (j+1) % GD) went out at the end of step kt-GD, followed by two
-          // gathers in each of the GD-1 steps since (index loads not counted: with them the bound only gets safer).
-          if (kt + GD < ksteps) wait_vmem_at_most<2 * (GD - 1)>(); else wait_vmem_at_most<0>();
-          const int sl = (j + 1) % GD;
-          store_w((kt & 1) ^ 1, greg[sl]);
-          if (kt + 1 + GD < ksteps) {
-            // the wait above also covers the index loads this gather needs (they are older than those centroids)
-            if (j + 1 < GD) { settle_group(nxt); issue_gather(greg[sl], pick(nxt, j + 1)); }
-            else { settle_group(far); issue_gather(greg[sl], pick(far, 0)); }
-          }
-        }
+        // The centroids of step kt+1 (slot (j+1) % GD) went out at the end of step kt-GD, followed by two
+        // gathers in each of the GD-1 steps since (index loads not counted: with them the bound only gets safer).
+        wait_vmem_at_most<2 * (GD - 1)>();
+        const int sl = (j + 1) % GD;
+        store_w((kt & 1) ^ 1, greg[sl]);                          // (after the last step: a tile nobody reads)
+        // the wait above also covers the index loads this gather needs (they are older than those centroids)
+        if (j + 1 < GD) { settle_group(nxt); issue_gather(greg[sl], pick(nxt, j + 1)); }
+        else { settle_group(far); issue_gather(greg[sl], pick(far, 0)); }
         step_barrier();
       }
       nxt = far;      // the group after next becomes the next group (its loads completed before the last wait above)
     }
+    wait_vmem_at_most<0>();
     return;
   }
 
