@@ -480,6 +480,16 @@ def detail(vq, s, np, torch, use_graph, skip):
                 "TFLOP/s": round(flops / best_q / 1e9, 1), "bound": "alu",
                 "frac_fp32_vector_peak": round(flops / best_q / 1e9 / FP32_VECTOR_PEAK_TFLOPS, 4)})
     del Uq, W0q, Wq, Cq
+    # the paper's other (v, k) settings on the headline shape (App. "Impact of Vector Length"): tables in LDS, whole-window index loads
+    for label, kw in (("v4 k256", dict(v=4, k=256)), ("v4 k256 + residual k256", dict(v=4, k=256, k_res=256)), ("v2 k16", dict(v=2, k=16)),
+                      ("v12 k4096", dict(v=12, k=4096))):
+        Lo = s.make_layer(1, "up", L1.out_features, L1.in_features, **kw)
+        r = bench_gemv(vq, Lo, s.make_activations(1, Lo, 1), steps, warmup, use_graph)
+        sec = r["event_s"] / steps
+        alg = Lo.algorithmic_bytes(1)
+        out.append({"op": "vq_gemv", "cfg": "1 shape with " + label, "batch": 1, "us": round(sec * 1e6, 3), "GB/s": round(alg / sec / 1e9, 1),
+                    "frac_hbm_peak": round(alg / sec / 1e9 / HBM_PEAK_GBPS, 4)})
+        del Lo
     # the headline shape stored in the paper's own orientation (vectors down the output dimension)
     Ld = s.make_layer(1, "up", L1.out_features, L1.in_features, 6, 4096, orientation=1)
     for batch in (1, 4, 16):

@@ -116,6 +116,8 @@ __global__ __launch_bounds__(256) void gemv_down_kernel(Params p, const __half *
 
 bool gemv_fast_applicable(const Params &p, const __half *x, long long ldx);
 bool gemv_res8_applicable(const Params &p, const __half *x);
+bool gemv_lds_applicable(const Params &p, int batch);
+int launch_gemv_lds(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
 int launch_gemv_res8(const Params &p, const __half *x, __half *y, hipStream_t s);
 int launch_gemv_fast(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
 
@@ -168,6 +170,22 @@ bool gemv_has_fast_kernel(const Params &p, const __half *x, long long ldx) {
   return gemv_fast_applicable(p, x, ldx) || gemv_v8_applicable(p, x, ldx);
 }
 
+// Layers without a kernel of their own whose tables fit LDS (vq_gemv_lds.hip): batch rows in launches of 4, 2 or 1, fewer
+// when that many activation rows do not fit beside the tables.  VQ_ERR_UNSUPPORTED when the kernel does not take the layer.
+static int gemv_through_lds_tables(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
+  if (force_generic() || !gemv_lds_applicable(p, 1)) return VQ_ERR_UNSUPPORTED;
+  int done = 0, g_max = 4, rc = VQ_OK;
+  while (done < batch) {
+    int g = batch - done >= 4 ? 4 : batch - done >= 2 ? 2 : 1;
+    if (g > g_max) g = g_max;
+    rc = launch_gemv_lds(p, x + done * ldx, ldx, g, y + done * ldy, ldy, s);
+    if (rc == VQ_ERR_UNSUPPORTED && g > 1) { g_max = g / 2; continue; }
+    if (rc != VQ_OK) return rc;
+    done += g;
+  }
+  return VQ_OK;
+}
+
 int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
   if (p.perm) {
     // Permuted column order without a workspace: the dot-product kernel for v = 6 that stages the activations in LDS
@@ -186,6 +204,10 @@ int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __ha
         if (rc == VQ_OK) return VQ_OK;
         if (rc != VQ_ERR_UNSUPPORTED || done != 0) return rc;
       }
+    }
+    {
+      const int rc = gemv_through_lds_tables(p, x, ldx, batch, y, ldy, s);       // gathers the activations while it stages them
+      if (rc != VQ_ERR_UNSUPPORTED) return rc;
     }
     if (p.orientation == 1) hipLaunchKernelGGL(gemv_down_kernel, dim3((unsigned)((p.S + 3) / 4)), dim3(256), 0, s, p, x, ldx, batch, y, ldy);
     else hipLaunchKernelGGL(gemv_generic_kernel, dim3((unsigned)((p.out_features + 3) / 4)), dim3(256), 0, s, p, x, ldx, batch, y, ldy);
@@ -278,6 +300,10 @@ int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __ha
       if (rc == VQ_OK) done += g;
     }
     if (rc != VQ_ERR_UNSUPPORTED || done != 0) return rc;
+  }
+  {
+    const int rc = gemv_through_lds_tables(p, x, ldx, batch, y, ldy, s);
+    if (rc != VQ_ERR_UNSUPPORTED) return rc;
   }
   const unsigned blocks = (unsigned)((p.out_features + 3) / 4);
   hipLaunchKernelGGL(gemv_generic_kernel, dim3(blocks), dim3(256), 0, s, p, x, ldx, batch, y, ldy);

@@ -1,0 +1,335 @@
+// vq_gemv for the layers that have no kernel of their own but whose tables fit LDS: any vector length, any table sizes and
+// index widths, residual and outlier tables, a column permutation -- the paper's other (v, k) settings (App. "Impact of
+// Vector Length": v = 2 / k = 16, v = 4 / k = 256; Table "Quantization parameters") -- one to four activation rows a launch.
+// (App. "Our Dequantization Implementation", decode phase: restore and multiply fused, the tables in fast memory.)
+//
+// One 1024-thread workgroup per compute unit owns a block of output rows.  Tables go into LDS as they are ([k][v] halves),
+// the activation rows too, gathered into stored column order on the way when the layer has a column permutation, so the
+// row loop never sees it.  A wave takes a row at a time; its lanes stride over the row's vectors, read their indices from
+// the packed streams (two dwords and a shift), look the centroids up in LDS and accumulate d * x in binary32 -- in pairs
+// with v_dot2_f32_f16 when vectors start on even columns, else element by element -- and the row ends in
+// y = scale * sum(d x) + bias * sum(x), as in the other decode kernels.  No layout tricks: this kernel's job is to keep
+// every such layer off the generic kernel, whose table reads go through the caches (about 90 GB/s).
+#include "vq_common.hpp"
+
+namespace vq {
+
+namespace {
+
+constexpr int LW = 16;           // waves per workgroup
+
+struct LdsPlan {
+  unsigned off_res, off_out, off_x, off_xsum, bytes;   // byte offsets in dynamic LDS (main table at 0)
+  int rows_per_wg;
+  unsigned x_pitch;                                    // bytes per staged activation row
+};
+
+__device__ __forceinline__ float dot2(unsigned a, unsigned b, float c) {
+  typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+  return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, a), __builtin_bit_cast(half2v, b), c, false);
+}
+
+template <int B>
+__global__ __launch_bounds__(LW * 64) void gemv_lds_kernel(Params p, LdsPlan plan, const __half *__restrict__ x, long long ldx,
+                                                           __half *__restrict__ y, long long ldy) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const __half *T = reinterpret_cast<const __half *>(lds);
+  const __half *Tr = reinterpret_cast<const __half *>(lds + plan.off_res);
+  const __half *To = reinterpret_cast<const __half *>(lds + plan.off_out);
+  float *xsum = reinterpret_cast<float *>(lds + plan.off_xsum);          // [B], then the waves' parts [B][LW]
+  float *xpart = xsum + B;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+
+  // ---- tables and activations into LDS
+  {
+    __half *dst = reinterpret_cast<__half *>(lds);
+    const int n_main = p.k * p.v, n_res = p.k_res * p.v, n_out = p.k_out * p.v_out;
+    for (int e = threadIdx.x; e < n_main; e += LW * 64) dst[e] = p.cb[e];
+    dst = reinterpret_cast<__half *>(lds + plan.off_res);
+    for (int e = threadIdx.x; e < n_res; e += LW * 64) dst[e] = p.cb_res[e];
+    dst = reinterpret_cast<__half *>(lds + plan.off_out);
+    for (int e = threadIdx.x; e < n_out; e += LW * 64) dst[e] = p.cb_out[e];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int t = 0; t < B; ++t) {
+    __half *xs = reinterpret_cast<__half *>(lds + plan.off_x + t * plan.x_pitch);
+    float part = 0.0f;
+    for (int c = threadIdx.x; c < p.in_features; c += LW * 64) {
+      int src = c;
+      if (p.perm) src = p.perm[c];                      // stored column c meets x[perm[c]] (Sec. 3.2.3); entries outside the row count as zero
+      const __half v = (unsigned)src < (unsigned)p.in_features ? x[(long long)t * ldx + src] : __float2half_rn(0.0f);
+      xs[c] = v;
+      part += __half2float(v);
+    }
+    // (the pad of the last vector: zeros)
+    for (int c = p.in_features + threadIdx.x; c < (int)(plan.x_pitch / 2); c += LW * 64) xs[c] = __float2half_rn(0.0f);
+    part = wave_sum(part);
+    if (lane == 0) xpart[t * LW + wv] = part;
+  }
+  __syncthreads();
+  if (threadIdx.x < B) {                                  // the waves' parts in a fixed order: the same bits every run
+    float sum = 0.0f;
+    for (int w = 0; w < LW; ++w) sum += xpart[threadIdx.x * LW + w];
+    xsum[threadIdx.x] = sum;
+  }
+  __syncthreads();
+
+  const int row0 = blockIdx.x * plan.rows_per_wg;
+  const int row1 = min(p.out_features, row0 + plan.rows_per_wg);
+  const bool pairs = (p.v % 2 == 0) && (p.n_out % 2 == 0) && (p.v_out % 2 == 0 || p.Q == 0);   // every vector starts on an even column
+  for (int o = row0 + wv; o < row1; o += LW) {
+    float acc[B];
+#pragma unroll
+    for (int t = 0; t < B; ++t) acc[t] = 0.0f;
+    const uint8_t *ri = p.idx + (long long)o * p.stride;
+    const uint8_t *rr = p.k_res ? p.idx_res + (long long)o * p.stride_res : ri, *ro = p.Q ? p.idx_out + (long long)o * p.stride_out : ri;
+    for (int slot = lane; slot < p.Q + p.P; slot += 64) {
+      const __half *e, *er = nullptr;
+      int c0, len;
+      if (slot < p.Q) {
+        const unsigned i = min(load_index(ro, slot, p.bits_out), (unsigned)p.k_out - 1u);
+        e = To + i * p.v_out; c0 = slot * p.v_out; len = p.v_out;
+      } else {
+        const int pp = slot - p.Q;
+        const unsigned i = min(load_index(ri, pp, p.bits), (unsigned)p.k - 1u);
+        e = T + i * p.v;
+        if (p.k_res) er = Tr + min(load_index(rr, pp, p.bits_res), (unsigned)p.k_res - 1u) * p.v;
+        c0 = p.n_out + pp * p.v; len = p.v;             // (columns past in_features meet zeros in the staged row)
+      }
+      if (pairs) {
+        for (int j = 0; j < len; j += 2) {
+          const unsigned d = *reinterpret_cast<const unsigned *>(e + j);
+          const unsigned r = er ? *reinterpret_cast<const unsigned *>(er + j) : 0u;
+#pragma unroll
+          for (int t = 0; t < B; ++t) {
+            const unsigned xv = *reinterpret_cast<const unsigned *>(lds + plan.off_x + t * plan.x_pitch + (unsigned)(c0 + j) * 2u);
+            acc[t] = dot2(d, xv, acc[t]);
+            if (er) acc[t] = dot2(r, xv, acc[t]);
+          }
+        }
+      } else {
+        for (int j = 0; j < len; ++j) {
+          float d = __half2float(e[j]);
+          if (er) d = __fadd_rn(d, __half2float(er[j]));
+#pragma unroll
+          for (int t = 0; t < B; ++t)
+            acc[t] = __fmaf_rn(d, __half2float(*reinterpret_cast<const __half *>(lds + plan.off_x + t * plan.x_pitch + (unsigned)(c0 + j) * 2u)), acc[t]);
+        }
+      }
+    }
+    const float s = p.scale ? __half2float(p.scale[o]) : 1.0f, b = p.bias ? __half2float(p.bias[o]) : 0.0f;
+#pragma unroll
+    for (int t = 0; t < B; ++t) {
+      const float r = wave_sum(acc[t]);
+      if (lane == 0) y[(long long)t * ldy + o] = __float2half_rn(__fmaf_rn(s, r, b * xsum[t]));
+    }
+  }
+}
+
+
+// The same for the settings of the paper's tables when there are no outlier columns: vector length V and index width BITS
+// (main and residual streams alike) fixed at compile time.  A lane takes a whole window of its row's index stream at a
+// time -- 32 / gcd(32, BITS) vectors in BITS / gcd(32, BITS) dwords, consecutive lanes consecutive windows: one coalesced,
+// range-checked load per window instead of two dwords per index -- and the table entries sit in LDS padded to 4, 8, 16 or
+// 32 bytes, so that an entry is one aligned read (two for V = 12).
+constexpr int win_vectors(int bits) { return bits % 32 == 0 ? 1 : bits % 16 == 0 ? 2 : bits % 8 == 0 ? 4 : bits % 4 == 0 ? 8 : 32; }
+constexpr int entry_halfs(int v) { return v <= 2 ? 2 : v <= 4 ? 4 : v <= 8 ? 8 : 16; }
+
+template <int ND>
+__device__ __forceinline__ void load_window(unsigned (&w)[ND], __amdgpu_buffer_rsrc_t r, unsigned off) {
+  if constexpr (ND == 1) w[0] = __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, 0);
+  else {
+    static_assert(ND == 3, "windows of one or three dwords");
+    typedef unsigned uint3v __attribute__((ext_vector_type(3)));
+    const uint3v a = __builtin_amdgcn_raw_buffer_load_b96(r, off, 0, 0);
+    w[0] = a.x; w[1] = a.y; w[2] = a.z;
+  }
+}
+template <int BITS, int ND>
+__device__ __forceinline__ unsigned window_field(const unsigned (&w)[ND], int u) {      // u is a compile-time constant after unrolling
+  const int bit = u * BITS, j = bit >> 5, sh = bit & 31;
+  unsigned v = w[j] >> sh;
+  if (sh + BITS > 32) v |= w[j + 1 < ND ? j + 1 : j] << (32 - sh);
+  return v & ((1u << BITS) - 1u);
+}
+
+template <int V, int BITS, bool RES, int B>
+__global__ __launch_bounds__(LW * 64) void gemv_lds_window_kernel(Params p, LdsPlan plan, const __half *__restrict__ x, long long ldx,
+                                                                  __half *__restrict__ y, long long ldy) {
+  constexpr int U = win_vectors(BITS), ND = U * BITS / 32, EH = entry_halfs(V), ED = EH / 2, VD = V / 2;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  float *xsum = reinterpret_cast<float *>(lds + plan.off_xsum);          // [B], then the waves' parts [B][LW]
+  float *xpart = xsum + B;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+
+  // ---- tables into LDS as padded entries (zero past the table's last entry and in the pad), activations as in the kernel above
+  for (int e = threadIdx.x; e < (p.k + (RES ? p.k_res : 0)) * ED; e += LW * 64) {
+    const int entry = e / ED, d = e - entry * ED;
+    const bool res = entry >= p.k;
+    const unsigned *src = reinterpret_cast<const unsigned *>(res ? p.cb_res : p.cb) + (long long)(res ? entry - p.k : entry) * VD;
+    reinterpret_cast<unsigned *>(lds + (res ? plan.off_res : 0u))[(res ? entry - p.k : entry) * ED + d] = d < VD ? src[d] : 0u;
+  }
+#pragma unroll
+  for (int t = 0; t < B; ++t) {
+    __half *xs = reinterpret_cast<__half *>(lds + plan.off_x + t * plan.x_pitch);
+    float part = 0.0f;
+    for (int c = threadIdx.x; c < p.in_features; c += LW * 64) {
+      int src = c;
+      if (p.perm) src = p.perm[c];
+      const __half v = (unsigned)src < (unsigned)p.in_features ? x[(long long)t * ldx + src] : __float2half_rn(0.0f);
+      xs[c] = v;
+      part += __half2float(v);
+    }
+    for (int c = p.in_features + threadIdx.x; c < (int)(plan.x_pitch / 2); c += LW * 64) xs[c] = __float2half_rn(0.0f);
+    part = wave_sum(part);
+    if (lane == 0) xpart[t * LW + wv] = part;
+  }
+  __syncthreads();
+  if (threadIdx.x < B) {
+    float sum = 0.0f;
+    for (int w = 0; w < LW; ++w) sum += xpart[threadIdx.x * LW + w];
+    xsum[threadIdx.x] = sum;
+  }
+  __syncthreads();
+
+  const int row0 = blockIdx.x * plan.rows_per_wg;
+  const int row1 = min(p.out_features, row0 + plan.rows_per_wg);
+  const int windows = (p.P + U - 1) / U;
+  const __amdgpu_buffer_rsrc_t r_i = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.idx), 0, (unsigned)((long long)p.out_features * p.stride), 0x00020000);
+  const __amdgpu_buffer_rsrc_t r_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(RES ? p.idx_res : p.idx), 0,
+                                                                       RES ? (unsigned)((long long)p.out_features * p.stride_res) : 0u, 0x00020000);
+  for (int o = row0 + wv; o < row1; o += LW) {
+    float acc[B];
+#pragma unroll
+    for (int t = 0; t < B; ++t) acc[t] = 0.0f;
+    for (int wdx = lane; wdx < windows; wdx += 64) {
+      unsigned wm[ND], wr[ND];
+      load_window<ND>(wm, r_i, (unsigned)o * (unsigned)p.stride + (unsigned)wdx * (ND * 4u));
+      if (RES) load_window<ND>(wr, r_r, (unsigned)o * (unsigned)p.stride_res + (unsigned)wdx * (ND * 4u));
+      const unsigned xbase = plan.off_x + (unsigned)wdx * (U * V * 2u);          // the window's U * V columns of the staged rows
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        // (a vector past the row's last one: some entry of the table times the zeros that end the staged row)
+        const unsigned i = min(window_field<BITS, ND>(wm, u), (unsigned)p.k - 1u);
+        unsigned e[ED], f[ED];
+#pragma unroll
+        for (int d = 0; d < ED; ++d) e[d] = reinterpret_cast<const unsigned *>(lds)[i * ED + d];
+        if (RES) {
+          const unsigned ir = min(window_field<BITS, ND>(wr, u), (unsigned)p.k_res - 1u);
+#pragma unroll
+          for (int d = 0; d < ED; ++d) f[d] = reinterpret_cast<const unsigned *>(lds + plan.off_res)[ir * ED + d];
+        }
+#pragma unroll
+        for (int t = 0; t < B; ++t) {
+#pragma unroll
+          for (int d = 0; d < VD; ++d) {
+            const unsigned xv = *reinterpret_cast<const unsigned *>(lds + xbase + t * plan.x_pitch + (unsigned)(u * V + 2 * d) * 2u);
+            acc[t] = dot2(e[d], xv, acc[t]);
+            if (RES) acc[t] = dot2(f[d], xv, acc[t]);
+          }
+        }
+      }
+    }
+    const float s = p.scale ? __half2float(p.scale[o]) : 1.0f, b = p.bias ? __half2float(p.bias[o]) : 0.0f;
+#pragma unroll
+    for (int t = 0; t < B; ++t) {
+      const float r = wave_sum(acc[t]);
+      if (lane == 0) y[(long long)t * ldy + o] = __float2half_rn(__fmaf_rn(s, r, b * xsum[t]));
+    }
+  }
+}
+
+// plan of the windowed kernel: padded tables, staged rows that cover whole windows
+bool make_window_plan(const Params &p, int batch, int u, int eh, LdsPlan *plan) {
+  auto up16 = [](size_t v) { return (v + 15) / 16 * 16; };
+  const size_t main = up16((size_t)p.k * eh * 2), res = up16((size_t)p.k_res * eh * 2);
+  const size_t windows = ((size_t)p.P + u - 1) / u;
+  const size_t pitch = up16(windows * u * p.v * 2);
+  const size_t total = main + res + pitch * batch + 4 * 4 * (1 + LW);
+  if (total > 160 * 1024) return false;
+  if ((long long)p.out_features * p.stride >= (1LL << 32) || (long long)p.out_features * p.stride_res >= (1LL << 32)) return false;
+  plan->off_res = (unsigned)main; plan->off_out = (unsigned)(main + res); plan->off_x = (unsigned)(main + res);
+  plan->off_xsum = (unsigned)(main + res + pitch * batch); plan->bytes = (unsigned)total; plan->x_pitch = (unsigned)pitch;
+  const int wgs = cu_count();
+  plan->rows_per_wg = (p.out_features + wgs - 1) / wgs;
+  if (plan->rows_per_wg < LW) plan->rows_per_wg = LW;
+  return true;
+}
+
+template <int V, int BITS, bool RES, int B>
+int launch_window(const Params &p, const __half *x, long long ldx, __half *y, long long ldy, hipStream_t s) {
+  LdsPlan plan;
+  if (!make_window_plan(p, B, win_vectors(BITS), entry_halfs(V), &plan)) return VQ_ERR_UNSUPPORTED;
+  auto kernel = gemv_lds_window_kernel<V, BITS, RES, B>;
+  VQ_ALLOW_FULL_LDS(kernel);
+  const unsigned grid = (unsigned)((p.out_features + plan.rows_per_wg - 1) / plan.rows_per_wg);
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(LW * 64), plan.bytes, s, p, plan, x, ldx, y, ldy);
+  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+template <int V, int BITS>
+int launch_window_vb(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
+  const bool res = p.k_res != 0;
+  if (batch == 1) return res ? launch_window<V, BITS, true, 1>(p, x, ldx, y, ldy, s) : launch_window<V, BITS, false, 1>(p, x, ldx, y, ldy, s);
+  if (batch == 2) return res ? launch_window<V, BITS, true, 2>(p, x, ldx, y, ldy, s) : launch_window<V, BITS, false, 2>(p, x, ldx, y, ldy, s);
+  if (batch == 4) return res ? launch_window<V, BITS, true, 4>(p, x, ldx, y, ldy, s) : launch_window<V, BITS, false, 4>(p, x, ldx, y, ldy, s);
+  return VQ_ERR_UNSUPPORTED;
+}
+
+// the (V, BITS) pairs with a compiled kernel: no outlier columns, a residual stream (if any) of the same index width
+int launch_window_any(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
+  if (p.Q != 0 || (p.k_res && p.bits_res != p.bits)) return VQ_ERR_UNSUPPORTED;
+#define VQ_PAIR(V, BITS) if (p.v == V && p.bits == BITS) return launch_window_vb<V, BITS>(p, x, ldx, batch, y, ldy, s);
+  VQ_PAIR(2, 4) VQ_PAIR(4, 8) VQ_PAIR(6, 8) VQ_PAIR(8, 8) VQ_PAIR(4, 12) VQ_PAIR(8, 12) VQ_PAIR(12, 12)
+#undef VQ_PAIR
+  return VQ_ERR_UNSUPPORTED;
+}
+
+bool make_plan(const Params &p, int batch, LdsPlan *plan) {
+  auto up16 = [](size_t v) { return (v + 15) / 16 * 16; };
+  const size_t main = up16((size_t)p.k * p.v * 2), res = up16((size_t)p.k_res * p.v * 2), out = up16((size_t)p.k_out * p.v_out * 2);
+  // a staged row covers every column a vector can name: the outlier columns, then P whole vectors
+  const size_t pitch = up16(((size_t)p.n_out + (size_t)p.P * p.v) * 2);
+  const size_t total = main + res + out + pitch * batch + 4 * 4 * (1 + LW);
+  if (total > 160 * 1024) return false;
+  plan->off_res = (unsigned)main; plan->off_out = (unsigned)(main + res); plan->off_x = (unsigned)(main + res + out);
+  plan->off_xsum = (unsigned)(main + res + out + pitch * batch); plan->bytes = (unsigned)total; plan->x_pitch = (unsigned)pitch;
+  const int wgs = cu_count();
+  plan->rows_per_wg = (p.out_features + wgs - 1) / wgs;
+  if (plan->rows_per_wg < LW) plan->rows_per_wg = LW;       // at least a row per wave
+  return true;
+}
+
+template <int B>
+int launch_b(const Params &p, const LdsPlan &plan, const __half *x, long long ldx, __half *y, long long ldy, hipStream_t s) {
+  VQ_ALLOW_FULL_LDS(gemv_lds_kernel<B>);
+  const unsigned grid = (unsigned)((p.out_features + plan.rows_per_wg - 1) / plan.rows_per_wg);
+  hipLaunchKernelGGL(gemv_lds_kernel<B>, dim3(grid), dim3(LW * 64), plan.bytes, s, p, plan, x, ldx, y, ldy);
+  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+}  // namespace
+
+// Vectors along the rows, one codebook group, tables and `batch` activation rows within LDS.
+bool gemv_lds_applicable(const Params &p, int batch) {
+  LdsPlan plan;
+  return p.orientation == 0 && p.n_groups == 1 && make_plan(p, batch, &plan);
+}
+
+// batch in {1, 2, 4}
+int launch_gemv_lds(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
+  LdsPlan plan;
+  if (p.orientation != 0 || p.n_groups != 1) return VQ_ERR_UNSUPPORTED;
+  if (batch == 1 || batch == 2 || batch == 4) {           // the compile-time variants first
+    const int rc = launch_window_any(p, x, ldx, batch, y, ldy, s);
+    if (rc != VQ_ERR_UNSUPPORTED) return rc;
+  }
+  if (!make_plan(p, batch, &plan)) return VQ_ERR_UNSUPPORTED;
+  if (batch == 1) return launch_b<1>(p, plan, x, ldx, y, ldy, s);
+  if (batch == 2) return launch_b<2>(p, plan, x, ldx, y, ldy, s);
+  if (batch == 4) return launch_b<4>(p, plan, x, ldx, y, ldy, s);
+  return VQ_ERR_UNSUPPORTED;
+}
+
+}  // namespace vq

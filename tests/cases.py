@@ -88,6 +88,16 @@ SMALL = {
     "down_fast_long_rows_res12": dict(out_features=66, in_features=16000, v=6, k=4096, k_res=4096, orientation=1),
     "down_fast_groups_many": dict(out_features=5000, in_features=4096, v=6, k=4096, group_vectors=600, orientation=1),
     "down_dense_gemm": dict(out_features=203, in_features=1024, v=6, k=4096, k_res=4096, n_outlier_cols=16, v_out=4, k_out=4096, orientation=1),
+    # the paper's other (v, k) settings on the decode kernels that keep the tables in LDS: whole-window index loads for
+    # 4-, 8- and 12-bit streams (ragged last window, rows past a multiple of sixteen, a residual stream of the same width, a
+    # permutation), and the run-time variant for everything else (residual of another width, outlier columns)
+    "lds_v4_k256": dict(out_features=517, in_features=1030, v=4, k=256),
+    "lds_v4_k256_res256": dict(out_features=300, in_features=2052, v=4, k=256, k_res=256),
+    "lds_v2_k16": dict(out_features=1000, in_features=650, v=2, k=16, with_scale=False),
+    "lds_v12_k4096": dict(out_features=77, in_features=3000, v=12, k=4096),
+    "lds_v8_k4096": dict(out_features=260, in_features=1000, v=8, k=3000, k_res=4000),
+    "lds_v4_k4096_perm": dict(out_features=130, in_features=1023, v=4, k=4096, permute=True),
+    "lds_v4_k256_outlier": dict(out_features=130, in_features=1030, v=4, k=256, k_res=16, n_outlier_cols=16, v_out=2, k_out=64),
     # vq_gemm's on-the-fly kernel for v = 6 (tables in LDS; in_features a multiple of 256, no outlier columns, one group):
     # no residual, 8-bit and 12-bit residual streams, short tables, a ragged last channel block
     "v6_gemm_plain": dict(out_features=300, in_features=768, v=6, k=4096),
