@@ -105,8 +105,8 @@ typedef struct vq_layer_desc {
    * that the array is a permutation: entries outside [0, in_features) read as zero activations and are not stored
    * by vq_dequant, repeated entries give unspecified values in the columns involved; neither leaves the buffers.
    * Kernels: vq_gemv gathers the activations itself in its one- and two-row kernels for v = 6 layers, in the kernels
-   * that keep other layers' tables in LDS, and in the generic kernels; with a workspace (vq_gemv_with_workspace, vq_gemv_static_workspace, vq_gemm) the activations are
-   * first gathered into it (vq_gemv_workspace_bytes / vq_gemm_fast_workspace_bytes count that copy) and every kernel of
+   * that keep other layers' tables in LDS, and in the generic kernels; with a workspace (vq_gemv_with_workspace,
+   * vq_gemv_static_workspace, vq_gemm) the activations are first gathered into it (vq_gemv_workspace_bytes / vq_gemm_fast_workspace_bytes count that copy) and every kernel of
    * the library then runs as for an unpermuted layer; vq_dequant restores in stored order and then reorders each
    * row in place through LDS.  A caller that sets struct_size to VQ_LAYER_DESC_SIZE_V2 (the layout up to
    * `orientation`) gets the identity.                                                                             */
