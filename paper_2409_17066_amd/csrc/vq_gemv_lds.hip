@@ -19,7 +19,7 @@ namespace {
 constexpr int LW = 16;           // waves per workgroup
 
 struct LdsPlan {
-  unsigned off_res, off_out, off_x, off_xsum, bytes;   // byte offsets in dynamic LDS (main table at 0)
+  unsigned off_res, off_out, off_x, off_xsum, off_ypart, bytes;   // byte offsets in dynamic LDS (main table at 0)
   int rows_per_wg;
   unsigned x_pitch;                                    // bytes per staged activation row
 };
@@ -135,6 +135,7 @@ __global__ __launch_bounds__(LW * 64) void gemv_lds_kernel(Params p, LdsPlan pla
 // 32 bytes, so that an entry is one aligned read (two for V = 12).
 constexpr int win_vectors(int bits) { return bits % 32 == 0 ? 1 : bits % 16 == 0 ? 2 : bits % 8 == 0 ? 4 : bits % 4 == 0 ? 8 : 32; }
 constexpr int entry_halfs(int v) { return v <= 2 ? 2 : v <= 4 ? 4 : v <= 8 ? 8 : 16; }
+constexpr bool two_pass_compiled(int v, int bits) { return v >= 8 && bits == 12; }   // where two padded tables can exceed LDS
 
 template <int ND>
 __device__ __forceinline__ void load_window(unsigned (&w)[ND], __amdgpu_buffer_rsrc_t r, unsigned off) {
@@ -154,22 +155,19 @@ __device__ __forceinline__ unsigned window_field(const unsigned (&w)[ND], int u)
   return v & ((1u << BITS) - 1u);
 }
 
-template <int V, int BITS, bool RES, int B>
+template <int V, int BITS, int MODE, int B>      // MODE 0: no residual; 1: both tables in LDS; 2: one table at a time, two passes over the rows
 __global__ __launch_bounds__(LW * 64) void gemv_lds_window_kernel(Params p, LdsPlan plan, const __half *__restrict__ x, long long ldx,
                                                                   __half *__restrict__ y, long long ldy) {
   constexpr int U = win_vectors(BITS), ND = U * BITS / 32, EH = entry_halfs(V), ED = EH / 2, VD = V / 2;
+  constexpr bool BOTH = MODE == 1;
+  constexpr int PASSES = MODE == 2 ? 2 : 1;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   float *xsum = reinterpret_cast<float *>(lds + plan.off_xsum);          // [B], then the waves' parts [B][LW]
   float *xpart = xsum + B;
+  float *ypart = reinterpret_cast<float *>(lds + plan.off_ypart);        // MODE 2: the first pass's row sums [rows_per_wg][B]
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
 
-  // ---- tables into LDS as padded entries (zero past the table's last entry and in the pad), activations as in the kernel above
-  for (int e = threadIdx.x; e < (p.k + (RES ? p.k_res : 0)) * ED; e += LW * 64) {
-    const int entry = e / ED, d = e - entry * ED;
-    const bool res = entry >= p.k;
-    const unsigned *src = reinterpret_cast<const unsigned *>(res ? p.cb_res : p.cb) + (long long)(res ? entry - p.k : entry) * VD;
-    reinterpret_cast<unsigned *>(lds + (res ? plan.off_res : 0u))[(res ? entry - p.k : entry) * ED + d] = d < VD ? src[d] : 0u;
-  }
+  // ---- activations into LDS as in the kernel above
 #pragma unroll
   for (int t = 0; t < B; ++t) {
     __half *xs = reinterpret_cast<__half *>(lds + plan.off_x + t * plan.x_pitch);
@@ -191,77 +189,103 @@ __global__ __launch_bounds__(LW * 64) void gemv_lds_window_kernel(Params p, LdsP
     for (int w = 0; w < LW; ++w) sum += xpart[threadIdx.x * LW + w];
     xsum[threadIdx.x] = sum;
   }
-  __syncthreads();
 
   const int row0 = blockIdx.x * plan.rows_per_wg;
   const int row1 = min(p.out_features, row0 + plan.rows_per_wg);
   const int windows = (p.P + U - 1) / U;
   const __amdgpu_buffer_rsrc_t r_i = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.idx), 0, (unsigned)((long long)p.out_features * p.stride), 0x00020000);
-  const __amdgpu_buffer_rsrc_t r_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(RES ? p.idx_res : p.idx), 0,
-                                                                       RES ? (unsigned)((long long)p.out_features * p.stride_res) : 0u, 0x00020000);
-  for (int o = row0 + wv; o < row1; o += LW) {
-    float acc[B];
+  const __amdgpu_buffer_rsrc_t r_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(MODE ? p.idx_res : p.idx), 0,
+                                                                       MODE ? (unsigned)((long long)p.out_features * p.stride_res) : 0u, 0x00020000);
+  for (int pass = 0; pass < PASSES; ++pass) {
+    // ---- this pass's table(s) into LDS as padded entries (zero past the table's last entry and in the pad)
+    const bool second = pass == 1;                                        // (MODE 2 only) the residual table takes the main table's place
+    const int k_a = second ? p.k_res : p.k;
+    const __half *cb_a = second ? p.cb_res : p.cb;
+    if (second) __syncthreads();                                          // every wave has left the first pass's table
+    for (int e = threadIdx.x; e < (k_a + (BOTH ? p.k_res : 0)) * ED; e += LW * 64) {
+      const int entry = e / ED, d = e - entry * ED;
+      const bool res = BOTH && entry >= k_a;
+      const unsigned *src = reinterpret_cast<const unsigned *>(res ? p.cb_res : cb_a) + (long long)(res ? entry - k_a : entry) * VD;
+      reinterpret_cast<unsigned *>(lds + (res ? plan.off_res : 0u))[(res ? entry - k_a : entry) * ED + d] = d < VD ? src[d] : 0u;
+    }
+    __syncthreads();
+
+    const __amdgpu_buffer_rsrc_t r_a = second ? r_r : r_i;
+    const unsigned stride_a = (unsigned)(second ? p.stride_res : p.stride);
+    for (int o = row0 + wv; o < row1; o += LW) {
+      float acc[B];
 #pragma unroll
-    for (int t = 0; t < B; ++t) acc[t] = 0.0f;
-    for (int wdx = lane; wdx < windows; wdx += 64) {
-      unsigned wm[ND], wr[ND];
-      load_window<ND>(wm, r_i, (unsigned)o * (unsigned)p.stride + (unsigned)wdx * (ND * 4u));
-      if (RES) load_window<ND>(wr, r_r, (unsigned)o * (unsigned)p.stride_res + (unsigned)wdx * (ND * 4u));
-      const unsigned xbase = plan.off_x + (unsigned)wdx * (U * V * 2u);          // the window's U * V columns of the staged rows
+      for (int t = 0; t < B; ++t) acc[t] = 0.0f;
+      for (int wdx = lane; wdx < windows; wdx += 64) {
+        unsigned wm[ND], wr[ND];
+        load_window<ND>(wm, r_a, (unsigned)o * stride_a + (unsigned)wdx * (ND * 4u));
+        if (BOTH) load_window<ND>(wr, r_r, (unsigned)o * (unsigned)p.stride_res + (unsigned)wdx * (ND * 4u));
+        const unsigned xbase = plan.off_x + (unsigned)wdx * (U * V * 2u);          // the window's U * V columns of the staged rows
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        // (a vector past the row's last one: some entry of the table times the zeros that end the staged row)
-        const unsigned i = min(window_field<BITS, ND>(wm, u), (unsigned)p.k - 1u);
-        unsigned e[ED], f[ED];
+        for (int u = 0; u < U; ++u) {
+          // (a vector past the row's last one: some entry of the table times the zeros that end the staged row)
+          const unsigned i = min(window_field<BITS, ND>(wm, u), (unsigned)k_a - 1u);
+          unsigned e[ED], f[ED];
 #pragma unroll
-        for (int d = 0; d < ED; ++d) e[d] = reinterpret_cast<const unsigned *>(lds)[i * ED + d];
-        if (RES) {
-          const unsigned ir = min(window_field<BITS, ND>(wr, u), (unsigned)p.k_res - 1u);
+          for (int d = 0; d < ED; ++d) e[d] = reinterpret_cast<const unsigned *>(lds)[i * ED + d];
+          if (BOTH) {
+            const unsigned ir = min(window_field<BITS, ND>(wr, u), (unsigned)p.k_res - 1u);
 #pragma unroll
-          for (int d = 0; d < ED; ++d) f[d] = reinterpret_cast<const unsigned *>(lds + plan.off_res)[ir * ED + d];
-        }
+            for (int d = 0; d < ED; ++d) f[d] = reinterpret_cast<const unsigned *>(lds + plan.off_res)[ir * ED + d];
+          }
 #pragma unroll
-        for (int t = 0; t < B; ++t) {
+          for (int t = 0; t < B; ++t) {
 #pragma unroll
-          for (int d = 0; d < VD; ++d) {
-            const unsigned xv = *reinterpret_cast<const unsigned *>(lds + xbase + t * plan.x_pitch + (unsigned)(u * V + 2 * d) * 2u);
-            acc[t] = dot2(e[d], xv, acc[t]);
-            if (RES) acc[t] = dot2(f[d], xv, acc[t]);
+            for (int d = 0; d < VD; ++d) {
+              const unsigned xv = *reinterpret_cast<const unsigned *>(lds + xbase + t * plan.x_pitch + (unsigned)(u * V + 2 * d) * 2u);
+              acc[t] = dot2(e[d], xv, acc[t]);
+              if (BOTH) acc[t] = dot2(f[d], xv, acc[t]);
+            }
           }
         }
       }
-    }
-    const float s = p.scale ? __half2float(p.scale[o]) : 1.0f, b = p.bias ? __half2float(p.bias[o]) : 0.0f;
+      const float s = p.scale ? __half2float(p.scale[o]) : 1.0f, b = p.bias ? __half2float(p.bias[o]) : 0.0f;
 #pragma unroll
-    for (int t = 0; t < B; ++t) {
-      const float r = wave_sum(acc[t]);
-      if (lane == 0) y[(long long)t * ldy + o] = __float2half_rn(__fmaf_rn(s, r, b * xsum[t]));
+      for (int t = 0; t < B; ++t) {
+        float r = wave_sum(acc[t]);
+        if (lane == 0) {
+          if (MODE == 2 && !second) ypart[(o - row0) * B + t] = r;       // the same lane of the same wave picks it up in the second pass
+          else {
+            if (MODE == 2) r = __fadd_rn(ypart[(o - row0) * B + t], r);
+            y[(long long)t * ldy + o] = __float2half_rn(__fmaf_rn(s, r, b * xsum[t]));
+          }
+        }
+      }
     }
   }
 }
 
 // plan of the windowed kernel: padded tables, staged rows that cover whole windows
-bool make_window_plan(const Params &p, int batch, int u, int eh, LdsPlan *plan) {
+// (two_pass: the residual table takes the main table's place for a second pass over the rows, whose first-pass sums wait in LDS)
+bool make_window_plan(const Params &p, int batch, int u, int eh, bool two_pass, LdsPlan *plan) {
   auto up16 = [](size_t v) { return (v + 15) / 16 * 16; };
   const size_t main = up16((size_t)p.k * eh * 2), res = up16((size_t)p.k_res * eh * 2);
+  const size_t tables = two_pass ? (main > res ? main : res) : main + res;
   const size_t windows = ((size_t)p.P + u - 1) / u;
   const size_t pitch = up16(windows * u * p.v * 2);
-  const size_t total = main + res + pitch * batch + 4 * 4 * (1 + LW);
-  if (total > 160 * 1024) return false;
-  if ((long long)p.out_features * p.stride >= (1LL << 32) || (long long)p.out_features * p.stride_res >= (1LL << 32)) return false;
-  plan->off_res = (unsigned)main; plan->off_out = (unsigned)(main + res); plan->off_x = (unsigned)(main + res);
-  plan->off_xsum = (unsigned)(main + res + pitch * batch); plan->bytes = (unsigned)total; plan->x_pitch = (unsigned)pitch;
   const int wgs = cu_count();
   plan->rows_per_wg = (p.out_features + wgs - 1) / wgs;
   if (plan->rows_per_wg < LW) plan->rows_per_wg = LW;
+  const size_t sums = up16(4 * 4 * (1 + LW));
+  const size_t total = tables + pitch * batch + sums + (two_pass ? (size_t)plan->rows_per_wg * batch * 4 : 0);
+  if (total > 160 * 1024) return false;
+  if ((long long)p.out_features * p.stride >= (1LL << 32) || (long long)p.out_features * p.stride_res >= (1LL << 32)) return false;
+  plan->off_res = (unsigned)main; plan->off_out = (unsigned)tables; plan->off_x = (unsigned)tables;
+  plan->off_xsum = (unsigned)(tables + pitch * batch); plan->off_ypart = (unsigned)(tables + pitch * batch + sums);
+  plan->bytes = (unsigned)total; plan->x_pitch = (unsigned)pitch;
   return true;
 }
 
-template <int V, int BITS, bool RES, int B>
+template <int V, int BITS, int MODE, int B>
 int launch_window(const Params &p, const __half *x, long long ldx, __half *y, long long ldy, hipStream_t s) {
   LdsPlan plan;
-  if (!make_window_plan(p, B, win_vectors(BITS), entry_halfs(V), &plan)) return VQ_ERR_UNSUPPORTED;
-  auto kernel = gemv_lds_window_kernel<V, BITS, RES, B>;
+  if (!make_window_plan(p, B, win_vectors(BITS), entry_halfs(V), MODE == 2, &plan)) return VQ_ERR_UNSUPPORTED;
+  auto kernel = gemv_lds_window_kernel<V, BITS, MODE, B>;
   VQ_ALLOW_FULL_LDS(kernel);
   const unsigned grid = (unsigned)((p.out_features + plan.rows_per_wg - 1) / plan.rows_per_wg);
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(LW * 64), plan.bytes, s, p, plan, x, ldx, y, ldy);
@@ -270,14 +294,24 @@ int launch_window(const Params &p, const __half *x, long long ldx, __half *y, lo
 
 template <int V, int BITS>
 int launch_window_vb(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
-  const bool res = p.k_res != 0;
-  if (batch == 1) return res ? launch_window<V, BITS, true, 1>(p, x, ldx, y, ldy, s) : launch_window<V, BITS, false, 1>(p, x, ldx, y, ldy, s);
-  if (batch == 2) return res ? launch_window<V, BITS, true, 2>(p, x, ldx, y, ldy, s) : launch_window<V, BITS, false, 2>(p, x, ldx, y, ldy, s);
-  if (batch == 4) return res ? launch_window<V, BITS, true, 4>(p, x, ldx, y, ldy, s) : launch_window<V, BITS, false, 4>(p, x, ldx, y, ldy, s);
-  return VQ_ERR_UNSUPPORTED;
+  if (batch != 1 && batch != 2 && batch != 4) return VQ_ERR_UNSUPPORTED;
+  if (p.k_res == 0)
+    return batch == 1 ? launch_window<V, BITS, 0, 1>(p, x, ldx, y, ldy, s) : batch == 2 ? launch_window<V, BITS, 0, 2>(p, x, ldx, y, ldy, s)
+                                                                                         : launch_window<V, BITS, 0, 4>(p, x, ldx, y, ldy, s);
+  int rc = batch == 1 ? launch_window<V, BITS, 1, 1>(p, x, ldx, y, ldy, s) : batch == 2 ? launch_window<V, BITS, 1, 2>(p, x, ldx, y, ldy, s)
+                                                                                          : launch_window<V, BITS, 1, 4>(p, x, ldx, y, ldy, s);
+  if (rc != VQ_ERR_UNSUPPORTED) return rc;
+  // both tables do not fit: one after the other (v = 12 with two 4096-entry tables, Table "Quantization parameters")
+  if constexpr (!two_pass_compiled(V, BITS)) return VQ_ERR_UNSUPPORTED;
+  else return batch == 1 ? launch_window<V, BITS, 2, 1>(p, x, ldx, y, ldy, s) : batch == 2 ? launch_window<V, BITS, 2, 2>(p, x, ldx, y, ldy, s)
+                                                                                        : launch_window<V, BITS, 2, 4>(p, x, ldx, y, ldy, s);
 }
 
 // the (V, BITS) pairs with a compiled kernel: no outlier columns, a residual stream (if any) of the same index width
+bool window_pair(const Params &p) {
+  if (p.Q != 0 || (p.k_res && p.bits_res != p.bits)) return false;
+  return (p.v == 2 && p.bits == 4) || ((p.v == 4 || p.v == 6 || p.v == 8) && p.bits == 8) || ((p.v == 4 || p.v == 8 || p.v == 12) && p.bits == 12);
+}
 int launch_window_any(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
   if (p.Q != 0 || (p.k_res && p.bits_res != p.bits)) return VQ_ERR_UNSUPPORTED;
 #define VQ_PAIR(V, BITS) if (p.v == V && p.bits == BITS) return launch_window_vb<V, BITS>(p, x, ldx, batch, y, ldy, s);
@@ -314,7 +348,11 @@ int launch_b(const Params &p, const LdsPlan &plan, const __half *x, long long ld
 // Vectors along the rows, one codebook group, tables and `batch` activation rows within LDS.
 bool gemv_lds_applicable(const Params &p, int batch) {
   LdsPlan plan;
-  return p.orientation == 0 && p.n_groups == 1 && make_plan(p, batch, &plan);
+  if (p.orientation != 0 || p.n_groups != 1) return false;
+  if (make_plan(p, batch, &plan)) return true;
+  if (!window_pair(p) || (batch != 1 && batch != 2 && batch != 4)) return false;
+  if (make_window_plan(p, batch, win_vectors(p.bits), entry_halfs(p.v), false, &plan)) return true;
+  return p.k_res != 0 && two_pass_compiled(p.v, p.bits) && make_window_plan(p, batch, win_vectors(p.bits), entry_halfs(p.v), true, &plan);
 }
 
 // batch in {1, 2, 4}

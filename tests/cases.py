@@ -98,6 +98,11 @@ SMALL = {
     "lds_v8_k4096": dict(out_features=260, in_features=1000, v=8, k=3000, k_res=4000),
     "lds_v4_k4096_perm": dict(out_features=130, in_features=1023, v=4, k=4096, permute=True),
     "lds_v4_k256_outlier": dict(out_features=130, in_features=1030, v=4, k=256, k_res=16, n_outlier_cols=16, v_out=2, k_out=64),
+    # two tables that do not fit LDS together (v = 12 with two 4096-entry tables: Table "Quantization parameters", the 2.26-bit
+    # setting): one table at a time, two passes over the rows; several rows per wave; long rows of v = 8
+    "lds_v12_two_tables": dict(out_features=5000, in_features=1500, v=12, k=4096, k_res=4096),
+    "lds_v12_two_tables_perm": dict(out_features=77, in_features=3001, v=12, k=4000, k_res=3000, permute=True, with_bias=False),
+    "lds_v8_two_tables_long": dict(out_features=100, in_features=20000, v=8, k=4096, k_res=4096),
     # vq_gemm's on-the-fly kernel for v = 6 (tables in LDS; in_features a multiple of 256, no outlier columns, one group):
     # no residual, 8-bit and 12-bit residual streams, short tables, a ragged last channel block
     "v6_gemm_plain": dict(out_features=300, in_features=768, v=6, k=4096),
