@@ -387,9 +387,9 @@ def detail(vq, s, np, torch, use_graph, skip):
                     "GB/s": round(alg / sec / 1e9, 1), "frac_hbm_peak": round(alg / sec / 1e9 / HBM_PEAK_GBPS, 4),
                     "TFLOP/s": round(2.0 * batch * L4.out_features * L4.in_features / sec / 1e12, 2)})
     dl = gemm_lines(vq, s, torch, L4, out)
-    # the same two routes on the v = 6 layers (tables in LDS): the headline layer and the 7B attention projection with its
-    # 12-bit residual, at 512 and 2048 tokens
-    for cfg6, name6 in ((1, "up"), (2, "q")):
+    # the same two routes on the v = 6 layers (tables in LDS): the headline layer, the 7B attention projection with its
+    # 12-bit residual and the 70B-shaped layer with its 8-bit residual and 288 outlier columns, at 512 and 2048 tokens
+    for cfg6, name6 in ((1, "up"), (2, "q"), (3, "down70b")):
         _, L6 = next(s.config_layers(cfg6, only=name6))
         dl6 = vq.DeviceLayer(L6)
         for tokens in (512, 2048):

@@ -241,8 +241,9 @@ int vq_quantize_columns(void *W, int64_t ldw, int32_t rows, int32_t cols, const 
  *    multiple of 256), the call restores W into it once (as vq_dequant does) and multiplies from
  *    there, which is the faster route on this GPU; with less, the restored weights go straight from
  *    on-chip tiles into the matrix cores and W is never written to memory (kernels of their own for
- *    v = 8 / 16-bit indices, gathered from L2, and for v = 6 / 12-bit indices without outlier columns or
- *    codebook groups, whose tables sit in LDS; other layers restore through the generic tile kernel).
+ *    v = 8 / 16-bit indices, gathered from L2, and for v = 6 / 12-bit indices with one codebook group
+ *    and outlier columns in multiples of 16, whose tables sit in LDS; other layers restore through the
+ *    generic tile kernel).
  * Small token counts (too few tiles to fill the chip), and layers whose only tile kernel without a
  * workspace is the generic one, are computed as vq_gemv computes them, sixteen rows of X at a time,
  * where that is the faster way on this GPU: same result bar, nothing for the caller to do.          */

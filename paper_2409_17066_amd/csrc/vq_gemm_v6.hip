@@ -10,7 +10,9 @@
 // step does not hold whole 6-column vectors: a producer thread makes 16 consecutive columns of one channel, which lie in the
 // four vectors from floor(c0 / 6) on; c0 is a multiple of 16, so they start 0, 1 or 2 dwords into the twelve dwords of those
 // four entries.  Its 48 index bits (and 32 or 48 residual index bits) are three dwords of the channel's stream, loaded GD
-// steps ahead from inline assembly and waited for by count.
+// steps ahead from inline assembly and waited for by count.  Outlier columns (Sec. 3.2.3: the first n_outlier_cols stored
+// columns, here in whole runs of 16) are the few steps at the start of every row; a producer thread looks those up one
+// column at a time through the caches, with ordinary loads.
 // LDS: tables 64 KB (+ 64 KB or 4 KB), W tiles 16 KB, activation stages BM x 64 bytes each -- with a 12-bit residual table
 // that leaves room for two stages of 128 tokens, which is the tile such layers get.
 #include "vq_gemm_tiles.hpp"
@@ -98,7 +100,10 @@ __global__ __launch_bounds__((BM / 64 + 4) * 64) void gemm_v6_kernel(Params p, c
     constexpr int RB = RES_BITS == 8 ? 8 : 12;
     uint3v ireg[GD], rreg[GD];                  // index dwords of the steps in flight; step kt uses slot kt % GD
     // first vector and dword offset into the twelve dwords of step kt (wave-uniform: scalar arithmetic)
-    auto first_vector = [&](int kt) { return (unsigned)(kt * BK + w_half * 16) / 6u; };
+    // (stored columns [0, n_out) are the outlier columns, n_out a multiple of 16: a thread's 16 columns of a step are either all
+    // outlier columns, made by make_outlier_tile below while the ring loads main-stream words that nobody looks at, or none)
+    auto main_col = [&](int kt) { return (unsigned)max(kt * BK + w_half * 16 - p.n_out, 0); };
+    auto first_vector = [&](int kt) { return main_col(kt) / 6u; };
     auto issue = [&](int slot, int kt) {
       const unsigned p0 = first_vector(kt);
       async_load12(ireg[slot], r_i, row_i + ((p0 * 12u) >> 5) * 4u);
@@ -113,11 +118,33 @@ __global__ __launch_bounds__((BM / 64 + 4) * 64) void gemm_v6_kernel(Params p, c
       out[2] = bits == 12 ? __builtin_amdgcn_alignbit(hi, lo, 24) & mask : (lo >> 16) & mask;
       out[3] = bits == 12 ? (hi >> 4) & mask : lo >> 24;
     };
+    // 16 outlier columns (Sec. 3.2.3) from stored column col0 on: their own stream and table, no residual; the few steps that
+    // hold them (288 of 28672 columns on the 70B layer) look every column up through the caches with ordinary loads
+    auto make_outlier_tile = [&](int buf, int col0) {
+      const uint8_t *ro = p.idx_out + (long long)o_w * p.stride_out;
+      unsigned h[16];
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int c = col0 + j, q = c / p.v_out, el = c - q * p.v_out;
+        const unsigned i = min(load_index(ro, q, p.bits_out), (unsigned)p.k_out - 1u);
+        h[j] = (unsigned)__half_as_ushort(p.cb_out[(long long)i * p.v_out + el]);
+      }
+      uint4v a, b;
+      a.x = restore_pair<false>(h[0] | (h[1] << 16), 0u, s_w, b_w);   a.y = restore_pair<false>(h[2] | (h[3] << 16), 0u, s_w, b_w);
+      a.z = restore_pair<false>(h[4] | (h[5] << 16), 0u, s_w, b_w);   a.w = restore_pair<false>(h[6] | (h[7] << 16), 0u, s_w, b_w);
+      b.x = restore_pair<false>(h[8] | (h[9] << 16), 0u, s_w, b_w);   b.y = restore_pair<false>(h[10] | (h[11] << 16), 0u, s_w, b_w);
+      b.z = restore_pair<false>(h[12] | (h[13] << 16), 0u, s_w, b_w); b.w = restore_pair<false>(h[14] | (h[15] << 16), 0u, s_w, b_w);
+      if (!w_on) { a = uint4v{0u, 0u, 0u, 0u}; b = uint4v{0u, 0u, 0u, 0u}; }
+      unsigned char *wt = reinterpret_cast<unsigned char *>(Ws + buf * BN * LDT);
+      *reinterpret_cast<uint4v *>(wt + x_slot((unsigned)w_row, (unsigned)(w_half * 2))) = a;
+      *reinterpret_cast<uint4v *>(wt + x_slot((unsigned)w_row, (unsigned)(w_half * 2 + 1))) = b;
+    };
     auto make_tile = [&](int buf, int slot, int kt) {
       settle(ireg[slot]);
       if (RES_BITS) settle(rreg[slot]);
+      if (kt * BK + w_half * 16 < p.n_out) { make_outlier_tile(buf, kt * BK + w_half * 16); return; }   // (the same for the whole wave)
       const unsigned p0 = first_vector(kt);
-      const unsigned skip = ((unsigned)(kt * BK + w_half * 16) - p0 * 6u) >> 1;        // 0, 1 or 2 dwords of the first entry lie before the run
+      const unsigned skip = (main_col(kt) - p0 * 6u) >> 1;        // 0, 1 or 2 dwords of the first entry lie before the run
       unsigned im[4], ir[4];
       fields(ireg[slot], (p0 * 12u) & 31u, 12, im);
       if (RES_BITS) fields(rreg[slot], (p0 * (unsigned)RB) & 31u, RB, ir);
@@ -255,10 +282,10 @@ int launch_v6(const Params &p, const __half *X, long long ldx, int tokens, __hal
 
 }  // namespace
 
-// v = 6 with 12-bit indices along the rows, no outlier columns, one codebook group, no residual or one of 8 or 12 index bits;
-// whole groups of GD steps; stream offsets that fit 32 bits.
+// v = 6 with 12-bit indices along the rows, outlier columns in whole runs of 16, one codebook group, no residual or one of 8 or
+// 12 index bits; whole groups of GD steps; stream offsets that fit 32 bits.
 bool gemm_v6_applicable(const Params &p) {
-  return p.orientation == 0 && p.v == 6 && p.bits == 12 && p.n_out == 0 && p.n_groups == 1 && !p.perm &&
+  return p.orientation == 0 && p.v == 6 && p.bits == 12 && p.n_out % 16 == 0 && p.n_groups == 1 && !p.perm &&
          (p.k_res == 0 || p.bits_res == 8 || p.bits_res == 12) && p.in_features % (GD * BK) == 0 &&
          (long long)p.out_features * p.stride < (1LL << 32) && (long long)p.out_features * p.stride_res < (1LL << 32);
 }

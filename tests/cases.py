@@ -108,6 +108,10 @@ SMALL = {
     "v6_gemm_plain": dict(out_features=300, in_features=768, v=6, k=4096),
     "v6_gemm_res8": dict(out_features=200, in_features=512, v=6, k=3000, k_res=200),
     "v6_gemm_res12": dict(out_features=133, in_features=1024, v=6, k=4096, k_res=4096, with_bias=False),
+    # ... with outlier columns in whole runs of 16 (a whole step, a step and a half, half a step; a ragged last main vector)
+    "v6_gemm_outlier32": dict(out_features=200, in_features=512, v=6, k=4096, k_res=256, n_outlier_cols=32, v_out=4, k_out=4096),
+    "v6_gemm_outlier48": dict(out_features=133, in_features=768, v=6, k=3000, n_outlier_cols=48, v_out=3, k_out=100),
+    "v6_gemm_outlier16_res12": dict(out_features=140, in_features=512, v=6, k=4096, k_res=4096, n_outlier_cols=16, v_out=2, k_out=16),
     # stored column order a permutation of the layer's (the outlier columns scattered over the layer): the kernels that
     # gather the activations themselves, the generic ones, both orientations, groups, the long-row kernel, both vq_gemm routes
     "perm_v6_k4096": dict(out_features=261, in_features=1030, v=6, k=4096, permute=True),

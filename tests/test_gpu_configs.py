@@ -153,10 +153,11 @@ def test_config3_with_scattered_outlier_columns(gpu_lib):
             _matmul_ok(y, ref, "cfg3 with permuted columns, batch %d, workspace %s" % (batch, workspace))
 
 
-@pytest.mark.parametrize("cfg,name,tokens", [(1, "up", 512), (2, "q", 300), (2, "down", 130)])
+@pytest.mark.parametrize("cfg,name,tokens", [(1, "up", 512), (2, "q", 300), (2, "down", 130), (3, "down70b", 130)])
 def test_prefill_without_workspace_on_the_v6_layers(gpu_lib, layers, cfg, name, tokens):
-    """vq_gemm without a workspace on the 7B-shaped v = 6 layers (no residual; 12-bit residual): the kernel that restores W on
-    the fly from tables in LDS, every 16th output row plus the edges against the oracle."""
+    """vq_gemm without a workspace on the 7B-shaped v = 6 layers (no residual; 12-bit residual) and on the 70B-shaped one (8-bit
+    residual, 288 outlier columns): the kernel that restores W on the fly from tables in LDS, every 16th output row plus the
+    edges against the oracle."""
     import torch
     ordinal, L = layers(cfg, name)
     dl = gpu_lib.DeviceLayer(L)

@@ -97,7 +97,8 @@ def test_gemm_small(gpu_lib, monkeypatch, name, tokens, workspace):
     _check_matmul(Y, oracle.gemm(L, x), "%s tokens %d workspace %s" % (name, tokens, workspace))
 
 
-V6_GEMM = ["v6_gemm_plain", "v6_gemm_res8", "v6_gemm_res12", "single_row", "v6_exact_fit"]
+V6_GEMM = ["v6_gemm_plain", "v6_gemm_res8", "v6_gemm_res12", "single_row", "v6_exact_fit", "v6_gemm_outlier32", "v6_gemm_outlier48",
+           "v6_gemm_outlier16_res12"]
 
 
 @pytest.mark.parametrize("name", V6_GEMM)
