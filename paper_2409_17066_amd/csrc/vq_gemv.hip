@@ -188,9 +188,14 @@ static int gemv_through_lds_tables(const Params &p, const __half *x, long long l
 
 int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
   if (p.perm) {
-    // Permuted column order without a workspace: the dot-product kernel for v = 6 that stages the activations in LDS
-    // gathers them while it does so; everything else runs on the generic kernels, which look every activation up.
+    // Permuted column order without a workspace: the dot-product kernels for v = 6 gather the activations while they stage
+    // them in LDS (or load them into registers: long rows); everything else runs on the generic kernels, which look every
+    // activation up.
     if (p.orientation == 0 && !force_generic()) {
+      if (batch == 1 && p.in_features >= 16384 && gemv_res8_applicable(p, x)) {     // the long-row kernel gathers into its registers
+        const int rc = launch_gemv_res8(p, x, y, s);
+        if (rc != VQ_ERR_UNSUPPORTED) return rc;
+      }
       if (gemv_fast_applicable(p, x, ldx) && p.n_groups == 1) {
         int done = 0, rc = VQ_OK, g_max = 4;
         while (done < batch) {

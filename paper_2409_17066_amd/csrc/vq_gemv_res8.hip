@@ -153,7 +153,25 @@ __device__ __forceinline__ void gemv_res8_body(const Params &p, const Res8Plan &
   constexpr int XA = 3 * U < 2 * UO ? 3 * U : 2 * UO;           // dwords both kinds of wave need; the rest only the one with more
   const unsigned first_col = is_main ? (unsigned)p.n_out + (unsigned)(slice * 64 + lane) * (6u * U) : (unsigned)(slice * 64 + lane) * (4u * UO);
   unsigned xr[XN];
-  {
+  if (p.perm) {
+    // stored column c meets x[col_perm[c]] (Sec. 3.2.3): the lane's columns one by one, range-checked (zero for a column past
+    // its part of the row or an entry outside the row).  Every workgroup looks the whole row up: what a caller without a
+    // workspace pays; with one, a gather kernel does it once.
+    const unsigned lim = is_main ? (unsigned)p.in_features : is_out ? (unsigned)p.n_out : 0u;
+    const unsigned lim_rest = (3 * U > 2 * UO ? is_main : is_out) ? lim : 0u;
+    unsigned pc[2 * XN];
+    load_dwords<2 * XN>(pc, make_rsrc(p.perm, lim * 4u), first_col * 4u);
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(x, (unsigned)p.in_features * 2u);
+#pragma unroll
+    for (int i = 0; i < XN; ++i) {
+      const unsigned l = i < XA ? lim : lim_rest;
+      const bool ok0 = first_col + 2u * i < l && pc[2 * i] < (unsigned)p.in_features;
+      const bool ok1 = first_col + 2u * i + 1u < l && pc[2 * i + 1] < (unsigned)p.in_features;
+      const unsigned h0 = __builtin_amdgcn_raw_buffer_load_b16(rx, ok0 ? pc[2 * i] * 2u : 0xFFFFFFFEu, 0, 0);
+      const unsigned h1 = __builtin_amdgcn_raw_buffer_load_b16(rx, ok1 ? pc[2 * i + 1] * 2u : 0xFFFFFFFEu, 0, 0);
+      xr[i] = h0 | (h1 << 16);
+    }
+  } else {
     const unsigned bytes = is_main ? (unsigned)p.in_features * 2u : is_out ? (unsigned)p.n_out * 2u : 0u;
     const unsigned bytes_rest = (3 * U > 2 * UO ? is_main : is_out) ? bytes : 0u;
     unsigned head[XA];
