@@ -225,7 +225,10 @@ int launch_gemm(const Params &p, const __half *X, long long ldx, int tokens, __h
   // a specialised GEMV kernel (v = 8; orientation 1), whose cost grows faster with the rows: only without a workspace and
   // up to 128 tokens (v = 8, k = 65536 with a residual, 64 tokens: 191 against 848 us; 512 tokens would be 1480 against 880).
   // gemm=r: always.
-  if (gemm_v6_applicable(p) && (forced == '6' || (forced == '\0' && !have_ws && tokens > 64))) {
+  // (the on-the-fly kernel for v = 6 from 65 tokens on; up to 128 tokens only where its 128 x 128 tiles give 80 workgroups --
+  // 8192 x 28672 at 128 tokens: 64 workgroups, 612 us against 515 us for eight passes of the GEMV)
+  const bool v6_tiles_fill = tokens > 128 || (long long)((p.out_features + 127) / 128) * ((tokens + 127) / 128) >= 80;
+  if (gemm_v6_applicable(p) && (forced == '6' || (forced == '\0' && !have_ws && tokens > 64 && v6_tiles_fill))) {
     const int rc = launch_gemm_v6(p, X, ldx, tokens, Y, ldy, s);
     if (rc != VQ_ERR_UNSUPPORTED) return rc;
   }
