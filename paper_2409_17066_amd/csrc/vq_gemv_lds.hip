@@ -17,6 +17,7 @@ namespace vq {
 namespace {
 
 constexpr int LW = 16;           // waves per workgroup
+typedef unsigned uint4v __attribute__((ext_vector_type(4)));
 
 struct LdsPlan {
   unsigned off_res, off_out, off_x, off_xsum, off_ypart, bytes;   // byte offsets in dynamic LDS (main table at 0)
@@ -167,7 +168,37 @@ __global__ __launch_bounds__(LW * 64) void gemv_lds_window_kernel(Params p, LdsP
   float *ypart = reinterpret_cast<float *>(lds + plan.off_ypart);        // MODE 2: the first pass's row sums [rows_per_wg][B]
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
 
-  // ---- activations into LDS as in the kernel above
+  const int row0 = blockIdx.x * plan.rows_per_wg;
+  const int row1 = min(p.out_features, row0 + plan.rows_per_wg);
+  const int windows = (p.P + U - 1) / U;
+  const __amdgpu_buffer_rsrc_t r_i = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.idx), 0, (unsigned)((long long)p.out_features * p.stride), 0x00020000);
+  const __amdgpu_buffer_rsrc_t r_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(MODE ? p.idx_res : p.idx), 0,
+                                                                       MODE ? (unsigned)((long long)p.out_features * p.stride_res) : 0u, 0x00020000);
+  // The wave's rows go 64 windows at a time (`ipr` rounds a row), and the windows of the next round are loaded before the
+  // current ones are used, so that a row's trip to memory hides behind the row before it; the first round's go out here,
+  // ahead of the staging.  A round past the row's windows or past the wave's rows loads from an offset outside the buffer
+  // (zeros, never looked at).
+  const int ipr = (windows + 63) >> 6;
+  auto offset_of = [&](int o, int it, unsigned stride) {
+    const int w = lane + it * 64;
+    return o < row1 && w < windows ? (unsigned)o * stride + (unsigned)w * (ND * 4u) : 0xFFFFFFF0u;
+  };
+  unsigned wm[ND], wr[ND];
+  float s_row = 1.0f, b_row = 0.0f;                                       // scale and bias of the current row, loaded ahead like the windows
+  auto first_loads = [&](bool second) {
+    const int o = row0 + wv;
+    load_window<ND>(wm, second ? r_r : r_i, offset_of(o, 0, (unsigned)(second ? p.stride_res : p.stride)));
+    if (BOTH) load_window<ND>(wr, r_r, offset_of(o, 0, (unsigned)p.stride_res));
+    s_row = 1.0f; b_row = 0.0f;
+    if (o < row1) {
+      if (p.scale) s_row = __half2float(p.scale[o]);
+      if (p.bias) b_row = __half2float(p.bias[o]);
+    }
+  };
+  first_loads(false);
+
+  // ---- activations into LDS as in the kernel above (windows of U * V columns side by side: a lane's reads of consecutive
+  // columns stay aligned and wide; an odd pitch per window, tried against bank conflicts, made them narrow and twice as slow)
 #pragma unroll
   for (int t = 0; t < B; ++t) {
     __half *xs = reinterpret_cast<__half *>(lds + plan.off_x + t * plan.x_pitch);
@@ -190,36 +221,66 @@ __global__ __launch_bounds__(LW * 64) void gemv_lds_window_kernel(Params p, LdsP
     xsum[threadIdx.x] = sum;
   }
 
-  const int row0 = blockIdx.x * plan.rows_per_wg;
-  const int row1 = min(p.out_features, row0 + plan.rows_per_wg);
-  const int windows = (p.P + U - 1) / U;
-  const __amdgpu_buffer_rsrc_t r_i = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.idx), 0, (unsigned)((long long)p.out_features * p.stride), 0x00020000);
-  const __amdgpu_buffer_rsrc_t r_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(MODE ? p.idx_res : p.idx), 0,
-                                                                       MODE ? (unsigned)((long long)p.out_features * p.stride_res) : 0u, 0x00020000);
   for (int pass = 0; pass < PASSES; ++pass) {
     // ---- this pass's table(s) into LDS as padded entries (zero past the table's last entry and in the pad)
     const bool second = pass == 1;                                        // (MODE 2 only) the residual table takes the main table's place
     const int k_a = second ? p.k_res : p.k;
     const __half *cb_a = second ? p.cb_res : p.cb;
-    if (second) __syncthreads();                                          // every wave has left the first pass's table
-    for (int e = threadIdx.x; e < (k_a + (BOTH ? p.k_res : 0)) * ED; e += LW * 64) {
-      const int entry = e / ED, d = e - entry * ED;
-      const bool res = BOTH && entry >= k_a;
-      const unsigned *src = reinterpret_cast<const unsigned *>(res ? p.cb_res : cb_a) + (long long)(res ? entry - k_a : entry) * VD;
-      reinterpret_cast<unsigned *>(lds + (res ? plan.off_res : 0u))[(res ? entry - k_a : entry) * ED + d] = d < VD ? src[d] : 0u;
+    if (second) {
+      first_loads(true);
+      __syncthreads();                                                    // every wave has left the first pass's table
+    }
+    // (an entry per thread and round: its V / 2 dwords loaded together, stored as one padded entry; four rounds in flight)
+#pragma unroll 4
+    for (int en = threadIdx.x; en < k_a + (BOTH ? p.k_res : 0); en += LW * 64) {
+      const bool res = BOTH && en >= k_a;
+      const int entry = res ? en - k_a : en;
+      const unsigned *src = reinterpret_cast<const unsigned *>(res ? p.cb_res : cb_a) + (long long)entry * VD;
+      unsigned v[ED];
+#pragma unroll
+      for (int d = 0; d < ED; ++d) v[d] = 0u;
+      // (the tables are 16-byte aligned, so entries of an even number of dwords are 8-byte aligned, of 4 or 8 dwords 16-byte)
+      if constexpr (VD % 4 == 0) {
+#pragma unroll
+        for (int d = 0; d < VD; d += 4) { const uint4v a = *reinterpret_cast<const uint4v *>(src + d); v[d] = a.x; v[d + 1] = a.y; v[d + 2] = a.z; v[d + 3] = a.w; }
+      } else if constexpr (VD % 2 == 0) {
+        typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+#pragma unroll
+        for (int d = 0; d < VD; d += 2) { const uint2v a = *reinterpret_cast<const uint2v *>(src + d); v[d] = a.x; v[d + 1] = a.y; }
+      } else {
+#pragma unroll
+        for (int d = 0; d < VD; ++d) v[d] = src[d];
+      }
+      unsigned *dst = reinterpret_cast<unsigned *>(lds + (res ? plan.off_res : 0u)) + entry * ED;
+      if constexpr (ED >= 4) {
+#pragma unroll
+        for (int d = 0; d < ED; d += 4) *reinterpret_cast<uint4v *>(dst + d) = uint4v{v[d], v[d + 1], v[d + 2], v[d + 3]};
+      } else {
+#pragma unroll
+        for (int d = 0; d < ED; ++d) dst[d] = v[d];
+      }
     }
     __syncthreads();
 
     const __amdgpu_buffer_rsrc_t r_a = second ? r_r : r_i;
     const unsigned stride_a = (unsigned)(second ? p.stride_res : p.stride);
-    for (int o = row0 + wv; o < row1; o += LW) {
-      float acc[B];
+    int o = row0 + wv, it = 0;
+    float acc[B];
 #pragma unroll
-      for (int t = 0; t < B; ++t) acc[t] = 0.0f;
-      for (int wdx = lane; wdx < windows; wdx += 64) {
-        unsigned wm[ND], wr[ND];
-        load_window<ND>(wm, r_a, (unsigned)o * stride_a + (unsigned)wdx * (ND * 4u));
-        if (BOTH) load_window<ND>(wr, r_r, (unsigned)o * (unsigned)p.stride_res + (unsigned)wdx * (ND * 4u));
+    for (int t = 0; t < B; ++t) acc[t] = 0.0f;
+    while (o < row1) {
+      int on = o, itn = it + 1;
+      if (itn == ipr) { itn = 0; on = o + LW; }
+      float s_next = s_row, b_next = b_row;
+      if (itn == 0 && on < row1) {
+        if (p.scale) s_next = __half2float(p.scale[on]);
+        if (p.bias) b_next = __half2float(p.bias[on]);
+      }
+      unsigned nm[ND], nr[ND];
+      load_window<ND>(nm, r_a, offset_of(on, itn, stride_a));
+      if (BOTH) load_window<ND>(nr, r_r, offset_of(on, itn, (unsigned)p.stride_res));
+      const int wdx = lane + it * 64;
+      if (wdx < windows) {
         const unsigned xbase = plan.off_x + (unsigned)wdx * (U * V * 2u);          // the window's U * V columns of the staged rows
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -244,23 +305,28 @@ __global__ __launch_bounds__(LW * 64) void gemv_lds_window_kernel(Params p, LdsP
           }
         }
       }
-      const float s = p.scale ? __half2float(p.scale[o]) : 1.0f, b = p.bias ? __half2float(p.bias[o]) : 0.0f;
+      if (itn == 0) {                                                     // the row is complete
+        const float s = s_row, b = b_row;
 #pragma unroll
-      for (int t = 0; t < B; ++t) {
-        float r = wave_sum(acc[t]);
-        if (lane == 0) {
-          if (MODE == 2 && !second) ypart[(o - row0) * B + t] = r;       // the same lane of the same wave picks it up in the second pass
-          else {
-            if (MODE == 2) r = __fadd_rn(ypart[(o - row0) * B + t], r);
-            y[(long long)t * ldy + o] = __float2half_rn(__fmaf_rn(s, r, b * xsum[t]));
+        for (int t = 0; t < B; ++t) {
+          float r = wave_sum(acc[t]);
+          acc[t] = 0.0f;
+          if (lane == 0) {
+            if (MODE == 2 && !second) ypart[(o - row0) * B + t] = r;       // the same lane of the same wave picks it up in the second pass
+            else {
+              if (MODE == 2) r = __fadd_rn(ypart[(o - row0) * B + t], r);
+              y[(long long)t * ldy + o] = __float2half_rn(__fmaf_rn(s, r, b * xsum[t]));
+            }
           }
         }
       }
+#pragma unroll
+      for (int d = 0; d < ND; ++d) { wm[d] = nm[d]; if (BOTH) wr[d] = nr[d]; }
+      o = on; it = itn; s_row = s_next; b_row = b_next;
     }
   }
 }
 
-// plan of the windowed kernel: padded tables, staged rows that cover whole windows
 // (two_pass: the residual table takes the main table's place for a second pass over the rows, whose first-pass sums wait in LDS)
 bool make_window_plan(const Params &p, int batch, int u, int eh, bool two_pass, LdsPlan *plan) {
   auto up16 = [](size_t v) { return (v + 15) / 16 * 16; };
