@@ -192,8 +192,10 @@ int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __ha
     // them in LDS (or load them into registers: long rows); everything else runs on the generic kernels, which look every
     // activation up.
     if (p.orientation == 0 && !force_generic()) {
-      if (batch == 1 && p.in_features >= 16384 && gemv_res8_applicable(p, x)) {     // the long-row kernel gathers into its registers
-        const int rc = launch_gemv_res8(p, x, y, s);
+      if (p.in_features >= 16384 && gemv_res8_applicable(p, x) && (ldx & 1) == 0) {
+        // the long-row kernel gathers into its registers; more rows one after the other (still far ahead of the generic kernel)
+        int rc = VQ_OK;
+        for (int t = 0; t < batch && rc == VQ_OK; ++t) rc = launch_gemv_res8(p, x + t * ldx, y + t * ldy, s);
         if (rc != VQ_ERR_UNSUPPORTED) return rc;
       }
       if (gemv_fast_applicable(p, x, ldx) && p.n_groups == 1) {
