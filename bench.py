@@ -482,7 +482,10 @@ def detail(vq, s, np, torch, use_graph, skip):
     del Uq, W0q, Wq, Cq
     # the paper's other (v, k) settings on the headline shape (App. "Impact of Vector Length"): tables in LDS, whole-window index loads
     for label, kw in (("v4 k256", dict(v=4, k=256)), ("v4 k256 + residual k256", dict(v=4, k=256, k_res=256)), ("v2 k16", dict(v=2, k=16)),
-                      ("v12 k4096", dict(v=12, k=4096)), ("v12 k4096 + residual k4096 (two passes)", dict(v=12, k=4096, k_res=4096))):
+                      ("v12 k4096", dict(v=12, k=4096)), ("v12 k4096 + residual k4096 (two passes)", dict(v=12, k=4096, k_res=4096)),
+                      ("v12 k4096 + residual k4096, 4 codebook groups, 40 outlier columns of v4 k8192 (the 2.26-bit setting of "
+                       "Table 'Quantization parameters': nine passes)",
+                       dict(v=12, k=4096, k_res=4096, n_outlier_cols=40, v_out=4, k_out=8192, group_vectors=85))):
         Lo = s.make_layer(1, "up", L1.out_features, L1.in_features, **kw)
         r = bench_gemv(vq, Lo, s.make_activations(1, Lo, 1), steps, warmup, use_graph)
         sec = r["event_s"] / steps

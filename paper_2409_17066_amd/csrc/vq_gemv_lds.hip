@@ -386,6 +386,270 @@ int launch_window_any(const Params &p, const __half *x, long long ldx, int batch
   return VQ_ERR_UNSUPPORTED;
 }
 
+// The layers of the paper's 2.07- to 2.26-bit settings (Table "Quantization parameters": v = 12 with two 4096-entry tables,
+// 1 % outlier columns of v = 4, one to sixteen codebook groups) and whatever else the kernels above refuse for outlier
+// columns, codebook groups (Sec. 3.1) or size: one table in LDS at a time.  A pass is (group, main or residual table) or the
+// outlier table; the workgroup stages the pass's table (and, where groups differ, the activations with zeros outside the
+// group's columns, so that a window that straddles two groups needs no masks), walks its rows over the pass's windows, and
+// adds the row sums to those of the passes before, which wait in LDS; the dot product is linear in the sum of centroids, so
+// y = scale * (sum of the passes) + bias * sum(x).  Outlier vectors have v_out = 4 and any index width.
+struct PassPlan {
+  unsigned off_x, off_xo, off_xsum, off_ypart, bytes;     // byte offsets in dynamic LDS (the pass's table at 0)
+  unsigned x_pitch, xo_pitch;                             // bytes per staged row of main / outlier columns
+  int rows_per_wg;
+};
+
+template <int V, int BITS, int B>
+__global__ __launch_bounds__(LW * 64) void gemv_lds_passes_kernel(Params p, PassPlan plan, const __half *__restrict__ x, long long ldx,
+                                                                  __half *__restrict__ y, long long ldy) {
+  constexpr int U = win_vectors(BITS), ND = U * BITS / 32, EH = entry_halfs(V), ED = EH / 2, VD = V / 2;
+  typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  float *xsum = reinterpret_cast<float *>(lds + plan.off_xsum);          // [B], then the waves' parts [B][LW]
+  float *xpart = xsum + B;
+  float *ypart = reinterpret_cast<float *>(lds + plan.off_ypart);        // row sums of the passes so far [rows_per_wg][B]
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int row0 = blockIdx.x * plan.rows_per_wg;
+  const int row1 = min(p.out_features, row0 + plan.rows_per_wg);
+  const int windows = (p.P + U - 1) / U;
+  const __amdgpu_buffer_rsrc_t r_i = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.idx), 0, (unsigned)((long long)p.out_features * p.stride), 0x00020000);
+  const __amdgpu_buffer_rsrc_t r_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.k_res ? p.idx_res : p.idx), 0,
+                                                                       p.k_res ? (unsigned)((long long)p.out_features * p.stride_res) : 0u, 0x00020000);
+  const __amdgpu_buffer_rsrc_t r_o = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.Q ? p.idx_out : p.idx), 0,
+                                                                       p.Q ? (unsigned)((long long)p.out_features * p.stride_out) : 0u, 0x00020000);
+  auto x_at = [&](int t, int c) {                         // activation of stored column c (Sec. 3.2.3), zero outside the row
+    int src = c;
+    if (p.perm) src = p.perm[c];
+    return (unsigned)src < (unsigned)p.in_features ? x[(long long)t * ldx + src] : __float2half_rn(0.0f);
+  };
+
+  // ---- once: the sum of every activation row, the activations of the outlier columns
+#pragma unroll
+  for (int t = 0; t < B; ++t) {
+    __half *xo = reinterpret_cast<__half *>(lds + plan.off_xo + t * plan.xo_pitch);
+    float part = 0.0f;
+    for (int c = threadIdx.x; c < p.in_features; c += LW * 64) {
+      const __half v = x_at(t, c);
+      if (c < p.n_out) xo[c] = v;
+      part += __half2float(v);
+    }
+    part = wave_sum(part);
+    if (lane == 0) xpart[t * LW + wv] = part;
+  }
+
+  const int tables_per_group = p.k_res ? 2 : 1;
+  const int table_passes = p.n_groups * tables_per_group;
+  for (int pass = 0; pass < table_passes + (p.Q ? 1 : 0); ++pass) {
+    const bool outlier = pass == table_passes;
+    const int g = pass / tables_per_group;
+    const bool second = !outlier && pass - g * tables_per_group == 1;
+    // the pass's vectors [p_lo, p_hi) of the row, its windows [w_lo, w_hi) (outlier pass: its Q vectors, one per "window")
+    const int p_lo = outlier ? 0 : g * p.Pg, p_hi = outlier ? p.Q : min(p.P, p_lo + p.Pg);
+    const int w_lo = outlier ? 0 : p_lo / U, w_hi = outlier ? p.Q : (p_hi + U - 1) / U;
+    // few windows (a narrow codebook group, the outlier vectors): segments of SEG lanes take a row each, 64 / SEG rows a round
+    const int nw = w_hi - w_lo;
+    const int SEG = nw > 32 ? 64 : nw > 16 ? 32 : nw > 8 ? 16 : 8;
+    const int lane_w = lane & (SEG - 1), row_step = (64 / SEG) * LW;
+    const int o_lane_off = (lane / SEG) * LW;                             // this lane's row within the round's rows
+    const int ipr = max((nw + 63) >> 6, 1);
+    const int k_a = outlier ? p.k_out : second ? p.k_res : p.k;
+    const __half *cb_a = outlier ? p.cb_out : second ? p.cb_res + (long long)g * p.k_res * V : p.cb + (long long)g * p.k * V;
+    const __amdgpu_buffer_rsrc_t r_a = outlier ? r_o : second ? r_r : r_i;
+    const unsigned stride_a = (unsigned)(outlier ? p.stride_out : second ? p.stride_res : p.stride);
+    // index words of a round: a window of U vectors (ND dwords), or the two dwords that hold an outlier index
+    auto offset_of = [&](int o, int it) {
+      const int w = w_lo + lane_w + it * 64;
+      o += o_lane_off;
+      if (!(o < row1 && w < w_hi)) return 0xFFFFFFF0u;
+      return (unsigned)o * stride_a + (outlier ? (((unsigned)w * (unsigned)p.bits_out) >> 5) * 4u : (unsigned)w * (ND * 4u));
+    };
+    auto load_round = [&](unsigned (&w)[ND < 2 ? 2 : ND], int o, int it) {
+      const unsigned off = offset_of(o, it);
+      if (outlier) {
+        const uint2v a = __builtin_amdgcn_raw_buffer_load_b64(r_a, off, 0, 0);
+        w[0] = a.x; w[1] = a.y;
+      } else {
+        unsigned v[ND];
+        load_window<ND>(v, r_a, off);
+#pragma unroll
+        for (int d = 0; d < ND; ++d) w[d] = v[d];
+      }
+    };
+    int o = row0 + wv, it = 0;
+    unsigned wm[ND < 2 ? 2 : ND];
+    load_round(wm, o, 0);                                                 // the first round's words go out ahead of the staging
+
+    __syncthreads();                                                      // every wave has left the table and rows of the pass before
+    // ---- the pass's table into LDS: padded entries, an entry per thread and round (outlier entries: 8 bytes as they are)
+    if (outlier) {
+      for (int en = threadIdx.x; en < k_a; en += LW * 64)
+        *reinterpret_cast<uint2v *>(lds + (unsigned)en * 8u) = *reinterpret_cast<const uint2v *>(cb_a + (long long)en * 4);
+    } else {
+#pragma unroll 4
+      for (int en = threadIdx.x; en < k_a; en += LW * 64) {
+        const unsigned *src = reinterpret_cast<const unsigned *>(cb_a) + (long long)en * VD;
+        unsigned v[ED];
+#pragma unroll
+        for (int d = 0; d < ED; ++d) v[d] = 0u;
+        if constexpr (VD % 4 == 0) {
+#pragma unroll
+          for (int d = 0; d < VD; d += 4) { const uint4v a = *reinterpret_cast<const uint4v *>(src + d); v[d] = a.x; v[d + 1] = a.y; v[d + 2] = a.z; v[d + 3] = a.w; }
+        } else if constexpr (VD % 2 == 0) {
+#pragma unroll
+          for (int d = 0; d < VD; d += 2) { const uint2v a = *reinterpret_cast<const uint2v *>(src + d); v[d] = a.x; v[d + 1] = a.y; }
+        } else {
+#pragma unroll
+          for (int d = 0; d < VD; ++d) v[d] = src[d];
+        }
+        unsigned *dst = reinterpret_cast<unsigned *>(lds) + en * ED;
+        if constexpr (ED >= 4) {
+#pragma unroll
+          for (int d = 0; d < ED; d += 4) *reinterpret_cast<uint4v *>(dst + d) = uint4v{v[d], v[d + 1], v[d + 2], v[d + 3]};
+        } else {
+#pragma unroll
+          for (int d = 0; d < ED; ++d) dst[d] = v[d];
+        }
+      }
+    }
+    // ---- the activations of the pass's windows: a new group's, with zeros outside the group (and past the row)
+    if (!outlier && !second) {
+#pragma unroll
+      for (int t = 0; t < B; ++t) {
+        __half *xs = reinterpret_cast<__half *>(lds + plan.off_x + t * plan.x_pitch);
+        for (int j = w_lo * (U * V) + (int)threadIdx.x; j < w_hi * (U * V); j += LW * 64) {
+          const int c = p.n_out + j, pv = j / V;
+          xs[j] = pv >= p_lo && pv < p_hi && c < p.in_features ? x_at(t, c) : __float2half_rn(0.0f);
+        }
+      }
+    }
+    if (pass == 0 && threadIdx.x < B) {                                   // the waves' parts in a fixed order
+      float sum = 0.0f;
+      for (int w = 0; w < LW; ++w) sum += xpart[threadIdx.x * LW + w];
+      xsum[threadIdx.x] = sum;
+    }
+    __syncthreads();
+
+    // ---- the wave's rows, 64 windows a round, the next round's words loaded before the current ones are used
+    float acc[B];
+#pragma unroll
+    for (int t = 0; t < B; ++t) acc[t] = 0.0f;
+    while (o < row1) {
+      int on = o, itn = it + 1;
+      if (itn == ipr) { itn = 0; on = o + row_step; }
+      unsigned nm[ND < 2 ? 2 : ND];
+      load_round(nm, on, itn);
+      const int wdx = w_lo + lane_w + it * 64;
+      if (wdx < w_hi && o + o_lane_off < row1) {
+        if (outlier) {
+          const unsigned sh = ((unsigned)wdx * (unsigned)p.bits_out) & 31u;
+          unsigned i = wm[0] >> sh;
+          if (sh + (unsigned)p.bits_out > 32u) i |= wm[1] << (32u - sh);
+          i = min(i & ((1u << p.bits_out) - 1u), (unsigned)k_a - 1u);
+          const uint2v e = *reinterpret_cast<const uint2v *>(lds + i * 8u);
+#pragma unroll
+          for (int t = 0; t < B; ++t) {
+            const uint2v xv = *reinterpret_cast<const uint2v *>(lds + plan.off_xo + t * plan.xo_pitch + (unsigned)wdx * 8u);
+            acc[t] = dot2(e.x, xv.x, acc[t]);
+            acc[t] = dot2(e.y, xv.y, acc[t]);
+          }
+        } else {
+          const unsigned xbase = plan.off_x + (unsigned)wdx * (U * V * 2u);
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            const unsigned i = min(window_field<BITS, ND < 2 ? 2 : ND>(wm, u), (unsigned)k_a - 1u);
+            unsigned e[ED];
+#pragma unroll
+            for (int d = 0; d < ED; ++d) e[d] = reinterpret_cast<const unsigned *>(lds)[i * ED + d];
+#pragma unroll
+            for (int t = 0; t < B; ++t) {
+#pragma unroll
+              for (int d = 0; d < VD; ++d) {
+                const unsigned xv = *reinterpret_cast<const unsigned *>(lds + xbase + t * plan.x_pitch + (unsigned)(u * V + 2 * d) * 2u);
+                acc[t] = dot2(e[d], xv, acc[t]);
+              }
+            }
+          }
+        }
+      }
+      if (itn == 0) {                                                     // the row's part of this pass is complete
+#pragma unroll
+        for (int t = 0; t < B; ++t) {
+          float r = acc[t];
+          acc[t] = 0.0f;
+#pragma unroll
+          for (int off = 32; off > 0; off >>= 1)
+            if (off < SEG) r += __shfl_xor(r, off, 64);                   // (the same for the whole wave)
+          if (lane_w == 0 && o + o_lane_off < row1) {                     // (a row stays with its wave in every pass; barriers lie between)
+            float *yp = ypart + (o + o_lane_off - row0) * B + t;
+            *yp = pass ? __fadd_rn(*yp, r) : r;
+          }
+        }
+      }
+#pragma unroll
+      for (int d = 0; d < (ND < 2 ? 2 : ND); ++d) wm[d] = nm[d];
+      o = on; it = itn;
+    }
+  }
+  // ---- scale, bias, store: a lane per row
+  __syncthreads();
+  for (int r = threadIdx.x; r < row1 - row0; r += LW * 64) {
+    const int o = row0 + r;
+    const float s = p.scale ? __half2float(p.scale[o]) : 1.0f, b = p.bias ? __half2float(p.bias[o]) : 0.0f;
+#pragma unroll
+    for (int t = 0; t < B; ++t) y[(long long)t * ldy + o] = __float2half_rn(__fmaf_rn(s, ypart[r * B + t], b * xsum[t]));
+  }
+}
+
+bool make_pass_plan(const Params &p, int batch, int u, int eh, PassPlan *plan) {
+  auto up16 = [](size_t v) { return (v + 15) / 16 * 16; };
+  size_t table = up16((size_t)p.k * eh * 2);
+  if (up16((size_t)p.k_res * eh * 2) > table) table = up16((size_t)p.k_res * eh * 2);
+  if (p.Q && up16((size_t)p.k_out * 8) > table) table = up16((size_t)p.k_out * 8);
+  const size_t windows = ((size_t)p.P + u - 1) / u;
+  const size_t pitch = up16(windows * u * p.v * 2), xo_pitch = up16((size_t)p.n_out * 2);
+  const int wgs = cu_count();
+  plan->rows_per_wg = (p.out_features + wgs - 1) / wgs;
+  if (plan->rows_per_wg < LW) plan->rows_per_wg = LW;
+  const size_t sums = up16(4 * 4 * (1 + LW));
+  const size_t total = table + (pitch + xo_pitch) * batch + sums + (size_t)plan->rows_per_wg * batch * 4;
+  if (total > 160 * 1024) return false;
+  if ((long long)p.out_features * p.stride >= (1LL << 32) || (long long)p.out_features * p.stride_res >= (1LL << 32) ||
+      (long long)p.out_features * p.stride_out >= (1LL << 32)) return false;
+  plan->off_x = (unsigned)table; plan->off_xo = (unsigned)(table + pitch * batch);
+  plan->off_xsum = (unsigned)(table + (pitch + xo_pitch) * batch); plan->off_ypart = plan->off_xsum + (unsigned)sums;
+  plan->bytes = (unsigned)total; plan->x_pitch = (unsigned)pitch; plan->xo_pitch = (unsigned)xo_pitch;
+  return true;
+}
+
+// layers the pass kernel takes: a compiled (V, BITS) pair, a residual stream of the same width, outlier vectors of four
+bool pass_pair(const Params &p) {
+  if ((p.k_res && p.bits_res != p.bits) || (p.Q && (p.v_out != 4 || p.bits_out > 16))) return false;
+  return (p.v == 2 && p.bits == 4) || ((p.v == 4 || p.v == 6 || p.v == 8) && p.bits == 8) ||
+         ((p.v == 4 || p.v == 6 || p.v == 8 || p.v == 12) && p.bits == 12);
+}
+
+template <int V, int BITS, int B>
+int launch_passes(const Params &p, const __half *x, long long ldx, __half *y, long long ldy, hipStream_t s) {
+  PassPlan plan;
+  if (!make_pass_plan(p, B, win_vectors(BITS), entry_halfs(V), &plan)) return VQ_ERR_UNSUPPORTED;
+  auto kernel = gemv_lds_passes_kernel<V, BITS, B>;
+  VQ_ALLOW_FULL_LDS(kernel);
+  const unsigned grid = (unsigned)((p.out_features + plan.rows_per_wg - 1) / plan.rows_per_wg);
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(LW * 64), plan.bytes, s, p, plan, x, ldx, y, ldy);
+  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+int launch_passes_any(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
+  if (!pass_pair(p) || (batch != 1 && batch != 2 && batch != 4)) return VQ_ERR_UNSUPPORTED;
+#define VQ_PAIR(V, BITS)                                                                                              \
+  if (p.v == V && p.bits == BITS)                                                                                     \
+    return batch == 1 ? launch_passes<V, BITS, 1>(p, x, ldx, y, ldy, s) : batch == 2 ? launch_passes<V, BITS, 2>(p, x, ldx, y, ldy, s) \
+                                                                                     : launch_passes<V, BITS, 4>(p, x, ldx, y, ldy, s);
+  VQ_PAIR(2, 4) VQ_PAIR(4, 8) VQ_PAIR(6, 8) VQ_PAIR(8, 8) VQ_PAIR(4, 12) VQ_PAIR(6, 12) VQ_PAIR(8, 12) VQ_PAIR(12, 12)
+#undef VQ_PAIR
+  return VQ_ERR_UNSUPPORTED;
+}
+
 bool make_plan(const Params &p, int batch, LdsPlan *plan) {
   auto up16 = [](size_t v) { return (v + 15) / 16 * 16; };
   const size_t main = up16((size_t)p.k * p.v * 2), res = up16((size_t)p.k_res * p.v * 2), out = up16((size_t)p.k_out * p.v_out * 2);
@@ -414,26 +678,37 @@ int launch_b(const Params &p, const LdsPlan &plan, const __half *x, long long ld
 // Vectors along the rows, one codebook group, tables and `batch` activation rows within LDS.
 bool gemv_lds_applicable(const Params &p, int batch) {
   LdsPlan plan;
-  if (p.orientation != 0 || p.n_groups != 1) return false;
-  if (make_plan(p, batch, &plan)) return true;
-  if (!window_pair(p) || (batch != 1 && batch != 2 && batch != 4)) return false;
-  if (make_window_plan(p, batch, win_vectors(p.bits), entry_halfs(p.v), false, &plan)) return true;
-  return p.k_res != 0 && two_pass_compiled(p.v, p.bits) && make_window_plan(p, batch, win_vectors(p.bits), entry_halfs(p.v), true, &plan);
+  PassPlan pplan;
+  if (p.orientation != 0) return false;
+  if (p.n_groups == 1) {
+    if (make_plan(p, batch, &plan)) return true;
+    if (window_pair(p) && (batch == 1 || batch == 2 || batch == 4) && make_window_plan(p, batch, win_vectors(p.bits), entry_halfs(p.v), false, &plan))
+      return true;
+  }
+  return pass_pair(p) && (batch == 1 || batch == 2 || batch == 4) && make_pass_plan(p, batch, win_vectors(p.bits), entry_halfs(p.v), &pplan);
 }
 
 // batch in {1, 2, 4}
 int launch_gemv_lds(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
   LdsPlan plan;
-  if (p.orientation != 0 || p.n_groups != 1) return VQ_ERR_UNSUPPORTED;
-  if (batch == 1 || batch == 2 || batch == 4) {           // the compile-time variants first
-    const int rc = launch_window_any(p, x, ldx, batch, y, ldy, s);
-    if (rc != VQ_ERR_UNSUPPORTED) return rc;
+  if (p.orientation != 0) return VQ_ERR_UNSUPPORTED;
+  if (p.n_groups == 1) {
+    if (batch == 1 || batch == 2 || batch == 4) {           // the compile-time variants first
+      const int rc = launch_window_any(p, x, ldx, batch, y, ldy, s);
+      if (rc != VQ_ERR_UNSUPPORTED) return rc;
+    }
+    {                                                       // then one table at a time, where a (V, BITS) pair is compiled
+      const int rc = launch_passes_any(p, x, ldx, batch, y, ldy, s);
+      if (rc != VQ_ERR_UNSUPPORTED) return rc;
+    }
+    if (make_plan(p, batch, &plan)) {
+      if (batch == 1) return launch_b<1>(p, plan, x, ldx, y, ldy, s);
+      if (batch == 2) return launch_b<2>(p, plan, x, ldx, y, ldy, s);
+      if (batch == 4) return launch_b<4>(p, plan, x, ldx, y, ldy, s);
+      return VQ_ERR_UNSUPPORTED;
+    }
   }
-  if (!make_plan(p, batch, &plan)) return VQ_ERR_UNSUPPORTED;
-  if (batch == 1) return launch_b<1>(p, plan, x, ldx, y, ldy, s);
-  if (batch == 2) return launch_b<2>(p, plan, x, ldx, y, ldy, s);
-  if (batch == 4) return launch_b<4>(p, plan, x, ldx, y, ldy, s);
-  return VQ_ERR_UNSUPPORTED;
+  return launch_passes_any(p, x, ldx, batch, y, ldy, s);      // outlier columns, codebook groups, tables that do not fit together
 }
 
 }  // namespace vq
