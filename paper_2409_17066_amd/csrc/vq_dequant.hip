@@ -95,6 +95,7 @@ int launch_dequant_outliers(const Params &p, __half *W, long long ldw, hipStream
 
 int launch_dequant_fast(const Params &p, __half *W, long long ldw, hipStream_t s);
 int launch_dequant_down_fast(const Params &p, __half *W, long long ldw, hipStream_t s);
+int launch_dequant_lds(const Params &p, __half *W, long long ldw, hipStream_t s);
 
 int launch_dequant(const Params &p, __half *W, long long ldw, hipStream_t s) {
   if (p.perm && switches().dequant != 'g') {
@@ -124,6 +125,12 @@ int launch_dequant(const Params &p, __half *W, long long ldw, hipStream_t s) {
   }
   const int rc = p.perm ? VQ_ERR_UNSUPPORTED : launch_dequant_fast(p, W, ldw, s);
   if (rc != VQ_ERR_UNSUPPORTED) return rc;
+  if (!p.perm) {
+    // the other (v, k) settings: main columns with the tables in LDS, the few outlier columns by the generic kernel
+    const int rl = launch_dequant_lds(p, W, ldw, s);
+    if (rl == VQ_OK) return p.Q ? launch_dequant_outliers(p, W, ldw, s) : VQ_OK;
+    if (rl != VQ_ERR_UNSUPPORTED) return rl;
+  }
   const int slots = p.P + p.Q;
   const int blocks_per_row = (slots + 255) / 256;
   const long long blocks = (long long)blocks_per_row * p.out_features;
