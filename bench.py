@@ -436,7 +436,22 @@ def detail(vq, s, np, torch, use_graph, skip):
     moved = W1.numel() * 2 + L1.algorithmic_bytes(1)
     out.append({"op": "vq_dequant", "cfg": 1, "us": round(sec * 1e6, 1), "GB/s": round(moved / sec / 1e9, 1),
                 "frac_hbm_peak": round(moved / sec / 1e9 / HBM_PEAK_GBPS, 4)})
-    del dl1, W1
+    del dl1
+    # ... and of the same shape in the 2.26-bit setting of Table "Quantization parameters" (v = 12, two 4096-entry tables, 4 codebook
+    # groups, 40 outlier columns): one table in LDS at a time
+    L12 = s.make_layer(1, "up", L1.out_features, L1.in_features, 12, 4096, 4096, n_outlier_cols=40, v_out=4, k_out=8192, group_vectors=85)
+    dl12 = vq.DeviceLayer(L12)
+
+    def launch_dq12(i):
+        rc = vq.vq_dequant(dl12.desc, W1.data_ptr(), W1.stride(0), torch.cuda.current_stream().cuda_stream)
+        if rc != 0:
+            raise vq.VQError(rc, "vq_dequant")
+    wall, ev = timed(launch_dq12, 20, 3, use_graph=False)
+    sec = ev / 20
+    moved = W1.numel() * 2 + L12.algorithmic_bytes(1)
+    out.append({"op": "vq_dequant", "cfg": "1 shape with v12 k4096 + residual k4096, 4 codebook groups, 40 outlier columns", "us": round(sec * 1e6, 1),
+                "GB/s": round(moved / sec / 1e9, 1), "frac_hbm_peak": round(moved / sec / 1e9 / HBM_PEAK_GBPS, 4)})
+    del dl12, L12, W1
     # encode side: nearest-centroid assignment of the headline layer's 11008 x 683 vectors against its 4096 x 6 table
     Wenc = torch.from_numpy(s.to_fp16(s.normal(77, L1.out_features * L1.in_features, 0.02)).reshape(L1.out_features, L1.in_features)).cuda()
     Cenc = torch.from_numpy(L1.codebook).cuda()
