@@ -449,8 +449,9 @@ __global__ __launch_bounds__(LW * 64) void gemv_lds_passes_kernel(Params p, Pass
     // few windows (a narrow codebook group, the outlier vectors): segments of SEG lanes take a row each, 64 / SEG rows a round
     const int nw = w_hi - w_lo;
     const int SEG = nw > 32 ? 64 : nw > 16 ? 32 : nw > 8 ? 16 : 8;
+    // (a wave's segments take consecutive rows, so that a block of few rows keeps few waves busy instead of a segment of each)
     const int lane_w = lane & (SEG - 1), row_step = (64 / SEG) * LW;
-    const int o_lane_off = (lane / SEG) * LW;                             // this lane's row within the round's rows
+    const int o_lane_off = lane / SEG;                                    // this lane's row within the round's rows
     const int ipr = max((nw + 63) >> 6, 1);
     const int k_a = outlier ? p.k_out : second ? p.k_res : p.k;
     const __half *cb_a = outlier ? p.cb_out : second ? p.cb_res + (long long)g * p.k_res * V : p.cb + (long long)g * p.k * V;
@@ -475,7 +476,7 @@ __global__ __launch_bounds__(LW * 64) void gemv_lds_passes_kernel(Params p, Pass
         for (int d = 0; d < ND; ++d) w[d] = v[d];
       }
     };
-    int o = row0 + wv, it = 0;
+    int o = row0 + wv * (64 / SEG), it = 0;
     unsigned wm[ND < 2 ? 2 : ND];
     load_round(wm, o, 0);                                                 // the first round's words go out ahead of the staging
 
@@ -579,7 +580,7 @@ __global__ __launch_bounds__(LW * 64) void gemv_lds_passes_kernel(Params p, Pass
 #pragma unroll
           for (int off = 32; off > 0; off >>= 1)
             if (off < SEG) r += __shfl_xor(r, off, 64);                   // (the same for the whole wave)
-          if (lane_w == 0 && o + o_lane_off < row1) {                     // (a row stays with its wave in every pass; barriers lie between)
+          if (lane_w == 0 && o + o_lane_off < row1) {                     // (a row changes hands between passes; barriers lie between)
             float *yp = ypart + (o + o_lane_off - row0) * B + t;
             *yp = pass ? __fadd_rn(*yp, r) : r;
           }
