@@ -466,3 +466,51 @@ def test_eight_component_layers_random_shapes(gpu_lib, seed):
         torch.cuda.synchronize()
         _check_matmul(yb[:, :out], oracle.gemv(L, x), "v = 8, orientation %d, %d x %d, k %d, %s, batch %d" % (orientation, out, in_features, k, kw, batch))
         assert (yb[:, out:] == 7.0).all()
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_lds_table_kernels_random_shapes(gpu_lib, seed):
+    """The (v, index width) pairs of the LDS-table kernels with random sizes, table sizes, residual tables of the same index
+    width, codebook groups, outlier columns of v = 4 (up to 13 index bits) and permutations: vq_dequant bit for bit (W with a
+    padded, sentinel-filled pitch), vq_gemv on padded buffers (NaN in x's padding, sentinels in y's), vq_gemm with the
+    restore-then-multiply workspace where the layer has one."""
+    import torch
+    rng = np.random.default_rng(97531 + seed)
+    v, bits = [(2, 4), (4, 8), (6, 8), (8, 8), (4, 12), (8, 12), (12, 12), (6, 12)][seed % 8]
+    k = int(rng.integers(2 ** (bits - 1) + 1, 2 ** bits + 1))
+    out = int(rng.integers(1, 6000)) if seed % 3 == 0 else int(rng.integers(1, 700))
+    n_out = 4 * int(rng.integers(0, 12)) if rng.integers(0, 2) else 0
+    in_features = n_out + int(rng.integers(1, 2600))
+    kw = {}
+    if rng.integers(0, 2):
+        kw["k_res"] = int(rng.integers(2 ** (bits - 1) + 1, 2 ** bits + 1))
+    if n_out:
+        kw.update(n_outlier_cols=n_out, v_out=4, k_out=int(rng.choice([8192, 4096, 300, 5000])))
+    P = -(-(in_features - n_out) // v)
+    if rng.integers(0, 2):
+        kw["group_vectors"] = int(rng.integers(max(1, P // 17), P + 1))
+    if rng.integers(0, 3) == 0:
+        kw["permute"] = True
+    what = "v %d, %d-bit, %d x %d, k %d, %s" % (v, bits, out, in_features, k, kw)
+    L = s.make_layer(9300 + seed, "lds_random_%d" % seed, out, in_features, v, k, **kw)
+    dl = gpu_lib.DeviceLayer(L)
+    ldw = in_features + int(rng.choice([0, 2, 5, 8]))
+    W = torch.full((out, ldw), 3.0, dtype=torch.float16, device="cuda")
+    assert gpu_lib.vq_dequant(dl.desc, W.data_ptr(), ldw, torch.cuda.current_stream().cuda_stream) == 0
+    torch.cuda.synchronize()
+    assert np.array_equal(W[:, :in_features].cpu().numpy().view(np.uint16), oracle.dequant(L).view(np.uint16)), what
+    assert (W[:, in_features:] == 3.0).all(), what
+    for batch in (1, 2, 4, int(rng.integers(3, 17))):
+        x = s.make_activations(9300 + seed, L, batch)
+        xb = torch.full((batch, (in_features + 7) // 8 * 8 + 8), float("nan"), dtype=torch.float16, device="cuda")
+        xb[:, :in_features] = torch.from_numpy(x).cuda()
+        yb = torch.full((batch, out + 3), 7.0, dtype=torch.float16, device="cuda")
+        gpu_lib.gemv(dl, xb, out=yb)
+        torch.cuda.synchronize()
+        _check_matmul(yb[:, :out], oracle.gemv(L, x), what + ", batch %d" % batch)
+        assert (yb[:, out:] == 7.0).all()
+    if in_features % 256 == 0:
+        x = s.make_activations(9300 + seed, L, 70)
+        Y = gpu_lib.gemm(dl, torch.from_numpy(x).cuda(), workspace="fast")
+        torch.cuda.synchronize()
+        _check_matmul(Y, oracle.gemm(L, x), what + ", 70 tokens")
