@@ -137,7 +137,8 @@ int vq_gemv(const vq_layer_desc *desc, const void *x, int64_t ldx, int32_t batch
             void *y, int64_t ldy, void *hip_stream);
 
 /* vq_gemv with a workspace on loan (device memory, 256-byte aligned, owned by the caller, contents undefined
- * afterwards).  Only layers with codebook groups (Sec. 3.1) use it: with vq_gemv_workspace_bytes(desc, batch) bytes
+ * afterwards).  Only layers with codebook groups (Sec. 3.1) use it (v = 6 layers on the matrix-core kernel, the other
+ * settings on the kernel that keeps one table in LDS at a time): with vq_gemv_workspace_bytes(desc, batch) bytes
  * every workgroup takes one group, whose tables it loads once, and a share of the rows, writes binary32 sums to the
  * workspace, and a second kernel adds the groups up in ascending order and applies scale and bias -- instead of every
  * workgroup walking all groups and swapping its tables for each.  Layers of orientation 1 with one group use it from

@@ -118,6 +118,8 @@ bool gemv_fast_applicable(const Params &p, const __half *x, long long ldx);
 bool gemv_res8_applicable(const Params &p, const __half *x);
 bool gemv_lds_applicable(const Params &p, int batch);
 int launch_gemv_lds(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
+size_t gemv_lds_slots_workspace_bytes(const Params &p, int batch);
+int launch_gemv_lds_slots(const Params &p, const __half *x, long long ldx, int batch, float *part, float *part_xs, hipStream_t s);
 int launch_gemv_res8(const Params &p, const __half *x, __half *y, hipStream_t s);
 int launch_gemv_fast(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
 
@@ -348,7 +350,9 @@ size_t gemv_workspace_bytes(const Params &p, const __half *x, long long ldx, int
   if (p.orientation == 1)           // vectors down the output dimension: the same workspace layout, filled by that orientation's kernel
     return p.n_groups > 1 && p.n_groups <= 256 && gemv_down_applicable(p, x, ldx)
                ? ((size_t)(p.n_groups + (p.Q ? 1 : 0)) * ((size_t)batch * (size_t)p.out_features + 16) * sizeof(float) + 255) / 256 * 256 : 0;
-  if (forced_kernel() == 'd' || !gemv_fast_applicable(p, x, ldx)) return 0;
+  if (!gemv_fast_applicable(p, x, ldx))       // the LDS-table kernels, when the layer gets that far: a slot per workgroup
+    return gemv_v8_applicable(p, x, ldx) ? 0 : gemv_lds_slots_workspace_bytes(p, batch);
+  if (forced_kernel() == 'd') return 0;
   return gemv_mfma_groups_workspace_bytes(p, batch);
 }
 
@@ -387,6 +391,14 @@ int launch_gemv_ws(const Params &p, const __half *x, long long ldx, int batch, _
     }
     if (rc == VQ_OK) return launch_groups_finish(part, part_xs, slots, batch, p, y, ldy, s);
     if (rc != VQ_ERR_UNSUPPORTED || done != 0) return rc;
+  } else if (need && workspace && workspace_bytes >= need && !gemv_fast_applicable(p, x, ldx)) {
+    if (!switches().groups_loop) {
+      const int slots = p.n_groups;                         // (the first group's workgroups also take the outlier columns)
+      float *part = static_cast<float *>(workspace), *part_xs = part + (size_t)slots * (size_t)batch * (size_t)p.out_features;
+      const int rc = launch_gemv_lds_slots(p, x, ldx, batch, part, part_xs, s);
+      if (rc == VQ_OK) return launch_groups_finish(part, part_xs, slots, batch, p, y, ldy, s);
+      if (rc != VQ_ERR_UNSUPPORTED) return rc;
+    }
   } else if (need && workspace && workspace_bytes >= need && !switches().groups_loop) {
     const int rc = launch_gemv_mfma_groups(p, x, ldx, batch, y, ldy, workspace, s);
     if (rc != VQ_ERR_UNSUPPORTED) return rc;

@@ -397,6 +397,11 @@ struct PassPlan {
   unsigned off_x, off_xo, off_xsum, off_ypart, bytes;     // byte offsets in dynamic LDS (the pass's table at 0)
   unsigned x_pitch, xo_pitch;                             // bytes per staged row of main / outlier columns
   int rows_per_wg;
+  // With a workspace on loan a workgroup takes one "slot" -- a codebook group (its main and residual table; the first group's
+  // workgroups also the outlier columns) -- and a block of rows, and leaves its sums in the workspace for the kernel that adds
+  // the slots up:
+  int n_slots, batch_total;                               // 0: every workgroup walks all passes and writes y
+  float *part, *part_xs;                                  // [n_slots][batch_total][out_features] sums, [n_slots][16] activation sums
 };
 
 template <int V, int BITS, int B>
@@ -409,7 +414,9 @@ __global__ __launch_bounds__(LW * 64) void gemv_lds_passes_kernel(Params p, Pass
   float *xpart = xsum + B;
   float *ypart = reinterpret_cast<float *>(lds + plan.off_ypart);        // row sums of the passes so far [rows_per_wg][B]
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const int row0 = blockIdx.x * plan.rows_per_wg;
+  const bool slots = plan.n_slots != 0;
+  const int slot = slots ? (int)blockIdx.x % plan.n_slots : 0;
+  const int row0 = (slots ? (int)blockIdx.x / plan.n_slots : (int)blockIdx.x) * plan.rows_per_wg;
   const int row1 = min(p.out_features, row0 + plan.rows_per_wg);
   const int windows = (p.P + U - 1) / U;
   const __amdgpu_buffer_rsrc_t r_i = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.idx), 0, (unsigned)((long long)p.out_features * p.stride), 0x00020000);
@@ -423,12 +430,14 @@ __global__ __launch_bounds__(LW * 64) void gemv_lds_passes_kernel(Params p, Pass
     return (unsigned)src < (unsigned)p.in_features ? x[(long long)t * ldx + src] : __float2half_rn(0.0f);
   };
 
-  // ---- once: the sum of every activation row, the activations of the outlier columns
+  // ---- once: the sum of every activation row, the activations of the outlier columns (a workgroup with a slot: the first
+  // slot's over the outlier columns; every slot adds what it restages)
+  const int once_cols = !slots ? p.in_features : slot == 0 ? p.n_out : 0;
 #pragma unroll
   for (int t = 0; t < B; ++t) {
     __half *xo = reinterpret_cast<__half *>(lds + plan.off_xo + t * plan.xo_pitch);
     float part = 0.0f;
-    for (int c = threadIdx.x; c < p.in_features; c += LW * 64) {
+    for (int c = threadIdx.x; c < once_cols; c += LW * 64) {
       const __half v = x_at(t, c);
       if (c < p.n_out) xo[c] = v;
       part += __half2float(v);
@@ -439,7 +448,11 @@ __global__ __launch_bounds__(LW * 64) void gemv_lds_passes_kernel(Params p, Pass
 
   const int tables_per_group = p.k_res ? 2 : 1;
   const int table_passes = p.n_groups * tables_per_group;
-  for (int pass = 0; pass < table_passes + (p.Q ? 1 : 0); ++pass) {
+  const int pass_begin = slots ? slot * tables_per_group : 0;
+  const int my_table_passes = slots ? tables_per_group : table_passes;
+  const int my_passes = my_table_passes + (p.Q && slot == 0 ? 1 : 0);
+  for (int ip = 0; ip < my_passes; ++ip) {
+    const int pass = ip < my_table_passes ? pass_begin + ip : table_passes;
     const bool outlier = pass == table_passes;
     const int g = pass / tables_per_group;
     const bool second = !outlier && pass - g * tables_per_group == 1;
@@ -517,18 +530,25 @@ __global__ __launch_bounds__(LW * 64) void gemv_lds_passes_kernel(Params p, Pass
 #pragma unroll
       for (int t = 0; t < B; ++t) {
         __half *xs = reinterpret_cast<__half *>(lds + plan.off_x + t * plan.x_pitch);
+        float part = 0.0f;
         for (int j = w_lo * (U * V) + (int)threadIdx.x; j < w_hi * (U * V); j += LW * 64) {
           const int c = p.n_out + j, pv = j / V;
-          xs[j] = pv >= p_lo && pv < p_hi && c < p.in_features ? x_at(t, c) : __float2half_rn(0.0f);
+          const __half v = pv >= p_lo && pv < p_hi && c < p.in_features ? x_at(t, c) : __float2half_rn(0.0f);
+          xs[j] = v;
+          part += __half2float(v);
+        }
+        if (slots) {                                                      // the group's share of sum(x), on top of the outlier columns'
+          part = wave_sum(part);
+          if (lane == 0) xpart[t * LW + wv] += part;
         }
       }
     }
-    if (pass == 0 && threadIdx.x < B) {                                   // the waves' parts in a fixed order
+    __syncthreads();
+    if (pass == pass_begin && threadIdx.x < B) {                          // the waves' parts in a fixed order (read again after the last barrier)
       float sum = 0.0f;
       for (int w = 0; w < LW; ++w) sum += xpart[threadIdx.x * LW + w];
       xsum[threadIdx.x] = sum;
     }
-    __syncthreads();
 
     // ---- the wave's rows, 64 windows a round, the next round's words loaded before the current ones are used
     float acc[B];
@@ -582,7 +602,7 @@ __global__ __launch_bounds__(LW * 64) void gemv_lds_passes_kernel(Params p, Pass
             if (off < SEG) r += __shfl_xor(r, off, 64);                   // (the same for the whole wave)
           if (lane_w == 0 && o + o_lane_off < row1) {                     // (a row changes hands between passes; barriers lie between)
             float *yp = ypart + (o + o_lane_off - row0) * B + t;
-            *yp = pass ? __fadd_rn(*yp, r) : r;
+            *yp = pass != pass_begin ? __fadd_rn(*yp, r) : r;
           }
         }
       }
@@ -593,6 +613,13 @@ __global__ __launch_bounds__(LW * 64) void gemv_lds_passes_kernel(Params p, Pass
   }
   // ---- scale, bias, store: a lane per row
   __syncthreads();
+  if (slots) {
+    for (int r = threadIdx.x; r < row1 - row0; r += LW * 64)
+#pragma unroll
+      for (int t = 0; t < B; ++t) plan.part[((long long)slot * plan.batch_total + t) * p.out_features + row0 + r] = ypart[r * B + t];
+    if (row0 == 0 && threadIdx.x < B) plan.part_xs[slot * 16 + threadIdx.x] = xsum[threadIdx.x];
+    return;
+  }
   for (int r = threadIdx.x; r < row1 - row0; r += LW * 64) {
     const int o = row0 + r;
     const float s = p.scale ? __half2float(p.scale[o]) : 1.0f, b = p.bias ? __half2float(p.bias[o]) : 0.0f;
@@ -601,16 +628,17 @@ __global__ __launch_bounds__(LW * 64) void gemv_lds_passes_kernel(Params p, Pass
   }
 }
 
-bool make_pass_plan(const Params &p, int batch, int u, int eh, PassPlan *plan) {
+bool make_pass_plan(const Params &p, int batch, int u, int eh, PassPlan *plan, int n_slots = 0) {
   auto up16 = [](size_t v) { return (v + 15) / 16 * 16; };
   size_t table = up16((size_t)p.k * eh * 2);
   if (up16((size_t)p.k_res * eh * 2) > table) table = up16((size_t)p.k_res * eh * 2);
   if (p.Q && up16((size_t)p.k_out * 8) > table) table = up16((size_t)p.k_out * 8);
   const size_t windows = ((size_t)p.P + u - 1) / u;
   const size_t pitch = up16(windows * u * p.v * 2), xo_pitch = up16((size_t)p.n_out * 2);
-  const int wgs = cu_count();
+  const int wgs = n_slots ? (cu_count() / n_slots > 0 ? cu_count() / n_slots : 1) : cu_count();     // workgroups per slot
   plan->rows_per_wg = (p.out_features + wgs - 1) / wgs;
   if (plan->rows_per_wg < LW) plan->rows_per_wg = LW;
+  plan->n_slots = n_slots; plan->batch_total = 0; plan->part = nullptr; plan->part_xs = nullptr;
   const size_t sums = up16(4 * 4 * (1 + LW));
   const size_t total = table + (pitch + xo_pitch) * batch + sums + (size_t)plan->rows_per_wg * batch * 4;
   if (total > 160 * 1024) return false;
@@ -638,6 +666,31 @@ int launch_passes(const Params &p, const __half *x, long long ldx, __half *y, lo
   const unsigned grid = (unsigned)((p.out_features + plan.rows_per_wg - 1) / plan.rows_per_wg);
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(LW * 64), plan.bytes, s, p, plan, x, ldx, y, ldy);
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+template <int V, int BITS, int B>
+int launch_slots(const Params &p, const __half *x, long long ldx, int n_slots, int batch_total, float *part, float *part_xs, hipStream_t s) {
+  PassPlan plan;
+  if (!make_pass_plan(p, B, win_vectors(BITS), entry_halfs(V), &plan, n_slots)) return VQ_ERR_UNSUPPORTED;
+  plan.batch_total = batch_total; plan.part = part; plan.part_xs = part_xs;
+  auto kernel = gemv_lds_passes_kernel<V, BITS, B>;
+  VQ_ALLOW_FULL_LDS(kernel);
+  const unsigned grid = (unsigned)((p.out_features + plan.rows_per_wg - 1) / plan.rows_per_wg) * (unsigned)n_slots;
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(LW * 64), plan.bytes, s, p, plan, x, ldx, static_cast<__half *>(nullptr), 0LL);
+  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+int launch_slots_any(const Params &p, const __half *x, long long ldx, int batch, int n_slots, int batch_total, float *part, float *part_xs,
+                     hipStream_t s) {
+  if (!pass_pair(p) || (batch != 1 && batch != 2 && batch != 4)) return VQ_ERR_UNSUPPORTED;
+#define VQ_PAIR(V, BITS)                                                                                                     \
+  if (p.v == V && p.bits == BITS)                                                                                            \
+    return batch == 1   ? launch_slots<V, BITS, 1>(p, x, ldx, n_slots, batch_total, part, part_xs, s)                         \
+           : batch == 2 ? launch_slots<V, BITS, 2>(p, x, ldx, n_slots, batch_total, part, part_xs, s)                         \
+                        : launch_slots<V, BITS, 4>(p, x, ldx, n_slots, batch_total, part, part_xs, s);
+  VQ_PAIR(2, 4) VQ_PAIR(4, 8) VQ_PAIR(6, 8) VQ_PAIR(8, 8) VQ_PAIR(4, 12) VQ_PAIR(6, 12) VQ_PAIR(8, 12) VQ_PAIR(12, 12)
+#undef VQ_PAIR
+  return VQ_ERR_UNSUPPORTED;
 }
 
 int launch_passes_any(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
@@ -710,6 +763,31 @@ int launch_gemv_lds(const Params &p, const __half *x, long long ldx, int batch, 
     }
   }
   return launch_passes_any(p, x, ldx, batch, y, ldy, s);      // outlier columns, codebook groups, tables that do not fit together
+}
+
+// Layers that the pass kernel takes and that have at least two codebook groups: with a workspace of
+// slots x (batch x out_features + 16) binary32 sums every workgroup takes one slot; 0 when that does not apply.
+size_t gemv_lds_slots_workspace_bytes(const Params &p, int batch) {
+  PassPlan plan;
+  const int n_slots = p.n_groups;
+  if (p.orientation != 0 || n_slots < 2 || n_slots > 64 || !pass_pair(p)) return 0;
+  if (!make_pass_plan(p, 1, win_vectors(p.bits), entry_halfs(p.v), &plan, n_slots)) return 0;
+  return ((size_t)n_slots * ((size_t)batch * (size_t)p.out_features + 16) * sizeof(float) + 255) / 256 * 256;
+}
+
+// The slots' sums into part [slots][batch][out_features] and part_xs [slots][16]; the caller adds them up.
+int launch_gemv_lds_slots(const Params &p, const __half *x, long long ldx, int batch, float *part, float *part_xs, hipStream_t s) {
+  const int n_slots = p.n_groups;
+  int done = 0, g_max = 4;
+  while (done < batch) {
+    int g = batch - done >= 4 ? 4 : batch - done >= 2 ? 2 : 1;
+    if (g > g_max) g = g_max;
+    const int rc = launch_slots_any(p, x + done * ldx, ldx, g, n_slots, batch, part + (size_t)done * p.out_features, part_xs + done, s);
+    if (rc == VQ_ERR_UNSUPPORTED && g > 1) { g_max = g / 2; continue; }
+    if (rc != VQ_OK) return done ? VQ_ERR_HIP : rc;
+    done += g;
+  }
+  return VQ_OK;
 }
 
 }  // namespace vq

@@ -107,7 +107,7 @@ SMALL = {
     # 8192 entries (13 index bits), a permutation; one table in LDS per pass
     "lds_v12_groups_res_outlier": dict(out_features=300, in_features=2000, v=12, k=4096, k_res=4096, n_outlier_cols=20, v_out=4,
                                        k_out=8192, group_vectors=50),
-    "lds_v12_groups_perm": dict(out_features=5000, in_features=1500, v=12, k=1000, k_res=300, group_vectors=40, permute=True),
+    "lds_v12_groups_perm": dict(out_features=5000, in_features=1500, v=12, k=4000, k_res=3000, group_vectors=40, permute=True),
     "lds_v4_k256_groups": dict(out_features=517, in_features=1030, v=4, k=256, k_res=256, group_vectors=100),
     "lds_v6_outlier13": dict(out_features=150, in_features=1208, v=6, k=4096, n_outlier_cols=24, v_out=4, k_out=8192),
     "lds_v12_outlier_only": dict(out_features=130, in_features=1500, v=12, k=4096, n_outlier_cols=16, v_out=4, k_out=4096, with_scale=False),

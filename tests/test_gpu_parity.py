@@ -266,6 +266,33 @@ def test_gemv_groups_with_workspace(gpu_lib, monkeypatch, name, batch):
     _check_matmul(plain, oracle.gemv(L, x_np), "%s batch %d" % (name, batch))
 
 
+LDS_SLOTS = ["lds_v12_groups_res_outlier", "lds_v12_groups_perm", "lds_v4_k256_groups"]
+
+
+@pytest.mark.parametrize("name", LDS_SLOTS)
+@pytest.mark.parametrize("batch", [1, 3, 4, 7, 16])
+def test_gemv_lds_table_slots_with_workspace(gpu_lib, name, batch):
+    """The layers of the LDS-table pass kernel with two codebook groups or more when the caller lends a workspace: a group per
+    workgroup (the first group's also take the outlier columns), then the sum over the groups.  Workspace filled with NaN
+    patterns beforehand, guarded behind; too small a workspace is the plain route."""
+    import torch
+    L = small_layer(name)
+    dl = gpu_lib.DeviceLayer(L)
+    need = gpu_lib.vq_gemv_workspace_bytes(dl.desc, batch)
+    assert need >= L.n_groups * batch * L.out_features * 4
+    x_np = s.make_activations(300, L, batch)
+    x = torch.from_numpy(x_np).cuda()
+    ws = torch.full((need + 256,), 0xFF, dtype=torch.uint8, device="cuda")
+    y = gpu_lib.gemv(dl, x, workspace=ws[:need])
+    torch.cuda.synchronize()
+    _check_matmul(y, oracle.gemv(L, x_np), "%s batch %d with workspace" % (name, batch))
+    assert (ws[need:] == 0xFF).all()
+    small = gpu_lib.gemv(dl, x, workspace=ws[:need - 256])
+    plain = gpu_lib.gemv(dl, x)
+    torch.cuda.synchronize()
+    assert torch.equal(small, plain)
+
+
 PERMUTED = [n for n in SMALL if n.startswith("perm_")]
 
 
@@ -505,10 +532,13 @@ def test_lds_table_kernels_random_shapes(gpu_lib, seed):
         xb = torch.full((batch, (in_features + 7) // 8 * 8 + 8), float("nan"), dtype=torch.float16, device="cuda")
         xb[:, :in_features] = torch.from_numpy(x).cuda()
         yb = torch.full((batch, out + 3), 7.0, dtype=torch.float16, device="cuda")
-        gpu_lib.gemv(dl, xb, out=yb)
-        torch.cuda.synchronize()
-        _check_matmul(yb[:, :out], oracle.gemv(L, x), what + ", batch %d" % batch)
-        assert (yb[:, out:] == 7.0).all()
+        ref = oracle.gemv(L, x)
+        for workspace in (None, "fast"):     # (with a workspace: a codebook group or the outlier columns per workgroup, then a sum)
+            yb.fill_(7.0)
+            gpu_lib.gemv(dl, xb, out=yb, workspace=workspace)
+            torch.cuda.synchronize()
+            _check_matmul(yb[:, :out], ref, what + ", batch %d, workspace %s" % (batch, workspace))
+            assert (yb[:, out:] == 7.0).all()
     if in_features % 256 == 0:
         x = s.make_activations(9300 + seed, L, 70)
         Y = gpu_lib.gemm(dl, torch.from_numpy(x).cuda(), workspace="fast")
