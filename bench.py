@@ -507,6 +507,11 @@ def detail(vq, s, np, torch, use_graph, skip):
         alg = Lo.algorithmic_bytes(1)
         out.append({"op": "vq_gemv", "cfg": "1 shape with " + label, "batch": 1, "us": round(sec * 1e6, 3), "GB/s": round(alg / sec / 1e9, 1),
                     "frac_hbm_peak": round(alg / sec / 1e9 / HBM_PEAK_GBPS, 4)})
+        if kw.get("group_vectors"):           # with a workspace: a codebook group per workgroup, then the sum over the groups
+            r = bench_gemv(vq, Lo, s.make_activations(1, Lo, 1), steps, warmup, use_graph, workspace=True)
+            sec = r["event_s"] / steps
+            out.append({"op": "vq_gemv_with_workspace", "cfg": "1 shape with " + label, "batch": 1, "us": round(sec * 1e6, 3),
+                        "GB/s": round(alg / sec / 1e9, 1), "frac_hbm_peak": round(alg / sec / 1e9 / HBM_PEAK_GBPS, 4)})
         del Lo
     # the headline shape stored in the paper's own orientation (vectors down the output dimension)
     Ld = s.make_layer(1, "up", L1.out_features, L1.in_features, 6, 4096, orientation=1)
