@@ -12,7 +12,7 @@ except ImportError:                      # run as a script
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvq.so")
-SOURCES = ["vq_api.hip", "vq_dequant.hip", "vq_dequant_fast.hip", "vq_gemv.hip", "vq_gemv_fast.hip", "vq_gemv_res8.hip", "vq_gemv_mfma.hip", "vq_gemm.hip", "vq_gemm_fused.hip", "vq_assign.hip", "vq_gemv_down.hip", "vq_gemv_down_mfma.hip", "vq_gemv_v8.hip", "vq_colperm.hip", "vq_quantize.hip", "vq_gemm_v6.hip", "vq_gemv_lds.hip", "vq_dequant_lds.hip"]
+SOURCES = ["vq_api.hip", "vq_dequant.hip", "vq_dequant_fast.hip", "vq_gemv.hip", "vq_gemv_fast.hip", "vq_gemv_res8.hip", "vq_gemv_mfma.hip", "vq_gemm.hip", "vq_gemm_fused.hip", "vq_assign.hip", "vq_gemv_down.hip", "vq_gemv_down_mfma.hip", "vq_gemv_v8.hip", "vq_colperm.hip", "vq_quantize.hip", "vq_gemm_v6.hip", "vq_gemv_lds.hip", "vq_dequant_lds.hip", "vq_gemv_down_lds.hip"]
 # packed-FP32 VALU forms are switched off for every device compile (they are not trusted on the test machines)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument"]

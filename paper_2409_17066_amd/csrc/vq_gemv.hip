@@ -119,6 +119,8 @@ bool gemv_res8_applicable(const Params &p, const __half *x);
 bool gemv_lds_applicable(const Params &p, int batch);
 int launch_gemv_lds(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
 size_t gemv_lds_slots_workspace_bytes(const Params &p, int batch);
+bool gemv_down_lds_applicable(const Params &p, int batch);
+int launch_gemv_down_lds(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
 int launch_gemv_lds_slots(const Params &p, const __half *x, long long ldx, int batch, float *part, float *part_xs, hipStream_t s);
 int launch_gemv_res8(const Params &p, const __half *x, __half *y, hipStream_t s);
 int launch_gemv_fast(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
@@ -175,12 +177,13 @@ bool gemv_has_fast_kernel(const Params &p, const __half *x, long long ldx) {
 // Layers without a kernel of their own whose tables fit LDS (vq_gemv_lds.hip): batch rows in launches of 4, 2 or 1, fewer
 // when that many activation rows do not fit beside the tables.  VQ_ERR_UNSUPPORTED when the kernel does not take the layer.
 static int gemv_through_lds_tables(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
-  if (force_generic() || !gemv_lds_applicable(p, 1)) return VQ_ERR_UNSUPPORTED;
+  const bool down = p.orientation == 1;
+  if (force_generic() || !(down ? gemv_down_lds_applicable(p, 1) : gemv_lds_applicable(p, 1))) return VQ_ERR_UNSUPPORTED;
   int done = 0, g_max = 4, rc = VQ_OK;
   while (done < batch) {
     int g = batch - done >= 4 ? 4 : batch - done >= 2 ? 2 : 1;
     if (g > g_max) g = g_max;
-    rc = launch_gemv_lds(p, x + done * ldx, ldx, g, y + done * ldy, ldy, s);
+    rc = down ? launch_gemv_down_lds(p, x + done * ldx, ldx, g, y + done * ldy, ldy, s) : launch_gemv_lds(p, x + done * ldx, ldx, g, y + done * ldy, ldy, s);
     if (rc == VQ_ERR_UNSUPPORTED && g > 1) { g_max = g / 2; continue; }
     if (rc != VQ_OK) return rc;
     done += g;
@@ -260,6 +263,10 @@ int launch_gemv(const Params &p, const __half *x, long long ldx, int batch, __ha
         if (rc == VQ_OK) done += g;
       }
       if (rc != VQ_ERR_UNSUPPORTED || done != 0) return rc;
+    }
+    {
+      const int rc = gemv_through_lds_tables(p, x, ldx, batch, y, ldy, s);
+      if (rc != VQ_ERR_UNSUPPORTED) return rc;
     }
     hipLaunchKernelGGL(gemv_down_kernel, dim3((unsigned)((p.S + 3) / 4)), dim3(256), 0, s, p, x, ldx, batch, y, ldy);
     return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;

@@ -111,6 +111,15 @@ SMALL = {
     "lds_v4_k256_groups": dict(out_features=517, in_features=1030, v=4, k=256, k_res=256, group_vectors=100),
     "lds_v6_outlier13": dict(out_features=150, in_features=1208, v=6, k=4096, n_outlier_cols=24, v_out=4, k_out=8192),
     "lds_v12_outlier_only": dict(out_features=130, in_features=1500, v=12, k=4096, n_outlier_cols=16, v_out=4, k_out=4096, with_scale=False),
+    # ... and the same settings stored with vectors down the output dimension (Sec. 3.1): streams of v rows, a ragged last
+    # stream, outlier streams of 4 rows (also under v = 6 streams), groups of columns, a permutation
+    "down_lds_v12_two_tables": dict(out_features=1000, in_features=900, v=12, k=4096, k_res=4096, orientation=1),
+    "down_lds_v12_groups_outlier": dict(out_features=530, in_features=1200, v=12, k=4000, k_res=3000, n_outlier_cols=12, v_out=4, k_out=8192,
+                                        group_vectors=300, orientation=1),
+    "down_lds_v4_k256_perm": dict(out_features=203, in_features=2000, v=4, k=256, k_res=256, orientation=1, permute=True),
+    "down_lds_v6_outlier13": dict(out_features=151, in_features=700, v=6, k=4096, n_outlier_cols=21, v_out=4, k_out=8192, orientation=1),
+    "down_lds_v2_k16": dict(out_features=77, in_features=3000, v=2, k=16, orientation=1, with_bias=False),
+    "down_lds_v8_many_streams": dict(out_features=30011, in_features=300, v=8, k=4096, k_res=3000, orientation=1),
     # vq_gemm's on-the-fly kernel for v = 6 (tables in LDS; in_features a multiple of 256, no outlier columns, one group):
     # no residual, 8-bit and 12-bit residual streams, short tables, a ragged last channel block
     "v6_gemm_plain": dict(out_features=300, in_features=768, v=6, k=4096),
