@@ -96,6 +96,7 @@ int launch_dequant_outliers(const Params &p, __half *W, long long ldw, hipStream
 int launch_dequant_fast(const Params &p, __half *W, long long ldw, hipStream_t s);
 int launch_dequant_down_fast(const Params &p, __half *W, long long ldw, hipStream_t s);
 int launch_dequant_lds(const Params &p, __half *W, long long ldw, hipStream_t s);
+int launch_dequant_down_lds(const Params &p, __half *W, long long ldw, hipStream_t s);
 
 int launch_dequant(const Params &p, __half *W, long long ldw, hipStream_t s) {
   if (p.perm && switches().dequant != 'g') {
@@ -111,7 +112,8 @@ int launch_dequant(const Params &p, __half *W, long long ldw, hipStream_t s) {
   if (p.orientation == 1) {
     const int bps_main = (p.P + 255) / 256, bps_out = p.Q ? (p.Q + 255) / 256 : 1;
     long long main_blocks = (long long)bps_main * p.S;
-    const int rc = p.perm ? VQ_ERR_UNSUPPORTED : launch_dequant_down_fast(p, W, ldw, s);          // the main columns, when a fast kernel takes them
+    int rc = p.perm ? VQ_ERR_UNSUPPORTED : launch_dequant_down_fast(p, W, ldw, s);          // the main columns, when a fast kernel takes them
+    if (rc == VQ_ERR_UNSUPPORTED && !p.perm) rc = launch_dequant_down_lds(p, W, ldw, s);      // (the other settings: tables in LDS)
     if (rc == VQ_OK) {
       if (!p.Q) return VQ_OK;
       main_blocks = 0;                                               // the generic kernel below: outlier streams only

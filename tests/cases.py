@@ -119,6 +119,7 @@ SMALL = {
     "down_lds_v4_k256_perm": dict(out_features=203, in_features=2000, v=4, k=256, k_res=256, orientation=1, permute=True),
     "down_lds_v6_outlier13": dict(out_features=151, in_features=700, v=6, k=4096, n_outlier_cols=21, v_out=4, k_out=8192, orientation=1),
     "down_lds_v2_k16": dict(out_features=77, in_features=3000, v=2, k=16, orientation=1, with_bias=False),
+    "down_lds_v12_odd_groups": dict(out_features=100, in_features=1001, v=12, k=4096, k_res=4096, group_vectors=333, orientation=1),
     "down_lds_v8_many_streams": dict(out_features=30011, in_features=300, v=8, k=4096, k_res=3000, orientation=1),
     # vq_gemm's on-the-fly kernel for v = 6 (tables in LDS; in_features a multiple of 256, no outlier columns, one group):
     # no residual, 8-bit and 12-bit residual streams, short tables, a ragged last channel block
