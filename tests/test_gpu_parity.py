@@ -495,10 +495,10 @@ def test_eight_component_layers_random_shapes(gpu_lib, seed):
         assert (yb[:, out:] == 7.0).all()
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(48))
 def test_lds_table_kernels_random_shapes(gpu_lib, seed):
-    """The (v, index width) pairs of the LDS-table kernels with random sizes, table sizes, residual tables of the same index
-    width, codebook groups, outlier columns of v = 4 (up to 13 index bits) and permutations: vq_dequant bit for bit (W with a
+    """The (v, index width) pairs of the LDS-table kernels, in both orientations, with random sizes, table sizes, residual
+    tables of the same index width, codebook groups, outlier columns of v = 4 (up to 13 index bits) and permutations: vq_dequant bit for bit (W with a
     padded, sentinel-filled pitch), vq_gemv on padded buffers (NaN in x's padding, sentinels in y's), vq_gemm with the
     restore-then-multiply workspace where the layer has one."""
     import torch
@@ -506,18 +506,21 @@ def test_lds_table_kernels_random_shapes(gpu_lib, seed):
     v, bits = [(2, 4), (4, 8), (6, 8), (8, 8), (4, 12), (8, 12), (12, 12), (6, 12)][seed % 8]
     k = int(rng.integers(2 ** (bits - 1) + 1, 2 ** bits + 1))
     out = int(rng.integers(1, 6000)) if seed % 3 == 0 else int(rng.integers(1, 700))
-    n_out = 4 * int(rng.integers(0, 12)) if rng.integers(0, 2) else 0
+    orientation = 1 if seed >= 24 else 0               # (the second half: vectors down the output dimension, any number of outlier columns)
+    n_out = (4 if orientation == 0 else 1) * int(rng.integers(0, 12)) if rng.integers(0, 2) else 0
     in_features = n_out + int(rng.integers(1, 2600))
     kw = {}
     if rng.integers(0, 2):
         kw["k_res"] = int(rng.integers(2 ** (bits - 1) + 1, 2 ** bits + 1))
     if n_out:
         kw.update(n_outlier_cols=n_out, v_out=4, k_out=int(rng.choice([8192, 4096, 300, 5000])))
-    P = -(-(in_features - n_out) // v)
+    P = -(-(in_features - n_out) // v) if orientation == 0 else in_features - n_out
     if rng.integers(0, 2):
         kw["group_vectors"] = int(rng.integers(max(1, P // 17), P + 1))
     if rng.integers(0, 3) == 0:
         kw["permute"] = True
+    if orientation:
+        kw["orientation"] = 1
     what = "v %d, %d-bit, %d x %d, k %d, %s" % (v, bits, out, in_features, k, kw)
     L = s.make_layer(9300 + seed, "lds_random_%d" % seed, out, in_features, v, k, **kw)
     dl = gpu_lib.DeviceLayer(L)
