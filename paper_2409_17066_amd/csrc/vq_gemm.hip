@@ -174,6 +174,7 @@ size_t gemm_fast_workspace_bytes(const Params &p, int tokens) {
 }
 
 bool gemm_fused_applicable(const Params &p);
+bool gemv_has_lds_kernel(const Params &p, const __half *x, long long ldx);
 bool gemm_v6_applicable(const Params &p);
 int launch_gemm_v6(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy, hipStream_t s);
 int launch_gemm_fused(const Params &p, const __half *X, long long ldx, int tokens, __half *Y, long long ldy, const __half *Wd,
@@ -233,8 +234,14 @@ int launch_gemm(const Params &p, const __half *X, long long ldx, int tokens, __h
     if (rc != VQ_ERR_UNSUPPORTED) return rc;
   }
   const bool rows_cheap = p.orientation == 0 && p.v == 6;
-  if (forced == 'r' || (forced == '\0' && !gemm_fused_applicable(p) && gemv_has_fast_kernel(p, X, ldx) &&
-                        (rows_cheap ? (!have_ws || tokens <= 96) : (!have_ws && tokens <= 128)))) {
+  // (layers of the LDS-table decode kernels, whose only tile kernel is the generic one -- about 1 ms for any token count up to
+  // 128 on 11008 x 4096 -- and whose decode kernels take four rows a launch: up to 32 tokens, 4 with a workspace; v = 12 with two
+  // tables, 16 tokens: 239 against 987 us, with a workspace 164 us)
+  const bool lds_rows = forced == '\0' && !gemm_fused_applicable(p) && !gemm_v6_applicable(p) && gemv_has_lds_kernel(p, X, ldx) &&
+                        tokens <= (have_ws ? 4 : 32);
+  if (forced == 'r' || lds_rows ||
+      (forced == '\0' && !gemm_fused_applicable(p) && gemv_has_fast_kernel(p, X, ldx) &&
+       (rows_cheap ? (!have_ws || tokens <= 96) : (!have_ws && tokens <= 128)))) {
     for (int t0 = 0; t0 < tokens; t0 += 16) {
       const int rc = launch_gemv(p, X + (long long)t0 * ldx, ldx, tokens - t0 < 16 ? tokens - t0 : 16, Y + (long long)t0 * ldy, ldy, s);
       if (rc != VQ_OK) return rc;

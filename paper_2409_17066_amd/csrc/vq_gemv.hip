@@ -166,6 +166,13 @@ static bool down_mfma_alone_wanted(const Params &p, const __half *x, long long l
   return batch >= 5 || (batch >= 3 && (p.S >= 64 * 16 || (p.k_res && p.bits_res == 12))) || forced_kernel() == 'm';
 }
 
+// Whether vq_gemv would run this layer on the kernels that keep one table in LDS at a time (no kernel of its own, tables that fit).
+bool gemv_has_lds_kernel(const Params &p, const __half *x, long long ldx) {
+  if (forced_kernel() != '\0') return false;
+  if (p.orientation == 1) return !gemv_down_applicable(p, x, ldx) && !gemv_v8_down_applicable(p) && gemv_down_lds_applicable(p, 1);
+  return !gemv_fast_applicable(p, x, ldx) && !gemv_v8_applicable(p, x, ldx) && gemv_lds_applicable(p, 1);
+}
+
 // Whether vq_gemv has one of its specialised kernels for this layer and these activations (vq_gemm sends small token
 // counts, and layers its own kernels do not take, through vq_gemv sixteen rows at a time).
 bool gemv_has_fast_kernel(const Params &p, const __half *x, long long ldx) {
