@@ -10,18 +10,15 @@
 // leaves them in LDS, where the waves' parts of a stream are added in ascending order (the same bits every run) to the sums of
 // the passes before.  Activations are staged in stored column order (gathered by col_perm), with zeros outside the pass's
 // group, so that windows that straddle two groups need no masks.  y = scale * (sum of the passes) + bias * sum(x).
-#include "vq_common.hpp"
+#include "vq_lds_tables.hpp"
 
 namespace vq {
 
 namespace {
 
-constexpr int LW = 16;           // waves per workgroup
-typedef unsigned uint4v __attribute__((ext_vector_type(4)));
-typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+using namespace lds_tables;
 
-constexpr int win_vectors(int bits) { return bits % 32 == 0 ? 1 : bits % 16 == 0 ? 2 : bits % 8 == 0 ? 4 : bits % 4 == 0 ? 8 : 32; }
-constexpr int entry_halfs(int v) { return v <= 2 ? 2 : v <= 4 ? 4 : v <= 8 ? 8 : 16; }
+constexpr int LW = 16;           // waves per workgroup
 
 struct DownPlan {
   unsigned off_x, off_xo, off_xsum, off_part, off_ypart, bytes;   // byte offsets in dynamic LDS (the pass's table at 0)
@@ -97,12 +94,11 @@ __global__ __launch_bounds__(LW * 64) void gemv_down_lds_kernel(Params p, DownPl
       if (outlier) {
         const uint2v a = __builtin_amdgcn_raw_buffer_load_b64(r_a, off, 0, 0);
         w[0] = a.x; w[1] = a.y;
-      } else if constexpr (ND == 1) {
-        w[0] = __builtin_amdgcn_raw_buffer_load_b32(r_a, off, 0, 0);
       } else {
-        typedef unsigned uint3v __attribute__((ext_vector_type(3)));
-        const uint3v a = __builtin_amdgcn_raw_buffer_load_b96(r_a, off, 0, 0);
-        w[0] = a.x; w[1] = a.y; w[2] = a.z;
+        unsigned v[ND];
+        load_window<ND>(v, r_a, off);
+#pragma unroll
+        for (int d = 0; d < ND; ++d) w[d] = v[d];
       }
     };
     unsigned wm[NW];
@@ -115,30 +111,7 @@ __global__ __launch_bounds__(LW * 64) void gemv_down_lds_kernel(Params p, DownPl
         *reinterpret_cast<uint2v *>(lds + (unsigned)en * 8u) = *reinterpret_cast<const uint2v *>(cb_a + (long long)en * 4);
     } else {
 #pragma unroll 4
-      for (int en = threadIdx.x; en < k_a; en += LW * 64) {
-        const unsigned *src = reinterpret_cast<const unsigned *>(cb_a) + (long long)en * VD;
-        unsigned v[ED];
-#pragma unroll
-        for (int d = 0; d < ED; ++d) v[d] = 0u;
-        if constexpr (VD % 4 == 0) {
-#pragma unroll
-          for (int d = 0; d < VD; d += 4) { const uint4v a = *reinterpret_cast<const uint4v *>(src + d); v[d] = a.x; v[d + 1] = a.y; v[d + 2] = a.z; v[d + 3] = a.w; }
-        } else if constexpr (VD % 2 == 0) {
-#pragma unroll
-          for (int d = 0; d < VD; d += 2) { const uint2v a = *reinterpret_cast<const uint2v *>(src + d); v[d] = a.x; v[d + 1] = a.y; }
-        } else {
-#pragma unroll
-          for (int d = 0; d < VD; ++d) v[d] = src[d];
-        }
-        unsigned *dst = reinterpret_cast<unsigned *>(lds) + en * ED;
-        if constexpr (ED >= 4) {
-#pragma unroll
-          for (int d = 0; d < ED; d += 4) *reinterpret_cast<uint4v *>(dst + d) = uint4v{v[d], v[d + 1], v[d + 2], v[d + 3]};
-        } else {
-#pragma unroll
-          for (int d = 0; d < ED; ++d) dst[d] = v[d];
-        }
-      }
+      for (int en = threadIdx.x; en < k_a; en += LW * 64) stage_entry<V>(lds, cb_a, en);
     }
     // ---- the activations of the pass's windows: a new group's, with zeros outside the group (and past the row)
     if (!outlier && !second) {
@@ -191,9 +164,7 @@ __global__ __launch_bounds__(LW * 64) void gemv_down_lds_kernel(Params p, DownPl
               xw[t][q] = *reinterpret_cast<const unsigned *>(lds + plan.off_x + t * plan.x_pitch + (unsigned)wdx * (U * 2u) + q * 4u);
 #pragma unroll
           for (int u = 0; u < U; ++u) {
-            unsigned i = wm[(u * BITS) >> 5] >> ((u * BITS) & 31);
-            if (((u * BITS) & 31) + BITS > 32) i |= wm[((u * BITS) >> 5) + 1 < NW ? ((u * BITS) >> 5) + 1 : 0] << (32 - ((u * BITS) & 31));
-            i = min(i & ((1u << BITS) - 1u), (unsigned)k_a - 1u);
+            const unsigned i = min(window_field<BITS, NW>(wm, u), (unsigned)k_a - 1u);
             unsigned e[ED];
 #pragma unroll
             for (int d = 0; d < ED; ++d) e[d] = reinterpret_cast<const unsigned *>(lds)[i * ED + d];
@@ -247,8 +218,7 @@ __global__ __launch_bounds__(LW * 64) void gemv_down_lds_kernel(Params p, DownPl
 
 bool pair_ok(const Params &p) {
   if ((p.k_res && p.bits_res != p.bits) || (p.Q && (p.v_out != 4 || p.bits_out > 16))) return false;
-  return (p.v == 2 && p.bits == 4) || ((p.v == 4 || p.v == 6 || p.v == 8) && p.bits == 8) ||
-         ((p.v == 4 || p.v == 6 || p.v == 8 || p.v == 12) && p.bits == 12);
+  return compiled_pair(p.v, p.bits, true);
 }
 
 bool make_down_plan(const Params &p, int batch, DownPlan *plan) {

@@ -10,25 +10,21 @@
 // with v_dot2_f32_f16 when vectors start on even columns, else element by element -- and the row ends in
 // y = scale * sum(d x) + bias * sum(x), as in the other decode kernels.  No layout tricks: this kernel's job is to keep
 // every such layer off the generic kernel, whose table reads go through the caches (about 90 GB/s).
-#include "vq_common.hpp"
+#include "vq_lds_tables.hpp"
 
 namespace vq {
 
 namespace {
 
+using namespace lds_tables;
+
 constexpr int LW = 16;           // waves per workgroup
-typedef unsigned uint4v __attribute__((ext_vector_type(4)));
 
 struct LdsPlan {
   unsigned off_res, off_out, off_x, off_xsum, off_ypart, bytes;   // byte offsets in dynamic LDS (main table at 0)
   int rows_per_wg;
   unsigned x_pitch;                                    // bytes per staged activation row
 };
-
-__device__ __forceinline__ float dot2(unsigned a, unsigned b, float c) {
-  typedef _Float16 half2v __attribute__((ext_vector_type(2)));
-  return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, a), __builtin_bit_cast(half2v, b), c, false);
-}
 
 template <int B>
 __global__ __launch_bounds__(LW * 64) void gemv_lds_kernel(Params p, LdsPlan plan, const __half *__restrict__ x, long long ldx,
@@ -134,27 +130,7 @@ __global__ __launch_bounds__(LW * 64) void gemv_lds_kernel(Params p, LdsPlan pla
 // time -- 32 / gcd(32, BITS) vectors in BITS / gcd(32, BITS) dwords, consecutive lanes consecutive windows: one coalesced,
 // range-checked load per window instead of two dwords per index -- and the table entries sit in LDS padded to 4, 8, 16 or
 // 32 bytes, so that an entry is one aligned read (two for V = 12).
-constexpr int win_vectors(int bits) { return bits % 32 == 0 ? 1 : bits % 16 == 0 ? 2 : bits % 8 == 0 ? 4 : bits % 4 == 0 ? 8 : 32; }
-constexpr int entry_halfs(int v) { return v <= 2 ? 2 : v <= 4 ? 4 : v <= 8 ? 8 : 16; }
 constexpr bool two_pass_compiled(int v, int bits) { return v >= 8 && bits == 12; }   // where two padded tables can exceed LDS
-
-template <int ND>
-__device__ __forceinline__ void load_window(unsigned (&w)[ND], __amdgpu_buffer_rsrc_t r, unsigned off) {
-  if constexpr (ND == 1) w[0] = __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, 0);
-  else {
-    static_assert(ND == 3, "windows of one or three dwords");
-    typedef unsigned uint3v __attribute__((ext_vector_type(3)));
-    const uint3v a = __builtin_amdgcn_raw_buffer_load_b96(r, off, 0, 0);
-    w[0] = a.x; w[1] = a.y; w[2] = a.z;
-  }
-}
-template <int BITS, int ND>
-__device__ __forceinline__ unsigned window_field(const unsigned (&w)[ND], int u) {      // u is a compile-time constant after unrolling
-  const int bit = u * BITS, j = bit >> 5, sh = bit & 31;
-  unsigned v = w[j] >> sh;
-  if (sh + BITS > 32) v |= w[j + 1 < ND ? j + 1 : j] << (32 - sh);
-  return v & ((1u << BITS) - 1u);
-}
 
 template <int V, int BITS, int MODE, int B>      // MODE 0: no residual; 1: both tables in LDS; 2: one table at a time, two passes over the rows
 __global__ __launch_bounds__(LW * 64) void gemv_lds_window_kernel(Params p, LdsPlan plan, const __half *__restrict__ x, long long ldx,
@@ -234,31 +210,8 @@ __global__ __launch_bounds__(LW * 64) void gemv_lds_window_kernel(Params p, LdsP
 #pragma unroll 4
     for (int en = threadIdx.x; en < k_a + (BOTH ? p.k_res : 0); en += LW * 64) {
       const bool res = BOTH && en >= k_a;
-      const int entry = res ? en - k_a : en;
-      const unsigned *src = reinterpret_cast<const unsigned *>(res ? p.cb_res : cb_a) + (long long)entry * VD;
-      unsigned v[ED];
-#pragma unroll
-      for (int d = 0; d < ED; ++d) v[d] = 0u;
-      // (the tables are 16-byte aligned, so entries of an even number of dwords are 8-byte aligned, of 4 or 8 dwords 16-byte)
-      if constexpr (VD % 4 == 0) {
-#pragma unroll
-        for (int d = 0; d < VD; d += 4) { const uint4v a = *reinterpret_cast<const uint4v *>(src + d); v[d] = a.x; v[d + 1] = a.y; v[d + 2] = a.z; v[d + 3] = a.w; }
-      } else if constexpr (VD % 2 == 0) {
-        typedef unsigned uint2v __attribute__((ext_vector_type(2)));
-#pragma unroll
-        for (int d = 0; d < VD; d += 2) { const uint2v a = *reinterpret_cast<const uint2v *>(src + d); v[d] = a.x; v[d + 1] = a.y; }
-      } else {
-#pragma unroll
-        for (int d = 0; d < VD; ++d) v[d] = src[d];
-      }
-      unsigned *dst = reinterpret_cast<unsigned *>(lds + (res ? plan.off_res : 0u)) + entry * ED;
-      if constexpr (ED >= 4) {
-#pragma unroll
-        for (int d = 0; d < ED; d += 4) *reinterpret_cast<uint4v *>(dst + d) = uint4v{v[d], v[d + 1], v[d + 2], v[d + 3]};
-      } else {
-#pragma unroll
-        for (int d = 0; d < ED; ++d) dst[d] = v[d];
-      }
+      if (res) stage_entry<V>(lds + plan.off_res, p.cb_res, en - k_a);
+      else stage_entry<V>(lds, cb_a, en);
     }
     __syncthreads();
 
@@ -376,7 +329,7 @@ int launch_window_vb(const Params &p, const __half *x, long long ldx, int batch,
 // the (V, BITS) pairs with a compiled kernel: no outlier columns, a residual stream (if any) of the same index width
 bool window_pair(const Params &p) {
   if (p.Q != 0 || (p.k_res && p.bits_res != p.bits)) return false;
-  return (p.v == 2 && p.bits == 4) || ((p.v == 4 || p.v == 6 || p.v == 8) && p.bits == 8) || ((p.v == 4 || p.v == 8 || p.v == 12) && p.bits == 12);
+  return compiled_pair(p.v, p.bits, false);
 }
 int launch_window_any(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s) {
   if (p.Q != 0 || (p.k_res && p.bits_res != p.bits)) return VQ_ERR_UNSUPPORTED;
@@ -408,7 +361,6 @@ template <int V, int BITS, int B>
 __global__ __launch_bounds__(LW * 64) void gemv_lds_passes_kernel(Params p, PassPlan plan, const __half *__restrict__ x, long long ldx,
                                                                   __half *__restrict__ y, long long ldy) {
   constexpr int U = win_vectors(BITS), ND = U * BITS / 32, EH = entry_halfs(V), ED = EH / 2, VD = V / 2;
-  typedef unsigned uint2v __attribute__((ext_vector_type(2)));
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   float *xsum = reinterpret_cast<float *>(lds + plan.off_xsum);          // [B], then the waves' parts [B][LW]
   float *xpart = xsum + B;
@@ -500,30 +452,7 @@ __global__ __launch_bounds__(LW * 64) void gemv_lds_passes_kernel(Params p, Pass
         *reinterpret_cast<uint2v *>(lds + (unsigned)en * 8u) = *reinterpret_cast<const uint2v *>(cb_a + (long long)en * 4);
     } else {
 #pragma unroll 4
-      for (int en = threadIdx.x; en < k_a; en += LW * 64) {
-        const unsigned *src = reinterpret_cast<const unsigned *>(cb_a) + (long long)en * VD;
-        unsigned v[ED];
-#pragma unroll
-        for (int d = 0; d < ED; ++d) v[d] = 0u;
-        if constexpr (VD % 4 == 0) {
-#pragma unroll
-          for (int d = 0; d < VD; d += 4) { const uint4v a = *reinterpret_cast<const uint4v *>(src + d); v[d] = a.x; v[d + 1] = a.y; v[d + 2] = a.z; v[d + 3] = a.w; }
-        } else if constexpr (VD % 2 == 0) {
-#pragma unroll
-          for (int d = 0; d < VD; d += 2) { const uint2v a = *reinterpret_cast<const uint2v *>(src + d); v[d] = a.x; v[d + 1] = a.y; }
-        } else {
-#pragma unroll
-          for (int d = 0; d < VD; ++d) v[d] = src[d];
-        }
-        unsigned *dst = reinterpret_cast<unsigned *>(lds) + en * ED;
-        if constexpr (ED >= 4) {
-#pragma unroll
-          for (int d = 0; d < ED; d += 4) *reinterpret_cast<uint4v *>(dst + d) = uint4v{v[d], v[d + 1], v[d + 2], v[d + 3]};
-        } else {
-#pragma unroll
-          for (int d = 0; d < ED; ++d) dst[d] = v[d];
-        }
-      }
+      for (int en = threadIdx.x; en < k_a; en += LW * 64) stage_entry<V>(lds, cb_a, en);
     }
     // ---- the activations of the pass's windows: a new group's, with zeros outside the group (and past the row)
     if (!outlier && !second) {
@@ -653,8 +582,7 @@ bool make_pass_plan(const Params &p, int batch, int u, int eh, PassPlan *plan, i
 // layers the pass kernel takes: a compiled (V, BITS) pair, a residual stream of the same width, outlier vectors of four
 bool pass_pair(const Params &p) {
   if ((p.k_res && p.bits_res != p.bits) || (p.Q && (p.v_out != 4 || p.bits_out > 16))) return false;
-  return (p.v == 2 && p.bits == 4) || ((p.v == 4 || p.v == 6 || p.v == 8) && p.bits == 8) ||
-         ((p.v == 4 || p.v == 6 || p.v == 8 || p.v == 12) && p.bits == 12);
+  return compiled_pair(p.v, p.bits, true);
 }
 
 template <int V, int BITS, int B>
