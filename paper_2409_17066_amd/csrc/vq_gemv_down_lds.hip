@@ -166,8 +166,7 @@ __global__ __launch_bounds__(LW * 64) void gemv_down_lds_kernel(Params p, DownPl
           for (int u = 0; u < U; ++u) {
             const unsigned i = min(window_field<BITS, NW>(wm, u), (unsigned)k_a - 1u);
             unsigned e[ED];
-#pragma unroll
-            for (int d = 0; d < ED; ++d) e[d] = reinterpret_cast<const unsigned *>(lds)[i * ED + d];
+            read_entry<V>(e, lds, i);
 #pragma unroll
             for (int t = 0; t < B; ++t) {
               const float xf = (u & 1) ? hi_half(xw[t][u / 2]) : lo_half(xw[t][u / 2]);

@@ -240,12 +240,10 @@ __global__ __launch_bounds__(LW * 64) void gemv_lds_window_kernel(Params p, LdsP
           // (a vector past the row's last one: some entry of the table times the zeros that end the staged row)
           const unsigned i = min(window_field<BITS, ND>(wm, u), (unsigned)k_a - 1u);
           unsigned e[ED], f[ED];
-#pragma unroll
-          for (int d = 0; d < ED; ++d) e[d] = reinterpret_cast<const unsigned *>(lds)[i * ED + d];
+          read_entry<V>(e, lds, i);
           if (BOTH) {
             const unsigned ir = min(window_field<BITS, ND>(wr, u), (unsigned)p.k_res - 1u);
-#pragma unroll
-            for (int d = 0; d < ED; ++d) f[d] = reinterpret_cast<const unsigned *>(lds + plan.off_res)[ir * ED + d];
+            read_entry<V>(f, lds + plan.off_res, ir);
           }
 #pragma unroll
           for (int t = 0; t < B; ++t) {
@@ -508,8 +506,7 @@ __global__ __launch_bounds__(LW * 64) void gemv_lds_passes_kernel(Params p, Pass
           for (int u = 0; u < U; ++u) {
             const unsigned i = min(window_field<BITS, ND < 2 ? 2 : ND>(wm, u), (unsigned)k_a - 1u);
             unsigned e[ED];
-#pragma unroll
-            for (int d = 0; d < ED; ++d) e[d] = reinterpret_cast<const unsigned *>(lds)[i * ED + d];
+            read_entry<V>(e, lds, i);
 #pragma unroll
             for (int t = 0; t < B; ++t) {
 #pragma unroll

@@ -13,8 +13,9 @@ typedef unsigned uint4v __attribute__((ext_vector_type(4)));
 // A window is the smallest run of vectors whose index bits fill whole dwords: 32 / gcd(32, bits) vectors in bits / gcd(32, bits)
 // dwords (one dword for 4- and 8-bit indices, three for 12-bit ones).
 constexpr int win_vectors(int bits) { return bits % 32 == 0 ? 1 : bits % 16 == 0 ? 2 : bits % 8 == 0 ? 4 : bits % 4 == 0 ? 8 : 32; }
-// Halves a table entry takes in LDS: padded to 4, 8, 16 or 32 bytes, so that an entry is one aligned read (two for v = 12).
-constexpr int entry_halfs(int v) { return v <= 2 ? 2 : v <= 4 ? 4 : v <= 8 ? 8 : 16; }
+// Halves a table entry takes in LDS: padded to 4, 8 or 16 bytes, so that an entry is one aligned read; v = 12 keeps its 24
+// bytes (three 8-byte reads cost no more LDS time than two 16-byte ones, and 4096 entries are 96 KB instead of 128).
+constexpr int entry_halfs(int v) { return v <= 2 ? 2 : v <= 4 ? 4 : v <= 8 ? 8 : (v + 3) / 4 * 4; }
 // The (v, index width) pairs the kernels are compiled for.
 inline bool compiled_pair(int v, int bits, bool with_v6_12) {
   return (v == 2 && bits == 4) || ((v == 4 || v == 6 || v == 8) && bits == 8) || ((v == 4 || v == 8 || v == 12 || (with_v6_12 && v == 6)) && bits == 12);
@@ -65,12 +66,32 @@ __device__ __forceinline__ void stage_entry(unsigned char *lds_table, const __ha
     for (int d = 0; d < VD; ++d) v[d] = src[d];
   }
   unsigned *dst = reinterpret_cast<unsigned *>(lds_table) + en * ED;
-  if constexpr (ED >= 4) {
+  if constexpr (ED % 4 == 0) {
 #pragma unroll
     for (int d = 0; d < ED; d += 4) *reinterpret_cast<uint4v *>(dst + d) = uint4v{v[d], v[d + 1], v[d + 2], v[d + 3]};
+  } else if constexpr (ED % 2 == 0) {
+#pragma unroll
+    for (int d = 0; d < ED; d += 2) *reinterpret_cast<uint2v *>(dst + d) = uint2v{v[d], v[d + 1]};
   } else {
 #pragma unroll
     for (int d = 0; d < ED; ++d) dst[d] = v[d];
+  }
+}
+
+// Entry i of a staged table: aligned reads of 16, 8 or 4 bytes.
+template <int V>
+__device__ __forceinline__ void read_entry(unsigned (&e)[entry_halfs(V) / 2], const unsigned char *lds_table, unsigned i) {
+  constexpr int ED = entry_halfs(V) / 2;
+  const unsigned *src = reinterpret_cast<const unsigned *>(lds_table) + i * ED;
+  if constexpr (ED % 4 == 0) {
+#pragma unroll
+    for (int d = 0; d < ED; d += 4) { const uint4v a = *reinterpret_cast<const uint4v *>(src + d); e[d] = a.x; e[d + 1] = a.y; e[d + 2] = a.z; e[d + 3] = a.w; }
+  } else if constexpr (ED % 2 == 0) {
+#pragma unroll
+    for (int d = 0; d < ED; d += 2) { const uint2v a = *reinterpret_cast<const uint2v *>(src + d); e[d] = a.x; e[d + 1] = a.y; }
+  } else {
+#pragma unroll
+    for (int d = 0; d < ED; ++d) e[d] = src[d];
   }
 }
 #endif
