@@ -130,7 +130,11 @@ int vq_dequant(const vq_layer_desc *desc, void *W, int64_t ldw, void *hip_stream
  * result.  One or two activation rows run on the vector ALUs (v_dot2_f32_f16, DPP reductions); from
  * three rows on, and for layers with codebook groups or outlier columns, the fp16 matrix cores do the
  * multiplications (the LDS lookups cost the same and the vector ALUs stop binding); VQ_SWITCHES gemv=d
- * keeps every batch on the vector ALUs.  x: fp16 [batch][ldx], ldx >= in_features; y: fp16 [batch][ldy],
+ * keeps every batch on the vector ALUs.  That is the v = 6 / 12-bit layers; v = 8 with 8- or 16-bit indices gathers its
+ * table from L2; the paper's other settings (v = 12 with two 4096-entry tables, v = 4 / k = 256, v = 2 / k = 16, ..., with
+ * codebook groups and outlier columns of v = 4, in either orientation) run four rows a launch on the vector ALUs with
+ * one table in LDS at a time; what is left runs on generic kernels.
+ * x: fp16 [batch][ldx], ldx >= in_features; y: fp16 [batch][ldy],
  * ldy >= out_features; batch in [1,16]; x and y 2-byte aligned (a 16-byte aligned x with ldx % 8 == 0
  * lets the fastest kernels run).  y must not alias x.                                               */
 int vq_gemv(const vq_layer_desc *desc, const void *x, int64_t ldx, int32_t batch,
