@@ -120,6 +120,8 @@ bool gemv_lds_applicable(const Params &p, int batch);
 int launch_gemv_lds(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
 size_t gemv_lds_slots_workspace_bytes(const Params &p, int batch);
 bool gemv_down_lds_applicable(const Params &p, int batch);
+size_t gemv_down_lds_slots_workspace_bytes(const Params &p, int batch);
+int launch_gemv_down_lds_slots(const Params &p, const __half *x, long long ldx, int batch, float *part, float *part_xs, hipStream_t s);
 int launch_gemv_down_lds(const Params &p, const __half *x, long long ldx, int batch, __half *y, long long ldy, hipStream_t s);
 int launch_gemv_lds_slots(const Params &p, const __half *x, long long ldx, int batch, float *part, float *part_xs, hipStream_t s);
 int launch_gemv_res8(const Params &p, const __half *x, __half *y, hipStream_t s);
@@ -361,9 +363,12 @@ size_t gemv_workspace_bytes(const Params &p, const __half *x, long long ldx, int
     const int parts = gemv_down_mfma_parts(p);            // the outlier columns are one more set of sums to add up
     return parts > 1 ? ((size_t)(parts + (p.Q ? 1 : 0)) * ((size_t)batch * (size_t)p.out_features + 16) * sizeof(float) + 255) / 256 * 256 : 0;
   }
-  if (p.orientation == 1)           // vectors down the output dimension: the same workspace layout, filled by that orientation's kernel
-    return p.n_groups > 1 && p.n_groups <= 256 && gemv_down_applicable(p, x, ldx)
-               ? ((size_t)(p.n_groups + (p.Q ? 1 : 0)) * ((size_t)batch * (size_t)p.out_features + 16) * sizeof(float) + 255) / 256 * 256 : 0;
+  if (p.orientation == 1) {         // vectors down the output dimension: the same workspace layout, filled by that orientation's kernel
+    if (p.n_groups > 1 && p.n_groups <= 256 && gemv_down_applicable(p, x, ldx))
+      return ((size_t)(p.n_groups + (p.Q ? 1 : 0)) * ((size_t)batch * (size_t)p.out_features + 16) * sizeof(float) + 255) / 256 * 256;
+    // (the other settings, on the kernel that keeps one table in LDS at a time: a group per workgroup)
+    return gemv_down_applicable(p, x, ldx) || gemv_v8_down_applicable(p) ? 0 : gemv_down_lds_slots_workspace_bytes(p, batch);
+  }
   if (!gemv_fast_applicable(p, x, ldx))       // the LDS-table kernels, when the layer gets that far: a slot per workgroup
     return gemv_v8_applicable(p, x, ldx) ? 0 : gemv_lds_slots_workspace_bytes(p, batch);
   if (forced_kernel() == 'd') return 0;
@@ -391,6 +396,13 @@ int launch_gemv_ws(const Params &p, const __half *x, long long ldx, int batch, _
     int rc = launch_gemv_down_mfma(p, x, ldx, batch, nullptr, 0, s, part, part_xs, parts);
     if (rc == VQ_OK) return launch_groups_finish(part, part_xs, slots, batch, p, y, ldy, s);
     if (rc != VQ_ERR_UNSUPPORTED) return rc;
+  } else if (need && workspace && workspace_bytes >= need && p.orientation == 1 && !gemv_down_applicable(p, x, ldx)) {
+    if (!switches().groups_loop) {                            // the LDS-table kernel of this orientation: a group per workgroup
+      float *part = static_cast<float *>(workspace), *part_xs = part + (size_t)p.n_groups * (size_t)batch * (size_t)p.out_features;
+      const int rc = launch_gemv_down_lds_slots(p, x, ldx, batch, part, part_xs, s);
+      if (rc == VQ_OK) return launch_groups_finish(part, part_xs, p.n_groups, batch, p, y, ldy, s);
+      if (rc != VQ_ERR_UNSUPPORTED) return rc;
+    }
   } else if (need && workspace && workspace_bytes >= need && p.orientation == 1) {
     const int slots = p.n_groups + (p.Q ? 1 : 0);             // the outlier columns are one more set of sums to add up
     float *part = static_cast<float *>(workspace), *part_xs = part + (size_t)slots * (size_t)batch * (size_t)p.out_features;

@@ -24,6 +24,10 @@ struct DownPlan {
   unsigned off_x, off_xo, off_xsum, off_part, off_ypart, bytes;   // byte offsets in dynamic LDS (the pass's table at 0)
   unsigned x_pitch, xo_pitch;                                     // bytes per staged row of main / outlier columns
   int streams_per_wg;
+  // With a workspace on loan a workgroup takes one codebook group (the first group's workgroups also the outlier streams) and
+  // a block of streams, and leaves its sums in the workspace for the kernel that adds the groups up:
+  int n_slots, batch_total;                                       // 0: every workgroup walks all passes and writes y
+  float *gpart, *gpart_xs;                                        // [n_slots][batch_total][out_features] sums, [n_slots][16] activation sums
 };
 
 __device__ __forceinline__ float lo_half(unsigned w) { return __half2float(__ushort_as_half((unsigned short)(w & 0xFFFFu))); }
@@ -40,7 +44,9 @@ __global__ __launch_bounds__(LW * 64) void gemv_down_lds_kernel(Params p, DownPl
   float *part = reinterpret_cast<float *>(lds + plan.off_part);          // [unit][wave][AM][B]: a wave's sums of a stream in this pass
   float *ypart = reinterpret_cast<float *>(lds + plan.off_ypart);        // [row of the workgroup][B]: the passes so far
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const int s0 = blockIdx.x * plan.streams_per_wg, s1 = min(p.S, s0 + plan.streams_per_wg);
+  const bool slots = plan.n_slots != 0;
+  const int slot = slots ? (int)blockIdx.x % plan.n_slots : 0;
+  const int s0 = (slots ? (int)blockIdx.x / plan.n_slots : (int)blockIdx.x) * plan.streams_per_wg, s1 = min(p.S, s0 + plan.streams_per_wg);
   const int row_base = s0 * V, n_rows = min(p.out_features, s1 * V) - row_base;      // (row_base is a multiple of 4 when there are outlier columns)
   const __amdgpu_buffer_rsrc_t r_i = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.idx), 0, (unsigned)((long long)p.S * p.stride), 0x00020000);
   const __amdgpu_buffer_rsrc_t r_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.k_res ? p.idx_res : p.idx), 0,
@@ -53,12 +59,14 @@ __global__ __launch_bounds__(LW * 64) void gemv_down_lds_kernel(Params p, DownPl
     return (unsigned)src < (unsigned)p.in_features ? x[(long long)t * ldx + src] : __float2half_rn(0.0f);
   };
 
-  // ---- once: the sum of every activation row, the activations of the outlier columns
+  // ---- once: the sum of every activation row, the activations of the outlier columns (a workgroup with a slot: the first
+  // slot's over the outlier columns; every slot adds what it restages)
+  const int once_cols = !slots ? p.in_features : slot == 0 ? p.n_out : 0;
 #pragma unroll
   for (int t = 0; t < B; ++t) {
     __half *xo = reinterpret_cast<__half *>(lds + plan.off_xo + t * plan.xo_pitch);
     float sum = 0.0f;
-    for (int c = threadIdx.x; c < p.in_features; c += LW * 64) {
+    for (int c = threadIdx.x; c < once_cols; c += LW * 64) {
       const __half v = x_at(t, c);
       if (c < p.n_out) xo[c] = v;
       sum += __half2float(v);
@@ -69,7 +77,11 @@ __global__ __launch_bounds__(LW * 64) void gemv_down_lds_kernel(Params p, DownPl
 
   const int tables_per_group = p.k_res ? 2 : 1;
   const int table_passes = p.n_groups * tables_per_group;
-  for (int pass = 0; pass < table_passes + (p.Q ? 1 : 0); ++pass) {
+  const int pass_begin = slots ? slot * tables_per_group : 0;
+  const int my_table_passes = slots ? tables_per_group : table_passes;
+  const int my_passes = my_table_passes + (p.Q && slot == 0 ? 1 : 0);
+  for (int ip = 0; ip < my_passes; ++ip) {
+    const int pass = ip < my_table_passes ? pass_begin + ip : table_passes;
     const bool outlier = pass == table_passes;
     const int g = pass / tables_per_group;
     const bool second = !outlier && pass - g * tables_per_group == 1;
@@ -118,12 +130,20 @@ __global__ __launch_bounds__(LW * 64) void gemv_down_lds_kernel(Params p, DownPl
 #pragma unroll
       for (int t = 0; t < B; ++t) {
         __half *xs = reinterpret_cast<__half *>(lds + plan.off_x + t * plan.x_pitch);
-        for (int pos = w_lo * U + (int)threadIdx.x; pos < w_hi * U; pos += LW * 64)
-          xs[pos] = pos >= p_lo && pos < p_hi ? x_at(t, p.n_out + pos) : __float2half_rn(0.0f);
+        float sum = 0.0f;
+        for (int pos = w_lo * U + (int)threadIdx.x; pos < w_hi * U; pos += LW * 64) {
+          const __half v = pos >= p_lo && pos < p_hi ? x_at(t, p.n_out + pos) : __float2half_rn(0.0f);
+          xs[pos] = v;
+          sum += __half2float(v);
+        }
+        if (slots) {                                      // the group's share of sum(x), on top of the outlier columns'
+          sum = wave_sum(sum);
+          if (lane == 0) xpart[t * LW + wv] += sum;
+        }
       }
     }
     __syncthreads();
-    if (pass == 0 && threadIdx.x < B) {                   // the waves' parts in a fixed order (read after the last barrier)
+    if (ip == 0 && threadIdx.x < B) {                   // the waves' parts in a fixed order (read after the last barrier)
       float sum = 0.0f;
       for (int w = 0; w < LW; ++w) sum += xpart[threadIdx.x * LW + w];
       xsum[threadIdx.x] = sum;
@@ -202,11 +222,18 @@ __global__ __launch_bounds__(LW * 64) void gemv_down_lds_kernel(Params p, DownPl
       float sum = 0.0f;
       for (int w = w_first; w <= w_last; ++w) sum += part[((unit * LW + w) * AM + j) * B + t];
       const int r = unit * VA + j;
-      if (r < n_rows) ypart[r * B + t] = pass ? __fadd_rn(ypart[r * B + t], sum) : sum;
+      if (r < n_rows) ypart[r * B + t] = ip ? __fadd_rn(ypart[r * B + t], sum) : sum;
     }
   }
   // ---- scale, bias, store: a lane per row
   __syncthreads();
+  if (slots) {
+    for (int r = threadIdx.x; r < n_rows; r += LW * 64)
+#pragma unroll
+      for (int t = 0; t < B; ++t) plan.gpart[((long long)slot * plan.batch_total + t) * p.out_features + row_base + r] = ypart[r * B + t];
+    if (s0 == 0 && threadIdx.x < B) plan.gpart_xs[slot * 16 + threadIdx.x] = xsum[threadIdx.x];
+    return;
+  }
   for (int r = threadIdx.x; r < n_rows; r += LW * 64) {
     const int o = row_base + r;
     const float s = p.scale ? __half2float(p.scale[o]) : 1.0f, b = p.bias ? __half2float(p.bias[o]) : 0.0f;
@@ -220,7 +247,7 @@ bool pair_ok(const Params &p) {
   return compiled_pair(p.v, p.bits, true);
 }
 
-bool make_down_plan(const Params &p, int batch, DownPlan *plan) {
+bool make_down_plan(const Params &p, int batch, DownPlan *plan, int n_slots = 0) {
   auto up16 = [](size_t v) { return (v + 15) / 16 * 16; };
   const int u = win_vectors(p.bits), eh = entry_halfs(p.v), am = p.v > 4 ? p.v : 4;
   size_t table = up16((size_t)p.k * eh * 2);
@@ -228,7 +255,8 @@ bool make_down_plan(const Params &p, int batch, DownPlan *plan) {
   if (p.Q && up16((size_t)p.k_out * 8) > table) table = up16((size_t)p.k_out * 8);
   const size_t windows = ((size_t)p.P + u - 1) / u;
   const size_t pitch = up16(windows * u * 2), xo_pitch = up16((size_t)p.n_out * 2);
-  const int wgs = cu_count();
+  const int wgs = n_slots ? (cu_count() / n_slots > 0 ? cu_count() / n_slots : 1) : cu_count();     // workgroups per slot
+  plan->n_slots = n_slots; plan->batch_total = 0; plan->gpart = nullptr; plan->gpart_xs = nullptr;
   int spw = (p.S + wgs - 1) / wgs;
   if (spw < 1) spw = 1;
   if (p.Q && (p.v & 3)) spw = (spw + 1) & ~1;               // a workgroup's rows start on a multiple of 4, the outlier streams' height
@@ -257,6 +285,18 @@ int launch_one(const Params &p, const __half *x, long long ldx, __half *y, long 
   return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
 
+template <int V, int BITS, int B>
+int launch_one_slots(const Params &p, const __half *x, long long ldx, int batch_total, float *part, float *part_xs, hipStream_t s) {
+  DownPlan plan;
+  if (!make_down_plan(p, B, &plan, p.n_groups)) return VQ_ERR_UNSUPPORTED;
+  plan.batch_total = batch_total; plan.gpart = part; plan.gpart_xs = part_xs;
+  auto kernel = gemv_down_lds_kernel<V, BITS, B>;
+  VQ_ALLOW_FULL_LDS(kernel);
+  const unsigned grid = (unsigned)((p.S + plan.streams_per_wg - 1) / plan.streams_per_wg) * (unsigned)p.n_groups;
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(LW * 64), plan.bytes, s, p, plan, x, ldx, static_cast<__half *>(nullptr), 0LL);
+  return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
 }  // namespace
 
 // Vectors down the output dimension, a compiled (v, index width) pair, a table that fits LDS beside `batch` activation rows.
@@ -275,6 +315,38 @@ int launch_gemv_down_lds(const Params &p, const __half *x, long long ldx, int ba
   VQ_PAIR(2, 4) VQ_PAIR(4, 8) VQ_PAIR(6, 8) VQ_PAIR(8, 8) VQ_PAIR(4, 12) VQ_PAIR(6, 12) VQ_PAIR(8, 12) VQ_PAIR(12, 12)
 #undef VQ_PAIR
   return VQ_ERR_UNSUPPORTED;
+}
+
+// Two codebook groups or more: with a workspace of groups x (batch x out_features + 16) binary32 sums every workgroup takes
+// one group; 0 when that does not apply.
+size_t gemv_down_lds_slots_workspace_bytes(const Params &p, int batch) {
+  DownPlan plan;
+  if (p.orientation != 1 || p.n_groups < 2 || p.n_groups > 64 || !pair_ok(p)) return 0;
+  if (!make_down_plan(p, 1, &plan, p.n_groups)) return 0;
+  return ((size_t)p.n_groups * ((size_t)batch * (size_t)p.out_features + 16) * sizeof(float) + 255) / 256 * 256;
+}
+
+// The groups' sums into part [groups][batch][out_features] and part_xs [groups][16]; the caller adds them up.
+int launch_gemv_down_lds_slots(const Params &p, const __half *x, long long ldx, int batch, float *part, float *part_xs, hipStream_t s) {
+  if (p.orientation != 1 || !pair_ok(p)) return VQ_ERR_UNSUPPORTED;
+  int done = 0, g_max = 4;
+  while (done < batch) {
+    int g = batch - done >= 4 ? 4 : batch - done >= 2 ? 2 : 1;
+    if (g > g_max) g = g_max;
+    int rc = VQ_ERR_UNSUPPORTED;
+    float *pt = part + (size_t)done * p.out_features, *px = part_xs + done;
+    const __half *xd = x + done * ldx;
+#define VQ_PAIR(V, BITS)                                                                                                  \
+    if (p.v == V && p.bits == BITS)                                                                                       \
+      rc = g == 1 ? launch_one_slots<V, BITS, 1>(p, xd, ldx, batch, pt, px, s) : g == 2 ? launch_one_slots<V, BITS, 2>(p, xd, ldx, batch, pt, px, s) \
+                                                                                        : launch_one_slots<V, BITS, 4>(p, xd, ldx, batch, pt, px, s);
+    VQ_PAIR(2, 4) VQ_PAIR(4, 8) VQ_PAIR(6, 8) VQ_PAIR(8, 8) VQ_PAIR(4, 12) VQ_PAIR(6, 12) VQ_PAIR(8, 12) VQ_PAIR(12, 12)
+#undef VQ_PAIR
+    if (rc == VQ_ERR_UNSUPPORTED && g > 1) { g_max = g / 2; continue; }
+    if (rc != VQ_OK) return done ? VQ_ERR_HIP : rc;
+    done += g;
+  }
+  return VQ_OK;
 }
 
 }  // namespace vq

@@ -266,7 +266,7 @@ def test_gemv_groups_with_workspace(gpu_lib, monkeypatch, name, batch):
     _check_matmul(plain, oracle.gemv(L, x_np), "%s batch %d" % (name, batch))
 
 
-LDS_SLOTS = ["lds_v12_groups_res_outlier", "lds_v12_groups_perm", "lds_v4_k256_groups"]
+LDS_SLOTS = ["lds_v12_groups_res_outlier", "lds_v12_groups_perm", "lds_v4_k256_groups", "down_lds_v12_groups_outlier", "down_lds_v12_odd_groups"]
 
 
 @pytest.mark.parametrize("name", LDS_SLOTS)
