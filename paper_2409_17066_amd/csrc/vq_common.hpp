@@ -44,7 +44,8 @@ int cu_count();
 //   gemm=g|f|w|r|6 vq_gemm: generic tile kernel / no restore-then-multiply / restore-then-multiply whenever a workspace is
 //                there / rows through vq_gemv / the on-the-fly kernel for v = 6 layers at every token count
 //   dense=0|1    the dense product of the restore-then-multiply route: never / always the 256 x 256 tile kernel
-//   dequant=g|s  vq_dequant: generic kernel / never the wide-store kernel
+//   dequant=g|s  vq_dequant: generic kernel / never the wide-store kernel (v = 6); two passes with a read-back instead of residual
+//                entries from memory where two tables do not fit LDS together (the other settings)
 struct Switches {
   char gemv = 0, gemm = 0, dequant = 0;
   bool groups_loop = false, multi_off = false;

@@ -9,7 +9,9 @@
 // codebook group fit together, one pass per group does everything.  Where they do not (two 4096 x 12 tables are 192 KB), the
 // group takes two passes: the first writes the main centroids to W as they are -- binary16 values, exact -- and the second,
 // with the residual table in the main table's place, reads them back (the same thread that wrote them), adds, restores and
-// writes the final weights.  Outlier columns are left to the caller (the generic kernel restores them afterwards).
+// writes the final weights.  That scheme is the fallback (dequant=s): by default the residual entries of such layers are
+// read from memory (the table stays in L2) while the main table is in LDS, one pass, which is faster (11008 x 4096, v = 12:
+// 63 against 100 us).  Outlier columns are left to the caller (the generic kernel restores them afterwards).
 #include "vq_common.hpp"
 
 namespace vq {
@@ -21,6 +23,7 @@ constexpr int DW = 16;           // waves per workgroup
 struct DqLdsPlan {
   unsigned off_res, bytes;       // residual table behind the main table (both resident), LDS bytes
   int both, rows_per_wg;
+  int res_global;                // the residual table does not fit beside the main one: its entries are read from memory
 };
 
 // index p of a row's stream: the two dwords that hold it, range-checked against the end of the stream array
@@ -30,6 +33,21 @@ __device__ __forceinline__ unsigned stream_index(__amdgpu_buffer_rsrc_t r, unsig
   const unsigned bit = (unsigned)pv * BITS;
   const uint2v w = __builtin_amdgcn_raw_buffer_load_b64(r, row_off + (bit >> 5) * 4u, 0, 0);
   return __builtin_amdgcn_alignbit(w.y, w.x, bit & 31u) & ((1u << BITS) - 1u);
+}
+
+// entry i of a [k][V] table in memory (16-byte aligned table: entries of an even number of dwords are 8-byte aligned)
+template <int V>
+__device__ __forceinline__ void global_entry(unsigned (&e)[V / 2], const __half *table, unsigned i) {
+  constexpr int VD = V / 2;
+  typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+  const unsigned *src = reinterpret_cast<const unsigned *>(table) + (long long)i * VD;
+  if constexpr (VD % 2 == 0) {
+#pragma unroll
+    for (int d = 0; d < VD; d += 2) { const uint2v a = *reinterpret_cast<const uint2v *>(src + d); e[d] = a.x; e[d + 1] = a.y; }
+  } else {
+#pragma unroll
+    for (int d = 0; d < VD; ++d) e[d] = src[d];
+  }
 }
 
 template <int V, int BITS, bool A4>      // A4: W, ldw and the first main column allow dword stores
@@ -44,7 +62,7 @@ __global__ __launch_bounds__(DW * 64) void dequant_lds_kernel(Params p, DqLdsPla
   const __amdgpu_buffer_rsrc_t r_i = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.idx), 0, (unsigned)((long long)p.out_features * p.stride), 0x00020000);
   const __amdgpu_buffer_rsrc_t r_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.k_res ? p.idx_res : p.idx), 0,
                                                                        p.k_res ? (unsigned)((long long)p.out_features * p.stride_res) : 0u, 0x00020000);
-  const bool two = p.k_res && !plan.both;                 // two passes per group
+  const bool two = p.k_res && !plan.both && !plan.res_global;     // two passes per group
   const int per_group = two ? 2 : 1;
   for (int pass = 0; pass < p.n_groups * per_group; ++pass) {
     const int g = pass / per_group;
@@ -66,7 +84,7 @@ __global__ __launch_bounds__(DW * 64) void dequant_lds_kernel(Params p, DqLdsPla
     }
     __syncthreads();
 
-    const bool add_res = plan.both || second;             // this pass adds a residual centroid
+    const bool add_res = plan.both || second || plan.res_global;   // this pass adds a residual centroid
     const bool final_pass = !two || second;               // this pass writes final weights
     const unsigned k_main = (unsigned)(second ? p.k_res : p.k);
     for (int o = row0 + wv; o < row1; o += DW) {
@@ -83,6 +101,9 @@ __global__ __launch_bounds__(DW * 64) void dequant_lds_kernel(Params p, DqLdsPla
           const unsigned ir = min(stream_index<BITS>(r_r, ro_r, pv), (unsigned)p.k_res - 1u);
 #pragma unroll
           for (int d = 0; d < VD; ++d) f[d] = Tr[ir * VD + d];
+        } else if (plan.res_global) {
+          const unsigned ir = min(stream_index<BITS>(r_r, ro_r, pv), (unsigned)p.k_res - 1u);
+          global_entry<V>(f, p.cb_res + (long long)g * p.k_res * V, ir);
         }
         const int c0 = pv * V;                            // first main column of the vector (stored order, after the outlier columns)
         const int n_cols = min(V, p.in_features - p.n_out - c0);          // the row's last vector may stick out
@@ -148,7 +169,7 @@ __global__ __launch_bounds__(DW * 64) void dequant_down_lds_kernel(Params p, DqL
   const __amdgpu_buffer_rsrc_t r_i = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.idx), 0, (unsigned)((long long)p.S * p.stride), 0x00020000);
   const __amdgpu_buffer_rsrc_t r_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.k_res ? p.idx_res : p.idx), 0,
                                                                        p.k_res ? (unsigned)((long long)p.S * p.stride_res) : 0u, 0x00020000);
-  const bool two = p.k_res && !plan.both;
+  const bool two = p.k_res && !plan.both && !plan.res_global;
   const int per_group = two ? 2 : 1;
   for (int pass = 0; pass < p.n_groups * per_group; ++pass) {
     const int g = pass / per_group;
@@ -170,7 +191,7 @@ __global__ __launch_bounds__(DW * 64) void dequant_down_lds_kernel(Params p, DqL
     }
     __syncthreads();
 
-    const bool add_res = plan.both || second, final_pass = !two || second;
+    const bool add_res = plan.both || second || plan.res_global, final_pass = !two || second;
     const unsigned k_main = (unsigned)(second ? p.k_res : p.k);
     const int chunks = (p_hi - p_lo + 127) / 128;
     for (int item = wv; item < (s1 - s0) * chunks; item += DW) {
@@ -189,6 +210,9 @@ __global__ __launch_bounds__(DW * 64) void dequant_down_lds_kernel(Params p, DqL
           const unsigned ir = min(stream_index<BITS>(r_r, ro_r, pos), (unsigned)p.k_res - 1u);
 #pragma unroll
           for (int d = 0; d < VD; ++d) f[c][d] = Tr[ir * VD + d];
+        } else if (plan.res_global) {
+          const unsigned ir = min(stream_index<BITS>(r_r, ro_r, pos), (unsigned)p.k_res - 1u);
+          global_entry<V>(f[c], p.cb_res + (long long)g * p.k_res * V, ir);
         }
       }
 #pragma unroll
@@ -200,7 +224,7 @@ __global__ __launch_bounds__(DW * 64) void dequant_down_lds_kernel(Params p, DqL
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
           h[c] = (unsigned short)((j & 1) ? e[c][j / 2] >> 16 : e[c][j / 2] & 0xFFFFu);
-          r[c] = plan.both ? (unsigned short)((j & 1) ? f[c][j / 2] >> 16 : f[c][j / 2] & 0xFFFFu) : (unsigned short)0;
+          r[c] = plan.both || plan.res_global ? (unsigned short)((j & 1) ? f[c][j / 2] >> 16 : f[c][j / 2] & 0xFFFFu) : (unsigned short)0;
         }
         if (second) {                                     // the main centroids, written by this thread in the pass before
           r[0] = h[0]; r[1] = h[1];
@@ -256,7 +280,8 @@ int launch_dequant_lds(const Params &p, __half *W, long long ldw, hipStream_t s)
   DqLdsPlan plan{};
   plan.both = p.k_res && main + res <= 160 * 1024;
   plan.off_res = (unsigned)main;
-  plan.bytes = (unsigned)(plan.both ? main + res : main > res ? main : res);
+  plan.res_global = p.k_res && !plan.both && main <= 160 * 1024 && switches().dequant != 's';
+  plan.bytes = (unsigned)(plan.both ? main + res : plan.res_global ? main : main > res ? main : res);
   if (plan.bytes > 160u * 1024u) return VQ_ERR_UNSUPPORTED;
   const int wgs = cu_count();
   plan.rows_per_wg = (p.out_features + wgs - 1) / wgs;
@@ -278,7 +303,8 @@ int launch_dequant_down_lds(const Params &p, __half *W, long long ldw, hipStream
   DqLdsPlan plan{};
   plan.both = p.k_res && main + res <= 160 * 1024;
   plan.off_res = (unsigned)main;
-  plan.bytes = (unsigned)(plan.both ? main + res : main > res ? main : res);
+  plan.res_global = p.k_res && !plan.both && main <= 160 * 1024 && switches().dequant != 's';
+  plan.bytes = (unsigned)(plan.both ? main + res : plan.res_global ? main : main > res ? main : res);
   if (plan.bytes > 160u * 1024u) return VQ_ERR_UNSUPPORTED;
   const int wgs = cu_count();
   plan.rows_per_wg = (p.S + wgs - 1) / wgs;                 // streams per workgroup

@@ -338,6 +338,21 @@ def test_dequant_permuted_columns_by_the_scattering_kernels(gpu_lib, monkeypatch
     assert np.array_equal(W.cpu().numpy().view(np.uint16), oracle.dequant(L, L.in_features + 5).view(np.uint16)), name
 
 
+@pytest.mark.parametrize("name", ["lds_v12_two_tables", "lds_v12_groups_res_outlier", "down_lds_v12_two_tables", "down_lds_v12_odd_groups"])
+def test_dequant_two_tables_beyond_lds_in_two_passes(gpu_lib, monkeypatch, name):
+    """Two tables that do not fit LDS together: by default the residual entries come from memory; dequant=s is the scheme
+    with two passes and a read-back of the main centroids.  Both bit for bit."""
+    import torch
+    L = small_layer(name)
+    want = oracle.dequant(L, L.in_features + 6).view(np.uint16)
+    for switch in (None, "dequant=s"):
+        if switch:
+            monkeypatch.setenv("VQ_SWITCHES", switch)
+        W = gpu_lib.dequant(gpu_lib.DeviceLayer(L), L.in_features + 6)
+        torch.cuda.synchronize()
+        assert np.array_equal(W.cpu().numpy().view(np.uint16), want), (name, switch)
+
+
 def test_permuted_unit_activation_reads_back_the_layers_column(gpu_lib):
     """x = e_t returns column t of the LAYER (not of the stored order), outlier columns included."""
     import torch
