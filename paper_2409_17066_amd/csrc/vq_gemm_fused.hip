@@ -394,16 +394,23 @@ int launch_gemm_fused(const Params &p, const __half *X, long long ldx, int token
                       long long ldw, hipStream_t s) {
   if (((long long)(tokens - 1) * ldx + p.in_features) * 2 >= (1LL << 32)) return VQ_ERR_UNSUPPORTED;   // 32-bit buffer offsets
   if (Wd) {
-    // enough 256 x 256 tiles to fill the chip: the four-wave kernel (switch dense=1 / =0: always / never, for measurement and tests)
+    // The four-wave kernel with 256 x 256 tiles or the producer/consumer kernel with BM x 128 tiles (no gathers to amortise:
+    // its tile height only has to fill the chip, out/128 x tokens/BM workgroups): whichever needs less time for its rounds of
+    // one workgroup per compute unit.  A round of the other kernel costs about 1.5 / 0.8 / 0.55 of a 256 x 256 round at BM =
+    // 512 / 256 / 128 (11008 x 4096: 86 tiles 127 against 143 us, 172 tiles 140 against 169 us; 4096 x 4096: 128 tiles 133
+    // against 112 us; 8192 x 28672: 128 tiles 1001 against 696 us, 160 tiles 997 against 1223 us).  Switch dense=1 / =0:
+    // always / never the four-wave kernel, for measurement and tests.
     const int force_dense = switches().dense;
     const long long tiles256 = (long long)((p.out_features + DT - 1) / DT) * ((tokens + DT - 1) / DT);
-    if (force_dense == 1 || (force_dense != 0 && tiles256 >= 200)) {
+    const long long col_blocks = (p.out_features + BN - 1) / BN;
+    const int bm = (col_blocks * ((tokens + 511) / 512) >= 200 ? 512 : col_blocks * ((tokens + 255) / 256) >= 200 ? 256 : 128);
+    const long long cus = cu_count();
+    const long long rounds256 = (tiles256 + cus - 1) / cus, rounds_bm = (col_blocks * ((tokens + bm - 1) / bm) + cus - 1) / cus;
+    const long long cost_bm = rounds_bm * (bm == 512 ? 150 : bm == 256 ? 80 : 55);
+    if (force_dense == 1 || (force_dense != 0 && rounds256 * 100 <= cost_bm)) {
       const int rc = launch_dense256(p, X, ldx, tokens, Y, ldy, Wd, ldw, s);
       if (rc != VQ_ERR_UNSUPPORTED) return rc;
     }
-    // no gathers to amortise: the tile height only has to fill the chip (out/128 x tokens/BM workgroups)
-    const long long col_blocks = (p.out_features + BN - 1) / BN;
-    const int bm = (col_blocks * ((tokens + 511) / 512) >= 200 ? 512 : col_blocks * ((tokens + 255) / 256) >= 200 ? 256 : 128);
     if (bm == 512) return launch_fused<512, true>(p, X, ldx, tokens, Y, ldy, Wd, ldw, s);
     if (bm == 128) return launch_fused<128, true>(p, X, ldx, tokens, Y, ldy, Wd, ldw, s);
     return launch_fused<256, true>(p, X, ldx, tokens, Y, ldy, Wd, ldw, s);
