@@ -60,7 +60,7 @@ def test_a_copy_at_a_loop_back_edge_is_found():
     the next round before the counted wait."""
     loop = ["#ASMSTART", "buffer_load_dword v4, v1, s[8:11], 0 offen", "#ASMEND",
             ".LBB0_1:",
-            "v_mov_b32_e32 v9, v4",                                    # round 2 and later: v4 was refilled below
+            "v_mov_b32_e32 v9, v4",                                    # second trip through the loop and later: v4 was refilled below
             "#ASMSTART", "s_waitcnt vmcnt(0)", "#ASMEND",
             "v_add_u32_e32 v10, v4, v10",
             "#ASMSTART", "buffer_load_dword v4, v1, s[8:11], 0 offen", "#ASMEND",
