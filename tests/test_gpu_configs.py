@@ -167,3 +167,28 @@ def test_prefill_without_workspace_on_the_v6_layers(gpu_lib, layers, cfg, name, 
     torch.cuda.synchronize()
     rows = np.unique(np.concatenate([np.arange(0, L.out_features, 16), [L.out_features - 1, 127, 128, L.out_features - 128]])).astype(np.int32)
     _matmul_ok(Y[:, torch.from_numpy(rows.astype(np.int64)).cuda()], oracle.gemm(L, x, rows=rows), "cfg%d %s T=%d on the fly" % (cfg, name, tokens))
+
+
+@pytest.mark.parametrize("orientation", [0, 1])
+def test_the_2_26_bit_setting_at_full_size(gpu_lib, orientation):
+    """The 11008 x 4096 layer in the 2.26-bit setting of Table "Quantization parameters" (v = 12, two 4096-entry tables, four
+    codebook groups, 40 outlier columns of v = 4 with 8192 entries), both orientations: vq_dequant bit for bit, vq_gemv with one
+    and with five rows, without and with a workspace, vq_gemm at 300 tokens through the restore-then-multiply route on every
+    16th output row."""
+    import torch
+    P = -(-(4096 - 40) // 12) if orientation == 0 else 4096 - 40
+    L = s.make_layer(1, "up", 11008, 4096, 12, 4096, 4096, n_outlier_cols=40, v_out=4, k_out=8192, group_vectors=-(-P // 4),
+                     orientation=orientation)
+    dl = _dequant_exact(gpu_lib, L)
+    for batch in (1, 5):
+        x = s.make_activations(1, L, batch)
+        ref = oracle.gemv(L, x)
+        for workspace in (None, "fast"):
+            y = gpu_lib.gemv(dl, torch.from_numpy(x).cuda(), workspace=workspace)
+            torch.cuda.synchronize()
+            _matmul_ok(y, ref, "2.26-bit setting, orientation %d, batch %d, workspace %s" % (orientation, batch, workspace))
+    x = s.make_activations(1, L, 300)
+    Y = gpu_lib.gemm(dl, torch.from_numpy(x).cuda(), workspace="fast")
+    torch.cuda.synchronize()
+    rows = np.arange(0, L.out_features, 16).astype(np.int32)
+    _matmul_ok(Y[:, torch.from_numpy(rows.astype(np.int64)).cuda()], oracle.gemm(L, x, rows=rows), "2.26-bit setting, 300 tokens")
