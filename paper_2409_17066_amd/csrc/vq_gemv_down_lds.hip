@@ -59,9 +59,9 @@ __global__ __launch_bounds__(LW * 64) void gemv_down_lds_kernel(Params p, DownPl
     return (unsigned)src < (unsigned)p.in_features ? x[(long long)t * ldx + src] : __float2half_rn(0.0f);
   };
 
-  // ---- once: the sum of every activation row, the activations of the outlier columns (a workgroup with a slot: the first
-  // slot's over the outlier columns; every slot adds what it restages)
-  const int once_cols = !slots ? p.in_features : slot == 0 ? p.n_out : 0;
+  // ---- once: the activations of the outlier columns and their sum (with slots: the first slot's workgroups only); the main
+  // columns are added to the sums as the passes restage them
+  const int once_cols = slot == 0 ? p.n_out : 0;
 #pragma unroll
   for (int t = 0; t < B; ++t) {
     __half *xo = reinterpret_cast<__half *>(lds + plan.off_xo + t * plan.xo_pitch);
@@ -136,18 +136,11 @@ __global__ __launch_bounds__(LW * 64) void gemv_down_lds_kernel(Params p, DownPl
           xs[pos] = v;
           sum += __half2float(v);
         }
-        if (slots) {                                      // the group's share of sum(x), on top of the outlier columns'
-          sum = wave_sum(sum);
-          if (lane == 0) xpart[t * LW + wv] += sum;
-        }
+        sum = wave_sum(sum);                              // the group's share of sum(x)
+        if (lane == 0) xpart[t * LW + wv] += sum;
       }
     }
     __syncthreads();
-    if (ip == 0 && threadIdx.x < B) {                   // the waves' parts in a fixed order (read after the last barrier)
-      float sum = 0.0f;
-      for (int w = 0; w < LW; ++w) sum += xpart[threadIdx.x * LW + w];
-      xsum[threadIdx.x] = sum;
-    }
 
     // ---- this wave's items
     float acc[AM][B];
@@ -226,6 +219,12 @@ __global__ __launch_bounds__(LW * 64) void gemv_down_lds_kernel(Params p, DownPl
     }
   }
   // ---- scale, bias, store: a lane per row
+  __syncthreads();
+  if (threadIdx.x < B) {                                  // the waves' parts of sum(x) in a fixed order
+    float sum = 0.0f;
+    for (int w = 0; w < LW; ++w) sum += xpart[threadIdx.x * LW + w];
+    xsum[threadIdx.x] = sum;
+  }
   __syncthreads();
   if (slots) {
     for (int r = threadIdx.x; r < n_rows; r += LW * 64)
