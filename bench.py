@@ -201,7 +201,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16 in, f32 accumulate",
         "data": "synthetic (seeded Gaussian tables, uniform indices; stands in for quantized Llama-2 layers)",
         "config": {"workload": workload, "algorithmic_bytes": alg, "index_copies_rotated": r["copies"],
-                   "launch": "hip graph replay" if use_graph else "eager", "clock": "HIP events on the launching stream",
+                   "launch": ("hip graph replay" if args.steps >= EAGER_BELOW else "eager launches queued behind a graph lead-in") if use_graph else "eager", "clock": "HIP events on the launching stream",
                    "host_wall_us_per_step": round(r["wall_s"] / args.steps * 1e6, 3)},
         "roofline": {"bound": "hbm", "achieved": round(gbps, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": measured_traffic_bytes(cfg),
