@@ -198,8 +198,8 @@ __global__ __launch_bounds__(LW * 64) void gemv_down_lds_kernel(Params p, DownPl
 #pragma unroll
           for (int t = 0; t < B; ++t) {
             if (j < VA) {
-              const float r = wave_sum(acc[j][t]);
-              if (lane == 0) part[((unit * LW + wv) * AM + j) * B + t] = r;
+              const float r = segment_sum_to_last(acc[j][t], 64);
+              if (lane == 63) part[((unit * LW + wv) * AM + j) * B + t] = r;
             }
             acc[j][t] = 0.0f;
           }

@@ -260,9 +260,9 @@ __global__ __launch_bounds__(LW * 64) void gemv_lds_window_kernel(Params p, LdsP
         const float s = s_row, b = b_row;
 #pragma unroll
         for (int t = 0; t < B; ++t) {
-          float r = wave_sum(acc[t]);
+          float r = segment_sum_to_last(acc[t], 64);
           acc[t] = 0.0f;
-          if (lane == 0) {
+          if (lane == 63) {
             if (MODE == 2 && !second) ypart[(o - row0) * B + t] = r;       // the same lane of the same wave picks it up in the second pass
             else {
               if (MODE == 2) r = __fadd_rn(ypart[(o - row0) * B + t], r);
@@ -514,12 +514,9 @@ __global__ __launch_bounds__(LW * 64) void gemv_lds_passes_kernel(Params p, Pass
       if (itn == 0) {                                                     // the row's part of this pass is complete
 #pragma unroll
         for (int t = 0; t < B; ++t) {
-          float r = acc[t];
+          const float r = segment_sum_to_last(acc[t], SEG);
           acc[t] = 0.0f;
-#pragma unroll
-          for (int off = 32; off > 0; off >>= 1)
-            if (off < SEG) r += __shfl_xor(r, off, 64);                   // (the same for the whole wave)
-          if (lane_w == 0 && o + o_lane_off < row1) {                     // (a row changes hands between passes; barriers lie between)
+          if (lane_w == SEG - 1 && o + o_lane_off < row1) {                     // (a row changes hands between passes; barriers lie between)
             float *yp = ypart + (o + o_lane_off - row0) * B + t;
             *yp = pass != pass_begin ? __fadd_rn(*yp, r) : r;
           }

@@ -27,6 +27,22 @@ __device__ __forceinline__ float dot2(unsigned a, unsigned b, float c) {
   return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, a), __builtin_bit_cast(half2v, b), c, false);
 }
 
+// v + (v moved between lanes by a DPP control word); lanes whose row is masked out add 0
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float v) {
+  return v + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, false));
+}
+// Sum over every aligned segment of `seg` lanes (8, 16, 32 or 64; the same for the whole wave): the segment's LAST lane holds it.
+__device__ __forceinline__ float segment_sum_to_last(float v, int seg) {
+  v = dpp_add<0xB1, 0xF>(v);                  // quad_perm [1,0,3,2]
+  v = dpp_add<0x4E, 0xF>(v);                  // quad_perm [2,3,0,1]
+  v = dpp_add<0x141, 0xF>(v);                 // row_half_mirror: every lane of an 8-lane half holds the half's sum
+  if (seg > 8) v = dpp_add<0x140, 0xF>(v);    // row_mirror: every lane of a 16-lane row holds the row's sum
+  if (seg > 16) v = dpp_add<0x142, 0xA>(v);   // row_bcast15 into rows 1 and 3: lanes 31 and 63 hold 32 lanes' sums
+  if (seg > 32) v = dpp_add<0x143, 0xC>(v);   // row_bcast31 into rows 2 and 3: lane 63 holds the wave's sum
+  return v;
+}
+
 // ND dwords of a stream from byte offset `off`, range-checked (zeros past the buffer's end)
 template <int ND>
 __device__ __forceinline__ void load_window(unsigned (&w)[ND], __amdgpu_buffer_rsrc_t r, unsigned off) {
