@@ -126,10 +126,18 @@ __device__ __forceinline__ void warm_kernel_arguments() {      // the first LINE
 #endif
 }
 
+// Sum over the 64 lanes of a wave, in every lane: DPP adds (within quads, half rows, rows, then across rows into lane 63)
+// and one broadcast -- a sixth of what the same butterfly costs through ds_bpermute.  All 64 lanes must be active.
 __device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
-  return x;
+#define VQ_DPP_ADD(CTRL, ROWS) x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, ROWS, 0xF, false))
+  VQ_DPP_ADD(0xB1, 0xF);     // quad_perm [1,0,3,2]
+  VQ_DPP_ADD(0x4E, 0xF);     // quad_perm [2,3,0,1]
+  VQ_DPP_ADD(0x141, 0xF);    // row_half_mirror
+  VQ_DPP_ADD(0x140, 0xF);    // row_mirror
+  VQ_DPP_ADD(0x142, 0xA);    // row_bcast15 into rows 1 and 3
+  VQ_DPP_ADD(0x143, 0xC);    // row_bcast31 into rows 2 and 3
+#undef VQ_DPP_ADD
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
 }
 #endif
 
